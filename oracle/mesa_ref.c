@@ -1,0 +1,481 @@
+/*
+ * mesa_ref.c -- CPU oracle for Mesa's activation-compression hot path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference that the
+ * tests, the smoke check and the benchmark's cpu_baseline leg compare the GPU
+ * library against.  Nothing in the product path may call it, and it shares no
+ * code, header, table or constant generator with the HIP sources.
+ *
+ * What it follows (Mesa, arXiv 2111.11124):
+ *   Sec. 3.2 Eq. (3)   x_bar = clip(round((x - beta_h) * 255 / alpha_h), 0, 255)
+ *   Sec. 3.2 Eq. (4)   stochastic rounding: ceil with probability frac(x)
+ *   Sec. 3.2 Eq. (5)   x_hat = x_bar * alpha_h / 255 + beta_h
+ *   Sec. 3.2 Eq. (6,7) running estimates of alpha (range) and beta (minimum)
+ *   Sec. 3.1 Eq. (2)   layer gradients evaluated at the de-quantized x_hat
+ *   Sec. 3.2 / Fig. "bucketing": one (alpha, beta) pair per head or channel group
+ *
+ * Conventions
+ *   - A tensor is viewed as (outer, groups, inner): element (o, g, i) sits at
+ *     flat index (o*groups + g)*inner + i and uses alpha[g], beta[g].
+ *   - Codes are stored signed: q = x_bar - 128, so Eq. (3)'s clip to [0, 255]
+ *     is a clip of q to [-128, 127]; Eq. (5) adds the 128 back.
+ *   - Everything that decides an integer code or a running parameter is done
+ *     in IEEE binary32, one rounded operation per line (build with
+ *     -ffp-contract=off); gradients are evaluated in binary64 from the
+ *     binary32 x_hat and returned as doubles.
+ *   - dt: 0 = binary32 storage, 1 = binary16 storage (raw uint16 bit patterns).
+ *   - OpenMP (optional) splits the outermost independent index only.
+ *
+ * Pins: see tests/test_oracle_*.py.  The Philox generator is pinned to the
+ * known-answer vectors of its publication's reference distribution; the
+ * assignment of generator output bits to elements is this project's own
+ * convention (the paper names no random source) -- that part is
+ * "parity unpinned" beyond statistical tests.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------------ */
+/* binary16 <-> binary32, written out bit by bit                             */
+/* ------------------------------------------------------------------------ */
+
+float mesa_ref_half_to_float(uint16_t h)
+{
+    uint32_t sign = (uint32_t)(h >> 15) << 31;
+    uint32_t expo = (h >> 10) & 0x1Fu;
+    uint32_t mant = h & 0x3FFu;
+    uint32_t bits;
+    if (expo == 0) {
+        if (mant == 0) {
+            bits = sign;
+        } else { /* subnormal half: value = mant * 2^-24, exact in binary32 */
+            float v = (float)mant * 5.9604644775390625e-08f; /* 2^-24 */
+            memcpy(&bits, &v, 4);
+            bits |= sign;
+        }
+    } else if (expo == 31) {
+        bits = sign | 0x7F800000u | (mant << 13);
+    } else {
+        bits = sign | ((expo + 112u) << 23) | (mant << 13);
+    }
+    float f;
+    memcpy(&f, &bits, 4);
+    return f;
+}
+
+/* round-to-nearest, ties-to-even */
+uint16_t mesa_ref_float_to_half(float f)
+{
+    uint32_t bits;
+    memcpy(&bits, &f, 4);
+    uint16_t sign = (uint16_t)((bits >> 16) & 0x8000u);
+    uint32_t absb = bits & 0x7FFFFFFFu;
+    if (absb >= 0x7F800000u) { /* inf / nan */
+        return (uint16_t)(sign | 0x7C00u | ((absb > 0x7F800000u) ? 0x200u : 0u));
+    }
+    if (absb >= 0x477FF000u) { /* >= 65520 rounds to infinity */
+        return (uint16_t)(sign | 0x7C00u);
+    }
+    if (absb < 0x33000001u) { /* <= 2^-25: rounds to zero (tie at 2^-25 goes to even = 0) */
+        return sign;
+    }
+    int32_t e = (int32_t)(absb >> 23) - 127; /* unbiased exponent */
+    uint32_t m = (absb & 0x7FFFFFu) | 0x800000u; /* 24-bit significand */
+    int shift; /* number of low bits of m to drop */
+    uint32_t base;
+    if (e >= -14) { /* normal half */
+        shift = 13;
+        base = (uint32_t)(e + 15) << 10;
+    } else { /* subnormal half: unit is 2^-24 */
+        shift = 13 + (-14 - e);
+        base = 0;
+    }
+    uint32_t kept = m >> shift;
+    uint32_t rem = m & ((1u << shift) - 1u);
+    uint32_t half = 1u << (shift - 1);
+    if (rem > half || (rem == half && (kept & 1u))) kept += 1u;
+    /* for normals 'kept' carries the implicit bit at position 10: adding it to
+       base - 0x400 lets a mantissa overflow bump the exponent naturally */
+    uint32_t out = (e >= -14) ? (base - 0x400u + kept) : kept;
+    return (uint16_t)(sign | out);
+}
+
+static float load_as_float(const void *p, int dt, int64_t idx)
+{
+    if (dt == 0) return ((const float *)p)[idx];
+    return mesa_ref_half_to_float(((const uint16_t *)p)[idx]);
+}
+
+static double load_as_double(const void *p, int dt, int64_t idx)
+{
+    return (double)load_as_float(p, dt, idx);
+}
+
+/* ------------------------------------------------------------------------ */
+/* Philox-4x32 counter-based generator (Salmon, Moraes, Dror, Shaw, SC'11)   */
+/* ------------------------------------------------------------------------ */
+
+#define MESA_REF_PHILOX_ROUNDS 10
+
+void mesa_ref_philox4x32(const uint32_t ctr[4], const uint32_t key[2], int rounds, uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int r = 0; r < rounds; ++r) {
+        if (r > 0) { /* Weyl sequence on the key: golden ratio and sqrt(3)-1 */
+            k0 += 0x9E3779B9u;
+            k1 += 0xBB67AE85u;
+        }
+        uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/*
+ * Random fraction for stochastic rounding of flat element e.
+ * Convention (the paper names no random source): elements are taken in blocks
+ * of 8; block b = e / 8 uses counter (offset + b) as a 64-bit value in counter
+ * words 0 and 1 (words 2, 3 zero) and the 64-bit seed as key words 0 and 1.
+ * Element j = e % 8 takes 16 bits: word j/2, low half for even j, high half
+ * for odd j; u = bits * 2^-16 lies in [0, 1).
+ */
+float mesa_ref_sr_uniform(uint64_t seed, uint64_t offset, uint64_t e)
+{
+    uint64_t c = offset + (e >> 3);
+    uint32_t ctr[4] = { (uint32_t)c, (uint32_t)(c >> 32), 0u, 0u };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t out[4];
+    mesa_ref_philox4x32(ctr, key, MESA_REF_PHILOX_ROUNDS, out);
+    unsigned j = (unsigned)(e & 7u);
+    uint32_t w = out[j >> 1];
+    uint32_t bits16 = (j & 1u) ? (w >> 16) : (w & 0xFFFFu);
+    return (float)bits16 * 1.52587890625e-05f; /* 2^-16, exact */
+}
+
+/* ------------------------------------------------------------------------ */
+/* Eq. (6), (7): running estimates                                           */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * For each group: min and max over every element of the group in this call
+ * (all samples and tokens: the parameters are shared across samples), then
+ *   first call : alpha = max - min, beta = min               (Sec. 5.1)
+ *   otherwise  : alpha = lambda*alpha + (1-lambda)*(max-min)  Eq. (6)
+ *                beta  = lambda*beta  + (1-lambda)*min        Eq. (7)
+ * each line one binary32 operation.
+ */
+int mesa_ref_update_running_params(const void *x, int dt, int64_t outer, int64_t groups, int64_t inner,
+                                   float *alpha, float *beta, float lambda, int first_call)
+{
+    if (outer <= 0 || groups <= 0 || inner <= 0) return 0;
+    for (int64_t g = 0; g < groups; ++g) {
+        float mn = INFINITY, mx = -INFINITY;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static) reduction(min : mn) reduction(max : mx)
+#endif
+        for (int64_t o = 0; o < outer; ++o) {
+            for (int64_t i = 0; i < inner; ++i) {
+                float v = load_as_float(x, dt, (o * groups + g) * inner + i);
+                if (v < mn) mn = v;
+                if (v > mx) mx = v;
+            }
+        }
+        float range = mx - mn;
+        if (first_call) {
+            alpha[g] = range;
+            beta[g] = mn;
+        } else {
+            float a = lambda * alpha[g];
+            float b = 1.0f - lambda;
+            float c = b * range;
+            alpha[g] = a + c;
+            float e = lambda * beta[g];
+            float f = b * mn;
+            beta[g] = e + f;
+        }
+    }
+    return 0;
+}
+
+/* raw per-group extrema, exposed for tests */
+int mesa_ref_group_minmax(const void *x, int dt, int64_t outer, int64_t groups, int64_t inner,
+                          float *mn_out, float *mx_out)
+{
+    for (int64_t g = 0; g < groups; ++g) {
+        float mn = INFINITY, mx = -INFINITY;
+        for (int64_t o = 0; o < outer; ++o)
+            for (int64_t i = 0; i < inner; ++i) {
+                float v = load_as_float(x, dt, (o * groups + g) * inner + i);
+                if (v < mn) mn = v;
+                if (v > mx) mx = v;
+            }
+        mn_out[g] = mn;
+        mx_out[g] = mx;
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Eq. (3), (4): quantize                                                    */
+/* ------------------------------------------------------------------------ */
+
+/* mode 0: round to nearest, ties to even; mode 1: stochastic rounding, Eq. (4) */
+int mesa_ref_quantize_headwise(const void *x, int dt, int64_t outer, int64_t groups, int64_t inner,
+                               const float *alpha, const float *beta, int8_t *q,
+                               int mode, uint64_t seed, uint64_t offset)
+{
+    if (outer <= 0 || groups <= 0 || inner <= 0) return 0;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t o = 0; o < outer; ++o) {
+        for (int64_t g = 0; g < groups; ++g) {
+            float a = alpha[g];
+            float b = beta[g];
+            float r = (a > 0.0f) ? 255.0f / a : 0.0f; /* constant group: every code is 0 */
+            for (int64_t i = 0; i < inner; ++i) {
+                int64_t e = (o * groups + g) * inner + i;
+                float xv = load_as_float(x, dt, e);
+                float t = xv - b;
+                float v = t * r;
+                float w;
+                if (mode == 0) {
+                    w = rintf(v); /* default rounding mode: nearest, ties to even */
+                } else {
+                    float u = mesa_ref_sr_uniform(seed, offset, (uint64_t)e);
+                    float s = v + u;  /* floor(v + u) rounds up with probability frac(v) */
+                    w = floorf(s);
+                }
+                if (w < 0.0f) w = 0.0f;
+                if (w > 255.0f) w = 255.0f;
+                q[e] = (int8_t)((int)w - 128);
+            }
+        }
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Eq. (5): dequantize                                                       */
+/* ------------------------------------------------------------------------ */
+
+static float dequant_one(int8_t code, float step, float b)
+{
+    float xh = (float)((int)code + 128) * step;
+    xh = xh + b;
+    return xh;
+}
+
+int mesa_ref_dequantize(const int8_t *q, int64_t outer, int64_t groups, int64_t inner,
+                        const float *alpha, const float *beta, void *x_hat, int dt)
+{
+    if (outer <= 0 || groups <= 0 || inner <= 0) return 0;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t o = 0; o < outer; ++o) {
+        for (int64_t g = 0; g < groups; ++g) {
+            float step = alpha[g] / 255.0f;
+            float b = beta[g];
+            for (int64_t i = 0; i < inner; ++i) {
+                int64_t e = (o * groups + g) * inner + i;
+                float xh = dequant_one(q[e], step, b);
+                if (dt == 0) ((float *)x_hat)[e] = xh;
+                else ((uint16_t *)x_hat)[e] = mesa_ref_float_to_half(xh);
+            }
+        }
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Eq. (2): layer gradients at x_hat                                         */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * Softmax.  The saved tensor is the softmax output y (the attention map,
+ * shape (B, H, rows, cols), one parameter pair per head).  For one row,
+ *   d = sum_j dy_j * y_hat_j,   dx_j = y_hat_j * (dy_j - d).
+ */
+int mesa_ref_softmax_bwd_q(const int8_t *yq, int64_t B, int64_t H, int64_t rows, int64_t cols,
+                           const float *alpha, const float *beta, const void *dy, int dt, double *dx)
+{
+    if (B <= 0 || H <= 0 || rows <= 0 || cols <= 0) return 0;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t b = 0; b < B; ++b) {
+        for (int64_t h = 0; h < H; ++h) {
+            float step = alpha[h] / 255.0f;
+            float off = beta[h];
+            for (int64_t r = 0; r < rows; ++r) {
+                int64_t base = ((b * H + h) * rows + r) * cols;
+                double d = 0.0;
+                for (int64_t j = 0; j < cols; ++j) {
+                    double yh = (double)dequant_one(yq[base + j], step, off);
+                    d += load_as_double(dy, dt, base + j) * yh;
+                }
+                for (int64_t j = 0; j < cols; ++j) {
+                    double yh = (double)dequant_one(yq[base + j], step, off);
+                    dx[base + j] = yh * (load_as_double(dy, dt, base + j) - d);
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+/*
+ * GELU (exact, erf form).  The saved tensor is the GELU input x.
+ *   gelu(x) = x * Phi(x),  gelu'(x) = Phi(x) + x * phi(x)
+ *   Phi(x) = (1 + erf(x / sqrt 2)) / 2,  phi(x) = exp(-x^2 / 2) / sqrt(2 pi)
+ */
+int mesa_ref_gelu_bwd_q(const int8_t *xq, int64_t outer, int64_t groups, int64_t inner,
+                        const float *alpha, const float *beta, const void *dy, int dt, double *dx)
+{
+    if (outer <= 0 || groups <= 0 || inner <= 0) return 0;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t o = 0; o < outer; ++o) {
+        for (int64_t g = 0; g < groups; ++g) {
+            float step = alpha[g] / 255.0f;
+            float off = beta[g];
+            for (int64_t i = 0; i < inner; ++i) {
+                int64_t e = (o * groups + g) * inner + i;
+                double xh = (double)dequant_one(xq[e], step, off);
+                double cdf = 0.5 * (1.0 + erf(xh / sqrt(2.0)));
+                double pdf = exp(-0.5 * xh * xh) / sqrt(2.0 * 3.14159265358979323846);
+                dx[e] = load_as_double(dy, dt, e) * (cdf + xh * pdf);
+            }
+        }
+    }
+    return 0;
+}
+
+/*
+ * LayerNorm over the last axis of an (M, D) matrix, D split into G channel
+ * groups of D/G columns.  Saved: codes of the input x plus the forward's own
+ * per-row mean and reciprocal standard deviation (binary32).
+ *   xn = (x_hat - mean) * rstd,  g = dy * gamma
+ *   dx = rstd * (g - mean_j(g) - xn * mean_j(g * xn))
+ *   dgamma_j = sum_rows dy * xn,  dbeta_j = sum_rows dy
+ */
+int mesa_ref_layernorm_bwd_q(const int8_t *xq, int64_t M, int64_t D, int64_t G,
+                             const float *alpha, const float *beta,
+                             const float *mean, const float *rstd, const void *gamma,
+                             const void *dy, int dt, double *dx, double *dgamma, double *dbeta)
+{
+    if (M <= 0 || D <= 0 || G <= 0 || D % G != 0) return (M <= 0 || D <= 0) ? 0 : 1;
+    int64_t per = D / G;
+    for (int64_t j = 0; j < D; ++j) { dgamma[j] = 0.0; dbeta[j] = 0.0; }
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t m = 0; m < M; ++m) {
+        double mu = (double)mean[m], rs = (double)rstd[m];
+        double s1 = 0.0, s2 = 0.0;
+        for (int64_t j = 0; j < D; ++j) {
+            int64_t g = j / per;
+            double xh = (double)dequant_one(xq[m * D + j], alpha[g] / 255.0f, beta[g]);
+            double xn = (xh - mu) * rs;
+            double gg = load_as_double(dy, dt, m * D + j) * load_as_double(gamma, dt, j);
+            s1 += gg;
+            s2 += gg * xn;
+        }
+        double c1 = s1 / (double)D, c2 = s2 / (double)D;
+        for (int64_t j = 0; j < D; ++j) {
+            int64_t g = j / per;
+            double xh = (double)dequant_one(xq[m * D + j], alpha[g] / 255.0f, beta[g]);
+            double xn = (xh - mu) * rs;
+            double gg = load_as_double(dy, dt, m * D + j) * load_as_double(gamma, dt, j);
+            dx[m * D + j] = rs * (gg - c1 - xn * c2);
+        }
+    }
+    /* column sums: rows in order, serial, so the result does not depend on threads */
+    for (int64_t m = 0; m < M; ++m) {
+        double mu = (double)mean[m], rs = (double)rstd[m];
+        for (int64_t j = 0; j < D; ++j) {
+            int64_t g = j / per;
+            double xh = (double)dequant_one(xq[m * D + j], alpha[g] / 255.0f, beta[g]);
+            double xn = (xh - mu) * rs;
+            double d = load_as_double(dy, dt, m * D + j);
+            dgamma[j] += d * xn;
+            dbeta[j] += d;
+        }
+    }
+    return 0;
+}
+
+/*
+ * Linear weight gradient.  y = x W^T with W of shape (N_out, K); saved: codes
+ * of x (M, K), K split into G channel groups.
+ *   dW[n, k] = sum_m dy[m, n] * x_hat[m, k],   db[n] = sum_m dy[m, n]
+ */
+static double dw_entry(const int8_t *xq, int64_t M, int64_t K, int64_t per,
+                       const float *alpha, const float *beta, const void *dy, int64_t N_out, int dt,
+                       int64_t n, int64_t k)
+{
+    int64_t g = k / per;
+    float step = alpha[g] / 255.0f;
+    float off = beta[g];
+    double acc = 0.0;
+    for (int64_t m = 0; m < M; ++m)
+        acc += load_as_double(dy, dt, m * N_out + n) * (double)dequant_one(xq[m * K + k], step, off);
+    return acc;
+}
+
+int mesa_ref_linear_dw_q(const int8_t *xq, int64_t M, int64_t K, int64_t G,
+                         const float *alpha, const float *beta, const void *dy, int64_t N_out, int dt,
+                         double *dW, double *db)
+{
+    if (M < 0 || K <= 0 || G <= 0 || N_out <= 0 || K % G != 0) return 1;
+    int64_t per = K / G;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t n = 0; n < N_out; ++n) {
+        for (int64_t k = 0; k < K; ++k)
+            dW[n * K + k] = dw_entry(xq, M, K, per, alpha, beta, dy, N_out, dt, n, k);
+        if (db) {
+            double acc = 0.0;
+            for (int64_t m = 0; m < M; ++m) acc += load_as_double(dy, dt, m * N_out + n);
+            db[n] = acc;
+        }
+    }
+    return 0;
+}
+
+/* the same definition at a list of (n, k) positions, for sizes where the full
+   matrix is out of reach of a CPU */
+int mesa_ref_linear_dw_q_entries(const int8_t *xq, int64_t M, int64_t K, int64_t G,
+                                 const float *alpha, const float *beta, const void *dy, int64_t N_out, int dt,
+                                 const int64_t *n_idx, const int64_t *k_idx, int64_t count, double *out)
+{
+    if (M < 0 || K <= 0 || G <= 0 || N_out <= 0 || K % G != 0) return 1;
+    int64_t per = K / G;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t t = 0; t < count; ++t)
+        out[t] = dw_entry(xq, M, K, per, alpha, beta, dy, N_out, dt, n_idx[t], k_idx[t]);
+    return 0;
+}
+
+int mesa_ref_num_threads(void)
+{
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

@@ -1,0 +1,214 @@
+"""ctypes shim over the CPU oracle (oracle/mesa_ref.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by __graft_entry__.smoke() and by
+bench.py's cpu_baseline leg.  It never imports the GPU package and the GPU
+package never imports it.  Arrays are numpy; binary16 tensors are passed as
+numpy float16 arrays (their raw bits are what the C side reads).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from pathlib import Path
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+_SRC = _HERE / "mesa_ref.c"
+_LIB = _HERE / "libmesa_ref.so"
+
+F32, F16 = 0, 1
+ROUND_NEAREST, ROUND_STOCHASTIC = 0, 1
+
+
+def build(force: bool = False) -> Path:
+    """Compile the oracle with gcc; -ffp-contract=off keeps every binary32
+    operation separately rounded, which the bit-exact comparisons rely on."""
+    if force or not _LIB.exists() or _LIB.stat().st_mtime < _SRC.stat().st_mtime:
+        tmp = _LIB.with_suffix(f".tmp{os.getpid()}.so")
+        cmd = ["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
+               "-shared", "-fPIC", "-o", str(tmp), str(_SRC), "-lm"]
+        subprocess.run(cmd, check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(str(build()))
+        _lib.mesa_ref_half_to_float.restype = C.c_float
+        _lib.mesa_ref_half_to_float.argtypes = [C.c_uint16]
+        _lib.mesa_ref_float_to_half.restype = C.c_uint16
+        _lib.mesa_ref_float_to_half.argtypes = [C.c_float]
+        _lib.mesa_ref_sr_uniform.restype = C.c_float
+        _lib.mesa_ref_sr_uniform.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64]
+        _lib.mesa_ref_num_threads.restype = C.c_int
+    return _lib
+
+
+def _dt(a: np.ndarray) -> int:
+    if a.dtype == np.float32:
+        return F32
+    if a.dtype == np.float16:
+        return F16
+    raise TypeError(f"unsupported dtype {a.dtype}")
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _c(a, dtype=None):
+    a = np.ascontiguousarray(a)
+    if dtype is not None and a.dtype != dtype:
+        a = a.astype(dtype)
+    return a
+
+
+I64 = C.c_int64
+
+
+def num_threads() -> int:
+    return int(lib().mesa_ref_num_threads())
+
+
+def half_to_float(bits: int) -> float:
+    return float(lib().mesa_ref_half_to_float(bits))
+
+
+def float_to_half(v: float) -> int:
+    return int(lib().mesa_ref_float_to_half(C.c_float(v)))
+
+
+def philox4x32(ctr, key, rounds=10):
+    c = (C.c_uint32 * 4)(*ctr)
+    k = (C.c_uint32 * 2)(*key)
+    out = (C.c_uint32 * 4)()
+    lib().mesa_ref_philox4x32(c, k, C.c_int(rounds), out)
+    return [int(v) for v in out]
+
+
+def sr_uniform(seed: int, offset: int, e: int) -> float:
+    return float(lib().mesa_ref_sr_uniform(seed, offset, e))
+
+
+def group_minmax(x, layout):
+    outer, groups, inner = layout
+    x = _c(x)
+    assert x.size == outer * groups * inner
+    mn = np.empty(groups, np.float32)
+    mx = np.empty(groups, np.float32)
+    lib().mesa_ref_group_minmax(_p(x), _dt(x), I64(outer), I64(groups), I64(inner), _p(mn), _p(mx))
+    return mn, mx
+
+
+def update_running_params(x, layout, alpha, beta, lam, first_call):
+    """Returns the new (alpha, beta); the inputs are not modified."""
+    outer, groups, inner = layout
+    x = _c(x)
+    assert x.size == outer * groups * inner
+    a = _c(alpha, np.float32).copy()
+    b = _c(beta, np.float32).copy()
+    assert a.size == groups and b.size == groups
+    lib().mesa_ref_update_running_params(_p(x), _dt(x), I64(outer), I64(groups), I64(inner),
+                                         _p(a), _p(b), C.c_float(lam), C.c_int(int(first_call)))
+    return a, b
+
+
+def quantize_headwise(x, layout, alpha, beta, mode=ROUND_NEAREST, seed=0, offset=0):
+    outer, groups, inner = layout
+    x = _c(x)
+    assert x.size == outer * groups * inner
+    a = _c(alpha, np.float32)
+    b = _c(beta, np.float32)
+    assert a.size == groups and b.size == groups
+    q = np.empty(x.size, np.int8)
+    lib().mesa_ref_quantize_headwise(_p(x), _dt(x), I64(outer), I64(groups), I64(inner), _p(a), _p(b), _p(q),
+                                     C.c_int(mode), C.c_uint64(seed), C.c_uint64(offset))
+    return q.reshape(x.shape)
+
+
+def dequantize(q, layout, alpha, beta, dtype=np.float32):
+    outer, groups, inner = layout
+    q = _c(q, np.int8)
+    assert q.size == outer * groups * inner
+    a = _c(alpha, np.float32)
+    b = _c(beta, np.float32)
+    out = np.empty(q.shape, dtype)
+    lib().mesa_ref_dequantize(_p(q), I64(outer), I64(groups), I64(inner), _p(a), _p(b), _p(out), _dt(out))
+    return out
+
+
+def softmax_bwd_q(yq, B, H, rows, cols, alpha, beta, dy):
+    yq = _c(yq, np.int8)
+    dy = _c(dy)
+    assert yq.size == B * H * rows * cols == dy.size
+    a = _c(alpha, np.float32)
+    b = _c(beta, np.float32)
+    dx = np.empty(yq.shape, np.float64)
+    lib().mesa_ref_softmax_bwd_q(_p(yq), I64(B), I64(H), I64(rows), I64(cols), _p(a), _p(b), _p(dy), _dt(dy), _p(dx))
+    return dx
+
+
+def gelu_bwd_q(xq, layout, alpha, beta, dy):
+    outer, groups, inner = layout
+    xq = _c(xq, np.int8)
+    dy = _c(dy)
+    assert xq.size == outer * groups * inner == dy.size
+    a = _c(alpha, np.float32)
+    b = _c(beta, np.float32)
+    dx = np.empty(xq.shape, np.float64)
+    lib().mesa_ref_gelu_bwd_q(_p(xq), I64(outer), I64(groups), I64(inner), _p(a), _p(b), _p(dy), _dt(dy), _p(dx))
+    return dx
+
+
+def layernorm_bwd_q(xq, M, D, G, alpha, beta, mean, rstd, gamma, dy):
+    xq = _c(xq, np.int8)
+    dy = _c(dy)
+    gamma = _c(gamma, dy.dtype)
+    assert xq.size == M * D == dy.size and gamma.size == D
+    a = _c(alpha, np.float32)
+    b = _c(beta, np.float32)
+    mean = _c(mean, np.float32)
+    rstd = _c(rstd, np.float32)
+    assert mean.size == M and rstd.size == M
+    dx = np.empty((M, D), np.float64)
+    dg = np.empty(D, np.float64)
+    db = np.empty(D, np.float64)
+    rc = lib().mesa_ref_layernorm_bwd_q(_p(xq), I64(M), I64(D), I64(G), _p(a), _p(b), _p(mean), _p(rstd), _p(gamma),
+                                        _p(dy), _dt(dy), _p(dx), _p(dg), _p(db))
+    assert rc == 0
+    return dx, dg, db
+
+
+def linear_dw_q(xq, M, K, G, alpha, beta, dy, N_out):
+    xq = _c(xq, np.int8)
+    dy = _c(dy)
+    assert xq.size == M * K and dy.size == M * N_out
+    a = _c(alpha, np.float32)
+    b = _c(beta, np.float32)
+    dW = np.empty((N_out, K), np.float64)
+    db = np.empty(N_out, np.float64)
+    rc = lib().mesa_ref_linear_dw_q(_p(xq), I64(M), I64(K), I64(G), _p(a), _p(b), _p(dy), I64(N_out), _dt(dy),
+                                    _p(dW), _p(db))
+    assert rc == 0
+    return dW, db
+
+
+def linear_dw_q_entries(xq, M, K, G, alpha, beta, dy, N_out, n_idx, k_idx):
+    xq = _c(xq, np.int8)
+    dy = _c(dy)
+    n_idx = _c(n_idx, np.int64)
+    k_idx = _c(k_idx, np.int64)
+    a = _c(alpha, np.float32)
+    b = _c(beta, np.float32)
+    out = np.empty(n_idx.size, np.float64)
+    rc = lib().mesa_ref_linear_dw_q_entries(_p(xq), I64(M), I64(K), I64(G), _p(a), _p(b), _p(dy), I64(N_out),
+                                            _dt(dy), _p(n_idx), _p(k_idx), I64(n_idx.size), _p(out))
+    assert rc == 0
+    return out

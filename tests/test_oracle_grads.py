@@ -1,0 +1,245 @@
+"""Pins for the oracle's layer gradients (Sec. 3.1, Eq. 2: the ordinary gradient function of the
+layer evaluated at the de-quantized activation).
+
+The paper prints no per-layer formula, so each one is pinned three ways: central finite
+differences of a forward written here in numpy (with inputs placed on the quantization grid, so
+x_hat = x and Eq. 2 is the true gradient), torch.autograd in fp64 at x_hat (a library routine for
+this exact special case), and identities the formulas must satisfy.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import mesa_ref as R
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+erf = np.vectorize(math.erf)
+
+
+def on_grid(rng, shape, G, step_log2=-5, lo=-4.0):
+    """Random codes with per-group parameters whose step is a power of two: x_hat is exact."""
+    codes = rng.integers(0, 256, size=shape)
+    step = 2.0 ** step_log2
+    alpha = np.full(G, 255.0 * step, np.float32)
+    beta = (lo + np.arange(G) * 0.25).astype(np.float32)
+    return codes, alpha, beta, step
+
+
+def fd_grad(f, x, eps=1e-6):
+    """dL/dx by central differences for scalar-valued f."""
+    g = np.zeros_like(x)
+    it = np.nditer(x, flags=["multi_index"])
+    for _ in it:
+        i = it.multi_index
+        xp, xm = x.copy(), x.copy()
+        xp[i] += eps
+        xm[i] -= eps
+        g[i] = (f(xp) - f(xm)) / (2 * eps)
+    return g
+
+
+def relerr(a, b):
+    return np.abs(a - b).max() / max(np.abs(b).max(), 1e-300)
+
+
+# ----------------------------------------------------------------------------- softmax
+
+def test_softmax_backward_against_finite_differences():
+    rng = np.random.default_rng(0)
+    B, H, rows, cols = 1, 2, 3, 6
+    # rows of y = k/256 with sum 256: exactly representable, sums to one, step 2^-8 exact
+    k = np.zeros((B, H, rows, cols), np.int64)
+    for idx in np.ndindex(B, H, rows):
+        cuts = np.sort(rng.choice(np.arange(1, 256), cols - 1, replace=False))
+        k[idx] = np.diff(np.concatenate([[0], cuts, [256]]))
+    assert k.max() <= 255 and (k.sum(-1) == 256).all()
+    alpha, beta = np.full(H, 255.0 / 256.0, np.float32), np.zeros(H, np.float32)
+    y = k / 256.0
+    dy = rng.standard_normal(y.shape).astype(np.float32)
+    dx = R.softmax_bwd_q((k - 128).astype(np.int8), B, H, rows, cols, alpha, beta, dy)
+    z = np.log(y)
+
+    def loss(zz):
+        e = np.exp(zz - zz.max(-1, keepdims=True))
+        return float((dy.astype(np.float64) * e / e.sum(-1, keepdims=True)).sum())
+
+    assert relerr(dx, fd_grad(loss, z)) < 1e-6
+
+
+def test_softmax_backward_rows_sum_to_zero_when_y_sums_to_one_and_in_general_to_d_times_the_defect():
+    rng = np.random.default_rng(1)
+    B, H, rows, cols = 2, 3, 5, 11
+    k = rng.integers(0, 256, (B, H, rows, cols))
+    alpha = np.array([0.7, 0.05, 0.3], np.float32)
+    beta = np.array([0.0, 0.01, 0.002], np.float32)
+    dy = rng.standard_normal(k.shape).astype(np.float32)
+    q = (k - 128).astype(np.int8)
+    dx = R.softmax_bwd_q(q, B, H, rows, cols, alpha, beta, dy)
+    yh = R.dequantize(q, (B, H, rows * cols), alpha, beta).astype(np.float64).reshape(k.shape)
+    d = (dy * yh).sum(-1)
+    assert np.allclose(dx.sum(-1), d * (1.0 - yh.sum(-1)), rtol=1e-9, atol=1e-9)
+    # exact-sum rows: the generalised identity collapses to a zero row sum
+    k1 = np.zeros((1, 1, 4, 8), np.int64)
+    k1[..., :] = [100, 50, 30, 20, 16, 24, 8, 8]
+    dy1 = rng.standard_normal(k1.shape).astype(np.float32)
+    dx1 = R.softmax_bwd_q((k1 - 128).astype(np.int8), 1, 1, 4, 8, [255.0 / 256.0], [0.0], dy1)
+    assert np.abs(dx1.sum(-1)).max() < 1e-12
+
+
+def test_softmax_backward_matches_torch_at_y_hat():
+    rng = np.random.default_rng(2)
+    B, H, rows, cols = 2, 3, 7, 13
+    q = rng.integers(-128, 128, (B, H, rows, cols)).astype(np.int8)
+    alpha, beta = np.array([0.9, 0.2, 0.5], np.float32), np.array([0.0, 0.003, 0.01], np.float32)
+    for dt in (np.float32, np.float16):
+        dy = rng.standard_normal(q.shape).astype(dt)
+        dx = R.softmax_bwd_q(q, B, H, rows, cols, alpha, beta, dy)
+        yh = torch.from_numpy(R.dequantize(q, (B, H, rows * cols), alpha, beta).reshape(q.shape)).double()
+        want = torch._softmax_backward_data(torch.from_numpy(dy.astype(np.float64)), yh, -1, torch.float64).numpy()
+        assert relerr(dx, want) < 1e-12
+
+
+# ----------------------------------------------------------------------------- GELU
+
+def gelu(x):
+    return 0.5 * x * (1.0 + erf(x / math.sqrt(2.0)))
+
+
+def test_gelu_backward_against_finite_differences_and_torch():
+    rng = np.random.default_rng(3)
+    outer, G, inner = 3, 2, 5
+    codes, alpha, beta, step = on_grid(rng, (outer, G, inner), G)
+    x = beta[None, :, None].astype(np.float64) + codes * step
+    dy = rng.standard_normal(x.shape).astype(np.float32)
+    dx = R.gelu_bwd_q((codes - 128).astype(np.int8), (outer, G, inner), alpha, beta, dy)
+    assert relerr(dx, fd_grad(lambda v: float((dy * gelu(v)).sum()), x)) < 1e-6
+    xt = torch.from_numpy(x).requires_grad_(True)
+    torch.nn.functional.gelu(xt).backward(torch.from_numpy(dy.astype(np.float64)))
+    assert relerr(dx, xt.grad.numpy()) < 1e-12
+
+
+def test_gelu_derivative_vanishes_at_the_minimum_the_paper_prints():
+    # FFN visualisation section: the offset of the second FC layer's input sits at min GELU = -0.17
+    want = float([l for l in open(os.path.join(GOLD, "gelu_min.txt")) if not l.startswith("#")][0])
+    step = 2.0 ** -10
+    alpha, beta = np.array([255 * step], np.float32), np.array([-0.875], np.float32)
+    codes = np.arange(256)
+    g = R.gelu_bwd_q((codes - 128).astype(np.int8), (1, 1, 256), alpha, beta, np.ones(256, np.float32))
+    x = -0.875 + codes * step
+    s = np.nonzero(np.diff(np.sign(g)))[0]
+    assert s.size == 1                        # one sign change of the derivative: the minimum
+    xmin = 0.5 * (x[s[0]] + x[s[0] + 1])
+    assert g[0] < 0 < g[-1]
+    assert round(float(gelu(xmin)), 2) == want
+    assert abs(float(gelu(xmin)) + 0.16997) < 2e-5
+
+
+# ----------------------------------------------------------------------------- LayerNorm
+
+def ln_forward(x, gamma, eps):
+    mu = x.mean(-1, keepdims=True)
+    var = ((x - mu) ** 2).mean(-1, keepdims=True)
+    return (x - mu) / np.sqrt(var + eps) * gamma
+
+
+def test_layernorm_backward_against_finite_differences():
+    rng = np.random.default_rng(4)
+    M, D, G = 3, 8, 2
+    codes, alpha, beta, step = on_grid(rng, (M, D), G)
+    x = np.repeat(beta.astype(np.float64), D // G)[None, :] + codes * step
+    gamma = rng.uniform(0.5, 1.5, D).astype(np.float32)
+    dy = rng.standard_normal((M, D)).astype(np.float32)
+    eps = 1e-5
+    mean = x.mean(-1)
+    rstd = 1.0 / np.sqrt(x.var(-1) + eps)
+    dx, dg, db = R.layernorm_bwd_q((codes - 128).astype(np.int8), M, D, G, alpha, beta,
+                                   mean.astype(np.float32), rstd.astype(np.float32), gamma, dy)
+    g64 = gamma.astype(np.float64)
+    assert relerr(dx, fd_grad(lambda v: float((dy * ln_forward(v, g64, eps)).sum()), x)) < 2e-6
+    assert relerr(dg, fd_grad(lambda gm: float((dy * ln_forward(x, gm, eps)).sum()), g64)) < 2e-6
+    assert np.allclose(db, dy.astype(np.float64).sum(0), rtol=1e-12)
+
+
+@pytest.mark.parametrize("dt", [np.float32, np.float16])
+def test_layernorm_backward_matches_torch_at_x_hat(dt):
+    rng = np.random.default_rng(5)
+    M, D, G = 6, 24, 3
+    q = rng.integers(-128, 128, (M, D)).astype(np.int8)
+    alpha, beta = np.array([3.0, 8.0, 1.5], np.float32), np.array([-1.0, -4.0, 0.5], np.float32)
+    xh = R.dequantize(q, (M, G, D // G), alpha, beta).astype(np.float64)
+    gamma = rng.uniform(0.5, 1.5, D).astype(dt)
+    dy = rng.standard_normal((M, D)).astype(dt)
+    eps = 1e-5
+    mean, rstd = xh.mean(-1), 1.0 / np.sqrt(xh.var(-1) + eps)
+    dx, dg, db = R.layernorm_bwd_q(q, M, D, G, alpha, beta, mean.astype(np.float32), rstd.astype(np.float32), gamma, dy)
+    xt = torch.from_numpy(xh).requires_grad_(True)
+    gt = torch.from_numpy(gamma.astype(np.float64)).requires_grad_(True)
+    bt = torch.zeros(D, dtype=torch.float64, requires_grad=True)
+    torch.nn.functional.layer_norm(xt, (D,), gt, bt, eps).backward(torch.from_numpy(dy.astype(np.float64)))
+    assert relerr(dx, xt.grad.numpy()) < 1e-6      # mean / rstd were rounded to binary32 on the way in
+    assert relerr(dg, gt.grad.numpy()) < 1e-6
+    assert relerr(db, bt.grad.numpy()) < 1e-12
+
+
+def test_layernorm_backward_row_identity():
+    # sum_j dx_j = -rstd * mean(g * xn) * sum_j xn_j  (zero when the saved statistics are x_hat's own)
+    rng = np.random.default_rng(6)
+    M, D, G = 4, 16, 4
+    q = rng.integers(-128, 128, (M, D)).astype(np.int8)
+    alpha, beta = rng.uniform(1, 5, G).astype(np.float32), rng.uniform(-2, 0, G).astype(np.float32)
+    xh = R.dequantize(q, (M, G, D // G), alpha, beta).astype(np.float64)
+    mean = (xh.mean(-1) + 0.05).astype(np.float32)          # deliberately not x_hat's own statistics
+    rstd = (1.0 / np.sqrt(xh.var(-1) + 1e-5) * 1.1).astype(np.float32)
+    gamma = rng.uniform(0.5, 1.5, D).astype(np.float32)
+    dy = rng.standard_normal((M, D)).astype(np.float32)
+    dx, _, _ = R.layernorm_bwd_q(q, M, D, G, alpha, beta, mean, rstd, gamma, dy)
+    xn = (xh - mean[:, None].astype(np.float64)) * rstd[:, None].astype(np.float64)
+    gg = dy.astype(np.float64) * gamma.astype(np.float64)
+    want = -rstd.astype(np.float64) * (gg * xn).mean(-1) * xn.sum(-1)
+    assert np.allclose(dx.sum(-1), want, rtol=1e-9, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------- Linear dW
+
+def test_linear_dw_is_exact_on_integers():
+    # alpha = 255, beta = 0: x_hat = q + 128 are integers; integer dy -> exact integer result
+    rng = np.random.default_rng(7)
+    M, K, N = 37, 12, 9
+    q = rng.integers(-128, 128, (M, K)).astype(np.int8)
+    dy = rng.integers(-8, 9, (M, N)).astype(np.float32)
+    dW, db = R.linear_dw_q(q, M, K, 3, np.full(3, 255.0, np.float32), np.zeros(3, np.float32), dy, N)
+    want = dy.astype(np.int64).T @ (q.astype(np.int64) + 128)
+    assert dW.shape == (N, K)
+    assert np.array_equal(dW, want.astype(np.float64))
+    assert np.array_equal(db, dy.astype(np.int64).sum(0).astype(np.float64))
+
+
+@pytest.mark.parametrize("dt", [np.float32, np.float16])
+def test_linear_dw_matches_torch_fd_and_the_factored_form(dt):
+    rng = np.random.default_rng(8)
+    M, K, N, G = 29, 8, 5, 2
+    q = rng.integers(-128, 128, (M, K)).astype(np.int8)
+    alpha, beta = np.array([2.0, 7.0], np.float32), np.array([-1.0, -3.0], np.float32)
+    dy = rng.standard_normal((M, N)).astype(dt)
+    dW, db = R.linear_dw_q(q, M, K, G, alpha, beta, dy, N)
+    xh = R.dequantize(q, (M, G, K // G), alpha, beta).astype(np.float64)
+    dy64 = dy.astype(np.float64)
+    # autograd of y = x W^T
+    Wt = torch.zeros((N, K), dtype=torch.float64, requires_grad=True)
+    (torch.from_numpy(xh) @ Wt.T).backward(torch.from_numpy(dy64))
+    assert relerr(dW, Wt.grad.numpy()) < 1e-13
+    # finite differences (the loss is linear in W, so they are exact up to rounding)
+    W0 = rng.standard_normal((N, K))
+    assert relerr(dW, fd_grad(lambda w: float((dy64 * (xh @ w.T)).sum()), W0, eps=1e-3)) < 1e-8
+    # factored form used by matrix-core implementations: s_g * (dy^T u) + beta_g * colsum(dy)
+    s = np.repeat((alpha / np.float32(255.0)).astype(np.float64), K // G)
+    bcol = np.repeat(beta.astype(np.float64), K // G)
+    fact = (dy64.T @ (q.astype(np.float64) + 128)) * s[None, :] + dy64.sum(0)[:, None] * bcol[None, :]
+    assert relerr(dW, fact) < 1e-6    # x_hat itself is rounded to binary32, the factored form is not
+    # sampled entries agree with the full matrix
+    n_idx, k_idx = np.array([0, 4, 2]), np.array([7, 0, 3])
+    ent = R.linear_dw_q_entries(q, M, K, G, alpha, beta, dy, N, n_idx, k_idx)
+    assert np.array_equal(ent, dW[n_idx, k_idx])

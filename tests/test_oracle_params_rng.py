@@ -1,0 +1,98 @@
+"""Pins for the oracle's running estimates (Sec. 3.2, Eq. 6-7; initialisation per Sec. 5.1) and for
+its counter-based generator (published known-answer vectors)."""
+import os
+
+import numpy as np
+
+from oracle import mesa_ref as R
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _x(seed, shape, dtype=np.float32):
+    return (np.random.default_rng(seed).standard_normal(shape) * 3).astype(dtype)
+
+
+def test_group_extrema_match_numpy_reductions():
+    for dtype in (np.float32, np.float16):
+        x = _x(0, (5, 4, 33), dtype)
+        mn, mx = R.group_minmax(x, (5, 4, 33))
+        assert np.array_equal(mn, x.astype(np.float32).min(axis=(0, 2)))
+        assert np.array_equal(mx, x.astype(np.float32).max(axis=(0, 2)))
+
+
+def test_first_call_sets_range_and_minimum_exactly():
+    x = _x(1, (6, 3, 50))
+    a, b = R.update_running_params(x, (6, 3, 50), np.full(3, 77.0), np.full(3, -55.0), 0.9, True)
+    mn, mx = x.min(axis=(0, 2)), x.max(axis=(0, 2))
+    assert np.array_equal(b, mn) and np.array_equal(a, mx - mn)
+
+
+def test_lambda_zero_tracks_the_current_batch():
+    # the paper's lambda = 0 row: parameters are the current min / max every iteration
+    a, b = np.full(3, 9.0, np.float32), np.full(3, 9.0, np.float32)
+    for it in range(3):
+        x = _x(10 + it, (4, 3, 20))
+        a, b = R.update_running_params(x, (4, 3, 20), a, b, 0.0, False)
+        mn, mx = x.min(axis=(0, 2)), x.max(axis=(0, 2))
+        assert np.array_equal(b, mn) and np.array_equal(a, mx - mn)
+
+
+def test_constant_statistics_follow_the_closed_form_of_the_recursion():
+    # alpha_t = lam^t alpha_0 + (1 - lam^t) * range, beta_t likewise with the minimum
+    x = _x(2, (4, 2, 30))
+    mn, mx = x.min(axis=(0, 2)).astype(np.float64), x.max(axis=(0, 2)).astype(np.float64)
+    lam = 0.9
+    a0, b0 = np.array([10.0, 0.5]), np.array([-7.0, 3.0])
+    a, b = a0.astype(np.float32), b0.astype(np.float32)
+    for t in range(1, 41):
+        a, b = R.update_running_params(x, (4, 2, 30), a, b, lam, False)
+        lt = np.float64(np.float32(lam)) ** t
+        assert np.allclose(a, lt * a0 + (1 - lt) * (mx - mn), rtol=2e-6, atol=1e-6)
+        assert np.allclose(b, lt * b0 + (1 - lt) * mn, rtol=2e-6, atol=1e-6)
+    for _ in range(400):
+        a, b = R.update_running_params(x, (4, 2, 30), a, b, lam, False)
+    assert np.allclose(a, mx - mn, rtol=1e-6) and np.allclose(b, mn, rtol=1e-6)   # fixed point
+
+
+def test_parameters_are_shared_across_samples():
+    # permuting the samples of the batch, or the positions inside a group, changes nothing
+    x = _x(3, (8, 3, 40), np.float16)
+    a0, b0 = np.full(3, 2.0, np.float32), np.full(3, -1.0, np.float32)
+    a, b = R.update_running_params(x, (8, 3, 40), a0, b0, 0.9, False)
+    rng = np.random.default_rng(4)
+    xp = x[rng.permutation(8)][:, :, rng.permutation(40)]
+    a2, b2 = R.update_running_params(xp, (8, 3, 40), a0, b0, 0.9, False)
+    assert np.array_equal(a, a2) and np.array_equal(b, b2)
+    assert a.shape == (3,) and b.shape == (3,)    # 2 * N_h parameters per layer
+
+
+def test_philox_known_answers():
+    rows = [l.split() for l in open(os.path.join(GOLD, "philox4x32_10_kat.txt")) if l.strip() and not l.startswith("#")]
+    assert len(rows) == 3
+    for r in rows:
+        v = [int(t, 16) for t in r]
+        assert R.philox4x32(v[0:4], v[4:6], 10) == v[6:10]
+
+
+def test_random_fractions_follow_the_documented_bit_assignment():
+    # block b = e // 8 -> counter offset + b (64-bit, words 0-1), key = seed; element j takes 16 bits
+    seed, offset = 0x0123456789ABCDEF, (1 << 32) - 3
+    for e in (0, 1, 7, 8, 29, 63, 1000, (1 << 35) + 5):
+        c = offset + (e >> 3)
+        out = R.philox4x32([c & 0xFFFFFFFF, c >> 32, 0, 0], [seed & 0xFFFFFFFF, seed >> 32], 10)
+        w = out[(e & 7) >> 1]
+        bits = (w >> 16) if (e & 1) else (w & 0xFFFF)
+        assert R.sr_uniform(seed, offset, e) == bits / 65536.0
+    # advancing the offset by one block is the same as moving on by eight elements
+    assert R.sr_uniform(5, 11, 3) == R.sr_uniform(5, 0, 3 + 8 * 11)
+
+
+def test_random_fractions_are_uniform():
+    u = np.array([R.sr_uniform(42, 0, e) for e in range(40000)])
+    assert 0.0 <= u.min() and u.max() < 1.0
+    hist, _ = np.histogram(u, bins=64, range=(0, 1))
+    exp = u.size / 64
+    chi2 = ((hist - exp) ** 2 / exp).sum()
+    assert chi2 < 120          # 63 degrees of freedom, p ~ 1e-5
+    assert abs(np.corrcoef(u[:-1], u[1:])[0, 1]) < 0.02
