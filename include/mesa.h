@@ -1,0 +1,178 @@
+/*
+ * mesa.h -- C ABI of libmesa: Mesa's activation-compression hot path on one MI355X (gfx950).
+ *
+ * Forward half: 8-bit quantization of the activations a Transformer layer saves, head-wise for
+ * multi-head self-attention and channel-group-wise elsewhere, with the clipping range alpha and
+ * the offset beta kept as running estimates.  Backward half: de-quantization fused into the
+ * gradients of softmax, GELU, LayerNorm and the Linear weight gradient.
+ * (Mesa, arXiv 2111.11124: Sec. 3.1 Eq. 1-2; Sec. 3.2 Eq. 3-7; Fig. "bucketing"; Sec. 3.3.)
+ *
+ * Common conventions
+ *   Pointers    Every data pointer is a DEVICE pointer owned by the caller.  The library never
+ *               allocates, frees or keeps one.  x, q, dy, dx, x_hat, dW and ws must be 16-byte
+ *               aligned; alpha, beta, mean, rstd, gamma, dgamma, dbeta, db 4-byte aligned.
+ *   Layout      A tensor is contiguous and viewed as (outer, groups, inner): element (o, g, i) is
+ *               at flat index (o*groups + g)*inner + i and uses alpha[g], beta[g].
+ *                 head-wise (q, k, v, attention):  (B, N_h, N, D_h) -> outer=B, groups=N_h, inner=N*D_h
+ *                 channel groups (token matrices): (B*N, D)        -> outer=B*N, groups=G, inner=D/G
+ *   Codes       int8, q = x_bar - 128 with x_bar in [0, 255] from Eq. (3); Eq. (5) adds 128 back.
+ *   Parameters  alpha[g], beta[g]: binary32 on the device, 2*groups values per tensor.
+ *   dtype       storage type of activations and gradients; all arithmetic is binary32
+ *               (the matrix-core contraction multiplies in the storage type, accumulates binary32).
+ *   stream      a hipStream_t (NULL = the default stream).  Every call only enqueues kernels and
+ *               returns; there is no host synchronisation and no host read of device data.
+ *   ws          caller-provided device scratch of at least mesa_workspace_bytes(...) bytes; its
+ *               contents are undefined before and after a call.
+ *   Errors      Arguments are checked on the host before anything is enqueued.  On any error
+ *               nothing is written.  Zero elements is MESA_OK and a no-op.
+ *   Threads     No global mutable state; calls on distinct streams may run concurrently provided
+ *               they use distinct ws and outputs.
+ *   Limits      groups <= 8192; for groups > 1, inner < 2^31.  Outside them: MESA_ERR_UNSUPPORTED.
+ */
+#ifndef MESA_H
+#define MESA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MESA_OK = 0,
+    MESA_ERR_INVALID_ARG = 1,  /* null pointer, negative extent, misaligned pointer, bad enum, lambda outside [0,1] */
+    MESA_ERR_UNSUPPORTED = 2,  /* a shape outside the limits stated with each call */
+    MESA_ERR_WORKSPACE = 3,    /* ws is null or ws_bytes is too small */
+    MESA_ERR_LAUNCH = 4        /* the HIP runtime reported an error at launch */
+} mesa_status;
+
+typedef enum { MESA_F32 = 0, MESA_F16 = 1 } mesa_dtype;
+
+typedef enum {
+    MESA_ROUND_NEAREST_EVEN = 0, /* ablation "nearest rounding"; ties to even */
+    MESA_ROUND_STOCHASTIC = 1    /* Eq. (4), the method's default */
+} mesa_round;
+
+typedef struct { int64_t outer, groups, inner; } mesa_layout;
+
+typedef enum {
+    MESA_OP_UPDATE_RUNNING_PARAMS = 0, /* d0,d1,d2 = outer, groups, inner */
+    MESA_OP_LAYERNORM_BWD_Q = 1,       /* d0,d1,d2 = M, D, G */
+    MESA_OP_LINEAR_DW_Q = 2            /* d0,d1,d2 = M, K, N_out */
+} mesa_op;
+
+/*
+ * Running estimates, Sec. 3.2 Eq. (6)-(7); initialisation from the first iteration's min-max
+ * (Sec. 5.1, implementation details).
+ *   mn_g, mx_g = min / max over every element of group g in x (all samples: the parameters are
+ *   shared across samples).
+ *   first_call != 0:  alpha_g = mx_g - mn_g,  beta_g = mn_g
+ *   otherwise:        alpha_g = lambda*alpha_g + (1-lambda)*(mx_g - mn_g)
+ *                     beta_g  = lambda*beta_g  + (1-lambda)*mn_g
+ * in binary32, each product, difference and sum rounded separately (no fused multiply-add), so the
+ * result is reproducible bit for bit.  A minimum of -0.0 is returned as +0.0.
+ * x: [outer*groups*inner] of dt (in).  alpha, beta: [groups] binary32 (in/out).
+ * ws: MESA_OP_UPDATE_RUNNING_PARAMS bytes.
+ */
+mesa_status mesa_update_running_params(const void *x, mesa_dtype dt, mesa_layout L,
+                                       float *alpha, float *beta, float lambda, int first_call,
+                                       void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Quantizer, Sec. 3.2 Eq. (3)-(4):  x_bar = clip(round((x - beta_g) * (255 / alpha_g)), 0, 255).
+ * binary32, separately rounded: r = 255/alpha_g (0 when alpha_g <= 0), t = x - beta_g, v = t*r,
+ *   nearest:     w = v rounded to the nearest integer, ties to even
+ *   stochastic:  w = floor(v + u), u in [0,1) -- rounds up with probability frac(v)
+ * then w is clipped to [0, 255] and stored as q = w - 128.
+ * Random source (the paper names none): Philox-4x32-10 keyed by `seed`; the counter is
+ * offset + e/8 for flat element index e (64-bit, counter words 0-1), and element e takes 16 bits of
+ * the 128-bit output: word (e%8)/2, low half for even e, high half for odd e; u = bits * 2^-16.
+ * A caller advances `offset` by ceil(numel/8) between calls so that streams never repeat.
+ * x: [numel] of dt (in).  q: [numel] int8 (out).  alpha, beta: [groups] (in).
+ */
+mesa_status mesa_quantize_headwise(const void *x, mesa_dtype dt, mesa_layout L,
+                                   const float *alpha, const float *beta, int8_t *q,
+                                   mesa_round mode, uint64_t seed, uint64_t offset, void *stream);
+
+/*
+ * De-quantizer, Sec. 3.2 Eq. (5):  x_hat = (q + 128) * (alpha_g / 255) + beta_g, binary32 with the
+ * quotient, product and sum rounded separately, then rounded to dt (nearest even).
+ * q: [numel] int8 (in).  x_hat: [numel] of dt (out).
+ */
+mesa_status mesa_dequantize(const int8_t *q, mesa_layout L, const float *alpha, const float *beta,
+                            void *x_hat, mesa_dtype dt, void *stream);
+
+/*
+ * Softmax backward at the de-quantized output, Sec. 3.1 Eq. (2) with G_l = softmax's gradient.
+ * The saved tensor is the softmax OUTPUT y (the attention map), shape (B, H, rows, cols),
+ * head-wise parameters alpha[H], beta[H].  Per row:  d = sum_j dy_j*y_hat_j,
+ * dx_j = y_hat_j * (dy_j - d), accumulated in binary32.
+ * yq: int8 (in); dy, dx: [B*H*rows*cols] of dt (in / out); dx may alias dy.
+ * Limits: 8 <= cols <= 16384 and B*H*rows < 2^31, else MESA_ERR_UNSUPPORTED.
+ */
+mesa_status mesa_softmax_bwd_q(const int8_t *yq, int64_t B, int64_t H, int64_t rows, int64_t cols,
+                               const float *alpha, const float *beta, const void *dy, void *dx,
+                               mesa_dtype dt, void *stream);
+
+/*
+ * GELU backward at the de-quantized input, Eq. (2) with the exact (erf) GELU:
+ *   dx = dy * (Phi(x_hat) + x_hat*phi(x_hat)),  Phi / phi the standard normal cdf / pdf.
+ * xq: int8 (in), channel-group layout L; dy, dx: [numel] of dt; dx may alias dy.
+ */
+mesa_status mesa_gelu_bwd_q(const int8_t *xq, mesa_layout L, const float *alpha, const float *beta,
+                            const void *dy, void *dx, mesa_dtype dt, void *stream);
+
+/*
+ * LayerNorm backward at the de-quantized input, Eq. (2).  Saved: codes of the input x (M, D) in G
+ * channel groups of D/G columns, plus the forward's per-row mean and 1/sqrt(var+eps) (binary32).
+ *   xn = (x_hat - mean)*rstd,  g = dy*gamma,
+ *   dx = rstd * (g - mean_j(g) - xn*mean_j(g*xn)),
+ *   dgamma_j = sum_rows dy*xn,  dbeta_j = sum_rows dy        (binary32, fixed summation order)
+ * gamma: [D] of dt.  dx: (M, D) of dt, may alias dy.  dgamma, dbeta: [D] binary32 (overwritten).
+ * ws: MESA_OP_LAYERNORM_BWD_Q bytes.
+ * Limits: D % 8 == 0, (D/G) % 8 == 0, D <= 8192, else MESA_ERR_UNSUPPORTED.
+ */
+mesa_status mesa_layernorm_bwd_q(const int8_t *xq, int64_t M, int64_t D, int64_t G,
+                                 const float *alpha, const float *beta,
+                                 const float *mean, const float *rstd, const void *gamma,
+                                 const void *dy, void *dx, float *dgamma, float *dbeta, mesa_dtype dt,
+                                 void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Linear weight gradient at the de-quantized input, Eq. (2) for y = x W^T, W of shape (N_out, K):
+ *   dW[n, k] = sum_m dy[m, n] * x_hat[m, k],   db[n] = sum_m dy[m, n]
+ * evaluated as  s_g(k) * sum_m dy[m,n]*(q[m,k]+128)  +  beta_g(k) * db[n]  on the matrix cores
+ * (binary16 products for MESA_F16, binary32 accumulation; fixed summation order).
+ * xq: (M, K) int8, K in G channel groups.  dy: (M, N_out) of dt.  dW: (N_out, K) binary32, row-major,
+ * overwritten.  db: [N_out] binary32 or NULL.  ws: MESA_OP_LINEAR_DW_Q bytes.
+ * Limits: K % 16 == 0, N_out % 8 == 0, K % G == 0, else MESA_ERR_UNSUPPORTED.
+ */
+mesa_status mesa_linear_dw_q(const int8_t *xq, int64_t M, int64_t K, int64_t G,
+                             const float *alpha, const float *beta,
+                             const void *dy, int64_t N_out, mesa_dtype dt,
+                             float *dW, float *db, void *ws, size_t ws_bytes, void *stream);
+
+/* Scratch size in bytes for `op` at the given extents (see mesa_op); 0 for unknown ops. */
+size_t mesa_workspace_bytes(mesa_op op, int64_t d0, int64_t d1, int64_t d2, mesa_dtype dt);
+
+const char *mesa_status_string(mesa_status s);
+int mesa_version(void);
+
+/*
+ * Measurement helpers (not part of the method).
+ * mesa_stream_copy: plain device-to-device copy kernel of `bytes` bytes (both pointers 16-byte
+ * aligned, bytes % 16 == 0): the known-traffic kernel that bandwidth counters are scaled against.
+ * mesa_event_*: HIP events recorded on the stream the kernels are launched on; elapsed_ms waits
+ * for `stop` on the host.
+ */
+mesa_status mesa_stream_copy(const void *src, void *dst, size_t bytes, void *stream);
+mesa_status mesa_event_create(void **event);
+mesa_status mesa_event_record(void *event, void *stream);
+mesa_status mesa_event_elapsed_ms(void *start, void *stop, float *ms);
+mesa_status mesa_event_destroy(void *event);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MESA_H */

@@ -1,0 +1,13 @@
+"""libmesa: Mesa's activation-compression hot path (arXiv 2111.11124) as HIP kernels for MI355X.
+
+The product is the C-ABI shared library declared in include/mesa.h; this package is its thin
+Python binding (same names, argument marshalling only).
+"""
+from ._ffi import (  # noqa: F401
+    F16, F32, ROUND_NEAREST_EVEN, ROUND_STOCHASTIC,
+    OP_UPDATE_RUNNING_PARAMS, OP_LAYERNORM_BWD_Q, OP_LINEAR_DW_Q,
+    OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH,
+    EXPORTS, Event, Layout, MesaError, lib, status_string, version, workspace_bytes,
+    mesa_update_running_params, mesa_quantize_headwise, mesa_dequantize, mesa_softmax_bwd_q,
+    mesa_gelu_bwd_q, mesa_layernorm_bwd_q, mesa_linear_dw_q, mesa_stream_copy,
+)

@@ -1,0 +1,186 @@
+"""ctypes binding of libmesa.so: argument marshalling only.
+
+Every function below has the name and the argument order of the C entry point it calls
+(include/mesa.h); tensors are torch tensors on the GPU, whose data pointers and current stream are
+passed through.  No arithmetic of the method happens in Python, and there is no fallback: if the
+shared library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from pathlib import Path
+
+import torch  # noqa: F401  (first, so that libmesa binds to the HIP runtime torch has loaded)
+
+_LIB_PATH = Path(__file__).resolve().parent / "libmesa.so"
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = range(5)
+F32, F16 = 0, 1
+ROUND_NEAREST_EVEN, ROUND_STOCHASTIC = 0, 1
+OP_UPDATE_RUNNING_PARAMS, OP_LAYERNORM_BWD_Q, OP_LINEAR_DW_Q = 0, 1, 2
+
+EXPORTS = [
+    "mesa_update_running_params", "mesa_quantize_headwise", "mesa_dequantize", "mesa_softmax_bwd_q",
+    "mesa_gelu_bwd_q", "mesa_layernorm_bwd_q", "mesa_linear_dw_q", "mesa_workspace_bytes",
+    "mesa_status_string", "mesa_version", "mesa_stream_copy", "mesa_event_create", "mesa_event_record",
+    "mesa_event_elapsed_ms", "mesa_event_destroy",
+]
+
+
+class MesaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+class Layout(C.Structure):
+    _fields_ = [("outer", C.c_int64), ("groups", C.c_int64), ("inner", C.c_int64)]
+
+
+_lib = None
+_vp, _i64, _u64, _int, _f32, _sz = C.c_void_p, C.c_int64, C.c_uint64, C.c_int, C.c_float, C.c_size_t
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        if not _LIB_PATH.exists():
+            raise RuntimeError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                               "(there is no fallback path)")
+        L = C.CDLL(str(_LIB_PATH))
+        L.mesa_update_running_params.argtypes = [_vp, _int, Layout, _vp, _vp, _f32, _int, _vp, _sz, _vp]
+        L.mesa_quantize_headwise.argtypes = [_vp, _int, Layout, _vp, _vp, _vp, _int, _u64, _u64, _vp]
+        L.mesa_dequantize.argtypes = [_vp, Layout, _vp, _vp, _vp, _int, _vp]
+        L.mesa_softmax_bwd_q.argtypes = [_vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _int, _vp]
+        L.mesa_gelu_bwd_q.argtypes = [_vp, Layout, _vp, _vp, _vp, _vp, _int, _vp]
+        L.mesa_layernorm_bwd_q.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _int,
+                                           _vp, _sz, _vp]
+        L.mesa_linear_dw_q.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _i64, _int, _vp, _vp, _vp, _sz, _vp]
+        L.mesa_workspace_bytes.argtypes = [_int, _i64, _i64, _i64, _int]
+        L.mesa_workspace_bytes.restype = _sz
+        L.mesa_status_string.argtypes = [_int]
+        L.mesa_status_string.restype = C.c_char_p
+        L.mesa_version.restype = _int
+        L.mesa_stream_copy.argtypes = [_vp, _vp, _sz, _vp]
+        L.mesa_event_create.argtypes = [C.POINTER(_vp)]
+        L.mesa_event_record.argtypes = [_vp, _vp]
+        L.mesa_event_elapsed_ms.argtypes = [_vp, _vp, C.POINTER(_f32)]
+        L.mesa_event_destroy.argtypes = [_vp]
+        for name in EXPORTS:
+            fn = getattr(L, name)
+            if name not in ("mesa_workspace_bytes", "mesa_status_string", "mesa_version"):
+                fn.restype = _int
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().mesa_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(lib().mesa_version())
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.float16:
+        return F16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("libmesa takes device tensors only")
+    if not t.is_contiguous():
+        raise ValueError("libmesa takes contiguous tensors only")
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(status: int, where: str):
+    if status != OK:
+        raise MesaError(status, where)
+
+
+def workspace_bytes(op: int, d0: int, d1: int, d2: int, dtype: int = F16) -> int:
+    return int(lib().mesa_workspace_bytes(op, d0, d1, d2, dtype))
+
+
+def _ws_args(ws):
+    return (_ptr(ws), ws.numel() * ws.element_size()) if ws is not None else (None, 0)
+
+
+def mesa_update_running_params(x, layout, alpha, beta, lam, first_call, ws):
+    p, n = _ws_args(ws)
+    _check(lib().mesa_update_running_params(_ptr(x), _dt(x), Layout(*layout), _ptr(alpha), _ptr(beta), float(lam),
+                                            int(bool(first_call)), p, n, _stream()), "mesa_update_running_params")
+
+
+def mesa_quantize_headwise(x, layout, alpha, beta, q, mode=ROUND_STOCHASTIC, seed=0, offset=0):
+    _check(lib().mesa_quantize_headwise(_ptr(x), _dt(x), Layout(*layout), _ptr(alpha), _ptr(beta), _ptr(q), int(mode),
+                                        int(seed), int(offset), _stream()), "mesa_quantize_headwise")
+
+
+def mesa_dequantize(q, layout, alpha, beta, x_hat):
+    _check(lib().mesa_dequantize(_ptr(q), Layout(*layout), _ptr(alpha), _ptr(beta), _ptr(x_hat), _dt(x_hat), _stream()),
+           "mesa_dequantize")
+
+
+def mesa_softmax_bwd_q(yq, B, H, rows, cols, alpha, beta, dy, dx):
+    assert dx.dtype == dy.dtype
+    _check(lib().mesa_softmax_bwd_q(_ptr(yq), B, H, rows, cols, _ptr(alpha), _ptr(beta), _ptr(dy), _ptr(dx), _dt(dy),
+                                    _stream()), "mesa_softmax_bwd_q")
+
+
+def mesa_gelu_bwd_q(xq, layout, alpha, beta, dy, dx):
+    assert dx.dtype == dy.dtype
+    _check(lib().mesa_gelu_bwd_q(_ptr(xq), Layout(*layout), _ptr(alpha), _ptr(beta), _ptr(dy), _ptr(dx), _dt(dy), _stream()),
+           "mesa_gelu_bwd_q")
+
+
+def mesa_layernorm_bwd_q(xq, M, D, G, alpha, beta, mean, rstd, gamma, dy, dx, dgamma, dbeta, ws):
+    assert dx.dtype == dy.dtype == gamma.dtype
+    p, n = _ws_args(ws)
+    _check(lib().mesa_layernorm_bwd_q(_ptr(xq), M, D, G, _ptr(alpha), _ptr(beta), _ptr(mean), _ptr(rstd), _ptr(gamma),
+                                      _ptr(dy), _ptr(dx), _ptr(dgamma), _ptr(dbeta), _dt(dy), p, n, _stream()),
+           "mesa_layernorm_bwd_q")
+
+
+def mesa_linear_dw_q(xq, M, K, G, alpha, beta, dy, N_out, dW, db, ws):
+    p, n = _ws_args(ws)
+    _check(lib().mesa_linear_dw_q(_ptr(xq), M, K, G, _ptr(alpha), _ptr(beta), _ptr(dy), N_out, _dt(dy), _ptr(dW), _ptr(db),
+                                  p, n, _stream()), "mesa_linear_dw_q")
+
+
+def mesa_stream_copy(src, dst, nbytes):
+    _check(lib().mesa_stream_copy(_ptr(src), _ptr(dst), int(nbytes), _stream()), "mesa_stream_copy")
+
+
+class Event:
+    """A HIP event recorded on the stream the kernels are launched on."""
+
+    def __init__(self):
+        self._h = _vp()
+        _check(lib().mesa_event_create(C.byref(self._h)), "mesa_event_create")
+
+    def record(self):
+        _check(lib().mesa_event_record(self._h, _stream()), "mesa_event_record")
+
+    def elapsed_ms(self, stop: "Event") -> float:
+        ms = _f32()
+        _check(lib().mesa_event_elapsed_ms(self._h, stop._h, C.byref(ms)), "mesa_event_elapsed_ms")
+        return float(ms.value)
+
+    def __del__(self):
+        try:
+            if self._h:
+                lib().mesa_event_destroy(self._h)
+        except Exception:
+            pass

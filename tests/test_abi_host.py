@@ -1,0 +1,131 @@
+"""CPU-side checks of the product: the shared library loads and exports every symbol the header
+declares, argument errors are reported before anything is launched, and the host-side integer
+helpers (division by multiplication, launch planning) are exact."""
+import ctypes as C
+import os
+import re
+import subprocess
+import sys
+import tempfile
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "mesa.h")
+
+
+@pytest.fixture(scope="module")
+def M():
+    import paper_2111_11124_amd as m
+    if not os.path.exists(os.path.join(ROOT, "paper_2111_11124_amd", "libmesa.so")):
+        from paper_2111_11124_amd.build import build
+        build(verbose=False)
+    m.lib()
+    return m
+
+
+def declared_functions():
+    src = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(mesa_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol(M):
+    names = declared_functions()
+    assert len(names) >= 15 and {"mesa_quantize_headwise", "mesa_dequantize", "mesa_update_running_params",
+                                 "mesa_softmax_bwd_q", "mesa_gelu_bwd_q", "mesa_layernorm_bwd_q",
+                                 "mesa_linear_dw_q"} <= set(names)
+    L = M.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(M.EXPORTS) == names
+    assert M.version() >= 100 and M.status_string(M.ERR_WORKSPACE).startswith("workspace")
+
+
+def test_argument_errors_are_reported_before_any_launch(M):
+    L = M.lib()
+    lay = M.Layout(2, 3, 64)
+    P = 0x10000  # a 16-byte aligned fake address: never dereferenced on the host, and no call below passes the checks
+    assert L.mesa_quantize_headwise(None, M.F16, lay, P, P, P, 0, 0, 0, None) == M.ERR_INVALID_ARG
+    assert L.mesa_quantize_headwise(P + 2, M.F16, lay, P, P, P, 0, 0, 0, None) == M.ERR_INVALID_ARG       # misaligned
+    assert L.mesa_quantize_headwise(P, 7, lay, P, P, P, 0, 0, 0, None) == M.ERR_INVALID_ARG               # dtype
+    assert L.mesa_quantize_headwise(P, M.F16, lay, P, P, P, 5, 0, 0, None) == M.ERR_INVALID_ARG           # rounding mode
+    assert L.mesa_quantize_headwise(P, M.F16, M.Layout(-1, 3, 4), P, P, P, 0, 0, 0, None) == M.ERR_INVALID_ARG
+    assert L.mesa_quantize_headwise(P, M.F16, M.Layout(2, 9000, 4), P, P, P, 0, 0, 0, None) == M.ERR_UNSUPPORTED
+    assert L.mesa_quantize_headwise(P, M.F16, M.Layout(2, 2, 1 << 31), P, P, P, 0, 0, 0, None) == M.ERR_UNSUPPORTED
+    assert L.mesa_update_running_params(P, M.F16, lay, P, P, 1.5, 0, P, 1 << 20, None) == M.ERR_INVALID_ARG  # lambda
+    assert L.mesa_update_running_params(P, M.F16, lay, P, P, float("nan"), 0, P, 1 << 20, None) == M.ERR_INVALID_ARG
+    assert L.mesa_update_running_params(P, M.F16, lay, P, P, 0.9, 0, P, 8, None) == M.ERR_WORKSPACE
+    assert L.mesa_update_running_params(P, M.F16, lay, P, P, 0.9, 0, None, 0, None) == M.ERR_WORKSPACE
+    assert L.mesa_dequantize(P, lay, P, None, P, M.F16, None) == M.ERR_INVALID_ARG
+    assert L.mesa_gelu_bwd_q(P, lay, P, P, P + 8, P, M.F16, None) == M.ERR_INVALID_ARG
+    assert L.mesa_softmax_bwd_q(P, 2, 3, 5, 4, P, P, P, P, M.F16, None) == M.ERR_UNSUPPORTED              # cols < 8
+    assert L.mesa_softmax_bwd_q(P, 2, 3, 5, 3001, P, P, P, P, M.F16, None) == M.ERR_UNSUPPORTED           # 8 odd rows exceed a tile
+    assert L.mesa_softmax_bwd_q(P, -2, 3, 5, 16, P, P, P, P, M.F16, None) == M.ERR_INVALID_ARG
+    assert L.mesa_layernorm_bwd_q(P, 10, 100, 5, P, P, P, P, P, P, P, P, P, M.F16, P, 1 << 20, None) == M.ERR_UNSUPPORTED
+    assert L.mesa_layernorm_bwd_q(P, 10, 96, 5, P, P, P, P, P, P, P, P, P, M.F16, P, 1 << 20, None) == M.ERR_INVALID_ARG
+    assert L.mesa_layernorm_bwd_q(P, 10, 96, 3, P, P, P, P, P, P, P, P, P, M.F16, P, 16, None) == M.ERR_WORKSPACE
+    assert L.mesa_linear_dw_q(P, 100, 40, 1, P, P, P, 64, M.F16, P, None, P, 1 << 30, None) == M.ERR_UNSUPPORTED   # K % 16
+    assert L.mesa_linear_dw_q(P, 100, 48, 5, P, P, P, 64, M.F16, P, None, P, 1 << 30, None) == M.ERR_INVALID_ARG   # K % G
+    assert L.mesa_linear_dw_q(P, 100, 48, 3, P, P, P, 64, M.F16, P, None, P, 64, None) == M.ERR_WORKSPACE
+    assert L.mesa_stream_copy(P, P, 24, None) == M.ERR_INVALID_ARG
+    # zero elements: OK without touching anything
+    assert L.mesa_quantize_headwise(None, M.F16, M.Layout(0, 3, 64), None, None, None, 0, 0, 0, None) == M.OK
+    assert L.mesa_softmax_bwd_q(None, 0, 3, 5, 16, None, None, None, None, M.F16, None) == M.OK
+
+
+def test_workspace_sizes(M):
+    assert M.workspace_bytes(M.OP_UPDATE_RUNNING_PARAMS, 128, 6, 38809) >= 2 * 6 * 4
+    assert M.workspace_bytes(M.OP_LAYERNORM_BWD_Q, 25216, 384, 6) >= 2 * 384 * 4
+    n = M.workspace_bytes(M.OP_LINEAR_DW_Q, 25216, 384, 1536, M.F16)
+    assert n >= (384 * 1536 + 1536) * 4 and n < (1 << 31)
+    assert M.workspace_bytes(99, 1, 1, 1) == 0
+
+
+HOST_TEST = r'''
+#include <cstdio>
+#include <cstdlib>
+#include "host_math.hpp"
+using namespace mesa;
+int main() {
+    // division by multiplication is exact for every dividend below 2^31 that matters: all small
+    // dividends, and dividends around every multiple boundary and at the top of the range
+    const uint32_t ds[] = {1, 2, 3, 5, 7, 8, 12, 16, 24, 32, 48, 49, 64, 96, 128, 197, 256, 384, 2401, 4096, 38809,
+                           65535, 65536, 1000003, 16777216, 2147483647u};
+    for (uint32_t d : ds) {
+        FastDiv f = make_fastdiv(d);
+        for (uint32_t n = 0; n < 200000; ++n) if (fastdiv_host(n, f) != n / d) { printf("FAIL d=%u n=%u\n", d, n); return 1; }
+        for (uint64_t q = 1; q * d < 2147483648ull; q += (2147483648ull / d) / 997 + 1)
+            for (int64_t o = -2; o <= 2; ++o) {
+                int64_t n = int64_t(q * d) + o;
+                if (n < 0 || n >= 2147483648ll) continue;
+                if (fastdiv_host(uint32_t(n), f) != uint32_t(n) / d) { printf("FAIL d=%u n=%lld\n", d, (long long)n); return 1; }
+            }
+        if (fastdiv_host(2147483647u, f) != 2147483647u / d) { printf("FAIL top d=%u\n", d); return 1; }
+    }
+    // cursor constants: stepping by `step` elements moves (rem, g) as plain division says
+    const int64_t cases[][3] = {{6, 38809, 2048 * 8 * 4}, {6, 64, 1365 * 8192}, {3, 2401, 777 * 8192}, {1, 12345, 8192}, {5, 3, 8192}};
+    for (auto &c : cases) {
+        GroupGeom g = make_geom(c[0], c[1], c[2]);
+        for (int64_t e = 0; e < 100000; e += 8) {
+            uint32_t rem = uint32_t(e % g.inner), grp = uint32_t((e / g.inner) % g.groups);
+            uint32_t r = rem + g.step_rem; uint32_t carry = r >= g.inner; r -= carry ? g.inner : 0;
+            uint32_t gg = grp + g.step_g + carry; if (gg >= g.groups) gg -= g.groups;
+            int64_t e2 = e + c[2];
+            if (r != uint32_t(e2 % g.inner) || gg != uint32_t((e2 / g.inner) % g.groups)) { printf("FAIL cursor\n"); return 1; }
+        }
+    }
+    printf("OK\n");
+    return 0;
+}
+'''
+
+
+def test_host_integer_helpers_are_exact():
+    with tempfile.TemporaryDirectory() as d:
+        src = os.path.join(d, "t.cpp")
+        open(src, "w").write(HOST_TEST)
+        exe = os.path.join(d, "t")
+        subprocess.run(["g++", "-O2", "-std=c++17", "-I", os.path.join(ROOT, "paper_2111_11124_amd", "csrc"), src, "-o", exe],
+                       check=True)
+        out = subprocess.run([exe], capture_output=True, text=True)
+        assert out.returncode == 0 and out.stdout.strip() == "OK", out.stdout

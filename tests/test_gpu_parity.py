@@ -1,0 +1,275 @@
+"""GPU parity: libmesa (through its C ABI) against the CPU oracle on the same seeded inputs.
+
+Codes, running parameters and mesa_dequantize output must match bit for bit; gradients within
+max|gpu - ref| / max|ref| <= 1e-5 (binary32 storage) or 2e-3 (binary16 storage).
+"""
+import numpy as np
+import pytest
+import torch
+
+import mesa_workloads as W
+from oracle import mesa_ref as R
+
+pytestmark = pytest.mark.gpu
+
+TOL = {torch.float32: 1e-5, torch.float16: 2e-3}
+
+
+@pytest.fixture(scope="module")
+def M():
+    import paper_2111_11124_amd as m
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    m.lib()
+    return m
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def canon(a):
+    """-0.0 -> +0.0 (the library returns a minimum of -0.0 as +0.0)."""
+    return (np.asarray(a, np.float32) + np.float32(0.0)).view(np.uint32)
+
+
+def relerr(got, ref):
+    got = np.asarray(got, np.float64)
+    return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+
+def ws_for(m, op, d0, d1, d2, dt=None):
+    n = m.workspace_bytes(op, d0, d1, d2, m.F16 if dt in (None, torch.float16) else m.F32)
+    return torch.empty(max(n, 16), dtype=torch.uint8, device="cuda")
+
+
+def run_params(m, xs, layout, lam=0.9):
+    """first_call update on xs[0], EMA updates on the rest; returns (gpu alpha, beta) and the oracle's."""
+    G = layout[1]
+    a = torch.full((G,), 123.0, device="cuda")
+    b = torch.full((G,), -77.0, device="cuda")
+    ra, rb = np.full(G, 123.0, np.float32), np.full(G, -77.0, np.float32)
+    ws = ws_for(m, m.OP_UPDATE_RUNNING_PARAMS, *layout)
+    for i, x in enumerate(xs):
+        m.mesa_update_running_params(x, layout, a, b, lam, i == 0, ws)
+        ra, rb = R.update_running_params(x.cpu().numpy(), layout, ra, rb, lam, i == 0)
+    torch.cuda.synchronize()
+    return a, b, ra, rb
+
+
+LAYOUTS = [
+    (3, 4, 1000),      # slabs of whole vectors
+    (5, 3, 361),       # odd slabs: vectors straddle heads (19 x 19 attention)
+    (37, 6, 64),       # channel groups of a (37, 384) token matrix
+    (50, 3, 32),
+    (1, 1, 12345),     # one group, ragged tail
+    (7, 5, 3),         # slabs shorter than a vector
+    (2, 2, 70001),
+    (3000, 12, 256),   # several grid steps
+]
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.float16])
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_params_codes_and_dequantize_are_bit_exact(M, layout, dtype):
+    outer, G, inner = layout
+    n = outer * G * inner
+    g = torch.Generator(device="cuda").manual_seed(n)
+    scale = torch.tensor([0.3, 1.0, 4.0, 11.0, 0.05, 2.0, 7.0, 1.5, 0.8, 3.0, 0.1, 6.0], device="cuda")[:G].view(1, G, 1)
+    xs = [(torch.randn((outer, G, inner), generator=g, device="cuda") * scale + 0.25 * i).to(dtype).contiguous()
+          for i in range(3)]
+    a, b, ra, rb = run_params(M, xs, layout)
+    assert np.array_equal(canon(a.cpu().numpy()), canon(ra)), (a.cpu().numpy(), ra)
+    assert np.array_equal(canon(b.cpu().numpy()), canon(rb)), (b.cpu().numpy(), rb)
+
+    x = xs[-1]
+    xh = x.cpu().numpy()
+    an, bn = a.cpu().numpy(), b.cpu().numpy()
+    for mode, seed, off in ((M.ROUND_NEAREST_EVEN, 0, 0), (M.ROUND_STOCHASTIC, 0xDEADBEEF12345, (1 << 33) + 17)):
+        q = torch.empty(n, dtype=torch.int8, device="cuda")
+        M.mesa_quantize_headwise(x, layout, a, b, q, mode, seed, off)
+        rq = R.quantize_headwise(xh, layout, an, bn, mode, seed, off).reshape(-1)
+        got = q.cpu().numpy()
+        bad = np.nonzero(got != rq)[0]
+        assert bad.size == 0, (mode, bad[:10], got[bad[:10]], rq[bad[:10]])
+    for odt in (torch.float32, torch.float16):
+        out = torch.empty(n, dtype=odt, device="cuda")
+        M.mesa_dequantize(q, layout, a, b, out)
+        ref = R.dequantize(rq, layout, an, bn, np.float32 if odt == torch.float32 else np.float16)
+        u = np.uint32 if odt == torch.float32 else np.uint16
+        assert np.array_equal(out.cpu().numpy().view(u), ref.view(u))
+
+
+def block_parity(m, spec, modes=("nearest", "stochastic")):
+    """The whole path on one block's saved-activation set, every output against the oracle."""
+    dt = spec.dtype
+    tol = TOL[dt]
+    npdt = np.float32 if dt == torch.float32 else np.float16
+    H = spec.heads
+    report = {}
+
+    def params_and_codes(draws, layout, mode, seed, off):
+        a, b, ra, rb = run_params(m, draws, layout, spec.lam)
+        assert np.array_equal(canon(a.cpu().numpy()), canon(ra)) and np.array_equal(canon(b.cpu().numpy()), canon(rb))
+        x = draws[-1]
+        q = torch.empty(x.numel(), dtype=torch.int8, device="cuda")
+        m.mesa_quantize_headwise(x, layout, a, b, q, mode, seed, off)
+        rq = R.quantize_headwise(x.cpu().numpy(), layout, ra, rb, mode, seed, off).reshape(-1)
+        assert np.array_equal(q.cpu().numpy(), rq)
+        return a, b, ra, rb, q, rq
+
+    for mi, mode_name in enumerate(modes):
+        mode = m.ROUND_NEAREST_EVEN if mode_name == "nearest" else m.ROUND_STOCHASTIC
+        seed = 1000 + spec.seed
+        # --- attention map -> softmax backward
+        B, Hh, rows, cols = spec.attn
+        draws = [W.attention_map(spec, d, "cuda") for d in range(3)]
+        a, b, ra, rb, q, rq = params_and_codes(draws, spec.attn_layout, mode, seed, 0)
+        assert (b.cpu().numpy() >= 0).all()
+        del draws
+        dy = W.upstream_grad(spec, "dy_attn", spec.attn, "cuda")
+        dx = torch.empty_like(dy)
+        m.mesa_softmax_bwd_q(q, B, Hh, rows, cols, a, b, dy, dx)
+        ref = R.softmax_bwd_q(rq, B, Hh, rows, cols, ra, rb, dy.cpu().numpy())
+        report[f"softmax_{mode_name}"] = relerr(dx.cpu().numpy().reshape(ref.shape), ref)
+        del dy, dx, ref
+        # --- GELU input -> GELU backward
+        lay = spec.gelu_layout
+        draws = [W.gelu_input(spec, d, "cuda") for d in range(3)]
+        a, b, ra, rb, q, rq = params_and_codes(draws, lay, mode, seed, 1 << 40)
+        del draws
+        dy = W.upstream_grad(spec, "dy_gelu", (spec.tokens, spec.mlp), "cuda")
+        dx = torch.empty_like(dy)
+        m.mesa_gelu_bwd_q(q, lay, a, b, dy, dx)
+        ref = R.gelu_bwd_q(rq, lay, ra, rb, dy.cpu().numpy())
+        report[f"gelu_{mode_name}"] = relerr(dx.cpu().numpy().reshape(ref.shape), ref)
+        del dy, dx, ref
+        # --- LayerNorm input -> LayerNorm backward
+        lay = spec.ln_layout
+        Mr, D = spec.tokens, spec.dim
+        draws = [W.token_matrix(spec, "ln", d, "cuda") for d in range(3)]
+        a, b, ra, rb, q, rq = params_and_codes(draws, lay, mode, seed, 2 << 40)
+        mean, rstd = W.layernorm_stats(draws[-1])
+        del draws
+        gamma = W.layernorm_gamma(spec, "cuda")
+        dy = W.upstream_grad(spec, "dy_ln", (Mr, D), "cuda")
+        dx = torch.empty_like(dy)
+        dg = torch.empty(D, device="cuda")
+        db = torch.empty(D, device="cuda")
+        ws = ws_for(m, m.OP_LAYERNORM_BWD_Q, Mr, D, H)
+        m.mesa_layernorm_bwd_q(q, Mr, D, H, a, b, mean, rstd, gamma, dy, dx, dg, db, ws)
+        rdx, rdg, rdb = R.layernorm_bwd_q(rq, Mr, D, H, ra, rb, mean.cpu().numpy(), rstd.cpu().numpy(),
+                                          gamma.cpu().numpy(), dy.cpu().numpy())
+        report[f"ln_dx_{mode_name}"] = relerr(dx.cpu().numpy(), rdx)
+        report[f"ln_dgamma_{mode_name}"] = relerr(dg.cpu().numpy(), rdg)
+        report[f"ln_dbeta_{mode_name}"] = relerr(db.cpu().numpy(), rdb)
+        del dy, dx
+        # --- Linear inputs -> dW (entries sampled when the full matrix is out of the oracle's reach)
+        for li, (K, N) in enumerate(spec.linears):
+            lay = (Mr, H, K // H)
+            draws = [W.token_matrix(spec, "lin", 10 * li + d, "cuda", width=K) for d in range(3)]
+            a, b, ra, rb, q, rq = params_and_codes(draws, lay, mode, seed, (3 + li) << 40)
+            del draws
+            dy = W.upstream_grad(spec, "dy_lin", (Mr, N), "cuda")
+            dW = torch.empty((N, K), device="cuda")
+            dbias = torch.empty(N, device="cuda")
+            ws = ws_for(m, m.OP_LINEAR_DW_Q, Mr, K, N, dt)
+            m.mesa_linear_dw_q(q, Mr, K, H, a, b, dy, N, dW, dbias, ws)
+            dyh = dy.cpu().numpy()
+            got = dW.cpu().numpy().astype(np.float64)
+            if Mr * K * N <= 4e9:
+                rW, rb_ = R.linear_dw_q(rq, Mr, K, H, ra, rb, dyh, N)
+                report[f"dw{li}_{mode_name}"] = relerr(got, rW)
+            else:
+                rng = np.random.default_rng(li)
+                n_idx = np.concatenate([np.repeat(rng.integers(0, N, 4), K), rng.integers(0, N, 4096)])
+                k_idx = np.concatenate([np.tile(np.arange(K), 4), rng.integers(0, K, 4096)])
+                ent = R.linear_dw_q_entries(rq, Mr, K, H, ra, rb, dyh, N, n_idx, k_idx)
+                scale = max(np.abs(ent).max(), 1e-30)
+                report[f"dw{li}_{mode_name}"] = float(np.abs(got[n_idx, k_idx] - ent).max() / scale)
+                rb_ = dyh.astype(np.float64).sum(0)
+            report[f"db{li}_{mode_name}"] = relerr(dbias.cpu().numpy(), rb_)
+            del dy, dW
+        if mi == 0:
+            # mesa_dequantize on the last codes, both output types, bit for bit
+            for odt, npo, u in ((torch.float32, np.float32, np.uint32), (torch.float16, np.float16, np.uint16)):
+                out = torch.empty(q.numel(), dtype=odt, device="cuda")
+                m.mesa_dequantize(q, lay, a, b, out)
+                assert np.array_equal(out.cpu().numpy().view(u), R.dequantize(rq, lay, ra, rb, npo).view(u))
+    bad = {k: v for k, v in report.items() if not v <= tol}
+    assert not bad, (bad, report)
+    return report
+
+
+def test_config1_deit_ti_block_fp32(M):
+    print(block_parity(M, W.CONFIGS[1]))
+
+
+def test_tiny_ragged_block_both_dtypes(M):
+    for dt in (torch.float32, torch.float16):
+        print(block_parity(M, W.small_case(dt, B=3, H=3, N=19, D=48, mlp=96)))
+
+
+def test_config2_deit_s_shape_batch8(M):
+    print(block_parity(M, W.scaled(W.CONFIGS[2], 16)))
+
+
+def test_config3_swin_t_shape_reduced(M):
+    print(block_parity(M, W.scaled(W.CONFIGS[3], 64), modes=("stochastic",)))
+
+
+def test_config4_deit_b_shape_batch4(M):
+    print(block_parity(M, W.scaled(W.CONFIGS[4], 64), modes=("stochastic",)))
+
+
+def test_config5_long_sequence_shape_reduced(M):
+    spec = W.scaled(W.CONFIGS[5], 8)       # one sample: attention map (1, 16, 4096, 4096)
+    from dataclasses import replace
+    spec = replace(spec, attn=(1, 16, 512, 4096))   # 512 of the 4096 query rows per head
+    print(block_parity(M, spec, modes=("stochastic",)))
+
+
+def test_empty_inputs_are_a_no_op(M):
+    z = torch.empty(0, device="cuda")
+    a = torch.ones(3, device="cuda")
+    b = torch.zeros(3, device="cuda")
+    q = torch.empty(0, dtype=torch.int8, device="cuda")
+    ws = torch.empty(16, dtype=torch.uint8, device="cuda")
+    M.mesa_update_running_params(z, (0, 3, 5), a, b, 0.9, True, ws)
+    M.mesa_quantize_headwise(z, (0, 3, 5), a, b, q)
+    M.mesa_dequantize(q, (0, 3, 5), a, b, z)
+    M.mesa_gelu_bwd_q(q, (0, 3, 5), a, b, z, z)
+    M.mesa_softmax_bwd_q(q, 0, 3, 4, 8, a, b, z, z)
+    torch.cuda.synchronize()
+    assert a.cpu().tolist() == [1, 1, 1]
+
+
+def test_in_place_gradients_and_determinism(M):
+    spec = W.small_case(torch.float16, B=4, H=3, N=49, D=96, mlp=384)
+    lay = spec.gelu_layout
+    x = W.gelu_input(spec, 0, "cuda")
+    a = torch.zeros(3, device="cuda"); b = torch.zeros(3, device="cuda")
+    ws = ws_for(M, M.OP_UPDATE_RUNNING_PARAMS, *lay)
+    M.mesa_update_running_params(x, lay, a, b, 0.9, True, ws)
+    q = torch.empty(x.numel(), dtype=torch.int8, device="cuda")
+    M.mesa_quantize_headwise(x, lay, a, b, q, M.ROUND_STOCHASTIC, 7, 0)
+    q2 = torch.empty_like(q)
+    M.mesa_quantize_headwise(x, lay, a, b, q2, M.ROUND_STOCHASTIC, 7, 0)
+    assert torch.equal(q, q2)
+    dy = W.upstream_grad(spec, "dy_gelu", x.shape, "cuda")
+    dx = torch.empty_like(dy)
+    M.mesa_gelu_bwd_q(q, lay, a, b, dy, dx)
+    dy2 = dy.clone()
+    M.mesa_gelu_bwd_q(q, lay, a, b, dy2, dy2)
+    assert torch.equal(dx, dy2)
+    # softmax in place
+    Bq, Hq, r, c = spec.attn
+    y = W.attention_map(spec, 0, "cuda")
+    M.mesa_update_running_params(y, spec.attn_layout, a, b, 0.9, True, ws_for(M, M.OP_UPDATE_RUNNING_PARAMS, *spec.attn_layout))
+    qa = torch.empty(y.numel(), dtype=torch.int8, device="cuda")
+    M.mesa_quantize_headwise(y, spec.attn_layout, a, b, qa, M.ROUND_NEAREST_EVEN)
+    dya = W.upstream_grad(spec, "dy_attn", y.shape, "cuda")
+    dxa = torch.empty_like(dya)
+    M.mesa_softmax_bwd_q(qa, Bq, Hq, r, c, a, b, dya, dxa)
+    dyb = dya.clone()
+    M.mesa_softmax_bwd_q(qa, Bq, Hq, r, c, a, b, dyb, dyb)
+    assert torch.equal(dxa, dyb)
