@@ -27,7 +27,7 @@
  *               nothing is written.  Zero elements is MESA_OK and a no-op.
  *   Threads     No global mutable state; calls on distinct streams may run concurrently provided
  *               they use distinct ws and outputs.
- *   Limits      groups <= 8192; for groups > 1, inner < 2^31.  Outside them: MESA_ERR_UNSUPPORTED.
+ *   Limits      groups <= 8192; for groups > 1, inner < 2^30.  Outside them: MESA_ERR_UNSUPPORTED.
  */
 #ifndef MESA_H
 #define MESA_H
@@ -109,7 +109,8 @@ mesa_status mesa_dequantize(const int8_t *q, mesa_layout L, const float *alpha, 
  * head-wise parameters alpha[H], beta[H].  Per row:  d = sum_j dy_j*y_hat_j,
  * dx_j = y_hat_j * (dy_j - d), accumulated in binary32.
  * yq: int8 (in); dy, dx: [B*H*rows*cols] of dt (in / out); dx may alias dy.
- * Limits: 8 <= cols <= 16384 and B*H*rows < 2^31, else MESA_ERR_UNSUPPORTED.
+ * Limits: cols >= 8, R*cols <= 8192 for R = 8/gcd(cols, 8) (so cols <= 8192 when cols % 8 == 0, cols <= 1024
+ * when cols is odd), and B*H*rows < 2^31; else MESA_ERR_UNSUPPORTED.
  */
 mesa_status mesa_softmax_bwd_q(const int8_t *yq, int64_t B, int64_t H, int64_t rows, int64_t cols,
                                const float *alpha, const float *beta, const void *dy, void *dx,
@@ -131,7 +132,7 @@ mesa_status mesa_gelu_bwd_q(const int8_t *xq, mesa_layout L, const float *alpha,
  *   dgamma_j = sum_rows dy*xn,  dbeta_j = sum_rows dy        (binary32, fixed summation order)
  * gamma: [D] of dt.  dx: (M, D) of dt, may alias dy.  dgamma, dbeta: [D] binary32 (overwritten).
  * ws: MESA_OP_LAYERNORM_BWD_Q bytes.
- * Limits: D % 8 == 0, (D/G) % 8 == 0, D <= 8192, else MESA_ERR_UNSUPPORTED.
+ * Limits: D % 8 == 0, (D/G) % 8 == 0, D <= 4096, else MESA_ERR_UNSUPPORTED.
  */
 mesa_status mesa_layernorm_bwd_q(const int8_t *xq, int64_t M, int64_t D, int64_t G,
                                  const float *alpha, const float *beta,

@@ -23,7 +23,7 @@ inline mesa_status check_layout(const mesa_layout &L)
 {
     if (L.outer < 0 || L.groups < 0 || L.inner < 0) return MESA_ERR_INVALID_ARG;
     if (L.groups > 8192) return MESA_ERR_UNSUPPORTED;
-    if (L.groups > 1 && L.inner >= (int64_t(1) << 31)) return MESA_ERR_UNSUPPORTED;
+    if (L.groups > 1 && L.inner >= (int64_t(1) << 30)) return MESA_ERR_UNSUPPORTED;
     // numel must stay below 2^53 (indices pass through binary64 once) -- far beyond any HBM
     if (L.outer > 0 && L.groups > 0 && L.inner > 0) {
         long double n = (long double)L.outer * (long double)L.groups * (long double)L.inner;

@@ -56,6 +56,18 @@ __device__ __forceinline__ void cursor_advance(Cursor &c, const GroupGeom &gg)
     c.g = (g >= gg.groups) ? g - gg.groups : g;
 }
 
+// the cursor `delta` elements further on (delta < 2^16; inner < 2^30 keeps the dividend below 2^31)
+__device__ __forceinline__ Cursor cursor_offset(const Cursor &c, uint32_t delta, const GroupGeom &gg)
+{
+    uint32_t r = c.rem + delta;
+    uint32_t adv = fastdiv(r, gg.div_inner);
+    Cursor o;
+    o.rem = r - adv * gg.inner;
+    uint32_t t = c.g + adv;
+    o.g = t - fastdiv(t, gg.div_groups) * gg.groups;
+    return o;
+}
+
 // group of element j (0..7) of a vector that starts at cursor c and may cross slab ends
 __device__ __forceinline__ uint32_t group_of(const Cursor &c, uint32_t j, const GroupGeom &gg)
 {
@@ -160,6 +172,38 @@ template <> struct Store<float> {
     __device__ static __forceinline__ void store1(void *base, int64_t e, float f)
     {
         static_cast<float *>(base)[e] = f;
+    }
+};
+
+// ---------------------------------------------------------------------------------------------
+// streaming accesses: every byte is touched once, so mark them non-temporal
+// ---------------------------------------------------------------------------------------------
+template <typename V> __device__ __forceinline__ V nt_load(const void *p)
+{
+    return __builtin_nontemporal_load(static_cast<const V *>(p));
+}
+template <typename V> __device__ __forceinline__ void nt_store(void *p, V v)
+{
+    __builtin_nontemporal_store(v, static_cast<V *>(p));
+}
+
+template <typename T> struct Nt;
+template <> struct Nt<_Float16> {
+    __device__ static __forceinline__ u32x4 load(const void *b, int64_t e) { return nt_load<u32x4>(static_cast<const char *>(b) + e * 2); }
+    __device__ static __forceinline__ void store(void *b, int64_t e, u32x4 v) { nt_store<u32x4>(static_cast<char *>(b) + e * 2, v); }
+};
+template <> struct Nt<float> {
+    __device__ static __forceinline__ Store<float>::raw_t load(const void *b, int64_t e)
+    {
+        Store<float>::raw_t r;
+        r.lo = nt_load<u32x4>(static_cast<const char *>(b) + e * 4);
+        r.hi = nt_load<u32x4>(static_cast<const char *>(b) + e * 4 + 16);
+        return r;
+    }
+    __device__ static __forceinline__ void store(void *b, int64_t e, Store<float>::raw_t v)
+    {
+        nt_store<u32x4>(static_cast<char *>(b) + e * 4, v.lo);
+        nt_store<u32x4>(static_cast<char *>(b) + e * 4 + 16, v.hi);
     }
 };
 

@@ -40,6 +40,8 @@ struct GroupGeom {
     uint32_t groups;
     uint32_t step_rem;  // step % inner
     uint32_t step_g;    // (step / inner) % groups
+    FastDiv div_inner;  // for the one-off placement of a thread's further vectors
+    FastDiv div_groups;
 };
 
 inline GroupGeom make_geom(int64_t groups, int64_t inner, int64_t step)
@@ -54,6 +56,8 @@ inline GroupGeom make_geom(int64_t groups, int64_t inner, int64_t step)
     }
     g.step_rem = uint32_t(step % int64_t(g.inner));
     g.step_g = uint32_t((step / int64_t(g.inner)) % int64_t(g.groups));
+    g.div_inner = make_fastdiv(g.inner);
+    g.div_groups = make_fastdiv(g.groups);
     return g;
 }
 

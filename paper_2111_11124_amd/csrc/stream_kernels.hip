@@ -23,8 +23,27 @@
 
 namespace mesa {
 
-constexpr int kU = 4;            // vectors in flight per thread and iteration
-constexpr int kGridCap = 2048;   // 8 workgroups of 4 waves on each of the 256 CUs
+constexpr int kU = 4;                            // vectors per thread and iteration
+constexpr int kChunk = kThreads * kU * kVec;     // 8192 elements: what a workgroup moves per iteration
+constexpr int kGridCap = 2048;                   // 8 workgroups of 4 waves on each of the 256 CUs
+constexpr int kLutMaxGroups = 64;                // GELU-gradient table: groups * 256 floats in LDS
+
+// The cursors of a thread's U vectors: vector u of the chunk that starts at `base` covers
+// elements base + (u*256 + tid)*8 ... + 7.
+template <int U> __device__ __forceinline__ void place_cursors(Cursor c[U], const GroupGeom &gg, int64_t numel)
+{
+    const int64_t e0 = int64_t(blockIdx.x) * kChunk + int64_t(threadIdx.x) * kVec;
+    if (numel < (int64_t(1) << 31)) {   // uniform branch: two multiplies instead of binary64 divisions
+        Cursor z;
+        z.rem = 0u;
+        z.g = 0u;
+        c[0] = (e0 < numel) ? cursor_offset(z, uint32_t(e0), gg) : z;
+    } else {
+        c[0] = cursor_init(e0, gg);
+    }
+#pragma unroll
+    for (int u = 1; u < U; ++u) c[u] = cursor_offset(c[0], uint32_t(u * kThreads * kVec), gg);
+}
 
 // ---------------------------------------------------------------------------------------------
 // per-group parameter table in LDS: (scale, beta) per group
@@ -54,6 +73,12 @@ __device__ __forceinline__ int order_key(float f)  // monotone map binary32 -> i
 }
 __device__ __forceinline__ float order_val(int k) { return __int_as_float(k >= 0 ? k : k ^ 0x7FFFFFFF); }
 
+// plain selection instructions: the data holds no NaN by contract, so no canonicalisation is wanted
+__device__ __forceinline__ float vmin(float a, float b) { float r; asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b)); return r; }
+__device__ __forceinline__ float vmax(float a, float b) { float r; asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b)); return r; }
+__device__ __forceinline__ uint32_t pkmin(uint32_t a, uint32_t b) { uint32_t r; asm("v_pk_min_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b)); return r; }
+__device__ __forceinline__ uint32_t pkmax(uint32_t a, uint32_t b) { uint32_t r; asm("v_pk_max_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b)); return r; }
+
 template <typename T> struct MinMax;
 
 template <> struct MinMax<float> {
@@ -64,39 +89,36 @@ template <> struct MinMax<float> {
         float f[8];
         Store<float>::unpack(v, f);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) { mn = fminf(mn, f[j]); mx = fmaxf(mx, f[j]); }
+        for (int j = 0; j < 8; ++j) { mn = vmin(mn, f[j]); mx = vmax(mx, f[j]); }
     }
-    __device__ __forceinline__ void add1(float f) { mn = fminf(mn, f); mx = fmaxf(mx, f); }
+    __device__ __forceinline__ void add1(float f) { mn = vmin(mn, f); mx = vmax(mx, f); }
     __device__ __forceinline__ float lo() const { return mn; }
     __device__ __forceinline__ float hi() const { return mx; }
 };
 
 // binary16 data: selection is exact in any precision, so compare packed pairs directly
 template <> struct MinMax<_Float16> {
-    h2 mn, mx;
+    uint32_t mn, mx;
     __device__ __forceinline__ void init()
     {
-        mn = as_h2(0x7C007C00u);  // +inf, +inf
-        mx = as_h2(0xFC00FC00u);  // -inf, -inf
+        mn = 0x7C007C00u;  // +inf, +inf
+        mx = 0xFC00FC00u;  // -inf, -inf
     }
     __device__ __forceinline__ void add(const Store<_Float16>::raw_t &v)
     {
-        h2 a = as_h2(v[0]), b = as_h2(v[1]), c = as_h2(v[2]), d = as_h2(v[3]);
-        mn = __builtin_elementwise_min(mn, __builtin_elementwise_min(__builtin_elementwise_min(a, b),
-                                                                     __builtin_elementwise_min(c, d)));
-        mx = __builtin_elementwise_max(mx, __builtin_elementwise_max(__builtin_elementwise_max(a, b),
-                                                                     __builtin_elementwise_max(c, d)));
+        mn = pkmin(mn, pkmin(pkmin(v[0], v[1]), pkmin(v[2], v[3])));
+        mx = pkmax(mx, pkmax(pkmax(v[0], v[1]), pkmax(v[2], v[3])));
     }
     __device__ __forceinline__ void add1(float f)
     {
         h2 p;
         p.x = _Float16(f);
         p.y = p.x;
-        mn = __builtin_elementwise_min(mn, p);
-        mx = __builtin_elementwise_max(mx, p);
+        mn = pkmin(mn, as_u32(p));
+        mx = pkmax(mx, as_u32(p));
     }
-    __device__ __forceinline__ float lo() const { return fminf(float(mn.x), float(mn.y)); }
-    __device__ __forceinline__ float hi() const { return fmaxf(float(mx.x), float(mx.y)); }
+    __device__ __forceinline__ float lo() const { h2 p = as_h2(mn); return vmin(float(p.x), float(p.y)); }
+    __device__ __forceinline__ float hi() const { h2 p = as_h2(mx); return vmax(float(p.x), float(p.y)); }
 };
 
 __device__ __forceinline__ void flush_lane(int *lmn, int *lmx, uint32_t g, float lo, float hi)
@@ -105,6 +127,30 @@ __device__ __forceinline__ void flush_lane(int *lmn, int *lmx, uint32_t g, float
         atomicMin(&lmn[g], order_key(lo));
         atomicMax(&lmx[g], order_key(hi));
     }
+}
+
+// Cold path, kept out of line so that the streaming loop stays small: the elements of one vector
+// taken one by one -- used when the vector crosses a slab end, when its group differs from the one
+// being accumulated, and for the ragged tail.  Returns the accumulator by value (registers).
+template <typename T> struct MinMaxState {
+    MinMax<T> acc;
+    uint32_t cur;
+};
+
+template <typename T>
+__device__ __attribute__((noinline)) MinMaxState<T> minmax_elements(const void *x, int64_t e, int n, Cursor c, GroupGeom gg,
+                                                                   MinMaxState<T> st, int *lmn, int *lmx)
+{
+    for (int j = 0; j < n; ++j) {
+        uint32_t g = group_of(c, j, gg);
+        if (g != st.cur) {
+            flush_lane(lmn, lmx, st.cur, st.acc.lo(), st.acc.hi());
+            st.cur = g;
+            st.acc.init();
+        }
+        st.acc.add1(Store<T>::load1(x, e + j));
+    }
+    return st;
 }
 
 // partial extrema of each workgroup: part[wg][0..G) = min, part[wg][G..2G) = max
@@ -121,66 +167,66 @@ __global__ __launch_bounds__(kThreads) void k_minmax_partial(const void *__restr
     }
     __syncthreads();
 
-    const int64_t span = int64_t(gridDim.x) * kThreads * kVec;
-    const int64_t step = span * U;
-    int64_t e[U];
     Cursor c[U];
-    MinMax<T> acc[U];
-    uint32_t cur[U];
+    place_cursors<U>(c, gg, numel);
+    MinMaxState<T> st[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        e[u] = u * span + (int64_t(blockIdx.x) * kThreads + threadIdx.x) * kVec;
-        c[u] = cursor_init(e[u], gg);
-        cur[u] = c[u].g;
-        acc[u].init();
-    }
+    for (int u = 0; u < U; ++u) { st[u].cur = c[u].g; st[u].acc.init(); }
 
-    while (e[0] < numel) {
+    const int64_t stride = int64_t(gridDim.x) * kChunk;
+    const int64_t toff = int64_t(threadIdx.x) * kVec;
+    int64_t base = int64_t(blockIdx.x) * kChunk;
+    for (; base + kChunk <= numel; base += stride) {
         typename Store<T>::raw_t v[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (e[u] + kVec <= numel) v[u] = Store<T>::load(x, e[u]);
+        for (int u = 0; u < U; ++u) v[u] = Nt<T>::load(x, base + u * (kThreads * kVec) + toff);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            if (e[u] + kVec <= numel && c[u].rem + kVec <= gg.inner) {
-                if (c[u].g != cur[u]) {
-                    flush_lane(lmn, lmx, cur[u], acc[u].lo(), acc[u].hi());
-                    cur[u] = c[u].g;
-                    acc[u].init();
+            if (__builtin_expect(c[u].rem + kVec <= gg.inner, 1)) {
+                if (c[u].g != st[u].cur) {   // moved on to another group: hand the finished one to LDS
+                    flush_lane(lmn, lmx, st[u].cur, st[u].acc.lo(), st[u].acc.hi());
+                    st[u].cur = c[u].g;
+                    st[u].acc.init();
                 }
-                acc[u].add(v[u]);
-            } else if (e[u] < numel) {  // crosses a slab end, or is the ragged tail
-                int64_t left = numel - e[u];
-                int n = left < kVec ? int(left) : kVec;
-                for (int j = 0; j < n; ++j) {
-                    uint32_t g = group_of(c[u], j, gg);
-                    if (g != cur[u]) {
-                        flush_lane(lmn, lmx, cur[u], acc[u].lo(), acc[u].hi());
-                        cur[u] = g;
-                        acc[u].init();
-                    }
-                    acc[u].add1(Store<T>::load1(x, e[u] + j));
-                }
+                st[u].acc.add(v[u]);
+            } else {
+                st[u] = minmax_elements<T>(x, base + u * (kThreads * kVec) + toff, kVec, c[u], gg, st[u], lmn, lmx);
             }
-            e[u] += step;
             cursor_advance(c[u], gg);
         }
     }
+    if (base < numel) {  // the chunk that holds the end of the tensor
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        // a wave whose lanes all sit in one group (head-wise tensors) combines in registers first
-        float lo = acc[u].lo(), hi = acc[u].hi();
-        uint32_t g0 = __builtin_amdgcn_readfirstlane(cur[u]);
-        if (__all(cur[u] == g0)) {
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) {
-                lo = fminf(lo, __shfl_xor(lo, off, 64));
-                hi = fmaxf(hi, __shfl_xor(hi, off, 64));
+        for (int u = 0; u < U; ++u) {
+            const int64_t e = base + u * (kThreads * kVec) + toff;
+            if (e < numel) {
+                const int64_t left = numel - e;
+                st[u] = minmax_elements<T>(x, e, left < kVec ? int(left) : kVec, c[u], gg, st[u], lmn, lmx);
             }
-            if ((threadIdx.x & 63) == 0) flush_lane(lmn, lmx, g0, lo, hi);
-        } else {
-            flush_lane(lmn, lmx, cur[u], lo, hi);
         }
+    }
+    // fold the U accumulators that sit in the same group, then let a wave whose lanes all sit in
+    // one group (head-wise tensors) combine in registers before touching LDS
+    float lo = st[0].acc.lo(), hi = st[0].acc.hi();
+#pragma unroll
+    for (int u = 1; u < U; ++u) {
+        if (st[u].cur == st[0].cur) {
+            lo = vmin(lo, st[u].acc.lo());
+            hi = vmax(hi, st[u].acc.hi());
+        } else {
+            flush_lane(lmn, lmx, st[u].cur, st[u].acc.lo(), st[u].acc.hi());
+        }
+    }
+    const uint32_t g0 = __builtin_amdgcn_readfirstlane(st[0].cur);
+    if (__all(st[0].cur == g0)) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            lo = vmin(lo, __shfl_xor(lo, off, 64));
+            hi = vmax(hi, __shfl_xor(hi, off, 64));
+        }
+        if ((threadIdx.x & 63) == 0) flush_lane(lmn, lmx, g0, lo, hi);
+    } else {
+        flush_lane(lmn, lmx, st[0].cur, lo, hi);
     }
     __syncthreads();
     float *out = part + int64_t(blockIdx.x) * 2 * gg.groups;
@@ -251,30 +297,56 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
-// the eight random fractions of the block of elements [8b, 8b+8): 16 bits each, u = bits * 2^-16
-__device__ __forceinline__ void sr_fractions(uint64_t seed, uint64_t counter, float u[8])
+// 16 random bits (as a float in [0, 65536)) for each of the eight elements of block `counter`
+__device__ __forceinline__ void sr_bits(uint64_t seed, uint64_t counter, float b[8])
 {
     uint32_t w[4];
     philox4x32_10(uint32_t(counter), uint32_t(counter >> 32), uint32_t(seed), uint32_t(seed >> 32), w);
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        u[2 * k] = float(w[k] & 0xFFFFu) * 1.52587890625e-05f;
-        u[2 * k + 1] = float(w[k] >> 16) * 1.52587890625e-05f;
+        b[2 * k] = float(w[k] & 0xFFFFu);
+        b[2 * k + 1] = float(w[k] >> 16);
     }
 }
 
-template <bool SR> __device__ __forceinline__ float quantize_one(float x, float r, float b, float u)
+// Eq. (3)-(4) for one element; returns the integer x_bar (unclipped) as a float.
+// Stochastic rounding adds u = bits*2^-16: the product is exact, so the fused form rounds once,
+// exactly like the separate sum v + u.
+template <bool SR> __device__ __forceinline__ float quantize_one(float x, float r, float b, float bits)
 {
     float t = x - b;
     float v = t * r;
-    float w;
-    if (SR) {
-        float s = v + u;
-        w = floorf(s);
-    } else {
-        w = rintf(v);  // nearest, ties to even
+    if (SR) return floorf(__builtin_fmaf(bits, 1.52587890625e-05f, v));
+    return rintf(v);  // nearest, ties to even
+}
+
+// eight unclipped integers -> eight codes; the conversion instruction saturates to [0, 255]
+__device__ __forceinline__ u32x2 pack_codes(const float w[8])
+{
+    u32x2 c;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        uint32_t b = 0u;
+        b = __builtin_amdgcn_cvt_pk_u8_f32(w[4 * k + 0], 0, b);
+        b = __builtin_amdgcn_cvt_pk_u8_f32(w[4 * k + 1], 1, b);
+        b = __builtin_amdgcn_cvt_pk_u8_f32(w[4 * k + 2], 2, b);
+        b = __builtin_amdgcn_cvt_pk_u8_f32(w[4 * k + 3], 3, b);
+        c[k] = b ^ 0x80808080u;  // -128 on each byte
     }
-    return clamp_code(w);
+    return c;
+}
+
+template <typename T, bool SR>
+__device__ __attribute__((noinline)) void quantize_elements(const void *x, int8_t *q, int64_t e, int n, Cursor c, GroupGeom gg,
+                                                            const float2 *tab, uint64_t seed, uint64_t counter)
+{
+    float bits[8];
+    if (SR) sr_bits(seed, counter, bits);
+    for (int j = 0; j < n; ++j) {
+        float2 p = tab[group_of(c, j, gg)];
+        float w = clamp_code(quantize_one<SR>(Store<T>::load1(x, e + j), p.x, p.y, SR ? bits[j] : 0.0f));
+        q[e + j] = int8_t(int(w) - 128);
+    }
 }
 
 template <typename T, int U, bool SR>
@@ -285,54 +357,41 @@ __global__ __launch_bounds__(kThreads) void k_quantize(const void *__restrict__ 
     extern __shared__ float2 lds_tab[];
     fill_table<Scale::Quant>(lds_tab, alpha, beta, gg.groups);
 
-    const int64_t span = int64_t(gridDim.x) * kThreads * kVec;
-    const int64_t step = span * U;
-    int64_t e[U];
     Cursor c[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        e[u] = u * span + (int64_t(blockIdx.x) * kThreads + threadIdx.x) * kVec;
-        c[u] = cursor_init(e[u], gg);
-    }
-    while (e[0] < numel) {
+    place_cursors<U>(c, gg, numel);
+    const int64_t stride = int64_t(gridDim.x) * kChunk;
+    const int64_t toff = int64_t(threadIdx.x) * kVec;
+    int64_t base = int64_t(blockIdx.x) * kChunk;
+    for (; base + kChunk <= numel; base += stride) {
         typename Store<T>::raw_t v[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (e[u] + kVec <= numel) v[u] = Store<T>::load(x, e[u]);
+        for (int u = 0; u < U; ++u) v[u] = Nt<T>::load(x, base + u * (kThreads * kVec) + toff);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            if (e[u] < numel) {
-                float rnd[8];
-                if (SR) sr_fractions(seed, offset + uint64_t(e[u] >> 3), rnd);
-                if (e[u] + kVec <= numel) {
-                    float f[8], w[8];
-                    Store<T>::unpack(v[u], f);
-                    if (c[u].rem + kVec <= gg.inner) {
-                        float2 p = lds_tab[c[u].g];
+            const int64_t e = base + u * (kThreads * kVec) + toff;
+            if (__builtin_expect(c[u].rem + kVec <= gg.inner, 1)) {
+                float f[8], w[8], bits[8];
+                if (SR) sr_bits(seed, offset + uint64_t(e >> 3), bits);
+                Store<T>::unpack(v[u], f);
+                const float2 p = lds_tab[c[u].g];
 #pragma unroll
-                        for (int j = 0; j < 8; ++j) w[j] = quantize_one<SR>(f[j], p.x, p.y, SR ? rnd[j] : 0.0f);
-                    } else {
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) {
-                            float2 p = lds_tab[group_of(c[u], j, gg)];
-                            w[j] = quantize_one<SR>(f[j], p.x, p.y, SR ? rnd[j] : 0.0f);
-                        }
-                    }
-                    *reinterpret_cast<u32x2 *>(q + e[u]) = float_to_codes(w);
-                } else {
-                    int n = int(numel - e[u]);
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        if (j < n) {
-                            float2 p = lds_tab[group_of(c[u], j, gg)];
-                            float w = quantize_one<SR>(Store<T>::load1(x, e[u] + j), p.x, p.y, SR ? rnd[j] : 0.0f);
-                            q[e[u] + j] = int8_t(int(w) - 128);
-                        }
-                    }
-                }
+                for (int j = 0; j < 8; ++j) w[j] = quantize_one<SR>(f[j], p.x, p.y, SR ? bits[j] : 0.0f);
+                nt_store<u32x2>(q + e, pack_codes(w));
+            } else {
+                quantize_elements<T, SR>(x, q, e, kVec, c[u], gg, lds_tab, seed, offset + uint64_t(e >> 3));
             }
-            e[u] += step;
             cursor_advance(c[u], gg);
+        }
+    }
+    if (base < numel) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t e = base + u * (kThreads * kVec) + toff;
+            if (e < numel) {
+                const int64_t left = numel - e;
+                quantize_elements<T, SR>(x, q, e, left < kVec ? int(left) : kVec, c[u], gg, lds_tab, seed,
+                                         offset + uint64_t(e >> 3));
+            }
         }
     }
 }
@@ -347,6 +406,16 @@ __device__ __forceinline__ float dequant_exact(float u, float s, float b)
     return xh;
 }
 
+template <typename T>
+__device__ __attribute__((noinline)) void dequantize_elements(const int8_t *q, void *xh, int64_t e, int n, Cursor c,
+                                                              GroupGeom gg, const float2 *tab)
+{
+    for (int j = 0; j < n; ++j) {
+        const float2 p = tab[group_of(c, j, gg)];
+        Store<T>::store1(xh, e + j, dequant_exact(code_to_float(q[e + j]), p.x, p.y));
+    }
+}
+
 template <typename T, int U>
 __global__ __launch_bounds__(kThreads) void k_dequantize(const int8_t *__restrict__ q, void *__restrict__ xh, int64_t numel,
                                                          GroupGeom gg, const float *__restrict__ alpha,
@@ -355,46 +424,39 @@ __global__ __launch_bounds__(kThreads) void k_dequantize(const int8_t *__restric
     extern __shared__ float2 lds_tab[];
     fill_table<Scale::Dequant>(lds_tab, alpha, beta, gg.groups);
 
-    const int64_t span = int64_t(gridDim.x) * kThreads * kVec;
-    const int64_t step = span * U;
-    int64_t e[U];
     Cursor c[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        e[u] = u * span + (int64_t(blockIdx.x) * kThreads + threadIdx.x) * kVec;
-        c[u] = cursor_init(e[u], gg);
-    }
-    while (e[0] < numel) {
+    place_cursors<U>(c, gg, numel);
+    const int64_t stride = int64_t(gridDim.x) * kChunk;
+    const int64_t toff = int64_t(threadIdx.x) * kVec;
+    int64_t base = int64_t(blockIdx.x) * kChunk;
+    for (; base + kChunk <= numel; base += stride) {
         u32x2 v[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (e[u] + kVec <= numel) v[u] = load_codes8(q, e[u]);
+        for (int u = 0; u < U; ++u) v[u] = nt_load<u32x2>(q + base + u * (kThreads * kVec) + toff);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            if (e[u] + kVec <= numel) {
+            const int64_t e = base + u * (kThreads * kVec) + toff;
+            if (__builtin_expect(c[u].rem + kVec <= gg.inner, 1)) {
                 float uu[8], f[8];
                 codes_to_float(v[u], uu);
-                if (c[u].rem + kVec <= gg.inner) {
-                    float2 p = lds_tab[c[u].g];
+                const float2 p = lds_tab[c[u].g];
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) f[j] = dequant_exact(uu[j], p.x, p.y);
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        float2 p = lds_tab[group_of(c[u], j, gg)];
-                        f[j] = dequant_exact(uu[j], p.x, p.y);
-                    }
-                }
-                Store<T>::store(xh, e[u], Store<T>::pack(f));
-            } else if (e[u] < numel) {
-                int n = int(numel - e[u]);
-                for (int j = 0; j < n; ++j) {
-                    float2 p = lds_tab[group_of(c[u], j, gg)];
-                    Store<T>::store1(xh, e[u] + j, dequant_exact(code_to_float(q[e[u] + j]), p.x, p.y));
-                }
+                for (int j = 0; j < 8; ++j) f[j] = dequant_exact(uu[j], p.x, p.y);
+                Nt<T>::store(xh, e, Store<T>::pack(f));
+            } else {
+                dequantize_elements<T>(q, xh, e, kVec, c[u], gg, lds_tab);
             }
-            e[u] += step;
             cursor_advance(c[u], gg);
+        }
+    }
+    if (base < numel) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t e = base + u * (kThreads * kVec) + toff;
+            if (e < numel) {
+                const int64_t left = numel - e;
+                dequantize_elements<T>(q, xh, e, left < kVec ? int(left) : kVec, c[u], gg, lds_tab);
+            }
         }
     }
 }
@@ -420,60 +482,91 @@ __device__ __forceinline__ float gelu_grad(float x)
     return fmaf(x * E, 0.39894228040143268f, cdf);
 }
 
-template <typename T, int U>
+template <typename T, bool LUT>
+__device__ __attribute__((noinline)) void gelu_elements(const int8_t *q, const void *dy, void *dx, int64_t e, int n, Cursor c,
+                                                        GroupGeom gg, const float *lds)
+{
+    for (int j = 0; j < n; ++j) {
+        const uint32_t g = group_of(c, j, gg);
+        const uint32_t raw = uint32_t(uint8_t(q[e + j]));
+        float gr;
+        if (LUT) {
+            gr = lds[g * 256u + raw];
+        } else {
+            const float2 p = reinterpret_cast<const float2 *>(lds)[g];
+            gr = gelu_grad(fmaf(float(raw ^ 0x80u), p.x, p.y));
+        }
+        Store<T>::store1(dx, e + j, Store<T>::load1(dy, e + j) * gr);
+    }
+}
+
+// x_hat takes only 256 values per group, so gelu'(x_hat) is a table of groups*256 entries: each
+// workgroup fills it once (indexed by the raw code byte) and the stream becomes one LDS gather and
+// one multiply per element.  With more than kLutMaxGroups groups the table does not fit and the
+// derivative is evaluated per element instead (LUT = false).
+template <typename T, int U, bool LUT>
 __global__ __launch_bounds__(kThreads) void k_gelu_bwd(const int8_t *__restrict__ q, const void *dy, void *dx, int64_t numel,
                                                        GroupGeom gg, const float *__restrict__ alpha,
                                                        const float *__restrict__ beta)
 {
-    extern __shared__ float2 lds_tab[];
-    fill_table<Scale::Dequant>(lds_tab, alpha, beta, gg.groups);
-
-    const int64_t span = int64_t(gridDim.x) * kThreads * kVec;
-    const int64_t step = span * U;
-    int64_t e[U];
-    Cursor c[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        e[u] = u * span + (int64_t(blockIdx.x) * kThreads + threadIdx.x) * kVec;
-        c[u] = cursor_init(e[u], gg);
+    extern __shared__ float lds_gelu[];
+    float2 *tab2 = reinterpret_cast<float2 *>(lds_gelu);   // LUT = false: (step, beta) per group
+    if (LUT) {
+        for (uint32_t i = threadIdx.x; i < gg.groups * 256u; i += kThreads) {
+            const uint32_t g = i >> 8;
+            const float u = float((i & 255u) ^ 0x80u);   // raw byte -> x_bar
+            lds_gelu[i] = gelu_grad(fmaf(u, alpha[g] / 255.0f, beta[g]));
+        }
+        __syncthreads();
+    } else {
+        fill_table<Scale::Dequant>(tab2, alpha, beta, gg.groups);
     }
-    while (e[0] < numel) {
+
+    Cursor c[U];
+    place_cursors<U>(c, gg, numel);
+    const int64_t stride = int64_t(gridDim.x) * kChunk;
+    const int64_t toff = int64_t(threadIdx.x) * kVec;
+    int64_t base = int64_t(blockIdx.x) * kChunk;
+    for (; base + kChunk <= numel; base += stride) {
         u32x2 v[U];
         typename Store<T>::raw_t d[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (e[u] + kVec <= numel) {
-                v[u] = load_codes8(q, e[u]);
-                d[u] = Store<T>::load(dy, e[u]);
-            }
+        for (int u = 0; u < U; ++u) {
+            v[u] = nt_load<u32x2>(q + base + u * (kThreads * kVec) + toff);
+            d[u] = Nt<T>::load(dy, base + u * (kThreads * kVec) + toff);
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            if (e[u] + kVec <= numel) {
-                float uu[8], g[8];
-                codes_to_float(v[u], uu);
+            const int64_t e = base + u * (kThreads * kVec) + toff;
+            if (__builtin_expect(c[u].rem + kVec <= gg.inner, 1)) {
+                float g[8];
                 Store<T>::unpack(d[u], g);
-                if (c[u].rem + kVec <= gg.inner) {
-                    float2 p = lds_tab[c[u].g];
+                if (LUT) {
+                    const float *row = lds_gelu + c[u].g * 256u;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) g[j] = g[j] * row[(v[u][j >> 2] >> (8 * (j & 3))) & 0xFFu];
+                } else {
+                    const float2 p = tab2[c[u].g];
+                    float uu[8];
+                    codes_to_float(v[u], uu);
 #pragma unroll
                     for (int j = 0; j < 8; ++j) g[j] = g[j] * gelu_grad(fmaf(uu[j], p.x, p.y));
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        float2 p = lds_tab[group_of(c[u], j, gg)];
-                        g[j] = g[j] * gelu_grad(fmaf(uu[j], p.x, p.y));
-                    }
                 }
-                Store<T>::store(dx, e[u], Store<T>::pack(g));
-            } else if (e[u] < numel) {
-                int n = int(numel - e[u]);
-                for (int j = 0; j < n; ++j) {
-                    float2 p = lds_tab[group_of(c[u], j, gg)];
-                    float xh = fmaf(code_to_float(q[e[u] + j]), p.x, p.y);
-                    Store<T>::store1(dx, e[u] + j, Store<T>::load1(dy, e[u] + j) * gelu_grad(xh));
-                }
+                Nt<T>::store(dx, e, Store<T>::pack(g));
+            } else {
+                gelu_elements<T, LUT>(q, dy, dx, e, kVec, c[u], gg, lds_gelu);
             }
-            e[u] += step;
             cursor_advance(c[u], gg);
+        }
+    }
+    if (base < numel) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t e = base + u * (kThreads * kVec) + toff;
+            if (e < numel) {
+                const int64_t left = numel - e;
+                gelu_elements<T, LUT>(q, dy, dx, e, left < kVec ? int(left) : kVec, c[u], gg, lds_gelu);
+            }
         }
     }
 }
@@ -483,13 +576,20 @@ __global__ __launch_bounds__(kThreads) void k_gelu_bwd(const int8_t *__restrict_
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void k_copy(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, int64_t n16)
 {
-    const int64_t span = int64_t(gridDim.x) * kThreads;
-    int64_t i = int64_t(blockIdx.x) * kThreads + threadIdx.x;
-    for (; i + 3 * span < n16; i += 4 * span) {
-        u32x4 a = src[i], b = src[i + span], c = src[i + 2 * span], d = src[i + 3 * span];
-        dst[i] = a; dst[i + span] = b; dst[i + 2 * span] = c; dst[i + 3 * span] = d;
+    const int64_t chunk = kThreads * 4;
+    for (int64_t base = int64_t(blockIdx.x) * chunk; base < n16; base += int64_t(gridDim.x) * chunk) {
+        u32x4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t i = base + u * kThreads + threadIdx.x;
+            if (i < n16) v[u] = nt_load<u32x4>(src + i);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t i = base + u * kThreads + threadIdx.x;
+            if (i < n16) nt_store<u32x4>(dst + i, v[u]);
+        }
     }
-    for (; i < n16; i += span) dst[i] = src[i];
 }
 
 }  // namespace mesa
@@ -501,7 +601,7 @@ using namespace mesa;
 
 static int stream_grid(int64_t numel, int64_t row)
 {
-    return plan_grid(numel, int64_t(kThreads) * kVec * kU, kGridCap, row);
+    return plan_grid(numel, kChunk, kGridCap, row);
 }
 
 static int minmax_grid(const mesa_layout &L)
@@ -513,7 +613,7 @@ static int minmax_grid(const mesa_layout &L)
         cap = int(int64_t(kGridCap) * 64 / L.groups);
         if (cap < 32) cap = 32;
     }
-    return plan_grid(numel, int64_t(kThreads) * kVec * kU, cap, L.groups > 1 ? L.groups * L.inner : 0);
+    return plan_grid(numel, kChunk, cap, L.groups > 1 ? L.groups * L.inner : 0);
 }
 
 extern "C" MESA_EXPORT mesa_status mesa_update_running_params(const void *x, mesa_dtype dt, mesa_layout L, float *alpha, float *beta,
@@ -530,8 +630,7 @@ extern "C" MESA_EXPORT mesa_status mesa_update_running_params(const void *x, mes
         return MESA_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int grid = minmax_grid(L);
-    const int64_t step = int64_t(grid) * kThreads * kVec * kU;
-    GroupGeom gg = make_geom(L.groups, L.inner, step);
+    GroupGeom gg = make_geom(L.groups, L.inner, int64_t(grid) * kChunk);
     const size_t lds = size_t(2) * gg.groups * sizeof(int);
     float *part = static_cast<float *>(ws);
     if (dt == MESA_F16)
@@ -556,7 +655,7 @@ extern "C" MESA_EXPORT mesa_status mesa_quantize_headwise(const void *x, mesa_dt
         return MESA_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int grid = stream_grid(numel, L.groups > 1 ? L.groups * L.inner : 0);
-    GroupGeom gg = make_geom(L.groups, L.inner, int64_t(grid) * kThreads * kVec * kU);
+    GroupGeom gg = make_geom(L.groups, L.inner, int64_t(grid) * kChunk);
     const size_t lds = size_t(gg.groups) * sizeof(float2);
     const bool sr = mode == MESA_ROUND_STOCHASTIC;
 #define MESA_LAUNCH_Q(T, SRF) \
@@ -579,7 +678,7 @@ extern "C" MESA_EXPORT mesa_status mesa_dequantize(const int8_t *q, mesa_layout 
         return MESA_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int grid = stream_grid(numel, L.groups > 1 ? L.groups * L.inner : 0);
-    GroupGeom gg = make_geom(L.groups, L.inner, int64_t(grid) * kThreads * kVec * kU);
+    GroupGeom gg = make_geom(L.groups, L.inner, int64_t(grid) * kChunk);
     const size_t lds = size_t(gg.groups) * sizeof(float2);
     if (dt == MESA_F16)
         hipLaunchKernelGGL((k_dequantize<_Float16, kU>), dim3(grid), dim3(kThreads), lds, s, q, x_hat, numel, gg, alpha, beta);
@@ -601,12 +700,14 @@ extern "C" MESA_EXPORT mesa_status mesa_gelu_bwd_q(const int8_t *xq, mesa_layout
         return MESA_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int grid = stream_grid(numel, L.groups > 1 ? L.groups * L.inner : 0);
-    GroupGeom gg = make_geom(L.groups, L.inner, int64_t(grid) * kThreads * kVec * kU);
-    const size_t lds = size_t(gg.groups) * sizeof(float2);
-    if (dt == MESA_F16)
-        hipLaunchKernelGGL((k_gelu_bwd<_Float16, kU>), dim3(grid), dim3(kThreads), lds, s, xq, dy, dx, numel, gg, alpha, beta);
-    else
-        hipLaunchKernelGGL((k_gelu_bwd<float, kU>), dim3(grid), dim3(kThreads), lds, s, xq, dy, dx, numel, gg, alpha, beta);
+    GroupGeom gg = make_geom(L.groups, L.inner, int64_t(grid) * kChunk);
+    const bool lut = gg.groups <= uint32_t(kLutMaxGroups);
+    const size_t lds = lut ? size_t(gg.groups) * 256 * sizeof(float) : size_t(gg.groups) * sizeof(float2);
+#define MESA_LAUNCH_G(T, L_) \
+    hipLaunchKernelGGL((k_gelu_bwd<T, kU, L_>), dim3(grid), dim3(kThreads), lds, s, xq, dy, dx, numel, gg, alpha, beta)
+    if (dt == MESA_F16) { if (lut) MESA_LAUNCH_G(_Float16, true); else MESA_LAUNCH_G(_Float16, false); }
+    else { if (lut) MESA_LAUNCH_G(float, true); else MESA_LAUNCH_G(float, false); }
+#undef MESA_LAUNCH_G
     return launch_status();
 }
 
@@ -615,7 +716,7 @@ extern "C" MESA_EXPORT mesa_status mesa_stream_copy(const void *src, void *dst, 
     if (bytes == 0) return MESA_OK;
     if (!src || !dst || !aligned16(src) || !aligned16(dst) || (bytes & 15u)) return MESA_ERR_INVALID_ARG;
     const int64_t n16 = int64_t(bytes / 16);
-    const int grid = plan_grid(n16, int64_t(kThreads) * 4, kGridCap, 0);
+    const int grid = plan_grid(n16, int64_t(kThreads) * 4, 4 * kGridCap, 0);
     hipLaunchKernelGGL(k_copy, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
                        static_cast<const u32x4 *>(src), static_cast<u32x4 *>(dst), n16);
     return launch_status();

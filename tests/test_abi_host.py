@@ -51,7 +51,7 @@ def test_argument_errors_are_reported_before_any_launch(M):
     assert L.mesa_quantize_headwise(P, M.F16, lay, P, P, P, 5, 0, 0, None) == M.ERR_INVALID_ARG           # rounding mode
     assert L.mesa_quantize_headwise(P, M.F16, M.Layout(-1, 3, 4), P, P, P, 0, 0, 0, None) == M.ERR_INVALID_ARG
     assert L.mesa_quantize_headwise(P, M.F16, M.Layout(2, 9000, 4), P, P, P, 0, 0, 0, None) == M.ERR_UNSUPPORTED
-    assert L.mesa_quantize_headwise(P, M.F16, M.Layout(2, 2, 1 << 31), P, P, P, 0, 0, 0, None) == M.ERR_UNSUPPORTED
+    assert L.mesa_quantize_headwise(P, M.F16, M.Layout(2, 2, 1 << 30), P, P, P, 0, 0, 0, None) == M.ERR_UNSUPPORTED
     assert L.mesa_update_running_params(P, M.F16, lay, P, P, 1.5, 0, P, 1 << 20, None) == M.ERR_INVALID_ARG  # lambda
     assert L.mesa_update_running_params(P, M.F16, lay, P, P, float("nan"), 0, P, 1 << 20, None) == M.ERR_INVALID_ARG
     assert L.mesa_update_running_params(P, M.F16, lay, P, P, 0.9, 0, P, 8, None) == M.ERR_WORKSPACE
