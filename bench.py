@@ -169,7 +169,7 @@ def cpu_baseline(spec, target_seconds=20.0):
         R.softmax_bwd_q(q["attn"], Bq, Hq, r, c, a["attn"], b["attn"], dy["attn"])
         passes += 1
         el = time.perf_counter() - t0
-        if el > target_seconds / 2 or passes >= 8:
+        if el > target_seconds / 2:
             break
     total_bytes = sum(algorithmic_bytes(s).values()) * passes
     return {"value": round(total_bytes / el / 1e9, 4), "unit": "GB/s", "cores": R.num_threads(), "kind": "oracle",

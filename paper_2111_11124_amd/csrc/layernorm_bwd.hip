@@ -2,9 +2,10 @@
 //   xn = (x_hat - mean)*rstd,  g = dy*gamma,
 //   dx = rstd*(g - mean_j(g) - xn*mean_j(g*xn)),   dgamma_j = sum_rows dy*xn,  dbeta_j = sum_rows dy.
 //
-// A workgroup takes tiles of R whole rows (R*D <= 4096 elements) and reads them flat as 8-element
-// vectors; codes and dy stay in registers between the reduction pass and the output pass, two
-// partial sums per vector go through LDS (16 lanes per row add them in a fixed order).  A thread
+// A wave (a whole workgroup when a row is longer than 1024 elements) takes tiles of R whole rows
+// and reads them flat as 8-element vectors; codes and dy stay in registers between the reduction
+// pass and the output pass, two partial sums per vector go through LDS (16 lanes per row add them
+// in a fixed order); waves owning their own tiles need no workgroup barrier.  A thread
 // meets the same columns in every tile, so it keeps its share of the column sums in registers
 // for the whole kernel; they are combined per workgroup in LDS, written as partials, and a small
 // second kernel adds the partials of all workgroups -- fixed order throughout, no float atomics.
@@ -15,37 +16,57 @@
 
 namespace mesa {
 
-constexpr int kLnU = 2;
-constexpr int kLnTileVec = kThreads * kLnU;   // 512 vectors = 4096 elements
-constexpr int kLnMaxGroups = kLnTileVec;      // (D/G) % 8 == 0 and D <= 4096
-constexpr int kLnGridCap = 512;
+constexpr int kLnU = 2;                 // vectors per thread in a tile
+constexpr int kLnGridCap = 1024;
+constexpr int kLnMaxD = kThreads * kLnU * kVec;   // 4096: a row must fit a workgroup tile
+constexpr int kLnMaxGroups = kLnMaxD / kVec;      // (D/G) % 8 == 0
+constexpr int kLnFinThreads = 1024;               // finalize: 32 columns x 32 slices of the workgroup list
 
-template <typename T>
-__global__ __launch_bounds__(kThreads) void k_layernorm_bwd(const int8_t *__restrict__ xq, const void *dy, void *dx,
-                                                            const void *__restrict__ gamma, const float *__restrict__ mean,
-                                                            const float *__restrict__ rstd, const float *__restrict__ alpha,
-                                                            const float *__restrict__ beta, int64_t M, uint32_t D,
-                                                            uint32_t R, int64_t tiles, uint32_t groups, FastDiv div_vpr,
-                                                            FastDiv div_vpg, float inv_D, float *__restrict__ part)
+template <int TPT> __device__ __forceinline__ void ln_sync()
 {
-    __shared__ float2 tab[kLnMaxGroups];
-    __shared__ float P1[kLnTileVec], P2[kLnTileVec];
-    __shared__ float C1[kLnTileVec], C2[kLnTileVec];
-    __shared__ float colG[kLnTileVec * kVec], colB[kLnTileVec * kVec];   // [slot r][D], R*D <= 4096
+    if (TPT == kThreads) {
+        __syncthreads();
+    } else {  // one wave owns the tile: order its own LDS traffic, nothing more
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+}
 
-    const uint32_t tid = threadIdx.x;
+__device__ __forceinline__ void ln_opaque(u32x2 &a, u32x4 &b) { asm volatile("" : "+v"(a), "+v"(b)); }
+__device__ __forceinline__ void ln_opaque(u32x2 &a, Store<float>::raw_t &b)
+{
+    asm volatile("" : "+v"(a), "+v"(b.lo), "+v"(b.hi));
+}
+
+// TPT threads (one wave when R whole rows fit 128 vectors, else the workgroup) own a tile of R rows.
+template <typename T, int TPT>
+__global__ __launch_bounds__(kThreads, 4) void k_layernorm_bwd(const int8_t *__restrict__ xq, const void *dy, void *dx,
+                                                               const void *__restrict__ gamma, const float *__restrict__ mean,
+                                                               const float *__restrict__ rstd, const float *__restrict__ alpha,
+                                                               const float *__restrict__ beta, int64_t M, uint32_t D,
+                                                               uint32_t R, int64_t tiles, uint32_t groups, FastDiv div_vpr,
+                                                               FastDiv div_vpg, float inv_D, float *__restrict__ part)
+{
+    constexpr int kTileVec = TPT * kLnU;
+    constexpr int kTeams = kThreads / TPT;
+    __shared__ float P1[kTeams][kTileVec], P2[kTeams][kTileVec];
+    __shared__ float C1[kTeams][kTileVec], C2[kTeams][kTileVec];
+    __shared__ float colG[kLnMaxD], colB[kLnMaxD];   // [team][slot r][D]: kTeams * R * D <= 4096
+
+    const uint32_t team = threadIdx.x / TPT;
+    const uint32_t tid = threadIdx.x % TPT;
     const uint32_t vpr = div_vpr.d;   // vectors per row = D/8
-    for (uint32_t g = tid; g < groups; g += kThreads) tab[g] = make_float2(alpha[g] / 255.0f, beta[g]);
+    float *p1 = P1[team], *p2 = P2[team], *c1s = C1[team], *c2s = C2[team];
 
-    // this thread's fixed place in every tile
+    // this thread's fixed place in every tile: row slot rr, columns col..col+7
     uint32_t rr[kLnU], col[kLnU];
     bool act[kLnU];
     float gam[kLnU][8], accG[kLnU][8], accB[kLnU][8];
     float2 prm[kLnU];
-    __syncthreads();
 #pragma unroll
     for (int u = 0; u < kLnU; ++u) {
-        const uint32_t v = u * kThreads + tid;
+        const uint32_t v = u * TPT + tid;
         act[u] = v < R * vpr;
         rr[u] = fastdiv(v, div_vpr);
         const uint32_t cv = v - rr[u] * vpr;
@@ -55,11 +76,12 @@ __global__ __launch_bounds__(kThreads) void k_layernorm_bwd(const int8_t *__rest
         prm[u] = make_float2(0.0f, 0.0f);
         if (act[u]) {
             Store<T>::unpack(Store<T>::load(gamma, col[u]), gam[u]);
-            prm[u] = tab[fastdiv(cv, div_vpg)];
+            const uint32_t g = fastdiv(cv, div_vpg);
+            prm[u] = make_float2(alpha[g] / 255.0f, beta[g]);
         }
     }
 
-    for (int64_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    for (int64_t tile = int64_t(blockIdx.x) * kTeams + team; tile < tiles; tile += int64_t(gridDim.x) * kTeams) {
         const int64_t row0 = tile * R;
         const uint32_t nrows = uint32_t((M - row0 < int64_t(R)) ? (M - row0) : int64_t(R));
 
@@ -68,14 +90,19 @@ __global__ __launch_bounds__(kThreads) void k_layernorm_bwd(const int8_t *__rest
         float mu[kLnU], rs[kLnU];
 #pragma unroll
         for (int u = 0; u < kLnU; ++u) {
-            const uint32_t v = u * kThreads + tid;
             if (act[u] && rr[u] < nrows) {
                 const int64_t row = row0 + rr[u];
                 const int64_t e = row * D + col[u];
-                cq[u] = load_codes8(xq, e);
-                cd[u] = Store<T>::load(dy, e);
+                cq[u] = nt_load<u32x2>(xq + e);
+                cd[u] = Nt<T>::load(dy, e);
                 mu[u] = mean[row];
                 rs[u] = rstd[row];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kLnU; ++u) {
+            const uint32_t v = u * TPT + tid;
+            if (act[u] && rr[u] < nrows) {
                 float y[8], d[8];
                 codes_to_float(cq[u], y);
                 Store<T>::unpack(cd[u], d);
@@ -89,27 +116,29 @@ __global__ __launch_bounds__(kThreads) void k_layernorm_bwd(const int8_t *__rest
                     accG[u][j] = fmaf(d[j], xn, accG[u][j]);
                     accB[u][j] += d[j];
                 }
-                P1[v] = s1;
-                P2[v] = s2;
+                p1[v] = s1;
+                p2[v] = s2;
             }
         }
-        __syncthreads();
+        ln_sync<TPT>();
         {
             const uint32_t lane16 = tid & 15u;
-            for (uint32_t r = tid >> 4; r < nrows; r += kThreads / 16) {
+            for (uint32_t r = tid >> 4; r < nrows; r += TPT / 16) {
                 float s1 = 0.0f, s2 = 0.0f;
-                for (uint32_t k = lane16; k < vpr; k += 16) { s1 += P1[r * vpr + k]; s2 += P2[r * vpr + k]; }
+                for (uint32_t k = lane16; k < vpr; k += 16) { s1 += p1[r * vpr + k]; s2 += p2[r * vpr + k]; }
                 s1 = lanes_sum<16>(s1);
                 s2 = lanes_sum<16>(s2);
-                if (lane16 == 0) { C1[r] = s1 * inv_D; C2[r] = s2 * inv_D; }
+                if (lane16 == 0) { c1s[r] = s1 * inv_D; c2s[r] = s2 * inv_D; }
             }
         }
-        __syncthreads();
+        ln_sync<TPT>();
+#pragma unroll
+        for (int u = 0; u < kLnU; ++u) ln_opaque(cq[u], cd[u]);   // rebuild the unpacked values instead of holding them
 #pragma unroll
         for (int u = 0; u < kLnU; ++u) {
             if (act[u] && rr[u] < nrows) {
                 const int64_t e = (row0 + rr[u]) * D + col[u];
-                const float c1 = C1[rr[u]], c2 = C2[rr[u]];
+                const float c1 = c1s[rr[u]], c2 = c2s[rr[u]];
                 float y[8], d[8], o[8];
                 codes_to_float(cq[u], y);
                 Store<T>::unpack(cd[u], d);
@@ -119,74 +148,97 @@ __global__ __launch_bounds__(kThreads) void k_layernorm_bwd(const int8_t *__rest
                     const float gg = d[j] * gam[u][j];
                     o[j] = rs[u] * (gg - c1 - xn * c2);
                 }
-                Store<T>::store(dx, e, Store<T>::pack(o));
+                Nt<T>::store(dx, e, Store<T>::pack(o));
             }
         }
-        __syncthreads();
+        ln_sync<TPT>();
     }
 
-    // column sums of this workgroup: slot r of the tile holds what its threads gathered
+    // column sums of this workgroup: slot (team, r) holds what its threads gathered
+    __syncthreads();
 #pragma unroll
     for (int u = 0; u < kLnU; ++u) {
         if (act[u]) {
+            const uint32_t o = (team * R + rr[u]) * D + col[u];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                colG[rr[u] * D + col[u] + j] = accG[u][j];
-                colB[rr[u] * D + col[u] + j] = accB[u][j];
+                colG[o + j] = accG[u][j];
+                colB[o + j] = accB[u][j];
             }
         }
     }
     __syncthreads();
     float *pg = part + int64_t(blockIdx.x) * 2 * D;
-    for (uint32_t c = tid; c < D; c += kThreads) {
+    for (uint32_t c = threadIdx.x; c < D; c += kThreads) {
         float sg = 0.0f, sb = 0.0f;
-        for (uint32_t r = 0; r < R; ++r) { sg += colG[r * D + c]; sb += colB[r * D + c]; }
+        for (uint32_t r = 0; r < kTeams * R; ++r) { sg += colG[r * D + c]; sb += colB[r * D + c]; }
         pg[c] = sg;
         pg[D + c] = sb;
     }
 }
 
-// dgamma / dbeta = sum over workgroups of their partial column sums; 64 columns per workgroup,
-// four interleaved slices of the workgroup list, combined in a fixed order
-__global__ __launch_bounds__(kThreads) void k_layernorm_finalize(const float *__restrict__ part, int nwg, uint32_t D,
-                                                                 float *__restrict__ dgamma, float *__restrict__ dbeta)
+// dgamma / dbeta = sum over workgroups of their partial column sums.  32 columns per workgroup,
+// 32 interleaved slices of the workgroup list (four loads in flight each), combined in a fixed order.
+__global__ __launch_bounds__(kLnFinThreads) void k_layernorm_finalize(const float *__restrict__ part, int nwg, uint32_t D,
+                                                                      float *__restrict__ dgamma, float *__restrict__ dbeta)
 {
-    __shared__ float sg[4][64], sb[4][64];
-    const uint32_t c = blockIdx.x * 64 + (threadIdx.x & 63u);
-    const uint32_t k = threadIdx.x >> 6;
-    float ag = 0.0f, ab = 0.0f;
-    if (c < D)
-        for (int w = k; w < nwg; w += 4) {
-            ag += part[int64_t(w) * 2 * D + c];
-            ab += part[int64_t(w) * 2 * D + D + c];
+    __shared__ float sg[32][33], sb[32][33];
+    const uint32_t cl = threadIdx.x & 31u, k = threadIdx.x >> 5;
+    const uint32_t c = blockIdx.x * 32 + cl;
+    float ag[4] = {0.0f, 0.0f, 0.0f, 0.0f}, ab[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (c < D) {
+        int w = int(k);
+        for (; w + 96 < nwg; w += 128) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                ag[i] += part[int64_t(w + 32 * i) * 2 * D + c];
+                ab[i] += part[int64_t(w + 32 * i) * 2 * D + D + c];
+            }
         }
-    sg[k][threadIdx.x & 63u] = ag;
-    sb[k][threadIdx.x & 63u] = ab;
+        for (int i = 0; w < nwg; w += 32, ++i) {
+            ag[i] += part[int64_t(w) * 2 * D + c];
+            ab[i] += part[int64_t(w) * 2 * D + D + c];
+        }
+    }
+    sg[k][cl] = (ag[0] + ag[1]) + (ag[2] + ag[3]);
+    sb[k][cl] = (ab[0] + ab[1]) + (ab[2] + ab[3]);
     __syncthreads();
     if (k == 0 && c < D) {
-        const uint32_t i = threadIdx.x;
-        dgamma[c] = ((sg[0][i] + sg[1][i]) + sg[2][i]) + sg[3][i];
-        dbeta[c] = ((sb[0][i] + sb[1][i]) + sb[2][i]) + sb[3][i];
+        float tg = 0.0f, tb = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 32; ++i) { tg += sg[i][cl]; tb += sb[i][cl]; }
+        dgamma[c] = tg;
+        dbeta[c] = tb;
     }
 }
 
-static int ln_plan(int64_t M, int64_t D, int64_t *R_out, int64_t *tiles_out)
+struct LnPlan {
+    bool wave_tiles;
+    int64_t R, tiles;
+    int grid;
+};
+
+static LnPlan ln_plan(int64_t M, int64_t D)
 {
-    int64_t R = int64_t(kLnTileVec) * kVec / D;
-    if (R > M) R = M;
-    if (R < 1) R = 1;
-    int64_t tiles = ceil_div(M, R);
-    *R_out = R;
-    *tiles_out = tiles;
-    return int(tiles < kLnGridCap ? tiles : kLnGridCap);
+    LnPlan p;
+    const int64_t vpr = D / kVec;
+    p.wave_tiles = vpr <= 64 * kLnU;
+    const int64_t cap = (p.wave_tiles ? 64 : kThreads) * int64_t(kLnU);   // vectors per tile
+    p.R = cap / vpr;
+    if (p.R > M) p.R = M;
+    if (p.R < 1) p.R = 1;
+    p.tiles = ceil_div(M, p.R);
+    const int64_t teams = p.wave_tiles ? kThreads / 64 : 1;
+    const int64_t wgs = ceil_div(p.tiles, teams);
+    p.grid = int(wgs < kLnGridCap ? wgs : kLnGridCap);
+    return p;
 }
 
 size_t layernorm_ws_bytes(int64_t M, int64_t D)
 {
-    if (M <= 0 || D <= 0 || D > int64_t(kLnTileVec) * kVec) return 16;
-    int64_t R, tiles;
-    int grid = ln_plan(M, D, &R, &tiles);
-    return size_t(grid) * 2 * size_t(D) * sizeof(float);
+    if (M <= 0 || D <= 0 || D > kLnMaxD || D % kVec != 0) return 16;
+    LnPlan p = ln_plan(M, D);
+    return size_t(p.grid) * 2 * size_t(D) * sizeof(float);
 }
 
 }  // namespace mesa
@@ -205,21 +257,20 @@ extern "C" MESA_EXPORT mesa_status mesa_layernorm_bwd_q(const int8_t *xq, int64_
     if (!aligned16(xq) || !aligned16(dy) || !aligned16(dx) || !aligned16(gamma) || !aligned4(alpha) || !aligned4(beta) ||
         !aligned4(mean) || !aligned4(rstd) || !aligned4(dgamma) || !aligned4(dbeta))
         return MESA_ERR_INVALID_ARG;
-    if (D % kVec != 0 || (D / G) % kVec != 0 || D > int64_t(kLnTileVec) * kVec) return MESA_ERR_UNSUPPORTED;
+    if (D % kVec != 0 || (D / G) % kVec != 0 || D > kLnMaxD) return MESA_ERR_UNSUPPORTED;
     if (!ws || !aligned16(ws) || ws_bytes < layernorm_ws_bytes(M, D)) return MESA_ERR_WORKSPACE;
-    int64_t R, tiles;
-    const int grid = ln_plan(M, D, &R, &tiles);
+    const LnPlan p = ln_plan(M, D);
     FastDiv dvpr = make_fastdiv(uint32_t(D / kVec)), dvpg = make_fastdiv(uint32_t(D / G / kVec));
     hipStream_t s = static_cast<hipStream_t>(stream);
     float *part = static_cast<float *>(ws);
     const float inv_D = 1.0f / float(D);
-    if (dt == MESA_F16)
-        hipLaunchKernelGGL((k_layernorm_bwd<_Float16>), dim3(grid), dim3(kThreads), 0, s, xq, dy, dx, gamma, mean, rstd, alpha,
-                           beta, M, uint32_t(D), uint32_t(R), tiles, uint32_t(G), dvpr, dvpg, inv_D, part);
-    else
-        hipLaunchKernelGGL((k_layernorm_bwd<float>), dim3(grid), dim3(kThreads), 0, s, xq, dy, dx, gamma, mean, rstd, alpha,
-                           beta, M, uint32_t(D), uint32_t(R), tiles, uint32_t(G), dvpr, dvpg, inv_D, part);
-    hipLaunchKernelGGL(k_layernorm_finalize, dim3(int(ceil_div(D, 64))), dim3(kThreads), 0, s, part, grid, uint32_t(D), dgamma,
-                       dbeta);
+#define MESA_LAUNCH_LN(T, TPT_) \
+    hipLaunchKernelGGL((k_layernorm_bwd<T, TPT_>), dim3(p.grid), dim3(kThreads), 0, s, xq, dy, dx, gamma, mean, rstd, alpha, \
+                       beta, M, uint32_t(D), uint32_t(p.R), p.tiles, uint32_t(G), dvpr, dvpg, inv_D, part)
+    if (dt == MESA_F16) { if (p.wave_tiles) MESA_LAUNCH_LN(_Float16, 64); else MESA_LAUNCH_LN(_Float16, kThreads); }
+    else { if (p.wave_tiles) MESA_LAUNCH_LN(float, 64); else MESA_LAUNCH_LN(float, kThreads); }
+#undef MESA_LAUNCH_LN
+    hipLaunchKernelGGL(k_layernorm_finalize, dim3(unsigned(ceil_div(D, 32))), dim3(kLnFinThreads), 0, s, part, p.grid,
+                       uint32_t(D), dgamma, dbeta);
     return launch_status();
 }

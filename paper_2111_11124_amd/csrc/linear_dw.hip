@@ -15,6 +15,8 @@
 // Workgroups are numbered so that those sharing a slice of m run on the same XCD (same L2).
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "api_util.hpp"
 #include "common.hpp"
 
@@ -30,9 +32,13 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kDwBM = 32;        // contraction rows per LDS stage
 constexpr int kDwXcd = 8;
+constexpr int kDwPF = 3;         // stages prefetched into registers ahead of the one being multiplied
 
-template <int BN, int BK> struct DwCfg {
-    static constexpr int WN = BN / 2, WK = BK / 2;      // 2 x 2 waves
+// BN x BK tile of dW per workgroup, WGN x WGK waves, each wave (BN/WGN) x (BK/WGK) as 32x32 MFMA tiles
+template <int BN, int BK, int WGN, int WGK> struct DwCfg {
+    static constexpr int NW = WGN * WGK;
+    static constexpr int THREADS = NW * 64;
+    static constexpr int WN = BN / WGN, WK = BK / WGK;  // wave tile
     static constexpr int TI = WN / 32, TJ = WK / 32;    // MFMA tiles per wave
     static constexpr int PA = BN * 2 + 64;              // LDS row pitch of the dy tile, bytes
     static constexpr int PB = BK + 32;                  // LDS row pitch of the code tile, bytes
@@ -41,34 +47,37 @@ template <int BN, int BK> struct DwCfg {
     static constexpr int STAGE = A_STAGE + B_STAGE;
     static constexpr int A_CPR = BN / 8;                // 16-byte chunks per tile row
     static constexpr int B_CPR = BK / 16;
-    static constexpr int A_CHUNKS = kDwBM * A_CPR / kThreads;
-    static constexpr int B_CHUNKS = kDwBM * B_CPR / kThreads;
-    static_assert(A_CHUNKS >= 1 && B_CHUNKS >= 1, "tile too small for 256 threads");
+    static constexpr int A_TOTAL = kDwBM * A_CPR, B_TOTAL = kDwBM * B_CPR;
+    static constexpr int A_CHUNKS = (A_TOTAL + THREADS - 1) / THREADS;
+    static constexpr int B_CHUNKS = (B_TOTAL + THREADS - 1) / THREADS;
+    static_assert(WN % 64 == 0 && WK % 32 == 0, "wave tile: an even number of 32-row MFMA tiles by whole 32-column tiles");
+    static_assert(2 * STAGE <= 64 * 1024, "two stages must fit the default dynamic LDS limit");
 };
 
-// eight codes (bytes, already +128) -> eight binary16 values: 0x6400|u is 1024+u exactly
+// eight signed codes (bytes) -> eight binary16 values q: 0x6400 | (byte ^ 0x80) is 1152 + q exactly
 __device__ __forceinline__ v8h codes_to_half8(v2i raw)
 {
     v8h out;
-    const h2 k1024 = {(_Float16)1024.0f, (_Float16)1024.0f};
+    const h2 k1152 = {(_Float16)1152.0f, (_Float16)1152.0f};
 #pragma unroll
     for (int w = 0; w < 2; ++w) {
-        uint32_t x = uint32_t(raw[w]) ^ 0x80808080u;
-        uint32_t lo = ((x & 0xFFu) | ((x & 0xFF00u) << 8)) | 0x64006400u;
-        uint32_t hi = (((x >> 16) & 0xFFu) | ((x >> 8) & 0xFF0000u)) | 0x64006400u;
-        h2 a = as_h2(lo) - k1024;
-        h2 b = as_h2(hi) - k1024;
+        const uint32_t x = uint32_t(raw[w]) ^ 0x80808080u;
+        const h2 a = as_h2(__builtin_amdgcn_perm(0x64646464u, x, 0x04010400u)) - k1152;   // bytes 0, 1
+        const h2 b = as_h2(__builtin_amdgcn_perm(0x64646464u, x, 0x04030402u)) - k1152;   // bytes 2, 3
         out[4 * w + 0] = a.x; out[4 * w + 1] = a.y; out[4 * w + 2] = b.x; out[4 * w + 3] = b.y;
     }
     return out;
 }
 
-template <int BN, int BK>
-__global__ __launch_bounds__(kThreads, 1) void k_dw_f16(const int8_t *__restrict__ xq, const _Float16 *__restrict__ dy,
-                                                        int64_t M, int K, int N, int tiles_n, int tiles_k, int splits,
-                                                        int64_t rows_per_split, float *__restrict__ P, float *__restrict__ S0)
+// P[split][n][k] = sum over the slice's m of dy[m][n] * q[m][k]   (q the signed code)
+// S0[split][n]   = sum over the slice's m of dy[m][n]
+template <int BN, int BK, int WGN, int WGK>
+__global__ __launch_bounds__(WGN * WGK * 64, 1) void k_dw_f16(const int8_t *__restrict__ xq, const _Float16 *__restrict__ dy,
+                                                              int64_t M, int K, int N, int tiles_n, int tiles_k, int splits,
+                                                              int64_t rows_per_split, float *__restrict__ P,
+                                                              float *__restrict__ S0)
 {
-    using C = DwCfg<BN, BK>;
+    using C = DwCfg<BN, BK, WGN, WGK>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -84,7 +93,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_dw_f16(const int8_t *__restrict
     const int64_t m_end = (m_begin + rows_per_split < M) ? m_begin + rows_per_split : M;
     const int nstages = (m_end > m_begin) ? int((m_end - m_begin + kDwBM - 1) / kDwBM) : 0;
 
-    const int wn = wave >> 1, wk = wave & 1;
+    const int wn = wave / WGK, wk = wave % WGK;
     const int blk = lane >> 4, sl = lane & 15;
     // byte offsets of this lane's transpose-read addresses inside a stage
     const int a_off = ((blk >> 1) * 8 + (sl >> 2)) * C::PA + (wn * C::WN + (blk & 1) * 16 + (sl & 3) * 4) * 2;
@@ -100,92 +109,207 @@ __global__ __launch_bounds__(kThreads, 1) void k_dw_f16(const int8_t *__restrict
     float s0[C::TI];
 #pragma unroll
     for (int i = 0; i < C::TI; ++i) s0[i] = 0.0f;
-    const bool do_s0 = (tk == 0) && (wk == 0);
+    const bool do_s0 = (tk == 0) && (wk == 0);   // the waves whose row sums are written out
 
-    u32x4 ra[C::A_CHUNKS], rb[C::B_CHUNKS];
+    // global -> register prefetch ring: stage s+1 .. s+kDwPF are in flight while stage s is multiplied,
+    // enough bytes per CU to cover the latency of L2 / memory-side-cache hits at the rate MFMA consumes them.
+    // Every load is unconditional from a clamped, always valid address; what lies outside the tile or
+    // past the end of the slice is zeroed by a select, so the steady-state loop has no branches.
+    u32x4 ring_a[kDwPF][C::A_CHUNKS], ring_b[kDwPF][C::B_CHUNKS];
+    const _Float16 *pa[C::A_CHUNKS];
+    const int8_t *pb[C::B_CHUNKS];
+    int row_a[C::A_CHUNKS], row_b[C::B_CHUNKS], lds_a[C::A_CHUNKS], lds_b[C::B_CHUNKS];
+    bool ok_a[C::A_CHUNKS], ok_b[C::B_CHUNKS];
+#pragma unroll
+    for (int i = 0; i < C::A_CHUNKS; ++i) {
+        const int c = i * C::THREADS + tid;
+        const int row = (c / C::A_CPR) % kDwBM, cc = c % C::A_CPR;
+        const int n = n0 + cc * 8;
+        ok_a[i] = c < C::A_TOTAL && n < N;
+        row_a[i] = row;
+        pa[i] = dy + (ok_a[i] ? n : 0);
+        lds_a[i] = row * C::PA + cc * 16;
+    }
+#pragma unroll
+    for (int i = 0; i < C::B_CHUNKS; ++i) {
+        const int c = i * C::THREADS + tid;
+        const int row = (c / C::B_CPR) % kDwBM, cc = c % C::B_CPR;
+        const int kk = kk0 + cc * 16;
+        ok_b[i] = c < C::B_TOTAL && kk < K;
+        row_b[i] = row;
+        pb[i] = xq + (ok_b[i] ? kk : 0);
+        lds_b[i] = C::A_STAGE + row * C::PB + cc * 16;
+    }
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    const int64_t m_last = (m_end > m_begin) ? m_end - 1 : 0;
 
-    auto load_stage = [&](int64_t m_stage) {
+    // EDGE = false: every row of the stage lies inside the slice (no row clamping, no row select).
+    // The zeroing select is applied when the registers are written to LDS, not at the load, so that
+    // nothing waits on a load before its stage is due.
+    auto load_stage = [&](int64_t m_stage, u32x4 *ra, u32x4 *rb, auto edge) {
+        constexpr bool EDGE = decltype(edge)::value;
 #pragma unroll
         for (int i = 0; i < C::A_CHUNKS; ++i) {
-            const int c = i * kThreads + tid;
-            const int row = c / C::A_CPR, cc = c - row * C::A_CPR;
-            const int64_t m = m_stage + row;
-            const int n = n0 + cc * 8;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (m < m_end && n < N) v = *reinterpret_cast<const u32x4 *>(dy + m * N + n);
-            ra[i] = v;
+            int64_t m = m_stage + row_a[i];
+            if (EDGE) m = m < m_end ? m : m_last;
+            ra[i] = *reinterpret_cast<const u32x4 *>(pa[i] + m * N);
         }
 #pragma unroll
         for (int i = 0; i < C::B_CHUNKS; ++i) {
-            const int c = i * kThreads + tid;
-            const int row = c / C::B_CPR, cc = c - row * C::B_CPR;
-            const int64_t m = m_stage + row;
-            const int kk = kk0 + cc * 16;
-            u32x4 v = {0x80808080u, 0x80808080u, 0x80808080u, 0x80808080u};   // code -128 <-> value 0
-            if (m < m_end && kk < K) v = *reinterpret_cast<const u32x4 *>(xq + m * K + kk);
-            rb[i] = v;
+            int64_t m = m_stage + row_b[i];
+            if (EDGE) m = m < m_end ? m : m_last;
+            rb[i] = *reinterpret_cast<const u32x4 *>(pb[i] + m * K);
         }
     };
-    auto store_stage = [&](unsigned char *st) {
+    auto store_stage = [&](unsigned char *st, int64_t m_stage, const u32x4 *ra, const u32x4 *rb, auto edge) {
+        constexpr bool EDGE = decltype(edge)::value;
 #pragma unroll
-        for (int i = 0; i < C::A_CHUNKS; ++i) {
-            const int c = i * kThreads + tid;
-            const int row = c / C::A_CPR, cc = c - row * C::A_CPR;
-            *reinterpret_cast<u32x4 *>(st + row * C::PA + cc * 16) = ra[i];
-        }
+        for (int i = 0; i < C::A_CHUNKS; ++i)
+            if (C::A_TOTAL % C::THREADS == 0 || i * C::THREADS + tid < C::A_TOTAL) {
+                const bool ok = ok_a[i] && (!EDGE || m_stage + row_a[i] < m_end);
+                *reinterpret_cast<u32x4 *>(st + lds_a[i]) = ok ? ra[i] : zero4;
+            }
 #pragma unroll
-        for (int i = 0; i < C::B_CHUNKS; ++i) {
-            const int c = i * kThreads + tid;
-            const int row = c / C::B_CPR, cc = c - row * C::B_CPR;
-            *reinterpret_cast<u32x4 *>(st + C::A_STAGE + row * C::PB + cc * 16) = rb[i];
+        for (int i = 0; i < C::B_CHUNKS; ++i)
+            if (C::B_TOTAL % C::THREADS == 0 || i * C::THREADS + tid < C::B_TOTAL) {
+                const bool ok = ok_b[i] && (!EDGE || m_stage + row_b[i] < m_end);
+                *reinterpret_cast<u32x4 *>(st + lds_b[i]) = ok ? rb[i] : zero4;
+            }
+    };
+    const std::true_type edge_yes;
+    const std::false_type edge_no;
+
+    // ---- software pipeline -------------------------------------------------------------------
+    // A stage holds two contraction steps of 16 rows.  While the MFMAs of one step run, the wave
+    // reads (and converts) the fragments of the next step, so LDS latency and the int8 -> binary16
+    // conversion sit in the shadow of the matrix cores; the workgroup barrier falls between the two
+    // MFMA batches of a stage, after this wave's last LDS read of the stage and its LDS writes of the
+    // next one.  The sched_group_barrier calls spell the interleaving out for the scheduler.
+    auto read_a = [&](const unsigned char *st, int ks, v8h af[C::TI]) {
+#pragma unroll
+        for (int i = 0; i < C::TI; ++i) {
+            const unsigned char *p = st + a_off + ks * 16 * C::PA + i * 64;
+            v4h lo = __builtin_bit_cast(v4h, __builtin_amdgcn_ds_read_tr16_b64_v4i16(MESA_LDS3(v4s, p)));
+            v4h hi = __builtin_bit_cast(v4h, __builtin_amdgcn_ds_read_tr16_b64_v4i16(MESA_LDS3(v4s, p + 4 * C::PA)));
+            af[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         }
     };
+    auto read_b = [&](const unsigned char *st, int ks, v2i braw[C::TJ]) {
+#pragma unroll
+        for (int j = 0; j < C::TJ; ++j)
+            braw[j] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(MESA_LDS3(v2i, st + b_off + ks * 16 * C::PB + j * 32));
+    };
+    // One contraction step on the matrix cores, in two halves.  First half: the row sums of the dy
+    // fragments (every wave keeps them -- 16 dot instructions hidden under the MFMAs -- and only the
+    // owners write them out) and the MFMAs of the upper fragment rows.  Second half: the remaining
+    // MFMAs, with the conversion of the NEXT step's code fragments in their shadow; by then the LDS
+    // reads issued before the first half have long returned, so the in-order instruction stream
+    // never waits on them while the matrix core idles.
+    auto mfma_half = [&](const v8h af[C::TI], const v8h bf[C::TJ], int half) {
+#pragma unroll
+        for (int i = half * (C::TI / 2); i < (half + 1) * (C::TI / 2); ++i)
+#pragma unroll
+            for (int j = 0; j < C::TJ; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[j], acc[i][j], 0, 0, 0);
+    };
+    auto row_sums = [&](const v8h af[C::TI]) {
+        const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
+#pragma unroll
+        for (int i = 0; i < C::TI; ++i)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                h2 pr = {af[i][2 * k], af[i][2 * k + 1]};
+                s0[i] = __builtin_amdgcn_fdot2(pr, ones, s0[i], false);
+            }
+    };
+    constexpr int kHalfMfma = (C::TI / 2) * C::TJ;
+    auto pace = [&](auto valu_per_mfma) {   // one MFMA, then a few VALU instructions, repeated
+#pragma unroll
+        for (int r = 0; r < kHalfMfma; ++r) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, decltype(valu_per_mfma)::value, 0);
+        }
+    };
+    const std::integral_constant<int, 2> few;
+    const std::integral_constant<int, 5> many;
 
     if (nstages > 0) {
-        load_stage(m_begin);
-        store_stage(smem);
+        load_stage(m_begin, ring_a[0], ring_b[0], edge_yes);
+        store_stage(smem, m_begin, ring_a[0], ring_b[0], edge_yes);
     }
+#pragma unroll
+    for (int d = 0; d < kDwPF; ++d)
+        if (d + 1 < nstages) load_stage(m_begin + int64_t(d + 1) * kDwBM, ring_a[d], ring_b[d], edge_yes);
     __syncthreads();
 
-    for (int s = 0; s < nstages; ++s) {
+    v8h af0[C::TI], af1[C::TI], bf0[C::TJ], bf1[C::TJ];
+    v2i braw[C::TJ];
+    if (nstages > 0) {
+        read_a(smem, 0, af0);
+        read_b(smem, 0, braw);
+#pragma unroll
+        for (int j = 0; j < C::TJ; ++j) bf0[j] = codes_to_half8(braw[j]);
+    }
+
+    // One stage.  STEADY: stage s+1+kDwPF exists and lies wholly inside the slice, so nothing here
+    // is conditional.  Otherwise the same steps with their guards (the last kDwPF+1 stages).
+    auto stage = [&](int s, u32x4 *ra, u32x4 *rb, auto steady) {
+        constexpr bool STEADY = decltype(steady)::value;
         unsigned char *cur = smem + (s & 1) * C::STAGE;
         unsigned char *nxt = smem + ((s + 1) & 1) * C::STAGE;
-        const bool more = s + 1 < nstages;
-        if (more) load_stage(m_begin + int64_t(s + 1) * kDwBM);
-
+        const bool more = STEADY || s + 1 < nstages;
+        // step 0 of stage s on the matrix cores; step 1's fragments on their way
+        read_a(cur, 1, af1);
+        read_b(cur, 1, braw);
+        row_sums(af0);
+        mfma_half(af0, bf0, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, C::TI * 2 + C::TJ, 0);
+        pace(few);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_half(af0, bf0, 1);
 #pragma unroll
-        for (int ks = 0; ks < kDwBM / 16; ++ks) {
-            v8h af[C::TI], bf[C::TJ];
-#pragma unroll
-            for (int i = 0; i < C::TI; ++i) {
-                const unsigned char *p = cur + a_off + ks * 16 * C::PA + i * 64;
-                v4h lo = __builtin_bit_cast(v4h, __builtin_amdgcn_ds_read_tr16_b64_v4i16(MESA_LDS3(v4s, p)));
-                v4h hi = __builtin_bit_cast(v4h, __builtin_amdgcn_ds_read_tr16_b64_v4i16(MESA_LDS3(v4s, p + 4 * C::PA)));
-                af[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            }
-#pragma unroll
-            for (int j = 0; j < C::TJ; ++j) {
-                const unsigned char *p = cur + b_off + ks * 16 * C::PB + j * 32;
-                bf[j] = codes_to_half8(__builtin_amdgcn_ds_read_tr8_b64_v2i32(MESA_LDS3(v2i, p)));
-            }
-            if (do_s0) {
-                const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
-#pragma unroll
-                for (int i = 0; i < C::TI; ++i)
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        h2 pr = {af[i][2 * k], af[i][2 * k + 1]};
-                        s0[i] = __builtin_amdgcn_fdot2(pr, ones, s0[i], false);
-                    }
-            }
-#pragma unroll
-            for (int i = 0; i < C::TI; ++i)
-#pragma unroll
-                for (int j = 0; j < C::TJ; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[j], acc[i][j], 0, 0, 0);
-        }
-        if (more) store_stage(nxt);
+        for (int j = 0; j < C::TJ; ++j) bf1[j] = codes_to_half8(braw[j]);
+        pace(many);
+        __builtin_amdgcn_sched_barrier(0);
+        if (STEADY) store_stage(nxt, m_begin + int64_t(s + 1) * kDwBM, ra, rb, edge_no);
+        else if (more) store_stage(nxt, m_begin + int64_t(s + 1) * kDwBM, ra, rb, edge_yes);
+        if (STEADY) load_stage(m_begin + int64_t(s + 1 + kDwPF) * kDwBM, ra, rb, edge_no);
+        else if (s + 1 + kDwPF < nstages) load_stage(m_begin + int64_t(s + 1 + kDwPF) * kDwBM, ra, rb, edge_yes);
         __syncthreads();
+        // step 1 of stage s; step 0 of stage s+1 on its way
+        if (more) {
+            read_a(nxt, 0, af0);
+            read_b(nxt, 0, braw);
+        }
+        row_sums(af1);
+        mfma_half(af1, bf1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, C::TI * 2 + C::TJ, 0);
+        pace(few);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_half(af1, bf1, 1);
+        if (more) {
+#pragma unroll
+            for (int j = 0; j < C::TJ; ++j) bf0[j] = codes_to_half8(braw[j]);
+        }
+        pace(many);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // The stage loop is unrolled by the ring length so that every ring slot is a fixed set of
+    // registers: stage s+1 sits in slot s % kDwPF, goes to LDS after the first step of stage s, and
+    // the slot is refilled at once with stage s+1+kDwPF.
+    // steady while (s + 1 + kDwPF) * 32 + 32 <= rows of the slice
+    const int full_stages = int((m_end - m_begin) / kDwBM);            // stages with all 32 rows inside
+    const int steady_end = full_stages - 1 - kDwPF > 0 ? ((full_stages - 1 - kDwPF) / kDwPF) * kDwPF : 0;
+    int sbase = 0;
+    for (; sbase < steady_end; sbase += kDwPF) {
+#pragma unroll
+        for (int d = 0; d < kDwPF; ++d) stage(sbase + d, ring_a[d], ring_b[d], edge_yes /* steady */);
+    }
+    for (; sbase < nstages; sbase += kDwPF) {
+#pragma unroll
+        for (int d = 0; d < kDwPF; ++d)
+            if (sbase + d < nstages) stage(sbase + d, ring_a[d], ring_b[d], edge_no /* guarded */);
     }
 
     // partial sums of this slice: lane l, register v of a 32x32 tile -> row 8*(v/4) + 4*(l/32) + v%4, column l%32
@@ -248,7 +372,7 @@ __global__ __launch_bounds__(kThreads) void k_dw_f32(const int8_t *__restrict__ 
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int kk = kkb + 32 * j;
-            const float b = (mv && kk < K) ? code_to_float(xq[m * K + kk]) : 0.0f;
+            const float b = (mv && kk < K) ? float(int(xq[m * K + kk])) : 0.0f;
             acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[j], 0, 0, 0);
         }
     }
@@ -269,7 +393,8 @@ __global__ __launch_bounds__(kThreads) void k_dw_f32(const int8_t *__restrict__ 
     }
 }
 
-// dW = s_g(k) * sum_slices S1 + beta_g(k) * sum_slices S0; db = sum_slices S0.  Four columns per thread.
+// With q the signed code, x_hat = s_g*q + (beta_g + 128 s_g), so
+// dW = s_g(k) * sum_slices P + (beta_g(k) + 128 s_g(k)) * sum_slices S0;  db = sum_slices S0.  Four columns per thread.
 __global__ __launch_bounds__(kThreads) void k_dw_reduce(const float *__restrict__ P, const float *__restrict__ S0, int splits,
                                                         int N, int K, FastDiv div_k4, FastDiv div_per,
                                                         const float *__restrict__ alpha, const float *__restrict__ beta,
@@ -291,13 +416,15 @@ __global__ __launch_bounds__(kThreads) void k_dw_reduce(const float *__restrict_
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const uint32_t g = fastdiv(kk + j, div_per);
-        o[j] = fmaf(alpha[g] / 255.0f, o[j], beta[g] * s0);
+        const float sg = alpha[g] / 255.0f;
+        o[j] = fmaf(sg, o[j], fmaf(128.0f, sg, beta[g]) * s0);
     }
     *reinterpret_cast<float4 *>(dW + int64_t(n) * K + kk) = make_float4(o[0], o[1], o[2], o[3]);
     if (db && kk == 0) db[n] = s0;
 }
 
 struct DwPlan {
+    int variant;   // 0: 256x256 tile, 8 waves; 1: 256x128 tile, 4 waves; 2: binary32
     int bn, bk, tiles_n, tiles_k, splits, grid;
     int64_t rows_per_split;
 };
@@ -306,9 +433,11 @@ static DwPlan dw_plan(int64_t M, int64_t K, int64_t N, mesa_dtype dt)
 {
     DwPlan p;
     if (dt == MESA_F16) {
+        p.variant = (K % 256 == 0 || K > 1024) ? 0 : 1;
         p.bn = 256;
-        p.bk = (K % 256 == 0 || K > 1024) ? 256 : 128;
+        p.bk = p.variant == 0 ? 256 : 128;
     } else {
+        p.variant = 2;
         p.bn = kDw32BN;
         p.bk = kDw32BK;
     }
@@ -363,17 +492,13 @@ extern "C" MESA_EXPORT mesa_status mesa_linear_dw_q(const int8_t *xq, int64_t M,
     const int Ki = int(K), Ni = int(N_out);
     if (dt == MESA_F16) {
         const _Float16 *dyh = static_cast<const _Float16 *>(dy);
-        if (p.bk == 256) {
-            using C = DwCfg<256, 256>;
-            hipFuncSetAttribute(reinterpret_cast<const void *>(&k_dw_f16<256, 256>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                2 * C::STAGE);
-            hipLaunchKernelGGL((k_dw_f16<256, 256>), dim3(p.grid), dim3(kThreads), 2 * C::STAGE, s, xq, dyh, M, Ki, Ni,
+        if (p.variant == 0) {
+            using C = DwCfg<256, 256, 2, 2>;
+            hipLaunchKernelGGL((k_dw_f16<256, 256, 2, 2>), dim3(p.grid), dim3(C::THREADS), 2 * C::STAGE, s, xq, dyh, M, Ki, Ni,
                                p.tiles_n, p.tiles_k, p.splits, p.rows_per_split, P, S0);
         } else {
-            using C = DwCfg<256, 128>;
-            hipFuncSetAttribute(reinterpret_cast<const void *>(&k_dw_f16<256, 128>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                2 * C::STAGE);
-            hipLaunchKernelGGL((k_dw_f16<256, 128>), dim3(p.grid), dim3(kThreads), 2 * C::STAGE, s, xq, dyh, M, Ki, Ni,
+            using C = DwCfg<256, 128, 2, 2>;
+            hipLaunchKernelGGL((k_dw_f16<256, 128, 2, 2>), dim3(p.grid), dim3(C::THREADS), 2 * C::STAGE, s, xq, dyh, M, Ki, Ni,
                                p.tiles_n, p.tiles_k, p.splits, p.rows_per_split, P, S0);
         }
     } else {
