@@ -23,15 +23,20 @@
 
 namespace mesa {
 
-constexpr int kU = 4;                            // vectors per thread and iteration
-constexpr int kChunk = kThreads * kU * kVec;     // 8192 elements: what a workgroup moves per iteration
-constexpr int kGridCap = 2048;                   // 8 workgroups of 4 waves on each of the 256 CUs
+// Launch shape, found by sweeping on the MI355X: the read-modify-write streams do best with two
+// vectors in flight per thread and many workgroups (more waves to hide the integer multiplies of
+// the random generator); the read-only min/max scan with four vectors and fewer workgroups.
+constexpr int kU = 2;                            // vectors per thread and iteration
+constexpr int kGridCap = 4096;                   // 16 workgroups of 4 waves per CU, two rounds of 8
+constexpr int kMmU = 4;                          // the same two numbers for the min/max scan
+constexpr int kMmGridCap = 1024;
 constexpr int kLutMaxGroups = 64;                // GELU-gradient table: groups * 256 floats in LDS
 
 // The cursors of a thread's U vectors: vector u of the chunk that starts at `base` covers
 // elements base + (u*256 + tid)*8 ... + 7.
 template <int U> __device__ __forceinline__ void place_cursors(Cursor c[U], const GroupGeom &gg, int64_t numel)
 {
+    constexpr int kChunk = kThreads * U * kVec;   // what a workgroup moves per iteration
     const int64_t e0 = int64_t(blockIdx.x) * kChunk + int64_t(threadIdx.x) * kVec;
     if (numel < (int64_t(1) << 31)) {   // uniform branch: two multiplies instead of binary64 divisions
         Cursor z;
@@ -153,7 +158,30 @@ __device__ __attribute__((noinline)) MinMaxState<T> minmax_elements(const void *
     return st;
 }
 
-// partial extrema of each workgroup: part[wg][0..G) = min, part[wg][G..2G) = max
+// Eq. (6)-(7) for one group from its extrema: each product, difference and sum rounded on its own.
+__device__ __forceinline__ void ema_update(float mn, float mx, float *alpha, float *beta, uint32_t g, float lambda,
+                                           int first_call)
+{
+    mn = mn + 0.0f;  // -0.0 -> +0.0
+    mx = mx + 0.0f;
+    float range = mx - mn;
+    if (first_call) {
+        alpha[g] = range;
+        beta[g] = mn;
+    } else {
+        float a = lambda * alpha[g];
+        float b = 1.0f - lambda;
+        float c = b * range;
+        alpha[g] = a + c;
+        float e = lambda * beta[g];
+        float f = b * mn;
+        beta[g] = e + f;
+    }
+}
+
+// Partial extrema of each workgroup: part[wg][0..G) = min, part[wg][G..2G) = max.  (Letting the last
+// workgroup to finish do the final step in the same launch was tried and dropped: the device-scope
+// fence it needs flushes the per-XCD L2 once per workgroup, which costs far more than a second launch.)
 template <typename T, int U>
 __global__ __launch_bounds__(kThreads) void k_minmax_partial(const void *__restrict__ x, int64_t numel, GroupGeom gg,
                                                              float *__restrict__ part)
@@ -173,6 +201,7 @@ __global__ __launch_bounds__(kThreads) void k_minmax_partial(const void *__restr
 #pragma unroll
     for (int u = 0; u < U; ++u) { st[u].cur = c[u].g; st[u].acc.init(); }
 
+    constexpr int kChunk = kThreads * U * kVec;
     const int64_t stride = int64_t(gridDim.x) * kChunk;
     const int64_t toff = int64_t(threadIdx.x) * kVec;
     int64_t base = int64_t(blockIdx.x) * kChunk;
@@ -244,34 +273,20 @@ __global__ __launch_bounds__(kThreads) void k_ema_finalize(const float *__restri
     const uint32_t g = blockIdx.x;
     float mn = __builtin_inff(), mx = -__builtin_inff();
     for (int w = threadIdx.x; w < nwg; w += kThreads) {
-        mn = fminf(mn, part[int64_t(w) * 2 * groups + g]);
-        mx = fmaxf(mx, part[int64_t(w) * 2 * groups + groups + g]);
+        mn = vmin(mn, part[int64_t(w) * 2 * groups + g]);
+        mx = vmax(mx, part[int64_t(w) * 2 * groups + groups + g]);
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
-        mn = fminf(mn, __shfl_xor(mn, off, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+        mn = vmin(mn, __shfl_xor(mn, off, 64));
+        mx = vmax(mx, __shfl_xor(mx, off, 64));
     }
     if ((threadIdx.x & 63) == 0) { smn[threadIdx.x >> 6] = mn; smx[threadIdx.x >> 6] = mx; }
     __syncthreads();
     if (threadIdx.x == 0) {
 #pragma unroll
-        for (int w = 1; w < kThreads / 64; ++w) { mn = fminf(mn, smn[w]); mx = fmaxf(mx, smx[w]); }
-        mn = mn + 0.0f;  // -0.0 -> +0.0
-        mx = mx + 0.0f;
-        float range = mx - mn;
-        if (first_call) {
-            alpha[g] = range;
-            beta[g] = mn;
-        } else {
-            float a = lambda * alpha[g];
-            float b = 1.0f - lambda;
-            float c = b * range;
-            alpha[g] = a + c;
-            float e = lambda * beta[g];
-            float f = b * mn;
-            beta[g] = e + f;
-        }
+        for (int w = 1; w < kThreads / 64; ++w) { mn = vmin(mn, smn[w]); mx = vmax(mx, smx[w]); }
+        ema_update(mn, mx, alpha, beta, g, lambda, first_call);
     }
 }
 
@@ -359,6 +374,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize(const void *__restrict__ 
 
     Cursor c[U];
     place_cursors<U>(c, gg, numel);
+    constexpr int kChunk = kThreads * U * kVec;
     const int64_t stride = int64_t(gridDim.x) * kChunk;
     const int64_t toff = int64_t(threadIdx.x) * kVec;
     int64_t base = int64_t(blockIdx.x) * kChunk;
@@ -426,6 +442,7 @@ __global__ __launch_bounds__(kThreads) void k_dequantize(const int8_t *__restric
 
     Cursor c[U];
     place_cursors<U>(c, gg, numel);
+    constexpr int kChunk = kThreads * U * kVec;
     const int64_t stride = int64_t(gridDim.x) * kChunk;
     const int64_t toff = int64_t(threadIdx.x) * kVec;
     int64_t base = int64_t(blockIdx.x) * kChunk;
@@ -524,6 +541,7 @@ __global__ __launch_bounds__(kThreads) void k_gelu_bwd(const int8_t *__restrict_
 
     Cursor c[U];
     place_cursors<U>(c, gg, numel);
+    constexpr int kChunk = kThreads * U * kVec;
     const int64_t stride = int64_t(gridDim.x) * kChunk;
     const int64_t toff = int64_t(threadIdx.x) * kVec;
     int64_t base = int64_t(blockIdx.x) * kChunk;
@@ -601,19 +619,19 @@ using namespace mesa;
 
 static int stream_grid(int64_t numel, int64_t row)
 {
-    return plan_grid(numel, kChunk, kGridCap, row);
+    return plan_grid(numel, int64_t(kThreads) * kU * kVec, kGridCap, row);
 }
 
 static int minmax_grid(const mesa_layout &L)
 {
     int64_t numel = layout_numel(L);
     // many groups: every workgroup writes 2*groups partial values, so keep their number down
-    int cap = kGridCap;
+    int cap = kMmGridCap;
     if (L.groups > 64) {
-        cap = int(int64_t(kGridCap) * 64 / L.groups);
+        cap = int(int64_t(kMmGridCap) * 64 / L.groups);
         if (cap < 32) cap = 32;
     }
-    return plan_grid(numel, kChunk, cap, L.groups > 1 ? L.groups * L.inner : 0);
+    return plan_grid(numel, int64_t(kThreads) * kMmU * kVec, cap, L.groups > 1 ? L.groups * L.inner : 0);
 }
 
 extern "C" MESA_EXPORT mesa_status mesa_update_running_params(const void *x, mesa_dtype dt, mesa_layout L, float *alpha, float *beta,
@@ -630,13 +648,13 @@ extern "C" MESA_EXPORT mesa_status mesa_update_running_params(const void *x, mes
         return MESA_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int grid = minmax_grid(L);
-    GroupGeom gg = make_geom(L.groups, L.inner, int64_t(grid) * kChunk);
+    GroupGeom gg = make_geom(L.groups, L.inner, int64_t(grid) * kThreads * kMmU * kVec);
     const size_t lds = size_t(2) * gg.groups * sizeof(int);
     float *part = static_cast<float *>(ws);
     if (dt == MESA_F16)
-        hipLaunchKernelGGL((k_minmax_partial<_Float16, kU>), dim3(grid), dim3(kThreads), lds, s, x, numel, gg, part);
+        hipLaunchKernelGGL((k_minmax_partial<_Float16, kMmU>), dim3(grid), dim3(kThreads), lds, s, x, numel, gg, part);
     else
-        hipLaunchKernelGGL((k_minmax_partial<float, kU>), dim3(grid), dim3(kThreads), lds, s, x, numel, gg, part);
+        hipLaunchKernelGGL((k_minmax_partial<float, kMmU>), dim3(grid), dim3(kThreads), lds, s, x, numel, gg, part);
     hipLaunchKernelGGL(k_ema_finalize, dim3(gg.groups), dim3(kThreads), 0, s, part, grid, gg.groups, alpha, beta, lambda,
                        first_call);
     return launch_status();
@@ -655,7 +673,7 @@ extern "C" MESA_EXPORT mesa_status mesa_quantize_headwise(const void *x, mesa_dt
         return MESA_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int grid = stream_grid(numel, L.groups > 1 ? L.groups * L.inner : 0);
-    GroupGeom gg = make_geom(L.groups, L.inner, int64_t(grid) * kChunk);
+    GroupGeom gg = make_geom(L.groups, L.inner, int64_t(grid) * kThreads * kU * kVec);
     const size_t lds = size_t(gg.groups) * sizeof(float2);
     const bool sr = mode == MESA_ROUND_STOCHASTIC;
 #define MESA_LAUNCH_Q(T, SRF) \
@@ -678,7 +696,7 @@ extern "C" MESA_EXPORT mesa_status mesa_dequantize(const int8_t *q, mesa_layout 
         return MESA_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int grid = stream_grid(numel, L.groups > 1 ? L.groups * L.inner : 0);
-    GroupGeom gg = make_geom(L.groups, L.inner, int64_t(grid) * kChunk);
+    GroupGeom gg = make_geom(L.groups, L.inner, int64_t(grid) * kThreads * kU * kVec);
     const size_t lds = size_t(gg.groups) * sizeof(float2);
     if (dt == MESA_F16)
         hipLaunchKernelGGL((k_dequantize<_Float16, kU>), dim3(grid), dim3(kThreads), lds, s, q, x_hat, numel, gg, alpha, beta);
@@ -700,7 +718,7 @@ extern "C" MESA_EXPORT mesa_status mesa_gelu_bwd_q(const int8_t *xq, mesa_layout
         return MESA_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int grid = stream_grid(numel, L.groups > 1 ? L.groups * L.inner : 0);
-    GroupGeom gg = make_geom(L.groups, L.inner, int64_t(grid) * kChunk);
+    GroupGeom gg = make_geom(L.groups, L.inner, int64_t(grid) * kThreads * kU * kVec);
     const bool lut = gg.groups <= uint32_t(kLutMaxGroups);
     const size_t lds = lut ? size_t(gg.groups) * 256 * sizeof(float) : size_t(gg.groups) * sizeof(float2);
 #define MESA_LAUNCH_G(T, L_) \
