@@ -29,6 +29,9 @@ sys.path.insert(0, ROOT)
 
 import mesa_workloads as W  # noqa: E402
 
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the plain copy kernel's reading
+# (profiles/bench_step_deit_s_b128_hbm_traffic.txt); algorithmic bytes are in algorithmic_bytes() below
+MEASURED_TRAFFIC_BYTES = {"gelu_bwd_q": 193.7e6, "softmax_bwd_q": 153.4e6}
 HBM_PEAK_GBS = 8000.0
 MFMA_F16_PEAK_TFLOPS = 2500.0
 NSETS = 3
@@ -238,6 +241,20 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     dom_ms = sum(e0.elapsed_ms(e1) for e0, e1 in events) / len(events)
 
+    # untimed: the plain copy kernel on 256 MiB (x2 buffers, rotated), the known-traffic reference that
+    # the bandwidth counters are scaled against and the measured ceiling quoted next to the nominal peak
+    n_copy = 256 << 20
+    src = [torch.empty(n_copy, dtype=torch.uint8, device="cuda") for _ in range(3)]
+    dst = [torch.empty(n_copy, dtype=torch.uint8, device="cuda") for _ in range(3)]
+    cps = []
+    for i in range(8):
+        e0, e1 = m.Event(), m.Event()
+        e0.record(); m.mesa_stream_copy(src[i % 3], dst[i % 3], n_copy); e1.record()
+        cps.append((e0, e1))
+    torch.cuda.synchronize()
+    copy_ms = sorted(e0.elapsed_ms(e1) for e0, e1 in cps[2:])[len(cps[2:]) // 2]
+    del src, dst
+
     value = total_bytes / (ms_per_step * 1e-3) / 1e9
     achieved = bytes_per[dominant] / (dom_ms * 1e-3) / 1e9
     out = {
@@ -252,11 +269,14 @@ def main():
                        / (ms_per_step * 1e-3), 1)},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": args.traffic,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": args.traffic if args.traffic is not None else MEASURED_TRAFFIC_BYTES.get(dominant),
                      "avg_launch_ms": round(dom_ms, 5), "algorithmic_bytes": bytes_per[dominant]},
         "dw": {"tflops": round(dw_flops / (per_kernel_ms["linear_dw_q"] * 1e-3) / 1e12, 1),
                "mfma_frac": round(dw_flops / (per_kernel_ms["linear_dw_q"] * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4),
                "ms": round(per_kernel_ms["linear_dw_q"], 5), "shape": [spec.tokens, K, N]},
+        "copy_probe": {"bytes": 2 * n_copy, "ms": round(copy_ms, 5), "GBps": round(2 * n_copy / (copy_ms * 1e-3) / 1e9, 1),
+                       "note": "mesa_stream_copy, 256 MiB read + 256 MiB written: the bandwidth a plain copy reaches on this GPU"},
         "per_call": {k: {"ms": round(v, 5), "GBps": round(bytes_per[k] / (v * 1e-3) / 1e9, 1),
                          "frac_hbm": round(bytes_per[k] / (v * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)} for k, v in per_kernel_ms.items()},
     }

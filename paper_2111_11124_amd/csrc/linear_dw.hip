@@ -1,15 +1,17 @@
 // linear_dw.hip -- Linear weight gradient at the de-quantized input (Sec. 3.1 Eq. 2 for y = x W^T):
-//   dW[n,k] = sum_m dy[m,n]*x_hat[m,k],  x_hat[m,k] = (q[m,k]+128)*s_g(k) + beta_g(k)
+//   dW[n,k] = sum_m dy[m,n]*x_hat[m,k],  x_hat[m,k] = (q[m,k]+128)*s_g(k) + beta_g(k)   (Sec. 3.2 Eq. 5)
 // evaluated in the factored form
-//   dW[n,k] = s_g(k) * S1[n,k] + beta_g(k) * S0[n],   S1 = dy^T (q+128),  S0[n] = sum_m dy[m,n]
-// so that the matrix cores contract dy with the 8-bit codes themselves (0..255 is exact in
-// binary16) and the per-column affine map is applied once to the finished sums.
+//   dW[n,k] = s_g(k) * P[n,k] + (beta_g(k) + 128 s_g(k)) * S0[n],   P = dy^T q,  S0[n] = sum_m dy[m,n]
+// so that the matrix cores contract dy with the signed 8-bit codes themselves (exact in binary16,
+// and centred, so P does not cancel against S0) and the per-column affine map is applied once to
+// the finished sums.
 //
 // binary16 path, gfx950.  Both operands are row-major in the contraction index m, which is the
 // layout the MFMA operands do NOT want (a lane holds 8 consecutive contraction values of one
 // row).  gfx950's LDS transpose reads solve exactly this: the dy and code tiles are copied to
 // LDS as they lie in memory, and ds_read_b64_tr_b16 / ds_read_b64_tr_b8 deliver, per lane, the
-// column of four binary16 / eight int8 values it needs.  A workgroup of four waves owns a
+// column of four binary16 / eight int8 values it needs (within 16 lanes, lanes 4k..4k+3 -- resp.
+// 2k, 2k+1 -- supply row k and lane i receives column i).  A workgroup of four waves owns a
 // BN x BK tile of dW (each wave a quarter, as 32x32x16 MFMA tiles) for one slice of m; slices
 // are combined in a fixed order by a second kernel that also applies the affine map.
 // Workgroups are numbered so that those sharing a slice of m run on the same XCD (same L2).
