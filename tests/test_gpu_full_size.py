@@ -1,0 +1,205 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py times.
+
+Whatever the oracle can do in full within seconds is compared in full (parameters, codes, element-wise
+and row-wise gradients of configs 2-4); the rest is sampled: dW by complete M-length dot products at
+sampled (n, k) positions, and the 2^31-element attention map of the long-sequence configuration by
+whole head slabs / row blocks taken at the start, at a head boundary and at the end of the tensor.
+"""
+import numpy as np
+import pytest
+import torch
+
+import mesa_workloads as W
+from oracle import mesa_ref as R
+
+pytestmark = pytest.mark.gpu
+TOL = {torch.float32: 1e-5, torch.float16: 2e-3}
+
+
+@pytest.fixture(scope="module")
+def M():
+    import paper_2111_11124_amd as m
+    assert torch.cuda.is_available()
+    m.lib()
+    return m
+
+
+def canon(a):
+    return (np.asarray(a, np.float32) + np.float32(0.0)).view(np.uint32)
+
+
+def relerr(got, ref):
+    got = np.asarray(got, np.float64).reshape(-1)
+    ref = np.asarray(ref).reshape(-1)
+    return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+
+def ws(m, op, a, b, c, dt=torch.float16):
+    n = m.workspace_bytes(op, a, b, c, m.F16 if dt == torch.float16 else m.F32)
+    return torch.empty(max(n, 16), dtype=torch.uint8, device="cuda")
+
+
+def forward(m, draws, layout, lam, seed, off, full_oracle=True):
+    """update x3 + stochastic quantize on the GPU; parameters always against the oracle, codes if asked."""
+    G = layout[1]
+    a = torch.zeros(G, device="cuda")
+    b = torch.zeros(G, device="cuda")
+    ra, rb = np.zeros(G, np.float32), np.zeros(G, np.float32)
+    w = ws(m, m.OP_UPDATE_RUNNING_PARAMS, *layout)
+    for i, x in enumerate(draws):
+        m.mesa_update_running_params(x, layout, a, b, lam, i == 0, w)
+        ra, rb = R.update_running_params(x.cpu().numpy(), layout, ra, rb, lam, i == 0)
+    assert np.array_equal(canon(a.cpu().numpy()), canon(ra)) and np.array_equal(canon(b.cpu().numpy()), canon(rb))
+    x = draws[-1]
+    q = torch.empty(x.numel(), dtype=torch.int8, device="cuda")
+    m.mesa_quantize_headwise(x, layout, a, b, q, m.ROUND_STOCHASTIC, seed, off)
+    rq = None
+    if full_oracle:
+        rq = R.quantize_headwise(x.cpu().numpy(), layout, ra, rb, R.ROUND_STOCHASTIC, seed, off).reshape(-1)
+        got = q.cpu().numpy()
+        assert np.array_equal(got, rq), np.nonzero(got != rq)[0][:8]
+    return a, b, ra, rb, q, rq
+
+
+def dw_sampled(m, spec, q, rq, a, b, ra, rb, K, N, tol, li):
+    Mr, H = spec.tokens, spec.heads
+    dy = W.upstream_grad(spec, "dy_lin", (Mr, N), "cuda")
+    dW = torch.empty((N, K), device="cuda")
+    db = torch.empty(N, device="cuda")
+    m.mesa_linear_dw_q(q, Mr, K, H, a, b, dy, N, dW, db, ws(m, m.OP_LINEAR_DW_Q, Mr, K, N, spec.dtype))
+    rng = np.random.default_rng(100 + li)
+    rows = rng.integers(0, N, 2)
+    n_idx = np.concatenate([np.repeat(rows, K), rng.integers(0, N, 2048), [0, N - 1, 0, N - 1]])
+    k_idx = np.concatenate([np.tile(np.arange(K), 2), rng.integers(0, K, 2048), [0, 0, K - 1, K - 1]])
+    dyh = dy.cpu().numpy()
+    ent = R.linear_dw_q_entries(rq, Mr, K, H, ra, rb, dyh, N, n_idx, k_idx)
+    got = dW.cpu().numpy().astype(np.float64)
+    scale = max(np.abs(ent).max(), 1e-30)
+    assert np.abs(got[n_idx, k_idx] - ent).max() / scale <= tol
+    assert np.isfinite(got).all()
+    assert relerr(db.cpu().numpy(), dyh.astype(np.float64).sum(0)) <= tol
+
+
+def full_block(m, spec):
+    tol = TOL[spec.dtype]
+    H = spec.heads
+    B, Hh, rows, cols = spec.attn
+    draws = [W.attention_map(spec, d, "cuda") for d in range(3)]
+    a, b, ra, rb, q, rq = forward(m, draws, spec.attn_layout, spec.lam, 5, 0)
+    del draws
+    dy = W.upstream_grad(spec, "dy_attn", spec.attn, "cuda")
+    dx = torch.empty_like(dy)
+    m.mesa_softmax_bwd_q(q, B, Hh, rows, cols, a, b, dy, dx)
+    assert relerr(dx.cpu().numpy(), R.softmax_bwd_q(rq, B, Hh, rows, cols, ra, rb, dy.cpu().numpy())) <= tol
+    del dy, dx
+
+    lay = spec.gelu_layout
+    draws = [W.gelu_input(spec, d, "cuda") for d in range(3)]
+    a, b, ra, rb, q, rq = forward(m, draws, lay, spec.lam, 6, 1 << 40)
+    del draws
+    dy = W.upstream_grad(spec, "dy_gelu", (spec.tokens, spec.mlp), "cuda")
+    dx = torch.empty_like(dy)
+    m.mesa_gelu_bwd_q(q, lay, a, b, dy, dx)
+    assert relerr(dx.cpu().numpy(), R.gelu_bwd_q(rq, lay, ra, rb, dy.cpu().numpy())) <= tol
+    del dy, dx
+
+    Mr, D = spec.tokens, spec.dim
+    draws = [W.token_matrix(spec, "ln", d, "cuda") for d in range(3)]
+    a, b, ra, rb, q, rq = forward(m, draws, spec.ln_layout, spec.lam, 7, 2 << 40)
+    mean, rstd = W.layernorm_stats(draws[-1])
+    del draws
+    gamma = W.layernorm_gamma(spec, "cuda")
+    dy = W.upstream_grad(spec, "dy_ln", (Mr, D), "cuda")
+    dx = torch.empty_like(dy)
+    dg = torch.empty(D, device="cuda")
+    db = torch.empty(D, device="cuda")
+    m.mesa_layernorm_bwd_q(q, Mr, D, H, a, b, mean, rstd, gamma, dy, dx, dg, db, ws(m, m.OP_LAYERNORM_BWD_Q, Mr, D, H))
+    rdx, rdg, rdb = R.layernorm_bwd_q(rq, Mr, D, H, ra, rb, mean.cpu().numpy(), rstd.cpu().numpy(), gamma.cpu().numpy(),
+                                      dy.cpu().numpy())
+    assert relerr(dx.cpu().numpy(), rdx) <= tol and relerr(dg.cpu().numpy(), rdg) <= tol and relerr(db.cpu().numpy(), rdb) <= tol
+    del dy, dx
+
+    for li, (K, N) in enumerate(spec.linears):
+        draws = [W.token_matrix(spec, "lin", 10 * li + d, "cuda", width=K) for d in range(3)]
+        a, b, ra, rb, q, rq = forward(m, draws, (Mr, H, K // H), spec.lam, 8 + li, (3 + li) << 40)
+        del draws
+        dw_sampled(m, spec, q, rq, a, b, ra, rb, K, N, tol, li)
+
+
+def test_config2_deit_s_batch128_full(M):
+    full_block(M, W.CONFIGS[2])
+
+
+def test_config3_swin_t_stage1_full(M):
+    full_block(M, W.CONFIGS[3])
+
+
+def test_config4_deit_b_batch256_one_block_full(M):
+    full_block(M, W.CONFIGS[4])
+
+
+def test_config5_long_sequence_full_sampled(M):
+    """(8, 16, 4096, 4096): 2^31 elements.  Parameters against properties and sampled slabs; codes and
+    softmax backward against the oracle on whole row blocks at the start, across a head boundary, in the
+    middle and at the very end of the tensor."""
+    m = M
+    spec = W.CONFIGS[5]
+    tol = TOL[spec.dtype]
+    B, H, rows, cols = spec.attn
+    lay = spec.attn_layout
+    n = B * H * rows * cols
+    assert n == 1 << 31
+    x = W.attention_map(spec, 0, "cuda")
+    a = torch.zeros(H, device="cuda")
+    b = torch.zeros(H, device="cuda")
+    m.mesa_update_running_params(x, lay, a, b, spec.lam, True, ws(m, m.OP_UPDATE_RUNNING_PARAMS, *lay))
+    # first call: alpha = max - min, beta = min over each head (torch's reductions as the checker)
+    xv = x.view(B, H, rows * cols)
+    mn = xv.amin(dim=(0, 2)).float()
+    mx = xv.amax(dim=(0, 2)).float()
+    assert torch.equal(b, mn + 0.0) and torch.equal(a, mx - mn)
+    q = torch.empty(n, dtype=torch.int8, device="cuda")
+    seed, off = 99, 12345
+    m.mesa_quantize_headwise(x, lay, a, b, q, m.ROUND_STOCHASTIC, seed, off)
+    dy = W.upstream_grad(spec, "dy_attn", spec.attn, "cuda")
+    dx = torch.empty_like(dy)
+    m.mesa_softmax_bwd_q(q, B, H, rows, cols, a, b, dy, dx)
+    an, bn = a.cpu().numpy(), b.cpu().numpy()
+    slab = rows * cols
+    nrows_blk = 64
+    # (first row of the block in global row numbering): start, last rows of head 0 + first of head 1, middle, end
+    starts = [0, rows - nrows_blk // 2, (B * H // 2) * rows + 1000, B * H * rows - nrows_blk]
+    xf, qf, dyf, dxf = x.view(-1), q, dy.view(-1), dx.view(-1)
+    for r0 in starts:
+        e0, e1 = r0 * cols, (r0 + nrows_blk) * cols
+        # rows r0 .. r0+63 may span two heads: split per head slab
+        for h_slab in sorted({r // rows for r in range(r0, r0 + nrows_blk)}):
+            lo, hi = max(e0, h_slab * slab), min(e1, (h_slab + 1) * slab)
+            g = h_slab % H
+            xs = xf[lo:hi].cpu().numpy()
+            rq = R.quantize_headwise(xs, (1, 1, hi - lo), an[g:g + 1], bn[g:g + 1], R.ROUND_STOCHASTIC, seed, off + lo // 8)
+            assert lo % 8 == 0
+            assert np.array_equal(qf[lo:hi].cpu().numpy(), rq.reshape(-1))
+            nr = (hi - lo) // cols
+            ref = R.softmax_bwd_q(rq, 1, 1, nr, cols, an[g:g + 1], bn[g:g + 1], dyf[lo:hi].cpu().numpy())
+            assert relerr(dxf[lo:hi].cpu().numpy(), ref) <= tol
+    # every code of a head lies inside [-128, 127] trivially; the extreme codes are reached by the head's extrema
+    assert int(q.view(B, H, -1)[:, 0].min()) == -128 and int(q.view(B, H, -1)[:, 0].max()) >= 126
+    del x, q, dy, dx
+
+    # GELU / LayerNorm / Linear tensors of this configuration are 134 M / 34 M elements: in full
+    lay = spec.gelu_layout
+    draws = [W.gelu_input(spec, d, "cuda") for d in range(3)]
+    a, b, ra, rb, q, rq = forward(m, draws, lay, spec.lam, 6, 1 << 40)
+    del draws
+    dy = W.upstream_grad(spec, "dy_gelu", (spec.tokens, spec.mlp), "cuda")
+    dx = torch.empty_like(dy)
+    m.mesa_gelu_bwd_q(q, lay, a, b, dy, dx)
+    assert relerr(dx.cpu().numpy(), R.gelu_bwd_q(rq, lay, ra, rb, dy.cpu().numpy())) <= tol
+    del dy, dx
+    Mr, H = spec.tokens, spec.heads
+    for li, (K, N) in enumerate(spec.linears):
+        draws = [W.token_matrix(spec, "lin", 10 * li + d, "cuda", width=K) for d in range(3)]
+        a, b, ra, rb, q, rq = forward(m, draws, (Mr, H, K // H), spec.lam, 8 + li, (3 + li) << 40)
+        del draws
+        dw_sampled(m, spec, q, rq, a, b, ra, rb, K, N, tol, li)
