@@ -16,6 +16,8 @@
 // kernel that may fuse (GELU backward) asks for it explicitly with fmaf.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "api_util.hpp"
 #include "common.hpp"
 
@@ -134,49 +136,44 @@ __device__ __forceinline__ void flush_lane(int *lmn, int *lmx, uint32_t g, float
     }
 }
 
-// Cold path, kept out of line so that the streaming loop stays small: the elements of one vector
-// taken one by one -- used when the vector crosses a slab end, when its group differs from the one
-// being accumulated, and for the ragged tail.  Returns the accumulator by value (registers).
+// All 64 lanes call this together; the lanes with `flush` set hand their extrema to LDS.  Lanes of a
+// wave cover 512 consecutive elements, so they normally leave a head's slab together and for the
+// same old group: then the wave combines in registers and one lane issues the two atomics
+// (64 same-address LDS atomics from one instruction are serialised and cost thousands of cycles).
+__device__ __forceinline__ void flush_wave(int *lmn, int *lmx, bool flush, uint32_t g, float lo, float hi)
+{
+    const unsigned long long mask = __ballot(flush);
+    const int first = __ffsll((long long)mask) - 1;
+    const uint32_t g0 = __builtin_amdgcn_readlane(g, first);
+    if (__ballot(flush && g != g0) == 0ull) {
+        lo = flush ? lo : __builtin_inff();
+        hi = flush ? hi : -__builtin_inff();
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            lo = vmin(lo, __shfl_xor(lo, off, 64));
+            hi = vmax(hi, __shfl_xor(hi, off, 64));
+        }
+        if (int(threadIdx.x & 63) == first) flush_lane(lmn, lmx, g0, lo, hi);
+    } else if (flush) {
+        flush_lane(lmn, lmx, g, lo, hi);
+    }
+}
+
+// the elements of a vector taken one by one: for vectors that cross a slab end and for the ragged tail
 template <typename T> struct MinMaxState {
     MinMax<T> acc;
     uint32_t cur;
 };
 
 template <typename T>
-__device__ __attribute__((noinline)) MinMaxState<T> minmax_elements(const void *x, int64_t e, int n, Cursor c, GroupGeom gg,
-                                                                   MinMaxState<T> st, int *lmn, int *lmx)
+__device__ __forceinline__ void minmax_element(MinMaxState<T> &st, uint32_t g, float f, int *lmn, int *lmx)
 {
-    for (int j = 0; j < n; ++j) {
-        uint32_t g = group_of(c, j, gg);
-        if (g != st.cur) {
-            flush_lane(lmn, lmx, st.cur, st.acc.lo(), st.acc.hi());
-            st.cur = g;
-            st.acc.init();
-        }
-        st.acc.add1(Store<T>::load1(x, e + j));
+    if (g != st.cur) {
+        flush_lane(lmn, lmx, st.cur, st.acc.lo(), st.acc.hi());
+        st.cur = g;
+        st.acc.init();
     }
-    return st;
-}
-
-// Eq. (6)-(7) for one group from its extrema: each product, difference and sum rounded on its own.
-__device__ __forceinline__ void ema_update(float mn, float mx, float *alpha, float *beta, uint32_t g, float lambda,
-                                           int first_call)
-{
-    mn = mn + 0.0f;  // -0.0 -> +0.0
-    mx = mx + 0.0f;
-    float range = mx - mn;
-    if (first_call) {
-        alpha[g] = range;
-        beta[g] = mn;
-    } else {
-        float a = lambda * alpha[g];
-        float b = 1.0f - lambda;
-        float c = b * range;
-        alpha[g] = a + c;
-        float e = lambda * beta[g];
-        float f = b * mn;
-        beta[g] = e + f;
-    }
+    st.acc.add1(f);
 }
 
 // Partial extrema of each workgroup: part[wg][0..G) = min, part[wg][G..2G) = max.  (Letting the last
@@ -204,36 +201,46 @@ __global__ __launch_bounds__(kThreads) void k_minmax_partial(const void *__restr
     constexpr int kChunk = kThreads * U * kVec;
     const int64_t stride = int64_t(gridDim.x) * kChunk;
     const int64_t toff = int64_t(threadIdx.x) * kVec;
-    int64_t base = int64_t(blockIdx.x) * kChunk;
-    for (; base + kChunk <= numel; base += stride) {
+    // CHECK = false: the chunk lies wholly inside the tensor, no per-vector bounds test
+    auto chunk = [&](int64_t base, auto check) {
+        constexpr bool CHECK = decltype(check)::value;
         typename Store<T>::raw_t v[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) v[u] = Nt<T>::load(x, base + u * (kThreads * kVec) + toff);
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (__builtin_expect(c[u].rem + kVec <= gg.inner, 1)) {
-                if (c[u].g != st[u].cur) {   // moved on to another group: hand the finished one to LDS
-                    flush_lane(lmn, lmx, st[u].cur, st[u].acc.lo(), st[u].acc.hi());
-                    st[u].cur = c[u].g;
-                    st[u].acc.init();
-                }
-                st[u].acc.add(v[u]);
-            } else {
-                st[u] = minmax_elements<T>(x, base + u * (kThreads * kVec) + toff, kVec, c[u], gg, st[u], lmn, lmx);
-            }
-            cursor_advance(c[u], gg);
-        }
-    }
-    if (base < numel) {  // the chunk that holds the end of the tensor
+        bool full[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t e = base + u * (kThreads * kVec) + toff;
-            if (e < numel) {
-                const int64_t left = numel - e;
-                st[u] = minmax_elements<T>(x, e, left < kVec ? int(left) : kVec, c[u], gg, st[u], lmn, lmx);
-            }
+            full[u] = !CHECK || e + kVec <= numel;
+            if (full[u]) v[u] = Nt<T>::load(x, e);
         }
-    }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t e = base + u * (kThreads * kVec) + toff;
+            const bool one = full[u] && c[u].rem + kVec <= gg.inner;
+            const bool moved = one && c[u].g != st[u].cur;   // on to another group: hand the finished one to LDS
+            if (__any(moved)) {                               // wave-uniform, rare
+                flush_wave(lmn, lmx, moved, st[u].cur, st[u].acc.lo(), st[u].acc.hi());
+                if (moved) {
+                    st[u].cur = c[u].g;
+                    st[u].acc.init();
+                }
+            }
+            if (__builtin_expect(one, 1)) {
+                st[u].acc.add(v[u]);
+            } else if (full[u]) {   // crosses a slab end: element by element, from the registers
+                float f[8];
+                Store<T>::unpack(v[u], f);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) minmax_element<T>(st[u], group_of(c[u], j, gg), f[j], lmn, lmx);
+            } else if (e < numel) {   // the ragged end of the tensor, once per launch
+                for (int j = 0; e + j < numel; ++j)
+                    minmax_element<T>(st[u], group_of(c[u], j, gg), Store<T>::load1(x, e + j), lmn, lmx);
+            }
+            cursor_advance(c[u], gg);
+        }
+    };
+    int64_t base = int64_t(blockIdx.x) * kChunk;
+    for (; base + kChunk <= numel; base += stride) chunk(base, std::false_type());
+    if (base < numel) chunk(base, std::true_type());   // the chunk that holds the end of the tensor
     // fold the U accumulators that sit in the same group, then let a wave whose lanes all sit in
     // one group (head-wise tensors) combine in registers before touching LDS
     float lo = st[0].acc.lo(), hi = st[0].acc.hi();
@@ -262,6 +269,27 @@ __global__ __launch_bounds__(kThreads) void k_minmax_partial(const void *__restr
     for (uint32_t g = threadIdx.x; g < gg.groups; g += kThreads) {
         out[g] = order_val(lmn[g]);
         out[gg.groups + g] = order_val(lmx[g]);
+    }
+}
+
+// Eq. (6)-(7) for one group from its extrema: each product, difference and sum rounded on its own.
+__device__ __forceinline__ void ema_update(float mn, float mx, float *alpha, float *beta, uint32_t g, float lambda,
+                                           int first_call)
+{
+    mn = mn + 0.0f;  // -0.0 -> +0.0
+    mx = mx + 0.0f;
+    float range = mx - mn;
+    if (first_call) {
+        alpha[g] = range;
+        beta[g] = mn;
+    } else {
+        float a = lambda * alpha[g];
+        float b = 1.0f - lambda;
+        float c = b * range;
+        alpha[g] = a + c;
+        float e = lambda * beta[g];
+        float f = b * mn;
+        beta[g] = e + f;
     }
 }
 
@@ -351,17 +379,11 @@ __device__ __forceinline__ u32x2 pack_codes(const float w[8])
     return c;
 }
 
-template <typename T, bool SR>
-__device__ __attribute__((noinline)) void quantize_elements(const void *x, int8_t *q, int64_t e, int n, Cursor c, GroupGeom gg,
-                                                            const float2 *tab, uint64_t seed, uint64_t counter)
+// per-element (scale, beta) of a vector whose elements do not all lie in one slab
+__device__ __forceinline__ void params_of(const Cursor &c, const GroupGeom &gg, const float2 *tab, float2 p[8])
 {
-    float bits[8];
-    if (SR) sr_bits(seed, counter, bits);
-    for (int j = 0; j < n; ++j) {
-        float2 p = tab[group_of(c, j, gg)];
-        float w = clamp_code(quantize_one<SR>(Store<T>::load1(x, e + j), p.x, p.y, SR ? bits[j] : 0.0f));
-        q[e + j] = int8_t(int(w) - 128);
-    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) p[j] = tab[group_of(c, j, gg)];
 }
 
 template <typename T, int U, bool SR>
@@ -377,39 +399,50 @@ __global__ __launch_bounds__(kThreads) void k_quantize(const void *__restrict__ 
     constexpr int kChunk = kThreads * U * kVec;
     const int64_t stride = int64_t(gridDim.x) * kChunk;
     const int64_t toff = int64_t(threadIdx.x) * kVec;
-    int64_t base = int64_t(blockIdx.x) * kChunk;
-    for (; base + kChunk <= numel; base += stride) {
+    // CHECK = false: the chunk lies wholly inside the tensor, no per-vector bounds test
+    auto chunk = [&](int64_t base, auto check) {
+        constexpr bool CHECK = decltype(check)::value;
         typename Store<T>::raw_t v[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) v[u] = Nt<T>::load(x, base + u * (kThreads * kVec) + toff);
+        bool full[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t e = base + u * (kThreads * kVec) + toff;
-            if (__builtin_expect(c[u].rem + kVec <= gg.inner, 1)) {
+            full[u] = !CHECK || e + kVec <= numel;
+            if (full[u]) v[u] = Nt<T>::load(x, e);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t e = base + u * (kThreads * kVec) + toff;
+            if (full[u]) {
                 float f[8], w[8], bits[8];
                 if (SR) sr_bits(seed, offset + uint64_t(e >> 3), bits);
                 Store<T>::unpack(v[u], f);
-                const float2 p = lds_tab[c[u].g];
+                if (__builtin_expect(c[u].rem + kVec <= gg.inner, 1)) {
+                    const float2 p = lds_tab[c[u].g];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) w[j] = quantize_one<SR>(f[j], p.x, p.y, SR ? bits[j] : 0.0f);
+                    for (int j = 0; j < 8; ++j) w[j] = quantize_one<SR>(f[j], p.x, p.y, SR ? bits[j] : 0.0f);
+                } else {   // the vector crosses a slab end: parameters per element
+                    float2 p[8];
+                    params_of(c[u], gg, lds_tab, p);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) w[j] = quantize_one<SR>(f[j], p[j].x, p[j].y, SR ? bits[j] : 0.0f);
+                }
                 nt_store<u32x2>(q + e, pack_codes(w));
-            } else {
-                quantize_elements<T, SR>(x, q, e, kVec, c[u], gg, lds_tab, seed, offset + uint64_t(e >> 3));
+            } else if (e < numel) {   // the ragged end of the tensor, once per launch
+                float bits[8];
+                if (SR) sr_bits(seed, offset + uint64_t(e >> 3), bits);
+                for (int j = 0; e + j < numel; ++j) {
+                    const float2 p = lds_tab[group_of(c[u], j, gg)];
+                    const float w = clamp_code(quantize_one<SR>(Store<T>::load1(x, e + j), p.x, p.y, SR ? bits[j] : 0.0f));
+                    q[e + j] = int8_t(int(w) - 128);
+                }
             }
             cursor_advance(c[u], gg);
         }
-    }
-    if (base < numel) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t e = base + u * (kThreads * kVec) + toff;
-            if (e < numel) {
-                const int64_t left = numel - e;
-                quantize_elements<T, SR>(x, q, e, left < kVec ? int(left) : kVec, c[u], gg, lds_tab, seed,
-                                         offset + uint64_t(e >> 3));
-            }
-        }
-    }
+    };
+    int64_t base = int64_t(blockIdx.x) * kChunk;
+    for (; base + kChunk <= numel; base += stride) chunk(base, std::false_type());
+    if (base < numel) chunk(base, std::true_type());   // the chunk that holds the end of the tensor
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -420,16 +453,6 @@ __device__ __forceinline__ float dequant_exact(float u, float s, float b)
     float xh = u * s;
     xh = xh + b;
     return xh;
-}
-
-template <typename T>
-__device__ __attribute__((noinline)) void dequantize_elements(const int8_t *q, void *xh, int64_t e, int n, Cursor c,
-                                                              GroupGeom gg, const float2 *tab)
-{
-    for (int j = 0; j < n; ++j) {
-        const float2 p = tab[group_of(c, j, gg)];
-        Store<T>::store1(xh, e + j, dequant_exact(code_to_float(q[e + j]), p.x, p.y));
-    }
 }
 
 template <typename T, int U>
@@ -445,37 +468,46 @@ __global__ __launch_bounds__(kThreads) void k_dequantize(const int8_t *__restric
     constexpr int kChunk = kThreads * U * kVec;
     const int64_t stride = int64_t(gridDim.x) * kChunk;
     const int64_t toff = int64_t(threadIdx.x) * kVec;
-    int64_t base = int64_t(blockIdx.x) * kChunk;
-    for (; base + kChunk <= numel; base += stride) {
+    // CHECK = false: the chunk lies wholly inside the tensor, no per-vector bounds test
+    auto chunk = [&](int64_t base, auto check) {
+        constexpr bool CHECK = decltype(check)::value;
         u32x2 v[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) v[u] = nt_load<u32x2>(q + base + u * (kThreads * kVec) + toff);
+        bool full[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t e = base + u * (kThreads * kVec) + toff;
-            if (__builtin_expect(c[u].rem + kVec <= gg.inner, 1)) {
+            full[u] = !CHECK || e + kVec <= numel;
+            if (full[u]) v[u] = nt_load<u32x2>(q + e);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t e = base + u * (kThreads * kVec) + toff;
+            if (full[u]) {
                 float uu[8], f[8];
                 codes_to_float(v[u], uu);
-                const float2 p = lds_tab[c[u].g];
+                if (__builtin_expect(c[u].rem + kVec <= gg.inner, 1)) {
+                    const float2 p = lds_tab[c[u].g];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) f[j] = dequant_exact(uu[j], p.x, p.y);
+                    for (int j = 0; j < 8; ++j) f[j] = dequant_exact(uu[j], p.x, p.y);
+                } else {
+                    float2 p[8];
+                    params_of(c[u], gg, lds_tab, p);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) f[j] = dequant_exact(uu[j], p[j].x, p[j].y);
+                }
                 Nt<T>::store(xh, e, Store<T>::pack(f));
-            } else {
-                dequantize_elements<T>(q, xh, e, kVec, c[u], gg, lds_tab);
+            } else if (e < numel) {
+                for (int j = 0; e + j < numel; ++j) {
+                    const float2 p = lds_tab[group_of(c[u], j, gg)];
+                    Store<T>::store1(xh, e + j, dequant_exact(code_to_float(q[e + j]), p.x, p.y));
+                }
             }
             cursor_advance(c[u], gg);
         }
-    }
-    if (base < numel) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t e = base + u * (kThreads * kVec) + toff;
-            if (e < numel) {
-                const int64_t left = numel - e;
-                dequantize_elements<T>(q, xh, e, left < kVec ? int(left) : kVec, c[u], gg, lds_tab);
-            }
-        }
-    }
+    };
+    int64_t base = int64_t(blockIdx.x) * kChunk;
+    for (; base + kChunk <= numel; base += stride) chunk(base, std::false_type());
+    if (base < numel) chunk(base, std::true_type());   // the chunk that holds the end of the tensor
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -497,24 +529,6 @@ __device__ __forceinline__ float gelu_grad(float x)
     float h = 0.5f * poly * E;
     float cdf = (x >= 0.0f) ? 1.0f - h : h;
     return fmaf(x * E, 0.39894228040143268f, cdf);
-}
-
-template <typename T, bool LUT>
-__device__ __attribute__((noinline)) void gelu_elements(const int8_t *q, const void *dy, void *dx, int64_t e, int n, Cursor c,
-                                                        GroupGeom gg, const float *lds)
-{
-    for (int j = 0; j < n; ++j) {
-        const uint32_t g = group_of(c, j, gg);
-        const uint32_t raw = uint32_t(uint8_t(q[e + j]));
-        float gr;
-        if (LUT) {
-            gr = lds[g * 256u + raw];
-        } else {
-            const float2 p = reinterpret_cast<const float2 *>(lds)[g];
-            gr = gelu_grad(fmaf(float(raw ^ 0x80u), p.x, p.y));
-        }
-        Store<T>::store1(dx, e + j, Store<T>::load1(dy, e + j) * gr);
-    }
 }
 
 // x_hat takes only 256 values per group, so gelu'(x_hat) is a table of groups*256 entries: each
@@ -539,54 +553,67 @@ __global__ __launch_bounds__(kThreads) void k_gelu_bwd(const int8_t *__restrict_
         fill_table<Scale::Dequant>(tab2, alpha, beta, gg.groups);
     }
 
+    auto grad_of = [&](uint32_t g, uint32_t raw) -> float {
+        if (LUT) return lds_gelu[g * 256u + raw];
+        const float2 p = tab2[g];
+        return gelu_grad(fmaf(float(raw ^ 0x80u), p.x, p.y));
+    };
+
     Cursor c[U];
     place_cursors<U>(c, gg, numel);
     constexpr int kChunk = kThreads * U * kVec;
     const int64_t stride = int64_t(gridDim.x) * kChunk;
     const int64_t toff = int64_t(threadIdx.x) * kVec;
-    int64_t base = int64_t(blockIdx.x) * kChunk;
-    for (; base + kChunk <= numel; base += stride) {
+    // CHECK = false: the chunk lies wholly inside the tensor, no per-vector bounds test
+    auto chunk = [&](int64_t base, auto check) {
+        constexpr bool CHECK = decltype(check)::value;
         u32x2 v[U];
         typename Store<T>::raw_t d[U];
+        bool full[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            v[u] = nt_load<u32x2>(q + base + u * (kThreads * kVec) + toff);
-            d[u] = Nt<T>::load(dy, base + u * (kThreads * kVec) + toff);
+            const int64_t e = base + u * (kThreads * kVec) + toff;
+            full[u] = !CHECK || e + kVec <= numel;
+            if (full[u]) {
+                v[u] = nt_load<u32x2>(q + e);
+                d[u] = Nt<T>::load(dy, e);
+            }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t e = base + u * (kThreads * kVec) + toff;
-            if (__builtin_expect(c[u].rem + kVec <= gg.inner, 1)) {
+            if (full[u]) {
                 float g[8];
                 Store<T>::unpack(d[u], g);
-                if (LUT) {
-                    const float *row = lds_gelu + c[u].g * 256u;
+                if (__builtin_expect(c[u].rem + kVec <= gg.inner, 1)) {
+                    if (LUT) {
+                        const float *row = lds_gelu + c[u].g * 256u;
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) g[j] = g[j] * row[(v[u][j >> 2] >> (8 * (j & 3))) & 0xFFu];
+                        for (int j = 0; j < 8; ++j) g[j] = g[j] * row[(v[u][j >> 2] >> (8 * (j & 3))) & 0xFFu];
+                    } else {
+                        const float2 p = tab2[c[u].g];
+                        float uu[8];
+                        codes_to_float(v[u], uu);
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) g[j] = g[j] * gelu_grad(fmaf(uu[j], p.x, p.y));
+                    }
                 } else {
-                    const float2 p = tab2[c[u].g];
-                    float uu[8];
-                    codes_to_float(v[u], uu);
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) g[j] = g[j] * gelu_grad(fmaf(uu[j], p.x, p.y));
+                    for (int j = 0; j < 8; ++j)
+                        g[j] = g[j] * grad_of(group_of(c[u], j, gg), (v[u][j >> 2] >> (8 * (j & 3))) & 0xFFu);
                 }
                 Nt<T>::store(dx, e, Store<T>::pack(g));
-            } else {
-                gelu_elements<T, LUT>(q, dy, dx, e, kVec, c[u], gg, lds_gelu);
+            } else if (e < numel) {
+                for (int j = 0; e + j < numel; ++j)
+                    Store<T>::store1(dx, e + j, Store<T>::load1(dy, e + j) *
+                                                    grad_of(group_of(c[u], j, gg), uint32_t(uint8_t(q[e + j]))));
             }
             cursor_advance(c[u], gg);
         }
-    }
-    if (base < numel) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t e = base + u * (kThreads * kVec) + toff;
-            if (e < numel) {
-                const int64_t left = numel - e;
-                gelu_elements<T, LUT>(q, dy, dx, e, left < kVec ? int(left) : kVec, c[u], gg, lds_gelu);
-            }
-        }
-    }
+    };
+    int64_t base = int64_t(blockIdx.x) * kChunk;
+    for (; base + kChunk <= numel; base += stride) chunk(base, std::false_type());
+    if (base < numel) chunk(base, std::true_type());   // the chunk that holds the end of the tensor
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -631,7 +658,22 @@ static int minmax_grid(const mesa_layout &L)
         cap = int(int64_t(kMmGridCap) * 64 / L.groups);
         if (cap < 32) cap = 32;
     }
-    return plan_grid(numel, int64_t(kThreads) * kMmU * kVec, cap, L.groups > 1 ? L.groups * L.inner : 0);
+    const int64_t chunk = int64_t(kThreads) * kMmU * kVec;
+    int n = plan_grid(numel, chunk, cap, L.groups > 1 ? L.groups * L.inner : 0);
+    // Long slabs (head-wise tensors): a thread hands its extrema to LDS whenever its group changes,
+    // so pick a grid whose step is a whole number of group cycles plus a small remainder -- then a
+    // thread stays with one head for many iterations instead of meeting a new one every time.
+    const int64_t row = L.groups * L.inner;
+    if (L.groups > 1 && L.inner > chunk && ceil_div(numel, chunk) > n) {
+        int best = n;
+        int64_t best_rem = (int64_t(n) * chunk) % row;
+        for (int k = n + 1; k < n + 256 && best_rem >= L.inner / 16; ++k) {
+            const int64_t rem = (int64_t(k) * chunk) % row;
+            if (rem < best_rem) { best_rem = rem; best = k; }
+        }
+        n = best;
+    }
+    return n;
 }
 
 extern "C" MESA_EXPORT mesa_status mesa_update_running_params(const void *x, mesa_dtype dt, mesa_layout L, float *alpha, float *beta,
