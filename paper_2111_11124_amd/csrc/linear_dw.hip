@@ -42,6 +42,7 @@ template <int BN, int BK, int WGN, int WGK> struct DwCfg {
     static constexpr int THREADS = NW * 64;
     static constexpr int WN = BN / WGN, WK = BK / WGK;  // wave tile
     static constexpr int TI = WN / 32, TJ = WK / 32;    // MFMA tiles per wave
+    static constexpr int TIS = TI / WGK;                // dy fragments whose row sums this wave keeps
     static constexpr int PA = BN * 2 + 64;              // LDS row pitch of the dy tile, bytes
     static constexpr int PB = BK + 32;                  // LDS row pitch of the code tile, bytes
     static constexpr int A_STAGE = kDwBM * PA;
@@ -50,24 +51,25 @@ template <int BN, int BK, int WGN, int WGK> struct DwCfg {
     static constexpr int A_CPR = BN / 8;                // 16-byte chunks per tile row
     static constexpr int B_CPR = BK / 16;
     static constexpr int A_TOTAL = kDwBM * A_CPR, B_TOTAL = kDwBM * B_CPR;
-    static constexpr int A_CHUNKS = (A_TOTAL + THREADS - 1) / THREADS;
-    static constexpr int B_CHUNKS = (B_TOTAL + THREADS - 1) / THREADS;
+    static constexpr int A_CHUNKS = A_TOTAL / THREADS;  // chunks a thread moves per stage
+    static constexpr int B_CHUNKS = B_TOTAL / THREADS;
+    static constexpr int RA = THREADS / A_CPR;          // rows between a thread's successive chunks
+    static constexpr int RB = THREADS / B_CPR;
+    static_assert(A_TOTAL % THREADS == 0 && B_TOTAL % THREADS == 0 && THREADS % A_CPR == 0 && THREADS % B_CPR == 0,
+                  "every thread moves whole rows' worth of chunks, the same column each time");
+    static_assert(TI % WGK == 0, "the row sums are shared out among the waves of a row");
     static_assert(WN % 64 == 0 && WK % 32 == 0, "wave tile: an even number of 32-row MFMA tiles by whole 32-column tiles");
     static_assert(2 * STAGE <= 64 * 1024, "two stages must fit the default dynamic LDS limit");
 };
 
-// eight signed codes (bytes) -> eight binary16 values q: 0x6400 | (byte ^ 0x80) is 1152 + q exactly
-__device__ __forceinline__ v8h codes_to_half8(v2i raw)
+// four signed codes (the bytes of x) -> four binary16 values q: 0x6400 | (byte ^ 0x80) is 1152 + q exactly
+__device__ __forceinline__ v4h codes_to_half4(int raw)
 {
-    v8h out;
     const h2 k1152 = {(_Float16)1152.0f, (_Float16)1152.0f};
-#pragma unroll
-    for (int w = 0; w < 2; ++w) {
-        const uint32_t x = uint32_t(raw[w]) ^ 0x80808080u;
-        const h2 a = as_h2(__builtin_amdgcn_perm(0x64646464u, x, 0x04010400u)) - k1152;   // bytes 0, 1
-        const h2 b = as_h2(__builtin_amdgcn_perm(0x64646464u, x, 0x04030402u)) - k1152;   // bytes 2, 3
-        out[4 * w + 0] = a.x; out[4 * w + 1] = a.y; out[4 * w + 2] = b.x; out[4 * w + 3] = b.y;
-    }
+    const uint32_t x = uint32_t(raw) ^ 0x80808080u;
+    const h2 a = as_h2(__builtin_amdgcn_perm(0x64646464u, x, 0x04010400u)) - k1152;   // bytes 0, 1
+    const h2 b = as_h2(__builtin_amdgcn_perm(0x64646464u, x, 0x04030402u)) - k1152;   // bytes 2, 3
+    v4h out = {a.x, a.y, b.x, b.y};
     return out;
 }
 
@@ -93,12 +95,19 @@ __global__ __launch_bounds__(WGN * WGK * 64, 1) void k_dw_f16(const int8_t *__re
     const int n0 = tn * BN, kk0 = tk * BK;
     const int64_t m_begin = int64_t(split) * rows_per_split;
     const int64_t m_end = (m_begin + rows_per_split < M) ? m_begin + rows_per_split : M;
-    const int nstages = (m_end > m_begin) ? int((m_end - m_begin + kDwBM - 1) / kDwBM) : 0;
 
     const int wn = wave / WGK, wk = wave % WGK;
     const int blk = lane >> 4, sl = lane & 15;
     // byte offsets of this lane's transpose-read addresses inside a stage
     const int a_off = ((blk >> 1) * 8 + (sl >> 2)) * C::PA + (wn * C::WN + (blk & 1) * 16 + (sl & 3) * 4) * 2;
+    // The WGK waves that hold the same dy rows visit the wave tile's 32-row blocks in rotated order:
+    // fragment i of wave wk is block a_block(i), so that "the first TIS fragments" -- a compile-time
+    // set -- is a different quarter or half of the rows in each of them, and each row sum is
+    // accumulated by exactly one wave.
+    int a_base[WGK];
+#pragma unroll
+    for (int g = 0; g < WGK; ++g) a_base[g] = a_off + ((g + wk) % WGK) * C::TIS * 64;
+    auto a_block = [&](int i) { return ((i / C::TIS + wk) % WGK) * C::TIS + i % C::TIS; };
     const int b_off = C::A_STAGE + ((blk >> 1) * 8 + (sl >> 1)) * C::PB + wk * C::WK + (blk & 1) * 16 + (sl & 1) * 8;
 
     v16f acc[C::TI][C::TJ];
@@ -108,210 +117,201 @@ __global__ __launch_bounds__(WGN * WGK * 64, 1) void k_dw_f16(const int8_t *__re
         for (int j = 0; j < C::TJ; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-    float s0[C::TI];
+    float s0[C::TIS];
 #pragma unroll
-    for (int i = 0; i < C::TI; ++i) s0[i] = 0.0f;
-    const bool do_s0 = (tk == 0) && (wk == 0);   // the waves whose row sums are written out
+    for (int i = 0; i < C::TIS; ++i) s0[i] = 0.0f;
+    const bool do_s0 = (tk == 0);   // the workgroups whose row sums are written out
 
     // global -> register prefetch ring: stage s+1 .. s+kDwPF are in flight while stage s is multiplied,
     // enough bytes per CU to cover the latency of L2 / memory-side-cache hits at the rate MFMA consumes them.
-    // Every load is unconditional from a clamped, always valid address; what lies outside the tile or
-    // past the end of the slice is zeroed by a select, so the steady-state loop has no branches.
+    // A thread moves the same 16-byte column chunk of rows row0, row0 + RA, row0 + 2 RA, ... of every
+    // stage, so one 32-bit offset per operand serves all its loads (the row of the item and the stage
+    // go into the uniform base address) and one LDS address all its writes.  Columns outside N or K
+    // are read from column 0 instead and left as they are: row n of the product depends on column n
+    // of dy only and column k on column k of the codes, and those rows and columns are never written.
     u32x4 ring_a[kDwPF][C::A_CHUNKS], ring_b[kDwPF][C::B_CHUNKS];
-    const _Float16 *pa[C::A_CHUNKS];
-    const int8_t *pb[C::B_CHUNKS];
-    int row_a[C::A_CHUNKS], row_b[C::B_CHUNKS], lds_a[C::A_CHUNKS], lds_b[C::B_CHUNKS];
-    bool ok_a[C::A_CHUNKS], ok_b[C::B_CHUNKS];
-#pragma unroll
-    for (int i = 0; i < C::A_CHUNKS; ++i) {
-        const int c = i * C::THREADS + tid;
-        const int row = (c / C::A_CPR) % kDwBM, cc = c % C::A_CPR;
-        const int n = n0 + cc * 8;
-        ok_a[i] = c < C::A_TOTAL && n < N;
-        row_a[i] = row;
-        pa[i] = dy + (ok_a[i] ? n : 0);
-        lds_a[i] = row * C::PA + cc * 16;
-    }
-#pragma unroll
-    for (int i = 0; i < C::B_CHUNKS; ++i) {
-        const int c = i * C::THREADS + tid;
-        const int row = (c / C::B_CPR) % kDwBM, cc = c % C::B_CPR;
-        const int kk = kk0 + cc * 16;
-        ok_b[i] = c < C::B_TOTAL && kk < K;
-        row_b[i] = row;
-        pb[i] = xq + (ok_b[i] ? kk : 0);
-        lds_b[i] = C::A_STAGE + row * C::PB + cc * 16;
-    }
+    const int row0_a = tid / C::A_CPR, col_a = n0 + (tid % C::A_CPR) * 8;
+    const int row0_b = tid / C::B_CPR, col_b = kk0 + (tid % C::B_CPR) * 16;
+    const uint32_t voff_a = (uint32_t(row0_a) * uint32_t(N) + uint32_t(col_a < N ? col_a : 0)) * 2u;   // bytes
+    const uint32_t voff_b = uint32_t(row0_b) * uint32_t(K) + uint32_t(col_b < K ? col_b : 0);
+    const int lds_a0 = row0_a * C::PA + (tid % C::A_CPR) * 16;
+    const int lds_b0 = C::A_STAGE + row0_b * C::PB + (tid % C::B_CPR) * 16;
+    const char *dy_bytes = reinterpret_cast<const char *>(dy);
+    const char *xq_bytes = reinterpret_cast<const char *>(xq);
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
-    const int64_t m_last = (m_end > m_begin) ? m_end - 1 : 0;
+    const int64_t len = m_end - m_begin;
+    const int nfull = int(len / kDwBM);                  // stages with all their rows inside the slice
+    const int64_t m_cap = M - kDwBM;                     // last row a whole stage may start at
 
-    // EDGE = false: every row of the stage lies inside the slice (no row clamping, no row select).
-    // The zeroing select is applied when the registers are written to LDS, not at the load, so that
-    // nothing waits on a load before its stage is due.
-    auto load_stage = [&](int64_t m_stage, u32x4 *ra, u32x4 *rb, auto edge) {
-        constexpr bool EDGE = decltype(edge)::value;
+    constexpr int kMove = C::A_CHUNKS + C::B_CHUNKS;     // 16-byte chunks a thread moves per stage
+    // Whole stages are loaded without any per-lane guard.  A stage that starts beyond the tensor's
+    // last whole stage (only ever a prefetch that is never used) is moved back to it: one scalar min.
+    auto load_item = [&](int t, int64_t m_stage, u32x4 *ra, u32x4 *rb) {
+        if (t < C::A_CHUNKS) {
+            const char *base = dy_bytes + (m_stage + t * C::RA) * int64_t(N) * 2;     // uniform
+            ra[t] = *reinterpret_cast<const u32x4 *>(base + voff_a);
+        } else {
+            const int i = t - C::A_CHUNKS;
+            const char *base = xq_bytes + (m_stage + i * C::RB) * int64_t(K);
+            rb[i] = *reinterpret_cast<const u32x4 *>(base + voff_b);
+        }
+    };
+    auto store_item = [&](int t, unsigned char *st, const u32x4 *ra, const u32x4 *rb) {
+        if (t < C::A_CHUNKS) *reinterpret_cast<u32x4 *>(st + lds_a0 + t * C::RA * C::PA) = ra[t];
+        else *reinterpret_cast<u32x4 *>(st + lds_b0 + (t - C::A_CHUNKS) * C::RB * C::PB) = rb[t - C::A_CHUNKS];
+    };
+    auto stage_start = [&](int s) {
+        const int64_t m = m_begin + int64_t(s) * kDwBM;
+        return m < m_cap ? m : m_cap;
+    };
+
+    // ---- software pipeline -------------------------------------------------------------------
+    // A stage holds two contraction steps of 16 rows.  With one wave per SIMD the instruction
+    // stream is issued in order, so the matrix core idles behind any burst of other instructions:
+    // each step is therefore written as kNM slices -- one MFMA followed by that slice's share of
+    // everything else -- fenced by scheduling barriers so that the program order is the issue order.
+    // "Everything else" is, per step: the LDS reads of the next step's fragments (codes first), the
+    // LDS writes of the next stage (first step) or the global loads that refill the ring slot just
+    // freed (second step), this wave's share of the row sums of dy, and -- in the second half, when
+    // the codes have arrived from LDS -- their conversion to binary16.  The workgroup barrier falls
+    // between the two steps: after this wave's last read of the current buffer and its writes to
+    // the other one.
+    // Nothing in a step is conditional.  The last stages of a slice therefore also write to LDS,
+    // read, convert and prefetch stages that do not exist: all of it lands in registers and LDS
+    // buffers that nobody uses afterwards.
+    constexpr int kNM = C::TI * C::TJ;                       // MFMAs per step
+    constexpr int kNR = C::TI * 2 + C::TJ;                   // LDS reads per step
+    constexpr int kND = C::TIS * 4;                          // dot instructions per step
+    constexpr int kNC = C::TJ * 2;                           // conversions (four codes each) per step
+    v4h afr[2][C::TI][2], bfr[2][C::TJ][2];                  // fragments of the step in flight and the next
+    v2i braw[C::TJ];
+    auto read_item = [&](int t, const unsigned char *st, int ks, int set) {
+        if (t < C::TJ) {
+            braw[t] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(MESA_LDS3(v2i, st + b_off + ks * 16 * C::PB + t * 32));
+        } else {
+            const int i = (t - C::TJ) >> 1, h = (t - C::TJ) & 1;
+            const unsigned char *p = st + a_base[i / C::TIS] + ks * 16 * C::PA + (i % C::TIS) * 64 + h * 4 * C::PA;
+            afr[set][i][h] = __builtin_bit_cast(v4h, __builtin_amdgcn_ds_read_tr16_b64_v4i16(MESA_LDS3(v4s, p)));
+        }
+    };
+    auto dot_item = [&](int d, int set) {
+        const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
+        const int i = d >> 2, k = d & 3;
+        const h2 pr = {afr[set][i][k >> 1][2 * (k & 1)], afr[set][i][k >> 1][2 * (k & 1) + 1]};
+        s0[i] = __builtin_amdgcn_fdot2(pr, ones, s0[i], false);
+    };
+    auto conv_item = [&](int c, int set) { bfr[set][c >> 1][c & 1] = codes_to_half4(braw[c >> 1][c & 1]); };
+    auto mfma_item = [&](int r, int set) {
+        const int i = r / C::TJ, j = r % C::TJ;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+            __builtin_shufflevector(afr[set][i][0], afr[set][i][1], 0, 1, 2, 3, 4, 5, 6, 7),
+            __builtin_shufflevector(bfr[set][j][0], bfr[set][j][1], 0, 1, 2, 3, 4, 5, 6, 7), acc[i][j], 0, 0, 0);
+    };
+
+    // One step.  PH = 0: multiplies fragment set 0 (step 0 of stage s), fetches step 1 into set 1 and
+    // writes stage s+1 (ring slot ra/rb) to the other LDS buffer.  PH = 1: multiplies set 1, fetches
+    // step 0 of stage s+1 into set 0 and refills the ring slot with stage s+1+kDwPF.
+    auto step = [&](auto phase, int s, u32x4 *ra, u32x4 *rb) {
+        constexpr int PH = decltype(phase)::value;
+        const unsigned char *cur = smem + (s & 1) * C::STAGE;
+        unsigned char *nxt = smem + ((s + 1) & 1) * C::STAGE;
+        const int64_t m_fill = stage_start(s + 1 + kDwPF);
+#pragma unroll
+        for (int r = 0; r < kNM; ++r) {
+            mfma_item(r, PH);
+#pragma unroll
+            for (int t = r * kNR / kNM; t < (r + 1) * kNR / kNM; ++t) {
+                if (PH == 0) read_item(t, cur, 1, 1);
+                else read_item(t, nxt, 0, 0);
+            }
+#pragma unroll
+            for (int t = r * kMove / kNM; t < (r + 1) * kMove / kNM; ++t) {
+                if (PH == 0) store_item(t, nxt, ra, rb);
+                else load_item(t, m_fill, ra, rb);
+            }
+#pragma unroll
+            for (int d = r * kND / kNM; d < (r + 1) * kND / kNM; ++d) dot_item(d, PH);
+            if (r >= kNM / 2) {
+#pragma unroll
+                for (int c = (r - kNM / 2) * kNC / (kNM / 2); c < (r + 1 - kNM / 2) * kNC / (kNM / 2); ++c)
+                    conv_item(c, 1 - PH);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    const std::integral_constant<int, 0> ph0;
+    const std::integral_constant<int, 1> ph1;
+    auto stage = [&](int s, u32x4 *ra, u32x4 *rb) {
+        step(ph0, s, ra, rb);
+        __syncthreads();
+        step(ph1, s, ra, rb);
+    };
+
+    if (nfull > 0) {
+        // (the scheduling barriers keep the ring loads in slot order: the waits inside the loop are
+        // counted from the youngest load, and the loop head must see the same order on every path)
+#pragma unroll
+        for (int t = 0; t < kMove; ++t) load_item(t, m_begin, ring_a[0], ring_b[0]);
+#pragma unroll
+        for (int t = 0; t < kMove; ++t) store_item(t, smem, ring_a[0], ring_b[0]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int d = 0; d < kDwPF; ++d) {
+#pragma unroll
+            for (int t = 0; t < kMove; ++t) load_item(t, stage_start(d + 1), ring_a[d], ring_b[d]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < kNR; ++t) read_item(t, smem, 0, 0);
+#pragma unroll
+        for (int c = 0; c < kNC; ++c) conv_item(c, 0);
+
+        // The stage loop is unrolled by the ring length so that every ring slot is a fixed set of
+        // registers: stage s+1 sits in slot s % kDwPF, goes to LDS during the first step of stage s,
+        // and the slot is refilled during the second step with stage s+1+kDwPF.
+        // The loop is left from the inside when the stages run out, so that there is one copy of
+        // each of the kDwPF stage bodies and every path to the loop head has all slots in flight.
+        for (int sbase = 0; sbase < nfull; sbase += kDwPF) {
+#pragma unroll
+            for (int d = 0; d < kDwPF; ++d) {
+                stage(sbase + d, ring_a[d], ring_b[d]);
+                if (d + 1 < kDwPF && sbase + d + 1 >= nfull) break;
+            }
+        }
+    }
+    // The rows left over when the slice is not a whole number of stages (only the slice that ends
+    // the tensor can be): one stage outside the pipeline, with every row checked.
+    if (len > int64_t(nfull) * kDwBM) {
+        const int64_t m0 = m_begin + int64_t(nfull) * kDwBM;
+        const int64_t m_last = m_end - 1;
+        __syncthreads();   // the pipeline's last LDS reads are done
 #pragma unroll
         for (int i = 0; i < C::A_CHUNKS; ++i) {
-            int64_t m = m_stage + row_a[i];
-            if (EDGE) m = m < m_end ? m : m_last;
-            ra[i] = *reinterpret_cast<const u32x4 *>(pa[i] + m * N);
+            const int64_t m = m0 + row0_a + i * C::RA;
+            const char *base = dy_bytes + ((m < m_end ? m : m_last) - row0_a) * int64_t(N) * 2;
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(base + voff_a);
+            *reinterpret_cast<u32x4 *>(smem + lds_a0 + i * C::RA * C::PA) = m < m_end ? v : zero4;
         }
 #pragma unroll
         for (int i = 0; i < C::B_CHUNKS; ++i) {
-            int64_t m = m_stage + row_b[i];
-            if (EDGE) m = m < m_end ? m : m_last;
-            rb[i] = *reinterpret_cast<const u32x4 *>(pb[i] + m * K);
+            const int64_t m = m0 + row0_b + i * C::RB;
+            const char *base = xq_bytes + ((m < m_end ? m : m_last) - row0_b) * int64_t(K);
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(base + voff_b);
+            *reinterpret_cast<u32x4 *>(smem + lds_b0 + i * C::RB * C::PB) = m < m_end ? v : zero4;
         }
-    };
-    auto store_stage = [&](unsigned char *st, int64_t m_stage, const u32x4 *ra, const u32x4 *rb, auto edge) {
-        constexpr bool EDGE = decltype(edge)::value;
-#pragma unroll
-        for (int i = 0; i < C::A_CHUNKS; ++i)
-            if (C::A_TOTAL % C::THREADS == 0 || i * C::THREADS + tid < C::A_TOTAL) {
-                const bool ok = ok_a[i] && (!EDGE || m_stage + row_a[i] < m_end);
-                *reinterpret_cast<u32x4 *>(st + lds_a[i]) = ok ? ra[i] : zero4;
-            }
-#pragma unroll
-        for (int i = 0; i < C::B_CHUNKS; ++i)
-            if (C::B_TOTAL % C::THREADS == 0 || i * C::THREADS + tid < C::B_TOTAL) {
-                const bool ok = ok_b[i] && (!EDGE || m_stage + row_b[i] < m_end);
-                *reinterpret_cast<u32x4 *>(st + lds_b[i]) = ok ? rb[i] : zero4;
-            }
-    };
-    const std::true_type edge_yes;
-    const std::false_type edge_no;
-
-    // ---- software pipeline -------------------------------------------------------------------
-    // A stage holds two contraction steps of 16 rows.  While the MFMAs of one step run, the wave
-    // reads (and converts) the fragments of the next step, so LDS latency and the int8 -> binary16
-    // conversion sit in the shadow of the matrix cores; the workgroup barrier falls between the two
-    // MFMA batches of a stage, after this wave's last LDS read of the stage and its LDS writes of the
-    // next one.  The sched_group_barrier calls spell the interleaving out for the scheduler.
-    auto read_a = [&](const unsigned char *st, int ks, v8h af[C::TI]) {
-#pragma unroll
-        for (int i = 0; i < C::TI; ++i) {
-            const unsigned char *p = st + a_off + ks * 16 * C::PA + i * 64;
-            v4h lo = __builtin_bit_cast(v4h, __builtin_amdgcn_ds_read_tr16_b64_v4i16(MESA_LDS3(v4s, p)));
-            v4h hi = __builtin_bit_cast(v4h, __builtin_amdgcn_ds_read_tr16_b64_v4i16(MESA_LDS3(v4s, p + 4 * C::PA)));
-            af[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        }
-    };
-    auto read_b = [&](const unsigned char *st, int ks, v2i braw[C::TJ]) {
-#pragma unroll
-        for (int j = 0; j < C::TJ; ++j)
-            braw[j] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(MESA_LDS3(v2i, st + b_off + ks * 16 * C::PB + j * 32));
-    };
-    // One contraction step on the matrix cores, in two halves.  First half: the row sums of the dy
-    // fragments (every wave keeps them -- 16 dot instructions hidden under the MFMAs -- and only the
-    // owners write them out) and the MFMAs of the upper fragment rows.  Second half: the remaining
-    // MFMAs, with the conversion of the NEXT step's code fragments in their shadow; by then the LDS
-    // reads issued before the first half have long returned, so the in-order instruction stream
-    // never waits on them while the matrix core idles.
-    auto mfma_half = [&](const v8h af[C::TI], const v8h bf[C::TJ], int half) {
-#pragma unroll
-        for (int i = half * (C::TI / 2); i < (half + 1) * (C::TI / 2); ++i)
-#pragma unroll
-            for (int j = 0; j < C::TJ; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[j], acc[i][j], 0, 0, 0);
-    };
-    auto row_sums = [&](const v8h af[C::TI]) {
-        const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
-#pragma unroll
-        for (int i = 0; i < C::TI; ++i)
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                h2 pr = {af[i][2 * k], af[i][2 * k + 1]};
-                s0[i] = __builtin_amdgcn_fdot2(pr, ones, s0[i], false);
-            }
-    };
-    constexpr int kHalfMfma = (C::TI / 2) * C::TJ;
-    auto pace = [&](auto valu_per_mfma) {   // one MFMA, then a few VALU instructions, repeated
-#pragma unroll
-        for (int r = 0; r < kHalfMfma; ++r) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, decltype(valu_per_mfma)::value, 0);
-        }
-    };
-    const std::integral_constant<int, 2> few;
-    const std::integral_constant<int, 5> many;
-
-    if (nstages > 0) {
-        load_stage(m_begin, ring_a[0], ring_b[0], edge_yes);
-        store_stage(smem, m_begin, ring_a[0], ring_b[0], edge_yes);
-    }
-#pragma unroll
-    for (int d = 0; d < kDwPF; ++d)
-        if (d + 1 < nstages) load_stage(m_begin + int64_t(d + 1) * kDwBM, ring_a[d], ring_b[d], edge_yes);
-    __syncthreads();
-
-    v8h af0[C::TI], af1[C::TI], bf0[C::TJ], bf1[C::TJ];
-    v2i braw[C::TJ];
-    if (nstages > 0) {
-        read_a(smem, 0, af0);
-        read_b(smem, 0, braw);
-#pragma unroll
-        for (int j = 0; j < C::TJ; ++j) bf0[j] = codes_to_half8(braw[j]);
-    }
-
-    // One stage.  STEADY: stage s+1+kDwPF exists and lies wholly inside the slice, so nothing here
-    // is conditional.  Otherwise the same steps with their guards (the last kDwPF+1 stages).
-    auto stage = [&](int s, u32x4 *ra, u32x4 *rb, auto steady) {
-        constexpr bool STEADY = decltype(steady)::value;
-        unsigned char *cur = smem + (s & 1) * C::STAGE;
-        unsigned char *nxt = smem + ((s + 1) & 1) * C::STAGE;
-        const bool more = STEADY || s + 1 < nstages;
-        // step 0 of stage s on the matrix cores; step 1's fragments on their way
-        read_a(cur, 1, af1);
-        read_b(cur, 1, braw);
-        row_sums(af0);
-        mfma_half(af0, bf0, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, C::TI * 2 + C::TJ, 0);
-        pace(few);
-        __builtin_amdgcn_sched_barrier(0);
-        mfma_half(af0, bf0, 1);
-#pragma unroll
-        for (int j = 0; j < C::TJ; ++j) bf1[j] = codes_to_half8(braw[j]);
-        pace(many);
-        __builtin_amdgcn_sched_barrier(0);
-        if (STEADY) store_stage(nxt, m_begin + int64_t(s + 1) * kDwBM, ra, rb, edge_no);
-        else if (more) store_stage(nxt, m_begin + int64_t(s + 1) * kDwBM, ra, rb, edge_yes);
-        if (STEADY) load_stage(m_begin + int64_t(s + 1 + kDwPF) * kDwBM, ra, rb, edge_no);
-        else if (s + 1 + kDwPF < nstages) load_stage(m_begin + int64_t(s + 1 + kDwPF) * kDwBM, ra, rb, edge_yes);
         __syncthreads();
-        // step 1 of stage s; step 0 of stage s+1 on its way
-        if (more) {
-            read_a(nxt, 0, af0);
-            read_b(nxt, 0, braw);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+            for (int t = 0; t < kNR; ++t) read_item(t, smem, ks, 0);
+#pragma unroll
+            for (int c = 0; c < kNC; ++c) conv_item(c, 0);
+#pragma unroll
+            for (int d = 0; d < kND; ++d) dot_item(d, 0);
+#pragma unroll
+            for (int r = 0; r < kNM; ++r) mfma_item(r, 0);
         }
-        row_sums(af1);
-        mfma_half(af1, bf1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, C::TI * 2 + C::TJ, 0);
-        pace(few);
-        __builtin_amdgcn_sched_barrier(0);
-        mfma_half(af1, bf1, 1);
-        if (more) {
-#pragma unroll
-            for (int j = 0; j < C::TJ; ++j) bf0[j] = codes_to_half8(braw[j]);
-        }
-        pace(many);
-        __builtin_amdgcn_sched_barrier(0);
-    };
-
-    // The stage loop is unrolled by the ring length so that every ring slot is a fixed set of
-    // registers: stage s+1 sits in slot s % kDwPF, goes to LDS after the first step of stage s, and
-    // the slot is refilled at once with stage s+1+kDwPF.
-    // steady while (s + 1 + kDwPF) * 32 + 32 <= rows of the slice
-    const int full_stages = int((m_end - m_begin) / kDwBM);            // stages with all 32 rows inside
-    const int steady_end = full_stages - 1 - kDwPF > 0 ? ((full_stages - 1 - kDwPF) / kDwPF) * kDwPF : 0;
-    int sbase = 0;
-    for (; sbase < steady_end; sbase += kDwPF) {
-#pragma unroll
-        for (int d = 0; d < kDwPF; ++d) stage(sbase + d, ring_a[d], ring_b[d], edge_yes /* steady */);
-    }
-    for (; sbase < nstages; sbase += kDwPF) {
-#pragma unroll
-        for (int d = 0; d < kDwPF; ++d)
-            if (sbase + d < nstages) stage(sbase + d, ring_a[d], ring_b[d], edge_no /* guarded */);
     }
 
     // partial sums of this slice: lane l, register v of a 32x32 tile -> row 8*(v/4) + 4*(l/32) + v%4, column l%32
@@ -324,15 +324,15 @@ __global__ __launch_bounds__(WGN * WGK * 64, 1) void k_dw_f16(const int8_t *__re
             const int kk = kk0 + wk * C::WK + j * 32 + col_l;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int n = n0 + wn * C::WN + i * 32 + (v >> 2) * 8 + row_l + (v & 3);
+                const int n = n0 + wn * C::WN + a_block(i) * 32 + (v >> 2) * 8 + row_l + (v & 3);
                 if (n < N && kk < K) Ps[int64_t(n) * K + kk] = acc[i][j][v];
             }
         }
     if (do_s0) {
 #pragma unroll
-        for (int i = 0; i < C::TI; ++i) {
+        for (int i = 0; i < C::TIS; ++i) {
             float tot = s0[i] + __shfl_xor(s0[i], 32, 64);   // the two halves of the contraction slots
-            const int n = n0 + wn * C::WN + i * 32 + col_l;
+            const int n = n0 + wn * C::WN + a_block(i) * 32 + col_l;
             if (lane < 32 && n < N) S0[int64_t(split) * N + n] = tot;
         }
     }
