@@ -252,4 +252,24 @@ template <int WIDTH> __device__ __forceinline__ float lanes_sum(float v)
     return v;
 }
 
+// The same sum over aligned groups of WIDTH lanes, every lane receiving it, with the first four
+// levels done by data-parallel-primitive lane swaps inside the adder instruction (pairs, quads,
+// mirrored halves of 8 and of 16: after each level both partners hold the same value, so a mirror
+// is as good as an exchange) and only the levels across 16-lane rows through the LDS crossbar.
+template <int CTRL> __device__ __forceinline__ float dpp_move(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+template <int WIDTH> __device__ __forceinline__ float lanes_sum_dpp(float v)
+{
+    static_assert(WIDTH == 4 || WIDTH == 8 || WIDTH == 16 || WIDTH == 32 || WIDTH == 64, "aligned power-of-two lane groups");
+    v += dpp_move<0xB1>(v);                      // quad_perm [1,0,3,2]
+    v += dpp_move<0x4E>(v);                      // quad_perm [2,3,0,1]
+    if (WIDTH >= 8) v += dpp_move<0x141>(v);     // row_half_mirror
+    if (WIDTH >= 16) v += dpp_move<0x140>(v);    // row_mirror
+    if (WIDTH >= 32) v += __shfl_xor(v, 16, 64);
+    if (WIDTH >= 64) v += __shfl_xor(v, 32, 64);
+    return v;
+}
+
 }  // namespace mesa

@@ -2,13 +2,16 @@
 //   xn = (x_hat - mean)*rstd,  g = dy*gamma,
 //   dx = rstd*(g - mean_j(g) - xn*mean_j(g*xn)),   dgamma_j = sum_rows dy*xn,  dbeta_j = sum_rows dy.
 //
-// A wave (a whole workgroup when a row is longer than 1024 elements) takes tiles of R whole rows
-// and reads them flat as 8-element vectors; codes and dy stay in registers between the reduction
-// pass and the output pass, two partial sums per vector go through LDS (16 lanes per row add them
-// in a fixed order); waves owning their own tiles need no workgroup barrier.  A thread
-// meets the same columns in every tile, so it keeps its share of the column sums in registers
-// for the whole kernel; they are combined per workgroup in LDS, written as partials, and a small
-// second kernel adds the partials of all workgroups -- fixed order throughout, no float atomics.
+// Rows of up to 1024 elements (the usual case): a row lives in an aligned group of 8..64 lanes of
+// one wave, one or two 8-element vectors per lane, so the two row means are lane-group sums taken
+// inside the adder instructions -- no LDS, no barrier, nothing between the loads and the stores
+// but arithmetic.  A wave has several rows in flight and a workgroup walks a contiguous run of
+// rows.  A lane meets the same columns in every row, so it keeps its share of the column sums
+// (dgamma, dbeta) in registers for the whole kernel; they are combined per workgroup in LDS,
+// written as partials, and a small second kernel adds the partials of all workgroups -- fixed
+// order throughout, no float atomics.
+// Longer rows (up to 4096 elements): a workgroup takes one row at a time, reads it flat as
+// 8-element vectors, and the row sums go through LDS.
 #include <hip/hip_runtime.h>
 
 #include "api_util.hpp"
@@ -19,7 +22,9 @@ namespace mesa {
 constexpr int kLnU = 2;                 // vectors per thread in a tile
 constexpr int kLnGridCap = 1024;
 constexpr int kLnMaxD = kThreads * kLnU * kVec;   // 4096: a row must fit a workgroup tile
-constexpr int kLnMaxGroups = kLnMaxD / kVec;      // (D/G) % 8 == 0
+constexpr int kLnRowsInFlight = 2;      // wave-row kernel: row groups a wave has in flight
+// ... and the workgroups per CU its register budget is set for (two blocks of rows live at a time)
+constexpr int ln_rows_wg_per_cu(size_t elem_bytes, int vpl) { return vpl == 1 ? (elem_bytes == 2 ? 4 : 3) : 2; }
 constexpr int kLnFinThreads = 1024;               // finalize: 32 columns x 32 slices of the workgroup list
 
 template <int TPT> __device__ __forceinline__ void ln_sync()
@@ -39,7 +44,141 @@ __device__ __forceinline__ void ln_opaque(u32x2 &a, Store<float>::raw_t &b)
     asm volatile("" : "+v"(a), "+v"(b.lo), "+v"(b.hi));
 }
 
-// TPT threads (one wave when R whole rows fit 128 vectors, else the workgroup) own a tile of R rows.
+// Rows inside a wave.  LPR lanes per row (a power of two), VPL vectors per lane: lane l of a row's
+// group holds the vectors l, l + LPR, ... of the row.  RPW = 64/LPR rows per wave at a time, U such
+// groups in flight; the four waves of a workgroup take neighbouring row groups, so that what the
+// workgroup has in flight is one contiguous block of rows, and the workgroups stride over the blocks.
+template <typename T, int LPR, int VPL>
+__global__ __launch_bounds__(kThreads, ln_rows_wg_per_cu(sizeof(T), VPL)) void k_layernorm_bwd_rows(const int8_t *__restrict__ xq, const void *dy, void *dx,
+                                                                    const void *__restrict__ gamma, const float *__restrict__ mean,
+                                                                    const float *__restrict__ rstd, const float *__restrict__ alpha,
+                                                                    const float *__restrict__ beta, int64_t M, uint32_t D,
+                                                                    FastDiv div_vpg, float inv_D,
+                                                                    float *__restrict__ part)
+{
+    constexpr int RPW = 64 / LPR;
+    constexpr int U = kLnRowsInFlight;
+    constexpr int kWaves = kThreads / 64;
+    constexpr int kBlockRows = kWaves * U * RPW;     // rows a workgroup has in flight
+    __shared__ float colG[kLnMaxD], colB[kLnMaxD];   // [wave][row slot][D]: kWaves * RPW * D <= 4096
+
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const uint32_t sub = lane / LPR, l = lane % LPR;
+    const uint32_t vpr = D / kVec;
+
+    uint32_t col[VPL];
+    bool act[VPL];
+    float gam[VPL][8], accG[VPL][8], accB[VPL][8];
+    float2 prm[VPL];
+#pragma unroll
+    for (int k = 0; k < VPL; ++k) {
+        const uint32_t cv = k * LPR + l;
+        act[k] = cv < vpr;
+        col[k] = cv * kVec;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { gam[k][j] = 0.0f; accG[k][j] = 0.0f; accB[k][j] = 0.0f; }
+        prm[k] = make_float2(0.0f, 0.0f);
+        if (act[k]) {
+            Store<T>::unpack(Store<T>::load(gamma, col[k]), gam[k]);
+            const uint32_t g = fastdiv(cv, div_vpg);
+            prm[k] = make_float2(alpha[g] / 255.0f, beta[g]);
+        }
+    }
+
+    // One block of rows is in registers while the previous one is worked on: the loads of block
+    // i+1 are issued before the arithmetic, the lane-group sums and the stores of block i.
+    // Lanes without a row or a vector work on zeros: dy = 0 adds nothing to any sum, and only the
+    // loads and the stores are predicated.
+    struct Block {
+        u32x2 cq[U][VPL];
+        typename Store<T>::raw_t cd[U][VPL];
+        float mu[U], rs[U];
+    };
+    const typename Store<T>::raw_t zero_d = Store<T>::pack((const float[8]){0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f});
+    auto load_block = [&](int64_t base, Block &blk) {
+#pragma unroll
+        for (int p = 0; p < U; ++p) {
+            const int64_t row = base + int64_t((p * kWaves + wave) * RPW + sub);
+            const bool ok = row < M;
+            blk.mu[p] = 0.0f;
+            blk.rs[p] = 0.0f;
+            if (ok) { blk.mu[p] = mean[row]; blk.rs[p] = rstd[row]; }
+#pragma unroll
+            for (int k = 0; k < VPL; ++k) {
+                blk.cq[p][k] = u32x2{0u, 0u};
+                blk.cd[p][k] = zero_d;
+                if (ok && act[k]) {
+                    const int64_t e = row * D + col[k];
+                    blk.cq[p][k] = nt_load<u32x2>(xq + e);
+                    blk.cd[p][k] = Nt<T>::load(dy, e);
+                }
+            }
+        }
+    };
+    const int64_t stride = int64_t(gridDim.x) * kBlockRows;
+    int64_t base = int64_t(blockIdx.x) * kBlockRows;
+    Block cur, nxt;
+    if (base < M) load_block(base, cur);
+    for (; base < M; base += stride) {
+        load_block(base + stride, nxt);    // past the last block: every row fails its check, nothing is read
+#pragma unroll
+        for (int p = 0; p < U; ++p) {
+            const int64_t row = base + int64_t((p * kWaves + wave) * RPW + sub);
+            const bool ok = row < M;
+            float xn[VPL][8], gg[VPL][8];
+            float s1 = 0.0f, s2 = 0.0f;
+#pragma unroll
+            for (int k = 0; k < VPL; ++k) {
+                float y[8], d[8];
+                codes_to_float(cur.cq[p][k], y);
+                Store<T>::unpack(cur.cd[p][k], d);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    xn[k][j] = (fmaf(y[j], prm[k].x, prm[k].y) - cur.mu[p]) * cur.rs[p];
+                    gg[k][j] = d[j] * gam[k][j];
+                    s1 += gg[k][j];
+                    s2 = fmaf(gg[k][j], xn[k][j], s2);
+                    accG[k][j] = fmaf(d[j], xn[k][j], accG[k][j]);
+                    accB[k][j] += d[j];
+                }
+            }
+            const float c1 = lanes_sum_dpp<LPR>(s1) * inv_D;
+            const float c2 = lanes_sum_dpp<LPR>(s2) * inv_D;
+#pragma unroll
+            for (int k = 0; k < VPL; ++k) {
+                float o[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) o[j] = cur.rs[p] * (gg[k][j] - c1 - xn[k][j] * c2);
+                if (ok && act[k]) Nt<T>::store(dx, row * D + col[k], Store<T>::pack(o));
+            }
+        }
+        cur = nxt;
+    }
+
+    // column sums of this workgroup: slot (wave, sub) holds what its lanes gathered
+#pragma unroll
+    for (int k = 0; k < VPL; ++k) {
+        if (act[k]) {
+            const uint32_t o = (wave * RPW + sub) * D + col[k];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                colG[o + j] = accG[k][j];
+                colB[o + j] = accB[k][j];
+            }
+        }
+    }
+    __syncthreads();
+    float *pg = part + int64_t(blockIdx.x) * 2 * D;
+    for (uint32_t c = threadIdx.x; c < D; c += kThreads) {
+        float sg = 0.0f, sb = 0.0f;
+#pragma unroll
+        for (uint32_t r = 0; r < kWaves * RPW; ++r) { sg += colG[r * D + c]; sb += colB[r * D + c]; }
+        pg[c] = sg;
+        pg[D + c] = sb;
+    }
+}
+
+// Long rows.  TPT threads (the workgroup) own a tile of R rows (R = 1 for rows this long).
 template <typename T, int TPT>
 __global__ __launch_bounds__(kThreads, 4) void k_layernorm_bwd(const int8_t *__restrict__ xq, const void *dy, void *dx,
                                                                const void *__restrict__ gamma, const float *__restrict__ mean,
@@ -213,32 +352,40 @@ __global__ __launch_bounds__(kLnFinThreads) void k_layernorm_finalize(const floa
 }
 
 struct LnPlan {
-    bool wave_tiles;
-    int64_t R, tiles;
+    bool in_wave;          // rows of at most 128 vectors: the wave-row kernel
+    int lpr, vpl;          // its lanes per row and vectors per lane
+    int64_t R, tiles;      // long rows: rows per workgroup tile, number of tiles
     int grid;
 };
 
-static LnPlan ln_plan(int64_t M, int64_t D)
+static LnPlan ln_plan(int64_t M, int64_t D, mesa_dtype dt)
 {
-    LnPlan p;
+    LnPlan p{};
     const int64_t vpr = D / kVec;
-    p.wave_tiles = vpr <= 64 * kLnU;
-    const int64_t cap = (p.wave_tiles ? 64 : kThreads) * int64_t(kLnU);   // vectors per tile
+    p.in_wave = vpr <= 128;
+    if (p.in_wave) {
+        p.lpr = vpr <= 8 ? 8 : vpr <= 16 ? 16 : vpr <= 32 ? 32 : 64;
+        p.vpl = vpr <= 64 ? 1 : 2;
+        const int64_t block_rows = (kThreads / 64) * kLnRowsInFlight * (64 / p.lpr);   // rows a workgroup has in flight
+        const int64_t wgs = ceil_div(M, block_rows);
+        const int64_t resident = 256 * ln_rows_wg_per_cu(dt == MESA_F16 ? 2 : 4, p.vpl);   // one round of workgroups
+        p.grid = int(wgs < resident ? wgs : resident);
+        return p;
+    }
+    const int64_t cap = kThreads * int64_t(kLnU);   // vectors per tile
     p.R = cap / vpr;
     if (p.R > M) p.R = M;
     if (p.R < 1) p.R = 1;
     p.tiles = ceil_div(M, p.R);
-    const int64_t teams = p.wave_tiles ? kThreads / 64 : 1;
-    const int64_t wgs = ceil_div(p.tiles, teams);
-    p.grid = int(wgs < kLnGridCap ? wgs : kLnGridCap);
+    p.grid = int(p.tiles < kLnGridCap ? p.tiles : kLnGridCap);
     return p;
 }
 
 size_t layernorm_ws_bytes(int64_t M, int64_t D)
 {
     if (M <= 0 || D <= 0 || D > kLnMaxD || D % kVec != 0) return 16;
-    LnPlan p = ln_plan(M, D);
-    return size_t(p.grid) * 2 * size_t(D) * sizeof(float);
+    const int g16 = ln_plan(M, D, MESA_F16).grid, g32 = ln_plan(M, D, MESA_F32).grid;   // enough for either type
+    return size_t(g16 > g32 ? g16 : g32) * 2 * size_t(D) * sizeof(float);
 }
 
 }  // namespace mesa
@@ -259,17 +406,33 @@ extern "C" MESA_EXPORT mesa_status mesa_layernorm_bwd_q(const int8_t *xq, int64_
         return MESA_ERR_INVALID_ARG;
     if (D % kVec != 0 || (D / G) % kVec != 0 || D > kLnMaxD) return MESA_ERR_UNSUPPORTED;
     if (!ws || !aligned16(ws) || ws_bytes < layernorm_ws_bytes(M, D)) return MESA_ERR_WORKSPACE;
-    const LnPlan p = ln_plan(M, D);
+    const LnPlan p = ln_plan(M, D, dt);
     FastDiv dvpr = make_fastdiv(uint32_t(D / kVec)), dvpg = make_fastdiv(uint32_t(D / G / kVec));
     hipStream_t s = static_cast<hipStream_t>(stream);
     float *part = static_cast<float *>(ws);
     const float inv_D = 1.0f / float(D);
-#define MESA_LAUNCH_LN(T, TPT_) \
-    hipLaunchKernelGGL((k_layernorm_bwd<T, TPT_>), dim3(p.grid), dim3(kThreads), 0, s, xq, dy, dx, gamma, mean, rstd, alpha, \
+#define MESA_LAUNCH_ROWS(T, LPR_, VPL_) \
+    hipLaunchKernelGGL((k_layernorm_bwd_rows<T, LPR_, VPL_>), dim3(p.grid), dim3(kThreads), 0, s, xq, dy, dx, gamma, mean, rstd, \
+                       alpha, beta, M, uint32_t(D), dvpg, inv_D, part)
+#define MESA_LAUNCH_ROWS_T(T) \
+    do { \
+        if (p.vpl == 2) MESA_LAUNCH_ROWS(T, 64, 2); \
+        else if (p.lpr == 64) MESA_LAUNCH_ROWS(T, 64, 1); \
+        else if (p.lpr == 32) MESA_LAUNCH_ROWS(T, 32, 1); \
+        else if (p.lpr == 16) MESA_LAUNCH_ROWS(T, 16, 1); \
+        else MESA_LAUNCH_ROWS(T, 8, 1); \
+    } while (0)
+#define MESA_LAUNCH_LN(T) \
+    hipLaunchKernelGGL((k_layernorm_bwd<T, kThreads>), dim3(p.grid), dim3(kThreads), 0, s, xq, dy, dx, gamma, mean, rstd, alpha, \
                        beta, M, uint32_t(D), uint32_t(p.R), p.tiles, uint32_t(G), dvpr, dvpg, inv_D, part)
-    if (dt == MESA_F16) { if (p.wave_tiles) MESA_LAUNCH_LN(_Float16, 64); else MESA_LAUNCH_LN(_Float16, kThreads); }
-    else { if (p.wave_tiles) MESA_LAUNCH_LN(float, 64); else MESA_LAUNCH_LN(float, kThreads); }
+    if (p.in_wave) {
+        if (dt == MESA_F16) MESA_LAUNCH_ROWS_T(_Float16); else MESA_LAUNCH_ROWS_T(float);
+    } else {
+        if (dt == MESA_F16) MESA_LAUNCH_LN(_Float16); else MESA_LAUNCH_LN(float);
+    }
 #undef MESA_LAUNCH_LN
+#undef MESA_LAUNCH_ROWS_T
+#undef MESA_LAUNCH_ROWS
     hipLaunchKernelGGL(k_layernorm_finalize, dim3(unsigned(ceil_div(D, 32))), dim3(kLnFinThreads), 0, s, part, p.grid,
                        uint32_t(D), dgamma, dbeta);
     return launch_status();

@@ -228,6 +228,62 @@ def test_config5_long_sequence_shape_reduced(M):
     print(block_parity(M, spec, modes=("stochastic",)))
 
 
+def _ln_case(M, spec, G):
+    """LayerNorm backward alone on one token matrix: dx, dgamma, dbeta against the oracle."""
+    Mr, D = spec.tokens, spec.dim
+    lay = (Mr, G, D // G)
+    draws = [W.token_matrix(spec, "ln", d, "cuda") for d in range(2)]
+    a, b, ra, rb = run_params(M, draws, lay, spec.lam)
+    x = draws[-1]
+    q = torch.empty(x.numel(), dtype=torch.int8, device="cuda")
+    M.mesa_quantize_headwise(x, lay, a, b, q, M.ROUND_STOCHASTIC, 5, 0)
+    rq = q.cpu().numpy()
+    mean, rstd = W.layernorm_stats(x)
+    gamma = W.layernorm_gamma(spec, "cuda")
+    dy = W.upstream_grad(spec, "dy_ln", (Mr, D), "cuda")
+    dx = torch.empty_like(dy)
+    dg = torch.empty(D, device="cuda")
+    db = torch.empty(D, device="cuda")
+    ws = ws_for(M, M.OP_LAYERNORM_BWD_Q, Mr, D, G)
+    M.mesa_layernorm_bwd_q(q, Mr, D, G, a, b, mean, rstd, gamma, dy, dx, dg, db, ws)
+    rdx, rdg, rdb = R.layernorm_bwd_q(rq, Mr, D, G, ra, rb, mean.cpu().numpy(), rstd.cpu().numpy(),
+                                      gamma.cpu().numpy(), dy.cpu().numpy())
+    return {"dx": relerr(dx.cpu().numpy(), rdx), "dgamma": relerr(dg.cpu().numpy(), rdg), "dbeta": relerr(db.cpu().numpy(), rdb)}
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.float16], ids=["f32", "f16"])
+@pytest.mark.parametrize("D,G,tokens", [(8, 1, 37), (48, 3, 57), (128, 4, 333), (192, 3, 1000), (384, 6, 1579), (512, 8, 130),
+                                        (768, 12, 517), (1024, 16, 259), (1032, 3, 77), (2048, 16, 35), (4096, 8, 19)])
+def test_layernorm_bwd_every_row_length_class(M, D, G, tokens, dtype):
+    """Rows of 1..128 vectors go through lane groups of 8, 16, 32 or 64 lanes (one or two vectors per lane),
+    longer rows through workgroup tiles; ragged row counts in every class."""
+    spec = W.small_case(dtype, seed=D + tokens, B=1, H=G, N=tokens, D=D, mlp=D)
+    rep = _ln_case(M, spec, G)
+    assert all(v <= TOL[dtype] for v in rep.values()), rep
+
+
+@pytest.mark.parametrize("Mr,K,N", [(31, 16, 8), (32, 48, 24), (97, 128, 264), (100 * 32, 384, 256), (101 * 32 + 5, 256, 520),
+                                    (4 * 32 * 7 + 13, 784, 136), (9000, 272, 1000)])
+def test_linear_dw_ragged_shapes(M, Mr, K, N):
+    """Slices of 1, 2 and 3k stages, a ragged last stage, K and N that leave partial tiles; binary16."""
+    H = 1 if K % 3 else 3
+    spec = W.small_case(torch.float16, seed=Mr + K, B=1, H=H, N=Mr, D=K, mlp=N)
+    lay = (Mr, H, K // H)
+    draws = [W.token_matrix(spec, "lin", d, "cuda", width=K) for d in range(2)]
+    a, b, ra, rb = run_params(M, draws, lay, spec.lam)
+    q = torch.empty(Mr * K, dtype=torch.int8, device="cuda")
+    M.mesa_quantize_headwise(draws[-1], lay, a, b, q, M.ROUND_STOCHASTIC, 9, 0)
+    rq = q.cpu().numpy()
+    dy = W.upstream_grad(spec, "dy_lin", (Mr, N), "cuda")
+    dW = torch.empty((N, K), device="cuda")
+    dbias = torch.empty(N, device="cuda")
+    ws = ws_for(M, M.OP_LINEAR_DW_Q, Mr, K, N, torch.float16)
+    M.mesa_linear_dw_q(q, Mr, K, H, a, b, dy, N, dW, dbias, ws)
+    rW, rb_ = R.linear_dw_q(rq, Mr, K, H, ra, rb, dy.cpu().numpy(), N)
+    rep = {"dW": relerr(dW.cpu().numpy().astype(np.float64), rW), "db": relerr(dbias.cpu().numpy(), rb_)}
+    assert all(v <= TOL[torch.float16] for v in rep.values()), rep
+
+
 def test_empty_inputs_are_a_no_op(M):
     z = torch.empty(0, device="cuda")
     a = torch.ones(3, device="cuda")
