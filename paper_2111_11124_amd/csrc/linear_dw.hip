@@ -52,11 +52,11 @@ template <int BN, int BK, int WGN, int WGK> struct DwCfg {
     static constexpr int B_CPR = BK / 16;
     static constexpr int A_TOTAL = kDwBM * A_CPR, B_TOTAL = kDwBM * B_CPR;
     static constexpr int A_CHUNKS = A_TOTAL / THREADS;  // chunks a thread moves per stage
-    static constexpr int B_CHUNKS = B_TOTAL / THREADS;
-    static constexpr int RA = THREADS / A_CPR;          // rows between a thread's successive chunks
-    static constexpr int RB = THREADS / B_CPR;
-    static_assert(A_TOTAL % THREADS == 0 && B_TOTAL % THREADS == 0 && THREADS % A_CPR == 0 && THREADS % B_CPR == 0,
-                  "every thread moves whole rows' worth of chunks, the same column each time");
+    static constexpr int RA = THREADS / A_CPR;          // dy: rows between a thread's successive chunks (same column)
+    static constexpr int TPR_B = THREADS / kDwBM;       // codes: threads per row, each taking every TPR_B-th chunk of it
+    static constexpr int B_CHUNKS = B_CPR / TPR_B;
+    static_assert(A_TOTAL % THREADS == 0 && THREADS % A_CPR == 0 && THREADS % kDwBM == 0 && B_CPR % TPR_B == 0,
+                  "every thread moves the same number of chunks, at fixed strides");
     static_assert(TI % WGK == 0, "the row sums are shared out among the waves of a row");
     static_assert(WN % 64 == 0 && WK % 32 == 0, "wave tile: an even number of 32-row MFMA tiles by whole 32-column tiles");
     static_assert(2 * STAGE <= 64 * 1024, "two stages must fit the default dynamic LDS limit");
@@ -124,18 +124,24 @@ __global__ __launch_bounds__(WGN * WGK * 64, 1) void k_dw_f16(const int8_t *__re
 
     // global -> register prefetch ring: stage s+1 .. s+kDwPF are in flight while stage s is multiplied,
     // enough bytes per CU to cover the latency of L2 / memory-side-cache hits at the rate MFMA consumes them.
-    // A thread moves the same 16-byte column chunk of rows row0, row0 + RA, row0 + 2 RA, ... of every
-    // stage, so one 32-bit offset per operand serves all its loads (the row of the item and the stage
-    // go into the uniform base address) and one LDS address all its writes.  Columns outside N or K
+    // Of dy a thread moves the same 16-byte column chunk of rows row0, row0 + RA, row0 + 2 RA, ... of
+    // every stage, so one 32-bit offset serves all its loads (the row of the item and the stage go into
+    // the uniform base address) and one LDS address all its writes; of the codes it moves every
+    // TPR_B-th chunk of one row (an offset per chunk, since each may be clamped).  Columns outside N or K
     // are read from column 0 instead and left as they are: row n of the product depends on column n
     // of dy only and column k on column k of the codes, and those rows and columns are never written.
     u32x4 ring_a[kDwPF][C::A_CHUNKS], ring_b[kDwPF][C::B_CHUNKS];
     const int row0_a = tid / C::A_CPR, col_a = n0 + (tid % C::A_CPR) * 8;
-    const int row0_b = tid / C::B_CPR, col_b = kk0 + (tid % C::B_CPR) * 16;
+    const int row_b = tid / C::TPR_B, cb = tid % C::TPR_B;
     const uint32_t voff_a = (uint32_t(row0_a) * uint32_t(N) + uint32_t(col_a < N ? col_a : 0)) * 2u;   // bytes
-    const uint32_t voff_b = uint32_t(row0_b) * uint32_t(K) + uint32_t(col_b < K ? col_b : 0);
+    uint32_t voff_b[C::B_CHUNKS];
+#pragma unroll
+    for (int i = 0; i < C::B_CHUNKS; ++i) {
+        const int col_b = kk0 + (cb + i * C::TPR_B) * 16;
+        voff_b[i] = uint32_t(row_b) * uint32_t(K) + uint32_t(col_b < K ? col_b : 0);
+    }
     const int lds_a0 = row0_a * C::PA + (tid % C::A_CPR) * 16;
-    const int lds_b0 = C::A_STAGE + row0_b * C::PB + (tid % C::B_CPR) * 16;
+    const int lds_b0 = C::A_STAGE + row_b * C::PB + cb * 16;
     const char *dy_bytes = reinterpret_cast<const char *>(dy);
     const char *xq_bytes = reinterpret_cast<const char *>(xq);
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
@@ -152,13 +158,13 @@ __global__ __launch_bounds__(WGN * WGK * 64, 1) void k_dw_f16(const int8_t *__re
             ra[t] = *reinterpret_cast<const u32x4 *>(base + voff_a);
         } else {
             const int i = t - C::A_CHUNKS;
-            const char *base = xq_bytes + (m_stage + i * C::RB) * int64_t(K);
-            rb[i] = *reinterpret_cast<const u32x4 *>(base + voff_b);
+            const char *base = xq_bytes + m_stage * int64_t(K);
+            rb[i] = *reinterpret_cast<const u32x4 *>(base + voff_b[i]);
         }
     };
     auto store_item = [&](int t, unsigned char *st, const u32x4 *ra, const u32x4 *rb) {
         if (t < C::A_CHUNKS) *reinterpret_cast<u32x4 *>(st + lds_a0 + t * C::RA * C::PA) = ra[t];
-        else *reinterpret_cast<u32x4 *>(st + lds_b0 + (t - C::A_CHUNKS) * C::RB * C::PB) = rb[t - C::A_CHUNKS];
+        else *reinterpret_cast<u32x4 *>(st + lds_b0 + (t - C::A_CHUNKS) * C::TPR_B * 16) = rb[t - C::A_CHUNKS];
     };
     auto stage_start = [&](int s) {
         const int64_t m = m_begin + int64_t(s) * kDwBM;
@@ -295,10 +301,10 @@ __global__ __launch_bounds__(WGN * WGK * 64, 1) void k_dw_f16(const int8_t *__re
         }
 #pragma unroll
         for (int i = 0; i < C::B_CHUNKS; ++i) {
-            const int64_t m = m0 + row0_b + i * C::RB;
-            const char *base = xq_bytes + ((m < m_end ? m : m_last) - row0_b) * int64_t(K);
-            const u32x4 v = *reinterpret_cast<const u32x4 *>(base + voff_b);
-            *reinterpret_cast<u32x4 *>(smem + lds_b0 + i * C::RB * C::PB) = m < m_end ? v : zero4;
+            const int64_t m = m0 + row_b;
+            const char *base = xq_bytes + ((m < m_end ? m : m_last) - row_b) * int64_t(K);
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(base + voff_b[i]);
+            *reinterpret_cast<u32x4 *>(smem + lds_b0 + i * C::TPR_B * 16) = m < m_end ? v : zero4;
         }
         __syncthreads();
 #pragma unroll
@@ -426,7 +432,7 @@ __global__ __launch_bounds__(kThreads) void k_dw_reduce(const float *__restrict_
 }
 
 struct DwPlan {
-    int variant;   // 0: 256x256 tile, 8 waves; 1: 256x128 tile, 4 waves; 2: binary32
+    int variant;   // binary16 tiles (n x k): 0: 256 x 256, 1: 256 x 128; 2: binary32
     int bn, bk, tiles_n, tiles_k, splits, grid;
     int64_t rows_per_split;
 };
@@ -435,9 +441,10 @@ static DwPlan dw_plan(int64_t M, int64_t K, int64_t N, mesa_dtype dt)
 {
     DwPlan p;
     if (dt == MESA_F16) {
-        p.variant = (K % 256 == 0 || K > 1024) ? 0 : 1;
-        p.bn = 256;
-        p.bk = p.variant == 0 ? 256 : 128;
+        // 256-wide k tiles unless they would waste much of the last one.  (A 128 x 384 tile for K = 384 was
+        // measured too: no faster per MFMA, and its 21 slices instead of 14 cost more partial-sum traffic.)
+        if (K % 256 == 0 || K > 1024) { p.variant = 0; p.bn = 256; p.bk = 256; }
+        else { p.variant = 1; p.bn = 256; p.bk = 128; }
     } else {
         p.variant = 2;
         p.bn = kDw32BN;

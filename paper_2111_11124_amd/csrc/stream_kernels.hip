@@ -273,8 +273,9 @@ __global__ __launch_bounds__(kThreads) void k_minmax_partial(const void *__restr
 }
 
 // Eq. (6)-(7) for one group from its extrema: each product, difference and sum rounded on its own.
-__device__ __forceinline__ void ema_update(float mn, float mx, float *alpha, float *beta, uint32_t g, float lambda,
-                                           int first_call)
+// (alpha_old, beta_old: the running estimates as they were, read by the caller ahead of time)
+__device__ __forceinline__ void ema_update(float mn, float mx, float alpha_old, float beta_old, float *alpha, float *beta,
+                                           uint32_t g, float lambda, int first_call)
 {
     mn = mn + 0.0f;  // -0.0 -> +0.0
     mx = mx + 0.0f;
@@ -283,11 +284,11 @@ __device__ __forceinline__ void ema_update(float mn, float mx, float *alpha, flo
         alpha[g] = range;
         beta[g] = mn;
     } else {
-        float a = lambda * alpha[g];
+        float a = lambda * alpha_old;
         float b = 1.0f - lambda;
         float c = b * range;
         alpha[g] = a + c;
-        float e = lambda * beta[g];
+        float e = lambda * beta_old;
         float f = b * mn;
         beta[g] = e + f;
     }
@@ -299,6 +300,7 @@ __global__ __launch_bounds__(kThreads) void k_ema_finalize(const float *__restri
 {
     __shared__ float smn[kThreads / 64], smx[kThreads / 64];
     const uint32_t g = blockIdx.x;
+    const float alpha_old = alpha[g], beta_old = beta[g];   // in flight together with the partial extrema
     float mn = __builtin_inff(), mx = -__builtin_inff();
     for (int w = threadIdx.x; w < nwg; w += kThreads) {
         mn = vmin(mn, part[int64_t(w) * 2 * groups + g]);
@@ -314,7 +316,7 @@ __global__ __launch_bounds__(kThreads) void k_ema_finalize(const float *__restri
     if (threadIdx.x == 0) {
 #pragma unroll
         for (int w = 1; w < kThreads / 64; ++w) { mn = vmin(mn, smn[w]); mx = vmax(mx, smx[w]); }
-        ema_update(mn, mx, alpha, beta, g, lambda, first_call);
+        ema_update(mn, mx, alpha_old, beta_old, alpha, beta, g, lambda, first_call);
     }
 }
 
