@@ -9,6 +9,8 @@
 // where 16 lanes per row add them in a fixed order.  One HBM read of codes and dy, one write of dx.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "api_util.hpp"
 #include "common.hpp"
 
@@ -16,6 +18,7 @@ namespace mesa {
 
 constexpr int kSmU = 4;             // vectors per thread in a tile
 constexpr int kSmMaxHeads = 1024;
+constexpr int kSmWgPerCu = 3;       // occupancy the kernel's register budget is set for
 
 // Synchronisation among the TPT threads that share a tile: a workgroup barrier, or -- when a tile
 // belongs to one wave -- only an ordering of that wave's own LDS traffic (its lanes run in lockstep).
@@ -39,9 +42,19 @@ __device__ __forceinline__ void opaque(u32x2 &a, Store<float>::raw_t &b)
     asm volatile("" : "+v"(a), "+v"(b.lo), "+v"(b.hi));
 }
 
+// Four codes (the bytes of w, stored as x_bar - 128) as two binary16 pairs holding x_bar itself:
+// 0x6400 | byte is 1024 + byte exactly, and the subtraction of 1024 is exact too.
+__device__ __forceinline__ void codes_to_h2(uint32_t w, h2 &lo, h2 &hi)
+{
+    const h2 k1024 = {(_Float16)1024.0f, (_Float16)1024.0f};
+    const uint32_t x = w ^ 0x80808080u;
+    lo = as_h2(__builtin_amdgcn_perm(0x64646464u, x, 0x04010400u)) - k1024;   // bytes 0, 1
+    hi = as_h2(__builtin_amdgcn_perm(0x64646464u, x, 0x04030402u)) - k1024;   // bytes 2, 3
+}
+
 // TPT threads (one wave, or the whole workgroup for long rows) own a tile of up to TPT*4 vectors.
 template <typename T, int TPT>
-__global__ __launch_bounds__(kThreads, 4) void k_softmax_bwd(const int8_t *__restrict__ yq, const void *dy, void *dx,
+__global__ __launch_bounds__(kThreads, kSmWgPerCu) void k_softmax_bwd(const int8_t *__restrict__ yq, const void *dy, void *dx,
                                                           int64_t total_rows, uint32_t cols, uint32_t R, int64_t tiles,
                                                           FastDiv div_cols, FastDiv div_rows, FastDiv div_heads,
                                                           const float *__restrict__ alpha, const float *__restrict__ beta)
@@ -59,6 +72,23 @@ __global__ __launch_bounds__(kThreads, 4) void k_softmax_bwd(const int8_t *__res
     const uint32_t tid = threadIdx.x % TPT;
     float *pa = PA[team], *pb = PB[team], *rd = rowD[team];
 
+    // Every tile has the same shape (R whole rows, a whole number of vectors), so where this thread's
+    // vectors lie in their rows is the same in every tile: the row r1 a vector starts in, how many of
+    // its elements belong to that row (nb; the rest to the next row), and -- for the binary16 fast
+    // path -- bit masks of the halves that belong to the next row.
+    constexpr bool kHalf = std::is_same<T, _Float16>::value;
+    uint32_t r1[kSmU], nb[kSmU];
+    uint32_t maskB[kSmU][4];
+#pragma unroll
+    for (int u = 0; u < kSmU; ++u) {
+        const uint32_t le = (u * TPT + tid) * kVec;
+        r1[u] = fastdiv(le, div_cols);
+        nb[u] = (r1[u] + 1) * cols - le;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            maskB[u][k] = (uint32_t(2 * k) >= nb[u] ? 0x0000FFFFu : 0u) | (uint32_t(2 * k + 1) >= nb[u] ? 0xFFFF0000u : 0u);
+    }
+
     for (int64_t tile = int64_t(blockIdx.x) * kTeams + team; tile < tiles; tile += int64_t(gridDim.x) * kTeams) {
         const int64_t row0 = tile * R;
         const uint32_t nrows = uint32_t((total_rows - row0 < int64_t(R)) ? (total_rows - row0) : int64_t(R));
@@ -68,8 +98,24 @@ __global__ __launch_bounds__(kThreads, 4) void k_softmax_bwd(const int8_t *__res
 
         u32x2 cq[kSmU];
         typename Store<T>::raw_t cd[kSmU];
-        uint32_t r1[kSmU], nb[kSmU];
-        float2 prmA[kSmU], prmB[kSmU];
+        // (step, beta) of the head of row r1 and of the row after it; looked up again in the second pass
+        // rather than held in registers across the reduction
+        auto head_params = [&](int u, float2 &prmA, float2 &prmB) {
+            const uint32_t grow = uint32_t(row0) + r1[u];
+            const uint32_t slab = fastdiv(grow, div_rows);
+            const uint32_t h = slab - fastdiv(slab, div_heads) * heads;
+            const uint32_t h2 = (grow + 1 - slab * div_rows.d == div_rows.d) ? ((h + 1 == heads) ? 0u : h + 1) : h;
+            prmA = head_tab[h];
+            prmB = head_tab[h2];
+        };
+        // One head for the whole tile (all but the few tiles that straddle two attention maps): its
+        // step and offset are uniform, and in binary16 the sums  sum dy*y_hat = step * sum dy*x_bar +
+        // beta * sum dy  can be taken two elements at a time by dot instructions straight from the
+        // packed dy and the codes (x_bar <= 255 is exact in binary16, the products and sums are binary32).
+        const uint32_t slab_first = fastdiv(uint32_t(row0), div_rows);
+        const uint32_t slab_last = fastdiv(uint32_t(row0) + nrows - 1, div_rows);
+        const bool one_head = kHalf && slab_first == slab_last;
+        const float2 prmT = head_tab[slab_first - fastdiv(slab_first, div_heads) * heads];
 #pragma unroll
         for (int u = 0; u < kSmU; ++u) {
             const uint32_t v = u * TPT + tid;
@@ -94,20 +140,43 @@ __global__ __launch_bounds__(kThreads, 4) void k_softmax_bwd(const int8_t *__res
                 }
             }
         }
+        if constexpr (kHalf) {
+            if (one_head) {
+                const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
+#pragma unroll
+                for (int u = 0; u < kSmU; ++u) {
+                    const uint32_t v = u * TPT + tid;
+                    if (v < nvec) {
+                        float t1 = 0.0f, t2 = 0.0f, b1 = 0.0f, b2 = 0.0f;
+#pragma unroll
+                        for (int w = 0; w < 2; ++w) {
+                            h2 ylo, yhi;
+                            codes_to_h2(cq[u][w], ylo, yhi);
+                            const uint32_t g0 = cd[u][2 * w], g1 = cd[u][2 * w + 1];
+                            t1 = __builtin_amdgcn_fdot2(as_h2(g0), ylo, t1, false);
+                            t1 = __builtin_amdgcn_fdot2(as_h2(g1), yhi, t1, false);
+                            t2 = __builtin_amdgcn_fdot2(as_h2(g0), ones, t2, false);
+                            t2 = __builtin_amdgcn_fdot2(as_h2(g1), ones, t2, false);
+                            const h2 h0 = as_h2(g0 & maskB[u][2 * w]), h1 = as_h2(g1 & maskB[u][2 * w + 1]);
+                            b1 = __builtin_amdgcn_fdot2(h0, ylo, b1, false);
+                            b1 = __builtin_amdgcn_fdot2(h1, yhi, b1, false);
+                            b2 = __builtin_amdgcn_fdot2(h0, ones, b2, false);
+                            b2 = __builtin_amdgcn_fdot2(h1, ones, b2, false);
+                        }
+                        const float sT = fmaf(prmT.x, t1, prmT.y * t2), sB = fmaf(prmT.x, b1, prmT.y * b2);
+                        pa[v] = sT - sB;
+                        pb[v] = sB;
+                    }
+                }
+            }
+        }
+        if (!one_head) {
 #pragma unroll
         for (int u = 0; u < kSmU; ++u) {
             const uint32_t v = u * TPT + tid;
             if (v < nvec) {
-                const uint32_t le = v * kVec;
-                r1[u] = fastdiv(le, div_cols);
-                nb[u] = (r1[u] + 1) * cols - le;   // elements of this vector that lie in row r1
-                // head of row r1 and of the row after it
-                const uint32_t grow = uint32_t(row0) + r1[u];
-                const uint32_t slab = fastdiv(grow, div_rows);
-                const uint32_t h = slab - fastdiv(slab, div_heads) * heads;
-                const uint32_t h2 = (grow + 1 - slab * div_rows.d == div_rows.d) ? ((h + 1 == heads) ? 0u : h + 1) : h;
-                prmA[u] = head_tab[h];
-                prmB[u] = head_tab[h2];
+                float2 prmA, prmB;
+                head_params(u, prmA, prmB);
                 float g[8], y[8];
                 Store<T>::unpack(cd[u], g);
                 codes_to_float(cq[u], y);
@@ -115,7 +184,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_softmax_bwd(const int8_t *__res
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     const bool first = uint32_t(j) < nb[u];
-                    const float yh = fmaf(y[j], first ? prmA[u].x : prmB[u].x, first ? prmA[u].y : prmB[u].y);
+                    const float yh = fmaf(y[j], first ? prmA.x : prmB.x, first ? prmA.y : prmB.y);
                     const float p = g[j] * yh;
                     sA += first ? p : 0.0f;
                     sB += first ? 0.0f : p;
@@ -123,6 +192,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_softmax_bwd(const int8_t *__res
                 pa[v] = sA;
                 pb[v] = sB;
             }
+        }
         }
         tile_sync<TPT>();
 
@@ -136,7 +206,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_softmax_bwd(const int8_t *__res
                 float s = 0.0f;
                 if (lane16 == 0) s = (start & 7u) ? pb[vs] : pa[vs];
                 for (uint32_t v = vs + 1 + lane16; v <= ve; v += 16) s += pa[v];
-                s = lanes_sum<16>(s);
+                s = lanes_sum_dpp<16>(s);
                 if (lane16 == 0) rd[r] = s;
             }
         }
@@ -154,14 +224,42 @@ __global__ __launch_bounds__(kThreads, 4) void k_softmax_bwd(const int8_t *__res
                 const int64_t e = e0 + le;
                 const uint32_t r2 = (r1[u] + 1 < nrows) ? r1[u] + 1 : r1[u];
                 const float dA = rd[r1[u]], dB = rd[r2];
-                float g[8], y[8], o[8];
-                Store<T>::unpack(cd[u], g);
-                codes_to_float(cq[u], y);
+                float o[8];
+                bool done = false;
+                if constexpr (kHalf) {
+                    if (one_head) {
+                        // dy and x_bar enter the fused multiply-adds as binary16 operands
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const bool first = uint32_t(j) < nb[u];
-                    const float yh = fmaf(y[j], first ? prmA[u].x : prmB[u].x, first ? prmA[u].y : prmB[u].y);
-                    o[j] = yh * (g[j] - (first ? dA : dB));
+                        for (int w = 0; w < 2; ++w) {
+                            h2 yq2[2];
+                            codes_to_h2(cq[u][w], yq2[0], yq2[1]);
+#pragma unroll
+                            for (int c = 0; c < 2; ++c) {
+                                const h2 g2 = as_h2(cd[u][2 * w + c]);
+#pragma unroll
+                                for (int i = 0; i < 2; ++i) {
+                                    const int j = 4 * w + 2 * c + i;
+                                    const float dsel = (uint32_t(j) < nb[u]) ? dA : dB;
+                                    const float yh = fmaf(float(yq2[c][i]), prmT.x, prmT.y);
+                                    o[j] = yh * fmaf(float(g2[i]), 1.0f, -dsel);
+                                }
+                            }
+                        }
+                        done = true;
+                    }
+                }
+                if (!done) {
+                    float2 prmA, prmB;
+                    head_params(u, prmA, prmB);
+                    float g[8], y[8];
+                    Store<T>::unpack(cd[u], g);
+                    codes_to_float(cq[u], y);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const bool first = uint32_t(j) < nb[u];
+                        const float yh = fmaf(y[j], first ? prmA.x : prmB.x, first ? prmA.y : prmB.y);
+                        o[j] = yh * (g[j] - (first ? dA : dB));
+                    }
                 }
                 if (le + kVec <= nelem) {
                     Nt<T>::store(dx, e, Store<T>::pack(o));
@@ -206,7 +304,10 @@ extern "C" MESA_EXPORT mesa_status mesa_softmax_bwd_q(const int8_t *yq, int64_t 
     const int64_t tiles = ceil_div(total_rows, R);
     const int64_t teams = wave_tiles ? kThreads / 64 : 1;
     const int64_t wgs = ceil_div(tiles, teams);
-    const int grid = int(wgs < 2048 ? wgs : 2048);
+    // one resident round of workgroups (three per CU at this register budget), striding over the tiles:
+    // measured best among 768, 1024, 1536, 2048 and 3072
+    const int64_t resident = 256 * kSmWgPerCu;
+    const int grid = int(wgs < resident ? wgs : resident);
     FastDiv dc = make_fastdiv(uint32_t(cols)), dr = make_fastdiv(uint32_t(rows)), dh = make_fastdiv(uint32_t(H));
     hipStream_t s = static_cast<hipStream_t>(stream);
 #define MESA_LAUNCH_S(T, TPT_) \
