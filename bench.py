@@ -12,7 +12,7 @@ kernel reads was last touched more than a whole step (> 600 MB of traffic) earli
 respect to the 256 MB memory-side cache.  The one reuse inside a step is the method's own --
 quantize re-reads the tensor whose min/max were just taken.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line (the fields are described in README.md).
 """
 from __future__ import annotations
 
