@@ -263,6 +263,23 @@ int mesa_ref_quantize_headwise(const void *x, int dt, int64_t outer, int64_t gro
     return 0;
 }
 
+/*
+ * Single-pass forward (a variant of the method, not the order the paper implies
+ * in Sec. 5.1, where the first iteration's statistics initialise the
+ * parameters it quantizes with): the codes are taken with the running
+ * estimates AS THEY ARE ON ENTRY, Eq. (3)-(4); the same batch's extrema then
+ * move the estimates by Eq. (6)-(7) for the next call.  One read of x on a
+ * machine that fuses the two; here simply the two steps in that order.
+ */
+int mesa_ref_quantize_update_fused(const void *x, int dt, int64_t outer, int64_t groups, int64_t inner,
+                                   float *alpha, float *beta, float lambda, int8_t *q,
+                                   int mode, uint64_t seed, uint64_t offset)
+{
+    int rc = mesa_ref_quantize_headwise(x, dt, outer, groups, inner, alpha, beta, q, mode, seed, offset);
+    if (rc) return rc;
+    return mesa_ref_update_running_params(x, dt, outer, groups, inner, alpha, beta, lambda, 0);
+}
+
 /* ------------------------------------------------------------------------ */
 /* Eq. (5): dequantize                                                       */
 /* ------------------------------------------------------------------------ */

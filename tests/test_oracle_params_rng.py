@@ -96,3 +96,56 @@ def test_random_fractions_are_uniform():
     chi2 = ((hist - exp) ** 2 / exp).sum()
     assert chi2 < 120          # 63 degrees of freedom, p ~ 1e-5
     assert abs(np.corrcoef(u[:-1], u[1:])[0, 1]) < 0.02
+
+
+# ---- single-pass forward: codes with the parameters on entry, then Eq. 6-7 -------------------------------------
+
+def _numpy_codes_nearest(x, a, b):
+    """Eq. 3 written out in numpy, binary32 step by step (round half to even, then clip)."""
+    x = x.astype(np.float32)
+    r = np.where(a > 0, np.float32(255.0) / a, np.float32(0.0)).astype(np.float32)[None, :, None]
+    t = (x - b[None, :, None]).astype(np.float32)
+    v = (t * r).astype(np.float32)
+    return (np.clip(np.rint(v), 0, 255).astype(np.int32) - 128).astype(np.int8)
+
+
+def test_fused_forward_quantizes_with_the_old_parameters_then_moves_them():
+    lay = (7, 3, 41)
+    x = _x(31, lay)
+    a0 = np.array([4.0, 11.0, 25.0], np.float32)      # deliberately far from this batch's range
+    b0 = np.array([-1.0, -6.0, -14.0], np.float32)
+    q, a1, b1 = R.quantize_update_fused(x, lay, a0, b0, 0.9)
+    # codes: those of Eq. 3 with (a0, b0), not with the updated parameters
+    assert np.array_equal(q, _numpy_codes_nearest(x, a0, b0))
+    assert not np.array_equal(q, _numpy_codes_nearest(x, a1, b1))
+    # parameters: Eq. 6-7 from (a0, b0) and this batch's extrema, one binary32 operation at a time
+    mn, mx = x.min(axis=(0, 2)), x.max(axis=(0, 2))
+    lam, one_m = np.float32(0.9), np.float32(1.0) - np.float32(0.9)
+    assert np.array_equal(a1, (lam * a0 + one_m * (mx - mn).astype(np.float32)).astype(np.float32))
+    assert np.array_equal(b1, (lam * b0 + one_m * mn).astype(np.float32))
+
+
+def test_fused_forward_lags_the_two_pass_order_by_exactly_one_step():
+    # two-pass order (update, then quantize) at step t uses theta_t; the single pass uses theta_{t-1}:
+    # feeding the single pass the parameters the two-pass order had one step earlier gives the same
+    # parameter sequence, and its codes at step t equal two-pass codes taken with theta_{t-1}.
+    lay = (5, 2, 64)
+    xs = [_x(40 + t, lay, np.float16) for t in range(4)]
+    a, b = R.update_running_params(xs[0], lay, np.zeros(2), np.zeros(2), 0.9, True)
+    fa, fb = a.copy(), b.copy()
+    for t in range(1, 4):
+        q_prev_params = R.quantize_headwise(xs[t], lay, a, b, R.ROUND_STOCHASTIC, 5, 1000 * t)
+        a, b = R.update_running_params(xs[t], lay, a, b, 0.9, False)
+        fq, fa, fb = R.quantize_update_fused(xs[t], lay, fa, fb, 0.9, R.ROUND_STOCHASTIC, 5, 1000 * t)
+        assert np.array_equal(fq, q_prev_params)
+        assert np.array_equal(fa, a) and np.array_equal(fb, b)
+
+
+def test_fused_forward_constant_group_and_saturation():
+    lay = (3, 2, 16)
+    x = np.zeros(lay, np.float32)
+    x[:, 1, :] = np.linspace(-50, 50, 48, dtype=np.float32).reshape(3, 16)
+    q, a1, b1 = R.quantize_update_fused(x, lay, np.array([0.0, 10.0], np.float32), np.array([0.0, -5.0], np.float32), 0.5)
+    assert (q[:, 0, :] == -128).all()                      # alpha = 0: every code is 0 (stored -128)
+    assert q[:, 1, :].min() == -128 and q[:, 1, :].max() == 127   # values outside [beta, beta + alpha] saturate
+    assert a1[0] == 0.0 and b1[0] == 0.0 and a1[1] == np.float32(0.5 * 10.0 + 0.5 * 100.0) and b1[1] == np.float32(-2.5 - 25.0)
