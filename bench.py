@@ -100,10 +100,15 @@ class Path:
         self.step_no = 0
         self.first = True
 
-    def calls(self, fwd: BufferSet, bwd: BufferSet, seed_off: int):
+    def calls(self, fwd: BufferSet, bwd: BufferSet, seed_off: int, single_pass: bool = False):
         m, spec, H = self.m, self.spec, self.spec.heads
         out = []
         for i, k in enumerate(("attn", "gelu", "ln", "lin")):
+            if single_pass and not self.first:
+                out.append((f"quantize_update_fused_{k}", lambda k=k, i=i: m.mesa_quantize_update_fused(
+                    fwd.x[k], fwd.layout[k], self.alpha[k], self.beta[k], spec.lam, fwd.q[k], self.ws, m.ROUND_STOCHASTIC, 2024,
+                    seed_off + (i << 36))))
+                continue
             out.append((f"update_{k}", lambda k=k: m.mesa_update_running_params(
                 fwd.x[k], fwd.layout[k], self.alpha[k], self.beta[k], spec.lam, self.first, self.ws)))
             out.append((f"quantize_{k}", lambda k=k, i=i: m.mesa_quantize_headwise(
@@ -124,11 +129,11 @@ class Path:
             bwd.q["attn"], B, Hh, rows, cols, self.alpha["attn"], self.beta["attn"], bwd.dy["attn"], bwd.dx["attn"])))
         return out
 
-    def step(self, timed_kernel=None, events=None):
+    def step(self, timed_kernel=None, events=None, single_pass=False):
         i = self.step_no
         fwd = self.sets[i % NSETS]
         bwd = self.sets[(i - 1) % NSETS]
-        for name, fn in self.calls(fwd, bwd, i * (1 << 30)):
+        for name, fn in self.calls(fwd, bwd, i * (1 << 30), single_pass):
             if name == timed_kernel:
                 e0, e1 = self.m.Event(), self.m.Event()
                 e0.record()
@@ -241,6 +246,19 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     dom_ms = sum(e0.elapsed_ms(e1) for e0, e1 in events) / len(events)
 
+    # outside the headline figure: the same step with the single-pass forward variant (one call per tensor that
+    # quantizes with the running estimates as they are and moves them afterwards), under its own byte accounting
+    for _ in range(3):
+        path.step(single_pass=True)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for _ in range(args.steps):
+        path.step(single_pass=True)
+    torch.cuda.synchronize()
+    sp_ms = (time.perf_counter() - t2) * 1e3 / args.steps
+    esz = 2 if spec.dtype == torch.float16 else 4
+    sp_bytes = total_bytes - esz * sum(path.sets[0].x[k].numel() for k in ("attn", "gelu", "ln", "lin"))
+
     # untimed: the plain copy kernel on 256 MiB (x2 buffers, rotated), the known-traffic reference that
     # the bandwidth counters are scaled against and the measured ceiling quoted next to the nominal peak
     n_copy = 256 << 20
@@ -277,6 +295,10 @@ def main():
                "ms": round(per_kernel_ms["linear_dw_q"], 5), "shape": [spec.tokens, K, N]},
         "copy_probe": {"bytes": 2 * n_copy, "ms": round(copy_ms, 5), "GBps": round(2 * n_copy / (copy_ms * 1e-3) / 1e9, 1),
                        "note": "mesa_stream_copy, 256 MiB read + 256 MiB written: the bandwidth a plain copy reaches on this GPU"},
+        "single_pass_forward": {"ms_per_step": round(sp_ms, 4), "GBps": round(sp_bytes / (sp_ms * 1e-3) / 1e9, 1),
+                                "bytes_per_step": sp_bytes,
+                                "note": "variant, not the headline: mesa_quantize_update_fused replaces update + quantize (x read "
+                                        "once; parameters lag one step), the backward half unchanged"},
         "per_call": {k: {"ms": round(v, 5), "GBps": round(bytes_per[k] / (v * 1e-3) / 1e9, 1),
                          "frac_hbm": round(bytes_per[k] / (v * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)} for k, v in per_kernel_ms.items()},
     }

@@ -96,6 +96,23 @@ mesa_status mesa_quantize_headwise(const void *x, mesa_dtype dt, mesa_layout L,
                                    mesa_round mode, uint64_t seed, uint64_t offset, void *stream);
 
 /*
+ * Single-pass forward: Sec. 3.2 Eq. (3)-(4) and Eq. (6)-(7) in ONE read of x.  The codes are taken
+ * with alpha, beta as they are on entry; the same pass gathers this batch's per-group extrema, and
+ * the running estimates are then moved by Eq. (6)-(7) (never the first-call form) for the next call.
+ * This is a variant, not the order Sec. 5.1 implies: there the first iteration's statistics
+ * initialise the parameters it quantizes with, so a training run starts with
+ * mesa_update_running_params(first_call = 1) + mesa_quantize_headwise and may use this call from
+ * the second iteration on; its parameters then lag the two-call order by exactly one step.
+ * Arithmetic, rounding modes, random source and layouts: as in the two calls it combines, bit for bit.
+ * x: [numel] of dt (in).  alpha, beta: [groups] (in/out).  q: [numel] int8 (out).
+ * ws: MESA_OP_UPDATE_RUNNING_PARAMS bytes.
+ */
+mesa_status mesa_quantize_update_fused(const void *x, mesa_dtype dt, mesa_layout L,
+                                       float *alpha, float *beta, float lambda, int8_t *q,
+                                       mesa_round mode, uint64_t seed, uint64_t offset,
+                                       void *ws, size_t ws_bytes, void *stream);
+
+/*
  * De-quantizer, Sec. 3.2 Eq. (5):  x_hat = (q + 128) * (alpha_g / 255) + beta_g, binary32 with the
  * quotient, product and sum rounded separately, then rounded to dt (nearest even).
  * q: [numel] int8 (in).  x_hat: [numel] of dt (out).

@@ -32,6 +32,8 @@ constexpr int kU = 2;                            // vectors per thread and itera
 constexpr int kGridCap = 4096;                   // 16 workgroups of 4 waves per CU, two rounds of 8
 constexpr int kMmU = 4;                          // the same two numbers for the min/max scan
 constexpr int kMmGridCap = 1024;
+constexpr int kFuU = 2;                          // and for the single-pass quantize + min/max
+constexpr int kFuGridCap = 2048;
 constexpr int kLutMaxGroups = 64;                // GELU-gradient table: groups * 256 floats in LDS
 
 // The cursors of a thread's U vectors: vector u of the chunk that starts at `base` covers
@@ -176,6 +178,43 @@ __device__ __forceinline__ void minmax_element(MinMaxState<T> &st, uint32_t g, f
     st.acc.add1(f);
 }
 
+// End of a kernel that tracked extrema: what the threads still hold goes to the LDS tables, and the
+// tables become this workgroup's partials.  The U accumulators that sit in the same group are folded
+// first, and a wave whose lanes all sit in one group (head-wise tensors) combines in registers
+// before touching LDS.
+template <typename T, int U>
+__device__ __forceinline__ void minmax_finish(MinMaxState<T> (&st)[U], int *lmn, int *lmx, float *__restrict__ part,
+                                              const GroupGeom &gg)
+{
+    float lo = st[0].acc.lo(), hi = st[0].acc.hi();
+#pragma unroll
+    for (int u = 1; u < U; ++u) {
+        if (st[u].cur == st[0].cur) {
+            lo = vmin(lo, st[u].acc.lo());
+            hi = vmax(hi, st[u].acc.hi());
+        } else {
+            flush_lane(lmn, lmx, st[u].cur, st[u].acc.lo(), st[u].acc.hi());
+        }
+    }
+    const uint32_t g0 = __builtin_amdgcn_readfirstlane(st[0].cur);
+    if (__all(st[0].cur == g0)) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            lo = vmin(lo, __shfl_xor(lo, off, 64));
+            hi = vmax(hi, __shfl_xor(hi, off, 64));
+        }
+        if ((threadIdx.x & 63) == 0) flush_lane(lmn, lmx, g0, lo, hi);
+    } else {
+        flush_lane(lmn, lmx, st[0].cur, lo, hi);
+    }
+    __syncthreads();
+    float *out = part + int64_t(blockIdx.x) * 2 * gg.groups;
+    for (uint32_t g = threadIdx.x; g < gg.groups; g += kThreads) {
+        out[g] = order_val(lmn[g]);
+        out[gg.groups + g] = order_val(lmx[g]);
+    }
+}
+
 // Partial extrema of each workgroup: part[wg][0..G) = min, part[wg][G..2G) = max.  (Letting the last
 // workgroup to finish do the final step in the same launch was tried and dropped: the device-scope
 // fence it needs flushes the per-XCD L2 once per workgroup, which costs far more than a second launch.)
@@ -241,35 +280,7 @@ __global__ __launch_bounds__(kThreads) void k_minmax_partial(const void *__restr
     int64_t base = int64_t(blockIdx.x) * kChunk;
     for (; base + kChunk <= numel; base += stride) chunk(base, std::false_type());
     if (base < numel) chunk(base, std::true_type());   // the chunk that holds the end of the tensor
-    // fold the U accumulators that sit in the same group, then let a wave whose lanes all sit in
-    // one group (head-wise tensors) combine in registers before touching LDS
-    float lo = st[0].acc.lo(), hi = st[0].acc.hi();
-#pragma unroll
-    for (int u = 1; u < U; ++u) {
-        if (st[u].cur == st[0].cur) {
-            lo = vmin(lo, st[u].acc.lo());
-            hi = vmax(hi, st[u].acc.hi());
-        } else {
-            flush_lane(lmn, lmx, st[u].cur, st[u].acc.lo(), st[u].acc.hi());
-        }
-    }
-    const uint32_t g0 = __builtin_amdgcn_readfirstlane(st[0].cur);
-    if (__all(st[0].cur == g0)) {
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) {
-            lo = vmin(lo, __shfl_xor(lo, off, 64));
-            hi = vmax(hi, __shfl_xor(hi, off, 64));
-        }
-        if ((threadIdx.x & 63) == 0) flush_lane(lmn, lmx, g0, lo, hi);
-    } else {
-        flush_lane(lmn, lmx, st[0].cur, lo, hi);
-    }
-    __syncthreads();
-    float *out = part + int64_t(blockIdx.x) * 2 * gg.groups;
-    for (uint32_t g = threadIdx.x; g < gg.groups; g += kThreads) {
-        out[g] = order_val(lmn[g]);
-        out[gg.groups + g] = order_val(lmx[g]);
-    }
+    minmax_finish<T, U>(st, lmn, lmx, part, gg);
 }
 
 // Eq. (6)-(7) for one group from its extrema: each product, difference and sum rounded on its own.
@@ -445,6 +456,95 @@ __global__ __launch_bounds__(kThreads) void k_quantize(const void *__restrict__ 
     int64_t base = int64_t(blockIdx.x) * kChunk;
     for (; base + kChunk <= numel; base += stride) chunk(base, std::false_type());
     if (base < numel) chunk(base, std::true_type());   // the chunk that holds the end of the tensor
+}
+
+// Quantize and take the extrema in one pass over x: the loop of k_quantize with the bookkeeping of
+// k_minmax_partial on the same registers.  Dynamic LDS: the (scale, beta) table, then the two
+// ordered-int extrema tables.  Partials as k_minmax_partial writes them.
+template <typename T, int U, bool SR>
+__global__ __launch_bounds__(kThreads) void k_quantize_minmax(const void *__restrict__ x, int8_t *__restrict__ q, int64_t numel,
+                                                              GroupGeom gg, const float *__restrict__ alpha,
+                                                              const float *__restrict__ beta, uint64_t seed, uint64_t offset,
+                                                              float *__restrict__ part)
+{
+    extern __shared__ float2 lds_tab[];
+    int *lmn = reinterpret_cast<int *>(lds_tab + gg.groups);
+    int *lmx = lmn + gg.groups;
+    for (uint32_t g = threadIdx.x; g < gg.groups; g += kThreads) {
+        lmn[g] = order_key(__builtin_inff());
+        lmx[g] = order_key(-__builtin_inff());
+    }
+    fill_table<Scale::Quant>(lds_tab, alpha, beta, gg.groups);   // ends with a barrier
+
+    Cursor c[U];
+    place_cursors<U>(c, gg, numel);
+    MinMaxState<T> st[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) { st[u].cur = c[u].g; st[u].acc.init(); }
+
+    constexpr int kChunk = kThreads * U * kVec;
+    const int64_t stride = int64_t(gridDim.x) * kChunk;
+    const int64_t toff = int64_t(threadIdx.x) * kVec;
+    auto chunk = [&](int64_t base, auto check) {
+        constexpr bool CHECK = decltype(check)::value;
+        typename Store<T>::raw_t v[U];
+        bool full[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t e = base + u * (kThreads * kVec) + toff;
+            full[u] = !CHECK || e + kVec <= numel;
+            if (full[u]) v[u] = Nt<T>::load(x, e);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t e = base + u * (kThreads * kVec) + toff;
+            const bool one = full[u] && c[u].rem + kVec <= gg.inner;
+            const bool moved = one && c[u].g != st[u].cur;
+            if (__any(moved)) {
+                flush_wave(lmn, lmx, moved, st[u].cur, st[u].acc.lo(), st[u].acc.hi());
+                if (moved) {
+                    st[u].cur = c[u].g;
+                    st[u].acc.init();
+                }
+            }
+            if (full[u]) {
+                float f[8], w[8], bits[8];
+                if (SR) sr_bits(seed, offset + uint64_t(e >> 3), bits);
+                Store<T>::unpack(v[u], f);
+                if (__builtin_expect(one, 1)) {
+                    st[u].acc.add(v[u]);
+                    const float2 p = lds_tab[c[u].g];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) w[j] = quantize_one<SR>(f[j], p.x, p.y, SR ? bits[j] : 0.0f);
+                } else {   // the vector crosses a slab end: group and parameters per element
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const uint32_t g = group_of(c[u], j, gg);
+                        minmax_element<T>(st[u], g, f[j], lmn, lmx);
+                        const float2 p = lds_tab[g];
+                        w[j] = quantize_one<SR>(f[j], p.x, p.y, SR ? bits[j] : 0.0f);
+                    }
+                }
+                nt_store<u32x2>(q + e, pack_codes(w));
+            } else if (e < numel) {   // the ragged end of the tensor, once per launch
+                float bits[8];
+                if (SR) sr_bits(seed, offset + uint64_t(e >> 3), bits);
+                for (int j = 0; e + j < numel; ++j) {
+                    const uint32_t g = group_of(c[u], j, gg);
+                    const float xv = Store<T>::load1(x, e + j);
+                    minmax_element<T>(st[u], g, xv, lmn, lmx);
+                    const float2 p = lds_tab[g];
+                    const float w = clamp_code(quantize_one<SR>(xv, p.x, p.y, SR ? bits[j] : 0.0f));
+                    q[e + j] = int8_t(int(w) - 128);
+                }
+            }
+            cursor_advance(c[u], gg);
+        }
+    };
+    int64_t base = int64_t(blockIdx.x) * kChunk;
+    for (; base + kChunk <= numel; base += stride) chunk(base, std::false_type());
+    if (base < numel) chunk(base, std::true_type());
+    minmax_finish<T, U>(st, lmn, lmx, part, gg);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -651,16 +751,17 @@ static int stream_grid(int64_t numel, int64_t row)
     return plan_grid(numel, int64_t(kThreads) * kU * kVec, kGridCap, row);
 }
 
-static int minmax_grid(const mesa_layout &L)
+// grid of a kernel that tracks extrema with `unroll` vectors per thread and at most `grid_cap` workgroups
+static int minmax_grid(const mesa_layout &L, int unroll = kMmU, int grid_cap = kMmGridCap)
 {
     int64_t numel = layout_numel(L);
     // many groups: every workgroup writes 2*groups partial values, so keep their number down
-    int cap = kMmGridCap;
+    int cap = grid_cap;
     if (L.groups > 64) {
-        cap = int(int64_t(kMmGridCap) * 64 / L.groups);
+        cap = int(int64_t(grid_cap) * 64 / L.groups);
         if (cap < 32) cap = 32;
     }
-    const int64_t chunk = int64_t(kThreads) * kMmU * kVec;
+    const int64_t chunk = int64_t(kThreads) * unroll * kVec;
     int n = plan_grid(numel, chunk, cap, L.groups > 1 ? L.groups * L.inner : 0);
     // Long slabs (head-wise tensors): a thread hands its extrema to LDS whenever its group changes,
     // so pick a grid whose step is a whole number of group cycles plus a small remainder -- then a
@@ -725,6 +826,35 @@ extern "C" MESA_EXPORT mesa_status mesa_quantize_headwise(const void *x, mesa_dt
     if (dt == MESA_F16) { if (sr) MESA_LAUNCH_Q(_Float16, true); else MESA_LAUNCH_Q(_Float16, false); }
     else { if (sr) MESA_LAUNCH_Q(float, true); else MESA_LAUNCH_Q(float, false); }
 #undef MESA_LAUNCH_Q
+    return launch_status();
+}
+
+extern "C" MESA_EXPORT mesa_status mesa_quantize_update_fused(const void *x, mesa_dtype dt, mesa_layout L, float *alpha, float *beta,
+                                                              float lambda, int8_t *q, mesa_round mode, uint64_t seed,
+                                                              uint64_t offset, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!valid_dtype(dt) || (mode != MESA_ROUND_NEAREST_EVEN && mode != MESA_ROUND_STOCHASTIC)) return MESA_ERR_INVALID_ARG;
+    mesa_status st = check_layout(L);
+    if (st != MESA_OK) return st;
+    if (!(lambda >= 0.0f && lambda <= 1.0f)) return MESA_ERR_INVALID_ARG;
+    const int64_t numel = layout_numel(L);
+    if (numel == 0) return MESA_OK;
+    if (!x || !q || !alpha || !beta || !aligned16(x) || !aligned16(q) || !aligned4(alpha) || !aligned4(beta))
+        return MESA_ERR_INVALID_ARG;
+    if (!ws || !aligned16(ws) || ws_bytes < update_ws_bytes(L.outer, L.groups, L.inner)) return MESA_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int grid = minmax_grid(L, kFuU, kFuGridCap);
+    GroupGeom gg = make_geom(L.groups, L.inner, int64_t(grid) * kThreads * kFuU * kVec);
+    const size_t lds = size_t(gg.groups) * (sizeof(float2) + 2 * sizeof(int));
+    float *part = static_cast<float *>(ws);
+    const bool sr = mode == MESA_ROUND_STOCHASTIC;
+#define MESA_LAUNCH_QM(T, SRF) \
+    hipLaunchKernelGGL((k_quantize_minmax<T, kFuU, SRF>), dim3(grid), dim3(kThreads), lds, s, x, q, numel, gg, alpha, beta, seed, \
+                       offset, part)
+    if (dt == MESA_F16) { if (sr) MESA_LAUNCH_QM(_Float16, true); else MESA_LAUNCH_QM(_Float16, false); }
+    else { if (sr) MESA_LAUNCH_QM(float, true); else MESA_LAUNCH_QM(float, false); }
+#undef MESA_LAUNCH_QM
+    hipLaunchKernelGGL(k_ema_finalize, dim3(gg.groups), dim3(kThreads), 0, s, part, grid, gg.groups, alpha, beta, lambda, 0);
     return launch_status();
 }
 
@@ -839,10 +969,11 @@ extern "C" MESA_EXPORT size_t mesa_workspace_bytes(mesa_op op, int64_t d0, int64
     return 0;
 }
 
-// size of the min/max partials; must agree with minmax_grid()
+// size of the min/max partials: enough for mesa_update_running_params and mesa_quantize_update_fused
 size_t mesa::update_ws_bytes(int64_t outer, int64_t groups, int64_t inner)
 {
     mesa_layout L = {outer, groups, inner};
     if (check_layout(L) != MESA_OK || layout_numel(L) == 0) return 16;
-    return size_t(minmax_grid(L)) * 2 * size_t(groups < 1 ? 1 : groups) * sizeof(float);
+    const int g0 = minmax_grid(L), g1 = minmax_grid(L, kFuU, kFuGridCap);   // the two callers of this workspace
+    return size_t(g0 > g1 ? g0 : g1) * 2 * size_t(groups < 1 ? 1 : groups) * sizeof(float);
 }

@@ -284,6 +284,30 @@ def test_linear_dw_ragged_shapes(M, Mr, K, N):
     assert all(v <= TOL[torch.float16] for v in rep.values()), rep
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.float16], ids=["f32", "f16"])
+@pytest.mark.parametrize("layout", [(3, 3, 19 * 19), (57, 3, 32), (5, 7, 1000), (1, 4, 8), (2, 6, 197 * 197), (1579, 6, 64)])
+def test_single_pass_forward_matches_the_oracle_bit_for_bit(M, layout, dtype):
+    """mesa_quantize_update_fused: codes with the parameters on entry and the moved parameters, three steps
+    in a row, both rounding modes; and the same codes / parameters as the two calls it combines."""
+    n = layout[0] * layout[1] * layout[2]
+    g = torch.Generator(device="cuda").manual_seed(n)
+    xs = [(torch.randn(n, generator=g, device="cuda") * (1 + t)).to(dtype) for t in range(4)]
+    a, b, ra, rb = run_params(M, xs[:1], layout)          # first call: the two-call order
+    ws = ws_for(M, M.OP_UPDATE_RUNNING_PARAMS, *layout)
+    for t in range(1, 4):
+        mode = M.ROUND_STOCHASTIC if t % 2 else M.ROUND_NEAREST_EVEN
+        q2 = torch.empty(n, dtype=torch.int8, device="cuda")
+        M.mesa_quantize_headwise(xs[t], layout, a, b, q2, mode, 77, 1000 * t)     # the two calls, for comparison
+        a2, b2 = a.clone(), b.clone()
+        M.mesa_update_running_params(xs[t], layout, a2, b2, 0.9, False, ws)
+        q = torch.empty(n, dtype=torch.int8, device="cuda")
+        M.mesa_quantize_update_fused(xs[t], layout, a, b, 0.9, q, ws, mode, 77, 1000 * t)
+        rq, ra, rb = R.quantize_update_fused(xs[t].cpu().numpy(), layout, ra, rb, 0.9, mode, 77, 1000 * t)
+        assert np.array_equal(q.cpu().numpy(), rq.reshape(-1))
+        assert np.array_equal(canon(a.cpu().numpy()), canon(ra)) and np.array_equal(canon(b.cpu().numpy()), canon(rb))
+        assert torch.equal(q, q2) and torch.equal(a, a2) and torch.equal(b, b2)
+
+
 def test_empty_inputs_are_a_no_op(M):
     z = torch.empty(0, device="cuda")
     a = torch.ones(3, device="cuda")
