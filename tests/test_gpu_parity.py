@@ -308,6 +308,44 @@ def test_single_pass_forward_matches_the_oracle_bit_for_bit(M, layout, dtype):
         assert torch.equal(q, q2) and torch.equal(a, a2) and torch.equal(b, b2)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.float16], ids=["f32", "f16"])
+def test_per_sample_statistics_through_the_layout_descriptor(M, dtype):
+    """One (alpha, beta) pair per sample and head -- the paper's per-sample ablation -- is the layout
+    (1, B*H, inner): parameters, codes, softmax backward (B = 1, H = B*H) and GELU backward with more
+    groups than its table holds (direct evaluation of the derivative)."""
+    B, H, N = 16, 6, 19
+    G = B * H
+    lay = (1, G, N * N)
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    logits = torch.randn((B, H, N, N), generator=gen, device="cuda") * torch.linspace(0.3, 5.0, G, device="cuda").view(B, H, 1, 1)
+    xs = [torch.softmax(logits + 0.1 * t, dim=-1).to(dtype).contiguous() for t in range(2)]
+    a, b, ra, rb = run_params(M, xs, lay)
+    assert np.array_equal(canon(a.cpu().numpy()), canon(ra)) and np.array_equal(canon(b.cpu().numpy()), canon(rb))
+    assert len(set(np.round(ra, 6))) > G // 2          # the samples really have their own ranges
+    q = torch.empty(xs[-1].numel(), dtype=torch.int8, device="cuda")
+    M.mesa_quantize_headwise(xs[-1], lay, a, b, q, M.ROUND_STOCHASTIC, 3, 0)
+    rq = R.quantize_headwise(xs[-1].cpu().numpy(), lay, ra, rb, R.ROUND_STOCHASTIC, 3, 0).reshape(-1)
+    assert np.array_equal(q.cpu().numpy(), rq)
+    dy = torch.randn((B, H, N, N), generator=gen, device="cuda").to(dtype)
+    dx = torch.empty_like(dy)
+    M.mesa_softmax_bwd_q(q, 1, G, N, N, a, b, dy, dx)
+    ref = R.softmax_bwd_q(rq, 1, G, N, N, ra, rb, dy.cpu().numpy())
+    assert relerr(dx.cpu().numpy().reshape(ref.shape), ref) <= TOL[dtype]
+    # GELU input with 96 groups of 40 channels
+    lay2 = (50, G, 40)
+    x = (torch.randn(lay2, generator=gen, device="cuda") * 1.5).to(dtype).contiguous()
+    a2, b2, ra2, rb2 = run_params(M, [x], lay2)
+    q2 = torch.empty(x.numel(), dtype=torch.int8, device="cuda")
+    M.mesa_quantize_headwise(x, lay2, a2, b2, q2, M.ROUND_NEAREST_EVEN, 0, 0)
+    rq2 = R.quantize_headwise(x.cpu().numpy(), lay2, ra2, rb2, R.ROUND_NEAREST, 0, 0).reshape(-1)
+    assert np.array_equal(q2.cpu().numpy(), rq2)
+    dy2 = torch.randn(lay2, generator=gen, device="cuda").to(dtype)
+    dx2 = torch.empty_like(dy2)
+    M.mesa_gelu_bwd_q(q2, lay2, a2, b2, dy2, dx2)
+    ref2 = R.gelu_bwd_q(rq2, lay2, ra2, rb2, dy2.cpu().numpy())
+    assert relerr(dx2.cpu().numpy().reshape(ref2.shape), ref2) <= TOL[dtype]
+
+
 def test_empty_inputs_are_a_no_op(M):
     z = torch.empty(0, device="cuda")
     a = torch.ones(3, device="cuda")
