@@ -37,45 +37,56 @@ MFMA_F16_PEAK_TFLOPS = 2500.0
 NSETS = 3
 
 
-def algorithmic_bytes(spec):
+def linear_of(spec, which=0):
+    """(K, N_out) of the Linear layer the step takes dW of, or None when the configuration names none."""
+    return spec.linears[which] if spec.linears else None
+
+
+def algorithmic_bytes(spec, which_linear=0):
     """Bytes each call must move at the very least (per-element figures x elements)."""
     T = 2 if spec.dtype == torch.float16 else 4
     n_attn = spec.attn[0] * spec.attn[1] * spec.attn[2] * spec.attn[3]
     n_gelu = spec.tokens * spec.mlp
     n_ln = spec.tokens * spec.dim
-    K, N = spec.linears[0]
-    n_lin = spec.tokens * K
+    tensors = [("attn", n_attn), ("gelu", n_gelu), ("ln", n_ln)]
+    lin = linear_of(spec, which_linear)
+    if lin:
+        tensors.append(("lin", spec.tokens * lin[0]))
     b = {}
-    for name, n in (("attn", n_attn), ("gelu", n_gelu), ("ln", n_ln), ("lin", n_lin)):
+    for name, n in tensors:
         b[f"update_{name}"] = T * n
         b[f"quantize_{name}"] = (T + 1) * n
-    b["dequantize_lin"] = (1 + T) * n_lin
     b["softmax_bwd_q"] = (1 + 2 * T) * n_attn
     b["gelu_bwd_q"] = (1 + 2 * T) * n_gelu
     b["layernorm_bwd_q"] = (1 + 2 * T) * n_ln + 8 * spec.tokens + (T + 8) * spec.dim
-    b["linear_dw_q"] = spec.tokens * K + T * spec.tokens * N + 4 * N * K + 4 * N
+    if lin:
+        K, N = lin
+        b["dequantize_lin"] = (1 + T) * spec.tokens * K
+        b["linear_dw_q"] = spec.tokens * K + T * spec.tokens * N + 4 * N * K + 4 * N
     return b
 
 
 class BufferSet:
-    def __init__(self, m, spec, draw):
+    def __init__(self, m, spec, draw, lin):
         dev = "cuda"
         H = spec.heads
-        K, N = spec.linears[0]
         self.x = {"attn": W.attention_map(spec, draw, dev), "gelu": W.gelu_input(spec, draw, dev),
-                  "ln": W.token_matrix(spec, "ln", draw, dev), "lin": W.token_matrix(spec, "lin", draw, dev, width=K)}
-        self.layout = {"attn": spec.attn_layout, "gelu": spec.gelu_layout, "ln": spec.ln_layout,
-                       "lin": (spec.tokens, H, K // H)}
-        self.q = {k: torch.empty(v.numel(), dtype=torch.int8, device=dev) for k, v in self.x.items()}
+                  "ln": W.token_matrix(spec, "ln", draw, dev)}
+        self.layout = {"attn": spec.attn_layout, "gelu": spec.gelu_layout, "ln": spec.ln_layout}
         self.dy = {"attn": W.upstream_grad(spec, "dy_attn", spec.attn, dev),
                    "gelu": W.upstream_grad(spec, "dy_gelu", (spec.tokens, spec.mlp), dev),
-                   "ln": W.upstream_grad(spec, "dy_ln", (spec.tokens, spec.dim), dev),
-                   "lin": W.upstream_grad(spec, "dy_lin", (spec.tokens, N), dev)}
+                   "ln": W.upstream_grad(spec, "dy_ln", (spec.tokens, spec.dim), dev)}
+        if lin:
+            K, N = lin
+            self.x["lin"] = W.token_matrix(spec, "lin", draw, dev, width=K)
+            self.layout["lin"] = (spec.tokens, H, K // H)
+            self.dy["lin"] = W.upstream_grad(spec, "dy_lin", (spec.tokens, N), dev)
+            self.xhat = torch.empty_like(self.x["lin"])
+            self.dW = torch.empty((N, K), device=dev)
+            self.db = torch.empty(N, device=dev)
+        self.q = {k: torch.empty(v.numel(), dtype=torch.int8, device=dev) for k, v in self.x.items()}
         self.dx = {k: torch.empty_like(self.dy[k]) for k in ("attn", "gelu", "ln")}
-        self.xhat = torch.empty_like(self.x["lin"])
         self.mean, self.rstd = W.layernorm_stats(self.x["ln"])
-        self.dW = torch.empty((N, K), device=dev)
-        self.db = torch.empty(N, device=dev)
         self.dgamma = torch.empty(spec.dim, device=dev)
         self.dbeta = torch.empty(spec.dim, device=dev)
 
@@ -83,19 +94,21 @@ class BufferSet:
 class Path:
     """The thirteen calls of a step, each a closure that only enqueues work."""
 
-    def __init__(self, m, spec):
+    def __init__(self, m, spec, which_linear=0):
         self.m, self.spec = m, spec
         H = spec.heads
-        K, N = spec.linears[0]
-        self.K, self.N = K, N
-        self.sets = [BufferSet(m, spec, d) for d in range(NSETS)]
-        self.alpha = {k: torch.zeros(H, device="cuda") for k in ("attn", "gelu", "ln", "lin")}
-        self.beta = {k: torch.zeros(H, device="cuda") for k in ("attn", "gelu", "ln", "lin")}
+        self.lin = linear_of(spec, which_linear)
+        self.K, self.N = self.lin if self.lin else (0, 0)
+        self.sets = [BufferSet(m, spec, d, self.lin) for d in range(NSETS)]
+        self.tensors = ("attn", "gelu", "ln", "lin") if self.lin else ("attn", "gelu", "ln")
+        self.alpha = {k: torch.zeros(H, device="cuda") for k in self.tensors}
+        self.beta = {k: torch.zeros(H, device="cuda") for k in self.tensors}
         self.gamma = W.layernorm_gamma(spec, "cuda")
         s0 = self.sets[0]
         ws_n = max(max(m.workspace_bytes(m.OP_UPDATE_RUNNING_PARAMS, *s0.layout[k]) for k in s0.layout),
                    m.workspace_bytes(m.OP_LAYERNORM_BWD_Q, spec.tokens, spec.dim, H),
-                   m.workspace_bytes(m.OP_LINEAR_DW_Q, spec.tokens, K, N, m.F16 if spec.dtype == torch.float16 else m.F32))
+                   m.workspace_bytes(m.OP_LINEAR_DW_Q, spec.tokens, self.K, self.N,
+                                     m.F16 if spec.dtype == torch.float16 else m.F32) if self.lin else 16)
         self.ws = torch.empty(ws_n, dtype=torch.uint8, device="cuda")
         self.step_no = 0
         self.first = True
@@ -103,7 +116,7 @@ class Path:
     def calls(self, fwd: BufferSet, bwd: BufferSet, seed_off: int, single_pass: bool = False):
         m, spec, H = self.m, self.spec, self.spec.heads
         out = []
-        for i, k in enumerate(("attn", "gelu", "ln", "lin")):
+        for i, k in enumerate(self.tensors):
             if single_pass and not self.first:
                 out.append((f"quantize_update_fused_{k}", lambda k=k, i=i: m.mesa_quantize_update_fused(
                     fwd.x[k], fwd.layout[k], self.alpha[k], self.beta[k], spec.lam, fwd.q[k], self.ws, m.ROUND_STOCHASTIC, 2024,
@@ -115,11 +128,12 @@ class Path:
                 fwd.x[k], fwd.layout[k], self.alpha[k], self.beta[k], fwd.q[k], m.ROUND_STOCHASTIC, 2024,
                 seed_off + (i << 36))))
         B, Hh, rows, cols = spec.attn
-        out.append(("linear_dw_q", lambda: m.mesa_linear_dw_q(
-            bwd.q["lin"], spec.tokens, self.K, H, self.alpha["lin"], self.beta["lin"], bwd.dy["lin"], self.N, bwd.dW,
-            bwd.db, self.ws)))
-        out.append(("dequantize_lin", lambda: m.mesa_dequantize(
-            bwd.q["lin"], bwd.layout["lin"], self.alpha["lin"], self.beta["lin"], bwd.xhat)))
+        if self.lin:
+            out.append(("linear_dw_q", lambda: m.mesa_linear_dw_q(
+                bwd.q["lin"], spec.tokens, self.K, H, self.alpha["lin"], self.beta["lin"], bwd.dy["lin"], self.N, bwd.dW,
+                bwd.db, self.ws)))
+            out.append(("dequantize_lin", lambda: m.mesa_dequantize(
+                bwd.q["lin"], bwd.layout["lin"], self.alpha["lin"], self.beta["lin"], bwd.xhat)))
         out.append(("layernorm_bwd_q", lambda: m.mesa_layernorm_bwd_q(
             bwd.q["ln"], spec.tokens, spec.dim, H, self.alpha["ln"], self.beta["ln"], bwd.mean, bwd.rstd, self.gamma,
             bwd.dy["ln"], bwd.dx["ln"], bwd.dgamma, bwd.dbeta, self.ws)))
@@ -185,12 +199,23 @@ def cpu_baseline(spec, target_seconds=20.0):
                       f"({el:.1f} s of CPU work; same algorithmic-byte accounting as the GPU figure)"}
 
 
+def workload_name(spec, number, lin):
+    b, h, r, c = spec.attn
+    dw = f"whole path incl. dW {lin[0]}->{lin[1]}" if lin else "whole path, no Linear layer named"
+    return (f"configs[{number - 1}]: {spec.name} -- attention maps ({b}, {h}, {r}, {c}), {spec.tokens} tokens, dim {spec.dim}, "
+            f"MLP {spec.mlp}, {'fp16' if spec.dtype == torch.float16 else 'fp32'}; stochastic rounding; {dw}")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4, 5],
+                    help="which of the baseline configurations to run; the default (2) is the one the metric is quoted on, "
+                         "the others are extra measurements (no cpu_baseline, no counter-based traffic figure)")
+    ap.add_argument("--linear", type=int, default=0, help="which of the configuration's Linear layers supplies dW")
     ap.add_argument("--traffic", type=float, default=None,
                     help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (see profiles/)")
     args = ap.parse_args()
@@ -203,13 +228,12 @@ def main():
 
     import paper_2111_11124_amd as m
     m.lib()
-    spec = W.CONFIGS[2]
-    bytes_per = algorithmic_bytes(spec)
+    spec = W.CONFIGS[args.config]
+    bytes_per = algorithmic_bytes(spec, args.linear)
     total_bytes = sum(bytes_per.values())
-    K, N = spec.linears[0]
+    path = Path(m, spec, args.linear)
+    K, N = path.K, path.N
     dw_flops = 2.0 * spec.tokens * K * N
-
-    path = Path(m, spec)
     torch.cuda.synchronize()
 
     # untimed: warm-up steps, the first of which initialises the running estimates
@@ -257,7 +281,7 @@ def main():
     torch.cuda.synchronize()
     sp_ms = (time.perf_counter() - t2) * 1e3 / args.steps
     esz = 2 if spec.dtype == torch.float16 else 4
-    sp_bytes = total_bytes - esz * sum(path.sets[0].x[k].numel() for k in ("attn", "gelu", "ln", "lin"))
+    sp_bytes = total_bytes - esz * sum(path.sets[0].x[k].numel() for k in path.tensors)
 
     # untimed: the plain copy kernel on 256 MiB (x2 buffers, rotated), the known-traffic reference that
     # the bandwidth counters are scaled against and the measured ceiling quoted next to the nominal peak
@@ -280,19 +304,19 @@ def main():
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16 storage, f32 arithmetic (f16 x f16 -> f32 MFMA for dW)", "data": "synthetic",
-        "config": {"workload": "configs[1]: DeiT-S-shaped block, batch 128, fp16, 197 tokens, dim 384, 6 heads, MLP 1536; "
-                               "stochastic rounding; whole path incl. dW 384->1536",
+        "config": {"workload": workload_name(spec, args.config, path.lin),
                    "bytes_per_step": total_bytes, "elements_per_s": round(
                        (spec.attn[0] * spec.attn[1] * spec.attn[2] * spec.attn[3] + spec.tokens * (spec.mlp + 2 * spec.dim))
                        / (ms_per_step * 1e-3), 1)},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": args.traffic if args.traffic is not None else MEASURED_TRAFFIC_BYTES.get(dominant),
+                     "traffic": args.traffic if args.traffic is not None else
+                     (MEASURED_TRAFFIC_BYTES.get(dominant) if args.config == 2 else None),
                      "avg_launch_ms": round(dom_ms, 5), "algorithmic_bytes": bytes_per[dominant]},
-        "dw": {"tflops": round(dw_flops / (per_kernel_ms["linear_dw_q"] * 1e-3) / 1e12, 1),
-               "mfma_frac": round(dw_flops / (per_kernel_ms["linear_dw_q"] * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4),
-               "ms": round(per_kernel_ms["linear_dw_q"], 5), "shape": [spec.tokens, K, N]},
+        "dw": ({"tflops": round(dw_flops / (per_kernel_ms["linear_dw_q"] * 1e-3) / 1e12, 1),
+                "mfma_frac": round(dw_flops / (per_kernel_ms["linear_dw_q"] * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4),
+                "ms": round(per_kernel_ms["linear_dw_q"], 5), "shape": [spec.tokens, K, N]} if path.lin else None),
         "copy_probe": {"bytes": 2 * n_copy, "ms": round(copy_ms, 5), "GBps": round(2 * n_copy / (copy_ms * 1e-3) / 1e9, 1),
                        "note": "mesa_stream_copy, 256 MiB read + 256 MiB written: the bandwidth a plain copy reaches on this GPU"},
         "single_pass_forward": {"ms_per_step": round(sp_ms, 4), "GBps": round(sp_bytes / (sp_ms * 1e-3) / 1e9, 1),
@@ -302,7 +326,7 @@ def main():
         "per_call": {k: {"ms": round(v, 5), "GBps": round(bytes_per[k] / (v * 1e-3) / 1e9, 1),
                          "frac_hbm": round(bytes_per[k] / (v * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)} for k, v in per_kernel_ms.items()},
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.config == 2:
         out["cpu_baseline"] = cpu_baseline(spec)
     print(json.dumps(out))
 

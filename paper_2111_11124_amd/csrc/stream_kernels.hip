@@ -32,6 +32,7 @@ constexpr int kU = 2;                            // vectors per thread and itera
 constexpr int kGridCap = 4096;                   // 16 workgroups of 4 waves per CU, two rounds of 8
 constexpr int kMmU = 4;                          // the same two numbers for the min/max scan
 constexpr int kMmGridCap = 1024;
+constexpr int kMmFew = 8;                        // groups for which a thread can hold every group's extrema
 constexpr int kFuU = 2;                          // and for the single-pass quantize + min/max
 constexpr int kFuGridCap = 2048;
 constexpr int kLutMaxGroups = 64;                // GELU-gradient table: groups * 256 floats in LDS
@@ -101,6 +102,7 @@ template <> struct MinMax<float> {
         for (int j = 0; j < 8; ++j) { mn = vmin(mn, f[j]); mx = vmax(mx, f[j]); }
     }
     __device__ __forceinline__ void add1(float f) { mn = vmin(mn, f); mx = vmax(mx, f); }
+    __device__ __forceinline__ void merge(const MinMax<float> &o) { mn = vmin(mn, o.mn); mx = vmax(mx, o.mx); }
     __device__ __forceinline__ float lo() const { return mn; }
     __device__ __forceinline__ float hi() const { return mx; }
 };
@@ -126,6 +128,7 @@ template <> struct MinMax<_Float16> {
         mn = pkmin(mn, as_u32(p));
         mx = pkmax(mx, as_u32(p));
     }
+    __device__ __forceinline__ void merge(const MinMax<_Float16> &o) { mn = pkmin(mn, o.mn); mx = pkmax(mx, o.mx); }
     __device__ __forceinline__ float lo() const { h2 p = as_h2(mn); return vmin(float(p.x), float(p.y)); }
     __device__ __forceinline__ float hi() const { h2 p = as_h2(mx); return vmax(float(p.x), float(p.y)); }
 };
@@ -281,6 +284,104 @@ __global__ __launch_bounds__(kThreads) void k_minmax_partial(const void *__restr
     for (; base + kChunk <= numel; base += stride) chunk(base, std::false_type());
     if (base < numel) chunk(base, std::true_type());   // the chunk that holds the end of the tensor
     minmax_finish<T, U>(st, lmn, lmx, part, gg);
+}
+
+// Few groups (at most GMAX) whose slabs are short and of awkward length -- a 49 x 49 window's attention
+// map -- so that a thread meets another group at almost every step: instead of handing extrema to LDS
+// whenever the group changes, every thread keeps running extrema for ALL groups (a select per group and
+// vector) and nothing is flushed before the end.  Same partials as k_minmax_partial.
+template <typename T, int U, int GMAX>
+__global__ __launch_bounds__(kThreads) void k_minmax_partial_few(const void *__restrict__ x, int64_t numel, GroupGeom gg,
+                                                                 float *__restrict__ part)
+{
+    extern __shared__ int lds_mm[];
+    int *lmn = lds_mm;
+    int *lmx = lds_mm + gg.groups;
+    for (uint32_t g = threadIdx.x; g < gg.groups; g += kThreads) {
+        lmn[g] = order_key(__builtin_inff());
+        lmx[g] = order_key(-__builtin_inff());
+    }
+    __syncthreads();
+
+    Cursor c[U];
+    place_cursors<U>(c, gg, numel);
+    MinMax<T> acc[GMAX];
+#pragma unroll
+    for (int k = 0; k < GMAX; ++k) acc[k].init();
+    // a vector's (or an element's) own extrema go to the accumulator of group g, the others keep theirs
+    auto merge = [&](uint32_t g, const MinMax<T> &m) {
+#pragma unroll
+        for (int k = 0; k < GMAX; ++k) {
+            MinMax<T> t = acc[k];
+            t.merge(m);
+            if (g == uint32_t(k)) acc[k] = t;
+        }
+    };
+
+    constexpr int kChunk = kThreads * U * kVec;
+    const int64_t stride = int64_t(gridDim.x) * kChunk;
+    const int64_t toff = int64_t(threadIdx.x) * kVec;
+    auto chunk = [&](int64_t base, auto check) {
+        constexpr bool CHECK = decltype(check)::value;
+        typename Store<T>::raw_t v[U];
+        bool full[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t e = base + u * (kThreads * kVec) + toff;
+            full[u] = !CHECK || e + kVec <= numel;
+            if (full[u]) v[u] = Nt<T>::load(x, e);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t e = base + u * (kThreads * kVec) + toff;
+            if (full[u] && c[u].rem + kVec <= gg.inner) {
+                MinMax<T> m;
+                m.init();
+                m.add(v[u]);
+                merge(c[u].g, m);
+            } else if (full[u]) {   // crosses a slab end: element by element, from the registers
+                float f[8];
+                Store<T>::unpack(v[u], f);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    MinMax<T> m;
+                    m.init();
+                    m.add1(f[j]);
+                    merge(group_of(c[u], j, gg), m);
+                }
+            } else if (e < numel) {   // the ragged end of the tensor, once per launch
+                for (int j = 0; e + j < numel; ++j) {
+                    MinMax<T> m;
+                    m.init();
+                    m.add1(Store<T>::load1(x, e + j));
+                    merge(group_of(c[u], j, gg), m);
+                }
+            }
+            cursor_advance(c[u], gg);
+        }
+    };
+    int64_t base = int64_t(blockIdx.x) * kChunk;
+    for (; base + kChunk <= numel; base += stride) chunk(base, std::false_type());
+    if (base < numel) chunk(base, std::true_type());
+
+#pragma unroll
+    for (int k = 0; k < GMAX; ++k) {
+        if (uint32_t(k) < gg.groups) {
+            float lo = acc[k].lo(), hi = acc[k].hi();
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) {
+                lo = vmin(lo, __shfl_xor(lo, off, 64));
+                hi = vmax(hi, __shfl_xor(hi, off, 64));
+            }
+            if ((threadIdx.x & 63) == 0) flush_lane(lmn, lmx, uint32_t(k), lo, hi);
+        }
+    }
+    __syncthreads();
+    float *out = part + int64_t(blockIdx.x) * 2 * gg.groups;
+    for (uint32_t g = threadIdx.x; g < gg.groups; g += kThreads) {
+        out[g] = order_val(lmn[g]);
+        out[gg.groups + g] = order_val(lmx[g]);
+    }
 }
 
 // Eq. (6)-(7) for one group from its extrema: each product, difference and sum rounded on its own.
@@ -779,6 +880,17 @@ static int minmax_grid(const mesa_layout &L, int unroll = kMmU, int grid_cap = k
     return n;
 }
 
+// True when a thread of the min/max scan would meet another group at almost every step of the grid:
+// few groups, and the grid's step is neither a whole number of group cycles nor close to one.
+static bool minmax_few_groups(const mesa_layout &L, int grid, int unroll)
+{
+    if (L.groups < 2 || L.groups > kMmFew) return false;
+    const int64_t row = L.groups * L.inner;
+    const int64_t step = (int64_t(grid) * kThreads * unroll * kVec) % row;
+    const int64_t off = step < row - step ? step : row - step;   // how far a step lands from where it started, in the cycle
+    return off > L.inner / 16;
+}
+
 extern "C" MESA_EXPORT mesa_status mesa_update_running_params(const void *x, mesa_dtype dt, mesa_layout L, float *alpha, float *beta,
                                                   float lambda, int first_call, void *ws, size_t ws_bytes, void *stream)
 {
@@ -796,7 +908,21 @@ extern "C" MESA_EXPORT mesa_status mesa_update_running_params(const void *x, mes
     GroupGeom gg = make_geom(L.groups, L.inner, int64_t(grid) * kThreads * kMmU * kVec);
     const size_t lds = size_t(2) * gg.groups * sizeof(int);
     float *part = static_cast<float *>(ws);
-    if (dt == MESA_F16)
+    if (minmax_few_groups(L, grid, kMmU)) {
+#define MESA_LAUNCH_FEW(T, GM) \
+    hipLaunchKernelGGL((k_minmax_partial_few<T, kMmU, GM>), dim3(grid), dim3(kThreads), lds, s, x, numel, gg, part)
+#define MESA_LAUNCH_FEW_T(T) \
+    do { \
+        if (L.groups <= 2) MESA_LAUNCH_FEW(T, 2); \
+        else if (L.groups == 3) MESA_LAUNCH_FEW(T, 3); \
+        else if (L.groups == 4) MESA_LAUNCH_FEW(T, 4); \
+        else if (L.groups <= 6) MESA_LAUNCH_FEW(T, 6); \
+        else MESA_LAUNCH_FEW(T, 8); \
+    } while (0)
+        if (dt == MESA_F16) MESA_LAUNCH_FEW_T(_Float16); else MESA_LAUNCH_FEW_T(float);
+#undef MESA_LAUNCH_FEW_T
+#undef MESA_LAUNCH_FEW
+    } else if (dt == MESA_F16)
         hipLaunchKernelGGL((k_minmax_partial<_Float16, kMmU>), dim3(grid), dim3(kThreads), lds, s, x, numel, gg, part);
     else
         hipLaunchKernelGGL((k_minmax_partial<float, kMmU>), dim3(grid), dim3(kThreads), lds, s, x, numel, gg, part);
