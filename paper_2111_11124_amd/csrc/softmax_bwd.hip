@@ -196,20 +196,24 @@ __global__ __launch_bounds__(kThreads, kSmWgPerCu) void k_softmax_bwd(const int8
         }
         tile_sync<TPT>();
 
-        // 16 lanes per row: the row's own part of its first vector, then the vectors that start in it
-        {
-            const uint32_t lane16 = tid & 15u;
-            for (uint32_t r = tid >> 4; r < nrows; r += TPT / 16) {
+        // A group of lanes per row (8 when a row spans at most 8 vectors, else 16): the row's own part of
+        // its first vector, then the vectors that start in it
+        auto row_sums = [&](auto lanes) {
+            constexpr uint32_t LPR = decltype(lanes)::value;
+            const uint32_t ln = tid & (LPR - 1);
+            for (uint32_t r = tid / LPR; r < nrows; r += TPT / LPR) {
                 const uint32_t start = r * cols;
                 const uint32_t vs = start >> 3;
                 const uint32_t ve = (start + cols - 1) >> 3;
                 float s = 0.0f;
-                if (lane16 == 0) s = (start & 7u) ? pb[vs] : pa[vs];
-                for (uint32_t v = vs + 1 + lane16; v <= ve; v += 16) s += pa[v];
-                s = lanes_sum_dpp<16>(s);
-                if (lane16 == 0) rd[r] = s;
+                if (ln == 0) s = (start & 7u) ? pb[vs] : pa[vs];
+                for (uint32_t v = vs + 1 + ln; v <= ve; v += LPR) s += pa[v];
+                s = lanes_sum_dpp<LPR>(s);
+                if (ln == 0) rd[r] = s;
             }
-        }
+        };
+        if (cols <= 56) row_sums(std::integral_constant<uint32_t, 8>());   // at most 8 vectors touch such a row
+        else row_sums(std::integral_constant<uint32_t, 16>());
         tile_sync<TPT>();
 
         // keep only the packed inputs across the passes: the unpacked values are cheap to rebuild,
