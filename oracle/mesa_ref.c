@@ -11,7 +11,8 @@
  *   Sec. 3.2 Eq. (4)   stochastic rounding: ceil with probability frac(x)
  *   Sec. 3.2 Eq. (5)   x_hat = x_bar * alpha_h / 255 + beta_h
  *   Sec. 3.2 Eq. (6,7) running estimates of alpha (range) and beta (minimum)
- *   Sec. 3.1 Eq. (2)   layer gradients evaluated at the de-quantized x_hat
+ *   Sec. 3.1 Eq. (2)   layer gradients evaluated at the de-quantized x_hat (softmax, GELU,
+ *                      LayerNorm, the Linear weight, and the two matrix products of attention)
  *   Sec. 3.2 / Fig. "bucketing": one (alpha, beta) pair per head or channel group
  *
  * Conventions
@@ -484,6 +485,81 @@ int mesa_ref_linear_dw_q_entries(const int8_t *xq, int64_t M, int64_t K, int64_t
 #endif
     for (int64_t t = 0; t < count; ++t)
         out[t] = dw_entry(xq, M, K, per, alpha, beta, dy, N_out, dt, n_idx[t], k_idx[t]);
+    return 0;
+}
+
+/*
+ * The two matrix products of self-attention, backward, at the de-quantized
+ * operands (Eq. (2) with G_l the gradient of a matrix product; the operands
+ * are saved head-wise, Sec. 3.2: one (alpha, beta) pair per head for each of
+ * the four tensors).  All tensors are (B, H, N, .) contiguous.
+ *
+ *   O = A V,  A (N x N) the attention map, V (N x Dh):
+ *       dA[i,j] = sum_d dO[i,d] * V_hat[j,d]        dV[j,d] = sum_i A_hat[i,j] * dO[i,d]
+ */
+int mesa_ref_attn_av_bwd_q(const int8_t *aq, const int8_t *vq, int64_t B, int64_t H, int64_t N, int64_t Dh,
+                           const float *alpha_a, const float *beta_a, const float *alpha_v, const float *beta_v,
+                           const void *dO, int dt, double *dA, double *dV)
+{
+    if (B <= 0 || H <= 0 || N <= 0 || Dh <= 0) return 0;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t bh = 0; bh < B * H; ++bh) {
+        int64_t h = bh % H;
+        float sa = alpha_a[h] / 255.0f, sv = alpha_v[h] / 255.0f;
+        const int8_t *a = aq + bh * N * N;
+        const int8_t *v = vq + bh * N * Dh;
+        for (int64_t i = 0; i < N; ++i)
+            for (int64_t j = 0; j < N; ++j) {
+                double acc = 0.0;
+                for (int64_t d = 0; d < Dh; ++d)
+                    acc += load_as_double(dO, dt, (bh * N + i) * Dh + d) * (double)dequant_one(v[j * Dh + d], sv, beta_v[h]);
+                dA[(bh * N + i) * N + j] = acc;
+            }
+        for (int64_t j = 0; j < N; ++j)
+            for (int64_t d = 0; d < Dh; ++d) {
+                double acc = 0.0;
+                for (int64_t i = 0; i < N; ++i)
+                    acc += (double)dequant_one(a[i * N + j], sa, beta_a[h]) * load_as_double(dO, dt, (bh * N + i) * Dh + d);
+                dV[(bh * N + j) * Dh + d] = acc;
+            }
+    }
+    return 0;
+}
+
+/*
+ *   S = scale * Q K^T,  Q, K (N x Dh):
+ *       dQ[i,d] = scale * sum_j dS[i,j] * K_hat[j,d]     dK[j,d] = scale * sum_i dS[i,j] * Q_hat[i,d]
+ */
+int mesa_ref_attn_qk_bwd_q(const int8_t *qq, const int8_t *kq, int64_t B, int64_t H, int64_t N, int64_t Dh,
+                           const float *alpha_q, const float *beta_q, const float *alpha_k, const float *beta_k,
+                           const void *dS, int dt, double scale, double *dQ, double *dK)
+{
+    if (B <= 0 || H <= 0 || N <= 0 || Dh <= 0) return 0;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t bh = 0; bh < B * H; ++bh) {
+        int64_t h = bh % H;
+        float sq = alpha_q[h] / 255.0f, sk = alpha_k[h] / 255.0f;
+        const int8_t *q = qq + bh * N * Dh;
+        const int8_t *k = kq + bh * N * Dh;
+        for (int64_t i = 0; i < N; ++i)
+            for (int64_t d = 0; d < Dh; ++d) {
+                double acc = 0.0;
+                for (int64_t j = 0; j < N; ++j)
+                    acc += load_as_double(dS, dt, (bh * N + i) * N + j) * (double)dequant_one(k[j * Dh + d], sk, beta_k[h]);
+                dQ[(bh * N + i) * Dh + d] = scale * acc;
+            }
+        for (int64_t j = 0; j < N; ++j)
+            for (int64_t d = 0; d < Dh; ++d) {
+                double acc = 0.0;
+                for (int64_t i = 0; i < N; ++i)
+                    acc += load_as_double(dS, dt, (bh * N + i) * N + j) * (double)dequant_one(q[i * Dh + d], sq, beta_q[h]);
+                dK[(bh * N + j) * Dh + d] = scale * acc;
+            }
+    }
     return 0;
 }
 

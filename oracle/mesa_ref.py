@@ -200,6 +200,30 @@ def layernorm_bwd_q(xq, M, D, G, alpha, beta, mean, rstd, gamma, dy):
     return dx, dg, db
 
 
+def attn_av_bwd_q(aq, vq, B, H, N, Dh, alpha_a, beta_a, alpha_v, beta_v, dO):
+    """Backward of O = A V at the de-quantized A (B,H,N,N) and V (B,H,N,Dh): returns (dA, dV) in binary64."""
+    aq, vq, dO = _c(aq, np.int8), _c(vq, np.int8), _c(dO)
+    assert aq.size == B * H * N * N and vq.size == B * H * N * Dh and dO.size == B * H * N * Dh
+    dA = np.empty((B, H, N, N), np.float64)
+    dV = np.empty((B, H, N, Dh), np.float64)
+    lib().mesa_ref_attn_av_bwd_q(_p(aq), _p(vq), I64(B), I64(H), I64(N), I64(Dh), _p(_c(alpha_a, np.float32)),
+                                 _p(_c(beta_a, np.float32)), _p(_c(alpha_v, np.float32)), _p(_c(beta_v, np.float32)),
+                                 _p(dO), _dt(dO), _p(dA), _p(dV))
+    return dA, dV
+
+
+def attn_qk_bwd_q(qq, kq, B, H, N, Dh, alpha_q, beta_q, alpha_k, beta_k, dS, scale):
+    """Backward of S = scale Q K^T at the de-quantized Q, K (B,H,N,Dh): returns (dQ, dK) in binary64."""
+    qq, kq, dS = _c(qq, np.int8), _c(kq, np.int8), _c(dS)
+    assert qq.size == B * H * N * Dh and kq.size == B * H * N * Dh and dS.size == B * H * N * N
+    dQ = np.empty((B, H, N, Dh), np.float64)
+    dK = np.empty((B, H, N, Dh), np.float64)
+    lib().mesa_ref_attn_qk_bwd_q(_p(qq), _p(kq), I64(B), I64(H), I64(N), I64(Dh), _p(_c(alpha_q, np.float32)),
+                                 _p(_c(beta_q, np.float32)), _p(_c(alpha_k, np.float32)), _p(_c(beta_k, np.float32)),
+                                 _p(dS), _dt(dS), C.c_double(scale), _p(dQ), _p(dK))
+    return dQ, dK
+
+
 def linear_dw_q(xq, M, K, G, alpha, beta, dy, N_out):
     xq = _c(xq, np.int8)
     dy = _c(dy)

@@ -243,3 +243,92 @@ def test_linear_dw_matches_torch_fd_and_the_factored_form(dt):
     n_idx, k_idx = np.array([0, 4, 2]), np.array([7, 0, 3])
     ent = R.linear_dw_q_entries(q, M, K, G, alpha, beta, dy, N, n_idx, k_idx)
     assert np.array_equal(ent, dW[n_idx, k_idx])
+
+
+# ----------------------------------------------------------------------------- attention matrix products
+
+def _attn_case(rng, B, H, N, Dh, dt):
+    aq = rng.integers(-128, 128, (B, H, N, N)).astype(np.int8)
+    vq = rng.integers(-128, 128, (B, H, N, Dh)).astype(np.int8)
+    pa = (rng.uniform(0.5, 1.5, H).astype(np.float32), rng.uniform(0.0, 0.01, H).astype(np.float32))
+    pv = (rng.uniform(3.0, 9.0, H).astype(np.float32), rng.uniform(-4.0, -1.0, H).astype(np.float32))
+    dO = rng.standard_normal((B, H, N, Dh)).astype(dt)
+    return aq, vq, pa, pv, dO
+
+
+def test_attention_products_are_exact_on_integers():
+    # alpha = 255, beta = 0: every de-quantized operand is the integer q + 128; integer upstream gradients
+    rng = np.random.default_rng(21)
+    B, H, N, Dh = 2, 3, 7, 4
+    aq, vq, _, _, _ = _attn_case(rng, B, H, N, Dh, np.float32)
+    one, zero = np.full(H, 255.0, np.float32), np.zeros(H, np.float32)
+    dO = rng.integers(-5, 6, (B, H, N, Dh)).astype(np.float32)
+    dA, dV = R.attn_av_bwd_q(aq, vq, B, H, N, Dh, one, zero, one, zero, dO)
+    A, V, G = aq.astype(np.int64) + 128, vq.astype(np.int64) + 128, dO.astype(np.int64)
+    assert np.array_equal(dA, np.einsum("bhid,bhjd->bhij", G, V).astype(np.float64))
+    assert np.array_equal(dV, np.einsum("bhij,bhid->bhjd", A, G).astype(np.float64))
+    dS = rng.integers(-5, 6, (B, H, N, N)).astype(np.float32)
+    dQ, dK = R.attn_qk_bwd_q(vq, aq[..., :Dh].copy(), B, H, N, Dh, one, zero, one, zero, dS, 2.0)
+    Q, K, S = vq.astype(np.int64) + 128, aq[..., :Dh].astype(np.int64) + 128, dS.astype(np.int64)
+    assert np.array_equal(dQ, 2.0 * np.einsum("bhij,bhjd->bhid", S, K))
+    assert np.array_equal(dK, 2.0 * np.einsum("bhij,bhid->bhjd", S, Q))
+
+
+@pytest.mark.parametrize("dt", [np.float32, np.float16])
+def test_attention_products_match_torch_autograd_at_the_dequantized_operands(dt):
+    rng = np.random.default_rng(22)
+    B, H, N, Dh = 2, 3, 11, 6
+    aq, vq, pa, pv, dO = _attn_case(rng, B, H, N, Dh, dt)
+    dA, dV = R.attn_av_bwd_q(aq, vq, B, H, N, Dh, pa[0], pa[1], pv[0], pv[1], dO)
+    Ah = torch.from_numpy(R.dequantize(aq, (B, H, N * N), pa[0], pa[1]).astype(np.float64).reshape(B, H, N, N)).requires_grad_()
+    Vh = torch.from_numpy(R.dequantize(vq, (B, H, N * Dh), pv[0], pv[1]).astype(np.float64).reshape(B, H, N, Dh)).requires_grad_()
+    (Ah @ Vh).backward(torch.from_numpy(dO.astype(np.float64)))
+    assert relerr(dA, Ah.grad.numpy()) < 1e-13 and relerr(dV, Vh.grad.numpy()) < 1e-13
+    # S = scale Q K^T, heads with different parameters for Q and K
+    qq, kq = vq, rng.integers(-128, 128, (B, H, N, Dh)).astype(np.int8)
+    pq, pk = pv, (rng.uniform(1.0, 2.0, H).astype(np.float32), rng.uniform(-1.0, 0.0, H).astype(np.float32))
+    dS = rng.standard_normal((B, H, N, N)).astype(dt)
+    scale = Dh ** -0.5
+    dQ, dK = R.attn_qk_bwd_q(qq, kq, B, H, N, Dh, pq[0], pq[1], pk[0], pk[1], dS, scale)
+    Qh = torch.from_numpy(R.dequantize(qq, (B, H, N * Dh), pq[0], pq[1]).astype(np.float64).reshape(B, H, N, Dh)).requires_grad_()
+    Kh = torch.from_numpy(R.dequantize(kq, (B, H, N * Dh), pk[0], pk[1]).astype(np.float64).reshape(B, H, N, Dh)).requires_grad_()
+    (scale * (Qh @ Kh.transpose(-1, -2))).backward(torch.from_numpy(dS.astype(np.float64)))
+    assert relerr(dQ, Qh.grad.numpy()) < 1e-13 and relerr(dK, Kh.grad.numpy()) < 1e-13
+
+
+def test_attention_products_against_finite_differences_of_the_whole_attention():
+    # L = sum(dO * (softmax(scale Q K^T) V)): chain the oracle's three backward steps (A V, softmax, Q K^T) with the
+    # operands on the quantization grid (x_hat = x) and compare with central differences of that forward in numpy
+    rng = np.random.default_rng(23)
+    B, H, N, Dh = 1, 2, 5, 3
+    step = 2.0 ** -6
+    cq, ck, cv = (rng.integers(0, 256, (B, H, N, Dh)) for _ in range(3))
+    alpha, beta = np.full(H, 255.0 * step, np.float32), np.array([-2.0, -1.5], np.float32)
+    Q, K, V = (c * step + beta[None, :, None, None].astype(np.float64) for c in (cq, ck, cv))
+    dO = rng.standard_normal((B, H, N, Dh))
+    scale = 0.7
+
+    def softmax(s):
+        e = np.exp(s - s.max(-1, keepdims=True))
+        return e / e.sum(-1, keepdims=True)
+
+    def loss(q, k, v):
+        return float((dO * np.einsum("bhij,bhjd->bhid", softmax(scale * np.einsum("bhid,bhjd->bhij", q, k)), v)).sum())
+
+    A = softmax(scale * np.einsum("bhid,bhjd->bhij", Q, K))
+    # the attention map is not on a grid; give the oracle a fine one so that A_hat ~ A to 2^-21
+    astep = 2.0 ** -8
+    ca = np.rint(A / astep).astype(np.int64)
+    assert ca.max() <= 255
+    Ahat = ca * astep
+    a_alpha, a_beta = np.full(H, 255.0 * astep, np.float32), np.zeros(H, np.float32)
+    to_q = lambda c: (c - 128).astype(np.int8)
+    dA, dV = R.attn_av_bwd_q(to_q(ca), to_q(cv), B, H, N, Dh, a_alpha, a_beta, alpha, beta, dO.astype(np.float32))
+    dS = R.softmax_bwd_q(to_q(ca), B, H, N, N, a_alpha, a_beta, dA.astype(np.float32))
+    dQ, dK = R.attn_qk_bwd_q(to_q(cq), to_q(ck), B, H, N, Dh, alpha, beta, alpha, beta, dS.astype(np.float32), scale)
+    # dV is linear in A_hat; compare it at A_hat exactly, and dQ / dK to the tolerance the 8-bit attention map allows
+    assert relerr(dV, np.einsum("bhij,bhid->bhjd", Ahat, dO.astype(np.float32).astype(np.float64))) < 1e-12
+    gq = fd_grad(lambda q: loss(q, K, V), Q.copy())
+    gk = fd_grad(lambda k: loss(Q, k, V), K.copy())
+    gv = fd_grad(lambda v: loss(Q, K, v), V.copy())
+    assert relerr(dV, gv) < 2e-2 and relerr(dQ, gq) < 5e-2 and relerr(dK, gk) < 5e-2
