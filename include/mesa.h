@@ -171,6 +171,30 @@ mesa_status mesa_linear_dw_q(const int8_t *xq, int64_t M, int64_t K, int64_t G,
                              const void *dy, int64_t N_out, mesa_dtype dt,
                              float *dW, float *db, void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * Backward of the two matrix products of self-attention at head-wise de-quantized operands, Sec. 3.1
+ * Eq. (2) with G_l = the gradient of a matrix product (the "MatMul" rows of the paper's overhead table;
+ * Sec. 3.2: the operands are saved as codes with one (alpha, beta) pair per head).  All tensors are
+ * (B, H, N, .) contiguous, upstream gradients and results of dt (binary16 only: MESA_F32 returns
+ * MESA_ERR_UNSUPPORTED), accumulation in binary32; any N and Dh (nothing needs to be aligned).
+ *
+ * O = A V with A the attention map (B,H,N,N) and V (B,H,N,Dh):
+ *   dA[i,j] = sum_d dO[i,d] * V_hat[j,d],    dV[j,d] = sum_i A_hat[i,j] * dO[i,d]
+ * aq, vq: codes (in).  alpha_*, beta_*: [H] (in).  dO: [B,H,N,Dh] (in).  dA: [B,H,N,N], dV: [B,H,N,Dh] (out).
+ */
+mesa_status mesa_attn_av_bwd_q(const int8_t *aq, const int8_t *vq, int64_t B, int64_t H, int64_t N, int64_t Dh,
+                               const float *alpha_a, const float *beta_a, const float *alpha_v, const float *beta_v,
+                               const void *dO, void *dA, void *dV, mesa_dtype dt, void *stream);
+
+/*
+ * S = scale * Q K^T with Q, K (B,H,N,Dh):
+ *   dQ[i,d] = scale * sum_j dS[i,j] * K_hat[j,d],    dK[j,d] = scale * sum_i dS[i,j] * Q_hat[i,d]
+ * qq, kq: codes (in).  dS: [B,H,N,N] (in; e.g. the output of mesa_softmax_bwd_q).  dQ, dK: [B,H,N,Dh] (out).
+ */
+mesa_status mesa_attn_qk_bwd_q(const int8_t *qq, const int8_t *kq, int64_t B, int64_t H, int64_t N, int64_t Dh,
+                               const float *alpha_q, const float *beta_q, const float *alpha_k, const float *beta_k,
+                               const void *dS, float scale, void *dQ, void *dK, mesa_dtype dt, void *stream);
+
 /* Scratch size in bytes for `op` at the given extents (see mesa_op); 0 for unknown ops. */
 size_t mesa_workspace_bytes(mesa_op op, int64_t d0, int64_t d1, int64_t d2, mesa_dtype dt);
 

@@ -21,7 +21,8 @@ OP_UPDATE_RUNNING_PARAMS, OP_LAYERNORM_BWD_Q, OP_LINEAR_DW_Q = 0, 1, 2
 
 EXPORTS = [
     "mesa_update_running_params", "mesa_quantize_headwise", "mesa_quantize_update_fused", "mesa_dequantize", "mesa_softmax_bwd_q",
-    "mesa_gelu_bwd_q", "mesa_layernorm_bwd_q", "mesa_linear_dw_q", "mesa_workspace_bytes",
+    "mesa_gelu_bwd_q", "mesa_layernorm_bwd_q", "mesa_linear_dw_q", "mesa_attn_av_bwd_q", "mesa_attn_qk_bwd_q",
+    "mesa_workspace_bytes",
     "mesa_status_string", "mesa_version", "mesa_stream_copy", "mesa_event_create", "mesa_event_record",
     "mesa_event_elapsed_ms", "mesa_event_destroy",
 ]
@@ -57,6 +58,8 @@ def lib() -> C.CDLL:
         L.mesa_layernorm_bwd_q.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _int,
                                            _vp, _sz, _vp]
         L.mesa_linear_dw_q.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _i64, _int, _vp, _vp, _vp, _sz, _vp]
+        L.mesa_attn_av_bwd_q.argtypes = [_vp, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _int, _vp]
+        L.mesa_attn_qk_bwd_q.argtypes = [_vp, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _f32, _vp, _vp, _int, _vp]
         L.mesa_workspace_bytes.argtypes = [_int, _i64, _i64, _i64, _int]
         L.mesa_workspace_bytes.restype = _sz
         L.mesa_status_string.argtypes = [_int]
@@ -150,6 +153,18 @@ def mesa_gelu_bwd_q(xq, layout, alpha, beta, dy, dx):
     assert dx.dtype == dy.dtype
     _check(lib().mesa_gelu_bwd_q(_ptr(xq), Layout(*layout), _ptr(alpha), _ptr(beta), _ptr(dy), _ptr(dx), _dt(dy), _stream()),
            "mesa_gelu_bwd_q")
+
+
+def mesa_attn_av_bwd_q(aq, vq, B, H, N, Dh, alpha_a, beta_a, alpha_v, beta_v, dO, dA, dV):
+    assert dA.dtype == dO.dtype == dV.dtype
+    _check(lib().mesa_attn_av_bwd_q(_ptr(aq), _ptr(vq), B, H, N, Dh, _ptr(alpha_a), _ptr(beta_a), _ptr(alpha_v), _ptr(beta_v),
+                                    _ptr(dO), _ptr(dA), _ptr(dV), _dt(dO), _stream()), "mesa_attn_av_bwd_q")
+
+
+def mesa_attn_qk_bwd_q(qq, kq, B, H, N, Dh, alpha_q, beta_q, alpha_k, beta_k, dS, scale, dQ, dK):
+    assert dQ.dtype == dS.dtype == dK.dtype
+    _check(lib().mesa_attn_qk_bwd_q(_ptr(qq), _ptr(kq), B, H, N, Dh, _ptr(alpha_q), _ptr(beta_q), _ptr(alpha_k), _ptr(beta_k),
+                                    _ptr(dS), float(scale), _ptr(dQ), _ptr(dK), _dt(dS), _stream()), "mesa_attn_qk_bwd_q")
 
 
 def mesa_layernorm_bwd_q(xq, M, D, G, alpha, beta, mean, rstd, gamma, dy, dx, dgamma, dbeta, ws):

@@ -1,0 +1,228 @@
+// attn_matmul_bwd.hip -- backward of the two matrix products of self-attention at head-wise
+// de-quantized operands (Sec. 3.1 Eq. 2 with G_l the gradient of a matrix product; Sec. 3.2: the
+// operands of the products are saved as 8-bit codes with one (alpha, beta) pair per head):
+//   O = A V           dA[i,j] = sum_d dO[i,d]*V_hat[j,d]           dV[j,d] = sum_i A_hat[i,j]*dO[i,d]
+//   S = scale Q K^T   dQ[i,d] = scale*sum_j dS[i,j]*K_hat[j,d]     dK[j,d] = scale*sum_i dS[i,j]*Q_hat[i,d]
+//
+// All four are one batched product  C[r,c] = sum_t P(r,t)*Q(t,c)  per (sample, head), where P and Q are
+// strided views of the tensors and exactly one of them is coded.  As in the weight gradient, the matrix
+// cores contract with the signed codes themselves (exact in binary16) and the head's affine map is
+// applied to the finished sums:  x_hat = s*(q+128) + beta  gives
+//   C = s * sum_t P*q  +  (beta + 128 s) * sum_t P        (Q coded; symmetric when P is),
+// the plain sums coming from one more MFMA against a fragment of ones.
+//
+// The sequence length of a vision transformer is odd (197), so rows of the attention-shaped tensors
+// start at odd offsets and nothing here can be loaded in aligned vectors.  This first version stages
+// 64 x 32 operand tiles into LDS element by element (coalesced 1- and 2-byte loads, bounds-checked
+// and zero-filled, so any extents work), transposing on the way so that both MFMA operands are read
+// back as one aligned 16-byte LDS load per lane.  binary16 tensors only.
+#include <hip/hip_runtime.h>
+
+#include "api_util.hpp"
+#include "common.hpp"
+
+namespace mesa {
+
+typedef _Float16 bm_v8h __attribute__((ext_vector_type(8)));
+typedef float bm_v16f __attribute__((ext_vector_type(16)));
+
+constexpr int kBmTile = 64;     // output tile of a workgroup (rows and columns)
+constexpr int kBmT = 32;        // contraction extent per stage
+constexpr int kBmPitch = 40;    // LDS row pitch in binary16 elements: 80 bytes, keeps every fragment 16-byte aligned
+
+struct BmmArgs {
+    const _Float16 *x;          // the plain operand
+    const int8_t *y;            // the coded operand
+    _Float16 *c;                // output, row-major R x Cn per batch
+    int64_t x_batch, y_batch, c_batch;   // elements per (sample, head)
+    int R, Cn, Tn;              // output rows, output columns, contraction extent
+    int64_t p_rs, p_ts;         // element strides of the view P(r, t)
+    int64_t q_ts, q_cs;         // element strides of the view Q(t, c)
+    int tiles_r, tiles_c;
+    int heads;
+    float scale;
+    const float *alpha, *beta;  // of the coded operand, per head
+};
+
+// P_CODED: P is the coded operand (else Q).  P_TFAST / Q_TFAST: the contraction index is the unit-stride
+// index of that operand in memory (decides which index the threads of a wave run along when loading).
+template <bool P_CODED, bool P_TFAST, bool Q_TFAST>
+__global__ __launch_bounds__(kThreads) void k_bmm_q(BmmArgs a)
+{
+    __shared__ __attribute__((aligned(16))) _Float16 LP[kBmTile * kBmPitch];
+    __shared__ __attribute__((aligned(16))) _Float16 LQ[kBmTile * kBmPitch];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tiles = a.tiles_r * a.tiles_c;
+    const int64_t b = blockIdx.x / tiles;
+    const int tile = int(blockIdx.x - b * tiles);
+    const int r0 = (tile / a.tiles_c) * kBmTile, c0 = (tile % a.tiles_c) * kBmTile;
+    const int h = int(b % a.heads);
+
+    const _Float16 *xb = a.x + b * a.x_batch;
+    const int8_t *yb = a.y + b * a.y_batch;
+
+    // element (row, t) of the P tile and (t, col) of the Q tile this thread stages in its k-th turn
+    auto p_coord = [&](int k, int &row, int &t) {
+        if (P_TFAST) { t = tid % kBmT; row = tid / kBmT + k * (kThreads / kBmT); }
+        else { row = tid % kBmTile; t = tid / kBmTile + k * (kThreads / kBmTile); }
+    };
+    auto q_coord = [&](int k, int &col, int &t) {
+        if (Q_TFAST) { t = tid % kBmT; col = tid / kBmT + k * (kThreads / kBmT); }
+        else { col = tid % kBmTile; t = tid / kBmTile + k * (kThreads / kBmTile); }
+    };
+    constexpr int kTurns = kBmTile * kBmT / kThreads;   // 8
+
+    const int wr = wave >> 1, wc = wave & 1;            // 2 x 2 waves, a 32 x 32 MFMA tile each
+    const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
+    bm_v16f acc, acc1;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { acc[v] = 0.0f; acc1[v] = 0.0f; }
+    bm_v8h ones;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) ones[j] = (_Float16)1.0f;
+
+    for (int t0 = 0; t0 < a.Tn; t0 += kBmT) {
+        _Float16 pv[kTurns], qv[kTurns];
+#pragma unroll
+        for (int k = 0; k < kTurns; ++k) {
+            int row, t;
+            p_coord(k, row, t);
+            const int r = r0 + row, tt = t0 + t;
+            pv[k] = (_Float16)0.0f;
+            if (r < a.R && tt < a.Tn) {
+                const int64_t off = int64_t(r) * a.p_rs + int64_t(tt) * a.p_ts;
+                pv[k] = P_CODED ? (_Float16)float(int(yb[off])) : xb[off];
+            }
+            int col;
+            q_coord(k, col, t);
+            const int c = c0 + col;
+            const int tq = t0 + t;
+            qv[k] = (_Float16)0.0f;
+            if (c < a.Cn && tq < a.Tn) {
+                const int64_t off = int64_t(tq) * a.q_ts + int64_t(c) * a.q_cs;
+                qv[k] = P_CODED ? xb[off] : (_Float16)float(int(yb[off]));
+            }
+        }
+        __syncthreads();   // the previous stage's fragments have been read
+#pragma unroll
+        for (int k = 0; k < kTurns; ++k) {
+            int row, col, t;
+            p_coord(k, row, t);
+            LP[row * kBmPitch + t] = pv[k];
+            q_coord(k, col, t);
+            LQ[col * kBmPitch + t] = qv[k];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < kBmT / 16; ++ks) {
+            const bm_v8h fa = *reinterpret_cast<const bm_v8h *>(&LP[(wr * 32 + frag_row) * kBmPitch + ks * 16 + frag_k]);
+            const bm_v8h fb = *reinterpret_cast<const bm_v8h *>(&LQ[(wc * 32 + frag_row) * kBmPitch + ks * 16 + frag_k]);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa, fb, acc, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(P_CODED ? ones : fa, P_CODED ? fb : ones, acc1, 0, 0, 0);
+        }
+    }
+
+    // lane l, register v of a 32 x 32 tile: row 8*(v/4) + 4*(l/32) + v%4, column l%32
+    const float s = a.alpha[h] / 255.0f;
+    const float off = fmaf(128.0f, s, a.beta[h]);
+    _Float16 *cb = a.c + b * a.c_batch;
+    const int col = c0 + wc * 32 + (lane & 31);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int row = r0 + wr * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+        if (row < a.R && col < a.Cn) cb[int64_t(row) * a.Cn + col] = (_Float16)(a.scale * fmaf(s, acc[v], off * acc1[v]));
+    }
+}
+
+template <bool P_CODED, bool P_TFAST, bool Q_TFAST> static void launch_bmm(BmmArgs a, int64_t batches, hipStream_t s)
+{
+    a.tiles_r = int(ceil_div(a.R, kBmTile));
+    a.tiles_c = int(ceil_div(a.Cn, kBmTile));
+    const int64_t grid = batches * a.tiles_r * a.tiles_c;
+    hipLaunchKernelGGL((k_bmm_q<P_CODED, P_TFAST, Q_TFAST>), dim3(unsigned(grid)), dim3(kThreads), 0, s, a);
+}
+
+static mesa_status check_attn(int64_t B, int64_t H, int64_t N, int64_t Dh, mesa_dtype dt)
+{
+    if (!valid_dtype(dt) || B < 0 || H < 0 || N < 0 || Dh < 0) return MESA_ERR_INVALID_ARG;
+    if (dt != MESA_F16) return MESA_ERR_UNSUPPORTED;
+    if (N >= (int64_t(1) << 20) || Dh >= (int64_t(1) << 20)) return MESA_ERR_UNSUPPORTED;
+    // the grid is one workgroup per (sample, head, 64 x 64 tile)
+    const long double wgs = (long double)B * (long double)H * (long double)ceil_div(N > 0 ? N : 1, kBmTile) *
+                            (long double)ceil_div(N > 0 ? N : 1, kBmTile);
+    if (wgs >= 2147483648.0L) return MESA_ERR_UNSUPPORTED;
+    return MESA_OK;
+}
+
+}  // namespace mesa
+
+using namespace mesa;
+
+extern "C" MESA_EXPORT mesa_status mesa_attn_av_bwd_q(const int8_t *aq, const int8_t *vq, int64_t B, int64_t H, int64_t N,
+                                                      int64_t Dh, const float *alpha_a, const float *beta_a,
+                                                      const float *alpha_v, const float *beta_v, const void *dO, void *dA,
+                                                      void *dV, mesa_dtype dt, void *stream)
+{
+    mesa_status st = check_attn(B, H, N, Dh, dt);
+    if (st != MESA_OK) return st;
+    if (B == 0 || H == 0 || N == 0 || Dh == 0) return MESA_OK;
+    if (!aq || !vq || !dO || !dA || !dV || !alpha_a || !beta_a || !alpha_v || !beta_v) return MESA_ERR_INVALID_ARG;
+    if (!aligned16(aq) || !aligned16(vq) || !aligned16(dO) || !aligned16(dA) || !aligned16(dV) || !aligned4(alpha_a) ||
+        !aligned4(beta_a) || !aligned4(alpha_v) || !aligned4(beta_v))
+        return MESA_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t batches = B * H;
+    BmmArgs a{};
+    a.heads = int(H);
+    a.scale = 1.0f;
+    // dA[i,j] = sum_d dO[i,d] * V_hat[j,d]:  P = dO (r = i, t = d),  Q = V (t = d, c = j)
+    a.x = static_cast<const _Float16 *>(dO); a.y = vq; a.c = static_cast<_Float16 *>(dA);
+    a.x_batch = N * Dh; a.y_batch = N * Dh; a.c_batch = N * N;
+    a.R = int(N); a.Cn = int(N); a.Tn = int(Dh);
+    a.p_rs = Dh; a.p_ts = 1; a.q_ts = 1; a.q_cs = Dh;
+    a.alpha = alpha_v; a.beta = beta_v;
+    launch_bmm<false, true, true>(a, batches, s);
+    // dV[j,d] = sum_i A_hat[i,j] * dO[i,d]:  P = A (r = j, t = i),  Q = dO (t = i, c = d)
+    a.y = aq; a.c = static_cast<_Float16 *>(dV);
+    a.y_batch = N * N; a.c_batch = N * Dh;
+    a.R = int(N); a.Cn = int(Dh); a.Tn = int(N);
+    a.p_rs = 1; a.p_ts = N; a.q_ts = Dh; a.q_cs = 1;
+    a.alpha = alpha_a; a.beta = beta_a;
+    launch_bmm<true, false, false>(a, batches, s);
+    return launch_status();
+}
+
+extern "C" MESA_EXPORT mesa_status mesa_attn_qk_bwd_q(const int8_t *qq, const int8_t *kq, int64_t B, int64_t H, int64_t N,
+                                                      int64_t Dh, const float *alpha_q, const float *beta_q,
+                                                      const float *alpha_k, const float *beta_k, const void *dS, float scale,
+                                                      void *dQ, void *dK, mesa_dtype dt, void *stream)
+{
+    mesa_status st = check_attn(B, H, N, Dh, dt);
+    if (st != MESA_OK) return st;
+    if (!(scale == scale)) return MESA_ERR_INVALID_ARG;
+    if (B == 0 || H == 0 || N == 0 || Dh == 0) return MESA_OK;
+    if (!qq || !kq || !dS || !dQ || !dK || !alpha_q || !beta_q || !alpha_k || !beta_k) return MESA_ERR_INVALID_ARG;
+    if (!aligned16(qq) || !aligned16(kq) || !aligned16(dS) || !aligned16(dQ) || !aligned16(dK) || !aligned4(alpha_q) ||
+        !aligned4(beta_q) || !aligned4(alpha_k) || !aligned4(beta_k))
+        return MESA_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t batches = B * H;
+    BmmArgs a{};
+    a.heads = int(H);
+    a.scale = scale;
+    a.x = static_cast<const _Float16 *>(dS);
+    a.x_batch = N * N; a.y_batch = N * Dh; a.c_batch = N * Dh;
+    a.R = int(N); a.Cn = int(Dh); a.Tn = int(N);
+    // dQ[i,d] = scale * sum_j dS[i,j] * K_hat[j,d]:  P = dS (r = i, t = j),  Q = K (t = j, c = d)
+    a.y = kq; a.c = static_cast<_Float16 *>(dQ);
+    a.p_rs = N; a.p_ts = 1; a.q_ts = Dh; a.q_cs = 1;
+    a.alpha = alpha_k; a.beta = beta_k;
+    launch_bmm<false, true, false>(a, batches, s);
+    // dK[j,d] = scale * sum_i dS[i,j] * Q_hat[i,d]:  P = dS (r = j, t = i),  Q = Q codes (t = i, c = d)
+    a.y = qq; a.c = static_cast<_Float16 *>(dK);
+    a.p_rs = 1; a.p_ts = N; a.q_ts = Dh; a.q_cs = 1;
+    a.alpha = alpha_q; a.beta = beta_q;
+    launch_bmm<false, false, false>(a, batches, s);
+    return launch_status();
+}

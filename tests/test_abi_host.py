@@ -71,6 +71,11 @@ def test_argument_errors_are_reported_before_any_launch(M):
     assert L.mesa_linear_dw_q(P, 100, 40, 1, P, P, P, 64, M.F16, P, None, P, 1 << 30, None) == M.ERR_UNSUPPORTED   # K % 16
     assert L.mesa_linear_dw_q(P, 100, 48, 5, P, P, P, 64, M.F16, P, None, P, 1 << 30, None) == M.ERR_INVALID_ARG   # K % G
     assert L.mesa_linear_dw_q(P, 100, 48, 3, P, P, P, 64, M.F16, P, None, P, 64, None) == M.ERR_WORKSPACE
+    assert L.mesa_attn_av_bwd_q(P, P, 2, 3, 19, 8, P, P, P, P, P, P, P, M.F32, None) == M.ERR_UNSUPPORTED          # binary16 only
+    assert L.mesa_attn_av_bwd_q(P, P, 2, 3, 19, 8, P, P, P, P, None, P, P, M.F16, None) == M.ERR_INVALID_ARG
+    assert L.mesa_attn_qk_bwd_q(P, P, 2, 3, 19, 8, P, P, P, P, P, float("nan"), P, P, M.F16, None) == M.ERR_INVALID_ARG
+    assert L.mesa_attn_qk_bwd_q(P, P + 4, 2, 3, 19, 8, P, P, P, P, P, 0.5, P, P, M.F16, None) == M.ERR_INVALID_ARG
+    assert L.mesa_attn_qk_bwd_q(None, None, 0, 3, 19, 8, None, None, None, None, None, 0.5, None, None, M.F16, None) == M.OK
     assert L.mesa_stream_copy(P, P, 24, None) == M.ERR_INVALID_ARG
     # zero elements: OK without touching anything
     assert L.mesa_quantize_headwise(None, M.F16, M.Layout(0, 3, 64), None, None, None, 0, 0, 0, None) == M.OK

@@ -346,6 +346,39 @@ def test_per_sample_statistics_through_the_layout_descriptor(M, dtype):
     assert relerr(dx2.cpu().numpy().reshape(ref2.shape), ref2) <= TOL[dtype]
 
 
+@pytest.mark.parametrize("B,H,N,Dh", [(2, 3, 19, 8), (3, 6, 197, 64), (2, 4, 64, 32), (1, 2, 130, 100), (5, 3, 49, 32)])
+def test_attention_matmul_backward_against_the_oracle(M, B, H, N, Dh):
+    """dA, dV of O = A V and dQ, dK of S = scale Q K^T at head-wise codes (binary16), chained through the
+    library's own softmax backward as a training step would."""
+    dtype = torch.float16
+    gen = torch.Generator(device="cuda").manual_seed(B * 1000 + N)
+    sig = torch.linspace(0.5, 2.0, H, device="cuda").view(1, H, 1, 1)
+    q, k, v = ((torch.randn((B, H, N, Dh), generator=gen, device="cuda") * sig + 0.1 * i).to(dtype).contiguous() for i in range(3))
+    scale = Dh ** -0.5
+    attn = torch.softmax((q.float() @ k.float().transpose(-1, -2)) * scale, dim=-1).to(dtype).contiguous()
+    codes, par, rcodes, rpar = {}, {}, {}, {}
+    for name, t, inner in (("q", q, N * Dh), ("k", k, N * Dh), ("v", v, N * Dh), ("a", attn, N * N)):
+        lay = (B, H, inner)
+        a_, b_, ra, rb = run_params(M, [t], lay)
+        c = torch.empty(t.numel(), dtype=torch.int8, device="cuda")
+        M.mesa_quantize_headwise(t, lay, a_, b_, c, M.ROUND_STOCHASTIC, 11, 0)
+        codes[name], par[name], rcodes[name], rpar[name] = c, (a_, b_), c.cpu().numpy(), (ra, rb)
+    dO = torch.randn((B, H, N, Dh), generator=gen, device="cuda").to(dtype)
+    dA = torch.empty((B, H, N, N), dtype=dtype, device="cuda")
+    dV = torch.empty_like(dO)
+    M.mesa_attn_av_bwd_q(codes["a"], codes["v"], B, H, N, Dh, *par["a"], *par["v"], dO, dA, dV)
+    rdA, rdV = R.attn_av_bwd_q(rcodes["a"], rcodes["v"], B, H, N, Dh, *rpar["a"], *rpar["v"], dO.cpu().numpy())
+    rep = {"dA": relerr(dA.cpu().numpy(), rdA), "dV": relerr(dV.cpu().numpy(), rdV)}
+    dS = torch.empty_like(dA)
+    M.mesa_softmax_bwd_q(codes["a"], B, H, N, N, *par["a"], dA, dS)
+    dQ = torch.empty_like(dO)
+    dK = torch.empty_like(dO)
+    M.mesa_attn_qk_bwd_q(codes["q"], codes["k"], B, H, N, Dh, *par["q"], *par["k"], dS, scale, dQ, dK)
+    rdQ, rdK = R.attn_qk_bwd_q(rcodes["q"], rcodes["k"], B, H, N, Dh, *rpar["q"], *rpar["k"], dS.cpu().numpy(), scale)
+    rep["dQ"], rep["dK"] = relerr(dQ.cpu().numpy(), rdQ), relerr(dK.cpu().numpy(), rdK)
+    assert all(v <= TOL[dtype] for v in rep.values()), rep
+
+
 def test_empty_inputs_are_a_no_op(M):
     z = torch.empty(0, device="cuda")
     a = torch.ones(3, device="cuda")
