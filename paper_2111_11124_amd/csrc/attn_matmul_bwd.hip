@@ -12,10 +12,12 @@
 // the plain sums coming from one more MFMA against a fragment of ones.
 //
 // The sequence length of a vision transformer is odd (197), so rows of the attention-shaped tensors
-// start at odd offsets and nothing here can be loaded in aligned vectors.  This first version stages
-// 64 x 32 operand tiles into LDS element by element (coalesced 1- and 2-byte loads, bounds-checked
-// and zero-filled, so any extents work), transposing on the way so that both MFMA operands are read
-// back as one aligned 16-byte LDS load per lane.  binary16 tensors only.
+// start at odd offsets and nothing here can be loaded in ALIGNED vectors: operand tiles of 64 x 32 are
+// staged into LDS with element-aligned 8-element loads along each operand's unit-stride index (whole
+// vectors inside the extents, single elements and zero fill at the edges, so any extents work),
+// transposing on the way where needed so that both MFMA operands are read back as one aligned
+// 16-byte LDS load per lane.  The next stage's loads are in flight while a stage is multiplied.
+// binary16 tensors only.
 #include <hip/hip_runtime.h>
 
 #include "api_util.hpp"
@@ -44,8 +46,78 @@ struct BmmArgs {
     const float *alpha, *beta;  // of the coded operand, per head
 };
 
+// Eight consecutive elements of an operand as binary16 (codes: the signed code itself), from an address
+// that is only element-aligned: the compiler emits the unaligned vector load the target allows.
+struct BmVec {
+    _Float16 e[8];
+};
+__device__ __forceinline__ BmVec bm_load8(const _Float16 *p)
+{
+    BmVec v;
+    __builtin_memcpy(&v, p, 16);
+    return v;
+}
+__device__ __forceinline__ BmVec bm_load8(const int8_t *p)
+{
+    int8_t c[8];
+    __builtin_memcpy(c, p, 8);
+    BmVec v;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v.e[j] = (_Float16)float(int(c[j]));
+    return v;
+}
+__device__ __forceinline__ _Float16 bm_load1(const _Float16 *p) { return *p; }
+__device__ __forceinline__ _Float16 bm_load1(const int8_t *p) { return (_Float16)float(int(*p)); }
+
+// One 64 x 32 operand tile per stage is 256 vectors of eight elements along the operand's unit-stride
+// index: one per thread.  TFAST (unit stride along the contraction index t): thread -> (line = tid/4,
+// t = 8*(tid%4) ..+7), written to LDS as one 16-byte store.  Otherwise (unit stride along the row /
+// column index): thread -> (t = tid/8, lines 8*(tid%8) ..+7), scattered to LDS as eight 2-byte stores
+// (the transposition).  `line` is the row of P or the column of Q.
+template <bool TFAST, typename E>
+__device__ __forceinline__ BmVec bm_stage_load(const E *base, int64_t line_stride, int64_t t_stride, int line0, int t0, int lines,
+                                               int tn, int tid)
+{
+    BmVec v;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v.e[j] = (_Float16)0.0f;
+    if (TFAST) {
+        const int line = line0 + tid / 4, t = t0 + (tid % 4) * 8;
+        if (line < lines) {
+            const E *p = base + int64_t(line) * line_stride + t;    // t_stride == 1
+            if (t + 8 <= tn) v = bm_load8(p);
+            else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (t + j < tn) v.e[j] = bm_load1(p + j);
+            }
+        }
+    } else {
+        const int t = t0 + tid / 8, line = line0 + (tid % 8) * 8;
+        if (t < tn) {
+            const E *p = base + int64_t(t) * t_stride + line;       // line_stride == 1
+            if (line + 8 <= lines) v = bm_load8(p);
+            else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (line + j < lines) v.e[j] = bm_load1(p + j);
+            }
+        }
+    }
+    return v;
+}
+template <bool TFAST> __device__ __forceinline__ void bm_stage_store(_Float16 *lds, const BmVec &v, int tid)
+{
+    if (TFAST) {
+        *reinterpret_cast<bm_v8h *>(&lds[(tid / 4) * kBmPitch + (tid % 4) * 8]) = *reinterpret_cast<const bm_v8h *>(v.e);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) lds[((tid % 8) * 8 + j) * kBmPitch + tid / 8] = v.e[j];
+    }
+}
+
 // P_CODED: P is the coded operand (else Q).  P_TFAST / Q_TFAST: the contraction index is the unit-stride
-// index of that operand in memory (decides which index the threads of a wave run along when loading).
+// index of that operand in memory.
 template <bool P_CODED, bool P_TFAST, bool Q_TFAST>
 __global__ __launch_bounds__(kThreads) void k_bmm_q(BmmArgs a)
 {
@@ -61,17 +133,14 @@ __global__ __launch_bounds__(kThreads) void k_bmm_q(BmmArgs a)
 
     const _Float16 *xb = a.x + b * a.x_batch;
     const int8_t *yb = a.y + b * a.y_batch;
-
-    // element (row, t) of the P tile and (t, col) of the Q tile this thread stages in its k-th turn
-    auto p_coord = [&](int k, int &row, int &t) {
-        if (P_TFAST) { t = tid % kBmT; row = tid / kBmT + k * (kThreads / kBmT); }
-        else { row = tid % kBmTile; t = tid / kBmTile + k * (kThreads / kBmTile); }
+    auto load_p = [&](int t0) {
+        if (P_CODED) return bm_stage_load<P_TFAST>(yb, a.p_rs, a.p_ts, r0, t0, a.R, a.Tn, tid);
+        return bm_stage_load<P_TFAST>(xb, a.p_rs, a.p_ts, r0, t0, a.R, a.Tn, tid);
     };
-    auto q_coord = [&](int k, int &col, int &t) {
-        if (Q_TFAST) { t = tid % kBmT; col = tid / kBmT + k * (kThreads / kBmT); }
-        else { col = tid % kBmTile; t = tid / kBmTile + k * (kThreads / kBmTile); }
+    auto load_q = [&](int t0) {
+        if (P_CODED) return bm_stage_load<Q_TFAST>(xb, a.q_cs, a.q_ts, c0, t0, a.Cn, a.Tn, tid);
+        return bm_stage_load<Q_TFAST>(yb, a.q_cs, a.q_ts, c0, t0, a.Cn, a.Tn, tid);
     };
-    constexpr int kTurns = kBmTile * kBmT / kThreads;   // 8
 
     const int wr = wave >> 1, wc = wave & 1;            // 2 x 2 waves, a 32 x 32 MFMA tile each
     const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
@@ -82,38 +151,16 @@ __global__ __launch_bounds__(kThreads) void k_bmm_q(BmmArgs a)
 #pragma unroll
     for (int j = 0; j < 8; ++j) ones[j] = (_Float16)1.0f;
 
+    BmVec pv = load_p(0), qv = load_q(0);
     for (int t0 = 0; t0 < a.Tn; t0 += kBmT) {
-        _Float16 pv[kTurns], qv[kTurns];
-#pragma unroll
-        for (int k = 0; k < kTurns; ++k) {
-            int row, t;
-            p_coord(k, row, t);
-            const int r = r0 + row, tt = t0 + t;
-            pv[k] = (_Float16)0.0f;
-            if (r < a.R && tt < a.Tn) {
-                const int64_t off = int64_t(r) * a.p_rs + int64_t(tt) * a.p_ts;
-                pv[k] = P_CODED ? (_Float16)float(int(yb[off])) : xb[off];
-            }
-            int col;
-            q_coord(k, col, t);
-            const int c = c0 + col;
-            const int tq = t0 + t;
-            qv[k] = (_Float16)0.0f;
-            if (c < a.Cn && tq < a.Tn) {
-                const int64_t off = int64_t(tq) * a.q_ts + int64_t(c) * a.q_cs;
-                qv[k] = P_CODED ? xb[off] : (_Float16)float(int(yb[off]));
-            }
-        }
         __syncthreads();   // the previous stage's fragments have been read
-#pragma unroll
-        for (int k = 0; k < kTurns; ++k) {
-            int row, col, t;
-            p_coord(k, row, t);
-            LP[row * kBmPitch + t] = pv[k];
-            q_coord(k, col, t);
-            LQ[col * kBmPitch + t] = qv[k];
-        }
+        bm_stage_store<P_TFAST>(LP, pv, tid);
+        bm_stage_store<Q_TFAST>(LQ, qv, tid);
         __syncthreads();
+        if (t0 + kBmT < a.Tn) {   // the next stage's loads fly while this one is multiplied
+            pv = load_p(t0 + kBmT);
+            qv = load_q(t0 + kBmT);
+        }
 #pragma unroll
         for (int ks = 0; ks < kBmT / 16; ++ks) {
             const bm_v8h fa = *reinterpret_cast<const bm_v8h *>(&LP[(wr * 32 + frag_row) * kBmPitch + ks * 16 + frag_k]);
