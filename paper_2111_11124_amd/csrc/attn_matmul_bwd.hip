@@ -106,13 +106,19 @@ __device__ __forceinline__ BmVec bm_stage_load(const E *base, int64_t line_strid
     }
     return v;
 }
+// LDS position of element (line, t) of a tile: rows of kBmPitch elements, the four 8-element chunks of a
+// row permuted by the row's group of eight (an XOR), so that the transposing scatter -- eight lanes
+// writing rows 8 apart at the same t -- spreads over the banks (any 16-byte-aligned pitch maps rows 8
+// apart onto two bank groups only: 8-way conflicts, measured at 3/4 of the kernel's time).
+__device__ __forceinline__ int bm_lds_at(int line, int t) { return line * kBmPitch + ((((t >> 3) ^ (line >> 3)) & 3) << 3) + (t & 7); }
+
 template <bool TFAST> __device__ __forceinline__ void bm_stage_store(_Float16 *lds, const BmVec &v, int tid)
 {
     if (TFAST) {
-        *reinterpret_cast<bm_v8h *>(&lds[(tid / 4) * kBmPitch + (tid % 4) * 8]) = *reinterpret_cast<const bm_v8h *>(v.e);
+        *reinterpret_cast<bm_v8h *>(&lds[bm_lds_at(tid / 4, (tid % 4) * 8)]) = *reinterpret_cast<const bm_v8h *>(v.e);
     } else {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) lds[((tid % 8) * 8 + j) * kBmPitch + tid / 8] = v.e[j];
+        for (int j = 0; j < 8; ++j) lds[bm_lds_at((tid % 8) * 8 + j, tid / 8)] = v.e[j];
     }
 }
 
@@ -163,8 +169,8 @@ __global__ __launch_bounds__(kThreads) void k_bmm_q(BmmArgs a)
         }
 #pragma unroll
         for (int ks = 0; ks < kBmT / 16; ++ks) {
-            const bm_v8h fa = *reinterpret_cast<const bm_v8h *>(&LP[(wr * 32 + frag_row) * kBmPitch + ks * 16 + frag_k]);
-            const bm_v8h fb = *reinterpret_cast<const bm_v8h *>(&LQ[(wc * 32 + frag_row) * kBmPitch + ks * 16 + frag_k]);
+            const bm_v8h fa = *reinterpret_cast<const bm_v8h *>(&LP[bm_lds_at(wr * 32 + frag_row, ks * 16 + frag_k)]);
+            const bm_v8h fb = *reinterpret_cast<const bm_v8h *>(&LQ[bm_lds_at(wc * 32 + frag_row, ks * 16 + frag_k)]);
             acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa, fb, acc, 0, 0, 0);
             acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(P_CODED ? ones : fa, P_CODED ? fb : ones, acc1, 0, 0, 0);
         }
