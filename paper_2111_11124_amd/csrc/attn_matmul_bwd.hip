@@ -14,10 +14,10 @@
 // The sequence length of a vision transformer is odd (197), so rows of the attention-shaped tensors
 // start at odd offsets and nothing here can be loaded in ALIGNED vectors: operand tiles of 64 x 32 are
 // staged into LDS with element-aligned 8-element loads along each operand's unit-stride index (whole
-// vectors inside the extents, single elements and zero fill at the edges, so any extents work),
-// transposing on the way where needed so that both MFMA operands are read back as one aligned
-// 16-byte LDS load per lane.  The next stage's loads are in flight while a stage is multiplied.
-// binary16 tensors only.
+// vectors inside the extents, single elements and zero fill at the edges, so any extents work) and
+// kept in the operand's own orientation; where that is not the orientation the MFMA wants, the
+// fragments come from the LDS transpose reads.  The next stage's loads are in flight while a stage
+// is multiplied.  binary16 tensors only.
 #include <hip/hip_runtime.h>
 
 #include "api_util.hpp"
@@ -26,11 +26,30 @@
 namespace mesa {
 
 typedef _Float16 bm_v8h __attribute__((ext_vector_type(8)));
+typedef _Float16 bm_v4h __attribute__((ext_vector_type(4)));
+typedef short bm_v4s __attribute__((ext_vector_type(4)));
+typedef int bm_v2i __attribute__((ext_vector_type(2)));
 typedef float bm_v16f __attribute__((ext_vector_type(16)));
+
+#define BM_LDS3(T, p) ((__attribute__((address_space(3))) T *)(p))
 
 constexpr int kBmTile = 64;     // output tile of a workgroup (rows and columns)
 constexpr int kBmT = 32;        // contraction extent per stage
-constexpr int kBmPitch = 40;    // LDS row pitch in binary16 elements: 80 bytes, keeps every fragment 16-byte aligned
+
+// eight signed codes (bytes) -> eight binary16 values q: 0x6400 | (byte ^ 0x80) is 1152 + q exactly
+__device__ __forceinline__ bm_v8h bm_codes_to_half8(bm_v2i raw)
+{
+    bm_v8h out;
+    const h2 k1152 = {(_Float16)1152.0f, (_Float16)1152.0f};
+#pragma unroll
+    for (int w = 0; w < 2; ++w) {
+        const uint32_t x = uint32_t(raw[w]) ^ 0x80808080u;
+        const h2 lo = as_h2(__builtin_amdgcn_perm(0x64646464u, x, 0x04010400u)) - k1152;   // bytes 0, 1
+        const h2 hi = as_h2(__builtin_amdgcn_perm(0x64646464u, x, 0x04030402u)) - k1152;   // bytes 2, 3
+        out[4 * w + 0] = lo.x; out[4 * w + 1] = lo.y; out[4 * w + 2] = hi.x; out[4 * w + 3] = hi.y;
+    }
+    return out;
+}
 
 struct BmmArgs {
     const _Float16 *x;          // the plain operand
@@ -46,89 +65,107 @@ struct BmmArgs {
     const float *alpha, *beta;  // of the coded operand, per head
 };
 
-// Eight consecutive elements of an operand as binary16 (codes: the signed code itself), from an address
-// that is only element-aligned: the compiler emits the unaligned vector load the target allows.
-struct BmVec {
-    _Float16 e[8];
+// ---- staging: global -> registers -> LDS ---------------------------------------------------------
+// A 64 x 32 operand tile per stage is 256 vectors of eight elements along the operand's unit-stride
+// index, one per thread, loaded with one element-aligned 16-byte (binary16) or 8-byte (codes) load and
+// stored to LDS as they are, in the operand's own orientation:
+//   TFAST  (unit stride along the contraction index t):  thread -> (line = tid/4, t = 8*(tid%4) ..+7),
+//          LDS rows are lines ([line][t]) and an MFMA fragment is a plain 16- or 8-byte read;
+//   !TFAST (unit stride along the row / column index):   thread -> (t = tid/8, lines 8*(tid%8) ..+7),
+//          LDS rows are contraction steps ([t][line]) and the fragment comes from gfx950's transposing
+//          LDS reads (ds_read_b64_tr_b16 / _b8: within 16 lanes, the lanes 4k..4k+3 -- 2k, 2k+1 for bytes --
+//          supply row k, and lane i receives column i).
+// `line` is the row of P or the column of Q.  Codes stay bytes in LDS and become binary16 (the signed
+// code itself, exact) in the fragment.  Row pitches are padded so that neither access conflicts.
+template <bool CODED> struct BmRaw;
+template <> struct BmRaw<false> { u32x4 w; };   // eight binary16
+template <> struct BmRaw<true> { u32x2 w; };    // eight codes
+
+template <bool CODED> struct BmElem;
+template <> struct BmElem<false> {
+    typedef _Float16 type;
+    static constexpr int kBytes = 2;
 };
-__device__ __forceinline__ BmVec bm_load8(const _Float16 *p)
-{
-    BmVec v;
-    __builtin_memcpy(&v, p, 16);
-    return v;
-}
-__device__ __forceinline__ BmVec bm_load8(const int8_t *p)
-{
-    int8_t c[8];
-    __builtin_memcpy(c, p, 8);
-    BmVec v;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) v.e[j] = (_Float16)float(int(c[j]));
-    return v;
-}
-__device__ __forceinline__ _Float16 bm_load1(const _Float16 *p) { return *p; }
-__device__ __forceinline__ _Float16 bm_load1(const int8_t *p) { return (_Float16)float(int(*p)); }
+template <> struct BmElem<true> {
+    typedef int8_t type;
+    static constexpr int kBytes = 1;
+};
 
-// One 64 x 32 operand tile per stage is 256 vectors of eight elements along the operand's unit-stride
-// index: one per thread.  TFAST (unit stride along the contraction index t): thread -> (line = tid/4,
-// t = 8*(tid%4) ..+7), written to LDS as one 16-byte store.  Otherwise (unit stride along the row /
-// column index): thread -> (t = tid/8, lines 8*(tid%8) ..+7), scattered to LDS as eight 2-byte stores
-// (the transposition).  `line` is the row of P or the column of Q.
-template <bool TFAST, typename E>
-__device__ __forceinline__ BmVec bm_stage_load(const E *base, int64_t line_stride, int64_t t_stride, int line0, int t0, int lines,
-                                               int tn, int tid)
-{
-    BmVec v;
+template <bool CODED, bool TFAST> struct BmOperand {
+    typedef typename BmElem<CODED>::type E;
+    static constexpr int kEb = BmElem<CODED>::kBytes;
+    // bytes per LDS row: [line][t]: 32 elements + 8 of padding; [t][line]: 64 elements + 32 of padding
+    static constexpr int kPitch = TFAST ? (kBmT + 8) * kEb : (kBmTile + 32) * kEb;
+    static constexpr int kBytes = TFAST ? kBmTile * kPitch : kBmT * kPitch;
+
+    __device__ static __forceinline__ BmRaw<CODED> load(const E *base, int64_t line_stride, int64_t t_stride, int line0, int t0,
+                                                        int lines, int tn, int tid)
+    {
+        BmRaw<CODED> v;
+        E e[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) v.e[j] = (_Float16)0.0f;
-    if (TFAST) {
-        const int line = line0 + tid / 4, t = t0 + (tid % 4) * 8;
-        if (line < lines) {
-            const E *p = base + int64_t(line) * line_stride + t;    // t_stride == 1
-            if (t + 8 <= tn) v = bm_load8(p);
-            else {
+        for (int j = 0; j < 8; ++j) e[j] = E(0);
+        if (TFAST) {
+            const int line = line0 + tid / 4, t = t0 + (tid % 4) * 8;
+            if (line < lines) {
+                const E *p = base + int64_t(line) * line_stride + t;    // t_stride == 1
+                if (t + 8 <= tn) __builtin_memcpy(e, p, 8 * kEb);
+                else {
 #pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    if (t + j < tn) v.e[j] = bm_load1(p + j);
+                    for (int j = 0; j < 8; ++j)
+                        if (t + j < tn) e[j] = p[j];
+                }
+            }
+        } else {
+            const int t = t0 + tid / 8, line = line0 + (tid % 8) * 8;
+            if (t < tn) {
+                const E *p = base + int64_t(t) * t_stride + line;       // line_stride == 1
+                if (line + 8 <= lines) __builtin_memcpy(e, p, 8 * kEb);
+                else {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (line + j < lines) e[j] = p[j];
+                }
             }
         }
-    } else {
-        const int t = t0 + tid / 8, line = line0 + (tid % 8) * 8;
-        if (t < tn) {
-            const E *p = base + int64_t(t) * t_stride + line;       // line_stride == 1
-            if (line + 8 <= lines) v = bm_load8(p);
-            else {
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    if (line + j < lines) v.e[j] = bm_load1(p + j);
-            }
+        __builtin_memcpy(&v.w, e, 8 * kEb);
+        return v;
+    }
+    __device__ static __forceinline__ void store(unsigned char *lds, const BmRaw<CODED> &v, int tid)
+    {
+        const int off = TFAST ? (tid / 4) * kPitch + (tid % 4) * 8 * kEb : (tid / 8) * kPitch + (tid % 8) * 8 * kEb;
+        *reinterpret_cast<decltype(v.w) *>(lds + off) = v.w;
+    }
+    // the MFMA operand of a wave's 32 lines starting at l0, contraction slots 16*ks ..+15: lane l holds line
+    // l%32 and the eight slots 8*(l/32) ..+7
+    __device__ static __forceinline__ bm_v8h frag(const unsigned char *lds, int l0, int ks, int lane)
+    {
+        if (TFAST) {
+            const unsigned char *p = lds + (l0 + (lane & 31)) * kPitch + (ks * 16 + (lane >> 5) * 8) * kEb;
+            if (CODED) return bm_codes_to_half8(*reinterpret_cast<const bm_v2i *>(p));
+            return *reinterpret_cast<const bm_v8h *>(p);
         }
+        const int blk = lane >> 4, sl = lane & 15;
+        if (CODED) {
+            const unsigned char *p = lds + (ks * 16 + (blk >> 1) * 8 + (sl >> 1)) * kPitch + l0 + (blk & 1) * 16 + (sl & 1) * 8;
+            return bm_codes_to_half8(__builtin_amdgcn_ds_read_tr8_b64_v2i32(BM_LDS3(bm_v2i, p)));
+        }
+        const unsigned char *p = lds + (ks * 16 + (blk >> 1) * 8 + (sl >> 2)) * kPitch + (l0 + (blk & 1) * 16 + (sl & 3) * 4) * 2;
+        const bm_v4h lo = __builtin_bit_cast(bm_v4h, __builtin_amdgcn_ds_read_tr16_b64_v4i16(BM_LDS3(bm_v4s, p)));
+        const bm_v4h hi = __builtin_bit_cast(bm_v4h, __builtin_amdgcn_ds_read_tr16_b64_v4i16(BM_LDS3(bm_v4s, p + 4 * kPitch)));
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     }
-    return v;
-}
-// LDS position of element (line, t) of a tile: rows of kBmPitch elements, the four 8-element chunks of a
-// row permuted by the row's group of eight (an XOR), so that the transposing scatter -- eight lanes
-// writing rows 8 apart at the same t -- spreads over the banks (any 16-byte-aligned pitch maps rows 8
-// apart onto two bank groups only: 8-way conflicts, measured at 3/4 of the kernel's time).
-__device__ __forceinline__ int bm_lds_at(int line, int t) { return line * kBmPitch + ((((t >> 3) ^ (line >> 3)) & 3) << 3) + (t & 7); }
-
-template <bool TFAST> __device__ __forceinline__ void bm_stage_store(_Float16 *lds, const BmVec &v, int tid)
-{
-    if (TFAST) {
-        *reinterpret_cast<bm_v8h *>(&lds[bm_lds_at(tid / 4, (tid % 4) * 8)]) = *reinterpret_cast<const bm_v8h *>(v.e);
-    } else {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) lds[bm_lds_at((tid % 8) * 8 + j, tid / 8)] = v.e[j];
-    }
-}
+};
 
 // P_CODED: P is the coded operand (else Q).  P_TFAST / Q_TFAST: the contraction index is the unit-stride
 // index of that operand in memory.
 template <bool P_CODED, bool P_TFAST, bool Q_TFAST>
 __global__ __launch_bounds__(kThreads) void k_bmm_q(BmmArgs a)
 {
-    __shared__ __attribute__((aligned(16))) _Float16 LP[kBmTile * kBmPitch];
-    __shared__ __attribute__((aligned(16))) _Float16 LQ[kBmTile * kBmPitch];
+    typedef BmOperand<P_CODED, P_TFAST> OP;
+    typedef BmOperand<!P_CODED, Q_TFAST> OQ;
+    __shared__ __attribute__((aligned(16))) unsigned char LP[OP::kBytes];
+    __shared__ __attribute__((aligned(16))) unsigned char LQ[OQ::kBytes];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int tiles = a.tiles_r * a.tiles_c;
@@ -140,16 +177,15 @@ __global__ __launch_bounds__(kThreads) void k_bmm_q(BmmArgs a)
     const _Float16 *xb = a.x + b * a.x_batch;
     const int8_t *yb = a.y + b * a.y_batch;
     auto load_p = [&](int t0) {
-        if (P_CODED) return bm_stage_load<P_TFAST>(yb, a.p_rs, a.p_ts, r0, t0, a.R, a.Tn, tid);
-        return bm_stage_load<P_TFAST>(xb, a.p_rs, a.p_ts, r0, t0, a.R, a.Tn, tid);
+        if constexpr (P_CODED) return OP::load(yb, a.p_rs, a.p_ts, r0, t0, a.R, a.Tn, tid);
+        else return OP::load(xb, a.p_rs, a.p_ts, r0, t0, a.R, a.Tn, tid);
     };
     auto load_q = [&](int t0) {
-        if (P_CODED) return bm_stage_load<Q_TFAST>(xb, a.q_cs, a.q_ts, c0, t0, a.Cn, a.Tn, tid);
-        return bm_stage_load<Q_TFAST>(yb, a.q_cs, a.q_ts, c0, t0, a.Cn, a.Tn, tid);
+        if constexpr (P_CODED) return OQ::load(xb, a.q_cs, a.q_ts, c0, t0, a.Cn, a.Tn, tid);
+        else return OQ::load(yb, a.q_cs, a.q_ts, c0, t0, a.Cn, a.Tn, tid);
     };
 
     const int wr = wave >> 1, wc = wave & 1;            // 2 x 2 waves, a 32 x 32 MFMA tile each
-    const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
     bm_v16f acc, acc1;
 #pragma unroll
     for (int v = 0; v < 16; ++v) { acc[v] = 0.0f; acc1[v] = 0.0f; }
@@ -157,11 +193,12 @@ __global__ __launch_bounds__(kThreads) void k_bmm_q(BmmArgs a)
 #pragma unroll
     for (int j = 0; j < 8; ++j) ones[j] = (_Float16)1.0f;
 
-    BmVec pv = load_p(0), qv = load_q(0);
+    auto pv = load_p(0);
+    auto qv = load_q(0);
     for (int t0 = 0; t0 < a.Tn; t0 += kBmT) {
         __syncthreads();   // the previous stage's fragments have been read
-        bm_stage_store<P_TFAST>(LP, pv, tid);
-        bm_stage_store<Q_TFAST>(LQ, qv, tid);
+        OP::store(LP, pv, tid);
+        OQ::store(LQ, qv, tid);
         __syncthreads();
         if (t0 + kBmT < a.Tn) {   // the next stage's loads fly while this one is multiplied
             pv = load_p(t0 + kBmT);
@@ -169,8 +206,8 @@ __global__ __launch_bounds__(kThreads) void k_bmm_q(BmmArgs a)
         }
 #pragma unroll
         for (int ks = 0; ks < kBmT / 16; ++ks) {
-            const bm_v8h fa = *reinterpret_cast<const bm_v8h *>(&LP[bm_lds_at(wr * 32 + frag_row, ks * 16 + frag_k)]);
-            const bm_v8h fb = *reinterpret_cast<const bm_v8h *>(&LQ[bm_lds_at(wc * 32 + frag_row, ks * 16 + frag_k)]);
+            const bm_v8h fa = OP::frag(LP, wr * 32, ks, lane);
+            const bm_v8h fb = OQ::frag(LQ, wc * 32, ks, lane);
             acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa, fb, acc, 0, 0, 0);
             acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(P_CODED ? ones : fa, P_CODED ? fb : ones, acc1, 0, 0, 0);
         }
