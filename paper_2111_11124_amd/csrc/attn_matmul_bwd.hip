@@ -35,6 +35,7 @@ typedef float bm_v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kBmTile = 64;     // output tile of a workgroup (rows and columns)
 constexpr int kBmT = 32;        // contraction extent per stage
+constexpr int kBmParts = kBmT / 32;   // 8-element vectors per thread, operand and stage
 
 // eight signed codes (bytes) -> eight binary16 values q: 0x6400 | (byte ^ 0x80) is 1152 + q exactly
 __device__ __forceinline__ bm_v8h bm_codes_to_half8(bm_v2i raw)
@@ -66,12 +67,12 @@ struct BmmArgs {
 };
 
 // ---- staging: global -> registers -> LDS ---------------------------------------------------------
-// A 64 x 32 operand tile per stage is 256 vectors of eight elements along the operand's unit-stride
-// index, one per thread, loaded with one element-aligned 16-byte (binary16) or 8-byte (codes) load and
-// stored to LDS as they are, in the operand's own orientation:
-//   TFAST  (unit stride along the contraction index t):  thread -> (line = tid/4, t = 8*(tid%4) ..+7),
+// A 64 x kBmT operand tile per stage is kBmParts * 256 vectors of eight elements along the operand's
+// unit-stride index (vector idx = tid + 256 * part), each loaded with one element-aligned 16-byte
+// (binary16) or 8-byte (codes) load and stored to LDS as it is, in the operand's own orientation:
+//   TFAST  (unit stride along the contraction index t):  idx -> (line = idx / (kBmT/8), t = 8 * (idx % (kBmT/8)) ..+7),
 //          LDS rows are lines ([line][t]) and an MFMA fragment is a plain 16- or 8-byte read;
-//   !TFAST (unit stride along the row / column index):   thread -> (t = tid/8, lines 8*(tid%8) ..+7),
+//   !TFAST (unit stride along the row / column index):   idx -> (t = idx/8, lines 8*(idx%8) ..+7),
 //          LDS rows are contraction steps ([t][line]) and the fragment comes from gfx950's transposing
 //          LDS reads (ds_read_b64_tr_b16 / _b8: within 16 lanes, the lanes 4k..4k+3 -- 2k, 2k+1 for bytes --
 //          supply row k, and lane i receives column i).
@@ -91,50 +92,86 @@ template <> struct BmElem<true> {
     static constexpr int kBytes = 1;
 };
 
+// Edges.  Rows of P / columns of Q beyond the extents produce output rows / columns that are never
+// written, so they may hold any finite data; contraction steps t >= Tn must contribute nothing, so both
+// operands hold zeros there (never stale LDS contents: 0 x NaN would poison a sum).  Every load is an
+// unconditional whole-vector load from coordinates clamped into the tensor (no branch, no merge with
+// other values: nothing waits on a load before its stage is due); a vector that was moved back to stay
+// inside the extent is written to LDS at the position it really came from (element by element: the
+// slots overlap the neighbouring vector's, with the same values), and zeros are written where required.
 template <bool CODED, bool TFAST> struct BmOperand {
     typedef typename BmElem<CODED>::type E;
     static constexpr int kEb = BmElem<CODED>::kBytes;
-    // bytes per LDS row: [line][t]: 32 elements + 8 of padding; [t][line]: 64 elements + 32 of padding
+    // bytes per LDS row: [line][t]: kBmT elements + 8 of padding; [t][line]: 64 elements + 32 of padding
     static constexpr int kPitch = TFAST ? (kBmT + 8) * kEb : (kBmTile + 32) * kEb;
     static constexpr int kBytes = TFAST ? kBmTile * kPitch : kBmT * kPitch;
+    typedef decltype(BmRaw<CODED>::w) W;
 
-    __device__ static __forceinline__ BmRaw<CODED> load(const E *base, int64_t line_stride, int64_t t_stride, int line0, int t0,
-                                                        int lines, int tn, int tid)
+    // tile-relative coordinates of vector idx: (line, t) of its first element
+    __device__ static __forceinline__ void coord(int idx, int &line, int &t)
     {
+        if (TFAST) { line = idx / (kBmT / 8); t = (idx % (kBmT / 8)) * 8; }
+        else { t = idx / 8; line = (idx % 8) * 8; }
+    }
+    // lines >= 8 and tn >= 8 (checked by the entry points)
+    __device__ static __forceinline__ BmRaw<CODED> load(const E *base, int64_t line_stride, int64_t t_stride, int line0, int t0,
+                                                        int lines, int tn, int idx)
+    {
+        int line, t;
+        coord(idx, line, t);
+        line += line0;
+        t += t0;
         BmRaw<CODED> v;
-        E e[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) e[j] = E(0);
         if (TFAST) {
-            const int line = line0 + tid / 4, t = t0 + (tid % 4) * 8;
-            if (line < lines) {
-                const E *p = base + int64_t(line) * line_stride + t;    // t_stride == 1
-                if (t + 8 <= tn) __builtin_memcpy(e, p, 8 * kEb);
-                else {
-#pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        if (t + j < tn) e[j] = p[j];
-                }
-            }
+            line = line < lines ? line : lines - 1;
+            t = t + 8 <= tn ? t : tn - 8;
+            __builtin_memcpy(&v.w, base + int64_t(line) * line_stride + t, 8 * kEb);       // t_stride == 1
         } else {
-            const int t = t0 + tid / 8, line = line0 + (tid % 8) * 8;
-            if (t < tn) {
-                const E *p = base + int64_t(t) * t_stride + line;       // line_stride == 1
-                if (line + 8 <= lines) __builtin_memcpy(e, p, 8 * kEb);
-                else {
-#pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        if (line + j < lines) e[j] = p[j];
-                }
-            }
+            t = t < tn ? t : tn - 1;
+            line = line + 8 <= lines ? line : lines - 8;
+            __builtin_memcpy(&v.w, base + int64_t(t) * t_stride + line, 8 * kEb);          // line_stride == 1
         }
-        __builtin_memcpy(&v.w, e, 8 * kEb);
         return v;
     }
-    __device__ static __forceinline__ void store(unsigned char *lds, const BmRaw<CODED> &v, int tid)
+    __device__ static __forceinline__ void store(unsigned char *lds, const BmRaw<CODED> &v, int line0, int t0, int lines, int tn,
+                                                 int idx)
     {
-        const int off = TFAST ? (tid / 4) * kPitch + (tid % 4) * 8 * kEb : (tid / 8) * kPitch + (tid % 8) * 8 * kEb;
-        *reinterpret_cast<decltype(v.w) *>(lds + off) = v.w;
+        int line, t;
+        coord(idx, line, t);
+        E e[8];
+        __builtin_memcpy(e, &v.w, 8 * kEb);
+        W zero;
+#pragma unroll
+        for (int k = 0; k < int(sizeof(W) / 4); ++k) zero[k] = 0u;
+        if (TFAST) {
+            unsigned char *row = lds + line * kPitch;
+            const int tg = t0 + t;                                   // global contraction index of slot t
+            if (tg + 8 <= tn) {
+                *reinterpret_cast<W *>(row + t * kEb) = v.w;
+            } else if (tg < tn) {                                    // the vector was moved back to tn - 8
+                const int tc = tn - 8 - t0;                          // tile-relative slot of its first element (>= -7)
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (tc + i >= t) reinterpret_cast<E *>(row)[tc + i] = e[i];
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (tg + j >= tn) reinterpret_cast<E *>(row)[t + j] = E(0);
+            } else {
+                *reinterpret_cast<W *>(row + t * kEb) = zero;
+            }
+        } else {
+            unsigned char *row = lds + t * kPitch;
+            const bool t_ok = t0 + t < tn;
+            const int lg = line0 + line;
+            if (lg + 8 <= lines || lg >= lines) {                    // whole vector inside, or wholly outside (anything will do)
+                *reinterpret_cast<W *>(row + line * kEb) = t_ok ? v.w : zero;
+            } else {                                                 // moved back to lines - 8
+                const int lc = lines - 8 - line0;
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (lc + i >= line) reinterpret_cast<E *>(row)[lc + i] = t_ok ? e[i] : E(0);
+            }
+        }
     }
     // the MFMA operand of a wave's 32 lines starting at l0, contraction slots 16*ks ..+15: lane l holds line
     // l%32 and the eight slots 8*(l/32) ..+7
@@ -160,7 +197,7 @@ template <bool CODED, bool TFAST> struct BmOperand {
 // P_CODED: P is the coded operand (else Q).  P_TFAST / Q_TFAST: the contraction index is the unit-stride
 // index of that operand in memory.
 template <bool P_CODED, bool P_TFAST, bool Q_TFAST>
-__global__ __launch_bounds__(kThreads) void k_bmm_q(BmmArgs a)
+__global__ __launch_bounds__(kThreads, 6) void k_bmm_q(BmmArgs a)
 {
     typedef BmOperand<P_CODED, P_TFAST> OP;
     typedef BmOperand<!P_CODED, Q_TFAST> OQ;
@@ -176,13 +213,13 @@ __global__ __launch_bounds__(kThreads) void k_bmm_q(BmmArgs a)
 
     const _Float16 *xb = a.x + b * a.x_batch;
     const int8_t *yb = a.y + b * a.y_batch;
-    auto load_p = [&](int t0) {
-        if constexpr (P_CODED) return OP::load(yb, a.p_rs, a.p_ts, r0, t0, a.R, a.Tn, tid);
-        else return OP::load(xb, a.p_rs, a.p_ts, r0, t0, a.R, a.Tn, tid);
+    auto load_p = [&](int t0, int part) {
+        if constexpr (P_CODED) return OP::load(yb, a.p_rs, a.p_ts, r0, t0, a.R, a.Tn, tid + part * kThreads);
+        else return OP::load(xb, a.p_rs, a.p_ts, r0, t0, a.R, a.Tn, tid + part * kThreads);
     };
-    auto load_q = [&](int t0) {
-        if constexpr (P_CODED) return OQ::load(xb, a.q_cs, a.q_ts, c0, t0, a.Cn, a.Tn, tid);
-        else return OQ::load(yb, a.q_cs, a.q_ts, c0, t0, a.Cn, a.Tn, tid);
+    auto load_q = [&](int t0, int part) {
+        if constexpr (P_CODED) return OQ::load(xb, a.q_cs, a.q_ts, c0, t0, a.Cn, a.Tn, tid + part * kThreads);
+        else return OQ::load(yb, a.q_cs, a.q_ts, c0, t0, a.Cn, a.Tn, tid + part * kThreads);
     };
 
     const int wr = wave >> 1, wc = wave & 1;            // 2 x 2 waves, a 32 x 32 MFMA tile each
@@ -193,16 +230,21 @@ __global__ __launch_bounds__(kThreads) void k_bmm_q(BmmArgs a)
 #pragma unroll
     for (int j = 0; j < 8; ++j) ones[j] = (_Float16)1.0f;
 
-    auto pv = load_p(0);
-    auto qv = load_q(0);
+    BmRaw<P_CODED> pv[kBmParts];
+    BmRaw<!P_CODED> qv[kBmParts];
+#pragma unroll
+    for (int k = 0; k < kBmParts; ++k) { pv[k] = load_p(0, k); qv[k] = load_q(0, k); }
     for (int t0 = 0; t0 < a.Tn; t0 += kBmT) {
         __syncthreads();   // the previous stage's fragments have been read
-        OP::store(LP, pv, tid);
-        OQ::store(LQ, qv, tid);
+#pragma unroll
+        for (int k = 0; k < kBmParts; ++k) {
+            OP::store(LP, pv[k], r0, t0, a.R, a.Tn, tid + k * kThreads);
+            OQ::store(LQ, qv[k], c0, t0, a.Cn, a.Tn, tid + k * kThreads);
+        }
         __syncthreads();
         if (t0 + kBmT < a.Tn) {   // the next stage's loads fly while this one is multiplied
-            pv = load_p(t0 + kBmT);
-            qv = load_q(t0 + kBmT);
+#pragma unroll
+            for (int k = 0; k < kBmParts; ++k) { pv[k] = load_p(t0 + kBmT, k); qv[k] = load_q(t0 + kBmT, k); }
         }
 #pragma unroll
         for (int ks = 0; ks < kBmT / 16; ++ks) {
@@ -238,6 +280,7 @@ static mesa_status check_attn(int64_t B, int64_t H, int64_t N, int64_t Dh, mesa_
     if (!valid_dtype(dt) || B < 0 || H < 0 || N < 0 || Dh < 0) return MESA_ERR_INVALID_ARG;
     if (dt != MESA_F16) return MESA_ERR_UNSUPPORTED;
     if (N >= (int64_t(1) << 20) || Dh >= (int64_t(1) << 20)) return MESA_ERR_UNSUPPORTED;
+    if ((N > 0 && N < 8) || (Dh > 0 && Dh < 8)) return MESA_ERR_UNSUPPORTED;   // an extent shorter than one load vector
     // the grid is one workgroup per (sample, head, 64 x 64 tile)
     const long double wgs = (long double)B * (long double)H * (long double)ceil_div(N > 0 ? N : 1, kBmTile) *
                             (long double)ceil_div(N > 0 ? N : 1, kBmTile);
