@@ -61,6 +61,8 @@ struct BmmArgs {
     int64_t p_rs, p_ts;         // element strides of the view P(r, t)
     int64_t q_ts, q_cs;         // element strides of the view Q(t, c)
     int tiles_r, tiles_c;
+    int64_t batch0;             // first (sample, head) of this launch
+    int head0;                  // and its head: batch0 % heads
     int heads;
     float scale;
     const float *alpha, *beta;  // of the coded operand, per head
@@ -138,6 +140,10 @@ template <bool CODED, bool TFAST> struct BmOperand {
     {
         int line, t;
         coord(idx, line, t);
+        if (line0 + kBmTile <= lines && t0 + kBmT <= tn) {   // uniform: the whole tile lies inside the extents
+            *reinterpret_cast<W *>(lds + (TFAST ? line * kPitch + t * kEb : t * kPitch + line * kEb)) = v.w;
+            return;
+        }
         E e[8];
         __builtin_memcpy(e, &v.w, 8 * kEb);
         W zero;
@@ -205,14 +211,13 @@ __global__ __launch_bounds__(kThreads, 6) void k_bmm_q(BmmArgs a)
     __shared__ __attribute__((aligned(16))) unsigned char LQ[OQ::kBytes];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int tiles = a.tiles_r * a.tiles_c;
-    const int64_t b = blockIdx.x / tiles;
-    const int tile = int(blockIdx.x - b * tiles);
-    const int r0 = (tile / a.tiles_c) * kBmTile, c0 = (tile % a.tiles_c) * kBmTile;
-    const int h = int(b % a.heads);
+    // grid: x = column tile, y = row tile, z = (sample, head) in pieces of at most 65535 (32-bit, uniform arithmetic only)
+    const uint32_t b = blockIdx.z;
+    const int r0 = int(blockIdx.y) * kBmTile, c0 = int(blockIdx.x) * kBmTile;
+    const uint32_t h = (b + uint32_t(a.head0)) % uint32_t(a.heads);
 
-    const _Float16 *xb = a.x + b * a.x_batch;
-    const int8_t *yb = a.y + b * a.y_batch;
+    const _Float16 *xb = a.x + int64_t(b) * a.x_batch + a.batch0 * a.x_batch;
+    const int8_t *yb = a.y + int64_t(b) * a.y_batch + a.batch0 * a.y_batch;
     auto load_p = [&](int t0, int part) {
         if constexpr (P_CODED) return OP::load(yb, a.p_rs, a.p_ts, r0, t0, a.R, a.Tn, tid + part * kThreads);
         else return OP::load(xb, a.p_rs, a.p_ts, r0, t0, a.R, a.Tn, tid + part * kThreads);
@@ -258,12 +263,17 @@ __global__ __launch_bounds__(kThreads, 6) void k_bmm_q(BmmArgs a)
     // lane l, register v of a 32 x 32 tile: row 8*(v/4) + 4*(l/32) + v%4, column l%32
     const float s = a.alpha[h] / 255.0f;
     const float off = fmaf(128.0f, s, a.beta[h]);
-    _Float16 *cb = a.c + b * a.c_batch;
     const int col = c0 + wc * 32 + (lane & 31);
+    const int row_l = r0 + wr * 32 + (lane >> 5) * 4;
+    // R * Cn < 2^31 (checked by the entry points): 32-bit offsets from the batch's base
+    _Float16 *cb = a.c + (int64_t(b) + a.batch0) * a.c_batch;
+    const uint32_t o0 = uint32_t(row_l) * uint32_t(a.Cn) + uint32_t(col);
+    if (col < a.Cn) {
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int row = r0 + wr * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-        if (row < a.R && col < a.Cn) cb[int64_t(row) * a.Cn + col] = (_Float16)(a.scale * fmaf(s, acc[v], off * acc1[v]));
+        for (int v = 0; v < 16; ++v) {
+            const int dr = (v >> 2) * 8 + (v & 3);
+            if (row_l + dr < a.R) cb[o0 + uint32_t(dr) * uint32_t(a.Cn)] = (_Float16)(a.scale * fmaf(s, acc[v], off * acc1[v]));
+        }
     }
 }
 
@@ -271,8 +281,14 @@ template <bool P_CODED, bool P_TFAST, bool Q_TFAST> static void launch_bmm(BmmAr
 {
     a.tiles_r = int(ceil_div(a.R, kBmTile));
     a.tiles_c = int(ceil_div(a.Cn, kBmTile));
-    const int64_t grid = batches * a.tiles_r * a.tiles_c;
-    hipLaunchKernelGGL((k_bmm_q<P_CODED, P_TFAST, Q_TFAST>), dim3(unsigned(grid)), dim3(kThreads), 0, s, a);
+    // the z extent of a grid is limited to 65535: more (sample, head) pairs than that go in several launches
+    for (int64_t b0 = 0; b0 < batches; b0 += 65535) {
+        a.batch0 = b0;
+        a.head0 = int(b0 % a.heads);
+        const int64_t nb = batches - b0 < 65535 ? batches - b0 : 65535;
+        hipLaunchKernelGGL((k_bmm_q<P_CODED, P_TFAST, Q_TFAST>), dim3(unsigned(a.tiles_c), unsigned(a.tiles_r), unsigned(nb)),
+                           dim3(kThreads), 0, s, a);
+    }
 }
 
 static mesa_status check_attn(int64_t B, int64_t H, int64_t N, int64_t Dh, mesa_dtype dt)
@@ -281,10 +297,10 @@ static mesa_status check_attn(int64_t B, int64_t H, int64_t N, int64_t Dh, mesa_
     if (dt != MESA_F16) return MESA_ERR_UNSUPPORTED;
     if (N >= (int64_t(1) << 20) || Dh >= (int64_t(1) << 20)) return MESA_ERR_UNSUPPORTED;
     if ((N > 0 && N < 8) || (Dh > 0 && Dh < 8)) return MESA_ERR_UNSUPPORTED;   // an extent shorter than one load vector
-    // the grid is one workgroup per (sample, head, 64 x 64 tile)
-    const long double wgs = (long double)B * (long double)H * (long double)ceil_div(N > 0 ? N : 1, kBmTile) *
-                            (long double)ceil_div(N > 0 ? N : 1, kBmTile);
-    if (wgs >= 2147483648.0L) return MESA_ERR_UNSUPPORTED;
+    // 32-bit element offsets inside one (sample, head); the row / column tile counts fit a grid dimension
+    if ((long double)N * (long double)N >= 2147483648.0L || (long double)N * (long double)Dh >= 2147483648.0L)
+        return MESA_ERR_UNSUPPORTED;
+    if ((long double)B * (long double)H >= 9.0e15L) return MESA_ERR_UNSUPPORTED;
     return MESA_OK;
 }
 
