@@ -199,6 +199,50 @@ def cpu_baseline(spec, target_seconds=20.0):
                       f"({el:.1f} s of CPU work; same algorithmic-byte accounting as the GPU figure)"}
 
 
+def attention_matmul_leg(m, spec, steps):
+    """Outside the headline figure: backward of the two attention matrix products at head-wise codes
+    (mesa_attn_av_bwd_q, mesa_attn_qk_bwd_q) on the configuration's attention shape, synthetic codes."""
+    if spec.dtype != torch.float16:
+        return None
+    B, H, N, _ = spec.attn
+    Dh = spec.dim // spec.heads
+    dev = "cuda"
+    g = torch.Generator(device=dev).manual_seed(spec.seed)
+    sets = []
+    for _ in range(NSETS):
+        sets.append({
+            "a": torch.randint(-128, 128, (B, H, N, N), dtype=torch.int8, device=dev, generator=g),
+            "qkv": [torch.randint(-128, 128, (B, H, N, Dh), dtype=torch.int8, device=dev, generator=g) for _ in range(3)],
+            "dO": torch.randn((B, H, N, Dh), device=dev, generator=g).to(spec.dtype),
+            "dS": torch.randn((B, H, N, N), device=dev, generator=g).to(spec.dtype),
+            "dA": torch.empty((B, H, N, N), dtype=spec.dtype, device=dev),
+            "d3": [torch.empty((B, H, N, Dh), dtype=spec.dtype, device=dev) for _ in range(3)],
+        })
+    al = torch.full((H,), 3.0, device=dev)
+    be = torch.full((H,), -1.5, device=dev)
+
+    def run(i):
+        t = sets[i % NSETS]
+        m.mesa_attn_av_bwd_q(t["a"], t["qkv"][2], B, H, N, Dh, al, be, al, be, t["dO"], t["dA"], t["d3"][2])
+        m.mesa_attn_qk_bwd_q(t["qkv"][0], t["qkv"][1], B, H, N, Dh, al, be, al, be, t["dS"], Dh ** -0.5, t["d3"][0], t["d3"][1])
+
+    for i in range(3):
+        run(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        run(i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    n2, nd = B * H * N * N, B * H * N * Dh
+    nbytes = (n2 + nd + 2 * nd + 2 * n2 + 2 * nd) + (2 * nd + 2 * n2 + 4 * nd)
+    flops = 4 * 2.0 * B * H * N * N * Dh
+    return {"ms": round(ms, 4), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1), "frac_hbm": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "tflops": round(flops / (ms * 1e-3) / 1e12, 1), "bytes": nbytes, "shape": [B, H, N, Dh],
+            "note": "the four products dA, dV, dQ, dK of one block (two calls); HBM-bound: codes, upstream gradients and "
+                    "results each moved once"}
+
+
 def workload_name(spec, number, lin):
     b, h, r, c = spec.attn
     dw = f"whole path incl. dW {lin[0]}->{lin[1]}" if lin else "whole path, no Linear layer named"
@@ -323,6 +367,7 @@ def main():
                                 "bytes_per_step": sp_bytes,
                                 "note": "variant, not the headline: mesa_quantize_update_fused replaces update + quantize (x read "
                                         "once; parameters lag one step), the backward half unchanged"},
+        "attention_matmul_bwd": attention_matmul_leg(m, spec, args.steps) if args.config != 5 else None,
         "per_call": {k: {"ms": round(v, 5), "GBps": round(bytes_per[k] / (v * 1e-3) / 1e9, 1),
                          "frac_hbm": round(bytes_per[k] / (v * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)} for k, v in per_kernel_ms.items()},
     }
