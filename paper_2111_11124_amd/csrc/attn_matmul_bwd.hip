@@ -26,6 +26,7 @@
 namespace mesa {
 
 typedef _Float16 bm_v8h __attribute__((ext_vector_type(8)));
+typedef _Float16 bm_v2h __attribute__((ext_vector_type(2)));
 typedef _Float16 bm_v4h __attribute__((ext_vector_type(4)));
 typedef short bm_v4s __attribute__((ext_vector_type(4)));
 typedef int bm_v2i __attribute__((ext_vector_type(2)));
@@ -291,6 +292,324 @@ template <bool P_CODED, bool P_TFAST, bool Q_TFAST> static void launch_bmm(BmmAr
     }
 }
 
+// ---- the two products whose contraction index is the unit-stride index of BOTH operands' rows --------
+// They need no transposition and (almost) no LDS: an MFMA operand fragment -- lane l: line l%32, the eight
+// contraction slots 8*(l/32) ..+7 of a 16-slot step -- is one vector load straight from global memory.
+
+// dA[i,j] = sum_d dO[i,d] * V_hat[j,d].  A workgroup takes 32 rows i of one head; its waves share out the
+// blocks of 32 columns j.  Both operands' blocks are contiguous in memory (32 rows of dO, 32 rows of V
+// codes): they come in as consecutive aligned 16-byte vectors -- a lane per row would cost the memory
+// pipeline one access per lane -- and pass through LDS (dO once per workgroup, the codes privately per
+// wave) into the fragments.  The MFMA runs with the operands exchanged (codes as the M side, dO as the N
+// side), so that a lane ends up with ONE row i = l%32 and runs of four consecutive columns: the beta term's
+// row sum of dO is then a per-lane scalar, and the tile goes to LDS with 8-byte writes.  The 32 x N output
+// block is one contiguous piece of memory whose start is only element-aligned (N is odd for ViT): LDS holds
+// it at the same offset from a 16-byte boundary, and it leaves as aligned 16-byte vectors; the few elements
+// before the first and after the last whole vector are written one by one (the neighbouring blocks own the
+// rest of those vectors).  Dh == 16 * KS, KS even.
+// LDS: [output block, 64 N + 32 bytes | staged dO, 32 rows]  (the same space, one after the other in time),
+// then 32 code rows per wave at `codes_at`.
+// SOLO (short rows, N <= 64): a wave takes an item (head, block of 32 rows) all by itself, with its own
+// piece of LDS and no barrier, so that no wave of the workgroup idles for want of column blocks.
+template <int KS> struct DaCfg {
+    static constexpr int Dh = 16 * KS;
+    static constexpr int kRowO = 2 * Dh + 16;   // bytes per staged dO row (padded against bank conflicts)
+    static constexpr int kRowV = Dh + 16;       // bytes per staged code row
+    static constexpr int kVecO = Dh / 8;        // 16-byte vectors per dO row
+    static constexpr int kVecV = Dh / 16;       // and per code row
+    static constexpr int kCodeVecs = 32 * kVecV / 64;   // vectors per lane for a block of 32 code rows
+    static constexpr int kWaves = kThreads / 64;
+    // offset of the staged codes: behind the output block / the staged dO rows, whichever is longer
+    static size_t codes_at(int64_t N)
+    {
+        const size_t out = size_t(N) * 64 + 32, stage = size_t(32) * kRowO;
+        return ((out > stage ? out : stage) + 15) & ~size_t(15);
+    }
+    static size_t wave_bytes(int64_t N) { return codes_at(N) + size_t(32) * kRowV; }           // SOLO: per wave
+    static size_t lds_bytes(int64_t N, bool solo) { return solo ? kWaves * wave_bytes(N) : codes_at(N) + size_t(kWaves) * 32 * kRowV; }
+};
+
+template <int KS, bool SOLO>
+__global__ __launch_bounds__(kThreads, KS <= 4 ? 7 : 4) void k_attn_da(const _Float16 *__restrict__ dO,
+                                                                      const int8_t *__restrict__ vq, _Float16 *__restrict__ dA,
+                                                                      int N, int heads, const float *__restrict__ alpha_v,
+                                                                      const float *__restrict__ beta_v, int64_t batch0, int codes_at,
+                                                                      unsigned items)
+{
+    typedef DaCfg<KS> C;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_all[];
+    constexpr int Dh = C::Dh;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int fl = lane & 31, fk = (lane >> 5) * 8;
+    const int nblocks = (N + 31) >> 5;
+    // the threads that share an item, this thread's rank among them, and the column blocks this wave takes
+    constexpr int kTeam = SOLO ? 64 : kThreads;
+    const int t = SOLO ? lane : int(threadIdx.x);
+    const int cb_first = SOLO ? 0 : wave, cb_step = SOLO ? 1 : C::kWaves;
+    int64_t bh;
+    int r0;
+    if (SOLO) {                                            // items (at most 2^32) count (head, row block) pairs
+        const unsigned item = blockIdx.x * C::kWaves + wave;
+        if (item >= items) return;                         // no barrier in this mode
+        const unsigned q = item / unsigned(nblocks);
+        bh = q;
+        r0 = int(item - q * unsigned(nblocks)) * 32;
+    } else {
+        bh = batch0 + blockIdx.y;
+        r0 = int(blockIdx.x) * 32;
+    }
+    auto team_sync = [&]() {
+        if constexpr (!SOLO) __syncthreads();
+    };
+    unsigned char *lds_da = SOLO ? lds_all + wave * (codes_at + 32 * C::kRowV) : lds_all;
+    unsigned char *lv = SOLO ? lds_da + codes_at : lds_all + codes_at + wave * (32 * C::kRowV);
+    constexpr int kOVecs = (32 * C::kVecO + kTeam - 1) / kTeam;   // dO vectors per thread
+    const int code_vecs = N * C::kVecV;                    // of one head
+    const int rows = N - r0 < 32 ? N - r0 : 32;
+    const u32x4 *vvec = reinterpret_cast<const u32x4 *>(vq + bh * N * int64_t(Dh));
+    auto load_codes = [&](int c0, u32x4 (&raw)[C::kCodeVecs]) {
+#pragma unroll
+        for (int i = 0; i < C::kCodeVecs; ++i) {
+            const int g = c0 * C::kVecV + lane + 64 * i;   // rows past the head's end repeat its last vector; never used
+            raw[i] = vvec[g < code_vecs ? g : code_vecs - 1];
+        }
+    };
+    auto store_codes = [&](const u32x4 (&raw)[C::kCodeVecs]) {
+#pragma unroll
+        for (int i = 0; i < C::kCodeVecs; ++i) {
+            const int idx = lane + 64 * i;
+            *reinterpret_cast<u32x4 *>(lv + (idx / C::kVecV) * C::kRowV + (idx % C::kVecV) * 16) = raw[i];
+        }
+    };
+    u32x4 raw[C::kCodeVecs];
+    if (cb_first < nblocks) load_codes(cb_first * 32, raw);
+    {
+        const int o_vecs = rows * C::kVecO;
+        const u32x4 *ovec = reinterpret_cast<const u32x4 *>(dO + (bh * N + r0) * int64_t(Dh));
+        u32x4 ov[kOVecs];
+#pragma unroll
+        for (int k = 0; k < kOVecs; ++k) {                 // rows past the last one repeat its last vector
+            const int idx = t + k * kTeam;
+            ov[k] = ovec[idx < o_vecs ? idx : o_vecs - 1];
+        }
+#pragma unroll
+        for (int k = 0; k < kOVecs; ++k) {
+            const int idx = t + k * kTeam;
+            if (idx < 32 * C::kVecO) *reinterpret_cast<u32x4 *>(lds_da + (idx / C::kVecO) * C::kRowO + (idx % C::kVecO) * 16) = ov[k];
+        }
+    }
+    team_sync();
+    bm_v8h fo[KS];
+    float rsum = 0.0f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        fo[ks] = *reinterpret_cast<const bm_v8h *>(lds_da + fl * C::kRowO + (ks * 16 + fk) * 2);
+#pragma unroll
+        for (int j = 0; j < 8; j += 2)
+            rsum = __builtin_amdgcn_fdot2(bm_v2h{fo[ks][j], fo[ks][j + 1]}, bm_v2h{(_Float16)1.0f, (_Float16)1.0f}, rsum, false);
+    }
+    rsum += __shfl_xor(rsum, 32);                          // both halves of the row's slots
+    team_sync();                                           // every wave holds its fragments: the space becomes the output block
+    const int h = int(bh % heads);
+    const float s = alpha_v[h] / 255.0f;
+    const float add = fmaf(128.0f, s, beta_v[h]) * rsum;
+
+    const int64_t e0 = (bh * N + r0) * int64_t(N);         // first element of the output block
+    const int mis = int(e0 & 7);                           // its offset from a 16-byte boundary, in elements
+    _Float16 *lo = reinterpret_cast<_Float16 *>(lds_da);    // element (i, j) of the block at mis + i * N + j
+
+    for (int cbk = cb_first; cbk < nblocks; cbk += cb_step) {
+        const int c0 = cbk * 32;
+        store_codes(raw);
+        if (cbk + cb_step < nblocks) load_codes(c0 + 32 * cb_step, raw);   // the wave's next block
+        bm_v8h fc[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) fc[ks] = bm_codes_to_half8(*reinterpret_cast<const bm_v2i *>(lv + fl * C::kRowV + ks * 16 + fk));
+        bm_v16f acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(fc[ks], fo[ks], acc, 0, 0, 0);
+        // lane l, register v: column c0 + 8*(v/4) + 4*(l/32) + v%4, row l%32
+        if (fl < rows) {
+            const int at = mis + fl * N + c0 + (lane >> 5) * 4;
+            if (c0 + 32 <= N) {                            // uniform: the whole column block lies inside
+                // Four consecutive elements from an element-aligned position, with aligned writes only
+                // (LDS stalls for dozens of cycles on a misaligned 8-byte write): the first and the last
+                // element alone, the 4-byte word that holds elements 1, 2 (odd position) or 0, 1 (even),
+                // and element 2 (even) or, again, 3 (odd).
+                const bool odd = at & 1;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    bm_v4h o;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) o[k] = (_Float16)fmaf(s, acc[4 * g + k], add);
+                    _Float16 *q = lo + at + 8 * g;
+                    q[0] = o[0];
+                    q[3] = o[3];
+                    *reinterpret_cast<bm_v2h *>(q + (odd ? 1 : 0)) = odd ? bm_v2h{o[1], o[2]} : bm_v2h{o[0], o[1]};
+                    q[odd ? 3 : 2] = odd ? o[3] : o[2];
+                }
+            } else {
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)
+                        if (c0 + (lane >> 5) * 4 + 8 * g + k < N) lo[at + 8 * g + k] = (_Float16)fmaf(s, acc[4 * g + k], add);
+            }
+        }
+    }
+    team_sync();
+
+    // the block leaves: elements [e0, e1) of dA; LDS element x holds global element (e0 - mis) + x
+    const int total = rows * N;
+    const int64_t ebase = e0 - mis;
+    const int v_first = (mis + 7) >> 3, v_end = (mis + total) >> 3;   // whole vectors, in units of 8 elements from ebase
+    for (int v = v_first + t; v < v_end; v += kTeam)
+        *reinterpret_cast<u32x4 *>(dA + ebase + 8 * int64_t(v)) = *reinterpret_cast<const u32x4 *>(lo + 8 * v);
+    if (t < 8) {                                            // before the first whole vector
+        const int x = mis + t;
+        if (x < 8 * v_first && x < mis + total) dA[ebase + x] = lo[x];
+    } else if (t < 16) {                                    // after the last one
+        const int x = 8 * v_end + (t - 8);
+        if (x >= 8 * v_first && x < mis + total) dA[ebase + x] = lo[x];
+    }
+}
+
+// dQ[i,d] = scale * sum_j dS[i,j] * K_hat[j,d].  The head's K codes go to LDS once (rows j, zero beyond N),
+// from where the code fragments come by transposing reads; a wave takes 32 rows i of dS, whose fragments
+// are 16-byte element-aligned loads straight from global memory.  Dh == 32 * DT.
+template <int DT>
+__global__ __launch_bounds__(kThreads, DT <= 1 ? 6 : DT == 2 ? 5 : 4) void k_attn_dq(const _Float16 *__restrict__ dS, const int8_t *__restrict__ kq,
+                                                      _Float16 *__restrict__ dQ, int N, int Dh, int heads, float scale,
+                                                      const float *__restrict__ alpha_k, const float *__restrict__ beta_k,
+                                                      int t_chunk, int64_t batch0)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_k[];   // [t_chunk][Dh + 32] bytes
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t bh = batch0 + blockIdx.y;
+    constexpr int pitch = 32 * DT + 32;                  // Dh == 32 * DT (checked by the launcher)
+    const int r0 = (int(blockIdx.x) * (kThreads / 64) + wave) * 32;
+    const int fl = lane & 31;
+    const int row = r0 + fl < N ? r0 + fl : N - 1;
+    const _Float16 *prow = dS + (bh * N + row) * int64_t(N);
+    const int8_t *kb = kq + bh * N * int64_t(Dh);
+    // A step covers 64 contraction slots, as four MFMAs of 16: lane l takes the 32 consecutive slots
+    // 32*(l/32) ..+31 of its row (64 contiguous bytes, so that a cache line is fetched once), eight per MFMA;
+    // the code fragments follow the same slot order through their LDS row numbers.
+    const int blk = lane >> 4, sl = lane & 15;
+    const int b_off = ((blk >> 1) * 32 + (sl >> 1)) * pitch + (blk & 1) * 16 + (sl & 1) * 8;
+    const int fk32 = (lane >> 5) * 32;
+
+    bm_v16f acc[DT], acc1;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        acc1[v] = 0.0f;
+#pragma unroll
+        for (int j = 0; j < DT; ++j) acc[j][v] = 0.0f;
+    }
+    bm_v8h ones;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) ones[j] = (_Float16)1.0f;
+
+    for (int tc0 = 0; tc0 < N; tc0 += t_chunk) {
+        __syncthreads();   // the previous chunk has been read
+        // rows tc0 .. tc0 + t_chunk of the K codes, 16 bytes per thread and turn; rows past N are zeros
+        constexpr int vec_per_row = 2 * DT;
+        for (int idx = tid; idx < t_chunk * vec_per_row; idx += kThreads) {
+            const int tr = idx / vec_per_row, cv = (idx % vec_per_row) * 16;
+            u32x4 w = {0u, 0u, 0u, 0u};
+            if (tc0 + tr < N) w = *reinterpret_cast<const u32x4 *>(kb + int64_t(tc0 + tr) * Dh + cv);
+            *reinterpret_cast<u32x4 *>(lds_k + tr * pitch + cv) = w;
+        }
+        __syncthreads();
+        if (r0 < N) {
+            const int t_end = tc0 + t_chunk < N ? tc0 + t_chunk : N;
+            for (int t0 = tc0; t0 < t_end; t0 += 64) {
+                const int t = t0 + fk32;
+                bm_v8h fa[4];
+                if (t0 + 64 <= N) {                          // uniform: every lane's slots lie inside the row
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks) __builtin_memcpy(&fa[ks], prow + t + ks * 8, 16);
+                } else {                                     // the row's ragged end: zeros beyond it
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks) {
+                        const int tk = t + ks * 8;
+                        if (tk + 8 <= N) {
+                            __builtin_memcpy(&fa[ks], prow + tk, 16);
+                        } else {
+#pragma unroll
+                            for (int j = 0; j < 8; ++j) fa[ks][j] = tk + j < N ? prow[tk + j] : (_Float16)0.0f;
+                        }
+                    }
+                }
+                const unsigned char *pb = lds_k + (t0 - tc0) * pitch + b_off;
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ks], ones, acc1, 0, 0, 0);
+#pragma unroll
+                    for (int j = 0; j < DT; ++j) {
+                        const bm_v8h fb = bm_codes_to_half8(
+                            __builtin_amdgcn_ds_read_tr8_b64_v2i32(BM_LDS3(bm_v2i, pb + ks * 8 * pitch + j * 32)));
+                        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ks], fb, acc[j], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+    if (r0 >= N) return;
+    const int h = int(bh % heads);
+    const float s = alpha_k[h] / 255.0f;
+    const float off = fmaf(128.0f, s, beta_k[h]);
+    _Float16 *cb = dQ + bh * N * int64_t(Dh);
+    const int row_l = r0 + (lane >> 5) * 4;
+#pragma unroll
+    for (int j = 0; j < DT; ++j) {
+        const uint32_t o0 = uint32_t(row_l) * uint32_t(Dh) + uint32_t(j * 32 + fl);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int dr = (v >> 2) * 8 + (v & 3);
+            if (row_l + dr < N) cb[o0 + uint32_t(dr) * uint32_t(Dh)] = (_Float16)(scale * fmaf(s, acc[j][v], off * acc1[v]));
+        }
+    }
+}
+
+// whether k_attn_da can take the shape, and in which mode
+static bool da_solo(int64_t batches, int64_t N) { return N <= 64 && batches * ceil_div(N, 32) < (int64_t(1) << 32); }
+template <int KS> static bool da_fits(int64_t batches, int64_t N) { return DaCfg<KS>::lds_bytes(N, da_solo(batches, N)) <= 65536; }
+
+template <int KS> static void launch_da(const _Float16 *dO, const int8_t *vq, _Float16 *dA, int64_t batches, int N, int heads,
+                                        const float *alpha_v, const float *beta_v, hipStream_t s)
+{
+    typedef DaCfg<KS> C;
+    const int codes_at = int(C::codes_at(N));
+    if (da_solo(batches, N)) {
+        const int64_t items = batches * ceil_div(N, 32);
+        hipLaunchKernelGGL((k_attn_da<KS, true>), dim3(unsigned(ceil_div(items, C::kWaves))), dim3(kThreads), C::lds_bytes(N, true), s, dO,
+                           vq, dA, N, heads, alpha_v, beta_v, int64_t(0), codes_at, unsigned(items));
+        return;
+    }
+    const unsigned gx = unsigned(ceil_div(N, 32));
+    for (int64_t b0 = 0; b0 < batches; b0 += 65535) {   // the y extent of a grid is limited to 65535
+        const int64_t nb = batches - b0 < 65535 ? batches - b0 : 65535;
+        hipLaunchKernelGGL((k_attn_da<KS, false>), dim3(gx, unsigned(nb)), dim3(kThreads), C::lds_bytes(N, false), s, dO, vq, dA, N,
+                           heads, alpha_v, beta_v, b0, codes_at, 0u);
+    }
+}
+
+template <int DT> static void launch_dq(const _Float16 *dS, const int8_t *kq, _Float16 *dQ, int64_t batches, int N, int Dh,
+                                        int heads, float scale, const float *alpha_k, const float *beta_k, hipStream_t s)
+{
+    const unsigned gx = unsigned(ceil_div(N, 32 * (kThreads / 64)));
+    const int t_chunk = N < 256 ? int(ceil_div(N, 64)) * 64 : 256;
+    const size_t lds = size_t(t_chunk) * size_t(Dh + 32);      // at most 256 * 160 bytes
+    for (int64_t b0 = 0; b0 < batches; b0 += 65535) {
+        const int64_t nb = batches - b0 < 65535 ? batches - b0 : 65535;
+        hipLaunchKernelGGL((k_attn_dq<DT>), dim3(gx, unsigned(nb)), dim3(kThreads), lds, s, dS, kq, dQ, N, Dh, heads, scale,
+                           alpha_k, beta_k, t_chunk, b0);
+    }
+}
+
 static mesa_status check_attn(int64_t B, int64_t H, int64_t N, int64_t Dh, mesa_dtype dt)
 {
     if (!valid_dtype(dt) || B < 0 || H < 0 || N < 0 || Dh < 0) return MESA_ERR_INVALID_ARG;
@@ -331,7 +650,17 @@ extern "C" MESA_EXPORT mesa_status mesa_attn_av_bwd_q(const int8_t *aq, const in
     a.R = int(N); a.Cn = int(N); a.Tn = int(Dh);
     a.p_rs = Dh; a.p_ts = 1; a.q_ts = 1; a.q_cs = Dh;
     a.alpha = alpha_v; a.beta = beta_v;
-    launch_bmm<false, true, true>(a, batches, s);
+    // the 32 x N output block has to fit the 64 KiB of LDS a kernel gets by default; else the general kernel
+    if (Dh == 32 && da_fits<2>(batches, N))
+        launch_da<2>(a.x, vq, a.c, batches, int(N), int(H), alpha_v, beta_v, s);
+    else if (Dh == 64 && da_fits<4>(batches, N))
+        launch_da<4>(a.x, vq, a.c, batches, int(N), int(H), alpha_v, beta_v, s);
+    else if (Dh == 96 && da_fits<6>(batches, N))
+        launch_da<6>(a.x, vq, a.c, batches, int(N), int(H), alpha_v, beta_v, s);
+    else if (Dh == 128 && da_fits<8>(batches, N))
+        launch_da<8>(a.x, vq, a.c, batches, int(N), int(H), alpha_v, beta_v, s);
+    else
+        launch_bmm<false, true, true>(a, batches, s);
     // dV[j,d] = sum_i A_hat[i,j] * dO[i,d]:  P = A (r = j, t = i),  Q = dO (t = i, c = d)
     a.y = aq; a.c = static_cast<_Float16 *>(dV);
     a.y_batch = N * N; a.c_batch = N * Dh;
@@ -367,7 +696,16 @@ extern "C" MESA_EXPORT mesa_status mesa_attn_qk_bwd_q(const int8_t *qq, const in
     a.y = kq; a.c = static_cast<_Float16 *>(dQ);
     a.p_rs = N; a.p_ts = 1; a.q_ts = Dh; a.q_cs = 1;
     a.alpha = alpha_k; a.beta = beta_k;
-    launch_bmm<false, true, false>(a, batches, s);
+    if (Dh == 32)
+        launch_dq<1>(a.x, kq, a.c, batches, int(N), int(Dh), int(H), scale, alpha_k, beta_k, s);
+    else if (Dh == 64)
+        launch_dq<2>(a.x, kq, a.c, batches, int(N), int(Dh), int(H), scale, alpha_k, beta_k, s);
+    else if (Dh == 96)
+        launch_dq<3>(a.x, kq, a.c, batches, int(N), int(Dh), int(H), scale, alpha_k, beta_k, s);
+    else if (Dh == 128)
+        launch_dq<4>(a.x, kq, a.c, batches, int(N), int(Dh), int(H), scale, alpha_k, beta_k, s);
+    else
+        launch_bmm<false, true, false>(a, batches, s);
     // dK[j,d] = scale * sum_i dS[i,j] * Q_hat[i,d]:  P = dS (r = j, t = i),  Q = Q codes (t = i, c = d)
     a.y = qq; a.c = static_cast<_Float16 *>(dK);
     a.p_rs = 1; a.p_ts = N; a.q_ts = Dh; a.q_cs = 1;
