@@ -31,6 +31,8 @@ typedef _Float16 bm_v4h __attribute__((ext_vector_type(4)));
 typedef short bm_v4s __attribute__((ext_vector_type(4)));
 typedef int bm_v2i __attribute__((ext_vector_type(2)));
 typedef float bm_v16f __attribute__((ext_vector_type(16)));
+typedef float bm_v4f __attribute__((ext_vector_type(4)));
+typedef unsigned bm_v4u __attribute__((ext_vector_type(4)));
 
 #define BM_LDS3(T, p) ((__attribute__((address_space(3))) T *)(p))
 
@@ -696,13 +698,14 @@ extern "C" MESA_EXPORT mesa_status mesa_attn_qk_bwd_q(const int8_t *qq, const in
     a.y = kq; a.c = static_cast<_Float16 *>(dQ);
     a.p_rs = N; a.p_ts = 1; a.q_ts = Dh; a.q_cs = 1;
     a.alpha = alpha_k; a.beta = beta_k;
-    if (Dh == 32)
+    // short rows (windowed attention): the direct-fragment kernel; long rows: the general one
+    if (N <= 64 && Dh == 32)
         launch_dq<1>(a.x, kq, a.c, batches, int(N), int(Dh), int(H), scale, alpha_k, beta_k, s);
-    else if (Dh == 64)
+    else if (N <= 64 && Dh == 64)
         launch_dq<2>(a.x, kq, a.c, batches, int(N), int(Dh), int(H), scale, alpha_k, beta_k, s);
-    else if (Dh == 96)
+    else if (N <= 64 && Dh == 96)
         launch_dq<3>(a.x, kq, a.c, batches, int(N), int(Dh), int(H), scale, alpha_k, beta_k, s);
-    else if (Dh == 128)
+    else if (N <= 64 && Dh == 128)
         launch_dq<4>(a.x, kq, a.c, batches, int(N), int(Dh), int(H), scale, alpha_k, beta_k, s);
     else
         launch_bmm<false, true, false>(a, batches, s);
