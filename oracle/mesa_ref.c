@@ -206,6 +206,42 @@ int mesa_ref_update_running_params(const void *x, int dt, int64_t outer, int64_t
     return 0;
 }
 
+/*
+ * Symmetric range (the ablation of Sec. 5.3, asymmetric vs. symmetric quantization): one scale from
+ * m = max |x| over the group and no free offset.  Reading taken here (the paper gives the scale factor
+ * only): the clipping range is [-m, +m], i.e. Eq. (3)-(7) with the group's minimum replaced by -m and
+ * its maximum by +m, so alpha moves towards 2m and beta towards -m; everything downstream (quantizer,
+ * dequantizer, backward) is unchanged.
+ */
+int mesa_ref_update_running_params_sym(const void *x, int dt, int64_t outer, int64_t groups, int64_t inner,
+                                       float *alpha, float *beta, float lambda, int first_call)
+{
+    if (outer <= 0 || groups <= 0 || inner <= 0) return 0;
+    for (int64_t g = 0; g < groups; ++g) {
+        float m = 0.0f;
+        for (int64_t o = 0; o < outer; ++o)
+            for (int64_t i = 0; i < inner; ++i) {
+                float v = fabsf(load_as_float(x, dt, (o * groups + g) * inner + i));
+                if (v > m) m = v;
+            }
+        float mn = -m + 0.0f; /* -0.0 -> +0.0 */
+        float range = m - mn;
+        if (first_call) {
+            alpha[g] = range;
+            beta[g] = mn;
+        } else {
+            float a = lambda * alpha[g];
+            float b = 1.0f - lambda;
+            float c = b * range;
+            alpha[g] = a + c;
+            float e = lambda * beta[g];
+            float f = b * mn;
+            beta[g] = e + f;
+        }
+    }
+    return 0;
+}
+
 /* raw per-group extrema, exposed for tests */
 int mesa_ref_group_minmax(const void *x, int dt, int64_t outer, int64_t groups, int64_t inner,
                           float *mn_out, float *mx_out)

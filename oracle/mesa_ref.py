@@ -120,6 +120,19 @@ def update_running_params(x, layout, alpha, beta, lam, first_call):
     return a, b
 
 
+def update_running_params_sym(x, layout, alpha, beta, lam, first_call):
+    """Symmetric-range variant (range [-max|x|, +max|x|] per group); returns the new (alpha, beta)."""
+    outer, groups, inner = layout
+    x = _c(x)
+    assert x.size == outer * groups * inner
+    a = _c(alpha, np.float32).copy()
+    b = _c(beta, np.float32).copy()
+    assert a.size == groups and b.size == groups
+    lib().mesa_ref_update_running_params_sym(_p(x), _dt(x), I64(outer), I64(groups), I64(inner),
+                                             _p(a), _p(b), C.c_float(lam), C.c_int(int(first_call)))
+    return a, b
+
+
 def quantize_headwise(x, layout, alpha, beta, mode=ROUND_NEAREST, seed=0, offset=0):
     outer, groups, inner = layout
     x = _c(x)

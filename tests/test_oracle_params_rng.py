@@ -149,3 +149,40 @@ def test_fused_forward_constant_group_and_saturation():
     assert (q[:, 0, :] == -128).all()                      # alpha = 0: every code is 0 (stored -128)
     assert q[:, 1, :].min() == -128 and q[:, 1, :].max() == 127   # values outside [beta, beta + alpha] saturate
     assert a1[0] == 0.0 and b1[0] == 0.0 and a1[1] == np.float32(0.5 * 10.0 + 0.5 * 100.0) and b1[1] == np.float32(-2.5 - 25.0)
+
+
+# ---- symmetric range (Sec. 5.3, asymmetric vs. symmetric quantization) --------------------------------
+
+def test_symmetric_first_call_is_twice_and_minus_the_largest_magnitude():
+    for dtype in (np.float32, np.float16):
+        x = _x(40, (6, 3, 50), dtype)
+        a, b = R.update_running_params_sym(x, (6, 3, 50), np.full(3, 77.0), np.full(3, -55.0), 0.9, True)
+        m = np.abs(x.astype(np.float32)).max(axis=(0, 2))
+        assert np.array_equal(a, 2 * m) and np.array_equal(b, -m)
+
+
+def test_symmetric_update_equals_the_asymmetric_one_on_the_batch_with_its_mirror_image():
+    # the extrema of the batch joined with its negation are -max|x| and +max|x|: Eq. (6)-(7) on that
+    # joined batch is the symmetric update, whatever lambda and the previous estimates are
+    lay, lay2 = (4, 2, 30), (8, 2, 30)
+    a0, b0 = np.array([3.0, 5.0], np.float32), np.array([-1.0, -4.0], np.float32)
+    for seed, lam in ((41, 0.9), (42, 0.5), (43, 0.0)):
+        x = _x(seed, lay) + 0.7          # skewed, so that min != -max
+        joined = np.concatenate([x, -x], axis=0)
+        a, b = R.update_running_params_sym(x, lay, a0, b0, lam, False)
+        a2, b2 = R.update_running_params(joined, lay2, a0, b0, lam, False)
+        assert np.array_equal(a, a2) and np.array_equal(b, b2)
+        assert not np.array_equal(R.update_running_params(x, lay, a0, b0, lam, False)[1], b)
+
+
+def test_symmetric_range_bounds_the_nearest_rounding_error_and_centres_zero():
+    lay = (5, 3, 64)
+    x = _x(44, lay) - 1.0
+    a, b = R.update_running_params_sym(x, lay, np.zeros(3), np.zeros(3), 0.9, True)
+    q = R.quantize_headwise(x, lay, a, b, R.ROUND_NEAREST, 0, 0)
+    xh = R.dequantize(q, lay, a, b)
+    step = (a / 255.0)[None, :, None]
+    assert np.all(np.abs(xh.reshape(lay) - x) <= 0.5 * step * (1 + 1e-5) + 1e-6)
+    # zero sits in the middle of the code range: codes 127 / 128 (-1 / 0 as stored) dequantize to -+ step/2
+    z = R.dequantize(np.array([[-1, 0]] * 3, np.int8).reshape(1, 3, 2), (1, 3, 2), a, b).reshape(3, 2)
+    assert np.allclose(z[:, 0], -0.5 * a / 255, rtol=1e-5, atol=4e-6) and np.allclose(z[:, 1], 0.5 * a / 255, rtol=1e-5, atol=4e-6)
