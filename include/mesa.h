@@ -80,6 +80,17 @@ mesa_status mesa_update_running_params(const void *x, mesa_dtype dt, mesa_layout
                                        void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Symmetric range, the ablation of Sec. 5.3 (asymmetric vs. symmetric quantization): one scale from
+ * m_g = max |x| over group g, no free offset.  The paper states the scale factor only; here the
+ * clipping range is [-m_g, +m_g]: the call above with mn_g := -m_g and mx_g := +m_g, so that alpha_g
+ * moves towards 2 m_g and beta_g towards -m_g.  Quantizer, dequantizer and the backward calls take
+ * the resulting alpha, beta unchanged.  Arguments, workspace and errors: as for the call above.
+ */
+mesa_status mesa_update_running_params_sym(const void *x, mesa_dtype dt, mesa_layout L,
+                                           float *alpha, float *beta, float lambda, int first_call,
+                                           void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Quantizer, Sec. 3.2 Eq. (3)-(4):  x_bar = clip(round((x - beta_g) * (255 / alpha_g)), 0, 255).
  * binary32, separately rounded: r = 255/alpha_g (0 when alpha_g <= 0), t = x - beta_g, v = t*r,
  *   nearest:     w = v rounded to the nearest integer, ties to even

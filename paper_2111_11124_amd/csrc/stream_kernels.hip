@@ -407,8 +407,10 @@ __device__ __forceinline__ void ema_update(float mn, float mx, float alpha_old, 
 }
 
 // one workgroup per group: combine the partial extrema, then Eq. (6)-(7)
+// symmetric != 0: the extrema are replaced by -m and +m, m = max |x| = max(-min, max)
 __global__ __launch_bounds__(kThreads) void k_ema_finalize(const float *__restrict__ part, int nwg, uint32_t groups,
-                                                           float *alpha, float *beta, float lambda, int first_call)
+                                                           float *alpha, float *beta, float lambda, int first_call,
+                                                           int symmetric = 0)
 {
     __shared__ float smn[kThreads / 64], smx[kThreads / 64];
     const uint32_t g = blockIdx.x;
@@ -428,6 +430,10 @@ __global__ __launch_bounds__(kThreads) void k_ema_finalize(const float *__restri
     if (threadIdx.x == 0) {
 #pragma unroll
         for (int w = 1; w < kThreads / 64; ++w) { mn = vmin(mn, smn[w]); mx = vmax(mx, smx[w]); }
+        if (symmetric) {
+            mx = vmax(-mn, mx);
+            mn = -mx;
+        }
         ema_update(mn, mx, alpha_old, beta_old, alpha, beta, g, lambda, first_call);
     }
 }
@@ -891,8 +897,8 @@ static bool minmax_few_groups(const mesa_layout &L, int grid, int unroll)
     return off > L.inner / 16;
 }
 
-extern "C" MESA_EXPORT mesa_status mesa_update_running_params(const void *x, mesa_dtype dt, mesa_layout L, float *alpha, float *beta,
-                                                  float lambda, int first_call, void *ws, size_t ws_bytes, void *stream)
+static mesa_status update_running_params(const void *x, mesa_dtype dt, mesa_layout L, float *alpha, float *beta, float lambda,
+                                         int first_call, int symmetric, void *ws, size_t ws_bytes, void *stream)
 {
     if (!valid_dtype(dt)) return MESA_ERR_INVALID_ARG;
     mesa_status st = check_layout(L);
@@ -927,8 +933,21 @@ extern "C" MESA_EXPORT mesa_status mesa_update_running_params(const void *x, mes
     else
         hipLaunchKernelGGL((k_minmax_partial<float, kMmU>), dim3(grid), dim3(kThreads), lds, s, x, numel, gg, part);
     hipLaunchKernelGGL(k_ema_finalize, dim3(gg.groups), dim3(kThreads), 0, s, part, grid, gg.groups, alpha, beta, lambda,
-                       first_call);
+                       first_call, symmetric);
     return launch_status();
+}
+
+extern "C" MESA_EXPORT mesa_status mesa_update_running_params(const void *x, mesa_dtype dt, mesa_layout L, float *alpha, float *beta,
+                                                  float lambda, int first_call, void *ws, size_t ws_bytes, void *stream)
+{
+    return update_running_params(x, dt, L, alpha, beta, lambda, first_call, 0, ws, ws_bytes, stream);
+}
+
+extern "C" MESA_EXPORT mesa_status mesa_update_running_params_sym(const void *x, mesa_dtype dt, mesa_layout L, float *alpha,
+                                                      float *beta, float lambda, int first_call, void *ws, size_t ws_bytes,
+                                                      void *stream)
+{
+    return update_running_params(x, dt, L, alpha, beta, lambda, first_call, 1, ws, ws_bytes, stream);
 }
 
 extern "C" MESA_EXPORT mesa_status mesa_quantize_headwise(const void *x, mesa_dtype dt, mesa_layout L, const float *alpha,

@@ -379,6 +379,28 @@ def test_attention_matmul_backward_against_the_oracle(M, B, H, N, Dh):
     assert all(v <= TOL[dtype] for v in rep.values()), rep
 
 
+@pytest.mark.parametrize("dtype", [torch.float16, torch.float32])
+@pytest.mark.parametrize("layout", [(3, 4, 1000), (5, 3, 361), (37, 6, 64), (64, 3, 2401), (1, 1, 77)])
+def test_symmetric_range_update_matches_the_oracle_bit_for_bit(M, layout, dtype):
+    """Symmetric-range running estimates (Sec. 5.3 ablation): first call and two EMA steps, then the codes
+    taken with them."""
+    G = layout[1]
+    gen = torch.Generator(device="cuda").manual_seed(layout[0] * 31 + layout[2])
+    xs = [((torch.randn(layout, generator=gen, device="cuda") * (1 + t) + 0.4 * t - 0.3).to(dtype)).contiguous() for t in range(3)]
+    a = torch.full((G,), 5.0, device="cuda")
+    b = torch.full((G,), -2.0, device="cuda")
+    ra, rb = np.full(G, 5.0, np.float32), np.full(G, -2.0, np.float32)
+    ws = ws_for(M, M.OP_UPDATE_RUNNING_PARAMS, *layout, dt=dtype)
+    for t, x in enumerate(xs):
+        M.mesa_update_running_params_sym(x, layout, a, b, 0.9, t == 0, ws)
+        ra, rb = R.update_running_params_sym(x.cpu().numpy(), layout, ra, rb, 0.9, t == 0)
+        assert np.array_equal(a.cpu().numpy(), ra) and np.array_equal(b.cpu().numpy(), rb), t
+    q = torch.empty(xs[-1].numel(), dtype=torch.int8, device="cuda")
+    M.mesa_quantize_headwise(xs[-1], layout, a, b, q, M.ROUND_STOCHASTIC, 5, 3)
+    rq = R.quantize_headwise(xs[-1].cpu().numpy(), layout, ra, rb, R.ROUND_STOCHASTIC, 5, 3).reshape(-1)
+    assert np.array_equal(q.cpu().numpy(), rq)
+
+
 def test_empty_inputs_are_a_no_op(M):
     z = torch.empty(0, device="cuda")
     a = torch.ones(3, device="cuda")
