@@ -203,3 +203,37 @@ def test_config5_long_sequence_full_sampled(M):
         a, b, ra, rb, q, rq = forward(m, draws, (Mr, H, K // H), spec.lam, 8 + li, (3 + li) << 40)
         del draws
         dw_sampled(m, spec, q, rq, a, b, ra, rb, K, N, tol, li)
+
+
+@pytest.mark.parametrize("number", [2, 3])
+def test_attention_products_backward_full_size_sampled(M, number):
+    """The four attention-product gradients at the configuration's full attention shape (the launch the
+    bench times): the GPU runs every sample, the oracle the first, a middle and the last sample (all heads)."""
+    spec = W.CONFIGS[number]
+    if spec.dtype != torch.float16:
+        pytest.skip("binary16 tensors only")
+    B, H, N, _ = spec.attn
+    Dh = spec.dim // spec.heads
+    dev = "cuda"
+    g = torch.Generator(device=dev).manual_seed(spec.seed + 77)
+    aq = torch.randint(-128, 128, (B, H, N, N), dtype=torch.int8, device=dev, generator=g)
+    qq, kq, vq = (torch.randint(-128, 128, (B, H, N, Dh), dtype=torch.int8, device=dev, generator=g) for _ in range(3))
+    dO = torch.randn((B, H, N, Dh), device=dev, generator=g).to(spec.dtype)
+    dS = (torch.randn((B, H, N, N), device=dev, generator=g) * 0.05).to(spec.dtype)
+    par = {k: (torch.linspace(1.0, 4.0, H, device=dev) * s, torch.linspace(-2.0, -0.5, H, device=dev) * s)
+           for k, s in (("a", 0.25), ("q", 1.0), ("k", 1.5), ("v", 0.75))}
+    dA = torch.empty((B, H, N, N), dtype=spec.dtype, device=dev)
+    dV, dQ, dK = (torch.empty((B, H, N, Dh), dtype=spec.dtype, device=dev) for _ in range(3))
+    M.mesa_attn_av_bwd_q(aq, vq, B, H, N, Dh, *par["a"], *par["v"], dO, dA, dV)
+    scale = Dh ** -0.5
+    M.mesa_attn_qk_bwd_q(qq, kq, B, H, N, Dh, *par["q"], *par["k"], dS, scale, dQ, dK)
+    torch.cuda.synchronize()
+    rp = {k: (a.cpu().numpy(), b.cpu().numpy()) for k, (a, b) in par.items()}
+    rep = {}
+    for b in (0, B // 2, B - 1):
+        sl = slice(b, b + 1)
+        rdA, rdV = R.attn_av_bwd_q(aq[sl].cpu().numpy(), vq[sl].cpu().numpy(), 1, H, N, Dh, *rp["a"], *rp["v"], dO[sl].cpu().numpy())
+        rdQ, rdK = R.attn_qk_bwd_q(qq[sl].cpu().numpy(), kq[sl].cpu().numpy(), 1, H, N, Dh, *rp["q"], *rp["k"], dS[sl].cpu().numpy(), scale)
+        for name, got, ref in (("dA", dA, rdA), ("dV", dV, rdV), ("dQ", dQ, rdQ), ("dK", dK, rdK)):
+            rep[(name, b)] = relerr(got[sl].cpu().numpy(), ref)
+    assert all(v <= TOL[spec.dtype] for v in rep.values()), rep
