@@ -416,6 +416,28 @@ int mesa_ref_gelu_bwd_q(const int8_t *xq, int64_t outer, int64_t groups, int64_t
 }
 
 /*
+ * ReLU (one of the CNN layers Sec. 3.3 lists as covered, quantized group-wise like every other
+ * activation).  The saved tensor is the ReLU input x:  relu'(x) = 1 for x > 0, else 0 (0 at x = 0).
+ */
+int mesa_ref_relu_bwd_q(const int8_t *xq, int64_t outer, int64_t groups, int64_t inner,
+                        const float *alpha, const float *beta, const void *dy, int dt, double *dx)
+{
+    if (outer <= 0 || groups <= 0 || inner <= 0) return 0;
+    for (int64_t o = 0; o < outer; ++o) {
+        for (int64_t g = 0; g < groups; ++g) {
+            float step = alpha[g] / 255.0f;
+            float off = beta[g];
+            for (int64_t i = 0; i < inner; ++i) {
+                int64_t e = (o * groups + g) * inner + i;
+                float xh = dequant_one(xq[e], step, off);
+                dx[e] = xh > 0.0f ? load_as_double(dy, dt, e) : 0.0;
+            }
+        }
+    }
+    return 0;
+}
+
+/*
  * LayerNorm over the last axis of an (M, D) matrix, D split into G channel
  * groups of D/G columns.  Saved: codes of the input x plus the forward's own
  * per-row mean and reciprocal standard deviation (binary32).

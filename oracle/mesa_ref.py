@@ -194,6 +194,18 @@ def gelu_bwd_q(xq, layout, alpha, beta, dy):
     return dx
 
 
+def relu_bwd_q(xq, layout, alpha, beta, dy):
+    outer, groups, inner = layout
+    xq = _c(xq, np.int8)
+    dy = _c(dy)
+    assert xq.size == outer * groups * inner == dy.size
+    a = _c(alpha, np.float32)
+    b = _c(beta, np.float32)
+    dx = np.empty(xq.shape, np.float64)
+    lib().mesa_ref_relu_bwd_q(_p(xq), I64(outer), I64(groups), I64(inner), _p(a), _p(b), _p(dy), _dt(dy), _p(dx))
+    return dx
+
+
 def layernorm_bwd_q(xq, M, D, G, alpha, beta, mean, rstd, gamma, dy):
     xq = _c(xq, np.int8)
     dy = _c(dy)

@@ -121,6 +121,26 @@ def test_gelu_backward_against_finite_differences_and_torch():
     assert relerr(dx, xt.grad.numpy()) < 1e-12
 
 
+def test_relu_backward_against_finite_differences_torch_and_the_mask_it_is():
+    # ReLU is among the CNN layers Sec. 3.3 lists; saved tensor: its input, channel-group codes
+    rng = np.random.default_rng(31)
+    outer, G, inner = 4, 3, 7
+    codes, alpha, beta, step = on_grid(rng, (outer, G, inner), G, step_log2=-5, lo=-3.96875)   # no x_hat at exactly 0 ...
+    x = beta[None, :, None].astype(np.float64) + codes * step
+    assert np.all(np.abs(x) > 1e-3)
+    dy = rng.standard_normal(x.shape).astype(np.float32)
+    dx = R.relu_bwd_q((codes - 128).astype(np.int8), (outer, G, inner), alpha, beta, dy)
+    assert relerr(dx, fd_grad(lambda v: float((dy * np.maximum(v, 0.0)).sum()), x)) < 1e-6
+    xt = torch.from_numpy(x).requires_grad_(True)
+    torch.relu(xt).backward(torch.from_numpy(dy.astype(np.float64)))
+    assert np.array_equal(dx, xt.grad.numpy())
+    assert np.array_equal(dx != 0, (x > 0) & (dy != 0))
+    # ... and at exactly 0 the derivative is 0 (the library's convention too)
+    a0, b0 = np.array([255.0 * step], np.float32), np.array([-128 * step], np.float32)
+    q0 = np.array([0, 1, -1], np.int8)                      # x_bar = 128, 129, 127 -> x_hat = 0, +step, -step
+    assert np.array_equal(R.relu_bwd_q(q0, (1, 1, 3), a0, b0, np.ones(3, np.float32)), [0.0, 1.0, 0.0])
+
+
 def test_gelu_derivative_vanishes_at_the_minimum_the_paper_prints():
     # FFN visualisation section: the offset of the second FC layer's input sits at min GELU = -0.17
     want = float([l for l in open(os.path.join(GOLD, "gelu_min.txt")) if not l.startswith("#")][0])
