@@ -153,6 +153,15 @@ mesa_status mesa_gelu_bwd_q(const int8_t *xq, mesa_layout L, const float *alpha,
                             const void *dy, void *dx, mesa_dtype dt, void *stream);
 
 /*
+ * ReLU backward at the de-quantized input (ReLU is among the CNN layers Sec. 3.3 covers, quantized
+ * group-wise: for an (N, C, H, W) activation in G channel groups use L = {N, G, (C/G)*H*W}):
+ *   dx = dy where x_hat > 0, else 0     (x_hat as mesa_dequantize returns it; 0 at x_hat == 0).
+ * Arguments as for mesa_gelu_bwd_q.
+ */
+mesa_status mesa_relu_bwd_q(const int8_t *xq, mesa_layout L, const float *alpha, const float *beta,
+                            const void *dy, void *dx, mesa_dtype dt, void *stream);
+
+/*
  * LayerNorm backward at the de-quantized input, Eq. (2).  Saved: codes of the input x (M, D) in G
  * channel groups of D/G columns, plus the forward's per-row mean and 1/sqrt(var+eps) (binary32).
  *   xn = (x_hat - mean)*rstd,  g = dy*gamma,

@@ -21,7 +21,7 @@ OP_UPDATE_RUNNING_PARAMS, OP_LAYERNORM_BWD_Q, OP_LINEAR_DW_Q = 0, 1, 2
 
 EXPORTS = [
     "mesa_update_running_params", "mesa_update_running_params_sym", "mesa_quantize_headwise", "mesa_quantize_update_fused", "mesa_dequantize", "mesa_softmax_bwd_q",
-    "mesa_gelu_bwd_q", "mesa_layernorm_bwd_q", "mesa_linear_dw_q", "mesa_attn_av_bwd_q", "mesa_attn_qk_bwd_q",
+    "mesa_gelu_bwd_q", "mesa_relu_bwd_q", "mesa_layernorm_bwd_q", "mesa_linear_dw_q", "mesa_attn_av_bwd_q", "mesa_attn_qk_bwd_q",
     "mesa_workspace_bytes",
     "mesa_status_string", "mesa_version", "mesa_stream_copy", "mesa_event_create", "mesa_event_record",
     "mesa_event_elapsed_ms", "mesa_event_destroy",
@@ -56,6 +56,7 @@ def lib() -> C.CDLL:
         L.mesa_dequantize.argtypes = [_vp, Layout, _vp, _vp, _vp, _int, _vp]
         L.mesa_softmax_bwd_q.argtypes = [_vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _int, _vp]
         L.mesa_gelu_bwd_q.argtypes = [_vp, Layout, _vp, _vp, _vp, _vp, _int, _vp]
+        L.mesa_relu_bwd_q.argtypes = L.mesa_gelu_bwd_q.argtypes
         L.mesa_layernorm_bwd_q.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _int,
                                            _vp, _sz, _vp]
         L.mesa_linear_dw_q.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _i64, _int, _vp, _vp, _vp, _sz, _vp]
@@ -160,6 +161,12 @@ def mesa_gelu_bwd_q(xq, layout, alpha, beta, dy, dx):
     assert dx.dtype == dy.dtype
     _check(lib().mesa_gelu_bwd_q(_ptr(xq), Layout(*layout), _ptr(alpha), _ptr(beta), _ptr(dy), _ptr(dx), _dt(dy), _stream()),
            "mesa_gelu_bwd_q")
+
+
+def mesa_relu_bwd_q(xq, layout, alpha, beta, dy, dx):
+    assert dx.dtype == dy.dtype
+    _check(lib().mesa_relu_bwd_q(_ptr(xq), Layout(*layout), _ptr(alpha), _ptr(beta), _ptr(dy), _ptr(dx), _dt(dy), _stream()),
+           "mesa_relu_bwd_q")
 
 
 def mesa_attn_av_bwd_q(aq, vq, B, H, N, Dh, alpha_a, beta_a, alpha_v, beta_v, dO, dA, dV):

@@ -740,11 +740,20 @@ __device__ __forceinline__ float gelu_grad(float x)
     return fmaf(x * E, 0.39894228040143268f, cdf);
 }
 
+// The derivative of the activation at x_hat = x_bar*step + beta.  GELU: smooth, the fused form of x_hat will do
+// (tolerance-checked).  ReLU: a 0/1 decision, taken on the separately rounded x_hat that mesa_dequantize returns.
+enum { kActGelu = 0, kActRelu = 1 };
+template <int ACT> __device__ __forceinline__ float act_grad(float x_bar, float step, float beta)
+{
+    if (ACT == kActRelu) return dequant_exact(x_bar, step, beta) > 0.0f ? 1.0f : 0.0f;
+    return gelu_grad(fmaf(x_bar, step, beta));
+}
+
 // x_hat takes only 256 values per group, so gelu'(x_hat) is a table of groups*256 entries: each
 // workgroup fills it once (indexed by the raw code byte) and the stream becomes one LDS gather and
 // one multiply per element.  With more than kLutMaxGroups groups the table does not fit and the
 // derivative is evaluated per element instead (LUT = false).
-template <typename T, int U, bool LUT>
+template <typename T, int U, bool LUT, int ACT = kActGelu>
 __global__ __launch_bounds__(kThreads) void k_gelu_bwd(const int8_t *__restrict__ q, const void *dy, void *dx, int64_t numel,
                                                        GroupGeom gg, const float *__restrict__ alpha,
                                                        const float *__restrict__ beta)
@@ -755,7 +764,7 @@ __global__ __launch_bounds__(kThreads) void k_gelu_bwd(const int8_t *__restrict_
         for (uint32_t i = threadIdx.x; i < gg.groups * 256u; i += kThreads) {
             const uint32_t g = i >> 8;
             const float u = float((i & 255u) ^ 0x80u);   // raw byte -> x_bar
-            lds_gelu[i] = gelu_grad(fmaf(u, alpha[g] / 255.0f, beta[g]));
+            lds_gelu[i] = act_grad<ACT>(u, alpha[g] / 255.0f, beta[g]);
         }
         __syncthreads();
     } else {
@@ -765,7 +774,7 @@ __global__ __launch_bounds__(kThreads) void k_gelu_bwd(const int8_t *__restrict_
     auto grad_of = [&](uint32_t g, uint32_t raw) -> float {
         if (LUT) return lds_gelu[g * 256u + raw];
         const float2 p = tab2[g];
-        return gelu_grad(fmaf(float(raw ^ 0x80u), p.x, p.y));
+        return act_grad<ACT>(float(raw ^ 0x80u), p.x, p.y);
     };
 
     Cursor c[U];
@@ -804,7 +813,7 @@ __global__ __launch_bounds__(kThreads) void k_gelu_bwd(const int8_t *__restrict_
                         float uu[8];
                         codes_to_float(v[u], uu);
 #pragma unroll
-                        for (int j = 0; j < 8; ++j) g[j] = g[j] * gelu_grad(fmaf(uu[j], p.x, p.y));
+                        for (int j = 0; j < 8; ++j) g[j] = g[j] * act_grad<ACT>(uu[j], p.x, p.y);
                     }
                 } else {
 #pragma unroll
@@ -1024,8 +1033,9 @@ extern "C" MESA_EXPORT mesa_status mesa_dequantize(const int8_t *q, mesa_layout 
     return launch_status();
 }
 
-extern "C" MESA_EXPORT mesa_status mesa_gelu_bwd_q(const int8_t *xq, mesa_layout L, const float *alpha, const float *beta, const void *dy,
-                                       void *dx, mesa_dtype dt, void *stream)
+template <int ACT>
+static mesa_status act_bwd_q(const int8_t *xq, mesa_layout L, const float *alpha, const float *beta, const void *dy, void *dx,
+                             mesa_dtype dt, void *stream)
 {
     if (!valid_dtype(dt)) return MESA_ERR_INVALID_ARG;
     mesa_status st = check_layout(L);
@@ -1041,11 +1051,23 @@ extern "C" MESA_EXPORT mesa_status mesa_gelu_bwd_q(const int8_t *xq, mesa_layout
     const bool lut = gg.groups <= uint32_t(kLutMaxGroups);
     const size_t lds = lut ? size_t(gg.groups) * 256 * sizeof(float) : size_t(gg.groups) * sizeof(float2);
 #define MESA_LAUNCH_G(T, L_) \
-    hipLaunchKernelGGL((k_gelu_bwd<T, kU, L_>), dim3(grid), dim3(kThreads), lds, s, xq, dy, dx, numel, gg, alpha, beta)
+    hipLaunchKernelGGL((k_gelu_bwd<T, kU, L_, ACT>), dim3(grid), dim3(kThreads), lds, s, xq, dy, dx, numel, gg, alpha, beta)
     if (dt == MESA_F16) { if (lut) MESA_LAUNCH_G(_Float16, true); else MESA_LAUNCH_G(_Float16, false); }
     else { if (lut) MESA_LAUNCH_G(float, true); else MESA_LAUNCH_G(float, false); }
 #undef MESA_LAUNCH_G
     return launch_status();
+}
+
+extern "C" MESA_EXPORT mesa_status mesa_gelu_bwd_q(const int8_t *xq, mesa_layout L, const float *alpha, const float *beta, const void *dy,
+                                       void *dx, mesa_dtype dt, void *stream)
+{
+    return act_bwd_q<kActGelu>(xq, L, alpha, beta, dy, dx, dt, stream);
+}
+
+extern "C" MESA_EXPORT mesa_status mesa_relu_bwd_q(const int8_t *xq, mesa_layout L, const float *alpha, const float *beta, const void *dy,
+                                       void *dx, mesa_dtype dt, void *stream)
+{
+    return act_bwd_q<kActRelu>(xq, L, alpha, beta, dy, dx, dt, stream);
 }
 
 extern "C" MESA_EXPORT mesa_status mesa_stream_copy(const void *src, void *dst, size_t bytes, void *stream)

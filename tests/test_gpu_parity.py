@@ -401,6 +401,27 @@ def test_symmetric_range_update_matches_the_oracle_bit_for_bit(M, layout, dtype)
     assert np.array_equal(q.cpu().numpy(), rq)
 
 
+@pytest.mark.parametrize("dtype", [torch.float16, torch.float32])
+@pytest.mark.parametrize("layout", [(4, 3, 16 * 14 * 14), (5, 3, 361), (3, 40, 77), (1, 1, 1000)])
+def test_relu_backward_is_the_oracles_mask_exactly(M, layout, dtype):
+    """ReLU backward at group-wise codes (an (N, C, H, W) activation as (N, G, C/G*H*W)); the 0/1 decision is
+    taken on the same separately rounded x_hat on both sides, so the result is dy or 0 bit for bit.
+    40 groups exceed the table's capacity and take the per-element path."""
+    gen = torch.Generator(device="cuda").manual_seed(layout[1] * 7 + layout[2])
+    x = (torch.randn(layout, generator=gen, device="cuda") * 1.3 + 0.2).to(dtype).contiguous()
+    a, b, ra, rb = run_params(M, [x], layout)
+    q = torch.empty(x.numel(), dtype=torch.int8, device="cuda")
+    M.mesa_quantize_headwise(x, layout, a, b, q, M.ROUND_STOCHASTIC, 3, 0)
+    dy = torch.randn(layout, generator=gen, device="cuda").to(dtype)
+    dx = torch.empty_like(dy)
+    M.mesa_relu_bwd_q(q, layout, a, b, dy, dx)
+    ref = R.relu_bwd_q(q.cpu().numpy(), layout, ra, rb, dy.cpu().numpy())
+    got = dx.cpu().numpy().astype(np.float64).reshape(ref.shape)
+    assert np.array_equal(got, ref)
+    frac = float((ref != 0).mean())
+    assert 0.2 < frac < 0.8, frac
+
+
 def test_empty_inputs_are_a_no_op(M):
     z = torch.empty(0, device="cuda")
     a = torch.ones(3, device="cuda")
