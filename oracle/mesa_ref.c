@@ -242,6 +242,40 @@ int mesa_ref_update_running_params_sym(const void *x, int dt, int64_t outer, int
     return 0;
 }
 
+/*
+ * Fixed offset (Sec. 6, evolution of alpha and beta in FFN layers: the offset of the second FFN layer's
+ * input stays at GELU's minimum, -0.17, so it "can be fixed" there): beta_g = beta_fixed for every
+ * group, and only the range is a running estimate, of max - beta_fixed:
+ *   first call : alpha = max - beta_fixed
+ *   otherwise  : alpha = lambda*alpha + (1-lambda)*(max - beta_fixed)
+ * each line one binary32 operation.  Values below beta_fixed saturate at code 0 (Eq. 3's clip).
+ */
+int mesa_ref_update_running_params_fixed_beta(const void *x, int dt, int64_t outer, int64_t groups, int64_t inner,
+                                              float *alpha, float *beta, float lambda, int first_call, float beta_fixed)
+{
+    if (outer <= 0 || groups <= 0 || inner <= 0) return 0;
+    for (int64_t g = 0; g < groups; ++g) {
+        float mx = -INFINITY;
+        for (int64_t o = 0; o < outer; ++o)
+            for (int64_t i = 0; i < inner; ++i) {
+                float v = load_as_float(x, dt, (o * groups + g) * inner + i);
+                if (v > mx) mx = v;
+            }
+        mx = mx + 0.0f;
+        float range = mx - beta_fixed;
+        if (first_call) {
+            alpha[g] = range;
+        } else {
+            float a = lambda * alpha[g];
+            float b = 1.0f - lambda;
+            float c = b * range;
+            alpha[g] = a + c;
+        }
+        beta[g] = beta_fixed;
+    }
+    return 0;
+}
+
 /* raw per-group extrema, exposed for tests */
 int mesa_ref_group_minmax(const void *x, int dt, int64_t outer, int64_t groups, int64_t inner,
                           float *mn_out, float *mx_out)

@@ -133,6 +133,19 @@ def update_running_params_sym(x, layout, alpha, beta, lam, first_call):
     return a, b
 
 
+def update_running_params_fixed_beta(x, layout, alpha, lam, first_call, beta_fixed):
+    """Fixed-offset variant (beta = beta_fixed in every group, alpha tracks max - beta_fixed); returns (alpha, beta)."""
+    outer, groups, inner = layout
+    x = _c(x)
+    assert x.size == outer * groups * inner
+    a = _c(alpha, np.float32).copy()
+    b = np.empty(groups, np.float32)
+    assert a.size == groups
+    lib().mesa_ref_update_running_params_fixed_beta(_p(x), _dt(x), I64(outer), I64(groups), I64(inner), _p(a), _p(b),
+                                                    C.c_float(lam), C.c_int(int(first_call)), C.c_float(beta_fixed))
+    return a, b
+
+
 def quantize_headwise(x, layout, alpha, beta, mode=ROUND_NEAREST, seed=0, offset=0):
     outer, groups, inner = layout
     x = _c(x)

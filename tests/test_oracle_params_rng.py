@@ -186,3 +186,34 @@ def test_symmetric_range_bounds_the_nearest_rounding_error_and_centres_zero():
     # zero sits in the middle of the code range: codes 127 / 128 (-1 / 0 as stored) dequantize to -+ step/2
     z = R.dequantize(np.array([[-1, 0]] * 3, np.int8).reshape(1, 3, 2), (1, 3, 2), a, b).reshape(3, 2)
     assert np.allclose(z[:, 0], -0.5 * a / 255, rtol=1e-5, atol=4e-6) and np.allclose(z[:, 1], 0.5 * a / 255, rtol=1e-5, atol=4e-6)
+
+
+# ---- fixed offset (Sec. 6: beta of the second FFN layer's input stays at GELU's minimum) ---------------
+
+def test_fixed_offset_tracks_the_maximum_above_it():
+    lay = (6, 3, 50)
+    bf = np.float32(-0.17)
+    x0 = _x(50, lay)
+    a, b = R.update_running_params_fixed_beta(x0, lay, np.full(3, 9.0), 0.9, True, bf)
+    assert np.array_equal(b, np.full(3, bf)) and np.array_equal(a, x0.max(axis=(0, 2)) - bf)
+    # lambda = 0: the current batch's maximum above the offset, every time
+    for it in range(3):
+        x = _x(51 + it, lay)
+        a, b = R.update_running_params_fixed_beta(x, lay, a, 0.0, False, bf)
+        assert np.array_equal(a, x.max(axis=(0, 2)) - bf) and np.array_equal(b, np.full(3, bf))
+
+
+def test_fixed_offset_equals_the_general_update_when_the_minimum_is_the_offset():
+    # a GELU output whose minimum the batch attains: Eq. (6) for alpha is the same recursion in both forms
+    lay = (8, 2, 64)
+    bf = np.float32(-0.17)
+    rng = np.random.default_rng(55)
+    a_g, a_f = np.array([2.0, 3.0], np.float32), np.array([2.0, 3.0], np.float32)
+    b_g = np.full(2, bf)
+    for it in range(4):
+        x = np.maximum(rng.standard_normal(lay).astype(np.float32) * 2, bf)
+        x[0, :, 0] = bf
+        a_g, b_g = R.update_running_params(x, lay, a_g, b_g, 0.9, False)
+        a_f, b_f = R.update_running_params_fixed_beta(x, lay, a_f, 0.9, False, bf)
+        assert np.array_equal(a_g, a_f)
+        assert np.allclose(b_g, bf, rtol=3e-7, atol=0) and np.array_equal(b_f, np.full(2, bf))
