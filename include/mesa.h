@@ -91,6 +91,19 @@ mesa_status mesa_update_running_params_sym(const void *x, mesa_dtype dt, mesa_la
                                            void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Fixed offset, Sec. 6 (evolution of alpha and beta in FFN layers): the offset of the second FFN
+ * layer's input stays at GELU's minimum -0.17 and "can be fixed" there.  beta_g = beta_fixed for
+ * every group; alpha_g is the running estimate of mx_g - beta_fixed (Eq. (6) with the minimum
+ * replaced by beta_fixed; first_call != 0: alpha_g = mx_g - beta_fixed).  Values below beta_fixed
+ * saturate at the lowest code.  beta: [groups] (out).  beta_fixed must be finite.
+ * Other arguments, workspace and errors: as for mesa_update_running_params.
+ */
+mesa_status mesa_update_running_params_fixed_beta(const void *x, mesa_dtype dt, mesa_layout L,
+                                                  float *alpha, float *beta, float lambda,
+                                                  int first_call, float beta_fixed,
+                                                  void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Quantizer, Sec. 3.2 Eq. (3)-(4):  x_bar = clip(round((x - beta_g) * (255 / alpha_g)), 0, 255).
  * binary32, separately rounded: r = 255/alpha_g (0 when alpha_g <= 0), t = x - beta_g, v = t*r,
  *   nearest:     w = v rounded to the nearest integer, ties to even

@@ -20,7 +20,7 @@ ROUND_NEAREST_EVEN, ROUND_STOCHASTIC = 0, 1
 OP_UPDATE_RUNNING_PARAMS, OP_LAYERNORM_BWD_Q, OP_LINEAR_DW_Q = 0, 1, 2
 
 EXPORTS = [
-    "mesa_update_running_params", "mesa_update_running_params_sym", "mesa_quantize_headwise", "mesa_quantize_update_fused", "mesa_dequantize", "mesa_softmax_bwd_q",
+    "mesa_update_running_params", "mesa_update_running_params_sym", "mesa_update_running_params_fixed_beta", "mesa_quantize_headwise", "mesa_quantize_update_fused", "mesa_dequantize", "mesa_softmax_bwd_q",
     "mesa_gelu_bwd_q", "mesa_relu_bwd_q", "mesa_layernorm_bwd_q", "mesa_linear_dw_q", "mesa_attn_av_bwd_q", "mesa_attn_qk_bwd_q",
     "mesa_workspace_bytes",
     "mesa_status_string", "mesa_version", "mesa_stream_copy", "mesa_event_create", "mesa_event_record",
@@ -51,6 +51,7 @@ def lib() -> C.CDLL:
         L = C.CDLL(str(_LIB_PATH))
         L.mesa_update_running_params.argtypes = [_vp, _int, Layout, _vp, _vp, _f32, _int, _vp, _sz, _vp]
         L.mesa_update_running_params_sym.argtypes = L.mesa_update_running_params.argtypes
+        L.mesa_update_running_params_fixed_beta.argtypes = [_vp, _int, Layout, _vp, _vp, _f32, _int, _f32, _vp, _sz, _vp]
         L.mesa_quantize_headwise.argtypes = [_vp, _int, Layout, _vp, _vp, _vp, _int, _u64, _u64, _vp]
         L.mesa_quantize_update_fused.argtypes = [_vp, _int, Layout, _vp, _vp, _f32, _vp, _int, _u64, _u64, _vp, _sz, _vp]
         L.mesa_dequantize.argtypes = [_vp, Layout, _vp, _vp, _vp, _int, _vp]
@@ -133,6 +134,13 @@ def mesa_update_running_params_sym(x, layout, alpha, beta, lam, first_call, ws):
     p, n = _ws_args(ws)
     _check(lib().mesa_update_running_params_sym(_ptr(x), _dt(x), Layout(*layout), _ptr(alpha), _ptr(beta), float(lam),
                                                 int(bool(first_call)), p, n, _stream()), "mesa_update_running_params_sym")
+
+
+def mesa_update_running_params_fixed_beta(x, layout, alpha, beta, lam, first_call, beta_fixed, ws):
+    p, n = _ws_args(ws)
+    _check(lib().mesa_update_running_params_fixed_beta(_ptr(x), _dt(x), Layout(*layout), _ptr(alpha), _ptr(beta), float(lam),
+                                                       int(bool(first_call)), float(beta_fixed), p, n, _stream()),
+           "mesa_update_running_params_fixed_beta")
 
 
 def mesa_quantize_headwise(x, layout, alpha, beta, q, mode=ROUND_STOCHASTIC, seed=0, offset=0):

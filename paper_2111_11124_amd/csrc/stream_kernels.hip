@@ -407,10 +407,12 @@ __device__ __forceinline__ void ema_update(float mn, float mx, float alpha_old, 
 }
 
 // one workgroup per group: combine the partial extrema, then Eq. (6)-(7)
-// symmetric != 0: the extrema are replaced by -m and +m, m = max |x| = max(-min, max)
+// variant kEmaSymmetric: the extrema are replaced by -m and +m, m = max |x| = max(-min, max);
+// variant kEmaFixedBeta: the offset is beta_fixed, only alpha is a running estimate (of max - beta_fixed)
+enum { kEmaPlain = 0, kEmaSymmetric = 1, kEmaFixedBeta = 2 };
 __global__ __launch_bounds__(kThreads) void k_ema_finalize(const float *__restrict__ part, int nwg, uint32_t groups,
                                                            float *alpha, float *beta, float lambda, int first_call,
-                                                           int symmetric = 0)
+                                                           int variant = kEmaPlain, float beta_fixed = 0.0f)
 {
     __shared__ float smn[kThreads / 64], smx[kThreads / 64];
     const uint32_t g = blockIdx.x;
@@ -430,11 +432,16 @@ __global__ __launch_bounds__(kThreads) void k_ema_finalize(const float *__restri
     if (threadIdx.x == 0) {
 #pragma unroll
         for (int w = 1; w < kThreads / 64; ++w) { mn = vmin(mn, smn[w]); mx = vmax(mx, smx[w]); }
-        if (symmetric) {
+        if (variant == kEmaSymmetric) {
             mx = vmax(-mn, mx);
             mn = -mx;
         }
-        ema_update(mn, mx, alpha_old, beta_old, alpha, beta, g, lambda, first_call);
+        if (variant == kEmaFixedBeta) {
+            ema_update(beta_fixed, mx, alpha_old, beta_old, alpha, beta, g, lambda, first_call);
+            beta[g] = beta_fixed;
+        } else {
+            ema_update(mn, mx, alpha_old, beta_old, alpha, beta, g, lambda, first_call);
+        }
     }
 }
 
@@ -907,7 +914,7 @@ static bool minmax_few_groups(const mesa_layout &L, int grid, int unroll)
 }
 
 static mesa_status update_running_params(const void *x, mesa_dtype dt, mesa_layout L, float *alpha, float *beta, float lambda,
-                                         int first_call, int symmetric, void *ws, size_t ws_bytes, void *stream)
+                                         int first_call, int variant, float beta_fixed, void *ws, size_t ws_bytes, void *stream)
 {
     if (!valid_dtype(dt)) return MESA_ERR_INVALID_ARG;
     mesa_status st = check_layout(L);
@@ -942,21 +949,29 @@ static mesa_status update_running_params(const void *x, mesa_dtype dt, mesa_layo
     else
         hipLaunchKernelGGL((k_minmax_partial<float, kMmU>), dim3(grid), dim3(kThreads), lds, s, x, numel, gg, part);
     hipLaunchKernelGGL(k_ema_finalize, dim3(gg.groups), dim3(kThreads), 0, s, part, grid, gg.groups, alpha, beta, lambda,
-                       first_call, symmetric);
+                       first_call, variant, beta_fixed);
     return launch_status();
 }
 
 extern "C" MESA_EXPORT mesa_status mesa_update_running_params(const void *x, mesa_dtype dt, mesa_layout L, float *alpha, float *beta,
                                                   float lambda, int first_call, void *ws, size_t ws_bytes, void *stream)
 {
-    return update_running_params(x, dt, L, alpha, beta, lambda, first_call, 0, ws, ws_bytes, stream);
+    return update_running_params(x, dt, L, alpha, beta, lambda, first_call, kEmaPlain, 0.0f, ws, ws_bytes, stream);
 }
 
 extern "C" MESA_EXPORT mesa_status mesa_update_running_params_sym(const void *x, mesa_dtype dt, mesa_layout L, float *alpha,
                                                       float *beta, float lambda, int first_call, void *ws, size_t ws_bytes,
                                                       void *stream)
 {
-    return update_running_params(x, dt, L, alpha, beta, lambda, first_call, 1, ws, ws_bytes, stream);
+    return update_running_params(x, dt, L, alpha, beta, lambda, first_call, kEmaSymmetric, 0.0f, ws, ws_bytes, stream);
+}
+
+extern "C" MESA_EXPORT mesa_status mesa_update_running_params_fixed_beta(const void *x, mesa_dtype dt, mesa_layout L, float *alpha,
+                                                             float *beta, float lambda, int first_call, float beta_fixed,
+                                                             void *ws, size_t ws_bytes, void *stream)
+{
+    if (!(beta_fixed == beta_fixed) || beta_fixed - beta_fixed != 0.0f) return MESA_ERR_INVALID_ARG;   // NaN or infinite
+    return update_running_params(x, dt, L, alpha, beta, lambda, first_call, kEmaFixedBeta, beta_fixed, ws, ws_bytes, stream);
 }
 
 extern "C" MESA_EXPORT mesa_status mesa_quantize_headwise(const void *x, mesa_dtype dt, mesa_layout L, const float *alpha,

@@ -58,6 +58,9 @@ def test_argument_errors_are_reported_before_any_launch(M):
     assert L.mesa_update_running_params(P, M.F16, lay, P, P, 0.9, 0, None, 0, None) == M.ERR_WORKSPACE
     assert L.mesa_update_running_params_sym(P, M.F16, lay, P, P, 1.5, 0, P, 1 << 20, None) == M.ERR_INVALID_ARG
     assert L.mesa_update_running_params_sym(P, M.F16, lay, P, P, 0.9, 0, P, 8, None) == M.ERR_WORKSPACE
+    assert L.mesa_update_running_params_fixed_beta(P, M.F16, lay, P, P, 0.9, 0, float("nan"), P, 1 << 20, None) == M.ERR_INVALID_ARG
+    assert L.mesa_update_running_params_fixed_beta(P, M.F16, lay, P, P, 0.9, 0, float("inf"), P, 1 << 20, None) == M.ERR_INVALID_ARG
+    assert L.mesa_update_running_params_fixed_beta(P, M.F16, lay, P, P, 0.9, 0, -0.17, P, 8, None) == M.ERR_WORKSPACE
     assert L.mesa_quantize_update_fused(P, M.F16, lay, P, P, 0.9, P, 0, 0, 0, P, 8, None) == M.ERR_WORKSPACE
     assert L.mesa_quantize_update_fused(P, M.F16, lay, P, P, -0.1, P, 0, 0, 0, P, 1 << 20, None) == M.ERR_INVALID_ARG   # lambda
     assert L.mesa_quantize_update_fused(P, M.F16, lay, P, P, 0.9, None, 0, 0, 0, P, 1 << 20, None) == M.ERR_INVALID_ARG  # q

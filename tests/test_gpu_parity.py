@@ -422,6 +422,28 @@ def test_relu_backward_is_the_oracles_mask_exactly(M, layout, dtype):
     assert 0.2 < frac < 0.8, frac
 
 
+@pytest.mark.parametrize("dtype", [torch.float16, torch.float32])
+@pytest.mark.parametrize("layout", [(37, 6, 256), (5, 3, 361), (64, 12, 128)])
+def test_fixed_offset_update_matches_the_oracle_bit_for_bit(M, layout, dtype):
+    """Fixed beta = GELU's minimum (Sec. 6) on a GELU-output-like tensor: three steps, then the codes."""
+    G = layout[1]
+    bf = -0.17
+    gen = torch.Generator(device="cuda").manual_seed(layout[0] + 13 * layout[2])
+    xs = [torch.nn.functional.gelu(torch.randn(layout, generator=gen, device="cuda") * (1.5 + t)).to(dtype).contiguous() for t in range(3)]
+    a = torch.full((G,), 5.0, device="cuda")
+    b = torch.full((G,), 9.0, device="cuda")
+    ra = np.full(G, 5.0, np.float32)
+    ws = ws_for(M, M.OP_UPDATE_RUNNING_PARAMS, *layout, dt=dtype)
+    for t, x in enumerate(xs):
+        M.mesa_update_running_params_fixed_beta(x, layout, a, b, 0.9, t == 0, bf, ws)
+        ra, rb = R.update_running_params_fixed_beta(x.cpu().numpy(), layout, ra, 0.9, t == 0, bf)
+        assert np.array_equal(a.cpu().numpy(), ra) and np.array_equal(b.cpu().numpy(), rb), t
+    q = torch.empty(xs[-1].numel(), dtype=torch.int8, device="cuda")
+    M.mesa_quantize_headwise(xs[-1], layout, a, b, q, M.ROUND_STOCHASTIC, 9, 1)
+    rq = R.quantize_headwise(xs[-1].cpu().numpy(), layout, ra, rb, R.ROUND_STOCHASTIC, 9, 1).reshape(-1)
+    assert np.array_equal(q.cpu().numpy(), rq)
+
+
 def test_empty_inputs_are_a_no_op(M):
     z = torch.empty(0, device="cuda")
     a = torch.ones(3, device="cuda")
