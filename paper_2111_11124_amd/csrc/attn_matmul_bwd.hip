@@ -576,6 +576,223 @@ __global__ __launch_bounds__(kThreads, DT <= 1 ? 6 : DT == 2 ? 5 : 4) void k_att
     }
 }
 
+// ---- the two products that contract over the ROW index of both operands: dK = scale * dS^T Q_hat, dV = A_hat^T dO ----
+// One workgroup per head.  It walks down the rows i in chunks of 32: the chunk of the N x N operand (dS or the
+// A codes) is one contiguous, merely element-aligned piece of memory that comes in as aligned 16-byte
+// vectors and lies in LDS as it lies in memory; the chunk of the N x Dh operand (Q codes or dO) has aligned
+// rows and goes to LDS row by row.  The next chunk's loads are in flight while a chunk is multiplied
+// (two LDS buffers, one barrier per chunk).  The waves share out the blocks of 32 output rows j.  An MFMA
+// fragment of the N x N operand -- lane l: column j = l%32, the eight rows 8*(l/32) ..+7 of a 16-row step --
+// is gathered from LDS with eight 2-byte (1-byte) reads a row apart; the fragment of the other operand comes
+// from transposing reads.  The MFMA runs with the N x Dh operand on the M side, so a lane ends up with one
+// output row j and runs of four consecutive d.  Dh == 32 * DT; N <= 128 * JB (JB blocks of j per wave).
+template <int DT, int JB, bool WIDE_CODED, int NW> struct TnCfg {
+    static constexpr int kNt = 64 * NW;                     // threads of a workgroup (NW waves)
+    // WIDE_CODED: the N x N operand is the coded one (dV: A codes, dO plain); else dK: dS plain, Q codes
+    static constexpr int Dh = 32 * DT;
+    static constexpr int kWideEb = WIDE_CODED ? 1 : 2;     // bytes per element of the N x N operand
+    static constexpr int kRowNarrow = WIDE_CODED ? 2 * Dh + 32 : Dh + 32;   // bytes per staged row of the N x Dh operand
+    static constexpr int kNarrowVecs = 32 * Dh * (WIDE_CODED ? 2 : 1) / 16;   // 16-byte vectors per chunk of it
+    static constexpr int kMaxWideVecs = 4;                 // vectors of the N x N chunk per thread kept in flight
+    static size_t wide_bytes(int64_t N) { return (size_t(32) * N * kWideEb + 16 + 64 + 15) & ~size_t(15); }
+    static size_t narrow_bytes() { return size_t(32) * kRowNarrow; }
+    static size_t lds_bytes(int64_t N) { return 2 * (wide_bytes(N) + narrow_bytes()); }
+};
+
+template <int DT, int JB, bool WIDE_CODED, int NW>
+__global__ __launch_bounds__(64 * NW, (NW < 4 ? DT <= 2 : DT * JB <= 4 && DT < 4) ? 3 : DT * JB <= 6 ? 2 : 1) void k_attn_tn(const void *__restrict__ wide_, const void *__restrict__ narrow_,
+                                                         _Float16 *__restrict__ out, int N, int heads, float scale,
+                                                         const float *__restrict__ alpha, const float *__restrict__ beta,
+                                                         int wide_bytes, int64_t wide_elems)
+{
+    typedef TnCfg<DT, JB, WIDE_CODED, NW> C;
+    constexpr int kNt = C::kNt;
+    typedef typename BmElem<WIDE_CODED>::type WideT;        // element of the N x N operand
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_tn[];
+    constexpr int Dh = C::Dh;
+    constexpr int kEw = 16 / C::kWideEb;                   // elements of the N x N operand per 16-byte vector
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t bh = blockIdx.x;
+    const WideT *wide = static_cast<const WideT *>(wide_);
+    const unsigned char *narrow = static_cast<const unsigned char *>(narrow_) + bh * N * int64_t(Dh) * (WIDE_CODED ? 2 : 1);
+    const int fl = lane & 31, half = lane >> 5;
+    const int nchunks = (N + 31) >> 5;
+    // LDS: [chunk of the N x N operand] x 2, then [chunk of the N x Dh operand] x 2 (offsets, so that the
+    // accesses stay LDS accesses)
+    auto buf_w = [&](int b) { return lds_tn + b * wide_bytes; };
+    auto buf_n = [&](int b) { return lds_tn + 2 * wide_bytes + b * (32 * C::kRowNarrow); };
+
+    // ---- staging -------------------------------------------------------------------------------------
+    u32x4 wv[C::kMaxWideVecs], nv[(C::kNarrowVecs + kNt - 1) / kNt];
+    int mis = 0, nvec = 0, whole = 0;                      // of the chunk held in wv
+    auto chunk_geom = [&](int c, int &mis_, int &nvec_, int &whole_, int64_t &ebase_) {
+        const int i0 = c * 32;
+        const int rows = N - i0 < 32 ? N - i0 : 32;
+        const int64_t e0 = (bh * N + i0) * int64_t(N);     // first element of the chunk
+        mis_ = int(e0 & (kEw - 1));
+        ebase_ = e0 - mis_;
+        nvec_ = (mis_ + rows * N + kEw - 1) / kEw;
+        // the last vector of the whole tensor may reach past its end: that one is read element by element
+        whole_ = wide_elems - ebase_ >= int64_t(nvec_) * kEw ? nvec_ : nvec_ - 1;
+    };
+    auto load_chunk = [&](int c) {
+        int64_t ebase;
+        chunk_geom(c, mis, nvec, whole, ebase);
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(wide + ebase);
+#pragma unroll
+        for (int k = 0; k < C::kMaxWideVecs; ++k) {
+            const int v = tid + k * kNt;
+            if (v < whole) wv[k] = src[v];
+        }
+        const u32x4 *nsrc = reinterpret_cast<const u32x4 *>(narrow + int64_t(c) * 32 * Dh * (WIDE_CODED ? 2 : 1));
+        const int nrows = N - c * 32 < 32 ? N - c * 32 : 32;
+        const int nvecs = nrows * (C::kNarrowVecs / 32);
+#pragma unroll
+        for (int k = 0; k < int(sizeof(nv) / sizeof(nv[0])); ++k) {
+            const int v = tid + k * kNt;
+            if (v < nvecs) nv[k] = nsrc[v];
+            else nv[k] = u32x4{0u, 0u, 0u, 0u};            // rows past the end: zeros (codes of 0 / plain zeros)
+        }
+    };
+    auto store_chunk = [&](int c, int b) {
+        unsigned char *lw = buf_w(b);
+#pragma unroll
+        for (int k = 0; k < C::kMaxWideVecs; ++k) {
+            const int v = tid + k * kNt;
+            if (v < whole) *reinterpret_cast<u32x4 *>(lw + v * 16) = wv[k];
+        }
+        if (whole < nvec && tid < kEw) {                   // the tensor's very last, partial vector
+            int64_t ebase;
+            int m_, n_, w_;
+            chunk_geom(c, m_, n_, w_, ebase);
+            const int64_t g = ebase + int64_t(whole) * kEw + tid;
+            reinterpret_cast<WideT *>(lw)[whole * kEw + tid] = g < wide_elems ? wide[g] : WideT(0);
+        }
+        constexpr int kVecRow = C::kNarrowVecs / 32;
+#pragma unroll
+        for (int k = 0; k < int(sizeof(nv) / sizeof(nv[0])); ++k) {
+            const int v = tid + k * kNt;
+            if (v < C::kNarrowVecs) *reinterpret_cast<u32x4 *>(buf_n(b) + (v / kVecRow) * C::kRowNarrow + (v % kVecRow) * 16) = nv[k];
+        }
+    };
+
+    // ---- accumulators: wave w takes the blocks j = 32 * (w + NW * jb) ----------------------------------
+    bm_v16f acc[JB][DT];
+    bm_v16f acc1[WIDE_CODED ? DT : 1];                     // dV: column sums of dO per d, from MFMAs against ones
+    float csum[JB];                                        // dK: column sums of dS per j, per lane
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb) {
+        csum[jb] = 0.0f;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[jb][dt][v] = 0.0f;
+    }
+#pragma unroll
+    for (int dt = 0; dt < (WIDE_CODED ? DT : 1); ++dt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc1[dt][v] = 0.0f;
+    bm_v8h ones;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) ones[j] = (_Float16)1.0f;
+    const int blk = lane >> 4, sl = lane & 15;
+
+    load_chunk(0);
+    for (int c = 0; c < nchunks; ++c) {
+        const int b = c & 1;
+        const int mis_c = mis;
+        store_chunk(c, b);
+        if (c + 1 < nchunks) load_chunk(c + 1);
+        __syncthreads();   // chunk c is in LDS; every wave has finished with chunk c - 1 (the other buffer)
+        const int rows = N - c * 32 < 32 ? N - c * 32 : 32;
+        const WideT *lw = reinterpret_cast<const WideT *>(buf_w(b));
+        const unsigned char *ln = buf_n(b);
+        const bool ragged = rows < 32;                     // uniform: the head's last chunk
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            if (ks * 16 >= rows) break;                    // uniform
+            // fragments of the N x Dh operand: lane: d = 32*dt + l%32, rows 16*ks + 8*(l/32) ..+7
+            bm_v8h fn[DT];
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                if (WIDE_CODED) {
+                    const unsigned char *p = ln + (ks * 16 + (blk >> 1) * 8 + (sl >> 2)) * C::kRowNarrow + (dt * 32 + (blk & 1) * 16 + (sl & 3) * 4) * 2;
+                    const bm_v4h lo = __builtin_bit_cast(bm_v4h, __builtin_amdgcn_ds_read_tr16_b64_v4i16(BM_LDS3(bm_v4s, p)));
+                    const bm_v4h hi = __builtin_bit_cast(bm_v4h, __builtin_amdgcn_ds_read_tr16_b64_v4i16(BM_LDS3(bm_v4s, p + 4 * C::kRowNarrow)));
+                    fn[dt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    acc1[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fn[dt], ones, acc1[dt], 0, 0, 0);
+                } else {
+                    const unsigned char *p = ln + (ks * 16 + (blk >> 1) * 8 + (sl >> 1)) * C::kRowNarrow + dt * 32 + (blk & 1) * 16 + (sl & 1) * 8;
+                    fn[dt] = bm_codes_to_half8(__builtin_amdgcn_ds_read_tr8_b64_v2i32(BM_LDS3(bm_v2i, p)));
+                }
+            }
+#pragma unroll
+            for (int jb = 0; jb < JB; ++jb) {
+                const int j0 = (wave + NW * jb) * 32;
+                if (j0 >= N) break;                        // uniform per wave
+                const int j = j0 + fl < N ? j0 + fl : N - 1;   // columns past the end repeat the last one; never written
+                const int at = mis_c + (ks * 16 + half * 8) * N + j;
+                bm_v8h fw;
+                if (WIDE_CODED) {
+                    // rows past the end meet zeros of the other operand: any code will do there
+                    unsigned u[4];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)            // two codes per register: bits 0-7 and 16-23
+                        u[k] = unsigned(reinterpret_cast<const unsigned char *>(lw)[at + (2 * k) * N]) |
+                               (unsigned(reinterpret_cast<const unsigned char *>(lw)[at + (2 * k + 1) * N]) << 16);
+                    // stored byte -> binary16 of the signed code: (0x6400 | byte ^ 0x80) = 1024 + x_bar, minus 1152
+                    bm_v4u w4;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) w4[k] = (u[k] ^ 0x00800080u) | 0x64006400u;
+                    fw = __builtin_bit_cast(bm_v8h, w4);
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) fw[k] = fw[k] - (_Float16)1152.0f;
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) fw[k] = reinterpret_cast<const _Float16 *>(lw)[at + k * N];
+                    if (ragged) {                          // rows past the end: zeros (LDS holds stale data there)
+                        bm_v4u w4 = __builtin_bit_cast(bm_v4u, fw);
+                        const int r = ks * 16 + half * 8;
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) w4[k] &= (r + 2 * k < rows ? 0xffffu : 0u) | (r + 2 * k + 1 < rows ? 0xffff0000u : 0u);
+                        fw = __builtin_bit_cast(bm_v8h, w4);
+                    }
+#pragma unroll
+                    for (int k = 0; k < 8; k += 2)
+                        csum[jb] = __builtin_amdgcn_fdot2(bm_v2h{fw[k], fw[k + 1]}, bm_v2h{(_Float16)1.0f, (_Float16)1.0f}, csum[jb], false);
+                }
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) acc[jb][dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fn[dt], fw, acc[jb][dt], 0, 0, 0);
+            }
+        }
+    }
+
+    // ---- epilogue: lane l, register v of a tile: d = 32*dt + 8*(v/4) + 4*(l/32) + v%4, row j = j0 + l%32 ----
+    const int h = int(bh % heads);
+    const float s = alpha[h] / 255.0f;
+    const float off = fmaf(128.0f, s, beta[h]);
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb) {
+        const int j = (wave + NW * jb) * 32 + fl;
+        if (j >= N) continue;
+        float cs = 0.0f;
+        if (!WIDE_CODED) cs = off * (csum[jb] + __shfl_xor(csum[jb], 32));
+        _Float16 *po = out + (bh * N + j) * int64_t(Dh) + half * 4;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                bm_v4h o;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const float add = WIDE_CODED ? off * acc1[dt][4 * g + k] : cs;
+                    o[k] = (_Float16)(scale * fmaf(s, acc[jb][dt][4 * g + k], add));
+                }
+                *reinterpret_cast<bm_v4h *>(po + dt * 32 + g * 8) = o;
+            }
+    }
+}
+
 // whether k_attn_da can take the shape, and in which mode
 static bool da_solo(int64_t batches, int64_t N) { return N <= 64 && batches * ceil_div(N, 32) < (int64_t(1) << 32); }
 template <int KS> static bool da_fits(int64_t batches, int64_t N) { return DaCfg<KS>::lds_bytes(N, da_solo(batches, N)) <= 65536; }
@@ -610,6 +827,46 @@ template <int DT> static void launch_dq(const _Float16 *dS, const int8_t *kq, _F
         hipLaunchKernelGGL((k_attn_dq<DT>), dim3(gx, unsigned(nb)), dim3(kThreads), lds, s, dS, kq, dQ, N, Dh, heads, scale,
                            alpha_k, beta_k, t_chunk, b0);
     }
+}
+
+// whether k_attn_tn can take the shape: the chunk of 32 rows of the N x N operand within kMaxWideVecs vectors per
+// thread, at most 2 blocks of j per wave, LDS within the 64 KiB a kernel gets by default
+template <bool WIDE_CODED> static bool tn_fits(int64_t N, int64_t Dh)
+{
+    if (Dh != 32 && Dh != 64 && Dh != 96 && Dh != 128) return false;
+    const int64_t eb = WIDE_CODED ? 1 : 2, per_vec = 16 / eb;
+    if ((32 * N + 2 * (per_vec - 1)) / per_vec + 1 > int64_t(4) * kThreads) return false;
+    if (N > 256) return false;
+    const int64_t wide = (32 * N * eb + 16 + 64 + 15) / 16 * 16, narrow = 32 * (WIDE_CODED ? 2 * Dh + 32 : Dh + 32);
+    return 2 * (wide + narrow) <= 65536;
+}
+
+template <int DT, int JB, bool WIDE_CODED, int NW>
+static void launch_tn_one(const void *wide, const void *narrow, _Float16 *out, int64_t batches, int N, int heads, float scale,
+                          const float *alpha, const float *beta, hipStream_t s)
+{
+    typedef TnCfg<DT, JB, WIDE_CODED, NW> C;
+    hipLaunchKernelGGL((k_attn_tn<DT, JB, WIDE_CODED, NW>), dim3(unsigned(batches)), dim3(C::kNt), C::lds_bytes(N), s, wide, narrow,
+                       out, N, heads, scale, alpha, beta, int(C::wide_bytes(N)), batches * N * int64_t(N));
+}
+
+template <bool WIDE_CODED>
+static void launch_tn(const void *wide, const void *narrow, _Float16 *out, int64_t batches, int N, int Dh, int heads, float scale,
+                      const float *alpha, const float *beta, hipStream_t s)
+{
+    // waves per workgroup and blocks of j per wave, so that no wave is left without a block
+#define MESA_TN(DT_) \
+    do { \
+        if (N <= 32) launch_tn_one<DT_, 1, WIDE_CODED, 1>(wide, narrow, out, batches, N, heads, scale, alpha, beta, s); \
+        else if (N <= 64) launch_tn_one<DT_, 1, WIDE_CODED, 2>(wide, narrow, out, batches, N, heads, scale, alpha, beta, s); \
+        else if (N <= 128) launch_tn_one<DT_, 1, WIDE_CODED, 4>(wide, narrow, out, batches, N, heads, scale, alpha, beta, s); \
+        else launch_tn_one<DT_, 2, WIDE_CODED, 4>(wide, narrow, out, batches, N, heads, scale, alpha, beta, s); \
+    } while (0)
+    if (Dh == 32) MESA_TN(1);
+    else if (Dh == 64) MESA_TN(2);
+    else if (Dh == 96) MESA_TN(3);
+    else MESA_TN(4);
+#undef MESA_TN
 }
 
 static mesa_status check_attn(int64_t B, int64_t H, int64_t N, int64_t Dh, mesa_dtype dt)
@@ -669,7 +926,10 @@ extern "C" MESA_EXPORT mesa_status mesa_attn_av_bwd_q(const int8_t *aq, const in
     a.R = int(N); a.Cn = int(Dh); a.Tn = int(N);
     a.p_rs = 1; a.p_ts = N; a.q_ts = Dh; a.q_cs = 1;
     a.alpha = alpha_a; a.beta = beta_a;
-    launch_bmm<true, false, false>(a, batches, s);
+    if (tn_fits<true>(N, Dh) && batches < (int64_t(1) << 31))
+        launch_tn<true>(aq, dO, a.c, batches, int(N), int(Dh), int(H), 1.0f, alpha_a, beta_a, s);
+    else
+        launch_bmm<true, false, false>(a, batches, s);
     return launch_status();
 }
 
@@ -713,6 +973,9 @@ extern "C" MESA_EXPORT mesa_status mesa_attn_qk_bwd_q(const int8_t *qq, const in
     a.y = qq; a.c = static_cast<_Float16 *>(dK);
     a.p_rs = 1; a.p_ts = N; a.q_ts = Dh; a.q_cs = 1;
     a.alpha = alpha_q; a.beta = beta_q;
-    launch_bmm<false, false, false>(a, batches, s);
+    if (tn_fits<false>(N, Dh) && batches < (int64_t(1) << 31))
+        launch_tn<false>(dS, qq, a.c, batches, int(N), int(Dh), int(H), scale, alpha_q, beta_q, s);
+    else
+        launch_bmm<false, false, false>(a, batches, s);
     return launch_status();
 }
