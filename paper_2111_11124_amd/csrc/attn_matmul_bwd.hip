@@ -793,6 +793,148 @@ __global__ __launch_bounds__(64 * NW, (NW < 4 ? DT <= 2 : DT * JB <= 4 && DT < 4
     }
 }
 
+// ---- dQ = scale * dS K_hat for long rows: one workgroup per head -------------------------------------------
+// The head's K codes go to LDS once (rows j, zeros beyond N; fragments by transposing reads).  dS comes in
+// chunks of 64 rows -- contiguous, merely element-aligned pieces that lie in LDS as they lie in memory -- the
+// next chunk's vectors waiting in registers while a chunk is multiplied.  Wave w takes rows 32*(w&1) ..+31 of
+// the chunk and the d tiles of half w>>1.  A lane's dS fragment (eight consecutive j of its row) starts at an
+// arbitrary element of LDS: five aligned 4-byte reads, shifted into place (a misaligned 16-byte LDS read
+// stalls the LDS for dozens of cycles).  The MFMA runs with the codes on the M side, so a lane ends up with one
+// row i and runs of four consecutive d, and the beta term's row sum is a per-lane scalar.
+// Dh == 32 * DT, DT even or 1 (each half takes DT/2 tiles; DT == 1: only the waves of half 0 multiply).
+template <int DT> struct NnCfg {
+    static constexpr int Dh = 32 * DT;
+    static constexpr int kRowK = Dh + 32;                  // bytes per staged code row
+    static constexpr int kTiles = DT >= 2 ? DT / 2 : 1;    // d tiles of 32 per wave
+    static constexpr int kMaxVecs = 7;                     // dS vectors per thread and chunk
+    static size_t ds_bytes(int64_t N) { return (size_t(64) * N * 2 + 16 + 64 + 15) & ~size_t(15); }
+    static size_t lds_bytes(int64_t N) { return ds_bytes(N) + size_t(ceil_div(N, 16)) * 16 * kRowK; }
+};
+
+template <int DT>
+__global__ __launch_bounds__(kThreads, 3) void k_attn_nn(const _Float16 *__restrict__ dS, const int8_t *__restrict__ kq,
+                                                         _Float16 *__restrict__ dQ, int N, int heads, float scale,
+                                                         const float *__restrict__ alpha_k, const float *__restrict__ beta_k,
+                                                         int ds_bytes, int64_t ds_elems)
+{
+    typedef NnCfg<DT> C;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_nn[];
+    constexpr int Dh = C::Dh;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t bh = blockIdx.x;
+    unsigned char *lk = lds_nn + ds_bytes;
+    const int fl = lane & 31, half = lane >> 5;
+    const int nchunks = (N + 63) >> 6;
+
+    u32x4 wv[C::kMaxVecs];
+    int mis = 0, nvec = 0, whole = 0;
+    int64_t ebase = 0;
+    auto load_chunk = [&](int c) {
+        const int i0 = c * 64;
+        const int rows = N - i0 < 64 ? N - i0 : 64;
+        const int64_t e0 = (bh * N + i0) * int64_t(N);
+        mis = int(e0 & 7);
+        ebase = e0 - mis;
+        nvec = (mis + rows * N + 7) >> 3;
+        whole = ds_elems - ebase >= int64_t(nvec) * 8 ? nvec : nvec - 1;   // the tensor's last vector may reach past its end
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(dS + ebase);
+#pragma unroll
+        for (int k = 0; k < C::kMaxVecs; ++k) {
+            const int v = tid + k * kThreads;
+            if (v < whole) wv[k] = src[v];
+        }
+    };
+    auto store_chunk = [&]() {
+#pragma unroll
+        for (int k = 0; k < C::kMaxVecs; ++k) {
+            const int v = tid + k * kThreads;
+            if (v < whole) *reinterpret_cast<u32x4 *>(lds_nn + v * 16) = wv[k];
+        }
+        if (whole < nvec && tid < 8) {
+            const int64_t g = ebase + int64_t(whole) * 8 + tid;
+            reinterpret_cast<_Float16 *>(lds_nn)[whole * 8 + tid] = g < ds_elems ? dS[g] : (_Float16)0.0f;
+        }
+    };
+
+    load_chunk(0);
+    {   // the head's K codes: rows j of Dh bytes, rows N .. (a multiple of 16) zero
+        const u32x4 *kvec = reinterpret_cast<const u32x4 *>(kq + bh * N * int64_t(Dh));
+        constexpr int kVecRow = Dh / 16;
+        const int kvecs = N * kVecRow, all = ((N + 15) & ~15) * kVecRow;
+        for (int v = tid; v < all; v += kThreads) {
+            u32x4 w = {0u, 0u, 0u, 0u};
+            if (v < kvecs) w = kvec[v];
+            *reinterpret_cast<u32x4 *>(lk + (v / kVecRow) * C::kRowK + (v % kVecRow) * 16) = w;
+        }
+    }
+
+    const int blk = lane >> 4, sl = lane & 15;
+    const int i_loc = (wave & 1) * 32 + fl;                // row of the chunk
+    const int d0 = (wave >> 1) * (DT >= 2 ? Dh / 2 : 0);
+    const bool multiplies = DT >= 2 || (wave >> 1) == 0;
+    const unsigned char *pk = lk + ((blk >> 1) * 8 + (sl >> 1)) * C::kRowK + d0 + (blk & 1) * 16 + (sl & 1) * 8;
+    const unsigned *lds32 = reinterpret_cast<const unsigned *>(lds_nn);
+    const int h = int(bh % heads);
+    const float s = alpha_k[h] / 255.0f;
+    const float off = fmaf(128.0f, s, beta_k[h]);
+
+    for (int c = 0; c < nchunks; ++c) {
+        __syncthreads();                                   // the previous chunk has been multiplied
+        const int mis_c = mis;
+        store_chunk();
+        if (c + 1 < nchunks) load_chunk(c + 1);
+        __syncthreads();
+        const int rows = N - c * 64 < 64 ? N - c * 64 : 64;
+        if (!multiplies || (wave & 1) * 32 >= rows) continue;   // uniform per wave; the barriers are at the loop's top
+        const int e_row = mis_c + (i_loc < rows ? i_loc : rows - 1) * N + half * 8;   // rows past the end repeat the last one
+        const int shift = (e_row & 1) * 16;
+        bm_v16f acc[C::kTiles];
+#pragma unroll
+        for (int t = 0; t < C::kTiles; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
+        float rsum = 0.0f;
+        for (int j0 = 0; j0 < N; j0 += 16) {
+            const int w0 = (e_row + j0) >> 1;
+            unsigned w[5];
+#pragma unroll
+            for (int q = 0; q < 5; ++q) w[q] = lds32[w0 + q];
+            bm_v4u f;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) f[q] = __builtin_amdgcn_alignbit(w[q + 1], w[q], shift);
+            if (j0 + 16 > N) {                             // uniform: the row's ragged end, zeros beyond it
+                const int j = j0 + half * 8;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) f[q] &= (j + 2 * q < N ? 0xffffu : 0u) | (j + 2 * q + 1 < N ? 0xffff0000u : 0u);
+            }
+            const bm_v8h fs = __builtin_bit_cast(bm_v8h, f);
+#pragma unroll
+            for (int q = 0; q < 8; q += 2)
+                rsum = __builtin_amdgcn_fdot2(bm_v2h{fs[q], fs[q + 1]}, bm_v2h{(_Float16)1.0f, (_Float16)1.0f}, rsum, false);
+#pragma unroll
+            for (int t = 0; t < C::kTiles; ++t) {
+                const bm_v8h fc = bm_codes_to_half8(__builtin_amdgcn_ds_read_tr8_b64_v2i32(BM_LDS3(bm_v2i, pk + j0 * C::kRowK + t * 32)));
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fc, fs, acc[t], 0, 0, 0);
+            }
+        }
+        rsum += __shfl_xor(rsum, 32);                      // both halves of the row's slots
+        if (i_loc < rows) {
+            // lane l, register v of a tile: d = 32*t + 8*(v/4) + 4*(l/32) + v%4, row i = l%32
+            const float add = off * rsum;
+            _Float16 *po = dQ + (bh * N + c * 64 + i_loc) * int64_t(Dh) + d0 + half * 4;
+#pragma unroll
+            for (int t = 0; t < C::kTiles; ++t)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    bm_v4h o;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) o[k] = (_Float16)(scale * fmaf(s, acc[t][4 * g + k], add));
+                    *reinterpret_cast<bm_v4h *>(po + t * 32 + g * 8) = o;
+                }
+        }
+    }
+}
+
 // whether k_attn_da can take the shape, and in which mode
 static bool da_solo(int64_t batches, int64_t N) { return N <= 64 && batches * ceil_div(N, 32) < (int64_t(1) << 32); }
 template <int KS> static bool da_fits(int64_t batches, int64_t N) { return DaCfg<KS>::lds_bytes(N, da_solo(batches, N)) <= 65536; }
@@ -867,6 +1009,23 @@ static void launch_tn(const void *wide, const void *narrow, _Float16 *out, int64
     else if (Dh == 96) MESA_TN(3);
     else MESA_TN(4);
 #undef MESA_TN
+}
+
+// whether k_attn_nn can take the shape: a 64-row chunk of dS within kMaxVecs vectors per thread, LDS within 64 KiB
+static bool nn_fits(int64_t N, int64_t Dh)
+{
+    if (Dh != 32 && Dh != 64 && Dh != 128) return false;
+    if ((64 * N + 14) / 8 + 1 > int64_t(7) * kThreads) return false;
+    const int64_t ds = (64 * N * 2 + 16 + 64 + 15) / 16 * 16;
+    return ds + ceil_div(N, 16) * 16 * (Dh + 32) <= 65536;
+}
+
+template <int DT> static void launch_nn(const _Float16 *dS, const int8_t *kq, _Float16 *dQ, int64_t batches, int N, int heads,
+                                        float scale, const float *alpha_k, const float *beta_k, hipStream_t s)
+{
+    typedef NnCfg<DT> C;
+    hipLaunchKernelGGL((k_attn_nn<DT>), dim3(unsigned(batches)), dim3(kThreads), C::lds_bytes(N), s, dS, kq, dQ, N, heads, scale,
+                       alpha_k, beta_k, int(C::ds_bytes(N)), batches * N * int64_t(N));
 }
 
 static mesa_status check_attn(int64_t B, int64_t H, int64_t N, int64_t Dh, mesa_dtype dt)
@@ -967,7 +1126,11 @@ extern "C" MESA_EXPORT mesa_status mesa_attn_qk_bwd_q(const int8_t *qq, const in
         launch_dq<3>(a.x, kq, a.c, batches, int(N), int(Dh), int(H), scale, alpha_k, beta_k, s);
     else if (N <= 64 && Dh == 128)
         launch_dq<4>(a.x, kq, a.c, batches, int(N), int(Dh), int(H), scale, alpha_k, beta_k, s);
-    else
+    else if (nn_fits(N, Dh) && batches < (int64_t(1) << 31)) {
+        if (Dh == 32) launch_nn<1>(a.x, kq, a.c, batches, int(N), int(H), scale, alpha_k, beta_k, s);
+        else if (Dh == 64) launch_nn<2>(a.x, kq, a.c, batches, int(N), int(H), scale, alpha_k, beta_k, s);
+        else launch_nn<4>(a.x, kq, a.c, batches, int(N), int(H), scale, alpha_k, beta_k, s);
+    } else
         launch_bmm<false, true, false>(a, batches, s);
     // dK[j,d] = scale * sum_i dS[i,j] * Q_hat[i,d]:  P = dS (r = j, t = i),  Q = Q codes (t = i, c = d)
     a.y = qq; a.c = static_cast<_Float16 *>(dK);
