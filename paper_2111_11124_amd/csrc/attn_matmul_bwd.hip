@@ -478,104 +478,6 @@ __global__ __launch_bounds__(kThreads, KS <= 4 ? 7 : 4) void k_attn_da(const _Fl
     }
 }
 
-// dQ[i,d] = scale * sum_j dS[i,j] * K_hat[j,d].  The head's K codes go to LDS once (rows j, zero beyond N),
-// from where the code fragments come by transposing reads; a wave takes 32 rows i of dS, whose fragments
-// are 16-byte element-aligned loads straight from global memory.  Dh == 32 * DT.
-template <int DT>
-__global__ __launch_bounds__(kThreads, DT <= 1 ? 6 : DT == 2 ? 5 : 4) void k_attn_dq(const _Float16 *__restrict__ dS, const int8_t *__restrict__ kq,
-                                                      _Float16 *__restrict__ dQ, int N, int Dh, int heads, float scale,
-                                                      const float *__restrict__ alpha_k, const float *__restrict__ beta_k,
-                                                      int t_chunk, int64_t batch0)
-{
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds_k[];   // [t_chunk][Dh + 32] bytes
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t bh = batch0 + blockIdx.y;
-    constexpr int pitch = 32 * DT + 32;                  // Dh == 32 * DT (checked by the launcher)
-    const int r0 = (int(blockIdx.x) * (kThreads / 64) + wave) * 32;
-    const int fl = lane & 31;
-    const int row = r0 + fl < N ? r0 + fl : N - 1;
-    const _Float16 *prow = dS + (bh * N + row) * int64_t(N);
-    const int8_t *kb = kq + bh * N * int64_t(Dh);
-    // A step covers 64 contraction slots, as four MFMAs of 16: lane l takes the 32 consecutive slots
-    // 32*(l/32) ..+31 of its row (64 contiguous bytes, so that a cache line is fetched once), eight per MFMA;
-    // the code fragments follow the same slot order through their LDS row numbers.
-    const int blk = lane >> 4, sl = lane & 15;
-    const int b_off = ((blk >> 1) * 32 + (sl >> 1)) * pitch + (blk & 1) * 16 + (sl & 1) * 8;
-    const int fk32 = (lane >> 5) * 32;
-
-    bm_v16f acc[DT], acc1;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        acc1[v] = 0.0f;
-#pragma unroll
-        for (int j = 0; j < DT; ++j) acc[j][v] = 0.0f;
-    }
-    bm_v8h ones;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) ones[j] = (_Float16)1.0f;
-
-    for (int tc0 = 0; tc0 < N; tc0 += t_chunk) {
-        __syncthreads();   // the previous chunk has been read
-        // rows tc0 .. tc0 + t_chunk of the K codes, 16 bytes per thread and turn; rows past N are zeros
-        constexpr int vec_per_row = 2 * DT;
-        for (int idx = tid; idx < t_chunk * vec_per_row; idx += kThreads) {
-            const int tr = idx / vec_per_row, cv = (idx % vec_per_row) * 16;
-            u32x4 w = {0u, 0u, 0u, 0u};
-            if (tc0 + tr < N) w = *reinterpret_cast<const u32x4 *>(kb + int64_t(tc0 + tr) * Dh + cv);
-            *reinterpret_cast<u32x4 *>(lds_k + tr * pitch + cv) = w;
-        }
-        __syncthreads();
-        if (r0 < N) {
-            const int t_end = tc0 + t_chunk < N ? tc0 + t_chunk : N;
-            for (int t0 = tc0; t0 < t_end; t0 += 64) {
-                const int t = t0 + fk32;
-                bm_v8h fa[4];
-                if (t0 + 64 <= N) {                          // uniform: every lane's slots lie inside the row
-#pragma unroll
-                    for (int ks = 0; ks < 4; ++ks) __builtin_memcpy(&fa[ks], prow + t + ks * 8, 16);
-                } else {                                     // the row's ragged end: zeros beyond it
-#pragma unroll
-                    for (int ks = 0; ks < 4; ++ks) {
-                        const int tk = t + ks * 8;
-                        if (tk + 8 <= N) {
-                            __builtin_memcpy(&fa[ks], prow + tk, 16);
-                        } else {
-#pragma unroll
-                            for (int j = 0; j < 8; ++j) fa[ks][j] = tk + j < N ? prow[tk + j] : (_Float16)0.0f;
-                        }
-                    }
-                }
-                const unsigned char *pb = lds_k + (t0 - tc0) * pitch + b_off;
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) {
-                    acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ks], ones, acc1, 0, 0, 0);
-#pragma unroll
-                    for (int j = 0; j < DT; ++j) {
-                        const bm_v8h fb = bm_codes_to_half8(
-                            __builtin_amdgcn_ds_read_tr8_b64_v2i32(BM_LDS3(bm_v2i, pb + ks * 8 * pitch + j * 32)));
-                        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ks], fb, acc[j], 0, 0, 0);
-                    }
-                }
-            }
-        }
-    }
-    if (r0 >= N) return;
-    const int h = int(bh % heads);
-    const float s = alpha_k[h] / 255.0f;
-    const float off = fmaf(128.0f, s, beta_k[h]);
-    _Float16 *cb = dQ + bh * N * int64_t(Dh);
-    const int row_l = r0 + (lane >> 5) * 4;
-#pragma unroll
-    for (int j = 0; j < DT; ++j) {
-        const uint32_t o0 = uint32_t(row_l) * uint32_t(Dh) + uint32_t(j * 32 + fl);
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int dr = (v >> 2) * 8 + (v & 3);
-            if (row_l + dr < N) cb[o0 + uint32_t(dr) * uint32_t(Dh)] = (_Float16)(scale * fmaf(s, acc[j][v], off * acc1[v]));
-        }
-    }
-}
-
 // ---- the two products that contract over the ROW index of both operands: dK = scale * dS^T Q_hat, dV = A_hat^T dO ----
 // One workgroup per head.  It walks down the rows i in chunks of 32: the chunk of the N x N operand (dS or the
 // A codes) is one contiguous, merely element-aligned piece of memory that comes in as aligned 16-byte
@@ -806,13 +708,14 @@ template <int DT> struct NnCfg {
     static constexpr int Dh = 32 * DT;
     static constexpr int kRowK = Dh + 32;                  // bytes per staged code row
     static constexpr int kTiles = DT >= 2 ? DT / 2 : 1;    // d tiles of 32 per wave
-    static constexpr int kMaxVecs = 7;                     // dS vectors per thread and chunk
+    static constexpr int kNt = DT >= 2 ? 256 : 128;        // threads: four waves, or two when there is one d tile
+    static constexpr int kMaxVecs = 1792 / kNt;            // dS vectors per thread and chunk
     static size_t ds_bytes(int64_t N) { return (size_t(64) * N * 2 + 16 + 64 + 15) & ~size_t(15); }
     static size_t lds_bytes(int64_t N) { return ds_bytes(N) + size_t(ceil_div(N, 16)) * 16 * kRowK; }
 };
 
 template <int DT>
-__global__ __launch_bounds__(kThreads, 3) void k_attn_nn(const _Float16 *__restrict__ dS, const int8_t *__restrict__ kq,
+__global__ __launch_bounds__(NnCfg<DT>::kNt, 3) void k_attn_nn(const _Float16 *__restrict__ dS, const int8_t *__restrict__ kq,
                                                          _Float16 *__restrict__ dQ, int N, int heads, float scale,
                                                          const float *__restrict__ alpha_k, const float *__restrict__ beta_k,
                                                          int ds_bytes, int64_t ds_elems)
@@ -840,14 +743,14 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_nn(const _Float16 *__restr
         const u32x4 *src = reinterpret_cast<const u32x4 *>(dS + ebase);
 #pragma unroll
         for (int k = 0; k < C::kMaxVecs; ++k) {
-            const int v = tid + k * kThreads;
+            const int v = tid + k * C::kNt;
             if (v < whole) wv[k] = src[v];
         }
     };
     auto store_chunk = [&]() {
 #pragma unroll
         for (int k = 0; k < C::kMaxVecs; ++k) {
-            const int v = tid + k * kThreads;
+            const int v = tid + k * C::kNt;
             if (v < whole) *reinterpret_cast<u32x4 *>(lds_nn + v * 16) = wv[k];
         }
         if (whole < nvec && tid < 8) {
@@ -861,7 +764,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_nn(const _Float16 *__restr
         const u32x4 *kvec = reinterpret_cast<const u32x4 *>(kq + bh * N * int64_t(Dh));
         constexpr int kVecRow = Dh / 16;
         const int kvecs = N * kVecRow, all = ((N + 15) & ~15) * kVecRow;
-        for (int v = tid; v < all; v += kThreads) {
+        for (int v = tid; v < all; v += C::kNt) {
             u32x4 w = {0u, 0u, 0u, 0u};
             if (v < kvecs) w = kvec[v];
             *reinterpret_cast<u32x4 *>(lk + (v / kVecRow) * C::kRowK + (v % kVecRow) * 16) = w;
@@ -871,7 +774,6 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_nn(const _Float16 *__restr
     const int blk = lane >> 4, sl = lane & 15;
     const int i_loc = (wave & 1) * 32 + fl;                // row of the chunk
     const int d0 = (wave >> 1) * (DT >= 2 ? Dh / 2 : 0);
-    const bool multiplies = DT >= 2 || (wave >> 1) == 0;
     const unsigned char *pk = lk + ((blk >> 1) * 8 + (sl >> 1)) * C::kRowK + d0 + (blk & 1) * 16 + (sl & 1) * 8;
     const unsigned *lds32 = reinterpret_cast<const unsigned *>(lds_nn);
     const int h = int(bh % heads);
@@ -885,7 +787,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_nn(const _Float16 *__restr
         if (c + 1 < nchunks) load_chunk(c + 1);
         __syncthreads();
         const int rows = N - c * 64 < 64 ? N - c * 64 : 64;
-        if (!multiplies || (wave & 1) * 32 >= rows) continue;   // uniform per wave; the barriers are at the loop's top
+        if ((wave & 1) * 32 >= rows) continue;             // uniform per wave; the barriers are at the loop's top
         const int e_row = mis_c + (i_loc < rows ? i_loc : rows - 1) * N + half * 8;   // rows past the end repeat the last one
         const int shift = (e_row & 1) * 16;
         bm_v16f acc[C::kTiles];
@@ -958,19 +860,6 @@ template <int KS> static void launch_da(const _Float16 *dO, const int8_t *vq, _F
     }
 }
 
-template <int DT> static void launch_dq(const _Float16 *dS, const int8_t *kq, _Float16 *dQ, int64_t batches, int N, int Dh,
-                                        int heads, float scale, const float *alpha_k, const float *beta_k, hipStream_t s)
-{
-    const unsigned gx = unsigned(ceil_div(N, 32 * (kThreads / 64)));
-    const int t_chunk = N < 256 ? int(ceil_div(N, 64)) * 64 : 256;
-    const size_t lds = size_t(t_chunk) * size_t(Dh + 32);      // at most 256 * 160 bytes
-    for (int64_t b0 = 0; b0 < batches; b0 += 65535) {
-        const int64_t nb = batches - b0 < 65535 ? batches - b0 : 65535;
-        hipLaunchKernelGGL((k_attn_dq<DT>), dim3(gx, unsigned(nb)), dim3(kThreads), lds, s, dS, kq, dQ, N, Dh, heads, scale,
-                           alpha_k, beta_k, t_chunk, b0);
-    }
-}
-
 // whether k_attn_tn can take the shape: the chunk of 32 rows of the N x N operand within kMaxWideVecs vectors per
 // thread, at most 2 blocks of j per wave, LDS within the 64 KiB a kernel gets by default
 template <bool WIDE_CODED> static bool tn_fits(int64_t N, int64_t Dh)
@@ -1015,7 +904,7 @@ static void launch_tn(const void *wide, const void *narrow, _Float16 *out, int64
 static bool nn_fits(int64_t N, int64_t Dh)
 {
     if (Dh != 32 && Dh != 64 && Dh != 128) return false;
-    if ((64 * N + 14) / 8 + 1 > int64_t(7) * kThreads) return false;
+    if ((64 * N + 14) / 8 + 1 > 1792) return false;
     const int64_t ds = (64 * N * 2 + 16 + 64 + 15) / 16 * 16;
     return ds + ceil_div(N, 16) * 16 * (Dh + 32) <= 65536;
 }
@@ -1024,7 +913,7 @@ template <int DT> static void launch_nn(const _Float16 *dS, const int8_t *kq, _F
                                         float scale, const float *alpha_k, const float *beta_k, hipStream_t s)
 {
     typedef NnCfg<DT> C;
-    hipLaunchKernelGGL((k_attn_nn<DT>), dim3(unsigned(batches)), dim3(kThreads), C::lds_bytes(N), s, dS, kq, dQ, N, heads, scale,
+    hipLaunchKernelGGL((k_attn_nn<DT>), dim3(unsigned(batches)), dim3(C::kNt), C::lds_bytes(N), s, dS, kq, dQ, N, heads, scale,
                        alpha_k, beta_k, int(C::ds_bytes(N)), batches * N * int64_t(N));
 }
 
@@ -1117,16 +1006,7 @@ extern "C" MESA_EXPORT mesa_status mesa_attn_qk_bwd_q(const int8_t *qq, const in
     a.y = kq; a.c = static_cast<_Float16 *>(dQ);
     a.p_rs = N; a.p_ts = 1; a.q_ts = Dh; a.q_cs = 1;
     a.alpha = alpha_k; a.beta = beta_k;
-    // short rows (windowed attention): the direct-fragment kernel; long rows: the general one
-    if (N <= 64 && Dh == 32)
-        launch_dq<1>(a.x, kq, a.c, batches, int(N), int(Dh), int(H), scale, alpha_k, beta_k, s);
-    else if (N <= 64 && Dh == 64)
-        launch_dq<2>(a.x, kq, a.c, batches, int(N), int(Dh), int(H), scale, alpha_k, beta_k, s);
-    else if (N <= 64 && Dh == 96)
-        launch_dq<3>(a.x, kq, a.c, batches, int(N), int(Dh), int(H), scale, alpha_k, beta_k, s);
-    else if (N <= 64 && Dh == 128)
-        launch_dq<4>(a.x, kq, a.c, batches, int(N), int(Dh), int(H), scale, alpha_k, beta_k, s);
-    else if (nn_fits(N, Dh) && batches < (int64_t(1) << 31)) {
+    if (nn_fits(N, Dh) && batches < (int64_t(1) << 31)) {
         if (Dh == 32) launch_nn<1>(a.x, kq, a.c, batches, int(N), int(H), scale, alpha_k, beta_k, s);
         else if (Dh == 64) launch_nn<2>(a.x, kq, a.c, batches, int(N), int(H), scale, alpha_k, beta_k, s);
         else launch_nn<4>(a.x, kq, a.c, batches, int(N), int(H), scale, alpha_k, beta_k, s);
