@@ -501,8 +501,14 @@ template <int DT, int JB, bool WIDE_CODED, int NW> struct TnCfg {
     static size_t lds_bytes(int64_t N) { return 2 * (wide_bytes(N) + narrow_bytes()); }
 };
 
+// waves per SIMD the register budget is set for (the accumulators are 16 * DT * JB registers)
+template <int DT, int JB, int NW> constexpr int tn_waves_per_simd()
+{
+    return (NW < 4 ? DT <= 2 : DT * JB <= 4 && DT < 4) ? 3 : DT * JB <= 6 ? 2 : 1;
+}
+
 template <int DT, int JB, bool WIDE_CODED, int NW>
-__global__ __launch_bounds__(64 * NW, (NW < 4 ? DT <= 2 : DT * JB <= 4 && DT < 4) ? 3 : DT * JB <= 6 ? 2 : 1) void k_attn_tn(const void *__restrict__ wide_, const void *__restrict__ narrow_,
+__global__ __launch_bounds__(64 * NW, (tn_waves_per_simd<DT, JB, NW>())) void k_attn_tn(const void *__restrict__ wide_, const void *__restrict__ narrow_,
                                                          _Float16 *__restrict__ out, int N, int heads, float scale,
                                                          const float *__restrict__ alpha, const float *__restrict__ beta,
                                                          int wide_bytes, int64_t wide_elems)
