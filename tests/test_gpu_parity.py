@@ -346,7 +346,7 @@ def test_per_sample_statistics_through_the_layout_descriptor(M, dtype):
     assert relerr(dx2.cpu().numpy().reshape(ref2.shape), ref2) <= TOL[dtype]
 
 
-@pytest.mark.parametrize("B,H,N,Dh", [(2, 3, 19, 8), (3, 6, 197, 64), (2, 4, 64, 32), (1, 2, 130, 100), (5, 3, 49, 32), (1, 2, 300, 128), (2, 2, 33, 48), (1, 3, 40, 96), (3, 2, 40, 64), (2, 2, 8, 32), (1, 1, 65, 32), (1, 2, 24, 128)])
+@pytest.mark.parametrize("B,H,N,Dh", [(2, 3, 19, 8), (3, 6, 197, 64), (2, 4, 64, 32), (1, 2, 130, 100), (5, 3, 49, 32), (1, 2, 300, 128), (2, 2, 33, 48), (1, 3, 40, 96), (3, 2, 40, 64), (2, 2, 8, 32), (1, 1, 65, 32), (1, 2, 24, 128), (1, 1, 255, 128), (1, 2, 223, 32), (2, 1, 224, 64), (1, 1, 256, 96)])
 def test_attention_matmul_backward_against_the_oracle(M, B, H, N, Dh):
     """dA, dV of O = A V and dQ, dK of S = scale Q K^T at head-wise codes (binary16), chained through the
     library's own softmax backward as a training step would."""
