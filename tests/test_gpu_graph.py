@@ -1,0 +1,87 @@
+"""The library's calls inside a captured HIP graph: none of them allocates, clears memory or synchronises,
+so a captured step must replay to exactly what the same calls produce eagerly -- on every replay, with
+eager work and synchronisations in between."""
+import pytest
+import torch
+
+import mesa_workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def M():
+    import paper_2111_11124_amd as m
+    assert torch.cuda.is_available()
+    m.lib()
+    return m
+
+
+def ws(m, op, a, b, c):
+    return torch.empty(max(m.workspace_bytes(op, a, b, c, m.F16), 16), dtype=torch.uint8, device="cuda")
+
+
+def test_a_captured_step_replays_to_the_eager_results(M):
+    spec = W.small_case(torch.float16, B=6, H=3, N=49, D=96, mlp=384)
+    dev = "cuda"
+    B, H, N, _ = spec.attn
+    Dh = spec.dim // spec.heads
+    lay_a, lay_g = spec.attn_layout, spec.gelu_layout
+    y = W.attention_map(spec, 0, dev)
+    xg = W.gelu_input(spec, 0, dev)
+    dy_a = W.upstream_grad(spec, "dy_attn", y.shape, dev)
+    dy_g = W.upstream_grad(spec, "dy_gelu", xg.shape, dev)
+    g = torch.Generator(device=dev).manual_seed(5)
+    dO = torch.randn((B, H, N, Dh), device=dev, generator=g).half()
+    vq = torch.randint(-128, 128, (B, H, N, Dh), dtype=torch.int8, device=dev, generator=g)
+    xl = (torch.randn((B * N, spec.dim), device=dev, generator=g) * 0.7).half()
+    dyl = torch.randn((B * N, spec.mlp), device=dev, generator=g).half()
+    lay_l = (B * N, H, spec.dim // H)
+
+    init = {"aa": torch.full((H,), 0.8, device=dev), "ba": torch.full((H,), 0.0, device=dev),
+            "ag": torch.full((H,), 6.0, device=dev), "bg": torch.full((H,), -3.0, device=dev),
+            "al": torch.full((H,), 5.0, device=dev), "bl": torch.full((H,), -2.5, device=dev)}
+    st = {k: v.clone() for k, v in init.items()}
+    buf = {"qa": torch.empty(y.numel(), dtype=torch.int8, device=dev), "qg": torch.empty(xg.numel(), dtype=torch.int8, device=dev),
+           "ql": torch.empty(xl.numel(), dtype=torch.int8, device=dev), "dxa": torch.empty_like(dy_a), "dxg": torch.empty_like(dy_g),
+           "dA": torch.empty((B, H, N, N), dtype=torch.half, device=dev), "dV": torch.empty_like(dO),
+           "dW": torch.empty((spec.mlp, spec.dim), device=dev), "db": torch.empty(spec.mlp, device=dev)}
+    w_a, w_g, w_l = (ws(M, M.OP_UPDATE_RUNNING_PARAMS, *l) for l in (lay_a, lay_g, lay_l))
+    w_dw = ws(M, M.OP_LINEAR_DW_Q, B * N, spec.dim, spec.mlp)
+
+    def step():
+        M.mesa_update_running_params(y, lay_a, st["aa"], st["ba"], 0.9, False, w_a)
+        M.mesa_quantize_headwise(y, lay_a, st["aa"], st["ba"], buf["qa"], M.ROUND_STOCHASTIC, 3, 0)
+        M.mesa_quantize_update_fused(xg, lay_g, st["ag"], st["bg"], 0.9, buf["qg"], w_g, M.ROUND_STOCHASTIC, 4, 0)
+        M.mesa_update_running_params_sym(xl, lay_l, st["al"], st["bl"], 0.9, False, w_l)
+        M.mesa_quantize_headwise(xl, lay_l, st["al"], st["bl"], buf["ql"], M.ROUND_NEAREST_EVEN)
+        M.mesa_softmax_bwd_q(buf["qa"], B, H, N, N, st["aa"], st["ba"], dy_a, buf["dxa"])
+        M.mesa_gelu_bwd_q(buf["qg"], lay_g, st["ag"], st["bg"], dy_g, buf["dxg"])
+        M.mesa_attn_av_bwd_q(buf["qa"], vq, B, H, N, Dh, st["aa"], st["ba"], st["ag"], st["bg"], dO, buf["dA"], buf["dV"])
+        M.mesa_linear_dw_q(buf["ql"], B * N, spec.dim, H, st["al"], st["bl"], dyl, spec.mlp, buf["dW"], buf["db"], w_dw)
+
+    # eager: three steps from the initial estimates, every step's results kept
+    eager = []
+    for _ in range(3):
+        step()
+        torch.cuda.synchronize()
+        eager.append({k: v.clone() for k, v in list(st.items()) + list(buf.items())})
+
+    # captured once, from the same initial estimates; replayed three times with eager work in between
+    for k in st:
+        st[k].copy_(init[k])
+    for v in buf.values():
+        v.zero_()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    scratch = torch.empty_like(dy_g)
+    for t in range(3):
+        graph.replay()
+        M.mesa_dequantize(buf["qg"], lay_g, st["ag"], st["bg"], scratch)    # the program's own eager work
+        scratch.mul_(2.0)
+        torch.cuda.synchronize()
+        for k, ref in eager[t].items():
+            got = st[k] if k in st else buf[k]
+            assert torch.equal(got, ref), (t, k)
