@@ -351,6 +351,23 @@ int mesa_ref_quantize_update_fused(const void *x, int dt, int64_t outer, int64_t
     return mesa_ref_update_running_params(x, dt, outer, groups, inner, alpha, beta, lambda, 0);
 }
 
+/*
+ * A Mesa GELU layer's forward in one step (Sec. 3.1: the forward pass is computed exactly, the input
+ * is what gets saved, compressed): y = gelu(x) = x * Phi(x) from the exact x, and the single-pass
+ * forward above for the saved input (codes with the estimates as they are on entry, then Eq. (6)-(7)).
+ */
+int mesa_ref_gelu_fwd_q(const void *x, int dt, int64_t outer, int64_t groups, int64_t inner,
+                        float *alpha, float *beta, float lambda, double *y, int8_t *q,
+                        int mode, uint64_t seed, uint64_t offset)
+{
+    int64_t n = outer * groups * inner;
+    for (int64_t e = 0; e < n; ++e) {
+        double v = load_as_double(x, dt, e);
+        y[e] = 0.5 * v * (1.0 + erf(v / sqrt(2.0)));
+    }
+    return mesa_ref_quantize_update_fused(x, dt, outer, groups, inner, alpha, beta, lambda, q, mode, seed, offset);
+}
+
 /* ------------------------------------------------------------------------ */
 /* Eq. (5): dequantize                                                       */
 /* ------------------------------------------------------------------------ */

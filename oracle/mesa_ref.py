@@ -173,6 +173,21 @@ def quantize_update_fused(x, layout, alpha, beta, lam, mode=ROUND_NEAREST, seed=
     return q.reshape(x.shape), a, b
 
 
+def gelu_fwd_q(x, layout, alpha, beta, lam, mode=ROUND_NEAREST, seed=0, offset=0):
+    """A Mesa GELU layer's forward: returns (y in binary64, q, alpha', beta')."""
+    outer, groups, inner = layout
+    x = _c(x)
+    assert x.size == outer * groups * inner
+    a = _c(alpha, np.float32).copy()
+    b = _c(beta, np.float32).copy()
+    assert a.size == groups and b.size == groups
+    q = np.empty(x.size, np.int8)
+    y = np.empty(x.size, np.float64)
+    lib().mesa_ref_gelu_fwd_q(_p(x), _dt(x), I64(outer), I64(groups), I64(inner), _p(a), _p(b), C.c_float(lam), _p(y),
+                              _p(q), C.c_int(mode), C.c_uint64(seed), C.c_uint64(offset))
+    return y.reshape(x.shape), q.reshape(x.shape), a, b
+
+
 def dequantize(q, layout, alpha, beta, dtype=np.float32):
     outer, groups, inner = layout
     q = _c(q, np.int8)

@@ -141,6 +141,25 @@ def test_relu_backward_against_finite_differences_torch_and_the_mask_it_is():
     assert np.array_equal(R.relu_bwd_q(q0, (1, 1, 3), a0, b0, np.ones(3, np.float32)), [0.0, 1.0, 0.0])
 
 
+def test_gelu_layer_forward_is_the_library_gelu_plus_the_single_pass_codes():
+    # y against torch's exact GELU in binary64 and the erf formula typed out; its minimum is the -0.17 the paper prints;
+    # codes and estimates are the single-pass forward's (pinned on its own)
+    rng = np.random.default_rng(7)
+    lay = (5, 3, 40)
+    a0, b0 = np.array([6.0, 7.0, 8.0], np.float32), np.array([-3.0, -3.5, -4.0], np.float32)
+    for dt in (np.float32, np.float16):
+        x = (rng.standard_normal(lay) * 1.7).astype(dt)
+        y, q, a, b = R.gelu_fwd_q(x, lay, a0, b0, 0.9, R.ROUND_STOCHASTIC, 5, 2)
+        xd = x.astype(np.float64)
+        assert np.allclose(y, torch.nn.functional.gelu(torch.from_numpy(xd)).numpy(), rtol=1e-13, atol=1e-15)
+        assert np.allclose(y, gelu(xd), rtol=1e-13, atol=1e-15)
+        q2, a2, b2 = R.quantize_update_fused(x, lay, a0, b0, 0.9, R.ROUND_STOCHASTIC, 5, 2)
+        assert np.array_equal(q, q2) and np.array_equal(a, a2) and np.array_equal(b, b2)
+    grid = np.linspace(-2, 0, 200001).astype(np.float32)
+    yg = R.gelu_fwd_q(grid, (1, 1, grid.size), [1.0], [0.0], 0.9)[0]
+    assert abs(yg.min() - (-0.16997)) < 1e-5
+
+
 def test_gelu_derivative_vanishes_at_the_minimum_the_paper_prints():
     # FFN visualisation section: the offset of the second FC layer's input sits at min GELU = -0.17
     want = float([l for l in open(os.path.join(GOLD, "gelu_min.txt")) if not l.startswith("#")][0])
