@@ -243,6 +243,41 @@ def attention_matmul_leg(m, spec, steps):
                     "results each moved once"}
 
 
+def gelu_layer_forward_leg(m, spec, steps):
+    """Outside the headline figure: a GELU layer's forward in one pass (mesa_gelu_fwd_q: y = gelu(x) and the codes of x
+    from one read of x) on the configuration's GELU input, next to the two passes it replaces."""
+    lay = spec.gelu_layout
+    n = lay[0] * lay[1] * lay[2]
+    dev = "cuda"
+    g = torch.Generator(device=dev).manual_seed(spec.seed + 3)
+    xs = [torch.randn(lay, device=dev, generator=g).to(spec.dtype) for _ in range(NSETS)]
+    ys = [torch.empty(lay, dtype=spec.dtype, device=dev) for _ in range(NSETS)]
+    qs = [torch.empty(n, dtype=torch.int8, device=dev) for _ in range(NSETS)]
+    a = torch.full((lay[1],), 8.0, device=dev)
+    b = torch.full((lay[1],), -4.0, device=dev)
+    ws = torch.empty(max(m.workspace_bytes(m.OP_UPDATE_RUNNING_PARAMS, *lay, m.F16 if spec.dtype == torch.float16 else m.F32), 16),
+                     dtype=torch.uint8, device=dev)
+
+    def timed(fn):
+        for i in range(3):
+            fn(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            fn(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    one = timed(lambda i: m.mesa_gelu_fwd_q(xs[i % NSETS], lay, a, b, 0.9, ys[i % NSETS], qs[i % NSETS], ws, m.ROUND_STOCHASTIC, 1, i))
+    two = timed(lambda i: (torch.nn.functional.gelu(xs[i % NSETS]),
+                           m.mesa_quantize_update_fused(xs[i % NSETS], lay, a, b, 0.9, qs[i % NSETS], ws, m.ROUND_STOCHASTIC, 1, i)))
+    esz = 2 if spec.dtype == torch.float16 else 4
+    nbytes = (2 * esz + 1) * n
+    return {"ms": round(one, 4), "GBps": round(nbytes / (one * 1e-3) / 1e9, 1), "frac_hbm": round(nbytes / (one * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "bytes": nbytes, "two_pass_ms": round(two, 4),
+            "note": "mesa_gelu_fwd_q; two_pass_ms: the framework's own exact GELU kernel followed by mesa_quantize_update_fused"}
+
+
 def workload_name(spec, number, lin):
     b, h, r, c = spec.attn
     dw = f"whole path incl. dW {lin[0]}->{lin[1]}" if lin else "whole path, no Linear layer named"
@@ -368,6 +403,7 @@ def main():
                                 "note": "variant, not the headline: mesa_quantize_update_fused replaces update + quantize (x read "
                                         "once; parameters lag one step), the backward half unchanged"},
         "attention_matmul_bwd": attention_matmul_leg(m, spec, args.steps) if args.config != 5 else None,
+        "gelu_layer_forward": gelu_layer_forward_leg(m, spec, args.steps),
         "per_call": {k: {"ms": round(v, 5), "GBps": round(bytes_per[k] / (v * 1e-3) / 1e9, 1),
                          "frac_hbm": round(bytes_per[k] / (v * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)} for k, v in per_kernel_ms.items()},
     }

@@ -137,6 +137,20 @@ mesa_status mesa_quantize_update_fused(const void *x, mesa_dtype dt, mesa_layout
                                        void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * A Mesa GELU layer's forward in one pass over x (Sec. 3.1: the forward output is computed from the
+ * exact input, the input is what is saved, compressed): y = gelu(x) (exact, erf form), and for the
+ * saved input x exactly what mesa_quantize_update_fused does -- codes q with alpha, beta as they are
+ * on entry, Eq. (3)-(4), then the running estimates moved by this batch's extrema, Eq. (6)-(7).
+ * x is read once; per binary16 element 2 bytes in, 2 + 1 bytes out.
+ * x: [numel] of dt (in).  y: [numel] of dt (out), not aliasing x.  q: [numel] int8 (out).
+ * alpha, beta: [groups] (in/out).  ws: MESA_OP_UPDATE_RUNNING_PARAMS bytes.
+ */
+mesa_status mesa_gelu_fwd_q(const void *x, mesa_dtype dt, mesa_layout L,
+                            float *alpha, float *beta, float lambda, void *y, int8_t *q,
+                            mesa_round mode, uint64_t seed, uint64_t offset,
+                            void *ws, size_t ws_bytes, void *stream);
+
+/*
  * De-quantizer, Sec. 3.2 Eq. (5):  x_hat = (q + 128) * (alpha_g / 255) + beta_g, binary32 with the
  * quotient, product and sum rounded separately, then rounded to dt (nearest even).
  * q: [numel] int8 (in).  x_hat: [numel] of dt (out).

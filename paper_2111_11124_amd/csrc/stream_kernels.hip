@@ -575,11 +575,25 @@ __global__ __launch_bounds__(kThreads) void k_quantize(const void *__restrict__ 
 // Quantize and take the extrema in one pass over x: the loop of k_quantize with the bookkeeping of
 // k_minmax_partial on the same registers.  Dynamic LDS: the (scale, beta) table, then the two
 // ordered-int extrema tables.  Partials as k_minmax_partial writes them.
-template <typename T, int U, bool SR>
+// gelu(x) = x * Phi(x), Phi(-|x|) = erfc(|x|/sqrt 2)/2 by Abramowitz & Stegun 7.1.26 (|error| <= 7.5e-8 on Phi)
+__device__ __forceinline__ float gelu_value(float x)
+{
+    const float ax = fabsf(x);
+    const float t = __builtin_amdgcn_rcpf(fmaf(ax, 0.3275911f * 0.70710678118654752f, 1.0f));
+    float poly = fmaf(t, 1.061405429f, -1.453152027f);
+    poly = fmaf(poly, t, 1.421413741f);
+    poly = fmaf(poly, t, -0.284496736f);
+    poly = fmaf(poly, t, 0.254829592f);
+    const float h = 0.5f * (poly * t) * __builtin_amdgcn_exp2f(x * x * -0.72134752044448170f);   // Phi(-|x|)
+    return x * (x >= 0.0f ? 1.0f - h : h);
+}
+
+// GELU_FWD: the kernel is a GELU layer's whole forward -- y = gelu(x) leaves in the same pass that takes the codes of x
+template <typename T, int U, bool SR, bool GELU_FWD = false>
 __global__ __launch_bounds__(kThreads) void k_quantize_minmax(const void *__restrict__ x, int8_t *__restrict__ q, int64_t numel,
                                                               GroupGeom gg, const float *__restrict__ alpha,
                                                               const float *__restrict__ beta, uint64_t seed, uint64_t offset,
-                                                              float *__restrict__ part)
+                                                              float *__restrict__ part, void *__restrict__ y = nullptr)
 {
     extern __shared__ float2 lds_tab[];
     int *lmn = reinterpret_cast<int *>(lds_tab + gg.groups);
@@ -625,6 +639,12 @@ __global__ __launch_bounds__(kThreads) void k_quantize_minmax(const void *__rest
                 float f[8], w[8], bits[8];
                 if (SR) sr_bits(seed, offset + uint64_t(e >> 3), bits);
                 Store<T>::unpack(v[u], f);
+                if (GELU_FWD) {
+                    float yv[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) yv[j] = gelu_value(f[j]);
+                    Nt<T>::store(y, e, Store<T>::pack(yv));
+                }
                 if (__builtin_expect(one, 1)) {
                     st[u].acc.add(v[u]);
                     const float2 p = lds_tab[c[u].g];
@@ -646,6 +666,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_minmax(const void *__rest
                 for (int j = 0; e + j < numel; ++j) {
                     const uint32_t g = group_of(c[u], j, gg);
                     const float xv = Store<T>::load1(x, e + j);
+                    if (GELU_FWD) Store<T>::store1(y, e + j, gelu_value(xv));
                     minmax_element<T>(st[u], g, xv, lmn, lmx);
                     const float2 p = lds_tab[g];
                     const float w = clamp_code(quantize_one<SR>(xv, p.x, p.y, SR ? bits[j] : 0.0f));
@@ -998,9 +1019,10 @@ extern "C" MESA_EXPORT mesa_status mesa_quantize_headwise(const void *x, mesa_dt
     return launch_status();
 }
 
-extern "C" MESA_EXPORT mesa_status mesa_quantize_update_fused(const void *x, mesa_dtype dt, mesa_layout L, float *alpha, float *beta,
-                                                              float lambda, int8_t *q, mesa_round mode, uint64_t seed,
-                                                              uint64_t offset, void *ws, size_t ws_bytes, void *stream)
+// the single-pass forward, optionally with the layer's own output: gelu_fwd: y = gelu(x) leaves in the same pass
+static mesa_status quantize_update_fused(const void *x, mesa_dtype dt, mesa_layout L, float *alpha, float *beta, float lambda,
+                                         bool gelu_fwd, void *y, int8_t *q, mesa_round mode, uint64_t seed, uint64_t offset,
+                                         void *ws, size_t ws_bytes, void *stream)
 {
     if (!valid_dtype(dt) || (mode != MESA_ROUND_NEAREST_EVEN && mode != MESA_ROUND_STOCHASTIC)) return MESA_ERR_INVALID_ARG;
     mesa_status st = check_layout(L);
@@ -1010,6 +1032,8 @@ extern "C" MESA_EXPORT mesa_status mesa_quantize_update_fused(const void *x, mes
     if (numel == 0) return MESA_OK;
     if (!x || !q || !alpha || !beta || !aligned16(x) || !aligned16(q) || !aligned4(alpha) || !aligned4(beta))
         return MESA_ERR_INVALID_ARG;
+    if (gelu_fwd && (!y || !aligned16(y) || y == x)) return MESA_ERR_INVALID_ARG;   // not in place: the kernel's pointers do not alias
+    if (!gelu_fwd) y = nullptr;
     if (!ws || !aligned16(ws) || ws_bytes < update_ws_bytes(L.outer, L.groups, L.inner)) return MESA_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int grid = minmax_grid(L, kFuU, kFuGridCap);
@@ -1017,14 +1041,33 @@ extern "C" MESA_EXPORT mesa_status mesa_quantize_update_fused(const void *x, mes
     const size_t lds = size_t(gg.groups) * (sizeof(float2) + 2 * sizeof(int));
     float *part = static_cast<float *>(ws);
     const bool sr = mode == MESA_ROUND_STOCHASTIC;
-#define MESA_LAUNCH_QM(T, SRF) \
-    hipLaunchKernelGGL((k_quantize_minmax<T, kFuU, SRF>), dim3(grid), dim3(kThreads), lds, s, x, q, numel, gg, alpha, beta, seed, \
-                       offset, part)
-    if (dt == MESA_F16) { if (sr) MESA_LAUNCH_QM(_Float16, true); else MESA_LAUNCH_QM(_Float16, false); }
-    else { if (sr) MESA_LAUNCH_QM(float, true); else MESA_LAUNCH_QM(float, false); }
+#define MESA_LAUNCH_QM(T, SRF, GF) \
+    hipLaunchKernelGGL((k_quantize_minmax<T, kFuU, SRF, GF>), dim3(grid), dim3(kThreads), lds, s, x, q, numel, gg, alpha, beta, seed, \
+                       offset, part, y)
+#define MESA_LAUNCH_QM_T(T) \
+    do { \
+        if (y) { if (sr) MESA_LAUNCH_QM(T, true, true); else MESA_LAUNCH_QM(T, false, true); } \
+        else { if (sr) MESA_LAUNCH_QM(T, true, false); else MESA_LAUNCH_QM(T, false, false); } \
+    } while (0)
+    if (dt == MESA_F16) MESA_LAUNCH_QM_T(_Float16); else MESA_LAUNCH_QM_T(float);
+#undef MESA_LAUNCH_QM_T
 #undef MESA_LAUNCH_QM
     hipLaunchKernelGGL(k_ema_finalize, dim3(gg.groups), dim3(kThreads), 0, s, part, grid, gg.groups, alpha, beta, lambda, 0);
     return launch_status();
+}
+
+extern "C" MESA_EXPORT mesa_status mesa_quantize_update_fused(const void *x, mesa_dtype dt, mesa_layout L, float *alpha, float *beta,
+                                                              float lambda, int8_t *q, mesa_round mode, uint64_t seed,
+                                                              uint64_t offset, void *ws, size_t ws_bytes, void *stream)
+{
+    return quantize_update_fused(x, dt, L, alpha, beta, lambda, false, nullptr, q, mode, seed, offset, ws, ws_bytes, stream);
+}
+
+extern "C" MESA_EXPORT mesa_status mesa_gelu_fwd_q(const void *x, mesa_dtype dt, mesa_layout L, float *alpha, float *beta,
+                                                   float lambda, void *y, int8_t *q, mesa_round mode, uint64_t seed,
+                                                   uint64_t offset, void *ws, size_t ws_bytes, void *stream)
+{
+    return quantize_update_fused(x, dt, L, alpha, beta, lambda, true, y, q, mode, seed, offset, ws, ws_bytes, stream);
 }
 
 extern "C" MESA_EXPORT mesa_status mesa_dequantize(const int8_t *q, mesa_layout L, const float *alpha, const float *beta, void *x_hat,

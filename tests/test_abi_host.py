@@ -65,6 +65,10 @@ def test_argument_errors_are_reported_before_any_launch(M):
     assert L.mesa_quantize_update_fused(P, M.F16, lay, P, P, -0.1, P, 0, 0, 0, P, 1 << 20, None) == M.ERR_INVALID_ARG   # lambda
     assert L.mesa_quantize_update_fused(P, M.F16, lay, P, P, 0.9, None, 0, 0, 0, P, 1 << 20, None) == M.ERR_INVALID_ARG  # q
     assert L.mesa_quantize_update_fused(P, M.F16, lay, P, P, 0.9, P, 3, 0, 0, P, 1 << 20, None) == M.ERR_INVALID_ARG     # mode
+    P2 = 0x20000
+    assert L.mesa_gelu_fwd_q(P, M.F16, lay, P, P, 0.9, None, P, 0, 0, 0, P, 1 << 20, None) == M.ERR_INVALID_ARG   # y missing
+    assert L.mesa_gelu_fwd_q(P, M.F16, lay, P, P, 0.9, P, P, 0, 0, 0, P, 1 << 20, None) == M.ERR_INVALID_ARG      # y aliases x
+    assert L.mesa_gelu_fwd_q(P, M.F16, lay, P, P, 0.9, P2, P, 0, 0, 0, P, 8, None) == M.ERR_WORKSPACE
     assert L.mesa_dequantize(P, lay, P, None, P, M.F16, None) == M.ERR_INVALID_ARG
     assert L.mesa_gelu_bwd_q(P, lay, P, P, P + 8, P, M.F16, None) == M.ERR_INVALID_ARG
     assert L.mesa_softmax_bwd_q(P, 2, 3, 5, 4, P, P, P, P, M.F16, None) == M.ERR_UNSUPPORTED              # cols < 8

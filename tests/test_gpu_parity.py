@@ -444,6 +444,28 @@ def test_fixed_offset_update_matches_the_oracle_bit_for_bit(M, layout, dtype):
     assert np.array_equal(q.cpu().numpy(), rq)
 
 
+@pytest.mark.parametrize("dtype", [torch.float16, torch.float32])
+@pytest.mark.parametrize("layout", [(37, 6, 256), (5, 3, 361), (3, 40, 77), (1, 1, 1003)])
+def test_gelu_layer_forward_in_one_pass(M, layout, dtype):
+    """y = gelu(x) within tolerance of the oracle's binary64 GELU; codes of x and the moved estimates bit for bit
+    (two steps, both rounding modes)."""
+    G = layout[1]
+    gen = torch.Generator(device="cuda").manual_seed(layout[0] * 17 + layout[2])
+    a = torch.full((G,), 7.0, device="cuda")
+    b = torch.full((G,), -3.5, device="cuda")
+    ra, rb = np.full(G, 7.0, np.float32), np.full(G, -3.5, np.float32)
+    ws = ws_for(M, M.OP_UPDATE_RUNNING_PARAMS, *layout, dt=dtype)
+    for t, (mode, rmode) in enumerate(((M.ROUND_STOCHASTIC, R.ROUND_STOCHASTIC), (M.ROUND_NEAREST_EVEN, R.ROUND_NEAREST))):
+        x = (torch.randn(layout, generator=gen, device="cuda") * (1.5 + t)).to(dtype).contiguous()
+        y = torch.empty_like(x)
+        q = torch.empty(x.numel(), dtype=torch.int8, device="cuda")
+        M.mesa_gelu_fwd_q(x, layout, a, b, 0.9, y, q, ws, mode, 21, 4)
+        ry, rq, ra, rb = R.gelu_fwd_q(x.cpu().numpy(), layout, ra, rb, 0.9, rmode, 21, 4)
+        assert np.array_equal(q.cpu().numpy(), rq.reshape(-1))
+        assert np.array_equal(a.cpu().numpy(), ra) and np.array_equal(b.cpu().numpy(), rb)
+        assert relerr(y.cpu().numpy(), ry) <= TOL[dtype]
+
+
 def test_empty_inputs_are_a_no_op(M):
     z = torch.empty(0, device="cuda")
     a = torch.ones(3, device="cuda")
