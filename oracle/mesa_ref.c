@@ -401,6 +401,28 @@ int mesa_ref_dequantize(const int8_t *q, int64_t outer, int64_t groups, int64_t 
     return 0;
 }
 
+/*
+ * Softmax forward over the last axis, the exact forward of a Mesa softmax layer (Sec. 3.1: the
+ * forward pass is computed exactly; what the layer saves, compressed, is this output):
+ *   y_j = exp(s_j - max_k s_k) / sum_k exp(s_k - max_k s_k)   per row of cols elements.
+ */
+int mesa_ref_softmax_fwd(const void *s, int dt, int64_t total_rows, int64_t cols, double *y)
+{
+    for (int64_t r = 0; r < total_rows; ++r) {
+        double mx = -INFINITY, sum = 0.0;
+        for (int64_t j = 0; j < cols; ++j) {
+            double v = load_as_double(s, dt, r * cols + j);
+            if (v > mx) mx = v;
+        }
+        for (int64_t j = 0; j < cols; ++j) {
+            y[r * cols + j] = exp(load_as_double(s, dt, r * cols + j) - mx);
+            sum += y[r * cols + j];
+        }
+        for (int64_t j = 0; j < cols; ++j) y[r * cols + j] /= sum;
+    }
+    return 0;
+}
+
 /* ------------------------------------------------------------------------ */
 /* Eq. (2): layer gradients at x_hat                                         */
 /* ------------------------------------------------------------------------ */

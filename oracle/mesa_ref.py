@@ -199,6 +199,15 @@ def dequantize(q, layout, alpha, beta, dtype=np.float32):
     return out
 
 
+def softmax_fwd(s, total_rows, cols):
+    """Row softmax of s (binary16 or binary32 storage) in binary64."""
+    s = _c(s)
+    assert s.size == total_rows * cols
+    y = np.empty(s.size, np.float64)
+    lib().mesa_ref_softmax_fwd(_p(s), _dt(s), I64(total_rows), I64(cols), _p(y))
+    return y.reshape(s.shape)
+
+
 def softmax_bwd_q(yq, B, H, rows, cols, alpha, beta, dy):
     yq = _c(yq, np.int8)
     dy = _c(dy)

@@ -47,6 +47,23 @@ def relerr(a, b):
 
 # ----------------------------------------------------------------------------- softmax
 
+def test_softmax_forward_is_the_library_softmax_rows_sum_to_one_and_shifts_cancel():
+    rng = np.random.default_rng(17)
+    for dt in (np.float32, np.float16):
+        s = (rng.standard_normal((2, 3, 7, 19)) * 3).astype(dt)
+        y = R.softmax_fwd(s, 2 * 3 * 7, 19)
+        ref = torch.softmax(torch.from_numpy(s.astype(np.float64)), dim=-1).numpy()
+        assert np.allclose(y, ref, rtol=1e-13, atol=1e-300)
+        assert np.allclose(y.sum(-1), 1.0, rtol=1e-14)
+        assert np.all(y > 0)
+    s32 = (rng.integers(-256, 257, size=(5, 33)) / 64.0).astype(np.float32)   # a grid on which adding 4 is exact
+    shifted = s32 + np.float32(4.0)
+    assert np.array_equal(shifted.astype(np.float64) - 4.0, s32.astype(np.float64))
+    assert np.allclose(R.softmax_fwd(shifted, 5, 33), R.softmax_fwd(s32, 5, 33), rtol=1e-12)
+    one_hot = np.full((1, 8), -1e4, np.float32); one_hot[0, 3] = 0.0
+    assert np.array_equal(R.softmax_fwd(one_hot, 1, 8), np.eye(8)[3:4])
+
+
 def test_softmax_backward_against_finite_differences():
     rng = np.random.default_rng(0)
     B, H, rows, cols = 1, 2, 3, 6
