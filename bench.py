@@ -278,6 +278,49 @@ def gelu_layer_forward_leg(m, spec, steps):
             "note": "mesa_gelu_fwd_q; two_pass_ms: the framework's own exact GELU kernel followed by mesa_quantize_update_fused"}
 
 
+def softmax_layer_forward_leg(m, spec, steps):
+    """Outside the headline figure: a softmax layer's forward in one pass (mesa_softmax_fwd_q: the attention map and its
+    head-wise codes from one read of the logits), next to the two passes it replaces."""
+    B, H, r, c = spec.attn
+    n = B * H * r * c
+    lay = (B, H, r * c)
+    dev = "cuda"
+    g = torch.Generator(device=dev).manual_seed(spec.seed + 4)
+    ss = [torch.randn((B, H, r, c), device=dev, generator=g).to(spec.dtype) for _ in range(NSETS)]
+    ys = [torch.empty((B, H, r, c), dtype=spec.dtype, device=dev) for _ in range(NSETS)]
+    qs = [torch.empty(n, dtype=torch.int8, device=dev) for _ in range(NSETS)]
+    a = torch.full((H,), 0.8, device=dev)
+    b = torch.zeros(H, device=dev)
+    dtc = m.F16 if spec.dtype == torch.float16 else m.F32
+    if m.workspace_bytes(m.OP_SOFTMAX_FWD_Q, B * H * r, H, c, dtc) <= 16 or B * H * r >= 2 ** 31:
+        return None
+    ws = torch.empty(m.workspace_bytes(m.OP_SOFTMAX_FWD_Q, B * H * r, H, c, dtc), dtype=torch.uint8, device=dev)
+    ws2 = torch.empty(max(m.workspace_bytes(m.OP_UPDATE_RUNNING_PARAMS, *lay, dtc), 16), dtype=torch.uint8, device=dev)
+
+    def timed(fn):
+        for i in range(3):
+            fn(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            fn(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    one = timed(lambda i: m.mesa_softmax_fwd_q(ss[i % NSETS], B, H, r, c, a, b, 0.9, ys[i % NSETS], qs[i % NSETS], ws, m.ROUND_STOCHASTIC, 1, i))
+
+    def two_pass(i):
+        yy = torch.softmax(ss[i % NSETS], dim=-1)
+        m.mesa_quantize_update_fused(yy, lay, a, b, 0.9, qs[i % NSETS], ws2, m.ROUND_STOCHASTIC, 1, i)
+
+    two = timed(two_pass)
+    esz = 2 if spec.dtype == torch.float16 else 4
+    nbytes = (2 * esz + 1) * n
+    return {"ms": round(one, 4), "GBps": round(nbytes / (one * 1e-3) / 1e9, 1), "frac_hbm": round(nbytes / (one * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "bytes": nbytes, "two_pass_ms": round(two, 4),
+            "note": "mesa_softmax_fwd_q; two_pass_ms: the framework's own softmax kernel followed by mesa_quantize_update_fused"}
+
+
 def workload_name(spec, number, lin):
     b, h, r, c = spec.attn
     dw = f"whole path incl. dW {lin[0]}->{lin[1]}" if lin else "whole path, no Linear layer named"
@@ -404,6 +447,7 @@ def main():
                                         "once; parameters lag one step), the backward half unchanged"},
         "attention_matmul_bwd": attention_matmul_leg(m, spec, args.steps) if args.config != 5 else None,
         "gelu_layer_forward": gelu_layer_forward_leg(m, spec, args.steps),
+        "softmax_layer_forward": softmax_layer_forward_leg(m, spec, args.steps) if args.config != 5 else None,
         "per_call": {k: {"ms": round(v, 5), "GBps": round(bytes_per[k] / (v * 1e-3) / 1e9, 1),
                          "frac_hbm": round(bytes_per[k] / (v * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)} for k, v in per_kernel_ms.items()},
     }

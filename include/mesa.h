@@ -59,7 +59,8 @@ typedef struct { int64_t outer, groups, inner; } mesa_layout;
 typedef enum {
     MESA_OP_UPDATE_RUNNING_PARAMS = 0, /* d0,d1,d2 = outer, groups, inner */
     MESA_OP_LAYERNORM_BWD_Q = 1,       /* d0,d1,d2 = M, D, G */
-    MESA_OP_LINEAR_DW_Q = 2            /* d0,d1,d2 = M, K, N_out */
+    MESA_OP_LINEAR_DW_Q = 2,           /* d0,d1,d2 = M, K, N_out */
+    MESA_OP_SOFTMAX_FWD_Q = 3          /* d0,d1,d2 = B*H*rows, H, cols */
 } mesa_op;
 
 /*
@@ -149,6 +150,22 @@ mesa_status mesa_gelu_fwd_q(const void *x, mesa_dtype dt, mesa_layout L,
                             float *alpha, float *beta, float lambda, void *y, int8_t *q,
                             mesa_round mode, uint64_t seed, uint64_t offset,
                             void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * A Mesa softmax layer's forward in one pass over the logits s (B, H, rows, cols) (Sec. 3.1: the
+ * forward output is computed exactly; the output -- the attention map -- is what is saved, compressed):
+ *   y = softmax(s) over the last axis (max-subtracted, binary32 arithmetic), stored as dt;
+ *   q = codes of the STORED y, head-wise, with alpha, beta as they are on entry, Eq. (3)-(4);
+ *   alpha, beta then moved by the per-head extrema of the stored y, Eq. (6)-(7).
+ * I.e. mesa_quantize_update_fused applied to y with the layout {B, H, rows*cols}, without the pass
+ * that reads y back.  Per binary16 element 2 bytes in, 2 + 1 bytes out.
+ * s: [B*H*rows*cols] of dt (in).  y: same (out), not aliasing s.  q: int8 (out).
+ * alpha, beta: [H] (in/out).  ws: MESA_OP_SOFTMAX_FWD_Q bytes.  Limits: as for mesa_softmax_bwd_q.
+ */
+mesa_status mesa_softmax_fwd_q(const void *s, int64_t B, int64_t H, int64_t rows, int64_t cols,
+                               float *alpha, float *beta, float lambda, void *y, int8_t *q,
+                               mesa_round mode, uint64_t seed, uint64_t offset,
+                               void *ws, size_t ws_bytes, mesa_dtype dt, void *stream);
 
 /*
  * De-quantizer, Sec. 3.2 Eq. (5):  x_hat = (q + 128) * (alpha_g / 255) + beta_g, binary32 with the

@@ -80,6 +80,12 @@ __device__ __forceinline__ u32x2 pack_codes(const float w[8])
     return c;
 }
 
+// plain selection instructions: the data holds no NaN by contract, so no canonicalisation is wanted
+__device__ __forceinline__ float vmin(float a, float b) { float r; asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b)); return r; }
+__device__ __forceinline__ float vmax(float a, float b) { float r; asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b)); return r; }
+__device__ __forceinline__ uint32_t pkmin(uint32_t a, uint32_t b) { uint32_t r; asm("v_pk_min_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b)); return r; }
+__device__ __forceinline__ uint32_t pkmax(uint32_t a, uint32_t b) { uint32_t r; asm("v_pk_max_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b)); return r; }
+
 // Host side: combine the per-workgroup extrema part[nwg][2 * groups] (minima, then maxima) and move the running
 // estimates, Eq. (6)-(7); defined with the kernel in stream_kernels.hip.  variant: 0 plain, 1 symmetric range,
 // 2 fixed offset (beta_fixed).

@@ -77,12 +77,6 @@ __device__ __forceinline__ void fill_table(float2 *tab, const float *alpha, cons
 // ---------------------------------------------------------------------------------------------
 // min / max
 // ---------------------------------------------------------------------------------------------
-// plain selection instructions: the data holds no NaN by contract, so no canonicalisation is wanted
-__device__ __forceinline__ float vmin(float a, float b) { float r; asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b)); return r; }
-__device__ __forceinline__ float vmax(float a, float b) { float r; asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b)); return r; }
-__device__ __forceinline__ uint32_t pkmin(uint32_t a, uint32_t b) { uint32_t r; asm("v_pk_min_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b)); return r; }
-__device__ __forceinline__ uint32_t pkmax(uint32_t a, uint32_t b) { uint32_t r; asm("v_pk_max_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b)); return r; }
-
 template <typename T> struct MinMax;
 
 template <> struct MinMax<float> {
@@ -1131,6 +1125,7 @@ extern "C" MESA_EXPORT size_t mesa_workspace_bytes(mesa_op op, int64_t d0, int64
     case MESA_OP_UPDATE_RUNNING_PARAMS: return update_ws_bytes(d0, d1, d2);
     case MESA_OP_LAYERNORM_BWD_Q: return layernorm_ws_bytes(d0, d1);
     case MESA_OP_LINEAR_DW_Q: return linear_dw_ws_bytes(d0, d1, d2, dt);
+    case MESA_OP_SOFTMAX_FWD_Q: return softmax_fwd_ws_bytes(d0, d1, d2);
     }
     return 0;
 }

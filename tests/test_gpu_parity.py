@@ -466,6 +466,33 @@ def test_gelu_layer_forward_in_one_pass(M, layout, dtype):
         assert relerr(y.cpu().numpy(), ry) <= TOL[dtype]
 
 
+@pytest.mark.parametrize("dtype", [torch.float16, torch.float32])
+@pytest.mark.parametrize("B,H,rows,cols", [(3, 6, 197, 197), (5, 3, 49, 49), (2, 4, 64, 64), (1, 2, 33, 1000), (2, 3, 7, 19), (1, 1, 5, 8)])
+def test_softmax_layer_forward_in_one_pass(M, B, H, rows, cols, dtype):
+    """y = softmax(s) within tolerance of the oracle's binary64 softmax and with rows that sum to 1; the codes and
+    the moved estimates are exactly the oracle's single-pass forward applied to the y the kernel stored
+    (the decision is taken on the stored value on both sides); two steps, both rounding modes."""
+    gen = torch.Generator(device="cuda").manual_seed(B * 100 + cols)
+    lay = (B, H, rows * cols)
+    a = torch.full((H,), 0.9, device="cuda")
+    b = torch.full((H,), 0.01, device="cuda")
+    ws = torch.empty(max(M.workspace_bytes(M.OP_SOFTMAX_FWD_Q, B * H * rows, H, cols, M.F16), 16), dtype=torch.uint8, device="cuda")
+    sig = torch.linspace(0.5, 3.0, H, device="cuda").view(1, H, 1, 1)
+    for t, (mode, rmode) in enumerate(((M.ROUND_STOCHASTIC, R.ROUND_STOCHASTIC), (M.ROUND_NEAREST_EVEN, R.ROUND_NEAREST))):
+        s = (torch.randn((B, H, rows, cols), generator=gen, device="cuda") * sig * (1 + t)).to(dtype).contiguous()
+        y = torch.empty_like(s)
+        q = torch.empty(s.numel(), dtype=torch.int8, device="cuda")
+        ra, rb = a.cpu().numpy().copy(), b.cpu().numpy().copy()
+        M.mesa_softmax_fwd_q(s, B, H, rows, cols, a, b, 0.9, y, q, ws, mode, 31, 7)
+        yh = y.cpu().numpy()
+        ref = R.softmax_fwd(s.cpu().numpy(), B * H * rows, cols)
+        assert relerr(yh, ref) <= TOL[dtype]
+        assert np.abs(yh.astype(np.float64).sum(-1) - 1.0).max() <= (2e-3 if dtype == torch.float16 else 1e-5)
+        rq, ra2, rb2 = R.quantize_update_fused(yh, lay, ra, rb, 0.9, rmode, 31, 7)
+        assert np.array_equal(q.cpu().numpy(), rq.reshape(-1))
+        assert np.array_equal(canon(a.cpu().numpy()), canon(ra2)) and np.array_equal(canon(b.cpu().numpy()), canon(rb2))
+
+
 def test_empty_inputs_are_a_no_op(M):
     z = torch.empty(0, device="cuda")
     a = torch.ones(3, device="cuda")
