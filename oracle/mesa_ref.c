@@ -423,6 +423,33 @@ int mesa_ref_softmax_fwd(const void *s, int dt, int64_t total_rows, int64_t cols
     return 0;
 }
 
+/*
+ * LayerNorm forward over the last axis of an (M, D) matrix, the exact forward of a Mesa LayerNorm
+ * layer (Sec. 3.1); what the layer saves is its input x, compressed, plus the two statistics:
+ *   mean_m = sum_j x_mj / D,  var_m = sum_j (x_mj - mean_m)^2 / D,  rstd_m = 1 / sqrt(var_m + eps),
+ *   y_mj = (x_mj - mean_m) * rstd_m * gamma_j + bias_j.
+ */
+int mesa_ref_layernorm_fwd(const void *x, int dt, int64_t M, int64_t D, const void *gamma, const void *bias,
+                           double eps, double *y, double *mean, double *rstd)
+{
+    for (int64_t m = 0; m < M; ++m) {
+        double mu = 0.0, var = 0.0;
+        for (int64_t j = 0; j < D; ++j) mu += load_as_double(x, dt, m * D + j);
+        mu /= (double)D;
+        for (int64_t j = 0; j < D; ++j) {
+            double d = load_as_double(x, dt, m * D + j) - mu;
+            var += d * d;
+        }
+        var /= (double)D;
+        double rs = 1.0 / sqrt(var + eps);
+        mean[m] = mu;
+        rstd[m] = rs;
+        for (int64_t j = 0; j < D; ++j)
+            y[m * D + j] = (load_as_double(x, dt, m * D + j) - mu) * rs * load_as_double(gamma, dt, j) + load_as_double(bias, dt, j);
+    }
+    return 0;
+}
+
 /* ------------------------------------------------------------------------ */
 /* Eq. (2): layer gradients at x_hat                                         */
 /* ------------------------------------------------------------------------ */

@@ -243,6 +243,18 @@ def relu_bwd_q(xq, layout, alpha, beta, dy):
     return dx
 
 
+def layernorm_fwd(x, M, D, gamma, bias, eps):
+    """LayerNorm over the last axis in binary64: returns (y, mean, rstd)."""
+    x = _c(x)
+    gamma, bias = _c(gamma, x.dtype), _c(bias, x.dtype)
+    assert x.size == M * D and gamma.size == D and bias.size == D
+    y = np.empty((M, D), np.float64)
+    mean = np.empty(M, np.float64)
+    rstd = np.empty(M, np.float64)
+    lib().mesa_ref_layernorm_fwd(_p(x), _dt(x), I64(M), I64(D), _p(gamma), _p(bias), C.c_double(eps), _p(y), _p(mean), _p(rstd))
+    return y, mean, rstd
+
+
 def layernorm_bwd_q(xq, M, D, G, alpha, beta, mean, rstd, gamma, dy):
     xq = _c(xq, np.int8)
     dy = _c(dy)

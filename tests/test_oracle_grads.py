@@ -201,6 +201,23 @@ def ln_forward(x, gamma, eps):
     return (x - mu) / np.sqrt(var + eps) * gamma
 
 
+def test_layernorm_forward_is_the_library_layer_norm_and_normalises_rows():
+    rng = np.random.default_rng(23)
+    M_, D = 7, 48
+    for dt in (np.float32, np.float16):
+        x = (rng.standard_normal((M_, D)) * 2 + 0.5).astype(dt)
+        gamma = (1 + 0.1 * rng.standard_normal(D)).astype(dt)
+        bias = (0.1 * rng.standard_normal(D)).astype(dt)
+        y, mean, rstd = R.layernorm_fwd(x, M_, D, gamma, bias, 1e-5)
+        xt = torch.from_numpy(x.astype(np.float64))
+        ref = torch.nn.functional.layer_norm(xt, (D,), torch.from_numpy(gamma.astype(np.float64)), torch.from_numpy(bias.astype(np.float64)), 1e-5)
+        assert np.allclose(y, ref.numpy(), rtol=1e-12, atol=1e-13)
+        assert np.allclose(mean, x.astype(np.float64).mean(1), rtol=1e-14, atol=1e-15)
+        assert np.allclose(rstd, 1 / np.sqrt(x.astype(np.float64).var(1) + 1e-5), rtol=1e-13)
+    y1, _, _ = R.layernorm_fwd(x, M_, D, np.ones(D, dt), np.zeros(D, dt), 0.0)
+    assert np.allclose(y1.mean(1), 0.0, atol=1e-13) and np.allclose((y1 ** 2).mean(1), 1.0, rtol=1e-12)
+
+
 def test_layernorm_backward_against_finite_differences():
     rng = np.random.default_rng(4)
     M, D, G = 3, 8, 2
