@@ -321,6 +321,50 @@ def softmax_layer_forward_leg(m, spec, steps):
             "note": "mesa_softmax_fwd_q; two_pass_ms: the framework's own softmax kernel followed by mesa_quantize_update_fused"}
 
 
+def layernorm_layer_forward_leg(m, spec, steps):
+    """Outside the headline figure: a LayerNorm layer's forward in one pass (mesa_layernorm_fwd_q: output, row statistics
+    and the codes of the input from one read of the input), next to the two passes it replaces."""
+    M_, D, G = spec.tokens, spec.dim, spec.heads
+    dtc = m.F16 if spec.dtype == torch.float16 else m.F32
+    if m.workspace_bytes(m.OP_LAYERNORM_FWD_Q, M_, D, G, dtc) <= 16 or (D // G) % 8:
+        return None
+    n = M_ * D
+    lay = (M_, G, D // G)
+    dev = "cuda"
+    g = torch.Generator(device=dev).manual_seed(spec.seed + 5)
+    xs = [torch.randn((M_, D), device=dev, generator=g).to(spec.dtype) for _ in range(NSETS)]
+    ys = [torch.empty((M_, D), dtype=spec.dtype, device=dev) for _ in range(NSETS)]
+    qs = [torch.empty(n, dtype=torch.int8, device=dev) for _ in range(NSETS)]
+    mean = torch.empty(M_, device=dev)
+    rstd = torch.empty(M_, device=dev)
+    gamma = torch.ones(D, device=dev).to(spec.dtype)
+    bias = torch.zeros(D, device=dev).to(spec.dtype)
+    a = torch.full((G,), 8.0, device=dev)
+    b = torch.full((G,), -4.0, device=dev)
+    ws = torch.empty(m.workspace_bytes(m.OP_LAYERNORM_FWD_Q, M_, D, G, dtc), dtype=torch.uint8, device=dev)
+    ws2 = torch.empty(max(m.workspace_bytes(m.OP_UPDATE_RUNNING_PARAMS, *lay, dtc), 16), dtype=torch.uint8, device=dev)
+
+    def timed(fn):
+        for i in range(3):
+            fn(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            fn(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    one = timed(lambda i: m.mesa_layernorm_fwd_q(xs[i % NSETS], M_, D, G, gamma, bias, 1e-5, a, b, 0.9, ys[i % NSETS], mean, rstd,
+                                                 qs[i % NSETS], ws, m.ROUND_STOCHASTIC, 1, i))
+    two = timed(lambda i: (torch.nn.functional.layer_norm(xs[i % NSETS], (D,), gamma, bias, 1e-5),
+                           m.mesa_quantize_update_fused(xs[i % NSETS], lay, a, b, 0.9, qs[i % NSETS], ws2, m.ROUND_STOCHASTIC, 1, i)))
+    esz = 2 if spec.dtype == torch.float16 else 4
+    nbytes = (2 * esz + 1) * n + 8 * M_
+    return {"ms": round(one, 4), "GBps": round(nbytes / (one * 1e-3) / 1e9, 1), "frac_hbm": round(nbytes / (one * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "bytes": nbytes, "two_pass_ms": round(two, 4),
+            "note": "mesa_layernorm_fwd_q; two_pass_ms: the framework's own layer_norm kernel followed by mesa_quantize_update_fused"}
+
+
 def workload_name(spec, number, lin):
     b, h, r, c = spec.attn
     dw = f"whole path incl. dW {lin[0]}->{lin[1]}" if lin else "whole path, no Linear layer named"
@@ -448,6 +492,7 @@ def main():
         "attention_matmul_bwd": attention_matmul_leg(m, spec, args.steps) if args.config != 5 else None,
         "gelu_layer_forward": gelu_layer_forward_leg(m, spec, args.steps),
         "softmax_layer_forward": softmax_layer_forward_leg(m, spec, args.steps) if args.config != 5 else None,
+        "layernorm_layer_forward": layernorm_layer_forward_leg(m, spec, args.steps),
         "per_call": {k: {"ms": round(v, 5), "GBps": round(bytes_per[k] / (v * 1e-3) / 1e9, 1),
                          "frac_hbm": round(bytes_per[k] / (v * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)} for k, v in per_kernel_ms.items()},
     }

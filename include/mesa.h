@@ -60,7 +60,8 @@ typedef enum {
     MESA_OP_UPDATE_RUNNING_PARAMS = 0, /* d0,d1,d2 = outer, groups, inner */
     MESA_OP_LAYERNORM_BWD_Q = 1,       /* d0,d1,d2 = M, D, G */
     MESA_OP_LINEAR_DW_Q = 2,           /* d0,d1,d2 = M, K, N_out */
-    MESA_OP_SOFTMAX_FWD_Q = 3          /* d0,d1,d2 = B*H*rows, H, cols */
+    MESA_OP_SOFTMAX_FWD_Q = 3,         /* d0,d1,d2 = B*H*rows, H, cols */
+    MESA_OP_LAYERNORM_FWD_Q = 4        /* d0,d1,d2 = M, D, G */
 } mesa_op;
 
 /*
@@ -166,6 +167,23 @@ mesa_status mesa_softmax_fwd_q(const void *s, int64_t B, int64_t H, int64_t rows
                                float *alpha, float *beta, float lambda, void *y, int8_t *q,
                                mesa_round mode, uint64_t seed, uint64_t offset,
                                void *ws, size_t ws_bytes, mesa_dtype dt, void *stream);
+
+/*
+ * A Mesa LayerNorm layer's forward in one pass over x (M, D) (Sec. 3.1; the saved tensor is the input):
+ *   mean_m = sum_j x_mj / D,  rstd_m = 1/sqrt(sum_j (x_mj - mean_m)^2 / D + eps)     (binary32, out: what
+ *   y = (x - mean)*rstd*gamma + bias, stored as dt;                                   mesa_layernorm_bwd_q takes)
+ *   q = codes of x in G channel groups of D/G columns with alpha, beta as they are on entry, Eq. (3)-(4);
+ *   alpha, beta then moved by this batch's per-group extrema of x, Eq. (6)-(7)  (as mesa_quantize_update_fused).
+ * x: (M, D) of dt (in).  gamma, bias: [D] of dt.  y: (M, D) of dt (out), not aliasing x.  mean, rstd: [M] binary32
+ * (out).  q: int8 (out).  alpha, beta: [G] (in/out).  ws: MESA_OP_LAYERNORM_FWD_Q bytes.
+ * Limits: D % 8 == 0, (D/G) % 8 == 0, D <= 1024, G <= 1024, else MESA_ERR_UNSUPPORTED.
+ */
+mesa_status mesa_layernorm_fwd_q(const void *x, int64_t M, int64_t D, int64_t G,
+                                 const void *gamma, const void *bias, float eps,
+                                 float *alpha, float *beta, float lambda,
+                                 void *y, float *mean, float *rstd, int8_t *q,
+                                 mesa_round mode, uint64_t seed, uint64_t offset,
+                                 void *ws, size_t ws_bytes, mesa_dtype dt, void *stream);
 
 /*
  * De-quantizer, Sec. 3.2 Eq. (5):  x_hat = (q + 128) * (alpha_g / 255) + beta_g, binary32 with the

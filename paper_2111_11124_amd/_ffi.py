@@ -17,10 +17,10 @@ _LIB_PATH = Path(__file__).resolve().parent / "libmesa.so"
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = range(5)
 F32, F16 = 0, 1
 ROUND_NEAREST_EVEN, ROUND_STOCHASTIC = 0, 1
-OP_UPDATE_RUNNING_PARAMS, OP_LAYERNORM_BWD_Q, OP_LINEAR_DW_Q, OP_SOFTMAX_FWD_Q = 0, 1, 2, 3
+OP_UPDATE_RUNNING_PARAMS, OP_LAYERNORM_BWD_Q, OP_LINEAR_DW_Q, OP_SOFTMAX_FWD_Q, OP_LAYERNORM_FWD_Q = 0, 1, 2, 3, 4
 
 EXPORTS = [
-    "mesa_update_running_params", "mesa_update_running_params_sym", "mesa_update_running_params_fixed_beta", "mesa_quantize_headwise", "mesa_quantize_update_fused", "mesa_gelu_fwd_q", "mesa_softmax_fwd_q", "mesa_dequantize", "mesa_softmax_bwd_q",
+    "mesa_update_running_params", "mesa_update_running_params_sym", "mesa_update_running_params_fixed_beta", "mesa_quantize_headwise", "mesa_quantize_update_fused", "mesa_gelu_fwd_q", "mesa_softmax_fwd_q", "mesa_layernorm_fwd_q", "mesa_dequantize", "mesa_softmax_bwd_q",
     "mesa_gelu_bwd_q", "mesa_relu_bwd_q", "mesa_layernorm_bwd_q", "mesa_linear_dw_q", "mesa_attn_av_bwd_q", "mesa_attn_qk_bwd_q",
     "mesa_workspace_bytes",
     "mesa_status_string", "mesa_version", "mesa_stream_copy", "mesa_event_create", "mesa_event_record",
@@ -56,6 +56,8 @@ def lib() -> C.CDLL:
         L.mesa_quantize_update_fused.argtypes = [_vp, _int, Layout, _vp, _vp, _f32, _vp, _int, _u64, _u64, _vp, _sz, _vp]
         L.mesa_gelu_fwd_q.argtypes = [_vp, _int, Layout, _vp, _vp, _f32, _vp, _vp, _int, _u64, _u64, _vp, _sz, _vp]
         L.mesa_softmax_fwd_q.argtypes = [_vp, _i64, _i64, _i64, _i64, _vp, _vp, _f32, _vp, _vp, _int, _u64, _u64, _vp, _sz, _int, _vp]
+        L.mesa_layernorm_fwd_q.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _vp, _vp, _f32, _vp, _vp, _vp, _vp, _int, _u64, _u64,
+                                           _vp, _sz, _int, _vp]
         L.mesa_dequantize.argtypes = [_vp, Layout, _vp, _vp, _vp, _int, _vp]
         L.mesa_softmax_bwd_q.argtypes = [_vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _int, _vp]
         L.mesa_gelu_bwd_q.argtypes = [_vp, Layout, _vp, _vp, _vp, _vp, _int, _vp]
@@ -168,6 +170,14 @@ def mesa_softmax_fwd_q(s, B, H, rows, cols, alpha, beta, lam, y, q, ws, mode=ROU
     p, n = _ws_args(ws)
     _check(lib().mesa_softmax_fwd_q(_ptr(s), B, H, rows, cols, _ptr(alpha), _ptr(beta), float(lam), _ptr(y), _ptr(q), int(mode),
                                     int(seed), int(offset), p, n, _dt(s), _stream()), "mesa_softmax_fwd_q")
+
+
+def mesa_layernorm_fwd_q(x, M, D, G, gamma, bias, eps, alpha, beta, lam, y, mean, rstd, q, ws, mode=ROUND_STOCHASTIC, seed=0, offset=0):
+    assert y.dtype == x.dtype == gamma.dtype == bias.dtype
+    p, n = _ws_args(ws)
+    _check(lib().mesa_layernorm_fwd_q(_ptr(x), M, D, G, _ptr(gamma), _ptr(bias), float(eps), _ptr(alpha), _ptr(beta), float(lam),
+                                      _ptr(y), _ptr(mean), _ptr(rstd), _ptr(q), int(mode), int(seed), int(offset), p, n, _dt(x),
+                                      _stream()), "mesa_layernorm_fwd_q")
 
 
 def mesa_dequantize(q, layout, alpha, beta, x_hat):

@@ -15,6 +15,7 @@ size_t update_ws_bytes(int64_t outer, int64_t groups, int64_t inner);
 size_t layernorm_ws_bytes(int64_t M, int64_t D);
 size_t linear_dw_ws_bytes(int64_t M, int64_t K, int64_t N, mesa_dtype dt);
 size_t softmax_fwd_ws_bytes(int64_t total_rows, int64_t H, int64_t cols);
+size_t layernorm_fwd_ws_bytes(int64_t M, int64_t D, int64_t G);
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }

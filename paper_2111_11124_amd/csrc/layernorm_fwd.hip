@@ -1,0 +1,223 @@
+// layernorm_fwd.hip -- a Mesa LayerNorm layer's forward in one pass over x (Sec. 3.1: the forward output is
+// computed from the exact input; the input is what the layer saves, compressed -- Sec. 3.2 Eq. 3-4, 6-7 --
+// together with the row statistics the backward needs):
+//   per row  mean = sum x / D,  rstd = 1 / sqrt(sum (x - mean)^2 / D + eps),  y = (x - mean) * rstd * gamma + bias;
+//   codes of x in G channel groups with the running estimates as they are on entry; then the estimates
+//   moved by this batch's per-group extrema (the single-pass forward).
+//
+// A row lives in the registers of a group of LPR lanes (VPL vectors of 8 columns per lane), as in the
+// backward kernel; the two row sums are lane-group reductions.  A lane always holds the same columns, hence
+// the same channel groups: its extrema accumulate in registers over all its rows and reach LDS once.
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+
+#include "api_util.hpp"
+#include "common.hpp"
+#include "quantize.hpp"
+
+namespace mesa {
+
+constexpr int kLfMaxGroups = 1024;
+constexpr int kLfRows = 2;          // rows per lane group in flight
+
+template <typename T, int LPR, int VPL, bool SR>
+__global__ __launch_bounds__(kThreads, 3) void k_layernorm_fwd(const void *__restrict__ x, void *__restrict__ y,
+                                                               int8_t *__restrict__ q, float *__restrict__ mean,
+                                                               float *__restrict__ rstd, const void *__restrict__ gamma,
+                                                               const void *__restrict__ bias, float eps, int64_t M, uint32_t D,
+                                                               FastDiv div_vpg, uint32_t groups, float inv_D,
+                                                               const float *__restrict__ alpha, const float *__restrict__ beta,
+                                                               uint64_t seed, uint64_t offset, float *__restrict__ part)
+{
+    constexpr int RPW = 64 / LPR;                   // rows per wave and pass
+    constexpr int kWaves = kThreads / 64;
+    constexpr int kBlockRows = kWaves * kLfRows * RPW;
+    __shared__ int lmn[kLfMaxGroups], lmx[kLfMaxGroups];
+    for (uint32_t g = threadIdx.x; g < groups; g += kThreads) {
+        lmn[g] = order_key(__builtin_inff());
+        lmx[g] = order_key(-__builtin_inff());
+    }
+    __syncthreads();
+
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const uint32_t sub = lane / LPR, l = lane % LPR;
+    const uint32_t vpr = D / kVec;
+
+    uint32_t col[VPL], grp[VPL];
+    bool act[VPL];
+    float gam[VPL][8], bia[VPL][8], mn[VPL], mx[VPL];
+    float2 prm[VPL];                                // (255 / alpha, beta) of the vector's channel group
+#pragma unroll
+    for (int k = 0; k < VPL; ++k) {
+        const uint32_t cv = k * LPR + l;
+        act[k] = cv < vpr;
+        col[k] = cv * kVec;
+        grp[k] = 0;
+        mn[k] = __builtin_inff();
+        mx[k] = -__builtin_inff();
+        prm[k] = make_float2(0.0f, 0.0f);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { gam[k][j] = 0.0f; bia[k][j] = 0.0f; }
+        if (act[k]) {
+            Store<T>::unpack(Store<T>::load(gamma, col[k]), gam[k]);
+            Store<T>::unpack(Store<T>::load(bias, col[k]), bia[k]);
+            grp[k] = fastdiv(cv, div_vpg);
+            const float a = alpha[grp[k]];
+            prm[k] = make_float2(a > 0.0f ? 255.0f / a : 0.0f, beta[grp[k]]);
+        }
+    }
+
+    const int64_t stride = int64_t(gridDim.x) * kBlockRows;
+    for (int64_t base = int64_t(blockIdx.x) * kBlockRows; base < M; base += stride) {
+        typename Store<T>::raw_t raw[kLfRows][VPL];
+        const typename Store<T>::raw_t zero = Store<T>::pack((const float[8]){0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f});
+#pragma unroll
+        for (int p = 0; p < kLfRows; ++p) {
+            const int64_t row = base + int64_t((p * kWaves + wave) * RPW + sub);
+#pragma unroll
+            for (int k = 0; k < VPL; ++k) {
+                raw[p][k] = zero;                   // lanes without a row or a vector work on zeros; only loads and stores are predicated
+                if (row < M && act[k]) raw[p][k] = Nt<T>::load(x, row * D + col[k]);
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < kLfRows; ++p) {
+            const int64_t row = base + int64_t((p * kWaves + wave) * RPW + sub);
+            const bool ok = row < M;
+            float f[VPL][8];
+            float s1 = 0.0f;
+#pragma unroll
+            for (int k = 0; k < VPL; ++k) {
+                Store<T>::unpack(raw[p][k], f[k]);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) s1 += f[k][j];
+            }
+            const float mu = lanes_sum_dpp<LPR>(s1) * inv_D;
+            float s2 = 0.0f;
+#pragma unroll
+            for (int k = 0; k < VPL; ++k)
+                if (act[k]) {                       // columns past the row's end would add mu^2 each
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const float d = f[k][j] - mu;
+                        s2 = fmaf(d, d, s2);
+                    }
+                }
+            const float var = lanes_sum_dpp<LPR>(s2) * inv_D;
+            const float rs = 1.0f / sqrtf(var + eps);
+            if (ok && l == 0) {
+                mean[row] = mu;
+                rstd[row] = rs;
+            }
+#pragma unroll
+            for (int k = 0; k < VPL; ++k) {
+                if (ok && act[k]) {
+                    const int64_t e = row * D + col[k];
+                    float o[8], w[8], bits[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) o[j] = fmaf((f[k][j] - mu) * rs, gam[k][j], bia[k][j]);
+                    Nt<T>::store(y, e, Store<T>::pack(o));
+                    if (SR) sr_bits(seed, offset + uint64_t(e >> 3), bits);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        w[j] = quantize_one<SR>(f[k][j], prm[k].x, prm[k].y, SR ? bits[j] : 0.0f);
+                        mn[k] = vmin(mn[k], f[k][j]);
+                        mx[k] = vmax(mx[k], f[k][j]);
+                    }
+                    nt_store<u32x2>(q + e, pack_codes(w));
+                }
+            }
+        }
+    }
+
+    // this thread's extrema to its groups' slots, the workgroup's to its row of the partials
+#pragma unroll
+    for (int k = 0; k < VPL; ++k)
+        if (act[k] && mn[k] <= mx[k]) {
+            atomicMin(&lmn[grp[k]], order_key(mn[k]));
+            atomicMax(&lmx[grp[k]], order_key(mx[k]));
+        }
+    __syncthreads();
+    float *out = part + int64_t(blockIdx.x) * 2 * groups;
+    for (uint32_t g = threadIdx.x; g < groups; g += kThreads) {
+        out[g] = order_val(lmn[g]);
+        out[groups + g] = order_val(lmx[g]);
+    }
+}
+
+struct LfPlan {
+    bool ok;
+    int lpr, vpl, grid;
+};
+
+static LfPlan lf_plan(int64_t M, int64_t D)
+{
+    LfPlan p{};
+    const int64_t vpr = D / kVec;
+    p.ok = D % kVec == 0 && vpr >= 1 && vpr <= 128;
+    if (!p.ok) return p;
+    p.vpl = vpr > 64 ? 2 : 1;
+    int lpr = 8;
+    while (int64_t(lpr) * p.vpl < vpr) lpr *= 2;
+    p.lpr = lpr;
+    const int64_t block_rows = int64_t(kThreads / 64) * kLfRows * (64 / lpr);
+    const int64_t wgs = ceil_div(M, block_rows);
+    const int64_t resident = 256 * 3;
+    p.grid = int(wgs < resident ? wgs : resident);
+    return p;
+}
+
+size_t layernorm_fwd_ws_bytes(int64_t M, int64_t D, int64_t G)
+{
+    if (M <= 0 || D <= 0 || G <= 0 || G > kLfMaxGroups) return 16;
+    const LfPlan p = lf_plan(M, D);
+    if (!p.ok) return 16;
+    return size_t(p.grid) * 2 * size_t(G) * sizeof(float) + 16;
+}
+
+}  // namespace mesa
+
+using namespace mesa;
+
+extern "C" MESA_EXPORT mesa_status mesa_layernorm_fwd_q(const void *x, int64_t M, int64_t D, int64_t G, const void *gamma,
+                                                        const void *bias, float eps, float *alpha, float *beta, float lambda, void *y,
+                                                        float *mean, float *rstd, int8_t *q, mesa_round mode, uint64_t seed,
+                                                        uint64_t offset, void *ws, size_t ws_bytes, mesa_dtype dt, void *stream)
+{
+    if (!valid_dtype(dt) || M < 0 || D < 0 || G < 0) return MESA_ERR_INVALID_ARG;
+    if (mode != MESA_ROUND_NEAREST_EVEN && mode != MESA_ROUND_STOCHASTIC) return MESA_ERR_INVALID_ARG;
+    if (!(lambda >= 0.0f && lambda <= 1.0f) || !(eps >= 0.0f)) return MESA_ERR_INVALID_ARG;
+    if (M == 0 || D == 0) return MESA_OK;
+    if (G == 0 || D % G != 0) return MESA_ERR_INVALID_ARG;
+    if (!x || !y || !q || !mean || !rstd || !gamma || !bias || !alpha || !beta || !aligned16(x) || !aligned16(y) || !aligned16(q) ||
+        !aligned16(gamma) || !aligned16(bias) || !aligned4(mean) || !aligned4(rstd) || !aligned4(alpha) || !aligned4(beta) || y == x)
+        return MESA_ERR_INVALID_ARG;
+    const LfPlan p = lf_plan(M, D);
+    if (!p.ok || (D / G) % kVec != 0 || G > kLfMaxGroups || M >= (int64_t(1) << 40)) return MESA_ERR_UNSUPPORTED;
+    if (!ws || !aligned16(ws) || ws_bytes < layernorm_fwd_ws_bytes(M, D, G)) return MESA_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float *part = static_cast<float *>(ws);
+    FastDiv dv = make_fastdiv(uint32_t((D / G) / kVec));
+    const float inv_D = 1.0f / float(D);
+    const bool sr = mode == MESA_ROUND_STOCHASTIC;
+#define MESA_LAUNCH_LF(T, LPR_, VPL_, SR_) \
+    hipLaunchKernelGGL((k_layernorm_fwd<T, LPR_, VPL_, SR_>), dim3(p.grid), dim3(kThreads), 0, s, x, y, q, mean, rstd, gamma, bias, eps, M, \
+                       uint32_t(D), dv, uint32_t(G), inv_D, alpha, beta, seed, offset, part)
+#define MESA_LAUNCH_LF_S(T, LPR_, VPL_) \
+    do { if (sr) MESA_LAUNCH_LF(T, LPR_, VPL_, true); else MESA_LAUNCH_LF(T, LPR_, VPL_, false); } while (0)
+#define MESA_LAUNCH_LF_T(T) \
+    do { \
+        if (p.vpl == 2) MESA_LAUNCH_LF_S(T, 64, 2); \
+        else if (p.lpr == 8) MESA_LAUNCH_LF_S(T, 8, 1); \
+        else if (p.lpr == 16) MESA_LAUNCH_LF_S(T, 16, 1); \
+        else if (p.lpr == 32) MESA_LAUNCH_LF_S(T, 32, 1); \
+        else MESA_LAUNCH_LF_S(T, 64, 1); \
+    } while (0)
+    if (dt == MESA_F16) MESA_LAUNCH_LF_T(_Float16); else MESA_LAUNCH_LF_T(float);
+#undef MESA_LAUNCH_LF_T
+#undef MESA_LAUNCH_LF_S
+#undef MESA_LAUNCH_LF
+    launch_ema_finalize(part, p.grid, uint32_t(G), alpha, beta, lambda, 0, 0, 0.0f, s);
+    return launch_status();
+}

@@ -1126,6 +1126,7 @@ extern "C" MESA_EXPORT size_t mesa_workspace_bytes(mesa_op op, int64_t d0, int64
     case MESA_OP_LAYERNORM_BWD_Q: return layernorm_ws_bytes(d0, d1);
     case MESA_OP_LINEAR_DW_Q: return linear_dw_ws_bytes(d0, d1, d2, dt);
     case MESA_OP_SOFTMAX_FWD_Q: return softmax_fwd_ws_bytes(d0, d1, d2);
+    case MESA_OP_LAYERNORM_FWD_Q: return layernorm_fwd_ws_bytes(d0, d1, d2);
     }
     return 0;
 }

@@ -74,6 +74,12 @@ def test_argument_errors_are_reported_before_any_launch(M):
     assert L.mesa_softmax_fwd_q(P, 2, 3, 19, 5, P, P, 0.9, P2, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_UNSUPPORTED  # rows shorter than a vector
     assert L.mesa_softmax_fwd_q(P, 2, 3, 19, 19, P, P, 1.5, P2, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_INVALID_ARG  # lambda
     assert M.workspace_bytes(M.OP_SOFTMAX_FWD_Q, 128 * 6 * 197, 6, 197, M.F16) >= 768 * 2 * 6 * 4
+    F = C.c_float
+    assert L.mesa_layernorm_fwd_q(P, 100, 384, 6, P, P, F(1e-5), P, P, F(0.9), P, P, P, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_INVALID_ARG  # y aliases x
+    assert L.mesa_layernorm_fwd_q(P, 100, 384, 6, P, P, F(1e-5), P, P, F(0.9), P2, P, P, P, 0, 0, 0, P, 8, M.F16, None) == M.ERR_WORKSPACE
+    assert L.mesa_layernorm_fwd_q(P, 100, 2048, 8, P, P, F(1e-5), P, P, F(0.9), P2, P, P, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_UNSUPPORTED  # rows too long
+    assert L.mesa_layernorm_fwd_q(P, 100, 384, 5, P, P, F(1e-5), P, P, F(0.9), P2, P, P, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_INVALID_ARG  # D % G
+    assert L.mesa_layernorm_fwd_q(P, 100, 384, 6, P, P, F(-1.0), P, P, F(0.9), P2, P, P, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_INVALID_ARG  # eps
     assert L.mesa_dequantize(P, lay, P, None, P, M.F16, None) == M.ERR_INVALID_ARG
     assert L.mesa_gelu_bwd_q(P, lay, P, P, P + 8, P, M.F16, None) == M.ERR_INVALID_ARG
     assert L.mesa_softmax_bwd_q(P, 2, 3, 5, 4, P, P, P, P, M.F16, None) == M.ERR_UNSUPPORTED              # cols < 8

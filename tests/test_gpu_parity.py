@@ -493,6 +493,34 @@ def test_softmax_layer_forward_in_one_pass(M, B, H, rows, cols, dtype):
         assert np.array_equal(canon(a.cpu().numpy()), canon(ra2)) and np.array_equal(canon(b.cpu().numpy()), canon(rb2))
 
 
+@pytest.mark.parametrize("dtype", [torch.float16, torch.float32])
+@pytest.mark.parametrize("Mr,D,G", [(1000, 384, 6), (77, 768, 12), (50, 1024, 4), (33, 64, 2), (19, 8, 1), (300, 96, 3), (5, 520, 1)])
+def test_layernorm_layer_forward_in_one_pass(M, Mr, D, G, dtype):
+    """y, mean and rstd within tolerance of the oracle's binary64 LayerNorm; codes of x and the moved estimates bit
+    for bit (two steps, both rounding modes); the statistics feed the backward call as they are."""
+    gen = torch.Generator(device="cuda").manual_seed(Mr * 7 + D)
+    lay = (Mr, G, D // G)
+    a = torch.full((G,), 9.0, device="cuda")
+    b = torch.full((G,), -4.5, device="cuda")
+    ra, rb = np.full(G, 9.0, np.float32), np.full(G, -4.5, np.float32)
+    gamma = (1 + 0.1 * torch.randn(D, generator=gen, device="cuda")).to(dtype)
+    bias = (0.1 * torch.randn(D, generator=gen, device="cuda")).to(dtype)
+    ws = torch.empty(max(M.workspace_bytes(M.OP_LAYERNORM_FWD_Q, Mr, D, G, M.F16), 16), dtype=torch.uint8, device="cuda")
+    for t, (mode, rmode) in enumerate(((M.ROUND_STOCHASTIC, R.ROUND_STOCHASTIC), (M.ROUND_NEAREST_EVEN, R.ROUND_NEAREST))):
+        x = ((torch.randn((Mr, D), generator=gen, device="cuda") * (1.0 + t) + 0.3)).to(dtype).contiguous()
+        y = torch.empty_like(x)
+        mean = torch.empty(Mr, device="cuda")
+        rstd = torch.empty(Mr, device="cuda")
+        q = torch.empty(x.numel(), dtype=torch.int8, device="cuda")
+        M.mesa_layernorm_fwd_q(x, Mr, D, G, gamma, bias, 1e-5, a, b, 0.9, y, mean, rstd, q, ws, mode, 13, 5)
+        ry, rmean, rrstd = R.layernorm_fwd(x.cpu().numpy(), Mr, D, gamma.cpu().numpy(), bias.cpu().numpy(), 1e-5)
+        assert relerr(y.cpu().numpy(), ry) <= TOL[dtype]
+        assert relerr(mean.cpu().numpy(), rmean) <= 1e-5 and relerr(rstd.cpu().numpy(), rrstd) <= 1e-5
+        rq, ra, rb = R.quantize_update_fused(x.cpu().numpy(), lay, ra, rb, 0.9, rmode, 13, 5)
+        assert np.array_equal(q.cpu().numpy(), rq.reshape(-1))
+        assert np.array_equal(canon(a.cpu().numpy()), canon(ra)) and np.array_equal(canon(b.cpu().numpy()), canon(rb))
+
+
 def test_empty_inputs_are_a_no_op(M):
     z = torch.empty(0, device="cuda")
     a = torch.ones(3, device="cuda")
