@@ -17,6 +17,7 @@ Prints ONE JSON line (the fields are described in README.md).
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -37,6 +38,17 @@ MFMA_F16_PEAK_TFLOPS = 2500.0
 NSETS = 3
 
 
+def elem_bytes(dtype):
+    return 4 if dtype == torch.float32 else 2
+
+
+def dtype_code(m, dtype):
+    return {torch.float32: m.F32, torch.float16: m.F16, torch.bfloat16: m.BF16}[dtype]
+
+
+DTYPE_NAME = {torch.float32: "f32", torch.float16: "f16", torch.bfloat16: "bf16"}
+
+
 def linear_of(spec, which=0):
     """(K, N_out) of the Linear layer the step takes dW of, or None when the configuration names none."""
     return spec.linears[which] if spec.linears else None
@@ -44,7 +56,7 @@ def linear_of(spec, which=0):
 
 def algorithmic_bytes(spec, which_linear=0):
     """Bytes each call must move at the very least (per-element figures x elements)."""
-    T = 2 if spec.dtype == torch.float16 else 4
+    T = elem_bytes(spec.dtype)
     n_attn = spec.attn[0] * spec.attn[1] * spec.attn[2] * spec.attn[3]
     n_gelu = spec.tokens * spec.mlp
     n_ln = spec.tokens * spec.dim
@@ -108,7 +120,7 @@ class Path:
         ws_n = max(max(m.workspace_bytes(m.OP_UPDATE_RUNNING_PARAMS, *s0.layout[k]) for k in s0.layout),
                    m.workspace_bytes(m.OP_LAYERNORM_BWD_Q, spec.tokens, spec.dim, H),
                    m.workspace_bytes(m.OP_LINEAR_DW_Q, spec.tokens, self.K, self.N,
-                                     m.F16 if spec.dtype == torch.float16 else m.F32) if self.lin else 16)
+                                     dtype_code(m, spec.dtype)) if self.lin else 16)
         self.ws = torch.empty(ws_n, dtype=torch.uint8, device="cuda")
         self.step_no = 0
         self.first = True
@@ -255,7 +267,7 @@ def gelu_layer_forward_leg(m, spec, steps):
     qs = [torch.empty(n, dtype=torch.int8, device=dev) for _ in range(NSETS)]
     a = torch.full((lay[1],), 8.0, device=dev)
     b = torch.full((lay[1],), -4.0, device=dev)
-    ws = torch.empty(max(m.workspace_bytes(m.OP_UPDATE_RUNNING_PARAMS, *lay, m.F16 if spec.dtype == torch.float16 else m.F32), 16),
+    ws = torch.empty(max(m.workspace_bytes(m.OP_UPDATE_RUNNING_PARAMS, *lay, dtype_code(m, spec.dtype)), 16),
                      dtype=torch.uint8, device=dev)
 
     def timed(fn):
@@ -271,7 +283,7 @@ def gelu_layer_forward_leg(m, spec, steps):
     one = timed(lambda i: m.mesa_gelu_fwd_q(xs[i % NSETS], lay, a, b, 0.9, ys[i % NSETS], qs[i % NSETS], ws, m.ROUND_STOCHASTIC, 1, i))
     two = timed(lambda i: (torch.nn.functional.gelu(xs[i % NSETS]),
                            m.mesa_quantize_update_fused(xs[i % NSETS], lay, a, b, 0.9, qs[i % NSETS], ws, m.ROUND_STOCHASTIC, 1, i)))
-    esz = 2 if spec.dtype == torch.float16 else 4
+    esz = elem_bytes(spec.dtype)
     nbytes = (2 * esz + 1) * n
     return {"ms": round(one, 4), "GBps": round(nbytes / (one * 1e-3) / 1e9, 1), "frac_hbm": round(nbytes / (one * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "bytes": nbytes, "two_pass_ms": round(two, 4),
@@ -291,7 +303,7 @@ def softmax_layer_forward_leg(m, spec, steps):
     qs = [torch.empty(n, dtype=torch.int8, device=dev) for _ in range(NSETS)]
     a = torch.full((H,), 0.8, device=dev)
     b = torch.zeros(H, device=dev)
-    dtc = m.F16 if spec.dtype == torch.float16 else m.F32
+    dtc = dtype_code(m, spec.dtype)
     if m.workspace_bytes(m.OP_SOFTMAX_FWD_Q, B * H * r, H, c, dtc) <= 16 or B * H * r >= 2 ** 31:
         return None
     ws = torch.empty(m.workspace_bytes(m.OP_SOFTMAX_FWD_Q, B * H * r, H, c, dtc), dtype=torch.uint8, device=dev)
@@ -314,7 +326,7 @@ def softmax_layer_forward_leg(m, spec, steps):
         m.mesa_quantize_update_fused(yy, lay, a, b, 0.9, qs[i % NSETS], ws2, m.ROUND_STOCHASTIC, 1, i)
 
     two = timed(two_pass)
-    esz = 2 if spec.dtype == torch.float16 else 4
+    esz = elem_bytes(spec.dtype)
     nbytes = (2 * esz + 1) * n
     return {"ms": round(one, 4), "GBps": round(nbytes / (one * 1e-3) / 1e9, 1), "frac_hbm": round(nbytes / (one * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "bytes": nbytes, "two_pass_ms": round(two, 4),
@@ -325,7 +337,7 @@ def layernorm_layer_forward_leg(m, spec, steps):
     """Outside the headline figure: a LayerNorm layer's forward in one pass (mesa_layernorm_fwd_q: output, row statistics
     and the codes of the input from one read of the input), next to the two passes it replaces."""
     M_, D, G = spec.tokens, spec.dim, spec.heads
-    dtc = m.F16 if spec.dtype == torch.float16 else m.F32
+    dtc = dtype_code(m, spec.dtype)
     if m.workspace_bytes(m.OP_LAYERNORM_FWD_Q, M_, D, G, dtc) <= 16 or (D // G) % 8:
         return None
     n = M_ * D
@@ -358,7 +370,7 @@ def layernorm_layer_forward_leg(m, spec, steps):
                                                  qs[i % NSETS], ws, m.ROUND_STOCHASTIC, 1, i))
     two = timed(lambda i: (torch.nn.functional.layer_norm(xs[i % NSETS], (D,), gamma, bias, 1e-5),
                            m.mesa_quantize_update_fused(xs[i % NSETS], lay, a, b, 0.9, qs[i % NSETS], ws2, m.ROUND_STOCHASTIC, 1, i)))
-    esz = 2 if spec.dtype == torch.float16 else 4
+    esz = elem_bytes(spec.dtype)
     nbytes = (2 * esz + 1) * n + 8 * M_
     return {"ms": round(one, 4), "GBps": round(nbytes / (one * 1e-3) / 1e9, 1), "frac_hbm": round(nbytes / (one * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "bytes": nbytes, "two_pass_ms": round(two, 4),
@@ -369,7 +381,7 @@ def workload_name(spec, number, lin):
     b, h, r, c = spec.attn
     dw = f"whole path incl. dW {lin[0]}->{lin[1]}" if lin else "whole path, no Linear layer named"
     return (f"configs[{number - 1}]: {spec.name} -- attention maps ({b}, {h}, {r}, {c}), {spec.tokens} tokens, dim {spec.dim}, "
-            f"MLP {spec.mlp}, {'fp16' if spec.dtype == torch.float16 else 'fp32'}; stochastic rounding; {dw}")
+            f"MLP {spec.mlp}, {DTYPE_NAME[spec.dtype]}; stochastic rounding; {dw}")
 
 
 def main():
@@ -381,6 +393,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4, 5],
                     help="which of the baseline configurations to run; the default (2) is the one the metric is quoted on, "
                          "the others are extra measurements (no cpu_baseline, no counter-based traffic figure)")
+    ap.add_argument("--storage", default="f16", choices=["f16", "bf16"],
+                    help="storage type of activations and gradients: f16 (the paper's mixed precision, the headline) or bf16")
     ap.add_argument("--linear", type=int, default=0, help="which of the configuration's Linear layers supplies dW")
     ap.add_argument("--traffic", type=float, default=None,
                     help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (see profiles/)")
@@ -395,6 +409,8 @@ def main():
     import paper_2111_11124_amd as m
     m.lib()
     spec = W.CONFIGS[args.config]
+    if args.storage == "bf16":
+        spec = dataclasses.replace(spec, dtype=torch.bfloat16)
     bytes_per = algorithmic_bytes(spec, args.linear)
     total_bytes = sum(bytes_per.values())
     path = Path(m, spec, args.linear)
@@ -446,7 +462,7 @@ def main():
         path.step(single_pass=True)
     torch.cuda.synchronize()
     sp_ms = (time.perf_counter() - t2) * 1e3 / args.steps
-    esz = 2 if spec.dtype == torch.float16 else 4
+    esz = elem_bytes(spec.dtype)
     sp_bytes = total_bytes - esz * sum(path.sets[0].x[k].numel() for k in path.tensors)
 
     # untimed: the plain copy kernel on 256 MiB (x2 buffers, rotated), the known-traffic reference that
@@ -469,7 +485,7 @@ def main():
         "metric": "effective HBM GB/s (% of peak) for quantize + dequant-fused bwd; dW MFMA util",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16 storage, f32 arithmetic (f16 x f16 -> f32 MFMA for dW)", "data": "synthetic",
+        "dtype": "{0} storage, f32 arithmetic ({0} x {0} -> f32 MFMA for dW)".format(DTYPE_NAME[spec.dtype]), "data": "synthetic",
         "config": {"workload": workload_name(spec, args.config, path.lin),
                    "bytes_per_step": total_bytes, "elements_per_s": round(
                        (spec.attn[0] * spec.attn[1] * spec.attn[2] * spec.attn[3] + spec.tokens * (spec.mlp + 2 * spec.dim))
@@ -497,7 +513,8 @@ def main():
                          "frac_hbm": round(bytes_per[k] / (v * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)} for k, v in per_kernel_ms.items()},
     }
     if not args.no_cpu_baseline and args.config == 2:
-        out["cpu_baseline"] = cpu_baseline(spec)
+        # the oracle reads binary16 or binary32 arrays: for bfloat16 runs it is timed on the binary16 workload (same bytes)
+        out["cpu_baseline"] = cpu_baseline(dataclasses.replace(spec, dtype=torch.float16))
     print(json.dumps(out))
 
 

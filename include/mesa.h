@@ -47,7 +47,11 @@ typedef enum {
     MESA_ERR_LAUNCH = 4        /* the HIP runtime reported an error at launch */
 } mesa_status;
 
-typedef enum { MESA_F32 = 0, MESA_F16 = 1 } mesa_dtype;
+/* Storage type of activations and gradients.  The paper trains with binary16 mixed precision; bfloat16
+ * (upper half of a binary32 word, round to nearest even on store) is accepted wherever binary16 is,
+ * except by the attention matrix products.  Codes and parameters are decided in binary32 from the
+ * stored value whatever its type. */
+typedef enum { MESA_F32 = 0, MESA_F16 = 1, MESA_BF16 = 2 } mesa_dtype;
 
 typedef enum {
     MESA_ROUND_NEAREST_EVEN = 0, /* ablation "nearest rounding"; ties to even */
@@ -243,7 +247,7 @@ mesa_status mesa_layernorm_bwd_q(const int8_t *xq, int64_t M, int64_t D, int64_t
  * Linear weight gradient at the de-quantized input, Eq. (2) for y = x W^T, W of shape (N_out, K):
  *   dW[n, k] = sum_m dy[m, n] * x_hat[m, k],   db[n] = sum_m dy[m, n]
  * evaluated as  s_g(k) * sum_m dy[m,n]*(q[m,k]+128)  +  beta_g(k) * db[n]  on the matrix cores
- * (binary16 products for MESA_F16, binary32 accumulation; fixed summation order).
+ * (binary16 products for MESA_F16, bfloat16 products for MESA_BF16, binary32 accumulation; fixed summation order).
  * xq: (M, K) int8, K in G channel groups.  dy: (M, N_out) of dt.  dW: (N_out, K) binary32, row-major,
  * overwritten.  db: [N_out] binary32 or NULL.  ws: MESA_OP_LINEAR_DW_Q bytes.
  * Limits: K % 16 == 0, N_out % 8 == 0, K % G == 0, else MESA_ERR_UNSUPPORTED.
@@ -257,8 +261,8 @@ mesa_status mesa_linear_dw_q(const int8_t *xq, int64_t M, int64_t K, int64_t G,
  * Backward of the two matrix products of self-attention at head-wise de-quantized operands, Sec. 3.1
  * Eq. (2) with G_l = the gradient of a matrix product (the "MatMul" rows of the paper's overhead table;
  * Sec. 3.2: the operands are saved as codes with one (alpha, beta) pair per head).  All tensors are
- * (B, H, N, .) contiguous, upstream gradients and results of dt (binary16 only: MESA_F32 returns
- * MESA_ERR_UNSUPPORTED), accumulation in binary32; any N and Dh (nothing needs to be aligned).
+ * (B, H, N, .) contiguous, upstream gradients and results of dt (binary16 only: MESA_F32 and MESA_BF16
+ * return MESA_ERR_UNSUPPORTED), accumulation in binary32; any N and Dh (nothing needs to be aligned).
  *
  * O = A V with A the attention map (B,H,N,N) and V (B,H,N,Dh):
  *   dA[i,j] = sum_d dO[i,d] * V_hat[j,d],    dV[j,d] = sum_i A_hat[i,j] * dO[i,d]

@@ -4,7 +4,7 @@ The product is the C-ABI shared library declared in include/mesa.h; this package
 Python binding (same names, argument marshalling only).
 """
 from ._ffi import (  # noqa: F401
-    F16, F32, ROUND_NEAREST_EVEN, ROUND_STOCHASTIC,
+    F16, F32, BF16, ROUND_NEAREST_EVEN, ROUND_STOCHASTIC,
     OP_UPDATE_RUNNING_PARAMS, OP_LAYERNORM_BWD_Q, OP_LINEAR_DW_Q, OP_SOFTMAX_FWD_Q, OP_LAYERNORM_FWD_Q,
     OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH,
     EXPORTS, Event, Layout, MesaError, lib, status_string, version, workspace_bytes,

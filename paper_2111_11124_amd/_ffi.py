@@ -15,7 +15,7 @@ import torch  # noqa: F401  (first, so that libmesa binds to the HIP runtime tor
 _LIB_PATH = Path(__file__).resolve().parent / "libmesa.so"
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = range(5)
-F32, F16 = 0, 1
+F32, F16, BF16 = 0, 1, 2
 ROUND_NEAREST_EVEN, ROUND_STOCHASTIC = 0, 1
 OP_UPDATE_RUNNING_PARAMS, OP_LAYERNORM_BWD_Q, OP_LINEAR_DW_Q, OP_SOFTMAX_FWD_Q, OP_LAYERNORM_FWD_Q = 0, 1, 2, 3, 4
 
@@ -98,6 +98,8 @@ def _dt(t: torch.Tensor) -> int:
         return F32
     if t.dtype == torch.float16:
         return F16
+    if t.dtype == torch.bfloat16:
+        return BF16
     raise TypeError(f"unsupported dtype {t.dtype}")
 
 

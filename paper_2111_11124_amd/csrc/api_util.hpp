@@ -19,7 +19,16 @@ size_t layernorm_fwd_ws_bytes(int64_t M, int64_t D, int64_t G);
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
-inline bool valid_dtype(mesa_dtype dt) { return dt == MESA_F32 || dt == MESA_F16; }
+inline bool valid_dtype(mesa_dtype dt) { return dt == MESA_F32 || dt == MESA_F16 || dt == MESA_BF16; }
+inline int dtype_bytes(mesa_dtype dt) { return dt == MESA_F32 ? 4 : 2; }
+
+// expands X(T) with the element type that a valid dt names
+#define MESA_FOR_DTYPE(dt, X) \
+    do { \
+        if ((dt) == MESA_F16) X(_Float16); \
+        else if ((dt) == MESA_BF16) X(__bf16); \
+        else X(float); \
+    } while (0)
 
 inline mesa_status check_layout(const mesa_layout &L)
 {

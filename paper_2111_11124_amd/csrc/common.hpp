@@ -86,7 +86,7 @@ __device__ __forceinline__ uint32_t group_of(const Cursor &c, uint32_t j, const 
 __device__ __forceinline__ h2 as_h2(uint32_t w) { return __builtin_bit_cast(h2, w); }
 __device__ __forceinline__ uint32_t as_u32(h2 v) { return __builtin_bit_cast(uint32_t, v); }
 
-template <typename T> struct Store;  // T = float or _Float16
+template <typename T> struct Store;  // T = float, _Float16 or __bf16
 
 template <> struct Store<_Float16> {
     typedef u32x4 raw_t;  // 8 elements
@@ -127,6 +127,49 @@ template <> struct Store<_Float16> {
     __device__ static __forceinline__ void store1(void *base, int64_t e, float f)
     {
         static_cast<_Float16 *>(base)[e] = _Float16(f);
+    }
+};
+
+// bfloat16: the upper half of a binary32 word; widening is a shift, narrowing rounds to nearest even
+template <> struct Store<__bf16> {
+    typedef u32x4 raw_t;  // 8 elements
+    typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+    static constexpr int kBytes = 2;
+    __device__ static __forceinline__ raw_t load(const void *base, int64_t e)
+    {
+        return *reinterpret_cast<const u32x4 *>(static_cast<const char *>(base) + e * 2);
+    }
+    __device__ static __forceinline__ void store(void *base, int64_t e, raw_t v)
+    {
+        *reinterpret_cast<u32x4 *>(static_cast<char *>(base) + e * 2) = v;
+    }
+    __device__ static __forceinline__ void unpack(raw_t v, float f[8])
+    {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            f[2 * k] = __uint_as_float(v[k] << 16);
+            f[2 * k + 1] = __uint_as_float(v[k] & 0xFFFF0000u);
+        }
+    }
+    __device__ static __forceinline__ raw_t pack(const float f[8])
+    {
+        raw_t v;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            bf2 p;
+            p.x = __bf16(f[2 * k]);        // round to nearest even
+            p.y = __bf16(f[2 * k + 1]);
+            v[k] = __builtin_bit_cast(uint32_t, p);
+        }
+        return v;
+    }
+    __device__ static __forceinline__ float load1(const void *base, int64_t e)
+    {
+        return __uint_as_float(uint32_t(static_cast<const uint16_t *>(base)[e]) << 16);
+    }
+    __device__ static __forceinline__ void store1(void *base, int64_t e, float f)
+    {
+        static_cast<__bf16 *>(base)[e] = __bf16(f);
     }
 };
 
@@ -192,6 +235,7 @@ template <> struct Nt<_Float16> {
     __device__ static __forceinline__ u32x4 load(const void *b, int64_t e) { return nt_load<u32x4>(static_cast<const char *>(b) + e * 2); }
     __device__ static __forceinline__ void store(void *b, int64_t e, u32x4 v) { nt_store<u32x4>(static_cast<char *>(b) + e * 2, v); }
 };
+template <> struct Nt<__bf16> : Nt<_Float16> {};
 template <> struct Nt<float> {
     __device__ static __forceinline__ Store<float>::raw_t load(const void *b, int64_t e)
     {

@@ -368,7 +368,7 @@ static LnPlan ln_plan(int64_t M, int64_t D, mesa_dtype dt)
         p.vpl = vpr <= 64 ? 1 : 2;
         const int64_t block_rows = (kThreads / 64) * kLnRowsInFlight * (64 / p.lpr);   // rows a workgroup has in flight
         const int64_t wgs = ceil_div(M, block_rows);
-        const int64_t resident = 256 * ln_rows_wg_per_cu(dt == MESA_F16 ? 2 : 4, p.vpl);   // one round of workgroups
+        const int64_t resident = 256 * ln_rows_wg_per_cu(size_t(dtype_bytes(dt)), p.vpl);   // one round of workgroups
         p.grid = int(wgs < resident ? wgs : resident);
         return p;
     }
@@ -426,9 +426,9 @@ extern "C" MESA_EXPORT mesa_status mesa_layernorm_bwd_q(const int8_t *xq, int64_
     hipLaunchKernelGGL((k_layernorm_bwd<T, kThreads>), dim3(p.grid), dim3(kThreads), 0, s, xq, dy, dx, gamma, mean, rstd, alpha, \
                        beta, M, uint32_t(D), uint32_t(p.R), p.tiles, uint32_t(G), dvpr, dvpg, inv_D, part)
     if (p.in_wave) {
-        if (dt == MESA_F16) MESA_LAUNCH_ROWS_T(_Float16); else MESA_LAUNCH_ROWS_T(float);
+        MESA_FOR_DTYPE(dt, MESA_LAUNCH_ROWS_T);
     } else {
-        if (dt == MESA_F16) MESA_LAUNCH_LN(_Float16); else MESA_LAUNCH_LN(float);
+        MESA_FOR_DTYPE(dt, MESA_LAUNCH_LN);
     }
 #undef MESA_LAUNCH_LN
 #undef MESA_LAUNCH_ROWS_T

@@ -214,7 +214,7 @@ extern "C" MESA_EXPORT mesa_status mesa_layernorm_fwd_q(const void *x, int64_t M
         else if (p.lpr == 32) MESA_LAUNCH_LF_S(T, 32, 1); \
         else MESA_LAUNCH_LF_S(T, 64, 1); \
     } while (0)
-    if (dt == MESA_F16) MESA_LAUNCH_LF_T(_Float16); else MESA_LAUNCH_LF_T(float);
+    MESA_FOR_DTYPE(dt, MESA_LAUNCH_LF_T);
 #undef MESA_LAUNCH_LF_T
 #undef MESA_LAUNCH_LF_S
 #undef MESA_LAUNCH_LF

@@ -6,7 +6,10 @@
 // and centred, so P does not cancel against S0) and the per-column affine map is applied once to
 // the finished sums.
 //
-// binary16 path, gfx950.  Both operands are row-major in the contraction index m, which is the
+// (bfloat16 dy: the same kernel with bfloat16 matrix-core operands; there the contracted value is
+// x_bar = q + 128 itself, c = 0 in  dW = s_g (dy^T (x_bar - c)) + (beta_g + c s_g) S0.)
+//
+// 16-bit path, gfx950.  Both operands are row-major in the contraction index m, which is the
 // layout the MFMA operands do NOT want (a lane holds 8 consecutive contraction values of one
 // row).  gfx950's LDS transpose reads solve exactly this: the dy and code tiles are copied to
 // LDS as they lie in memory, and ds_read_b64_tr_b16 / ds_read_b64_tr_b8 deliver, per lane, the
@@ -26,6 +29,8 @@ namespace mesa {
 
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+typedef __bf16 v8b __attribute__((ext_vector_type(8)));
+typedef __bf16 v2b __attribute__((ext_vector_type(2)));
 typedef short v4s __attribute__((ext_vector_type(4)));
 typedef int v2i __attribute__((ext_vector_type(2)));
 typedef float v16f __attribute__((ext_vector_type(16)));
@@ -73,10 +78,54 @@ __device__ __forceinline__ v4h codes_to_half4(int raw)
     return out;
 }
 
-// P[split][n][k] = sum over the slice's m of dy[m][n] * q[m][k]   (q the signed code)
+// four signed codes -> four bfloat16 values q + 128 (bfloat16 has no spare mantissa bit for the exponent trick
+// above, and its eight significant bits hold 0..255 exactly): byte -> binary32 -> upper halves
+__device__ __forceinline__ v4s codes_to_bf4(int raw)
+{
+    const uint32_t x = uint32_t(raw) ^ 0x80808080u;
+    const uint32_t f0 = __float_as_uint(float(x & 0xFFu)), f1 = __float_as_uint(float((x >> 8) & 0xFFu));
+    const uint32_t f2 = __float_as_uint(float((x >> 16) & 0xFFu)), f3 = __float_as_uint(float(x >> 24));
+    const v2i w = {int(__builtin_amdgcn_perm(f1, f0, 0x07060302u)), int(__builtin_amdgcn_perm(f3, f2, 0x07060302u))};
+    return __builtin_bit_cast(v4s, w);
+}
+
+// What the operand type decides: how codes become matrix-core operands and which value of the code is
+// contracted (kCentre: the offset c in "operand = x_bar - c"), the row sums of dy, and the MFMA itself.
+template <typename E> struct DwElem;
+template <> struct DwElem<_Float16> {
+    static constexpr float kCentre = 128.0f;
+    __device__ static __forceinline__ v4s convert(int raw) { return __builtin_bit_cast(v4s, codes_to_half4(raw)); }
+    __device__ static __forceinline__ float dot_ones(uint32_t pair, float acc)
+    {
+        const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
+        return __builtin_amdgcn_fdot2(as_h2(pair), ones, acc, false);
+    }
+    __device__ static __forceinline__ v16f mfma(v4s a0, v4s a1, v4s b0, v4s b1, v16f c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7)),
+                                                      __builtin_bit_cast(v8h, __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7)),
+                                                      c, 0, 0, 0);
+    }
+};
+template <> struct DwElem<__bf16> {
+    static constexpr float kCentre = 0.0f;
+    __device__ static __forceinline__ v4s convert(int raw) { return codes_to_bf4(raw); }
+    __device__ static __forceinline__ float dot_ones(uint32_t pair, float acc)
+    {
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(v2b, pair), __builtin_bit_cast(v2b, 0x3F803F80u), acc, false);
+    }
+    __device__ static __forceinline__ v16f mfma(v4s a0, v4s a1, v4s b0, v4s b1, v16f c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8b, __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7)),
+                                                       __builtin_bit_cast(v8b, __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7)),
+                                                       c, 0, 0, 0);
+    }
+};
+
+// P[split][n][k] = sum over the slice's m of dy[m][n] * (x_bar[m][k] - kCentre)   (x_bar - 128 is the signed code)
 // S0[split][n]   = sum over the slice's m of dy[m][n]
-template <int BN, int BK, int WGN, int WGK>
-__global__ __launch_bounds__(WGN * WGK * 64, 1) void k_dw_f16(const int8_t *__restrict__ xq, const _Float16 *__restrict__ dy,
+template <typename E, int BN, int BK, int WGN, int WGK>
+__global__ __launch_bounds__(WGN * WGK * 64, 1) void k_dw_f16(const int8_t *__restrict__ xq, const E *__restrict__ dy,
                                                               int64_t M, int K, int N, int tiles_n, int tiles_k, int splits,
                                                               int64_t rows_per_split, float *__restrict__ P,
                                                               float *__restrict__ S0)
@@ -189,7 +238,7 @@ __global__ __launch_bounds__(WGN * WGK * 64, 1) void k_dw_f16(const int8_t *__re
     constexpr int kNR = C::TI * 2 + C::TJ;                   // LDS reads per step
     constexpr int kND = C::TIS * 4;                          // dot instructions per step
     constexpr int kNC = C::TJ * 2;                           // conversions (four codes each) per step
-    v4h afr[2][C::TI][2], bfr[2][C::TJ][2];                  // fragments of the step in flight and the next
+    v4s afr[2][C::TI][2], bfr[2][C::TJ][2];                  // fragments of the step in flight and the next (raw 16-bit lanes)
     v2i braw[C::TJ];
     auto read_item = [&](int t, const unsigned char *st, int ks, int set) {
         if (t < C::TJ) {
@@ -197,21 +246,17 @@ __global__ __launch_bounds__(WGN * WGK * 64, 1) void k_dw_f16(const int8_t *__re
         } else {
             const int i = (t - C::TJ) >> 1, h = (t - C::TJ) & 1;
             const unsigned char *p = st + a_base[i / C::TIS] + ks * 16 * C::PA + (i % C::TIS) * 64 + h * 4 * C::PA;
-            afr[set][i][h] = __builtin_bit_cast(v4h, __builtin_amdgcn_ds_read_tr16_b64_v4i16(MESA_LDS3(v4s, p)));
+            afr[set][i][h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(MESA_LDS3(v4s, p));
         }
     };
     auto dot_item = [&](int d, int set) {
-        const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
         const int i = d >> 2, k = d & 3;
-        const h2 pr = {afr[set][i][k >> 1][2 * (k & 1)], afr[set][i][k >> 1][2 * (k & 1) + 1]};
-        s0[i] = __builtin_amdgcn_fdot2(pr, ones, s0[i], false);
+        s0[i] = DwElem<E>::dot_ones(uint32_t(__builtin_bit_cast(v2i, afr[set][i][k >> 1])[k & 1]), s0[i]);
     };
-    auto conv_item = [&](int c, int set) { bfr[set][c >> 1][c & 1] = codes_to_half4(braw[c >> 1][c & 1]); };
+    auto conv_item = [&](int c, int set) { bfr[set][c >> 1][c & 1] = DwElem<E>::convert(braw[c >> 1][c & 1]); };
     auto mfma_item = [&](int r, int set) {
         const int i = r / C::TJ, j = r % C::TJ;
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-            __builtin_shufflevector(afr[set][i][0], afr[set][i][1], 0, 1, 2, 3, 4, 5, 6, 7),
-            __builtin_shufflevector(bfr[set][j][0], bfr[set][j][1], 0, 1, 2, 3, 4, 5, 6, 7), acc[i][j], 0, 0, 0);
+        acc[i][j] = DwElem<E>::mfma(afr[set][i][0], afr[set][i][1], bfr[set][j][0], bfr[set][j][1], acc[i][j]);
     };
 
     // One step.  PH = 0: multiplies fragment set 0 (step 0 of stage s), fetches step 1 into set 1 and
@@ -401,12 +446,12 @@ __global__ __launch_bounds__(kThreads) void k_dw_f32(const int8_t *__restrict__ 
     }
 }
 
-// With q the signed code, x_hat = s_g*q + (beta_g + 128 s_g), so
-// dW = s_g(k) * sum_slices P + (beta_g(k) + 128 s_g(k)) * sum_slices S0;  db = sum_slices S0.  Four columns per thread.
+// With the contracted operand u = x_bar - c, x_hat = s_g*u + (beta_g + c s_g), so
+// dW = s_g(k) * sum_slices P + (beta_g(k) + c s_g(k)) * sum_slices S0;  db = sum_slices S0.  Four columns per thread.
 __global__ __launch_bounds__(kThreads) void k_dw_reduce(const float *__restrict__ P, const float *__restrict__ S0, int splits,
                                                         int N, int K, FastDiv div_k4, FastDiv div_per,
                                                         const float *__restrict__ alpha, const float *__restrict__ beta,
-                                                        float *__restrict__ dW, float *__restrict__ db)
+                                                        float centre, float *__restrict__ dW, float *__restrict__ db)
 {
     const int64_t idx = int64_t(blockIdx.x) * kThreads + threadIdx.x;
     const int64_t nvec = int64_t(N) * (K / 4);
@@ -425,14 +470,14 @@ __global__ __launch_bounds__(kThreads) void k_dw_reduce(const float *__restrict_
     for (int j = 0; j < 4; ++j) {
         const uint32_t g = fastdiv(kk + j, div_per);
         const float sg = alpha[g] / 255.0f;
-        o[j] = fmaf(sg, o[j], fmaf(128.0f, sg, beta[g]) * s0);
+        o[j] = fmaf(sg, o[j], fmaf(centre, sg, beta[g]) * s0);
     }
     *reinterpret_cast<float4 *>(dW + int64_t(n) * K + kk) = make_float4(o[0], o[1], o[2], o[3]);
     if (db && kk == 0) db[n] = s0;
 }
 
 struct DwPlan {
-    int variant;   // binary16 tiles (n x k): 0: 256 x 256, 1: 256 x 128; 2: binary32
+    int variant;   // 16-bit tiles (n x k): 0: 256 x 256, 1: 256 x 128; 2: binary32
     int bn, bk, tiles_n, tiles_k, splits, grid;
     int64_t rows_per_split;
 };
@@ -440,7 +485,7 @@ struct DwPlan {
 static DwPlan dw_plan(int64_t M, int64_t K, int64_t N, mesa_dtype dt)
 {
     DwPlan p;
-    if (dt == MESA_F16) {
+    if (dt != MESA_F32) {
         // 256-wide k tiles unless they would waste much of the last one.  (A 128 x 384 tile for K = 384 was
         // measured too: no faster per MFMA, and its 21 slices instead of 14 cost more partial-sum traffic.)
         if (K % 256 == 0 || K > 1024) { p.variant = 0; p.bn = 256; p.bk = 256; }
@@ -499,17 +544,18 @@ extern "C" MESA_EXPORT mesa_status mesa_linear_dw_q(const int8_t *xq, int64_t M,
     float *P = static_cast<float *>(ws);
     float *S0 = P + size_t(p.splits) * size_t(N_out) * size_t(K);
     const int Ki = int(K), Ni = int(N_out);
+    float centre = 128.0f;
+#define MESA_LAUNCH_DW(E, BK_) \
+    do { \
+        using C = DwCfg<256, BK_, 2, 2>; \
+        hipLaunchKernelGGL((k_dw_f16<E, 256, BK_, 2, 2>), dim3(p.grid), dim3(C::THREADS), 2 * C::STAGE, s, xq, \
+                           static_cast<const E *>(dy), M, Ki, Ni, p.tiles_n, p.tiles_k, p.splits, p.rows_per_split, P, S0); \
+        centre = DwElem<E>::kCentre; \
+    } while (0)
     if (dt == MESA_F16) {
-        const _Float16 *dyh = static_cast<const _Float16 *>(dy);
-        if (p.variant == 0) {
-            using C = DwCfg<256, 256, 2, 2>;
-            hipLaunchKernelGGL((k_dw_f16<256, 256, 2, 2>), dim3(p.grid), dim3(C::THREADS), 2 * C::STAGE, s, xq, dyh, M, Ki, Ni,
-                               p.tiles_n, p.tiles_k, p.splits, p.rows_per_split, P, S0);
-        } else {
-            using C = DwCfg<256, 128, 2, 2>;
-            hipLaunchKernelGGL((k_dw_f16<256, 128, 2, 2>), dim3(p.grid), dim3(C::THREADS), 2 * C::STAGE, s, xq, dyh, M, Ki, Ni,
-                               p.tiles_n, p.tiles_k, p.splits, p.rows_per_split, P, S0);
-        }
+        if (p.variant == 0) MESA_LAUNCH_DW(_Float16, 256); else MESA_LAUNCH_DW(_Float16, 128);
+    } else if (dt == MESA_BF16) {
+        if (p.variant == 0) MESA_LAUNCH_DW(__bf16, 256); else MESA_LAUNCH_DW(__bf16, 128);
     } else {
         hipLaunchKernelGGL(k_dw_f32, dim3(p.grid), dim3(kThreads), 0, s, xq, static_cast<const float *>(dy), M, Ki, Ni,
                            p.tiles_n, p.tiles_k, p.splits, p.rows_per_split, P, S0);
@@ -517,6 +563,7 @@ extern "C" MESA_EXPORT mesa_status mesa_linear_dw_q(const int8_t *xq, int64_t M,
     const int64_t nvec = N_out * (K / 4);
     FastDiv dk4 = make_fastdiv(uint32_t(K / 4)), dper = make_fastdiv(uint32_t(K / G));
     hipLaunchKernelGGL(k_dw_reduce, dim3(unsigned(ceil_div(nvec, kThreads))), dim3(kThreads), 0, s, P, S0, p.splits, Ni, Ki, dk4,
-                       dper, alpha, beta, dW, db);
+                       dper, alpha, beta, centre, dW, db);
+#undef MESA_LAUNCH_DW
     return launch_status();
 }

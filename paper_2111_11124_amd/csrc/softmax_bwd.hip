@@ -317,8 +317,9 @@ extern "C" MESA_EXPORT mesa_status mesa_softmax_bwd_q(const int8_t *yq, int64_t 
 #define MESA_LAUNCH_S(T, TPT_) \
     hipLaunchKernelGGL((k_softmax_bwd<T, TPT_>), dim3(grid), dim3(kThreads), 0, s, yq, dy, dx, total_rows, uint32_t(cols), \
                        uint32_t(R), tiles, dc, dr, dh, alpha, beta)
-    if (dt == MESA_F16) { if (wave_tiles) MESA_LAUNCH_S(_Float16, 64); else MESA_LAUNCH_S(_Float16, kThreads); }
-    else { if (wave_tiles) MESA_LAUNCH_S(float, 64); else MESA_LAUNCH_S(float, kThreads); }
+#define MESA_LAUNCH_S_T(T) do { if (wave_tiles) MESA_LAUNCH_S(T, 64); else MESA_LAUNCH_S(T, kThreads); } while (0)
+    MESA_FOR_DTYPE(dt, MESA_LAUNCH_S_T);
+#undef MESA_LAUNCH_S_T
 #undef MESA_LAUNCH_S
     return launch_status();
 }

@@ -327,7 +327,7 @@ extern "C" MESA_EXPORT mesa_status mesa_softmax_fwd_q(const void *s_in, int64_t 
         if (p.wave_tiles) { if (sr) MESA_LAUNCH_SF(T, 64, true); else MESA_LAUNCH_SF(T, 64, false); } \
         else { if (sr) MESA_LAUNCH_SF(T, kThreads, true); else MESA_LAUNCH_SF(T, kThreads, false); } \
     } while (0)
-    if (dt == MESA_F16) MESA_LAUNCH_SF_T(_Float16); else MESA_LAUNCH_SF_T(float);
+    MESA_FOR_DTYPE(dt, MESA_LAUNCH_SF_T);
 #undef MESA_LAUNCH_SF_T
 #undef MESA_LAUNCH_SF
     launch_ema_finalize(part, p.grid, uint32_t(H), alpha, beta, lambda, 0, 0, 0.0f, s);

@@ -95,6 +95,23 @@ template <> struct MinMax<float> {
     __device__ __forceinline__ float hi() const { return mx; }
 };
 
+// bfloat16 data: widened (a shift or a mask per element) and compared as binary32
+template <> struct MinMax<__bf16> {
+    float mn, mx;
+    __device__ __forceinline__ void init() { mn = __builtin_inff(); mx = -__builtin_inff(); }
+    __device__ __forceinline__ void add(const Store<__bf16>::raw_t &v)
+    {
+        float f[8];
+        Store<__bf16>::unpack(v, f);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { mn = vmin(mn, f[j]); mx = vmax(mx, f[j]); }
+    }
+    __device__ __forceinline__ void add1(float f) { mn = vmin(mn, f); mx = vmax(mx, f); }
+    __device__ __forceinline__ void merge(const MinMax<__bf16> &o) { mn = vmin(mn, o.mn); mx = vmax(mx, o.mx); }
+    __device__ __forceinline__ float lo() const { return mn; }
+    __device__ __forceinline__ float hi() const { return mx; }
+};
+
 // binary16 data: selection is exact in any precision, so compare packed pairs directly
 template <> struct MinMax<_Float16> {
     uint32_t mn, mx;
@@ -897,13 +914,14 @@ static mesa_status update_running_params(const void *x, mesa_dtype dt, mesa_layo
         else if (L.groups <= 6) MESA_LAUNCH_FEW(T, 6); \
         else MESA_LAUNCH_FEW(T, 8); \
     } while (0)
-        if (dt == MESA_F16) MESA_LAUNCH_FEW_T(_Float16); else MESA_LAUNCH_FEW_T(float);
+        MESA_FOR_DTYPE(dt, MESA_LAUNCH_FEW_T);
 #undef MESA_LAUNCH_FEW_T
 #undef MESA_LAUNCH_FEW
-    } else if (dt == MESA_F16)
-        hipLaunchKernelGGL((k_minmax_partial<_Float16, kMmU>), dim3(grid), dim3(kThreads), lds, s, x, numel, gg, part);
-    else
-        hipLaunchKernelGGL((k_minmax_partial<float, kMmU>), dim3(grid), dim3(kThreads), lds, s, x, numel, gg, part);
+    } else {
+#define MESA_LAUNCH_MM(T) hipLaunchKernelGGL((k_minmax_partial<T, kMmU>), dim3(grid), dim3(kThreads), lds, s, x, numel, gg, part)
+        MESA_FOR_DTYPE(dt, MESA_LAUNCH_MM);
+#undef MESA_LAUNCH_MM
+    }
     hipLaunchKernelGGL(k_ema_finalize, dim3(gg.groups), dim3(kThreads), 0, s, part, grid, gg.groups, alpha, beta, lambda,
                        first_call, variant, beta_fixed);
     return launch_status();
@@ -948,8 +966,9 @@ extern "C" MESA_EXPORT mesa_status mesa_quantize_headwise(const void *x, mesa_dt
     const bool sr = mode == MESA_ROUND_STOCHASTIC;
 #define MESA_LAUNCH_Q(T, SRF) \
     hipLaunchKernelGGL((k_quantize<T, kU, SRF>), dim3(grid), dim3(kThreads), lds, s, x, q, numel, gg, alpha, beta, seed, offset)
-    if (dt == MESA_F16) { if (sr) MESA_LAUNCH_Q(_Float16, true); else MESA_LAUNCH_Q(_Float16, false); }
-    else { if (sr) MESA_LAUNCH_Q(float, true); else MESA_LAUNCH_Q(float, false); }
+#define MESA_LAUNCH_Q_T(T) do { if (sr) MESA_LAUNCH_Q(T, true); else MESA_LAUNCH_Q(T, false); } while (0)
+    MESA_FOR_DTYPE(dt, MESA_LAUNCH_Q_T);
+#undef MESA_LAUNCH_Q_T
 #undef MESA_LAUNCH_Q
     return launch_status();
 }
@@ -984,7 +1003,7 @@ static mesa_status quantize_update_fused(const void *x, mesa_dtype dt, mesa_layo
         if (y) { if (sr) MESA_LAUNCH_QM(T, true, true); else MESA_LAUNCH_QM(T, false, true); } \
         else { if (sr) MESA_LAUNCH_QM(T, true, false); else MESA_LAUNCH_QM(T, false, false); } \
     } while (0)
-    if (dt == MESA_F16) MESA_LAUNCH_QM_T(_Float16); else MESA_LAUNCH_QM_T(float);
+    MESA_FOR_DTYPE(dt, MESA_LAUNCH_QM_T);
 #undef MESA_LAUNCH_QM_T
 #undef MESA_LAUNCH_QM
     hipLaunchKernelGGL(k_ema_finalize, dim3(gg.groups), dim3(kThreads), 0, s, part, grid, gg.groups, alpha, beta, lambda, 0);
@@ -1019,10 +1038,9 @@ extern "C" MESA_EXPORT mesa_status mesa_dequantize(const int8_t *q, mesa_layout 
     const int grid = stream_grid(numel, L.groups > 1 ? L.groups * L.inner : 0);
     GroupGeom gg = make_geom(L.groups, L.inner, int64_t(grid) * kThreads * kU * kVec);
     const size_t lds = size_t(gg.groups) * sizeof(float2);
-    if (dt == MESA_F16)
-        hipLaunchKernelGGL((k_dequantize<_Float16, kU>), dim3(grid), dim3(kThreads), lds, s, q, x_hat, numel, gg, alpha, beta);
-    else
-        hipLaunchKernelGGL((k_dequantize<float, kU>), dim3(grid), dim3(kThreads), lds, s, q, x_hat, numel, gg, alpha, beta);
+#define MESA_LAUNCH_DQ(T) hipLaunchKernelGGL((k_dequantize<T, kU>), dim3(grid), dim3(kThreads), lds, s, q, x_hat, numel, gg, alpha, beta)
+    MESA_FOR_DTYPE(dt, MESA_LAUNCH_DQ);
+#undef MESA_LAUNCH_DQ
     return launch_status();
 }
 
@@ -1045,8 +1063,9 @@ static mesa_status act_bwd_q(const int8_t *xq, mesa_layout L, const float *alpha
     const size_t lds = lut ? size_t(gg.groups) * 256 * sizeof(float) : size_t(gg.groups) * sizeof(float2);
 #define MESA_LAUNCH_G(T, L_) \
     hipLaunchKernelGGL((k_gelu_bwd<T, kU, L_, ACT>), dim3(grid), dim3(kThreads), lds, s, xq, dy, dx, numel, gg, alpha, beta)
-    if (dt == MESA_F16) { if (lut) MESA_LAUNCH_G(_Float16, true); else MESA_LAUNCH_G(_Float16, false); }
-    else { if (lut) MESA_LAUNCH_G(float, true); else MESA_LAUNCH_G(float, false); }
+#define MESA_LAUNCH_G_T(T) do { if (lut) MESA_LAUNCH_G(T, true); else MESA_LAUNCH_G(T, false); } while (0)
+    MESA_FOR_DTYPE(dt, MESA_LAUNCH_G_T);
+#undef MESA_LAUNCH_G_T
 #undef MESA_LAUNCH_G
     return launch_status();
 }

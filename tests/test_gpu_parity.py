@@ -1,7 +1,9 @@
 """GPU parity: libmesa (through its C ABI) against the CPU oracle on the same seeded inputs.
 
 Codes, running parameters and mesa_dequantize output must match bit for bit; gradients within
-max|gpu - ref| / max|ref| <= 1e-5 (binary32 storage) or 2e-3 (binary16 storage).
+max|gpu - ref| / max|ref| <= 1e-5 (binary32 storage), 2e-3 (binary16 storage) or 1.6e-2 (bfloat16
+storage: four roundings of 2^-8, as 2e-3 is four of 2^-11).  numpy has no bfloat16: the oracle is given
+the stored values widened to binary32, which is exact, so codes and parameters are still bit for bit.
 """
 import numpy as np
 import pytest
@@ -12,7 +14,19 @@ from oracle import mesa_ref as R
 
 pytestmark = pytest.mark.gpu
 
-TOL = {torch.float32: 1e-5, torch.float16: 2e-3}
+TOL = {torch.float32: 1e-5, torch.float16: 2e-3, torch.bfloat16: 1.6e-2}
+DTYPES = [torch.float32, torch.float16, torch.bfloat16]
+DTYPE_IDS = ["f32", "f16", "bf16"]
+
+
+def npy(t):
+    """A tensor's values as a numpy array; bfloat16 widened to binary32 (exact)."""
+    return (t.float() if t.dtype == torch.bfloat16 else t).cpu().numpy()
+
+
+def bf16_bits(a32):
+    """binary32 array -> the bits of its round-to-nearest-even bfloat16 (torch's conversion)."""
+    return torch.from_numpy(np.ascontiguousarray(a32, np.float32)).to(torch.bfloat16).view(torch.int16).numpy()
 
 
 @pytest.fixture(scope="module")
@@ -38,7 +52,7 @@ def relerr(got, ref):
 
 
 def ws_for(m, op, d0, d1, d2, dt=None):
-    n = m.workspace_bytes(op, d0, d1, d2, m.F16 if dt in (None, torch.float16) else m.F32)
+    n = m.workspace_bytes(op, d0, d1, d2, {None: m.F16, torch.float16: m.F16, torch.bfloat16: m.BF16, torch.float32: m.F32}[dt])
     return torch.empty(max(n, 16), dtype=torch.uint8, device="cuda")
 
 
@@ -51,7 +65,7 @@ def run_params(m, xs, layout, lam=0.9):
     ws = ws_for(m, m.OP_UPDATE_RUNNING_PARAMS, *layout)
     for i, x in enumerate(xs):
         m.mesa_update_running_params(x, layout, a, b, lam, i == 0, ws)
-        ra, rb = R.update_running_params(x.cpu().numpy(), layout, ra, rb, lam, i == 0)
+        ra, rb = R.update_running_params(npy(x), layout, ra, rb, lam, i == 0)
     torch.cuda.synchronize()
     return a, b, ra, rb
 
@@ -68,7 +82,7 @@ LAYOUTS = [
 ]
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.float16])
+@pytest.mark.parametrize("dtype", DTYPES, ids=DTYPE_IDS)
 @pytest.mark.parametrize("layout", LAYOUTS)
 def test_params_codes_and_dequantize_are_bit_exact(M, layout, dtype):
     outer, G, inner = layout
@@ -78,17 +92,17 @@ def test_params_codes_and_dequantize_are_bit_exact(M, layout, dtype):
     xs = [(torch.randn((outer, G, inner), generator=g, device="cuda") * scale + 0.25 * i).to(dtype).contiguous()
           for i in range(3)]
     a, b, ra, rb = run_params(M, xs, layout)
-    assert np.array_equal(canon(a.cpu().numpy()), canon(ra)), (a.cpu().numpy(), ra)
-    assert np.array_equal(canon(b.cpu().numpy()), canon(rb)), (b.cpu().numpy(), rb)
+    assert np.array_equal(canon(npy(a)), canon(ra)), (npy(a), ra)
+    assert np.array_equal(canon(npy(b)), canon(rb)), (npy(b), rb)
 
     x = xs[-1]
-    xh = x.cpu().numpy()
-    an, bn = a.cpu().numpy(), b.cpu().numpy()
+    xh = npy(x)
+    an, bn = npy(a), npy(b)
     for mode, seed, off in ((M.ROUND_NEAREST_EVEN, 0, 0), (M.ROUND_STOCHASTIC, 0xDEADBEEF12345, (1 << 33) + 17)):
         q = torch.empty(n, dtype=torch.int8, device="cuda")
         M.mesa_quantize_headwise(x, layout, a, b, q, mode, seed, off)
         rq = R.quantize_headwise(xh, layout, an, bn, mode, seed, off).reshape(-1)
-        got = q.cpu().numpy()
+        got = npy(q)
         bad = np.nonzero(got != rq)[0]
         assert bad.size == 0, (mode, bad[:10], got[bad[:10]], rq[bad[:10]])
     for odt in (torch.float32, torch.float16):
@@ -96,25 +110,27 @@ def test_params_codes_and_dequantize_are_bit_exact(M, layout, dtype):
         M.mesa_dequantize(q, layout, a, b, out)
         ref = R.dequantize(rq, layout, an, bn, np.float32 if odt == torch.float32 else np.float16)
         u = np.uint32 if odt == torch.float32 else np.uint16
-        assert np.array_equal(out.cpu().numpy().view(u), ref.view(u))
+        assert np.array_equal(npy(out).view(u), ref.view(u))
+    out = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    M.mesa_dequantize(q, layout, a, b, out)
+    assert np.array_equal(out.view(torch.int16).cpu().numpy(), bf16_bits(R.dequantize(rq, layout, an, bn, np.float32)))
 
 
 def block_parity(m, spec, modes=("nearest", "stochastic")):
     """The whole path on one block's saved-activation set, every output against the oracle."""
     dt = spec.dtype
     tol = TOL[dt]
-    npdt = np.float32 if dt == torch.float32 else np.float16
     H = spec.heads
     report = {}
 
     def params_and_codes(draws, layout, mode, seed, off):
         a, b, ra, rb = run_params(m, draws, layout, spec.lam)
-        assert np.array_equal(canon(a.cpu().numpy()), canon(ra)) and np.array_equal(canon(b.cpu().numpy()), canon(rb))
+        assert np.array_equal(canon(npy(a)), canon(ra)) and np.array_equal(canon(npy(b)), canon(rb))
         x = draws[-1]
         q = torch.empty(x.numel(), dtype=torch.int8, device="cuda")
         m.mesa_quantize_headwise(x, layout, a, b, q, mode, seed, off)
-        rq = R.quantize_headwise(x.cpu().numpy(), layout, ra, rb, mode, seed, off).reshape(-1)
-        assert np.array_equal(q.cpu().numpy(), rq)
+        rq = R.quantize_headwise(npy(x), layout, ra, rb, mode, seed, off).reshape(-1)
+        assert np.array_equal(npy(q), rq)
         return a, b, ra, rb, q, rq
 
     for mi, mode_name in enumerate(modes):
@@ -124,13 +140,13 @@ def block_parity(m, spec, modes=("nearest", "stochastic")):
         B, Hh, rows, cols = spec.attn
         draws = [W.attention_map(spec, d, "cuda") for d in range(3)]
         a, b, ra, rb, q, rq = params_and_codes(draws, spec.attn_layout, mode, seed, 0)
-        assert (b.cpu().numpy() >= 0).all()
+        assert (npy(b) >= 0).all()
         del draws
         dy = W.upstream_grad(spec, "dy_attn", spec.attn, "cuda")
         dx = torch.empty_like(dy)
         m.mesa_softmax_bwd_q(q, B, Hh, rows, cols, a, b, dy, dx)
-        ref = R.softmax_bwd_q(rq, B, Hh, rows, cols, ra, rb, dy.cpu().numpy())
-        report[f"softmax_{mode_name}"] = relerr(dx.cpu().numpy().reshape(ref.shape), ref)
+        ref = R.softmax_bwd_q(rq, B, Hh, rows, cols, ra, rb, npy(dy))
+        report[f"softmax_{mode_name}"] = relerr(npy(dx).reshape(ref.shape), ref)
         del dy, dx, ref
         # --- GELU input -> GELU backward
         lay = spec.gelu_layout
@@ -140,8 +156,8 @@ def block_parity(m, spec, modes=("nearest", "stochastic")):
         dy = W.upstream_grad(spec, "dy_gelu", (spec.tokens, spec.mlp), "cuda")
         dx = torch.empty_like(dy)
         m.mesa_gelu_bwd_q(q, lay, a, b, dy, dx)
-        ref = R.gelu_bwd_q(rq, lay, ra, rb, dy.cpu().numpy())
-        report[f"gelu_{mode_name}"] = relerr(dx.cpu().numpy().reshape(ref.shape), ref)
+        ref = R.gelu_bwd_q(rq, lay, ra, rb, npy(dy))
+        report[f"gelu_{mode_name}"] = relerr(npy(dx).reshape(ref.shape), ref)
         del dy, dx, ref
         # --- LayerNorm input -> LayerNorm backward
         lay = spec.ln_layout
@@ -157,11 +173,11 @@ def block_parity(m, spec, modes=("nearest", "stochastic")):
         db = torch.empty(D, device="cuda")
         ws = ws_for(m, m.OP_LAYERNORM_BWD_Q, Mr, D, H)
         m.mesa_layernorm_bwd_q(q, Mr, D, H, a, b, mean, rstd, gamma, dy, dx, dg, db, ws)
-        rdx, rdg, rdb = R.layernorm_bwd_q(rq, Mr, D, H, ra, rb, mean.cpu().numpy(), rstd.cpu().numpy(),
-                                          gamma.cpu().numpy(), dy.cpu().numpy())
-        report[f"ln_dx_{mode_name}"] = relerr(dx.cpu().numpy(), rdx)
-        report[f"ln_dgamma_{mode_name}"] = relerr(dg.cpu().numpy(), rdg)
-        report[f"ln_dbeta_{mode_name}"] = relerr(db.cpu().numpy(), rdb)
+        rdx, rdg, rdb = R.layernorm_bwd_q(rq, Mr, D, H, ra, rb, npy(mean), npy(rstd),
+                                          npy(gamma), npy(dy))
+        report[f"ln_dx_{mode_name}"] = relerr(npy(dx), rdx)
+        report[f"ln_dgamma_{mode_name}"] = relerr(npy(dg), rdg)
+        report[f"ln_dbeta_{mode_name}"] = relerr(npy(db), rdb)
         del dy, dx
         # --- Linear inputs -> dW (entries sampled when the full matrix is out of the oracle's reach)
         for li, (K, N) in enumerate(spec.linears):
@@ -174,8 +190,8 @@ def block_parity(m, spec, modes=("nearest", "stochastic")):
             dbias = torch.empty(N, device="cuda")
             ws = ws_for(m, m.OP_LINEAR_DW_Q, Mr, K, N, dt)
             m.mesa_linear_dw_q(q, Mr, K, H, a, b, dy, N, dW, dbias, ws)
-            dyh = dy.cpu().numpy()
-            got = dW.cpu().numpy().astype(np.float64)
+            dyh = npy(dy)
+            got = npy(dW).astype(np.float64)
             if Mr * K * N <= 4e9:
                 rW, rb_ = R.linear_dw_q(rq, Mr, K, H, ra, rb, dyh, N)
                 report[f"dw{li}_{mode_name}"] = relerr(got, rW)
@@ -187,14 +203,17 @@ def block_parity(m, spec, modes=("nearest", "stochastic")):
                 scale = max(np.abs(ent).max(), 1e-30)
                 report[f"dw{li}_{mode_name}"] = float(np.abs(got[n_idx, k_idx] - ent).max() / scale)
                 rb_ = dyh.astype(np.float64).sum(0)
-            report[f"db{li}_{mode_name}"] = relerr(dbias.cpu().numpy(), rb_)
+            report[f"db{li}_{mode_name}"] = relerr(npy(dbias), rb_)
             del dy, dW
         if mi == 0:
             # mesa_dequantize on the last codes, both output types, bit for bit
             for odt, npo, u in ((torch.float32, np.float32, np.uint32), (torch.float16, np.float16, np.uint16)):
                 out = torch.empty(q.numel(), dtype=odt, device="cuda")
                 m.mesa_dequantize(q, lay, a, b, out)
-                assert np.array_equal(out.cpu().numpy().view(u), R.dequantize(rq, lay, ra, rb, npo).view(u))
+                assert np.array_equal(npy(out).view(u), R.dequantize(rq, lay, ra, rb, npo).view(u))
+            out = torch.empty(q.numel(), dtype=torch.bfloat16, device="cuda")
+            m.mesa_dequantize(q, lay, a, b, out)
+            assert np.array_equal(out.view(torch.int16).cpu().numpy(), bf16_bits(R.dequantize(rq, lay, ra, rb, np.float32)))
     bad = {k: v for k, v in report.items() if not v <= tol}
     assert not bad, (bad, report)
     return report
@@ -204,13 +223,18 @@ def test_config1_deit_ti_block_fp32(M):
     print(block_parity(M, W.CONFIGS[1]))
 
 
-def test_tiny_ragged_block_both_dtypes(M):
-    for dt in (torch.float32, torch.float16):
+def test_tiny_ragged_block_every_dtype(M):
+    for dt in DTYPES:
         print(block_parity(M, W.small_case(dt, B=3, H=3, N=19, D=48, mlp=96)))
 
 
 def test_config2_deit_s_shape_batch8(M):
     print(block_parity(M, W.scaled(W.CONFIGS[2], 16)))
+
+
+def test_config2_deit_s_shape_batch8_bfloat16(M):
+    from dataclasses import replace
+    print(block_parity(M, replace(W.scaled(W.CONFIGS[2], 16), dtype=torch.bfloat16), modes=("stochastic",)))
 
 
 def test_config3_swin_t_shape_reduced(M):
@@ -237,7 +261,7 @@ def _ln_case(M, spec, G):
     x = draws[-1]
     q = torch.empty(x.numel(), dtype=torch.int8, device="cuda")
     M.mesa_quantize_headwise(x, lay, a, b, q, M.ROUND_STOCHASTIC, 5, 0)
-    rq = q.cpu().numpy()
+    rq = npy(q)
     mean, rstd = W.layernorm_stats(x)
     gamma = W.layernorm_gamma(spec, "cuda")
     dy = W.upstream_grad(spec, "dy_ln", (Mr, D), "cuda")
@@ -246,12 +270,12 @@ def _ln_case(M, spec, G):
     db = torch.empty(D, device="cuda")
     ws = ws_for(M, M.OP_LAYERNORM_BWD_Q, Mr, D, G)
     M.mesa_layernorm_bwd_q(q, Mr, D, G, a, b, mean, rstd, gamma, dy, dx, dg, db, ws)
-    rdx, rdg, rdb = R.layernorm_bwd_q(rq, Mr, D, G, ra, rb, mean.cpu().numpy(), rstd.cpu().numpy(),
-                                      gamma.cpu().numpy(), dy.cpu().numpy())
-    return {"dx": relerr(dx.cpu().numpy(), rdx), "dgamma": relerr(dg.cpu().numpy(), rdg), "dbeta": relerr(db.cpu().numpy(), rdb)}
+    rdx, rdg, rdb = R.layernorm_bwd_q(rq, Mr, D, G, ra, rb, npy(mean), npy(rstd),
+                                      npy(gamma), npy(dy))
+    return {"dx": relerr(npy(dx), rdx), "dgamma": relerr(npy(dg), rdg), "dbeta": relerr(npy(db), rdb)}
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.float16], ids=["f32", "f16"])
+@pytest.mark.parametrize("dtype", DTYPES, ids=DTYPE_IDS)
 @pytest.mark.parametrize("D,G,tokens", [(8, 1, 37), (48, 3, 57), (128, 4, 333), (192, 3, 1000), (384, 6, 1579), (512, 8, 130),
                                         (768, 12, 517), (1024, 16, 259), (1032, 3, 77), (2048, 16, 35), (4096, 8, 19)])
 def test_layernorm_bwd_every_row_length_class(M, D, G, tokens, dtype):
@@ -264,27 +288,29 @@ def test_layernorm_bwd_every_row_length_class(M, D, G, tokens, dtype):
 
 @pytest.mark.parametrize("Mr,K,N", [(31, 16, 8), (32, 48, 24), (97, 128, 264), (100 * 32, 384, 256), (101 * 32 + 5, 256, 520),
                                     (4 * 32 * 7 + 13, 784, 136), (9000, 272, 1000)])
-def test_linear_dw_ragged_shapes(M, Mr, K, N):
-    """Slices of 1, 2 and 3k stages, a ragged last stage, K and N that leave partial tiles; binary16."""
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16], ids=["f16", "bf16"])
+def test_linear_dw_ragged_shapes(M, Mr, K, N, dtype):
+    """Slices of 1, 2 and 3k stages, a ragged last stage, K and N that leave partial tiles; both 16-bit types.
+    The products are exact and the sums binary32 for either type, so both meet the binary16 bound."""
     H = 1 if K % 3 else 3
-    spec = W.small_case(torch.float16, seed=Mr + K, B=1, H=H, N=Mr, D=K, mlp=N)
+    spec = W.small_case(dtype, seed=Mr + K, B=1, H=H, N=Mr, D=K, mlp=N)
     lay = (Mr, H, K // H)
     draws = [W.token_matrix(spec, "lin", d, "cuda", width=K) for d in range(2)]
     a, b, ra, rb = run_params(M, draws, lay, spec.lam)
     q = torch.empty(Mr * K, dtype=torch.int8, device="cuda")
     M.mesa_quantize_headwise(draws[-1], lay, a, b, q, M.ROUND_STOCHASTIC, 9, 0)
-    rq = q.cpu().numpy()
+    rq = npy(q)
     dy = W.upstream_grad(spec, "dy_lin", (Mr, N), "cuda")
     dW = torch.empty((N, K), device="cuda")
     dbias = torch.empty(N, device="cuda")
-    ws = ws_for(M, M.OP_LINEAR_DW_Q, Mr, K, N, torch.float16)
+    ws = ws_for(M, M.OP_LINEAR_DW_Q, Mr, K, N, dtype)
     M.mesa_linear_dw_q(q, Mr, K, H, a, b, dy, N, dW, dbias, ws)
-    rW, rb_ = R.linear_dw_q(rq, Mr, K, H, ra, rb, dy.cpu().numpy(), N)
-    rep = {"dW": relerr(dW.cpu().numpy().astype(np.float64), rW), "db": relerr(dbias.cpu().numpy(), rb_)}
+    rW, rb_ = R.linear_dw_q(rq, Mr, K, H, ra, rb, npy(dy), N)
+    rep = {"dW": relerr(npy(dW).astype(np.float64), rW), "db": relerr(npy(dbias), rb_)}
     assert all(v <= TOL[torch.float16] for v in rep.values()), rep
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.float16], ids=["f32", "f16"])
+@pytest.mark.parametrize("dtype", DTYPES, ids=DTYPE_IDS)
 @pytest.mark.parametrize("layout", [(3, 3, 19 * 19), (57, 3, 32), (5, 7, 1000), (1, 4, 8), (2, 6, 197 * 197), (1579, 6, 64)])
 def test_single_pass_forward_matches_the_oracle_bit_for_bit(M, layout, dtype):
     """mesa_quantize_update_fused: codes with the parameters on entry and the moved parameters, three steps
@@ -302,13 +328,13 @@ def test_single_pass_forward_matches_the_oracle_bit_for_bit(M, layout, dtype):
         M.mesa_update_running_params(xs[t], layout, a2, b2, 0.9, False, ws)
         q = torch.empty(n, dtype=torch.int8, device="cuda")
         M.mesa_quantize_update_fused(xs[t], layout, a, b, 0.9, q, ws, mode, 77, 1000 * t)
-        rq, ra, rb = R.quantize_update_fused(xs[t].cpu().numpy(), layout, ra, rb, 0.9, mode, 77, 1000 * t)
-        assert np.array_equal(q.cpu().numpy(), rq.reshape(-1))
-        assert np.array_equal(canon(a.cpu().numpy()), canon(ra)) and np.array_equal(canon(b.cpu().numpy()), canon(rb))
+        rq, ra, rb = R.quantize_update_fused(npy(xs[t]), layout, ra, rb, 0.9, mode, 77, 1000 * t)
+        assert np.array_equal(npy(q), rq.reshape(-1))
+        assert np.array_equal(canon(npy(a)), canon(ra)) and np.array_equal(canon(npy(b)), canon(rb))
         assert torch.equal(q, q2) and torch.equal(a, a2) and torch.equal(b, b2)
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.float16], ids=["f32", "f16"])
+@pytest.mark.parametrize("dtype", DTYPES, ids=DTYPE_IDS)
 def test_per_sample_statistics_through_the_layout_descriptor(M, dtype):
     """One (alpha, beta) pair per sample and head -- the paper's per-sample ablation -- is the layout
     (1, B*H, inner): parameters, codes, softmax backward (B = 1, H = B*H) and GELU backward with more
@@ -320,30 +346,30 @@ def test_per_sample_statistics_through_the_layout_descriptor(M, dtype):
     logits = torch.randn((B, H, N, N), generator=gen, device="cuda") * torch.linspace(0.3, 5.0, G, device="cuda").view(B, H, 1, 1)
     xs = [torch.softmax(logits + 0.1 * t, dim=-1).to(dtype).contiguous() for t in range(2)]
     a, b, ra, rb = run_params(M, xs, lay)
-    assert np.array_equal(canon(a.cpu().numpy()), canon(ra)) and np.array_equal(canon(b.cpu().numpy()), canon(rb))
+    assert np.array_equal(canon(npy(a)), canon(ra)) and np.array_equal(canon(npy(b)), canon(rb))
     assert len(set(np.round(ra, 6))) > G // 2          # the samples really have their own ranges
     q = torch.empty(xs[-1].numel(), dtype=torch.int8, device="cuda")
     M.mesa_quantize_headwise(xs[-1], lay, a, b, q, M.ROUND_STOCHASTIC, 3, 0)
-    rq = R.quantize_headwise(xs[-1].cpu().numpy(), lay, ra, rb, R.ROUND_STOCHASTIC, 3, 0).reshape(-1)
-    assert np.array_equal(q.cpu().numpy(), rq)
+    rq = R.quantize_headwise(npy(xs[-1]), lay, ra, rb, R.ROUND_STOCHASTIC, 3, 0).reshape(-1)
+    assert np.array_equal(npy(q), rq)
     dy = torch.randn((B, H, N, N), generator=gen, device="cuda").to(dtype)
     dx = torch.empty_like(dy)
     M.mesa_softmax_bwd_q(q, 1, G, N, N, a, b, dy, dx)
-    ref = R.softmax_bwd_q(rq, 1, G, N, N, ra, rb, dy.cpu().numpy())
-    assert relerr(dx.cpu().numpy().reshape(ref.shape), ref) <= TOL[dtype]
+    ref = R.softmax_bwd_q(rq, 1, G, N, N, ra, rb, npy(dy))
+    assert relerr(npy(dx).reshape(ref.shape), ref) <= TOL[dtype]
     # GELU input with 96 groups of 40 channels
     lay2 = (50, G, 40)
     x = (torch.randn(lay2, generator=gen, device="cuda") * 1.5).to(dtype).contiguous()
     a2, b2, ra2, rb2 = run_params(M, [x], lay2)
     q2 = torch.empty(x.numel(), dtype=torch.int8, device="cuda")
     M.mesa_quantize_headwise(x, lay2, a2, b2, q2, M.ROUND_NEAREST_EVEN, 0, 0)
-    rq2 = R.quantize_headwise(x.cpu().numpy(), lay2, ra2, rb2, R.ROUND_NEAREST, 0, 0).reshape(-1)
-    assert np.array_equal(q2.cpu().numpy(), rq2)
+    rq2 = R.quantize_headwise(npy(x), lay2, ra2, rb2, R.ROUND_NEAREST, 0, 0).reshape(-1)
+    assert np.array_equal(npy(q2), rq2)
     dy2 = torch.randn(lay2, generator=gen, device="cuda").to(dtype)
     dx2 = torch.empty_like(dy2)
     M.mesa_gelu_bwd_q(q2, lay2, a2, b2, dy2, dx2)
-    ref2 = R.gelu_bwd_q(rq2, lay2, ra2, rb2, dy2.cpu().numpy())
-    assert relerr(dx2.cpu().numpy().reshape(ref2.shape), ref2) <= TOL[dtype]
+    ref2 = R.gelu_bwd_q(rq2, lay2, ra2, rb2, npy(dy2))
+    assert relerr(npy(dx2).reshape(ref2.shape), ref2) <= TOL[dtype]
 
 
 @pytest.mark.parametrize("B,H,N,Dh", [(2, 3, 19, 8), (3, 6, 197, 64), (2, 4, 64, 32), (1, 2, 130, 100), (5, 3, 49, 32), (1, 2, 300, 128), (2, 2, 33, 48), (1, 3, 40, 96), (3, 2, 40, 64), (2, 2, 8, 32), (1, 1, 65, 32), (1, 2, 24, 128), (1, 1, 255, 128), (1, 2, 223, 32), (2, 1, 224, 64), (1, 1, 256, 96)])
@@ -362,24 +388,24 @@ def test_attention_matmul_backward_against_the_oracle(M, B, H, N, Dh):
         a_, b_, ra, rb = run_params(M, [t], lay)
         c = torch.empty(t.numel(), dtype=torch.int8, device="cuda")
         M.mesa_quantize_headwise(t, lay, a_, b_, c, M.ROUND_STOCHASTIC, 11, 0)
-        codes[name], par[name], rcodes[name], rpar[name] = c, (a_, b_), c.cpu().numpy(), (ra, rb)
+        codes[name], par[name], rcodes[name], rpar[name] = c, (a_, b_), npy(c), (ra, rb)
     dO = torch.randn((B, H, N, Dh), generator=gen, device="cuda").to(dtype)
     dA = torch.empty((B, H, N, N), dtype=dtype, device="cuda")
     dV = torch.empty_like(dO)
     M.mesa_attn_av_bwd_q(codes["a"], codes["v"], B, H, N, Dh, *par["a"], *par["v"], dO, dA, dV)
-    rdA, rdV = R.attn_av_bwd_q(rcodes["a"], rcodes["v"], B, H, N, Dh, *rpar["a"], *rpar["v"], dO.cpu().numpy())
-    rep = {"dA": relerr(dA.cpu().numpy(), rdA), "dV": relerr(dV.cpu().numpy(), rdV)}
+    rdA, rdV = R.attn_av_bwd_q(rcodes["a"], rcodes["v"], B, H, N, Dh, *rpar["a"], *rpar["v"], npy(dO))
+    rep = {"dA": relerr(npy(dA), rdA), "dV": relerr(npy(dV), rdV)}
     dS = torch.empty_like(dA)
     M.mesa_softmax_bwd_q(codes["a"], B, H, N, N, *par["a"], dA, dS)
     dQ = torch.empty_like(dO)
     dK = torch.empty_like(dO)
     M.mesa_attn_qk_bwd_q(codes["q"], codes["k"], B, H, N, Dh, *par["q"], *par["k"], dS, scale, dQ, dK)
-    rdQ, rdK = R.attn_qk_bwd_q(rcodes["q"], rcodes["k"], B, H, N, Dh, *rpar["q"], *rpar["k"], dS.cpu().numpy(), scale)
-    rep["dQ"], rep["dK"] = relerr(dQ.cpu().numpy(), rdQ), relerr(dK.cpu().numpy(), rdK)
+    rdQ, rdK = R.attn_qk_bwd_q(rcodes["q"], rcodes["k"], B, H, N, Dh, *rpar["q"], *rpar["k"], npy(dS), scale)
+    rep["dQ"], rep["dK"] = relerr(npy(dQ), rdQ), relerr(npy(dK), rdK)
     assert all(v <= TOL[dtype] for v in rep.values()), rep
 
 
-@pytest.mark.parametrize("dtype", [torch.float16, torch.float32])
+@pytest.mark.parametrize("dtype", DTYPES, ids=DTYPE_IDS)
 @pytest.mark.parametrize("layout", [(3, 4, 1000), (5, 3, 361), (37, 6, 64), (64, 3, 2401), (1, 1, 77)])
 def test_symmetric_range_update_matches_the_oracle_bit_for_bit(M, layout, dtype):
     """Symmetric-range running estimates (Sec. 5.3 ablation): first call and two EMA steps, then the codes
@@ -393,15 +419,15 @@ def test_symmetric_range_update_matches_the_oracle_bit_for_bit(M, layout, dtype)
     ws = ws_for(M, M.OP_UPDATE_RUNNING_PARAMS, *layout, dt=dtype)
     for t, x in enumerate(xs):
         M.mesa_update_running_params_sym(x, layout, a, b, 0.9, t == 0, ws)
-        ra, rb = R.update_running_params_sym(x.cpu().numpy(), layout, ra, rb, 0.9, t == 0)
-        assert np.array_equal(a.cpu().numpy(), ra) and np.array_equal(b.cpu().numpy(), rb), t
+        ra, rb = R.update_running_params_sym(npy(x), layout, ra, rb, 0.9, t == 0)
+        assert np.array_equal(npy(a), ra) and np.array_equal(npy(b), rb), t
     q = torch.empty(xs[-1].numel(), dtype=torch.int8, device="cuda")
     M.mesa_quantize_headwise(xs[-1], layout, a, b, q, M.ROUND_STOCHASTIC, 5, 3)
-    rq = R.quantize_headwise(xs[-1].cpu().numpy(), layout, ra, rb, R.ROUND_STOCHASTIC, 5, 3).reshape(-1)
-    assert np.array_equal(q.cpu().numpy(), rq)
+    rq = R.quantize_headwise(npy(xs[-1]), layout, ra, rb, R.ROUND_STOCHASTIC, 5, 3).reshape(-1)
+    assert np.array_equal(npy(q), rq)
 
 
-@pytest.mark.parametrize("dtype", [torch.float16, torch.float32])
+@pytest.mark.parametrize("dtype", DTYPES, ids=DTYPE_IDS)
 @pytest.mark.parametrize("layout", [(4, 3, 16 * 14 * 14), (5, 3, 361), (3, 40, 77), (1, 1, 1000)])
 def test_relu_backward_is_the_oracles_mask_exactly(M, layout, dtype):
     """ReLU backward at group-wise codes (an (N, C, H, W) activation as (N, G, C/G*H*W)); the 0/1 decision is
@@ -415,14 +441,14 @@ def test_relu_backward_is_the_oracles_mask_exactly(M, layout, dtype):
     dy = torch.randn(layout, generator=gen, device="cuda").to(dtype)
     dx = torch.empty_like(dy)
     M.mesa_relu_bwd_q(q, layout, a, b, dy, dx)
-    ref = R.relu_bwd_q(q.cpu().numpy(), layout, ra, rb, dy.cpu().numpy())
-    got = dx.cpu().numpy().astype(np.float64).reshape(ref.shape)
+    ref = R.relu_bwd_q(npy(q), layout, ra, rb, npy(dy))
+    got = npy(dx).astype(np.float64).reshape(ref.shape)
     assert np.array_equal(got, ref)
     frac = float((ref != 0).mean())
     assert 0.2 < frac < 0.8, frac
 
 
-@pytest.mark.parametrize("dtype", [torch.float16, torch.float32])
+@pytest.mark.parametrize("dtype", DTYPES, ids=DTYPE_IDS)
 @pytest.mark.parametrize("layout", [(37, 6, 256), (5, 3, 361), (64, 12, 128)])
 def test_fixed_offset_update_matches_the_oracle_bit_for_bit(M, layout, dtype):
     """Fixed beta = GELU's minimum (Sec. 6) on a GELU-output-like tensor: three steps, then the codes."""
@@ -436,15 +462,15 @@ def test_fixed_offset_update_matches_the_oracle_bit_for_bit(M, layout, dtype):
     ws = ws_for(M, M.OP_UPDATE_RUNNING_PARAMS, *layout, dt=dtype)
     for t, x in enumerate(xs):
         M.mesa_update_running_params_fixed_beta(x, layout, a, b, 0.9, t == 0, bf, ws)
-        ra, rb = R.update_running_params_fixed_beta(x.cpu().numpy(), layout, ra, 0.9, t == 0, bf)
-        assert np.array_equal(a.cpu().numpy(), ra) and np.array_equal(b.cpu().numpy(), rb), t
+        ra, rb = R.update_running_params_fixed_beta(npy(x), layout, ra, 0.9, t == 0, bf)
+        assert np.array_equal(npy(a), ra) and np.array_equal(npy(b), rb), t
     q = torch.empty(xs[-1].numel(), dtype=torch.int8, device="cuda")
     M.mesa_quantize_headwise(xs[-1], layout, a, b, q, M.ROUND_STOCHASTIC, 9, 1)
-    rq = R.quantize_headwise(xs[-1].cpu().numpy(), layout, ra, rb, R.ROUND_STOCHASTIC, 9, 1).reshape(-1)
-    assert np.array_equal(q.cpu().numpy(), rq)
+    rq = R.quantize_headwise(npy(xs[-1]), layout, ra, rb, R.ROUND_STOCHASTIC, 9, 1).reshape(-1)
+    assert np.array_equal(npy(q), rq)
 
 
-@pytest.mark.parametrize("dtype", [torch.float16, torch.float32])
+@pytest.mark.parametrize("dtype", DTYPES, ids=DTYPE_IDS)
 @pytest.mark.parametrize("layout", [(37, 6, 256), (5, 3, 361), (3, 40, 77), (1, 1, 1003)])
 def test_gelu_layer_forward_in_one_pass(M, layout, dtype):
     """y = gelu(x) within tolerance of the oracle's binary64 GELU; codes of x and the moved estimates bit for bit
@@ -460,13 +486,13 @@ def test_gelu_layer_forward_in_one_pass(M, layout, dtype):
         y = torch.empty_like(x)
         q = torch.empty(x.numel(), dtype=torch.int8, device="cuda")
         M.mesa_gelu_fwd_q(x, layout, a, b, 0.9, y, q, ws, mode, 21, 4)
-        ry, rq, ra, rb = R.gelu_fwd_q(x.cpu().numpy(), layout, ra, rb, 0.9, rmode, 21, 4)
-        assert np.array_equal(q.cpu().numpy(), rq.reshape(-1))
-        assert np.array_equal(a.cpu().numpy(), ra) and np.array_equal(b.cpu().numpy(), rb)
-        assert relerr(y.cpu().numpy(), ry) <= TOL[dtype]
+        ry, rq, ra, rb = R.gelu_fwd_q(npy(x), layout, ra, rb, 0.9, rmode, 21, 4)
+        assert np.array_equal(npy(q), rq.reshape(-1))
+        assert np.array_equal(npy(a), ra) and np.array_equal(npy(b), rb)
+        assert relerr(npy(y), ry) <= TOL[dtype]
 
 
-@pytest.mark.parametrize("dtype", [torch.float16, torch.float32])
+@pytest.mark.parametrize("dtype", DTYPES, ids=DTYPE_IDS)
 @pytest.mark.parametrize("B,H,rows,cols", [(3, 6, 197, 197), (5, 3, 49, 49), (2, 4, 64, 64), (1, 2, 33, 1000), (2, 3, 7, 19), (1, 1, 5, 8)])
 def test_softmax_layer_forward_in_one_pass(M, B, H, rows, cols, dtype):
     """y = softmax(s) within tolerance of the oracle's binary64 softmax and with rows that sum to 1; the codes and
@@ -482,18 +508,18 @@ def test_softmax_layer_forward_in_one_pass(M, B, H, rows, cols, dtype):
         s = (torch.randn((B, H, rows, cols), generator=gen, device="cuda") * sig * (1 + t)).to(dtype).contiguous()
         y = torch.empty_like(s)
         q = torch.empty(s.numel(), dtype=torch.int8, device="cuda")
-        ra, rb = a.cpu().numpy().copy(), b.cpu().numpy().copy()
+        ra, rb = npy(a).copy(), npy(b).copy()
         M.mesa_softmax_fwd_q(s, B, H, rows, cols, a, b, 0.9, y, q, ws, mode, 31, 7)
-        yh = y.cpu().numpy()
-        ref = R.softmax_fwd(s.cpu().numpy(), B * H * rows, cols)
+        yh = npy(y)
+        ref = R.softmax_fwd(npy(s), B * H * rows, cols)
         assert relerr(yh, ref) <= TOL[dtype]
-        assert np.abs(yh.astype(np.float64).sum(-1) - 1.0).max() <= (2e-3 if dtype == torch.float16 else 1e-5)
+        assert np.abs(yh.astype(np.float64).sum(-1) - 1.0).max() <= TOL[dtype]
         rq, ra2, rb2 = R.quantize_update_fused(yh, lay, ra, rb, 0.9, rmode, 31, 7)
-        assert np.array_equal(q.cpu().numpy(), rq.reshape(-1))
-        assert np.array_equal(canon(a.cpu().numpy()), canon(ra2)) and np.array_equal(canon(b.cpu().numpy()), canon(rb2))
+        assert np.array_equal(npy(q), rq.reshape(-1))
+        assert np.array_equal(canon(npy(a)), canon(ra2)) and np.array_equal(canon(npy(b)), canon(rb2))
 
 
-@pytest.mark.parametrize("dtype", [torch.float16, torch.float32])
+@pytest.mark.parametrize("dtype", DTYPES, ids=DTYPE_IDS)
 @pytest.mark.parametrize("Mr,D,G", [(1000, 384, 6), (77, 768, 12), (50, 1024, 4), (33, 64, 2), (19, 8, 1), (300, 96, 3), (5, 520, 1)])
 def test_layernorm_layer_forward_in_one_pass(M, Mr, D, G, dtype):
     """y, mean and rstd within tolerance of the oracle's binary64 LayerNorm; codes of x and the moved estimates bit
@@ -513,12 +539,12 @@ def test_layernorm_layer_forward_in_one_pass(M, Mr, D, G, dtype):
         rstd = torch.empty(Mr, device="cuda")
         q = torch.empty(x.numel(), dtype=torch.int8, device="cuda")
         M.mesa_layernorm_fwd_q(x, Mr, D, G, gamma, bias, 1e-5, a, b, 0.9, y, mean, rstd, q, ws, mode, 13, 5)
-        ry, rmean, rrstd = R.layernorm_fwd(x.cpu().numpy(), Mr, D, gamma.cpu().numpy(), bias.cpu().numpy(), 1e-5)
-        assert relerr(y.cpu().numpy(), ry) <= TOL[dtype]
-        assert relerr(mean.cpu().numpy(), rmean) <= 1e-5 and relerr(rstd.cpu().numpy(), rrstd) <= 1e-5
-        rq, ra, rb = R.quantize_update_fused(x.cpu().numpy(), lay, ra, rb, 0.9, rmode, 13, 5)
-        assert np.array_equal(q.cpu().numpy(), rq.reshape(-1))
-        assert np.array_equal(canon(a.cpu().numpy()), canon(ra)) and np.array_equal(canon(b.cpu().numpy()), canon(rb))
+        ry, rmean, rrstd = R.layernorm_fwd(npy(x), Mr, D, npy(gamma), npy(bias), 1e-5)
+        assert relerr(npy(y), ry) <= TOL[dtype]
+        assert relerr(npy(mean), rmean) <= 1e-5 and relerr(npy(rstd), rrstd) <= 1e-5
+        rq, ra, rb = R.quantize_update_fused(npy(x), lay, ra, rb, 0.9, rmode, 13, 5)
+        assert np.array_equal(npy(q), rq.reshape(-1))
+        assert np.array_equal(canon(npy(a)), canon(ra)) and np.array_equal(canon(npy(b)), canon(rb))
 
 
 def test_empty_inputs_are_a_no_op(M):
