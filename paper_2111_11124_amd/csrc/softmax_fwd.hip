@@ -4,11 +4,12 @@
 //   then for the stored y: codes with the running estimates as they are on entry and this batch's
 //   per-head extrema, from which the estimates are moved afterwards (the single-pass forward).
 //
-// Tiling as in the backward kernel: rows of 197 or 49 elements start at odd byte offsets, so a team (one
-// wave, or the workgroup for long rows) takes R consecutive rows with R*cols a multiple of 8 -- a run of
-// whole, aligned 8-element vectors, read and written flat.  A vector touches at most two rows; its two
-// partial maxima, then its two partial sums, go through LDS, where a group of lanes per row combines
-// them.  The exponentials stay in registers between the passes.
+// Two kernels.  Rows of up to 256 elements (the attention maps of the paper's models: 197, 49): k_softmax_fwd_rows,
+// further down -- tiles staged flat through LDS, a row per group of lanes.  Longer rows: k_softmax_fwd, tiled as
+// the backward kernel: rows start at odd byte offsets, so a team (one wave, or the workgroup for long rows) takes
+// R consecutive rows with R*cols a multiple of 8 -- a run of whole, aligned 8-element vectors, read and written
+// flat.  A vector touches at most two rows; its two partial maxima, then its two partial sums, go through LDS,
+// where a group of lanes per row combines them.  The exponentials stay in registers between the passes.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -257,6 +258,280 @@ __global__ __launch_bounds__(kThreads, kSfWaves) void k_softmax_fwd(const void *
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Short rows (at most 256 elements): a row per group of LPR lanes.
+//
+// A wave owns a tile of R consecutive rows, R * cols a multiple of 8 as above.  Flat phase: the tile's
+// aligned 8-element vectors are read from memory and copied to the wave's LDS region as they lie; the random
+// bits of stochastic rounding are generated per vector (one Philox block covers 8 consecutive elements) and laid
+// out next to them, 16 bits per element in element order.  Row phase: 64 / LPR rows at a time, lane l of a
+// row's group takes elements l, l + LPR, ... into registers (EPL slots); maximum and sum are reductions inside
+// the group; y is rounded to its storage type and written back over the logits, its code next to it.  Flat
+// phase: the finished vectors of y and of the codes leave as aligned 16- and 8-byte stores.  A lane's extrema
+// stay in registers as long as its rows belong to one head.
+// ---------------------------------------------------------------------------------------------
+constexpr int kSrTileElems = 2048;                    // elements of a wave's tile at most
+constexpr int kSrFlat = kSrTileElems / kVec / 64;     // vectors per lane in the flat phases
+constexpr int kSrMaxCols = 256;
+constexpr int kSrWaves = 4;                           // waves per SIMD the register budget is set for
+constexpr int kSrSlack = 1024;                        // bytes past the last region that unused slots may read
+
+template <int WIDTH, bool MAX> __device__ __forceinline__ float lanes_extreme_dpp(float v)
+{
+    static_assert(WIDTH == 8 || WIDTH == 16, "lane groups inside a DPP row");
+    v = MAX ? vmax(v, dpp_move<0xB1>(v)) : vmin(v, dpp_move<0xB1>(v));      // quad_perm [1,0,3,2]
+    v = MAX ? vmax(v, dpp_move<0x4E>(v)) : vmin(v, dpp_move<0x4E>(v));      // quad_perm [2,3,0,1]
+    v = MAX ? vmax(v, dpp_move<0x141>(v)) : vmin(v, dpp_move<0x141>(v));    // row_half_mirror
+    if (WIDTH >= 16) v = MAX ? vmax(v, dpp_move<0x140>(v)) : vmin(v, dpp_move<0x140>(v));   // row_mirror
+    return v;
+}
+
+// one staged element <-> binary32; put() returns the value as stored
+template <typename T> struct LdsElem;
+template <> struct LdsElem<_Float16> {
+    __device__ static __forceinline__ float get(const unsigned char *p) { return float(*reinterpret_cast<const _Float16 *>(p)); }
+    __device__ static __forceinline__ float put(unsigned char *p, float v)
+    {
+        const _Float16 h = _Float16(v);
+        *reinterpret_cast<_Float16 *>(p) = h;
+        return float(h);
+    }
+};
+template <> struct LdsElem<__bf16> {
+    __device__ static __forceinline__ float get(const unsigned char *p)
+    {
+        return __uint_as_float(uint32_t(*reinterpret_cast<const uint16_t *>(p)) << 16);
+    }
+    __device__ static __forceinline__ float put(unsigned char *p, float v)
+    {
+        const __bf16 h = __bf16(v);
+        const uint16_t bits = __builtin_bit_cast(uint16_t, h);
+        *reinterpret_cast<uint16_t *>(p) = bits;
+        return __uint_as_float(uint32_t(bits) << 16);
+    }
+};
+template <> struct LdsElem<float> {
+    __device__ static __forceinline__ float get(const unsigned char *p) { return *reinterpret_cast<const float *>(p); }
+    __device__ static __forceinline__ float put(unsigned char *p, float v)
+    {
+        *reinterpret_cast<float *>(p) = v;
+        return v;
+    }
+};
+
+// TIGHT: cols > LPR * (EPL - 1), so only the last slot of a lane can lie beyond the row's end
+template <typename T, int LPR, int EPL, bool TIGHT, bool SR>
+__global__ __launch_bounds__(kThreads, kSrWaves) void k_softmax_fwd_rows(const void *__restrict__ s_in, void *__restrict__ y,
+                                                                  int8_t *__restrict__ q, int64_t total_rows, uint32_t cols,
+                                                                  uint32_t R, int64_t tiles, FastDiv div_rows, FastDiv div_heads,
+                                                                  const float *__restrict__ alpha, const float *__restrict__ beta,
+                                                                  uint64_t seed, uint64_t offset, float *__restrict__ part,
+                                                                  uint32_t tab_bytes, uint32_t wave_bytes)
+{
+    constexpr int kB = Store<T>::kBytes;
+    constexpr int RPP = 64 / LPR;                        // rows per pass
+    constexpr int kWaves = kThreads / 64;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const uint32_t heads = div_heads.d;
+    float2 *head_tab = reinterpret_cast<float2 *>(smem);              // (255 / alpha, beta) per head
+    int *lmn = reinterpret_cast<int *>(smem + heads * sizeof(float2));
+    int *lmx = lmn + heads;
+    for (uint32_t h = threadIdx.x; h < heads; h += kThreads) {
+        const float a = alpha[h];
+        head_tab[h] = make_float2(a > 0.0f ? 255.0f / a : 0.0f, beta[h]);
+        lmn[h] = order_key(__builtin_inff());
+        lmx[h] = order_key(-__builtin_inff());
+    }
+    __syncthreads();
+
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const uint32_t sub = lane / LPR, l = lane % LPR;
+    const uint32_t tile_cap = R * cols;                  // elements of a whole tile, a multiple of 8
+    unsigned char *xs = smem + tab_bytes + wave * wave_bytes;         // logits, then y
+    unsigned char *ns = xs + tile_cap * kB;                           // 16 random bits per element
+    unsigned char *qs = ns + (SR ? tile_cap * 2 : 0);                 // codes
+
+    uint32_t cur_h = 0;
+    float mn = __builtin_inff(), mx = -__builtin_inff();              // extrema of this lane's elements of head cur_h
+    auto flush = [&]() {                                              // a whole lane group at a time
+        const float a = lanes_extreme_dpp<LPR, false>(mn), b = lanes_extreme_dpp<LPR, true>(mx);
+        if (l == 0 && a <= b) {
+            atomicMin(&lmn[cur_h], order_key(a));
+            atomicMax(&lmx[cur_h], order_key(b));
+        }
+    };
+
+    // The whole vectors of a tile are fetched one tile ahead: the loads are issued before the row phase of
+    // the tile before and have arrived when it ends.
+    typename Store<T>::raw_t raw[kSrFlat];
+    auto fetch = [&](int64_t t) {
+        const int64_t row0 = t * R;
+        const uint32_t nrows = uint32_t((total_rows - row0 < int64_t(R)) ? (total_rows - row0) : int64_t(R));
+        const uint32_t nfull = nrows * cols / kVec;
+#pragma unroll
+        for (int u = 0; u < kSrFlat; ++u) {
+            const uint32_t v = u * 64 + lane;
+            if (v < nfull) raw[u] = Nt<T>::load(s_in, row0 * cols + v * kVec);
+        }
+    };
+    const int64_t tile_step = int64_t(gridDim.x) * kWaves;
+    int64_t tile = int64_t(blockIdx.x) * kWaves + wave;
+    if (tile < tiles) fetch(tile);
+    for (; tile < tiles; tile += tile_step) {
+        const int64_t row0 = tile * R;
+        const uint32_t nrows = uint32_t((total_rows - row0 < int64_t(R)) ? (total_rows - row0) : int64_t(R));
+        const uint32_t nelem = nrows * cols;
+        const uint32_t nvec = (nelem + kVec - 1) / kVec;
+        const int64_t e0 = row0 * cols;                  // a multiple of 8
+
+        // flat: random bits and the fetched logits -> LDS
+        const uint32_t nfull = nelem / kVec, tail = nelem % kVec;    // a tail: only at the end of the whole tensor
+        if (lane < tail) LdsElem<T>::put(xs + (nfull * kVec + lane) * kB, Store<T>::load1(s_in, e0 + nfull * kVec + lane));
+        if (SR) {
+#pragma unroll 1   // one block at a time: four interleaved generators would not fit the register budget
+            for (int u = 0; u < kSrFlat; ++u) {
+                const uint32_t v = u * 64 + lane;
+                if (v < nvec) {
+                    const uint64_t counter = offset + uint64_t(e0 >> 3) + v;
+                    uint32_t w[4];
+                    philox4x32_10(uint32_t(counter), uint32_t(counter >> 32), uint32_t(seed), uint32_t(seed >> 32), w);
+                    const u32x4 w4 = {w[0], w[1], w[2], w[3]};
+                    *reinterpret_cast<u32x4 *>(ns + v * 16) = w4;     // element e's bits: halfword e of the block
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kSrFlat; ++u) {
+            const uint32_t v = u * 64 + lane;
+            if (v < nfull) Store<T>::store(xs, int64_t(v) * kVec, raw[u]);
+        }
+        team_sync<64>();
+        if (tile + tile_step < tiles) fetch(tile + tile_step);
+
+        // rows
+        for (uint32_t p0 = 0; p0 < nrows; p0 += RPP) {
+            const uint32_t r = p0 + sub;
+            const bool live = r < nrows;
+            const uint32_t eb = (live ? r : p0) * cols + l;           // groups without a row repeat the pass's first
+            // slot k is a constant distance from the lane's first element: one address register per array
+            unsigned char *xp = xs + eb * kB;
+            const unsigned char *np = ns + eb * 2;
+            unsigned char *qp = qs + eb;
+            float x[EPL];
+#pragma unroll
+            for (int k = 0; k < EPL; ++k) {
+                const float v = LdsElem<T>::get(xp + k * LPR * kB);
+                const bool valid = (TIGHT && k < EPL - 1) || l + k * LPR < cols;
+                x[k] = valid ? v : -__builtin_inff();
+            }
+            // the random bits are read before anything is written back: reads after a write to the same
+            // array would each wait for it
+            uint32_t bits[EPL];
+            if (SR) {
+#pragma unroll
+                for (int k = 0; k < EPL; ++k) bits[k] = *reinterpret_cast<const uint16_t *>(np + k * LPR * 2);   // unused slots: discarded
+            }
+            float m = x[0];
+#pragma unroll
+            for (int k = 1; k < EPL; ++k) m = vmax(m, x[k]);
+            m = lanes_extreme_dpp<LPR, true>(m);
+            const float ml = m * 1.4426950408889634f;
+            float sum = 0.0f;
+#pragma unroll
+            for (int k = 0; k < EPL; ++k) {
+                x[k] = __builtin_amdgcn_exp2f(__builtin_fmaf(x[k], 1.4426950408889634f, -ml));   // 0 in unused slots
+                sum += x[k];
+            }
+            sum = lanes_sum_dpp<LPR>(sum);
+            const float inv = 1.0f / sum;
+            if (live) {
+                const uint32_t grow = uint32_t(row0) + r;
+                const uint32_t slab = fastdiv(grow, div_rows);
+                const uint32_t h = slab - fastdiv(slab, div_heads) * heads;
+                if (h != cur_h) {
+                    flush();
+                    cur_h = h;
+                    mn = __builtin_inff();
+                    mx = -__builtin_inff();
+                }
+                const float2 prm = head_tab[h];
+#pragma unroll
+                for (int k = 0; k < EPL; ++k) {
+                    const bool valid = (TIGHT && k < EPL - 1) || l + k * LPR < cols;
+                    if (valid) {
+                        const float f = LdsElem<T>::put(xp + k * LPR * kB, x[k] * inv);   // y as stored
+                        const float w = quantize_one<SR>(f, prm.x, prm.y, SR ? float(bits[k]) : 0.0f);
+                        qp[k * LPR] = (unsigned char)(__builtin_amdgcn_cvt_pk_u8_f32(w, 0, 0u) ^ 0x80u);   // saturates to [0, 255]
+                        mn = vmin(mn, f);
+                        mx = vmax(mx, f);
+                    }
+                }
+            }
+        }
+        team_sync<64>();
+
+        // flat: LDS -> memory
+#pragma unroll
+        for (int u = 0; u < kSrFlat; ++u) {
+            const uint32_t v = u * 64 + lane;
+            if (v < nfull) {
+                const uint32_t le = v * kVec;
+                Nt<T>::store(y, e0 + le, Store<T>::load(xs, int64_t(le)));
+                nt_store<u32x2>(q + e0 + le, *reinterpret_cast<const u32x2 *>(qs + le));
+            }
+        }
+        if (lane < tail) {
+            const uint32_t le = nfull * kVec + lane;
+            Store<T>::store1(y, e0 + le, LdsElem<T>::get(xs + le * kB));   // exact: the value is already of type T
+            q[e0 + le] = int8_t(qs[le]);
+        }
+        team_sync<64>();   // the next tile rewrites the region
+    }
+    flush();
+    __syncthreads();
+    float *out = part + int64_t(blockIdx.x) * 2 * heads;
+    for (uint32_t h = threadIdx.x; h < heads; h += kThreads) {
+        out[h] = order_val(lmn[h]);
+        out[heads + h] = order_val(lmx[h]);
+    }
+}
+
+struct SrPlan {
+    bool ok, tight;
+    int lpr, epl, grid;
+    int64_t R, tiles;
+    uint32_t tab_bytes, wave_bytes;
+    size_t lds;
+};
+
+static SrPlan sr_plan(int64_t total_rows, int64_t H, int64_t cols, int elem_bytes, bool sr)
+{
+    SrPlan p{};
+    if (cols > kSrMaxCols) return p;
+    if (cols <= 56) { p.lpr = 8; p.epl = 7; }
+    else if (cols <= 104) { p.lpr = 8; p.epl = 13; }
+    else if (cols <= 200) { p.lpr = 8; p.epl = 25; }
+    else { p.lpr = 16; p.epl = 16; }
+    p.tight = cols > int64_t(p.lpr) * (p.epl - 1);
+    int64_t gc = cols, b8 = 8;
+    while (b8) { int64_t t = gc % b8; gc = b8; b8 = t; }
+    const int64_t unit = 8 / gc, rpp = 64 / p.lpr;
+    const int64_t step = unit > rpp ? unit : rpp;          // whole vectors per tile, whole passes
+    p.R = (kSrTileElems / cols) / step * step;             // step * cols <= 8 * 256
+    if (p.R > total_rows) p.R = ceil_div(total_rows, step) * step;
+    p.tiles = ceil_div(total_rows, p.R);
+    p.tab_bytes = uint32_t((H * 16 + 15) / 16 * 16);
+    p.wave_bytes = uint32_t((p.R * cols * (elem_bytes + (sr ? 2 : 0) + 1) + 15) / 16 * 16);
+    p.lds = size_t(p.tab_bytes) + size_t(kThreads / 64) * p.wave_bytes + kSrSlack;
+    p.ok = p.lds <= 64 * 1024;
+    if (!p.ok) return p;
+    int64_t per_cu = int64_t(160 * 1024) / int64_t(p.lds);
+    if (per_cu > kSrWaves) per_cu = kSrWaves;
+    const int64_t wgs = ceil_div(p.tiles, kThreads / 64), resident = 256 * per_cu;
+    p.grid = int(wgs < resident ? wgs : resident);
+    return p;
+}
+
 // tiles, grid and workspace of k_softmax_fwd
 struct SfPlan {
     bool ok, wave_tiles;
@@ -285,12 +560,22 @@ static SfPlan sf_plan(int64_t total_rows, int64_t cols)
     return p;
 }
 
+// enough for whichever kernel, storage type and rounding mode the call will use
 size_t softmax_fwd_ws_bytes(int64_t total_rows, int64_t H, int64_t cols)
 {
-    if (total_rows <= 0 || H <= 0 || cols < kVec || H > kSfMaxHeads || total_rows >= (int64_t(1) << 31)) return 16;
-    const SfPlan p = sf_plan(total_rows, cols);
-    if (!p.ok) return 16;
-    return size_t(p.grid) * 2 * size_t(H) * sizeof(float) + 16;
+    if (total_rows <= 0 || H <= 0 || cols <= 0 || H > kSfMaxHeads || total_rows >= (int64_t(1) << 31)) return 16;
+    int grid = 0;
+    for (int eb = 2; eb <= 4; eb += 2)
+        for (int sr = 0; sr < 2; ++sr) {
+            const SrPlan r = sr_plan(total_rows, H, cols, eb, sr != 0);
+            if (r.ok && r.grid > grid) grid = r.grid;
+        }
+    if (cols >= kVec) {
+        const SfPlan p = sf_plan(total_rows, cols);
+        if (p.ok && p.grid > grid) grid = p.grid;
+    }
+    if (grid == 0) return 16;
+    return size_t(grid) * 2 * size_t(H) * sizeof(float) + 16;
 }
 
 }  // namespace mesa
@@ -308,17 +593,45 @@ extern "C" MESA_EXPORT mesa_status mesa_softmax_fwd_q(const void *s_in, int64_t 
     if (!s_in || !y || !q || !alpha || !beta || !aligned16(s_in) || !aligned16(y) || !aligned16(q) || !aligned4(alpha) ||
         !aligned4(beta) || y == s_in)
         return MESA_ERR_INVALID_ARG;
-    if (H > kSfMaxHeads || rows >= (int64_t(1) << 31) || cols < kVec) return MESA_ERR_UNSUPPORTED;
+    if (H > kSfMaxHeads || rows >= (int64_t(1) << 31)) return MESA_ERR_UNSUPPORTED;
     const long double tr = (long double)B * (long double)H * (long double)rows;
     if (tr >= 2147483648.0L) return MESA_ERR_UNSUPPORTED;
     const int64_t total_rows = B * H * rows;
-    const SfPlan p = sf_plan(total_rows, cols);
-    if (!p.ok) return MESA_ERR_UNSUPPORTED;
+    const bool sr = mode == MESA_ROUND_STOCHASTIC;
+    const SrPlan rp = sr_plan(total_rows, H, cols, dtype_bytes(dt), sr);
+    SfPlan p{};
+    if (!rp.ok) {
+        if (cols < kVec) return MESA_ERR_UNSUPPORTED;
+        p = sf_plan(total_rows, cols);
+        if (!p.ok) return MESA_ERR_UNSUPPORTED;
+    }
     if (!ws || !aligned16(ws) || ws_bytes < softmax_fwd_ws_bytes(total_rows, H, cols)) return MESA_ERR_WORKSPACE;
     FastDiv dc = make_fastdiv(uint32_t(cols)), dr = make_fastdiv(uint32_t(rows)), dh = make_fastdiv(uint32_t(H));
     hipStream_t s = static_cast<hipStream_t>(stream);
     float *part = static_cast<float *>(ws);
-    const bool sr = mode == MESA_ROUND_STOCHASTIC;
+    if (rp.ok) {
+#define MESA_LAUNCH_SR(T, LPR_, EPL_, TIGHT_, SR_) \
+    hipLaunchKernelGGL((k_softmax_fwd_rows<T, LPR_, EPL_, TIGHT_, SR_>), dim3(rp.grid), dim3(kThreads), rp.lds, s, s_in, y, q, total_rows, \
+                       uint32_t(cols), uint32_t(rp.R), rp.tiles, dr, dh, alpha, beta, seed, offset, part, rp.tab_bytes, rp.wave_bytes)
+#define MESA_LAUNCH_SR_M(T, LPR_, EPL_, TIGHT_) \
+    do { if (sr) MESA_LAUNCH_SR(T, LPR_, EPL_, TIGHT_, true); else MESA_LAUNCH_SR(T, LPR_, EPL_, TIGHT_, false); } while (0)
+#define MESA_LAUNCH_SR_C(T, LPR_, EPL_) \
+    do { if (rp.tight) MESA_LAUNCH_SR_M(T, LPR_, EPL_, true); else MESA_LAUNCH_SR_M(T, LPR_, EPL_, false); } while (0)
+#define MESA_LAUNCH_SR_T(T) \
+    do { \
+        if (rp.lpr == 16) MESA_LAUNCH_SR_C(T, 16, 16); \
+        else if (rp.epl == 25) MESA_LAUNCH_SR_C(T, 8, 25); \
+        else if (rp.epl == 13) MESA_LAUNCH_SR_C(T, 8, 13); \
+        else MESA_LAUNCH_SR_C(T, 8, 7); \
+    } while (0)
+        MESA_FOR_DTYPE(dt, MESA_LAUNCH_SR_T);
+#undef MESA_LAUNCH_SR_T
+#undef MESA_LAUNCH_SR_C
+#undef MESA_LAUNCH_SR_M
+#undef MESA_LAUNCH_SR
+        launch_ema_finalize(part, rp.grid, uint32_t(H), alpha, beta, lambda, 0, 0, 0.0f, s);
+        return launch_status();
+    }
 #define MESA_LAUNCH_SF(T, TPT_, SR_) \
     hipLaunchKernelGGL((k_softmax_fwd<T, TPT_, SR_>), dim3(p.grid), dim3(kThreads), 0, s, s_in, y, q, total_rows, uint32_t(cols), \
                        uint32_t(p.R), p.tiles, dc, dr, dh, alpha, beta, seed, offset, part)

@@ -71,7 +71,8 @@ def test_argument_errors_are_reported_before_any_launch(M):
     assert L.mesa_gelu_fwd_q(P, M.F16, lay, P, P, 0.9, P2, P, 0, 0, 0, P, 8, None) == M.ERR_WORKSPACE
     assert L.mesa_softmax_fwd_q(P, 2, 3, 19, 19, P, P, 0.9, P, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_INVALID_ARG   # y aliases s
     assert L.mesa_softmax_fwd_q(P, 2, 3, 19, 19, P, P, 0.9, P2, P, 0, 0, 0, P, 8, M.F16, None) == M.ERR_WORKSPACE
-    assert L.mesa_softmax_fwd_q(P, 2, 3, 19, 5, P, P, 0.9, P2, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_UNSUPPORTED  # rows shorter than a vector
+    assert L.mesa_softmax_fwd_q(P, 2, 3, 19, 3001, P, P, 0.9, P2, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_UNSUPPORTED  # 8 odd rows exceed a tile
+    assert L.mesa_softmax_fwd_q(P, 2, 2000, 19, 19, P, P, 0.9, P2, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_UNSUPPORTED  # heads
     assert L.mesa_softmax_fwd_q(P, 2, 3, 19, 19, P, P, 1.5, P2, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_INVALID_ARG  # lambda
     assert M.workspace_bytes(M.OP_SOFTMAX_FWD_Q, 128 * 6 * 197, 6, 197, M.F16) >= 768 * 2 * 6 * 4
     F = C.c_float

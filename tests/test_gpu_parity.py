@@ -493,7 +493,9 @@ def test_gelu_layer_forward_in_one_pass(M, layout, dtype):
 
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=DTYPE_IDS)
-@pytest.mark.parametrize("B,H,rows,cols", [(3, 6, 197, 197), (5, 3, 49, 49), (2, 4, 64, 64), (1, 2, 33, 1000), (2, 3, 7, 19), (1, 1, 5, 8)])
+@pytest.mark.parametrize("B,H,rows,cols", [(3, 6, 197, 197), (5, 3, 49, 49), (2, 4, 64, 64), (1, 2, 33, 1000), (2, 3, 7, 19), (1, 1, 5, 8),
+                                           (2, 2, 9, 3), (1, 3, 11, 57), (2, 1, 13, 104), (1, 2, 30, 105), (3, 1, 5, 200), (1, 2, 17, 201),
+                                           (2, 2, 6, 256), (1, 2, 10, 257), (40, 3, 61, 61)])
 def test_softmax_layer_forward_in_one_pass(M, B, H, rows, cols, dtype):
     """y = softmax(s) within tolerance of the oracle's binary64 softmax and with rows that sum to 1; the codes and
     the moved estimates are exactly the oracle's single-pass forward applied to the y the kernel stored
