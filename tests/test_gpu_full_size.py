@@ -237,3 +237,73 @@ def test_attention_products_backward_full_size_sampled(M, number):
         for name, got, ref in (("dA", dA, rdA), ("dV", dV, rdV), ("dQ", dQ, rdQ), ("dK", dK, rdK)):
             rep[(name, b)] = relerr(got[sl].cpu().numpy(), ref)
     assert all(v <= TOL[spec.dtype] for v in rep.values()), rep
+
+
+@pytest.mark.parametrize("number", [2, 3])
+def test_layer_forwards_full_size(M, number):
+    """The three layer-forward calls on the configuration's full tensors, two steps each (the second with moved
+    estimates): outputs against the oracle in full, codes and parameters bit for bit -- for the softmax against the
+    oracle's single-pass forward applied to the y the kernel stored."""
+    spec = W.CONFIGS[number]
+    tol = TOL[spec.dtype]
+    H = spec.heads
+    # softmax
+    B, Hh, rows, cols = spec.attn
+    lay = spec.attn_layout
+    a = torch.full((Hh,), 1.0, device="cuda")
+    b = torch.zeros(Hh, device="cuda")
+    w = torch.empty(max(M.workspace_bytes(M.OP_SOFTMAX_FWD_Q, B * Hh * rows, Hh, cols, M.F16), 16), dtype=torch.uint8, device="cuda")
+    g = torch.Generator(device="cuda").manual_seed(spec.seed)
+    sig = W.head_sigmas(spec).to("cuda").view(1, Hh, 1, 1)
+    for t in range(2):
+        s = (torch.randn(spec.attn, generator=g, device="cuda") * sig).to(spec.dtype)
+        y = torch.empty_like(s)
+        q = torch.empty(s.numel(), dtype=torch.int8, device="cuda")
+        ra, rb = a.cpu().numpy().copy(), b.cpu().numpy().copy()
+        M.mesa_softmax_fwd_q(s, B, Hh, rows, cols, a, b, spec.lam, y, q, w, M.ROUND_STOCHASTIC, 41, t << 40)
+        assert float((y.float().sum(-1) - 1.0).abs().max()) <= tol
+        yh = y.cpu().numpy()
+        assert relerr(yh, R.softmax_fwd(s.cpu().numpy(), B * Hh * rows, cols)) <= tol
+        rq, ra2, rb2 = R.quantize_update_fused(yh, lay, ra, rb, spec.lam, R.ROUND_STOCHASTIC, 41, t << 40)
+        assert np.array_equal(q.cpu().numpy(), rq.reshape(-1))
+        assert np.array_equal(canon(a.cpu().numpy()), canon(ra2)) and np.array_equal(canon(b.cpu().numpy()), canon(rb2))
+        del s, y, q, yh, rq
+    # GELU
+    lay = spec.gelu_layout
+    a = torch.full((H,), 8.0, device="cuda")
+    b = torch.full((H,), -4.0, device="cuda")
+    w = ws(M, M.OP_UPDATE_RUNNING_PARAMS, *lay)
+    for t in range(2):
+        x = W.gelu_input(spec, t, "cuda")
+        y = torch.empty_like(x)
+        q = torch.empty(x.numel(), dtype=torch.int8, device="cuda")
+        ra, rb = a.cpu().numpy().copy(), b.cpu().numpy().copy()
+        M.mesa_gelu_fwd_q(x, lay, a, b, spec.lam, y, q, w, M.ROUND_STOCHASTIC, 42, t << 40)
+        ry, rq, ra2, rb2 = R.gelu_fwd_q(x.cpu().numpy(), lay, ra, rb, spec.lam, R.ROUND_STOCHASTIC, 42, t << 40)
+        assert relerr(y.cpu().numpy(), ry) <= tol
+        assert np.array_equal(q.cpu().numpy(), rq.reshape(-1))
+        assert np.array_equal(canon(a.cpu().numpy()), canon(ra2)) and np.array_equal(canon(b.cpu().numpy()), canon(rb2))
+        del x, y, q, ry, rq
+    # LayerNorm
+    Mr, D = spec.tokens, spec.dim
+    lay = spec.ln_layout
+    a = torch.full((H,), 8.0, device="cuda")
+    b = torch.full((H,), -4.0, device="cuda")
+    w = torch.empty(max(M.workspace_bytes(M.OP_LAYERNORM_FWD_Q, Mr, D, H, M.F16), 16), dtype=torch.uint8, device="cuda")
+    gamma = W.layernorm_gamma(spec, "cuda")
+    bias = (0.1 * torch.randn(D, generator=g, device="cuda")).to(spec.dtype)
+    for t in range(2):
+        x = W.token_matrix(spec, "ln", t, "cuda")
+        y = torch.empty_like(x)
+        mean = torch.empty(Mr, device="cuda")
+        rstd = torch.empty(Mr, device="cuda")
+        q = torch.empty(x.numel(), dtype=torch.int8, device="cuda")
+        ra, rb = a.cpu().numpy().copy(), b.cpu().numpy().copy()
+        M.mesa_layernorm_fwd_q(x, Mr, D, H, gamma, bias, 1e-5, a, b, spec.lam, y, mean, rstd, q, w, M.ROUND_STOCHASTIC, 43, t << 40)
+        xh = x.cpu().numpy()
+        ry, rm, rr = R.layernorm_fwd(xh, Mr, D, gamma.cpu().numpy(), bias.cpu().numpy(), 1e-5)
+        assert relerr(y.cpu().numpy(), ry) <= tol and relerr(mean.cpu().numpy(), rm) <= 1e-5 and relerr(rstd.cpu().numpy(), rr) <= 1e-5
+        rq, ra2, rb2 = R.quantize_update_fused(xh, lay, ra, rb, spec.lam, R.ROUND_STOCHASTIC, 43, t << 40)
+        assert np.array_equal(q.cpu().numpy(), rq.reshape(-1))
+        assert np.array_equal(canon(a.cpu().numpy()), canon(ra2)) and np.array_equal(canon(b.cpu().numpy()), canon(rb2))
+        del x, y, q, xh, ry, rq
