@@ -214,7 +214,7 @@ def cpu_baseline(spec, target_seconds=20.0):
 def attention_matmul_leg(m, spec, steps):
     """Outside the headline figure: backward of the two attention matrix products at head-wise codes
     (mesa_attn_av_bwd_q, mesa_attn_qk_bwd_q) on the configuration's attention shape, synthetic codes."""
-    if spec.dtype != torch.float16:
+    if spec.dtype == torch.float32:
         return None
     B, H, N, _ = spec.attn
     Dh = spec.dim // spec.heads

@@ -48,8 +48,8 @@ typedef enum {
 } mesa_status;
 
 /* Storage type of activations and gradients.  The paper trains with binary16 mixed precision; bfloat16
- * (upper half of a binary32 word, round to nearest even on store) is accepted wherever binary16 is,
- * except by the attention matrix products.  Codes and parameters are decided in binary32 from the
+ * (upper half of a binary32 word, round to nearest even on store) is accepted wherever binary16 is.
+ * Codes and parameters are decided in binary32 from the
  * stored value whatever its type. */
 typedef enum { MESA_F32 = 0, MESA_F16 = 1, MESA_BF16 = 2 } mesa_dtype;
 
@@ -262,8 +262,8 @@ mesa_status mesa_linear_dw_q(const int8_t *xq, int64_t M, int64_t K, int64_t G,
  * Backward of the two matrix products of self-attention at head-wise de-quantized operands, Sec. 3.1
  * Eq. (2) with G_l = the gradient of a matrix product (the "MatMul" rows of the paper's overhead table;
  * Sec. 3.2: the operands are saved as codes with one (alpha, beta) pair per head).  All tensors are
- * (B, H, N, .) contiguous, upstream gradients and results of dt (binary16 only: MESA_F32 and MESA_BF16
- * return MESA_ERR_UNSUPPORTED), accumulation in binary32; any N and Dh (nothing needs to be aligned).
+ * (B, H, N, .) contiguous, upstream gradients and results of dt (binary16 or bfloat16: MESA_F32 returns
+ * MESA_ERR_UNSUPPORTED; the kernels specialised per product are binary16's, bfloat16 runs the general one), accumulation in binary32; any N and Dh (nothing needs to be aligned).
  *
  * O = A V with A the attention map (B,H,N,N) and V (B,H,N,Dh):
  *   dA[i,j] = sum_d dO[i,d] * V_hat[j,d],    dV[j,d] = sum_i A_hat[i,j] * dO[i,d]

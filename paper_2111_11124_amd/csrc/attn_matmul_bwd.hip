@@ -17,7 +17,7 @@
 // vectors inside the extents, single elements and zero fill at the edges, so any extents work) and
 // kept in the operand's own orientation; where that is not the orientation the MFMA wants, the
 // fragments come from the LDS transpose reads.  The next stage's loads are in flight while a stage
-// is multiplied.  binary16 tensors only.
+// is multiplied.  binary16 tensors; bfloat16 tensors through the general kernel (k_bmm_q) only.
 #include <hip/hip_runtime.h>
 
 #include "api_util.hpp"
@@ -55,8 +55,50 @@ __device__ __forceinline__ bm_v8h bm_codes_to_half8(bm_v2i raw)
     return out;
 }
 
+// What the 16-bit number type decides in the general kernel: how codes become matrix-core operands and which
+// value of the code is contracted (kCentre: c in "operand = x_bar - c"; bfloat16 has no spare mantissa bit for
+// the exponent trick and takes x_bar = q + 128 itself, byte -> binary32 -> upper half), the fragment of ones,
+// the MFMA and the rounding of a result.  Operands travel as raw 16-bit lanes (bm_v8h as a container).
+typedef __bf16 bm_v8b __attribute__((ext_vector_type(8)));
+template <typename ET> struct BmNum;
+template <> struct BmNum<_Float16> {
+    static constexpr float kCentre = 128.0f;
+    static constexpr uint16_t kOne = 0x3C00u;
+    __device__ static __forceinline__ bm_v8h codes8(bm_v2i raw) { return bm_codes_to_half8(raw); }
+    __device__ static __forceinline__ bm_v16f mfma(bm_v8h a, bm_v8h b, bm_v16f c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+    }
+    __device__ static __forceinline__ _Float16 round(float v) { return (_Float16)v; }
+};
+template <> struct BmNum<__bf16> {
+    static constexpr float kCentre = 0.0f;
+    static constexpr uint16_t kOne = 0x3F80u;
+    __device__ static __forceinline__ bm_v8h codes8(bm_v2i raw)
+    {
+        bm_v4u out;
+#pragma unroll
+        for (int w = 0; w < 2; ++w) {
+            const uint32_t x = uint32_t(raw[w]) ^ 0x80808080u;
+            const uint32_t f0 = __float_as_uint(float(x & 0xFFu)), f1 = __float_as_uint(float((x >> 8) & 0xFFu));
+            const uint32_t f2 = __float_as_uint(float((x >> 16) & 0xFFu)), f3 = __float_as_uint(float(x >> 24));
+            out[2 * w] = __builtin_amdgcn_perm(f1, f0, 0x07060302u);
+            out[2 * w + 1] = __builtin_amdgcn_perm(f3, f2, 0x07060302u);
+        }
+        return __builtin_bit_cast(bm_v8h, out);
+    }
+    __device__ static __forceinline__ bm_v16f mfma(bm_v8h a, bm_v8h b, bm_v16f c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bm_v8b, a), __builtin_bit_cast(bm_v8b, b), c, 0, 0, 0);
+    }
+    __device__ static __forceinline__ _Float16 round(float v)   // the bits of the bfloat16, in the 16-bit container
+    {
+        return __builtin_bit_cast(_Float16, __bf16(v));
+    }
+};
+
 struct BmmArgs {
-    const _Float16 *x;          // the plain operand
+    const _Float16 *x;          // the plain operand (16-bit container: binary16 or bfloat16 bits)
     const int8_t *y;            // the coded operand
     _Float16 *c;                // output, row-major R x Cn per batch
     int64_t x_batch, y_batch, c_batch;   // elements per (sample, head)
@@ -184,17 +226,17 @@ template <bool CODED, bool TFAST> struct BmOperand {
     }
     // the MFMA operand of a wave's 32 lines starting at l0, contraction slots 16*ks ..+15: lane l holds line
     // l%32 and the eight slots 8*(l/32) ..+7
-    __device__ static __forceinline__ bm_v8h frag(const unsigned char *lds, int l0, int ks, int lane)
+    template <typename ET> __device__ static __forceinline__ bm_v8h frag(const unsigned char *lds, int l0, int ks, int lane)
     {
         if (TFAST) {
             const unsigned char *p = lds + (l0 + (lane & 31)) * kPitch + (ks * 16 + (lane >> 5) * 8) * kEb;
-            if (CODED) return bm_codes_to_half8(*reinterpret_cast<const bm_v2i *>(p));
+            if (CODED) return BmNum<ET>::codes8(*reinterpret_cast<const bm_v2i *>(p));
             return *reinterpret_cast<const bm_v8h *>(p);
         }
         const int blk = lane >> 4, sl = lane & 15;
         if (CODED) {
             const unsigned char *p = lds + (ks * 16 + (blk >> 1) * 8 + (sl >> 1)) * kPitch + l0 + (blk & 1) * 16 + (sl & 1) * 8;
-            return bm_codes_to_half8(__builtin_amdgcn_ds_read_tr8_b64_v2i32(BM_LDS3(bm_v2i, p)));
+            return BmNum<ET>::codes8(__builtin_amdgcn_ds_read_tr8_b64_v2i32(BM_LDS3(bm_v2i, p)));
         }
         const unsigned char *p = lds + (ks * 16 + (blk >> 1) * 8 + (sl >> 2)) * kPitch + (l0 + (blk & 1) * 16 + (sl & 3) * 4) * 2;
         const bm_v4h lo = __builtin_bit_cast(bm_v4h, __builtin_amdgcn_ds_read_tr16_b64_v4i16(BM_LDS3(bm_v4s, p)));
@@ -204,8 +246,9 @@ template <bool CODED, bool TFAST> struct BmOperand {
 };
 
 // P_CODED: P is the coded operand (else Q).  P_TFAST / Q_TFAST: the contraction index is the unit-stride
-// index of that operand in memory.
-template <bool P_CODED, bool P_TFAST, bool Q_TFAST>
+// index of that operand in memory.  ET: _Float16 or __bf16 (the tensors' 16-bit type; BmmArgs carries them as
+// 16-bit containers).
+template <bool P_CODED, bool P_TFAST, bool Q_TFAST, typename ET>
 __global__ __launch_bounds__(kThreads, 6) void k_bmm_q(BmmArgs a)
 {
     typedef BmOperand<P_CODED, P_TFAST> OP;
@@ -236,7 +279,7 @@ __global__ __launch_bounds__(kThreads, 6) void k_bmm_q(BmmArgs a)
     for (int v = 0; v < 16; ++v) { acc[v] = 0.0f; acc1[v] = 0.0f; }
     bm_v8h ones;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) ones[j] = (_Float16)1.0f;
+    for (int j = 0; j < 8; ++j) ones[j] = __builtin_bit_cast(_Float16, BmNum<ET>::kOne);
 
     BmRaw<P_CODED> pv[kBmParts];
     BmRaw<!P_CODED> qv[kBmParts];
@@ -256,16 +299,16 @@ __global__ __launch_bounds__(kThreads, 6) void k_bmm_q(BmmArgs a)
         }
 #pragma unroll
         for (int ks = 0; ks < kBmT / 16; ++ks) {
-            const bm_v8h fa = OP::frag(LP, wr * 32, ks, lane);
-            const bm_v8h fb = OQ::frag(LQ, wc * 32, ks, lane);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa, fb, acc, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(P_CODED ? ones : fa, P_CODED ? fb : ones, acc1, 0, 0, 0);
+            const bm_v8h fa = OP::template frag<ET>(LP, wr * 32, ks, lane);
+            const bm_v8h fb = OQ::template frag<ET>(LQ, wc * 32, ks, lane);
+            acc = BmNum<ET>::mfma(fa, fb, acc);
+            acc1 = BmNum<ET>::mfma(P_CODED ? ones : fa, P_CODED ? fb : ones, acc1);
         }
     }
 
     // lane l, register v of a 32 x 32 tile: row 8*(v/4) + 4*(l/32) + v%4, column l%32
     const float s = a.alpha[h] / 255.0f;
-    const float off = fmaf(128.0f, s, a.beta[h]);
+    const float off = fmaf(BmNum<ET>::kCentre, s, a.beta[h]);
     const int col = c0 + wc * 32 + (lane & 31);
     const int row_l = r0 + wr * 32 + (lane >> 5) * 4;
     // R * Cn < 2^31 (checked by the entry points): 32-bit offsets from the batch's base
@@ -275,12 +318,13 @@ __global__ __launch_bounds__(kThreads, 6) void k_bmm_q(BmmArgs a)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int dr = (v >> 2) * 8 + (v & 3);
-            if (row_l + dr < a.R) cb[o0 + uint32_t(dr) * uint32_t(a.Cn)] = (_Float16)(a.scale * fmaf(s, acc[v], off * acc1[v]));
+            if (row_l + dr < a.R) cb[o0 + uint32_t(dr) * uint32_t(a.Cn)] = BmNum<ET>::round(a.scale * fmaf(s, acc[v], off * acc1[v]));
         }
     }
 }
 
-template <bool P_CODED, bool P_TFAST, bool Q_TFAST> static void launch_bmm(BmmArgs a, int64_t batches, hipStream_t s)
+template <bool P_CODED, bool P_TFAST, bool Q_TFAST, typename ET = _Float16>
+static void launch_bmm(BmmArgs a, int64_t batches, hipStream_t s)
 {
     a.tiles_r = int(ceil_div(a.R, kBmTile));
     a.tiles_c = int(ceil_div(a.Cn, kBmTile));
@@ -289,7 +333,7 @@ template <bool P_CODED, bool P_TFAST, bool Q_TFAST> static void launch_bmm(BmmAr
         a.batch0 = b0;
         a.head0 = int(b0 % a.heads);
         const int64_t nb = batches - b0 < 65535 ? batches - b0 : 65535;
-        hipLaunchKernelGGL((k_bmm_q<P_CODED, P_TFAST, Q_TFAST>), dim3(unsigned(a.tiles_c), unsigned(a.tiles_r), unsigned(nb)),
+        hipLaunchKernelGGL((k_bmm_q<P_CODED, P_TFAST, Q_TFAST, ET>), dim3(unsigned(a.tiles_c), unsigned(a.tiles_r), unsigned(nb)),
                            dim3(kThreads), 0, s, a);
     }
 }
@@ -926,7 +970,7 @@ template <int DT> static void launch_nn(const _Float16 *dS, const int8_t *kq, _F
 static mesa_status check_attn(int64_t B, int64_t H, int64_t N, int64_t Dh, mesa_dtype dt)
 {
     if (!valid_dtype(dt) || B < 0 || H < 0 || N < 0 || Dh < 0) return MESA_ERR_INVALID_ARG;
-    if (dt != MESA_F16) return MESA_ERR_UNSUPPORTED;
+    if (dt == MESA_F32) return MESA_ERR_UNSUPPORTED;
     if (N >= (int64_t(1) << 20) || Dh >= (int64_t(1) << 20)) return MESA_ERR_UNSUPPORTED;
     if ((N > 0 && N < 8) || (Dh > 0 && Dh < 8)) return MESA_ERR_UNSUPPORTED;   // an extent shorter than one load vector
     // 32-bit element offsets inside one (sample, head); the row / column tile counts fit a grid dimension
@@ -963,6 +1007,16 @@ extern "C" MESA_EXPORT mesa_status mesa_attn_av_bwd_q(const int8_t *aq, const in
     a.R = int(N); a.Cn = int(N); a.Tn = int(Dh);
     a.p_rs = Dh; a.p_ts = 1; a.q_ts = 1; a.q_cs = Dh;
     a.alpha = alpha_v; a.beta = beta_v;
+    if (dt == MESA_BF16) {   // bfloat16 tensors: the general kernel for both products
+        launch_bmm<false, true, true, __bf16>(a, batches, s);
+        a.y = aq; a.c = static_cast<_Float16 *>(dV);
+        a.y_batch = N * N; a.c_batch = N * Dh;
+        a.R = int(N); a.Cn = int(Dh); a.Tn = int(N);
+        a.p_rs = 1; a.p_ts = N; a.q_ts = Dh; a.q_cs = 1;
+        a.alpha = alpha_a; a.beta = beta_a;
+        launch_bmm<true, false, false, __bf16>(a, batches, s);
+        return launch_status();
+    }
     // the 32 x N output block has to fit the 64 KiB of LDS a kernel gets by default; else the general kernel
     if (Dh == 32 && da_fits<2>(batches, N))
         launch_da<2>(a.x, vq, a.c, batches, int(N), int(H), alpha_v, beta_v, s);
@@ -1012,6 +1066,14 @@ extern "C" MESA_EXPORT mesa_status mesa_attn_qk_bwd_q(const int8_t *qq, const in
     a.y = kq; a.c = static_cast<_Float16 *>(dQ);
     a.p_rs = N; a.p_ts = 1; a.q_ts = Dh; a.q_cs = 1;
     a.alpha = alpha_k; a.beta = beta_k;
+    if (dt == MESA_BF16) {   // bfloat16 tensors: the general kernel for both products
+        launch_bmm<false, true, false, __bf16>(a, batches, s);
+        a.y = qq; a.c = static_cast<_Float16 *>(dK);
+        a.p_rs = 1; a.p_ts = N; a.q_ts = Dh; a.q_cs = 1;
+        a.alpha = alpha_q; a.beta = beta_q;
+        launch_bmm<false, false, false, __bf16>(a, batches, s);
+        return launch_status();
+    }
     if (nn_fits(N, Dh) && batches < (int64_t(1) << 31)) {
         if (Dh == 32) launch_nn<1>(a.x, kq, a.c, batches, int(N), int(H), scale, alpha_k, beta_k, s);
         else if (Dh == 64) launch_nn<2>(a.x, kq, a.c, batches, int(N), int(H), scale, alpha_k, beta_k, s);

@@ -376,7 +376,16 @@ def test_per_sample_statistics_through_the_layout_descriptor(M, dtype):
 def test_attention_matmul_backward_against_the_oracle(M, B, H, N, Dh):
     """dA, dV of O = A V and dQ, dK of S = scale Q K^T at head-wise codes (binary16), chained through the
     library's own softmax backward as a training step would."""
-    dtype = torch.float16
+    _attention_case(M, B, H, N, Dh, torch.float16)
+
+
+@pytest.mark.parametrize("B,H,N,Dh", [(2, 3, 19, 8), (2, 6, 197, 64), (3, 3, 49, 32), (1, 2, 130, 100), (1, 1, 65, 96), (1, 2, 8, 128)])
+def test_attention_matmul_backward_bfloat16(M, B, H, N, Dh):
+    """The same products on bfloat16 tensors (the general kernel: full and partial tiles in every extent)."""
+    _attention_case(M, B, H, N, Dh, torch.bfloat16)
+
+
+def _attention_case(M, B, H, N, Dh, dtype):
     gen = torch.Generator(device="cuda").manual_seed(B * 1000 + N)
     sig = torch.linspace(0.5, 2.0, H, device="cuda").view(1, H, 1, 1)
     q, k, v = ((torch.randn((B, H, N, Dh), generator=gen, device="cuda") * sig + 0.1 * i).to(dtype).contiguous() for i in range(3))
