@@ -13,6 +13,7 @@
 
 #include "api_util.hpp"
 #include "common.hpp"
+#include "softmax_rows.hpp"
 
 namespace mesa {
 
@@ -278,6 +279,151 @@ __global__ __launch_bounds__(kThreads, kSmWgPerCu) void k_softmax_bwd(const int8
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Rows of at most 256 elements (the attention maps of the paper's models): a row per group of LPR lanes.
+// A wave's tile of codes and dy goes through its LDS region flat, fetched one tile ahead; in the row phase a lane
+// holds its EPL slots of dy and y_hat in registers, the row's d = sum dy*y_hat is a reduction inside the group,
+// and dx is written back over dy in LDS, from where it leaves as aligned vectors.  dx may be dy (in place): a
+// tile's dy is in LDS before any of its dx is stored, and tiles do not overlap.
+// ---------------------------------------------------------------------------------------------
+constexpr int kSbRowWaves = 4;      // waves per SIMD the row kernel's register budget is set for
+
+template <typename T, int LPR, int EPL, bool TIGHT>
+__global__ __launch_bounds__(kThreads, kSbRowWaves) void k_softmax_bwd_rows(const int8_t *__restrict__ yq, const void *dy, void *dx,
+                                                                           int64_t total_rows, uint32_t cols, uint32_t R,
+                                                                           int64_t tiles, FastDiv div_rows, FastDiv div_heads,
+                                                                           const float *__restrict__ alpha,
+                                                                           const float *__restrict__ beta, uint32_t tab_bytes,
+                                                                           uint32_t wave_bytes)
+{
+    constexpr int kB = Store<T>::kBytes;
+    constexpr int RPP = 64 / LPR;                        // rows per pass
+    constexpr int kWaves = kThreads / 64;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const uint32_t heads = div_heads.d;
+    float2 *head_tab = reinterpret_cast<float2 *>(smem);              // y_hat = s * q + off with q the signed code
+    for (uint32_t h = threadIdx.x; h < heads; h += kThreads) {
+        const float s = alpha[h] / 255.0f;
+        head_tab[h] = make_float2(s, fmaf(128.0f, s, beta[h]));
+    }
+    __syncthreads();
+
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const uint32_t sub = lane / LPR, l = lane % LPR;
+    const uint32_t tile_cap = R * cols;                  // elements of a whole tile, a multiple of 8
+    unsigned char *gs = smem + tab_bytes + wave * wave_bytes;         // dy, then dx
+    unsigned char *cs = gs + tile_cap * kB;                           // codes
+
+    typename Store<T>::raw_t raw[kSrFlat];
+    u32x2 rawq[kSrFlat];
+    auto fetch = [&](int64_t t) {
+        const int64_t row0 = t * R;
+        const uint32_t nrows = uint32_t((total_rows - row0 < int64_t(R)) ? (total_rows - row0) : int64_t(R));
+        const uint32_t nfull = nrows * cols / kVec;
+#pragma unroll
+        for (int u = 0; u < kSrFlat; ++u) {
+            const uint32_t v = u * 64 + lane;
+            if (v < nfull) {
+                raw[u] = Nt<T>::load(dy, row0 * cols + v * kVec);
+                rawq[u] = nt_load<u32x2>(yq + row0 * cols + v * kVec);
+            }
+        }
+    };
+    const int64_t tile_step = int64_t(gridDim.x) * kWaves;
+    int64_t tile = int64_t(blockIdx.x) * kWaves + wave;
+    if (tile < tiles) fetch(tile);
+    for (; tile < tiles; tile += tile_step) {
+        const int64_t row0 = tile * R;
+        const uint32_t nrows = uint32_t((total_rows - row0 < int64_t(R)) ? (total_rows - row0) : int64_t(R));
+        const uint32_t nelem = nrows * cols;
+        const int64_t e0 = row0 * cols;                  // a multiple of 8
+        const uint32_t nfull = nelem / kVec, tail = nelem % kVec;    // a tail: only at the end of the whole tensor
+        if (lane < tail) {
+            const uint32_t le = nfull * kVec + lane;
+            LdsElem<T>::put(gs + le * kB, Store<T>::load1(dy, e0 + le));
+            cs[le] = uint8_t(yq[e0 + le]);
+        }
+#pragma unroll
+        for (int u = 0; u < kSrFlat; ++u) {
+            const uint32_t v = u * 64 + lane;
+            if (v < nfull) {
+                Store<T>::store(gs, int64_t(v) * kVec, raw[u]);
+                *reinterpret_cast<u32x2 *>(cs + v * kVec) = rawq[u];
+            }
+        }
+        team_sync<64>();
+        if (tile + tile_step < tiles) fetch(tile + tile_step);
+
+        for (uint32_t p0 = 0; p0 < nrows; p0 += RPP) {
+            const uint32_t r = p0 + sub;
+            const bool live = r < nrows;
+            const uint32_t rr = live ? r : p0;                        // groups without a row repeat the pass's first
+            const uint32_t eb = rr * cols + l;
+            unsigned char *gp = gs + eb * kB;
+            const unsigned char *cp = cs + eb;
+            const uint32_t grow = uint32_t(row0) + rr;
+            const uint32_t slab = fastdiv(grow, div_rows);
+            const float2 prm = head_tab[slab - fastdiv(slab, div_heads) * heads];
+            float g[EPL], yh[EPL];
+            float d = 0.0f;
+#pragma unroll
+            for (int k = 0; k < EPL; ++k) {
+                const bool valid = (TIGHT && k < EPL - 1) || l + k * LPR < cols;
+                const float gv = LdsElem<T>::get(gp + k * LPR * kB);
+                const float qv = float(int(*reinterpret_cast<const int8_t *>(cp + k * LPR)));
+                g[k] = valid ? gv : 0.0f;                             // unused slots add nothing
+                yh[k] = fmaf(qv, prm.x, prm.y);
+                d = fmaf(g[k], yh[k], d);
+            }
+            d = lanes_sum_dpp<LPR>(d);
+            if (live) {
+#pragma unroll
+                for (int k = 0; k < EPL; ++k) {
+                    const bool valid = (TIGHT && k < EPL - 1) || l + k * LPR < cols;
+                    if (valid) LdsElem<T>::put(gp + k * LPR * kB, yh[k] * (g[k] - d));
+                }
+            }
+        }
+        team_sync<64>();
+
+#pragma unroll
+        for (int u = 0; u < kSrFlat; ++u) {
+            const uint32_t v = u * 64 + lane;
+            if (v < nfull) Nt<T>::store(dx, e0 + v * kVec, Store<T>::load(gs, int64_t(v) * kVec));
+        }
+        if (lane < tail) {
+            const uint32_t le = nfull * kVec + lane;
+            Store<T>::store1(dx, e0 + le, LdsElem<T>::get(gs + le * kB));   // exact: the value is already of type T
+        }
+        team_sync<64>();   // the next tile rewrites the region
+    }
+}
+
+struct SbPlan {
+    bool ok;
+    SrShape sh;
+    int grid;
+    uint32_t tab_bytes, wave_bytes;
+    size_t lds;
+};
+
+static SbPlan sb_plan(int64_t total_rows, int64_t H, int64_t cols, int elem_bytes)
+{
+    SbPlan p{};
+    if (cols > kSrMaxCols) return p;
+    p.sh = sr_shape(total_rows, cols);
+    p.tab_bytes = uint32_t((H * 8 + 15) / 16 * 16);
+    p.wave_bytes = uint32_t((p.sh.R * cols * (elem_bytes + 1) + 15) / 16 * 16);
+    p.lds = size_t(p.tab_bytes) + size_t(kThreads / 64) * p.wave_bytes + kSrSlack;
+    p.ok = p.lds <= 64 * 1024;
+    if (!p.ok) return p;
+    int64_t per_cu = int64_t(160 * 1024) / int64_t(p.lds);
+    if (per_cu > kSbRowWaves) per_cu = kSbRowWaves;
+    const int64_t wgs = ceil_div(p.sh.tiles, kThreads / 64), resident = 256 * per_cu;
+    p.grid = int(wgs < resident ? wgs : resident);
+    return p;
+}
+
 }  // namespace mesa
 
 using namespace mesa;
@@ -291,10 +437,33 @@ extern "C" MESA_EXPORT mesa_status mesa_softmax_bwd_q(const int8_t *yq, int64_t 
     if (!yq || !dy || !dx || !alpha || !beta || !aligned16(yq) || !aligned16(dy) || !aligned16(dx) || !aligned4(alpha) ||
         !aligned4(beta))
         return MESA_ERR_INVALID_ARG;
-    if (H > kSmMaxHeads || rows >= (int64_t(1) << 31) || cols < kVec) return MESA_ERR_UNSUPPORTED;
+    if (H > kSmMaxHeads || rows >= (int64_t(1) << 31)) return MESA_ERR_UNSUPPORTED;
     const long double tr = (long double)B * (long double)H * (long double)rows;
     if (tr >= 2147483648.0L) return MESA_ERR_UNSUPPORTED;
     const int64_t total_rows = B * H * rows;
+    const SbPlan rp = sb_plan(total_rows, H, cols, dtype_bytes(dt));
+    if (rp.ok) {
+        FastDiv drr = make_fastdiv(uint32_t(rows)), dhh = make_fastdiv(uint32_t(H));
+        hipStream_t sr = static_cast<hipStream_t>(stream);
+#define MESA_LAUNCH_SB(T, LPR_, EPL_, TIGHT_) \
+    hipLaunchKernelGGL((k_softmax_bwd_rows<T, LPR_, EPL_, TIGHT_>), dim3(rp.grid), dim3(kThreads), rp.lds, sr, yq, dy, dx, total_rows, \
+                       uint32_t(cols), uint32_t(rp.sh.R), rp.sh.tiles, drr, dhh, alpha, beta, rp.tab_bytes, rp.wave_bytes)
+#define MESA_LAUNCH_SB_C(T, LPR_, EPL_) \
+    do { if (rp.sh.tight) MESA_LAUNCH_SB(T, LPR_, EPL_, true); else MESA_LAUNCH_SB(T, LPR_, EPL_, false); } while (0)
+#define MESA_LAUNCH_SB_T(T) \
+    do { \
+        if (rp.sh.lpr == 16) MESA_LAUNCH_SB_C(T, 16, 16); \
+        else if (rp.sh.epl == 25) MESA_LAUNCH_SB_C(T, 8, 25); \
+        else if (rp.sh.epl == 13) MESA_LAUNCH_SB_C(T, 8, 13); \
+        else MESA_LAUNCH_SB_C(T, 8, 7); \
+    } while (0)
+        MESA_FOR_DTYPE(dt, MESA_LAUNCH_SB_T);
+#undef MESA_LAUNCH_SB_T
+#undef MESA_LAUNCH_SB_C
+#undef MESA_LAUNCH_SB
+        return launch_status();
+    }
+    if (cols < kVec) return MESA_ERR_UNSUPPORTED;
     // rows per tile: a multiple of 8/gcd(cols, 8) so that every tile starts on a vector boundary.
     // Short rows: one wave per tile (2048 elements); long rows: the whole workgroup (8192 elements).
     int64_t gc = cols, b8 = 8;

@@ -17,23 +17,13 @@
 #include "api_util.hpp"
 #include "common.hpp"
 #include "quantize.hpp"
+#include "softmax_rows.hpp"
 
 namespace mesa {
 
 constexpr int kSfU = 4;             // vectors per thread in a tile
 constexpr int kSfMaxHeads = 1024;
 constexpr int kSfWaves = 3;         // waves per SIMD the register budget is set for
-
-template <int TPT> __device__ __forceinline__ void team_sync()
-{
-    if (TPT == kThreads) {
-        __syncthreads();
-    } else {   // the team is one wave: order its own LDS traffic
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    }
-}
 
 template <int WIDTH, bool MAX> __device__ __forceinline__ float lanes_combine(float v)
 {
@@ -270,58 +260,11 @@ __global__ __launch_bounds__(kThreads, kSfWaves) void k_softmax_fwd(const void *
 // phase: the finished vectors of y and of the codes leave as aligned 16- and 8-byte stores.  A lane's extrema
 // stay in registers as long as its rows belong to one head.
 // ---------------------------------------------------------------------------------------------
-constexpr int kSrTileElems = 2048;                    // elements of a wave's tile at most
-constexpr int kSrFlat = kSrTileElems / kVec / 64;     // vectors per lane in the flat phases
-constexpr int kSrMaxCols = 256;
-constexpr int kSrWaves = 4;                           // waves per SIMD the register budget is set for
-constexpr int kSrSlack = 1024;                        // bytes past the last region that unused slots may read
-
-template <int WIDTH, bool MAX> __device__ __forceinline__ float lanes_extreme_dpp(float v)
-{
-    static_assert(WIDTH == 8 || WIDTH == 16, "lane groups inside a DPP row");
-    v = MAX ? vmax(v, dpp_move<0xB1>(v)) : vmin(v, dpp_move<0xB1>(v));      // quad_perm [1,0,3,2]
-    v = MAX ? vmax(v, dpp_move<0x4E>(v)) : vmin(v, dpp_move<0x4E>(v));      // quad_perm [2,3,0,1]
-    v = MAX ? vmax(v, dpp_move<0x141>(v)) : vmin(v, dpp_move<0x141>(v));    // row_half_mirror
-    if (WIDTH >= 16) v = MAX ? vmax(v, dpp_move<0x140>(v)) : vmin(v, dpp_move<0x140>(v));   // row_mirror
-    return v;
-}
-
-// one staged element <-> binary32; put() returns the value as stored
-template <typename T> struct LdsElem;
-template <> struct LdsElem<_Float16> {
-    __device__ static __forceinline__ float get(const unsigned char *p) { return float(*reinterpret_cast<const _Float16 *>(p)); }
-    __device__ static __forceinline__ float put(unsigned char *p, float v)
-    {
-        const _Float16 h = _Float16(v);
-        *reinterpret_cast<_Float16 *>(p) = h;
-        return float(h);
-    }
-};
-template <> struct LdsElem<__bf16> {
-    __device__ static __forceinline__ float get(const unsigned char *p)
-    {
-        return __uint_as_float(uint32_t(*reinterpret_cast<const uint16_t *>(p)) << 16);
-    }
-    __device__ static __forceinline__ float put(unsigned char *p, float v)
-    {
-        const __bf16 h = __bf16(v);
-        const uint16_t bits = __builtin_bit_cast(uint16_t, h);
-        *reinterpret_cast<uint16_t *>(p) = bits;
-        return __uint_as_float(uint32_t(bits) << 16);
-    }
-};
-template <> struct LdsElem<float> {
-    __device__ static __forceinline__ float get(const unsigned char *p) { return *reinterpret_cast<const float *>(p); }
-    __device__ static __forceinline__ float put(unsigned char *p, float v)
-    {
-        *reinterpret_cast<float *>(p) = v;
-        return v;
-    }
-};
+constexpr int kSfRowWaves = 4;      // waves per SIMD the row kernel's register budget is set for
 
 // TIGHT: cols > LPR * (EPL - 1), so only the last slot of a lane can lie beyond the row's end
 template <typename T, int LPR, int EPL, bool TIGHT, bool SR>
-__global__ __launch_bounds__(kThreads, kSrWaves) void k_softmax_fwd_rows(const void *__restrict__ s_in, void *__restrict__ y,
+__global__ __launch_bounds__(kThreads, kSfRowWaves) void k_softmax_fwd_rows(const void *__restrict__ s_in, void *__restrict__ y,
                                                                   int8_t *__restrict__ q, int64_t total_rows, uint32_t cols,
                                                                   uint32_t R, int64_t tiles, FastDiv div_rows, FastDiv div_heads,
                                                                   const float *__restrict__ alpha, const float *__restrict__ beta,
@@ -508,25 +451,15 @@ static SrPlan sr_plan(int64_t total_rows, int64_t H, int64_t cols, int elem_byte
 {
     SrPlan p{};
     if (cols > kSrMaxCols) return p;
-    if (cols <= 56) { p.lpr = 8; p.epl = 7; }
-    else if (cols <= 104) { p.lpr = 8; p.epl = 13; }
-    else if (cols <= 200) { p.lpr = 8; p.epl = 25; }
-    else { p.lpr = 16; p.epl = 16; }
-    p.tight = cols > int64_t(p.lpr) * (p.epl - 1);
-    int64_t gc = cols, b8 = 8;
-    while (b8) { int64_t t = gc % b8; gc = b8; b8 = t; }
-    const int64_t unit = 8 / gc, rpp = 64 / p.lpr;
-    const int64_t step = unit > rpp ? unit : rpp;          // whole vectors per tile, whole passes
-    p.R = (kSrTileElems / cols) / step * step;             // step * cols <= 8 * 256
-    if (p.R > total_rows) p.R = ceil_div(total_rows, step) * step;
-    p.tiles = ceil_div(total_rows, p.R);
+    const SrShape sh = sr_shape(total_rows, cols);
+    p.lpr = sh.lpr; p.epl = sh.epl; p.tight = sh.tight; p.R = sh.R; p.tiles = sh.tiles;
     p.tab_bytes = uint32_t((H * 16 + 15) / 16 * 16);
     p.wave_bytes = uint32_t((p.R * cols * (elem_bytes + (sr ? 2 : 0) + 1) + 15) / 16 * 16);
     p.lds = size_t(p.tab_bytes) + size_t(kThreads / 64) * p.wave_bytes + kSrSlack;
     p.ok = p.lds <= 64 * 1024;
     if (!p.ok) return p;
     int64_t per_cu = int64_t(160 * 1024) / int64_t(p.lds);
-    if (per_cu > kSrWaves) per_cu = kSrWaves;
+    if (per_cu > kSfRowWaves) per_cu = kSfRowWaves;
     const int64_t wgs = ceil_div(p.tiles, kThreads / 64), resident = 256 * per_cu;
     p.grid = int(wgs < resident ? wgs : resident);
     return p;

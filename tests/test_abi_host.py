@@ -83,7 +83,7 @@ def test_argument_errors_are_reported_before_any_launch(M):
     assert L.mesa_layernorm_fwd_q(P, 100, 384, 6, P, P, F(-1.0), P, P, F(0.9), P2, P, P, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_INVALID_ARG  # eps
     assert L.mesa_dequantize(P, lay, P, None, P, M.F16, None) == M.ERR_INVALID_ARG
     assert L.mesa_gelu_bwd_q(P, lay, P, P, P + 8, P, M.F16, None) == M.ERR_INVALID_ARG
-    assert L.mesa_softmax_bwd_q(P, 2, 3, 5, 4, P, P, P, P, M.F16, None) == M.ERR_UNSUPPORTED              # cols < 8
+    assert L.mesa_softmax_bwd_q(P, 2, 2000, 5, 40, P, P, P, P, M.F16, None) == M.ERR_UNSUPPORTED          # heads
     assert L.mesa_softmax_bwd_q(P, 2, 3, 5, 3001, P, P, P, P, M.F16, None) == M.ERR_UNSUPPORTED           # 8 odd rows exceed a tile
     assert L.mesa_softmax_bwd_q(P, -2, 3, 5, 16, P, P, P, P, M.F16, None) == M.ERR_INVALID_ARG
     assert L.mesa_layernorm_bwd_q(P, 10, 100, 5, P, P, P, P, P, P, P, P, P, M.F16, P, 1 << 20, None) == M.ERR_UNSUPPORTED

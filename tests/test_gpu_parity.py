@@ -504,6 +504,31 @@ def test_gelu_layer_forward_in_one_pass(M, layout, dtype):
 @pytest.mark.parametrize("dtype", DTYPES, ids=DTYPE_IDS)
 @pytest.mark.parametrize("B,H,rows,cols", [(3, 6, 197, 197), (5, 3, 49, 49), (2, 4, 64, 64), (1, 2, 33, 1000), (2, 3, 7, 19), (1, 1, 5, 8),
                                            (2, 2, 9, 3), (1, 3, 11, 57), (2, 1, 13, 104), (1, 2, 30, 105), (3, 1, 5, 200), (1, 2, 17, 201),
+                                           (2, 2, 6, 256), (1, 2, 10, 257), (40, 3, 61, 61), (1, 1, 3, 4096)])
+def test_softmax_backward_every_row_shape(M, B, H, rows, cols, dtype):
+    """Softmax backward at head-wise codes over every lane-group shape of the short-row kernel (and both of its
+    variants), rows shorter than a vector, ragged tiles, tiles that straddle heads, and the long-row kernel; out of
+    place and in place."""
+    gen = torch.Generator(device="cuda").manual_seed(B * 10 + cols)
+    lay = (B, H, rows * cols)
+    sig = torch.linspace(0.5, 3.0, H, device="cuda").view(1, H, 1, 1)
+    y = torch.softmax(torch.randn((B, H, rows, cols), generator=gen, device="cuda") * sig, dim=-1).to(dtype).contiguous()
+    a, b, ra, rb = run_params(M, [y], lay)
+    q = torch.empty(y.numel(), dtype=torch.int8, device="cuda")
+    M.mesa_quantize_headwise(y, lay, a, b, q, M.ROUND_STOCHASTIC, 5, 0)
+    dy = torch.randn((B, H, rows, cols), generator=gen, device="cuda").to(dtype)
+    dx = torch.empty_like(dy)
+    M.mesa_softmax_bwd_q(q, B, H, rows, cols, a, b, dy, dx)
+    ref = R.softmax_bwd_q(npy(q), B, H, rows, cols, ra, rb, npy(dy))
+    assert relerr(npy(dx).reshape(ref.shape), ref) <= TOL[dtype]
+    dy2 = dy.clone()
+    M.mesa_softmax_bwd_q(q, B, H, rows, cols, a, b, dy2, dy2)
+    assert torch.equal(dy2, dx)
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=DTYPE_IDS)
+@pytest.mark.parametrize("B,H,rows,cols", [(3, 6, 197, 197), (5, 3, 49, 49), (2, 4, 64, 64), (1, 2, 33, 1000), (2, 3, 7, 19), (1, 1, 5, 8),
+                                           (2, 2, 9, 3), (1, 3, 11, 57), (2, 1, 13, 104), (1, 2, 30, 105), (3, 1, 5, 200), (1, 2, 17, 201),
                                            (2, 2, 6, 256), (1, 2, 10, 257), (40, 3, 61, 61)])
 def test_softmax_layer_forward_in_one_pass(M, B, H, rows, cols, dtype):
     """y = softmax(s) within tolerance of the oracle's binary64 softmax and with rows that sum to 1; the codes and
