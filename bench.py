@@ -32,7 +32,7 @@ import mesa_workloads as W  # noqa: E402
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the plain copy kernel's reading
 # (profiles/bench_step_deit_s_b128_hbm_traffic.txt); algorithmic bytes are in algorithmic_bytes() below
-MEASURED_TRAFFIC_BYTES = {"gelu_bwd_q": 193.7e6, "softmax_bwd_q": 152.9e6}
+MEASURED_TRAFFIC_BYTES = {"gelu_bwd_q": 193.7e6, "softmax_bwd_q": 155.9e6}
 HBM_PEAK_GBS = 8000.0
 MFMA_F16_PEAK_TFLOPS = 2500.0
 NSETS = 3

@@ -204,8 +204,9 @@ mesa_status mesa_dequantize(const int8_t *q, mesa_layout L, const float *alpha, 
  * head-wise parameters alpha[H], beta[H].  Per row:  d = sum_j dy_j*y_hat_j,
  * dx_j = y_hat_j * (dy_j - d), accumulated in binary32.
  * yq: int8 (in); dy, dx: [B*H*rows*cols] of dt (in / out); dx may alias dy.
- * Limits: cols >= 8, R*cols <= 8192 for R = 8/gcd(cols, 8) (so cols <= 8192 when cols % 8 == 0, cols <= 1024
- * when cols is odd), and B*H*rows < 2^31; else MESA_ERR_UNSUPPORTED.
+ * Limits: rows of up to 256 elements: any length; longer rows: R*cols <= 8192 for R = 8/gcd(cols, 8) (so
+ * cols <= 8192 when cols % 8 == 0, cols <= 1024 when cols is odd); H <= 1024 and B*H*rows < 2^31; else
+ * MESA_ERR_UNSUPPORTED.
  */
 mesa_status mesa_softmax_bwd_q(const int8_t *yq, int64_t B, int64_t H, int64_t rows, int64_t cols,
                                const float *alpha, const float *beta, const void *dy, void *dx,

@@ -1,12 +1,15 @@
 // softmax_bwd.hip -- softmax backward at the de-quantized attention map (Sec. 3.1 Eq. 2):
 //   per row  d = sum_j dy_j*y_hat_j,  dx_j = y_hat_j*(dy_j - d),  y_hat = (q+128)*alpha_h/255 + beta_h.
 //
-// Rows of 197 or 49 elements start at odd byte offsets, so a workgroup takes a tile of R
-// consecutive rows with R*cols a multiple of 8: the tile is then a run of whole 8-element vectors
-// that start 16-byte aligned in dy / dx and 8-byte aligned in the codes, and is read and written
-// flat with full-width accesses.  Codes and dy stay in registers between the two passes; only two
-// partial sums per vector (a vector touches at most two rows when cols >= 8) go through LDS,
-// where 16 lanes per row add them in a fixed order.  One HBM read of codes and dy, one write of dx.
+// Rows of 197 or 49 elements start at odd byte offsets, so a wave (or, for long rows, a workgroup) takes a
+// tile of R consecutive rows with R*cols a multiple of 8: the tile is then a run of whole 8-element vectors
+// that start 16-byte aligned in dy / dx and 8-byte aligned in the codes, and is read and written flat with
+// full-width accesses.  One HBM read of codes and dy, one write of dx.  Two kernels:
+//   rows of up to 256 elements: k_softmax_bwd_rows, at the end of this file -- the tile staged through LDS, a
+//   row per group of lanes;
+//   longer rows: k_softmax_bwd -- codes and dy stay in registers between the two passes; only two partial
+//   sums per vector (a vector touches at most two rows when cols >= 8) go through LDS, where 16 lanes per row
+//   add them in a fixed order.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
