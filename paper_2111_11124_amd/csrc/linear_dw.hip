@@ -43,6 +43,7 @@ constexpr int kDwPF = 3;         // stages prefetched into registers ahead of th
 
 // BN x BK tile of dW per workgroup, WGN x WGK waves, each wave (BN/WGN) x (BK/WGK) as 32x32 MFMA tiles
 template <int BN, int BK, int WGN, int WGK> struct DwCfg {
+    static constexpr int PF = BN * BK <= 128 * 128 ? 2 * kDwPF : kDwPF;   // small tiles: less per stage, so more stages in flight
     static constexpr int NW = WGN * WGK;
     static constexpr int THREADS = NW * 64;
     static constexpr int WN = BN / WGN, WK = BK / WGK;  // wave tile
@@ -179,7 +180,7 @@ __global__ __launch_bounds__(WGN * WGK * 64, 1) void k_dw_f16(const int8_t *__re
     // TPR_B-th chunk of one row (an offset per chunk, since each may be clamped).  Columns outside N or K
     // are read from column 0 instead and left as they are: row n of the product depends on column n
     // of dy only and column k on column k of the codes, and those rows and columns are never written.
-    u32x4 ring_a[kDwPF][C::A_CHUNKS], ring_b[kDwPF][C::B_CHUNKS];
+    u32x4 ring_a[C::PF][C::A_CHUNKS], ring_b[C::PF][C::B_CHUNKS];
     const int row0_a = tid / C::A_CPR, col_a = n0 + (tid % C::A_CPR) * 8;
     const int row_b = tid / C::TPR_B, cb = tid % C::TPR_B;
     const uint32_t voff_a = (uint32_t(row0_a) * uint32_t(N) + uint32_t(col_a < N ? col_a : 0)) * 2u;   // bytes
@@ -266,7 +267,7 @@ __global__ __launch_bounds__(WGN * WGK * 64, 1) void k_dw_f16(const int8_t *__re
         constexpr int PH = decltype(phase)::value;
         const unsigned char *cur = smem + (s & 1) * C::STAGE;
         unsigned char *nxt = smem + ((s + 1) & 1) * C::STAGE;
-        const int64_t m_fill = stage_start(s + 1 + kDwPF);
+        const int64_t m_fill = stage_start(s + 1 + C::PF);
 #pragma unroll
         for (int r = 0; r < kNM; ++r) {
             mfma_item(r, PH);
@@ -307,7 +308,7 @@ __global__ __launch_bounds__(WGN * WGK * 64, 1) void k_dw_f16(const int8_t *__re
         for (int t = 0; t < kMove; ++t) store_item(t, smem, ring_a[0], ring_b[0]);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int d = 0; d < kDwPF; ++d) {
+        for (int d = 0; d < C::PF; ++d) {
 #pragma unroll
             for (int t = 0; t < kMove; ++t) load_item(t, stage_start(d + 1), ring_a[d], ring_b[d]);
             __builtin_amdgcn_sched_barrier(0);
@@ -323,11 +324,11 @@ __global__ __launch_bounds__(WGN * WGK * 64, 1) void k_dw_f16(const int8_t *__re
         // and the slot is refilled during the second step with stage s+1+kDwPF.
         // The loop is left from the inside when the stages run out, so that there is one copy of
         // each of the kDwPF stage bodies and every path to the loop head has all slots in flight.
-        for (int sbase = 0; sbase < nfull; sbase += kDwPF) {
+        for (int sbase = 0; sbase < nfull; sbase += C::PF) {
 #pragma unroll
-            for (int d = 0; d < kDwPF; ++d) {
+            for (int d = 0; d < C::PF; ++d) {
                 stage(sbase + d, ring_a[d], ring_b[d]);
-                if (d + 1 < kDwPF && sbase + d + 1 >= nfull) break;
+                if (d + 1 < C::PF && sbase + d + 1 >= nfull) break;
             }
         }
     }
@@ -477,7 +478,7 @@ __global__ __launch_bounds__(kThreads) void k_dw_reduce(const float *__restrict_
 }
 
 struct DwPlan {
-    int variant;   // 16-bit tiles (n x k): 0: 256 x 256, 1: 256 x 128; 2: binary32
+    int variant;   // 16-bit tiles (n x k): 0: 256 x 256, 1: 256 x 128, 3: 128 x 128; 2: binary32
     int bn, bk, tiles_n, tiles_k, splits, grid;
     int64_t rows_per_split;
 };
@@ -489,6 +490,7 @@ static DwPlan dw_plan(int64_t M, int64_t K, int64_t N, mesa_dtype dt)
         // 256-wide k tiles unless they would waste much of the last one.  (A 128 x 384 tile for K = 384 was
         // measured too: no faster per MFMA, and its 21 slices instead of 14 cost more partial-sum traffic.)
         if (K % 256 == 0 || K > 1024) { p.variant = 0; p.bn = 256; p.bk = 256; }
+        else if (K <= 128 && N % 256 != 0 && N % 256 <= 128) { p.variant = 3; p.bn = 128; p.bk = 128; }   // narrow K: no empty half tile in N
         else { p.variant = 1; p.bn = 256; p.bk = 128; }
     } else {
         p.variant = 2;
@@ -504,7 +506,7 @@ static DwPlan dw_plan(int64_t M, int64_t K, int64_t N, mesa_dtype dt)
     int64_t max_splits = M / 256;
     if (max_splits < 1) max_splits = 1;
     if (splits > max_splits) splits = max_splits;
-    if (splits > 64) splits = 64;
+    if (splits > 128) splits = 128;   // the second kernel adds the slices one after the other
     int64_t rps = ceil_div(ceil_div(M > 0 ? M : 1, splits), kDwBM) * kDwBM;
     splits = ceil_div(M > 0 ? M : 1, rps);
     p.splits = int(splits);
@@ -545,17 +547,17 @@ extern "C" MESA_EXPORT mesa_status mesa_linear_dw_q(const int8_t *xq, int64_t M,
     float *S0 = P + size_t(p.splits) * size_t(N_out) * size_t(K);
     const int Ki = int(K), Ni = int(N_out);
     float centre = 128.0f;
-#define MESA_LAUNCH_DW(E, BK_) \
+#define MESA_LAUNCH_DW(E, BN_, BK_) \
     do { \
-        using C = DwCfg<256, BK_, 2, 2>; \
-        hipLaunchKernelGGL((k_dw_f16<E, 256, BK_, 2, 2>), dim3(p.grid), dim3(C::THREADS), 2 * C::STAGE, s, xq, \
+        using C = DwCfg<BN_, BK_, 2, 2>; \
+        hipLaunchKernelGGL((k_dw_f16<E, BN_, BK_, 2, 2>), dim3(p.grid), dim3(C::THREADS), 2 * C::STAGE, s, xq, \
                            static_cast<const E *>(dy), M, Ki, Ni, p.tiles_n, p.tiles_k, p.splits, p.rows_per_split, P, S0); \
         centre = DwElem<E>::kCentre; \
     } while (0)
     if (dt == MESA_F16) {
-        if (p.variant == 0) MESA_LAUNCH_DW(_Float16, 256); else MESA_LAUNCH_DW(_Float16, 128);
+        if (p.variant == 0) MESA_LAUNCH_DW(_Float16, 256, 256); else if (p.variant == 1) MESA_LAUNCH_DW(_Float16, 256, 128); else MESA_LAUNCH_DW(_Float16, 128, 128);
     } else if (dt == MESA_BF16) {
-        if (p.variant == 0) MESA_LAUNCH_DW(__bf16, 256); else MESA_LAUNCH_DW(__bf16, 128);
+        if (p.variant == 0) MESA_LAUNCH_DW(__bf16, 256, 256); else if (p.variant == 1) MESA_LAUNCH_DW(__bf16, 256, 128); else MESA_LAUNCH_DW(__bf16, 128, 128);
     } else {
         hipLaunchKernelGGL(k_dw_f32, dim3(p.grid), dim3(kThreads), 0, s, xq, static_cast<const float *>(dy), M, Ki, Ni,
                            p.tiles_n, p.tiles_k, p.splits, p.rows_per_split, P, S0);
