@@ -166,7 +166,8 @@ mesa_status mesa_gelu_fwd_q(const void *x, mesa_dtype dt, mesa_layout L,
  * that reads y back.  Per binary16 element 2 bytes in, 2 + 1 bytes out.
  * s: [B*H*rows*cols] of dt (in).  y: same (out), not aliasing s.  q: int8 (out).
  * alpha, beta: [H] (in/out).  ws: MESA_OP_SOFTMAX_FWD_Q bytes.  Limits: rows of up to 256 elements: any
- * length; longer rows as for mesa_softmax_bwd_q.
+ * length (with more than 256 heads such rows may fall under the next rule); longer rows as for
+ * mesa_softmax_bwd_q.
  */
 mesa_status mesa_softmax_fwd_q(const void *s, int64_t B, int64_t H, int64_t rows, int64_t cols,
                                float *alpha, float *beta, float lambda, void *y, int8_t *q,
