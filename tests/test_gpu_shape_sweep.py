@@ -1,0 +1,157 @@
+"""Seeded sweeps over extents around every kernel's size limits, outputs framed by guard zones.
+
+Each case runs the HIP path on a buffer that carries 32 sentinel elements before and after the output, compares the
+output with the oracle as the parity tests do, and checks that the sentinels are untouched: a kernel that writes a
+partial vector or a ragged tile past its extent shows up here even when the values it owes are right.
+"""
+import random
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import mesa_ref as R
+
+pytestmark = pytest.mark.gpu
+TOL = {torch.float32: 1e-5, torch.float16: 2e-3, torch.bfloat16: 1.6e-2}
+GUARD = 32
+
+
+@pytest.fixture(scope="module")
+def M():
+    import paper_2111_11124_amd as m
+    assert torch.cuda.is_available()
+    m.lib()
+    return m
+
+
+def npy(t):
+    return (t.float() if t.dtype == torch.bfloat16 else t).cpu().numpy()
+
+
+def relerr(got, ref):
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+
+def framed(shape, dtype, val=7):
+    """(frame, view): a buffer of sentinels with the output in its middle (the view starts 16-byte aligned)."""
+    n = int(np.prod(shape))
+    frame = torch.full((n + 2 * GUARD,), val, dtype=dtype, device="cuda")
+    return frame, frame[GUARD:GUARD + n].view(shape)
+
+
+def intact(frame, val=7):
+    return bool((frame[:GUARD] == val).all() and (frame[-GUARD:] == val).all())
+
+
+ATTN_N = (8, 9, 15, 16, 17, 31, 32, 33, 48, 63, 64, 65, 96, 127, 128, 129, 160, 191, 192, 193, 197, 222, 223, 224, 225, 254, 255,
+          256, 257)
+
+
+@pytest.mark.parametrize("Dh", [32, 64, 96, 128, 8, 40])
+def test_attention_products_around_every_size_limit(M, Dh):
+    """Sequence lengths on both sides of each dedicated kernel's limits (chunk sizes, LDS capacity, the general
+    kernel's tiles) for the head sizes with dedicated kernels and two without."""
+    rnd = random.Random(Dh)
+    for idx, N in enumerate(ATTN_N):
+        B, H = rnd.choice((1, 2, 3)), rnd.choice((1, 2, 3, 5))
+        g = torch.Generator(device="cuda").manual_seed(1000 * Dh + idx)
+        aq = torch.randint(-128, 128, (B, H, N, N), dtype=torch.int8, device="cuda", generator=g)
+        qq, kq, vq = (torch.randint(-128, 128, (B, H, N, Dh), dtype=torch.int8, device="cuda", generator=g) for _ in range(3))
+        dO = torch.randn((B, H, N, Dh), device="cuda", generator=g).half()
+        dS = (torch.randn((B, H, N, N), device="cuda", generator=g) * 0.1).half()
+        par = {k: (torch.linspace(1.0, 4.0, H, device="cuda") * s, torch.linspace(-2.0, -0.5, H, device="cuda") * s)
+               for k, s in (("a", 0.25), ("q", 1.0), ("k", 1.5), ("v", 0.75))}
+        fA, dA = framed((B, H, N, N), torch.float16)
+        fV, dV = framed((B, H, N, Dh), torch.float16)
+        fQ, dQ = framed((B, H, N, Dh), torch.float16)
+        fK, dK = framed((B, H, N, Dh), torch.float16)
+        M.mesa_attn_av_bwd_q(aq, vq, B, H, N, Dh, *par["a"], *par["v"], dO, dA, dV)
+        M.mesa_attn_qk_bwd_q(qq, kq, B, H, N, Dh, *par["q"], *par["k"], dS, 0.2, dQ, dK)
+        rp = {k: (npy(a), npy(b)) for k, (a, b) in par.items()}
+        rdA, rdV = R.attn_av_bwd_q(npy(aq), npy(vq), B, H, N, Dh, *rp["a"], *rp["v"], npy(dO))
+        rdQ, rdK = R.attn_qk_bwd_q(npy(qq), npy(kq), B, H, N, Dh, *rp["q"], *rp["k"], npy(dS), 0.2)
+        errs = {"dA": relerr(npy(dA), rdA), "dV": relerr(npy(dV), rdV), "dQ": relerr(npy(dQ), rdQ), "dK": relerr(npy(dK), rdK)}
+        assert all(v <= TOL[torch.float16] for v in errs.values()), ((B, H, N, Dh), errs)
+        assert all(intact(f) for f in (fA, fV, fQ, fK)), (B, H, N, Dh)
+
+
+SOFTMAX_COLS = (1, 2, 3, 5, 7, 8, 9, 16, 17, 31, 33, 49, 56, 57, 64, 100, 104, 105, 127, 128, 197, 199, 200, 201, 255, 256, 257, 264,
+                511, 577, 1000, 1024)
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.float32, torch.bfloat16], ids=["f16", "f32", "bf16"])
+def test_softmax_layer_forward_and_backward_over_row_lengths(M, dtype):
+    """Row lengths on both sides of every lane-group shape of the short-row kernels and into the long-row kernels;
+    row counts that leave ragged tiles and tiles that straddle heads."""
+    rnd = random.Random(str(dtype))
+    for cols in SOFTMAX_COLS:
+        B, H, rows = rnd.choice((1, 2, 7)), rnd.choice((1, 3, 4)), rnd.choice((1, 5, 17, 61, cols))
+        n = B * H * rows * cols
+        lay = (B, H, rows * cols)
+        g = torch.Generator(device="cuda").manual_seed(cols)
+        s = (torch.randn((B, H, rows, cols), device="cuda", generator=g) * 2).to(dtype)
+        fy, y = framed((B, H, rows, cols), dtype)
+        fq, q = framed((n,), torch.int8)
+        a = torch.full((H,), 0.9, device="cuda")
+        b = torch.full((H,), 0.01, device="cuda")
+        ra, rb = npy(a).copy(), npy(b).copy()
+        ws = torch.empty(max(M.workspace_bytes(M.OP_SOFTMAX_FWD_Q, B * H * rows, H, cols, M.F16), 16), dtype=torch.uint8, device="cuda")
+        mode, rmode = rnd.choice(((M.ROUND_STOCHASTIC, R.ROUND_STOCHASTIC), (M.ROUND_NEAREST_EVEN, R.ROUND_NEAREST)))
+        M.mesa_softmax_fwd_q(s, B, H, rows, cols, a, b, 0.9, y, q, ws, mode, 3, 1)
+        yh = npy(y)
+        assert relerr(yh, R.softmax_fwd(npy(s), B * H * rows, cols)) <= TOL[dtype], (B, H, rows, cols)
+        rq, ra2, rb2 = R.quantize_update_fused(yh, lay, ra, rb, 0.9, rmode, 3, 1)
+        assert np.array_equal(npy(q), rq.reshape(-1)), (B, H, rows, cols)
+        assert np.array_equal(npy(a), ra2) and np.array_equal(npy(b), rb2), (B, H, rows, cols)
+        assert intact(fy) and intact(fq), (B, H, rows, cols)
+        # backward at the codes just taken, with the moved estimates
+        dy = torch.randn((B, H, rows, cols), device="cuda", generator=g).to(dtype)
+        fx, dx = framed((B, H, rows, cols), dtype)
+        M.mesa_softmax_bwd_q(q, B, H, rows, cols, a, b, dy, dx)
+        ref = R.softmax_bwd_q(npy(q), B, H, rows, cols, ra2, rb2, npy(dy))
+        assert relerr(npy(dx).reshape(ref.shape), ref) <= TOL[dtype], (B, H, rows, cols)
+        assert intact(fx), (B, H, rows, cols)
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.float32, torch.bfloat16], ids=["f16", "f32", "bf16"])
+def test_layernorm_and_gelu_layer_forwards_over_extents(M, dtype):
+    rnd = random.Random("ln" + str(dtype))
+    for D in (8, 16, 24, 64, 96, 128, 192, 384, 512, 520, 768, 1000, 1024):
+        Mr = rnd.choice((1, 3, 31, 100, 257))
+        G = rnd.choice([gg for gg in (1, 2, 3, 4, 6, 8, 12) if D % gg == 0 and (D // gg) % 8 == 0])
+        g = torch.Generator(device="cuda").manual_seed(D)
+        x = (torch.randn((Mr, D), device="cuda", generator=g) * 1.5 + 0.2).to(dtype)
+        gamma = (1 + 0.1 * torch.randn(D, device="cuda", generator=g)).to(dtype)
+        bias = (0.1 * torch.randn(D, device="cuda", generator=g)).to(dtype)
+        fy, y = framed((Mr, D), dtype)
+        fq, q = framed((Mr * D,), torch.int8)
+        fm, mean = framed((Mr,), torch.float32)
+        fr, rstd = framed((Mr,), torch.float32)
+        a = torch.full((G,), 9.0, device="cuda")
+        b = torch.full((G,), -4.5, device="cuda")
+        ra, rb = npy(a).copy(), npy(b).copy()
+        ws = torch.empty(max(M.workspace_bytes(M.OP_LAYERNORM_FWD_Q, Mr, D, G, M.F16), 16), dtype=torch.uint8, device="cuda")
+        M.mesa_layernorm_fwd_q(x, Mr, D, G, gamma, bias, 1e-5, a, b, 0.9, y, mean, rstd, q, ws, M.ROUND_STOCHASTIC, 3, 1)
+        ry, rm, rr = R.layernorm_fwd(npy(x), Mr, D, npy(gamma), npy(bias), 1e-5)
+        rq, ra2, rb2 = R.quantize_update_fused(npy(x), (Mr, G, D // G), ra, rb, 0.9, R.ROUND_STOCHASTIC, 3, 1)
+        assert relerr(npy(y), ry) <= TOL[dtype] and relerr(npy(mean), rm) <= 1e-5 and relerr(npy(rstd), rr) <= 1e-5, (Mr, D, G)
+        assert np.array_equal(npy(q), rq.reshape(-1)) and np.array_equal(npy(a), ra2) and np.array_equal(npy(b), rb2), (Mr, D, G)
+        assert all(intact(f) for f in (fy, fm, fr, fq)), (Mr, D, G)
+    for lay in ((1, 1, 8), (1, 1, 9), (3, 2, 5), (7, 3, 333), (2, 40, 77), (5, 6, 256), (1, 1, 100003), (9, 12, 64)):
+        G = lay[1]
+        g = torch.Generator(device="cuda").manual_seed(lay[2])
+        x = (torch.randn(lay, device="cuda", generator=g) * 2).to(dtype)
+        fy, y = framed(lay, dtype)
+        fq, q = framed((x.numel(),), torch.int8)
+        a = torch.full((G,), 7.0, device="cuda")
+        b = torch.full((G,), -3.5, device="cuda")
+        ra, rb = npy(a).copy(), npy(b).copy()
+        ws = torch.empty(max(M.workspace_bytes(M.OP_UPDATE_RUNNING_PARAMS, *lay, M.F16), 16), dtype=torch.uint8, device="cuda")
+        M.mesa_gelu_fwd_q(x, lay, a, b, 0.9, y, q, ws, M.ROUND_STOCHASTIC, 3, 1)
+        ry, rq, ra2, rb2 = R.gelu_fwd_q(npy(x), lay, ra, rb, 0.9, R.ROUND_STOCHASTIC, 3, 1)
+        assert relerr(npy(y), ry) <= TOL[dtype], lay
+        assert np.array_equal(npy(q), rq.reshape(-1)) and np.array_equal(npy(a), ra2) and np.array_equal(npy(b), rb2), lay
+        assert intact(fy) and intact(fq), lay
