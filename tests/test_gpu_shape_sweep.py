@@ -155,3 +155,86 @@ def test_layernorm_and_gelu_layer_forwards_over_extents(M, dtype):
         assert relerr(npy(y), ry) <= TOL[dtype], lay
         assert np.array_equal(npy(q), rq.reshape(-1)) and np.array_equal(npy(a), ra2) and np.array_equal(npy(b), rb2), lay
         assert intact(fy) and intact(fq), lay
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.float32, torch.bfloat16], ids=["f16", "f32", "bf16"])
+def test_stream_kernels_and_layernorm_backward_keep_inside_their_outputs(M, dtype):
+    """Quantize, single-pass quantize, de-quantize, GELU / ReLU / LayerNorm backward on ragged layouts: results as
+    in the parity tests, and nothing written outside the outputs."""
+    rnd = random.Random("core" + str(dtype))
+    layouts = [(1, 1, 1), (1, 1, 7), (1, 1, 8), (1, 1, 4097), (3, 2, 5), (7, 3, 333), (2, 40, 77), (5, 6, 256), (1, 1, 100003), (9, 12, 64),
+               (37, 6, 64), (4, 3, 361), (1, 5, 2049), (129, 1, 24)]
+    for lay in layouts:
+        n = lay[0] * lay[1] * lay[2]
+        G = lay[1]
+        g = torch.Generator(device="cuda").manual_seed(n)
+        x = (torch.randn(lay, device="cuda", generator=g) * 1.7 + 0.1).to(dtype)
+        a = torch.zeros(G, device="cuda")
+        b = torch.zeros(G, device="cuda")
+        ws = torch.empty(max(M.workspace_bytes(M.OP_UPDATE_RUNNING_PARAMS, *lay, M.F16), 16), dtype=torch.uint8, device="cuda")
+        M.mesa_update_running_params(x, lay, a, b, 0.9, True, ws)
+        ra, rb = R.update_running_params(npy(x), lay, np.zeros(G, np.float32), np.zeros(G, np.float32), 0.9, True)
+        mode, rmode = rnd.choice(((M.ROUND_STOCHASTIC, R.ROUND_STOCHASTIC), (M.ROUND_NEAREST_EVEN, R.ROUND_NEAREST)))
+        fq, q = framed((n,), torch.int8)
+        M.mesa_quantize_headwise(x, lay, a, b, q, mode, 9, 5)
+        rq = R.quantize_headwise(npy(x), lay, ra, rb, rmode, 9, 5).reshape(-1)
+        assert np.array_equal(npy(q), rq) and intact(fq), lay
+        fq2, q2 = framed((n,), torch.int8)
+        a2, b2 = a.clone(), b.clone()
+        M.mesa_quantize_update_fused(x, lay, a2, b2, 0.9, q2, ws, mode, 9, 5)
+        assert torch.equal(q2, q) and intact(fq2), lay
+        fo, out = framed((n,), dtype)
+        M.mesa_dequantize(q, lay, a, b, out)
+        ref = R.dequantize(rq, lay, ra, rb, np.float32)
+        assert relerr(npy(out), ref) <= TOL[dtype] and intact(fo), lay
+        dy = torch.randn(lay, device="cuda", generator=g).to(dtype)
+        for call, oracle in ((M.mesa_gelu_bwd_q, R.gelu_bwd_q), (M.mesa_relu_bwd_q, R.relu_bwd_q)):
+            fx, dx = framed(lay, dtype)
+            call(q, lay, a, b, dy, dx)
+            ref = oracle(rq, lay, ra, rb, npy(dy))
+            assert relerr(npy(dx).reshape(ref.shape), ref) <= TOL[dtype] and intact(fx), (lay, call.__name__)
+    for Mr, D, G in ((1, 8, 1), (37, 48, 3), (333, 128, 4), (130, 512, 8), (259, 1024, 16), (77, 1032, 3), (19, 4096, 8), (5, 2056, 1)):
+        g = torch.Generator(device="cuda").manual_seed(Mr * D)
+        lay = (Mr, G, D // G)
+        x = (torch.randn((Mr, D), device="cuda", generator=g) * 1.3 + 0.3).to(dtype)
+        a = torch.zeros(G, device="cuda")
+        b = torch.zeros(G, device="cuda")
+        ws = torch.empty(max(M.workspace_bytes(M.OP_UPDATE_RUNNING_PARAMS, *lay, M.F16), 16), dtype=torch.uint8, device="cuda")
+        M.mesa_update_running_params(x, lay, a, b, 0.9, True, ws)
+        q = torch.empty(Mr * D, dtype=torch.int8, device="cuda")
+        M.mesa_quantize_headwise(x, lay, a, b, q, M.ROUND_STOCHASTIC, 2, 0)
+        xf = x.float()
+        mean = xf.mean(-1).contiguous()
+        rstd = (1.0 / torch.sqrt(xf.var(-1, unbiased=False) + 1e-5)).contiguous()
+        gamma = (1 + 0.1 * torch.randn(D, device="cuda", generator=g)).to(dtype)
+        dy = torch.randn((Mr, D), device="cuda", generator=g).to(dtype)
+        fx, dx = framed((Mr, D), dtype)
+        fg, dg = framed((D,), torch.float32)
+        fb, db = framed((D,), torch.float32)
+        w2 = torch.empty(max(M.workspace_bytes(M.OP_LAYERNORM_BWD_Q, Mr, D, G, M.F16), 16), dtype=torch.uint8, device="cuda")
+        M.mesa_layernorm_bwd_q(q, Mr, D, G, a, b, mean, rstd, gamma, dy, dx, dg, db, w2)
+        rdx, rdg, rdb = R.layernorm_bwd_q(npy(q), Mr, D, G, npy(a), npy(b), npy(mean), npy(rstd), npy(gamma), npy(dy))
+        assert relerr(npy(dx), rdx) <= TOL[dtype] and relerr(npy(dg), rdg) <= TOL[dtype] and relerr(npy(db), rdb) <= TOL[dtype], (Mr, D, G)
+        assert intact(fx) and intact(fg) and intact(fb), (Mr, D, G)
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16, torch.float32], ids=["f16", "bf16", "f32"])
+def test_linear_dw_keeps_inside_its_outputs(M, dtype):
+    """dW and db framed by sentinels, over every tile variant (256 x 256, 256 x 128, 128 x 128, the binary32 path)
+    with partial tiles in both extents and ragged slices of m."""
+    for Mr, K, N in ((31, 16, 8), (97, 128, 264), (3205, 256, 520), (909, 784, 136), (9000, 272, 1000), (5000, 96, 384), (777, 1280, 72)):
+        H = 1 if K % 3 else 3
+        lay = (Mr, H, K // H)
+        g = torch.Generator(device="cuda").manual_seed(Mr + K)
+        q = torch.randint(-128, 128, (Mr * K,), dtype=torch.int8, device="cuda", generator=g)
+        a = torch.linspace(1.0, 3.0, H, device="cuda")
+        b = torch.linspace(-1.5, -0.5, H, device="cuda")
+        dy = torch.randn((Mr, N), device="cuda", generator=g).to(dtype)
+        fW, dW = framed((N, K), torch.float32)
+        fb, db = framed((N,), torch.float32)
+        dtc = {torch.float16: M.F16, torch.bfloat16: M.BF16, torch.float32: M.F32}[dtype]
+        ws = torch.empty(max(M.workspace_bytes(M.OP_LINEAR_DW_Q, Mr, K, N, dtc), 16), dtype=torch.uint8, device="cuda")
+        M.mesa_linear_dw_q(q, Mr, K, H, a, b, dy, N, dW, db, ws)
+        rW, rb_ = R.linear_dw_q(npy(q), Mr, K, H, npy(a), npy(b), npy(dy), N)
+        assert relerr(npy(dW), rW) <= 2e-3 and relerr(npy(db), rb_) <= 2e-3, (Mr, K, N)
+        assert intact(fW) and intact(fb), (Mr, K, N)
