@@ -85,3 +85,75 @@ def test_a_captured_step_replays_to_the_eager_results(M):
         for k, ref in eager[t].items():
             got = st[k] if k in st else buf[k]
             assert torch.equal(got, ref), (t, k)
+
+
+def test_captured_layer_forwards_and_the_remaining_backwards_replay_exactly(M):
+    """The calls the first test leaves out: the three layer forwards (dynamic LDS, running estimates read and
+    moved inside one call), LayerNorm backward, the fixed-offset update, ReLU backward, de-quantize and the
+    Q K^T product's backward."""
+    dev = "cuda"
+    B, H, N, Dh = 4, 3, 49, 32
+    D, mlp = H * Dh, 4 * H * Dh
+    Mr = B * N
+    g = torch.Generator(device=dev).manual_seed(9)
+    s = (torch.randn((B, H, N, N), device=dev, generator=g) * 2).half()
+    xg = (torch.randn((Mr, mlp), device=dev, generator=g) * 1.5).half()
+    xl = (torch.randn((Mr, D), device=dev, generator=g) + 0.3).half()
+    gamma = (1 + 0.1 * torch.randn(D, device=dev, generator=g)).half()
+    bias = (0.1 * torch.randn(D, device=dev, generator=g)).half()
+    dyl = torch.randn((Mr, D), device=dev, generator=g).half()
+    dyg = torch.randn((Mr, mlp), device=dev, generator=g).half()
+    dS = (torch.randn((B, H, N, N), device=dev, generator=g) * 0.1).half()
+    kq = torch.randint(-128, 128, (B, H, N, Dh), dtype=torch.int8, device=dev, generator=g)
+    lay_g, lay_l = (Mr, H, mlp // H), (Mr, H, D // H)
+    init = {"aa": torch.full((H,), 0.8, device=dev), "ba": torch.full((H,), 0.0, device=dev),
+            "ag": torch.full((H,), 6.0, device=dev), "bg": torch.full((H,), -3.0, device=dev),
+            "al": torch.full((H,), 5.0, device=dev), "bl": torch.full((H,), -2.5, device=dev),
+            "af": torch.full((H,), 4.0, device=dev), "bf": torch.full((H,), -0.17, device=dev)}
+    st = {k: v.clone() for k, v in init.items()}
+    buf = {"y": torch.empty_like(s), "qa": torch.empty(s.numel(), dtype=torch.int8, device=dev),
+           "yg": torch.empty_like(xg), "qg": torch.empty(xg.numel(), dtype=torch.int8, device=dev),
+           "yl": torch.empty_like(xl), "ql": torch.empty(xl.numel(), dtype=torch.int8, device=dev),
+           "mean": torch.empty(Mr, device=dev), "rstd": torch.empty(Mr, device=dev),
+           "dxl": torch.empty_like(dyl), "dgamma": torch.empty(D, device=dev), "dbeta": torch.empty(D, device=dev),
+           "dxr": torch.empty_like(dyg), "xhat": torch.empty_like(xg),
+           "dQ": torch.empty((B, H, N, Dh), dtype=torch.half, device=dev), "dK": torch.empty((B, H, N, Dh), dtype=torch.half, device=dev)}
+    w_s = ws(M, M.OP_SOFTMAX_FWD_Q, B * H * N, H, N)
+    w_g = ws(M, M.OP_UPDATE_RUNNING_PARAMS, *lay_g)
+    w_lf = ws(M, M.OP_LAYERNORM_FWD_Q, Mr, D, H)
+    w_lb = ws(M, M.OP_LAYERNORM_BWD_Q, Mr, D, H)
+
+    def step():
+        M.mesa_softmax_fwd_q(s, B, H, N, N, st["aa"], st["ba"], 0.9, buf["y"], buf["qa"], w_s, M.ROUND_STOCHASTIC, 7, 0)
+        M.mesa_gelu_fwd_q(xg, lay_g, st["ag"], st["bg"], 0.9, buf["yg"], buf["qg"], w_g, M.ROUND_STOCHASTIC, 8, 0)
+        M.mesa_layernorm_fwd_q(xl, Mr, D, H, gamma, bias, 1e-5, st["al"], st["bl"], 0.9, buf["yl"], buf["mean"], buf["rstd"], buf["ql"],
+                               w_lf, M.ROUND_NEAREST_EVEN, 0, 0)
+        M.mesa_update_running_params_fixed_beta(buf["yg"], lay_g, st["af"], st["bf"], 0.9, False, -0.17, w_g)
+        M.mesa_layernorm_bwd_q(buf["ql"], Mr, D, H, st["al"], st["bl"], buf["mean"], buf["rstd"], gamma, dyl, buf["dxl"], buf["dgamma"],
+                               buf["dbeta"], w_lb)
+        M.mesa_relu_bwd_q(buf["qg"], lay_g, st["ag"], st["bg"], dyg, buf["dxr"])
+        M.mesa_dequantize(buf["qg"], lay_g, st["ag"], st["bg"], buf["xhat"])
+        M.mesa_attn_qk_bwd_q(buf["ql"], kq, B, H, N, Dh, st["al"], st["bl"], st["ag"], st["bg"], dS, 0.25, buf["dQ"], buf["dK"])
+
+    eager = []
+    for _ in range(3):
+        step()
+        torch.cuda.synchronize()
+        eager.append({k: v.clone() for k, v in list(st.items()) + list(buf.items())})
+    for k in st:
+        st[k].copy_(init[k])
+    for v in buf.values():
+        v.zero_()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    scratch = torch.empty_like(dyl)
+    for t in range(3):
+        graph.replay()
+        scratch.copy_(buf["dxl"])                     # the program's own eager work between replays
+        scratch.mul_(0.5)
+        torch.cuda.synchronize()
+        for k, ref in eager[t].items():
+            got = st[k] if k in st else buf[k]
+            assert torch.equal(got, ref), (t, k)
