@@ -163,7 +163,7 @@ mesa_status mesa_gelu_fwd_q(const void *x, mesa_dtype dt, mesa_layout L,
  *   q = codes of the STORED y, head-wise, with alpha, beta as they are on entry, Eq. (3)-(4);
  *   alpha, beta then moved by the per-head extrema of the stored y, Eq. (6)-(7).
  * I.e. mesa_quantize_update_fused applied to y with the layout {B, H, rows*cols}, without the pass
- * that reads y back.  Per binary16 element 2 bytes in, 2 + 1 bytes out.
+ * that reads y back.  Logits of -infinity (a mask) get probability 0; every row needs one finite logit.  Per binary16 element 2 bytes in, 2 + 1 bytes out.
  * s: [B*H*rows*cols] of dt (in).  y: same (out), not aliasing s.  q: int8 (out).
  * alpha, beta: [H] (in/out).  ws: MESA_OP_SOFTMAX_FWD_Q bytes.  Limits: rows of up to 256 elements: any
  * length (with more than 256 heads such rows may fall under the next rule); longer rows as for

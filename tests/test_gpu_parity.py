@@ -628,3 +628,29 @@ def test_in_place_gradients_and_determinism(M):
     dyb = dya.clone()
     M.mesa_softmax_bwd_q(qa, Bq, Hq, r, c, a, b, dyb, dyb)
     assert torch.equal(dxa, dyb)
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=DTYPE_IDS)
+@pytest.mark.parametrize("rows,cols", [(49, 49), (197, 197), (5, 300)])
+def test_softmax_layer_forward_with_masked_logits(M, rows, cols, dtype):
+    """Logits of -inf (an attention mask) get probability exactly 0 and do not disturb the rest of their row, in
+    the short-row and in the long-row kernel; rows keep at least one finite logit."""
+    B, H = 2, 3
+    gen = torch.Generator(device="cuda").manual_seed(rows + cols)
+    s = (torch.randn((B, H, rows, cols), generator=gen, device="cuda") * 3).to(dtype)
+    mask = torch.rand((B, H, rows, cols), generator=gen, device="cuda") < 0.4
+    mask[..., 0] = False
+    s = s.masked_fill(mask, float("-inf")).contiguous()
+    y = torch.empty_like(s)
+    q = torch.empty(s.numel(), dtype=torch.int8, device="cuda")
+    a = torch.full((H,), 0.9, device="cuda")
+    b = torch.zeros(H, device="cuda")
+    ra, rb = npy(a).copy(), npy(b).copy()
+    ws = torch.empty(max(M.workspace_bytes(M.OP_SOFTMAX_FWD_Q, B * H * rows, H, cols, M.F16), 16), dtype=torch.uint8, device="cuda")
+    M.mesa_softmax_fwd_q(s, B, H, rows, cols, a, b, 0.9, y, q, ws, M.ROUND_STOCHASTIC, 1, 2)
+    yh = npy(y)
+    assert np.all(yh[npy(mask)] == 0.0) and np.all(np.isfinite(yh))
+    assert relerr(yh, R.softmax_fwd(npy(s), B * H * rows, cols)) <= TOL[dtype]
+    rq, ra2, rb2 = R.quantize_update_fused(yh, (B, H, rows * cols), ra, rb, 0.9, R.ROUND_STOCHASTIC, 1, 2)
+    assert np.array_equal(npy(q), rq.reshape(-1))
+    assert np.array_equal(canon(npy(a)), canon(ra2)) and np.array_equal(canon(npy(b)), canon(rb2))
