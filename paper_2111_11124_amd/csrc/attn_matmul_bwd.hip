@@ -17,7 +17,7 @@
 // vectors inside the extents, single elements and zero fill at the edges, so any extents work) and
 // kept in the operand's own orientation; where that is not the orientation the MFMA wants, the
 // fragments come from the LDS transpose reads.  The next stage's loads are in flight while a stage
-// is multiplied.  binary16 tensors; bfloat16 tensors through the general kernel (k_bmm_q) only.
+// is multiplied.  binary16 or bfloat16 tensors (every kernel here takes the number type as a parameter).
 #include <hip/hip_runtime.h>
 
 #include "api_util.hpp"
@@ -70,6 +70,21 @@ template <> struct BmNum<_Float16> {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
     }
     __device__ static __forceinline__ _Float16 round(float v) { return (_Float16)v; }
+    // eight codes gathered two to a register (bits 0-7 and 16-23): 0x6400 | (byte ^ 0x80) is 1024 + x_bar, minus 1152
+    __device__ static __forceinline__ bm_v8h gathered(bm_v4u u)
+    {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) u[k] = (u[k] ^ 0x00800080u) | 0x64006400u;
+        bm_v8h f = __builtin_bit_cast(bm_v8h, u);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) f[k] = f[k] - (_Float16)1152.0f;
+        return f;
+    }
+    // acc + the two values of a register pair
+    __device__ static __forceinline__ float dot_ones(_Float16 a, _Float16 b, float acc)
+    {
+        return __builtin_amdgcn_fdot2(bm_v2h{a, b}, bm_v2h{(_Float16)1.0f, (_Float16)1.0f}, acc, false);
+    }
 };
 template <> struct BmNum<__bf16> {
     static constexpr float kCentre = 0.0f;
@@ -94,6 +109,21 @@ template <> struct BmNum<__bf16> {
     __device__ static __forceinline__ _Float16 round(float v)   // the bits of the bfloat16, in the 16-bit container
     {
         return __builtin_bit_cast(_Float16, __bf16(v));
+    }
+    __device__ static __forceinline__ bm_v8h gathered(bm_v4u u)
+    {
+        bm_v4u out;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t x = u[k] ^ 0x00800080u;
+            out[k] = __builtin_amdgcn_perm(__float_as_uint(float((x >> 16) & 0xFFu)), __float_as_uint(float(x & 0xFFu)), 0x07060302u);
+        }
+        return __builtin_bit_cast(bm_v8h, out);
+    }
+    __device__ static __forceinline__ float dot_ones(_Float16 a, _Float16 b, float acc)
+    {
+        typedef __bf16 v2b __attribute__((ext_vector_type(2)));
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(v2b, bm_v2h{a, b}), __builtin_bit_cast(v2b, 0x3F803F80u), acc, false);
     }
 };
 
@@ -375,7 +405,7 @@ template <int KS> struct DaCfg {
     static size_t lds_bytes(int64_t N, bool solo) { return solo ? kWaves * wave_bytes(N) : codes_at(N) + size_t(kWaves) * 32 * kRowV; }
 };
 
-template <int KS, bool SOLO>
+template <int KS, bool SOLO, typename ET>
 __global__ __launch_bounds__(kThreads, KS <= 4 ? 7 : 4) void k_attn_da(const _Float16 *__restrict__ dO,
                                                                       const int8_t *__restrict__ vq, _Float16 *__restrict__ dA,
                                                                       int N, int heads, const float *__restrict__ alpha_v,
@@ -452,13 +482,13 @@ __global__ __launch_bounds__(kThreads, KS <= 4 ? 7 : 4) void k_attn_da(const _Fl
         fo[ks] = *reinterpret_cast<const bm_v8h *>(lds_da + fl * C::kRowO + (ks * 16 + fk) * 2);
 #pragma unroll
         for (int j = 0; j < 8; j += 2)
-            rsum = __builtin_amdgcn_fdot2(bm_v2h{fo[ks][j], fo[ks][j + 1]}, bm_v2h{(_Float16)1.0f, (_Float16)1.0f}, rsum, false);
+            rsum = BmNum<ET>::dot_ones(fo[ks][j], fo[ks][j + 1], rsum);
     }
     rsum += __shfl_xor(rsum, 32);                          // both halves of the row's slots
     team_sync();                                           // every wave holds its fragments: the space becomes the output block
     const int h = int(bh % heads);
     const float s = alpha_v[h] / 255.0f;
-    const float add = fmaf(128.0f, s, beta_v[h]) * rsum;
+    const float add = fmaf(BmNum<ET>::kCentre, s, beta_v[h]) * rsum;
 
     const int64_t e0 = (bh * N + r0) * int64_t(N);         // first element of the output block
     const int mis = int(e0 & 7);                           // its offset from a 16-byte boundary, in elements
@@ -470,12 +500,12 @@ __global__ __launch_bounds__(kThreads, KS <= 4 ? 7 : 4) void k_attn_da(const _Fl
         if (cbk + cb_step < nblocks) load_codes(c0 + 32 * cb_step, raw);   // the wave's next block
         bm_v8h fc[KS];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) fc[ks] = bm_codes_to_half8(*reinterpret_cast<const bm_v2i *>(lv + fl * C::kRowV + ks * 16 + fk));
+        for (int ks = 0; ks < KS; ++ks) fc[ks] = BmNum<ET>::codes8(*reinterpret_cast<const bm_v2i *>(lv + fl * C::kRowV + ks * 16 + fk));
         bm_v16f acc;
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(fc[ks], fo[ks], acc, 0, 0, 0);
+        for (int ks = 0; ks < KS; ++ks) acc = BmNum<ET>::mfma(fc[ks], fo[ks], acc);
         // lane l, register v: column c0 + 8*(v/4) + 4*(l/32) + v%4, row l%32
         if (fl < rows) {
             const int at = mis + fl * N + c0 + (lane >> 5) * 4;
@@ -489,7 +519,7 @@ __global__ __launch_bounds__(kThreads, KS <= 4 ? 7 : 4) void k_attn_da(const _Fl
                 for (int g = 0; g < 4; ++g) {
                     bm_v4h o;
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) o[k] = (_Float16)fmaf(s, acc[4 * g + k], add);
+                    for (int k = 0; k < 4; ++k) o[k] = BmNum<ET>::round(fmaf(s, acc[4 * g + k], add));
                     _Float16 *q = lo + at + 8 * g;
                     q[0] = o[0];
                     q[3] = o[3];
@@ -501,7 +531,7 @@ __global__ __launch_bounds__(kThreads, KS <= 4 ? 7 : 4) void k_attn_da(const _Fl
                 for (int g = 0; g < 4; ++g)
 #pragma unroll
                     for (int k = 0; k < 4; ++k)
-                        if (c0 + (lane >> 5) * 4 + 8 * g + k < N) lo[at + 8 * g + k] = (_Float16)fmaf(s, acc[4 * g + k], add);
+                        if (c0 + (lane >> 5) * 4 + 8 * g + k < N) lo[at + 8 * g + k] = BmNum<ET>::round(fmaf(s, acc[4 * g + k], add));
             }
         }
     }
@@ -551,7 +581,7 @@ template <int DT, int JB, int NW> constexpr int tn_waves_per_simd()
     return (NW < 4 ? DT <= 2 : DT * JB <= 4 && DT < 4) ? 3 : DT * JB <= 6 ? 2 : 1;
 }
 
-template <int DT, int JB, bool WIDE_CODED, int NW>
+template <int DT, int JB, bool WIDE_CODED, int NW, typename ET>
 __global__ __launch_bounds__(64 * NW, (tn_waves_per_simd<DT, JB, NW>())) void k_attn_tn(const void *__restrict__ wide_, const void *__restrict__ narrow_,
                                                          _Float16 *__restrict__ out, int N, int heads, float scale,
                                                          const float *__restrict__ alpha, const float *__restrict__ beta,
@@ -646,7 +676,7 @@ __global__ __launch_bounds__(64 * NW, (tn_waves_per_simd<DT, JB, NW>())) void k_
         for (int v = 0; v < 16; ++v) acc1[dt][v] = 0.0f;
     bm_v8h ones;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) ones[j] = (_Float16)1.0f;
+    for (int j = 0; j < 8; ++j) ones[j] = __builtin_bit_cast(_Float16, BmNum<ET>::kOne);
     const int blk = lane >> 4, sl = lane & 15;
 
     load_chunk(0);
@@ -672,10 +702,10 @@ __global__ __launch_bounds__(64 * NW, (tn_waves_per_simd<DT, JB, NW>())) void k_
                     const bm_v4h lo = __builtin_bit_cast(bm_v4h, __builtin_amdgcn_ds_read_tr16_b64_v4i16(BM_LDS3(bm_v4s, p)));
                     const bm_v4h hi = __builtin_bit_cast(bm_v4h, __builtin_amdgcn_ds_read_tr16_b64_v4i16(BM_LDS3(bm_v4s, p + 4 * C::kRowNarrow)));
                     fn[dt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    acc1[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fn[dt], ones, acc1[dt], 0, 0, 0);
+                    acc1[dt] = BmNum<ET>::mfma(fn[dt], ones, acc1[dt]);
                 } else {
                     const unsigned char *p = ln + (ks * 16 + (blk >> 1) * 8 + (sl >> 1)) * C::kRowNarrow + dt * 32 + (blk & 1) * 16 + (sl & 1) * 8;
-                    fn[dt] = bm_codes_to_half8(__builtin_amdgcn_ds_read_tr8_b64_v2i32(BM_LDS3(bm_v2i, p)));
+                    fn[dt] = BmNum<ET>::codes8(__builtin_amdgcn_ds_read_tr8_b64_v2i32(BM_LDS3(bm_v2i, p)));
                 }
             }
 #pragma unroll
@@ -687,18 +717,12 @@ __global__ __launch_bounds__(64 * NW, (tn_waves_per_simd<DT, JB, NW>())) void k_
                 bm_v8h fw;
                 if (WIDE_CODED) {
                     // rows past the end meet zeros of the other operand: any code will do there
-                    unsigned u[4];
+                    bm_v4u u;
 #pragma unroll
                     for (int k = 0; k < 4; ++k)            // two codes per register: bits 0-7 and 16-23
                         u[k] = unsigned(reinterpret_cast<const unsigned char *>(lw)[at + (2 * k) * N]) |
                                (unsigned(reinterpret_cast<const unsigned char *>(lw)[at + (2 * k + 1) * N]) << 16);
-                    // stored byte -> binary16 of the signed code: (0x6400 | byte ^ 0x80) = 1024 + x_bar, minus 1152
-                    bm_v4u w4;
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) w4[k] = (u[k] ^ 0x00800080u) | 0x64006400u;
-                    fw = __builtin_bit_cast(bm_v8h, w4);
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) fw[k] = fw[k] - (_Float16)1152.0f;
+                    fw = BmNum<ET>::gathered(u);           // stored bytes -> operand values
                 } else {
 #pragma unroll
                     for (int k = 0; k < 8; ++k) fw[k] = reinterpret_cast<const _Float16 *>(lw)[at + k * N];
@@ -711,10 +735,10 @@ __global__ __launch_bounds__(64 * NW, (tn_waves_per_simd<DT, JB, NW>())) void k_
                     }
 #pragma unroll
                     for (int k = 0; k < 8; k += 2)
-                        csum[jb] = __builtin_amdgcn_fdot2(bm_v2h{fw[k], fw[k + 1]}, bm_v2h{(_Float16)1.0f, (_Float16)1.0f}, csum[jb], false);
+                        csum[jb] = BmNum<ET>::dot_ones(fw[k], fw[k + 1], csum[jb]);
                 }
 #pragma unroll
-                for (int dt = 0; dt < DT; ++dt) acc[jb][dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fn[dt], fw, acc[jb][dt], 0, 0, 0);
+                for (int dt = 0; dt < DT; ++dt) acc[jb][dt] = BmNum<ET>::mfma(fn[dt], fw, acc[jb][dt]);
             }
         }
     }
@@ -722,7 +746,7 @@ __global__ __launch_bounds__(64 * NW, (tn_waves_per_simd<DT, JB, NW>())) void k_
     // ---- epilogue: lane l, register v of a tile: d = 32*dt + 8*(v/4) + 4*(l/32) + v%4, row j = j0 + l%32 ----
     const int h = int(bh % heads);
     const float s = alpha[h] / 255.0f;
-    const float off = fmaf(128.0f, s, beta[h]);
+    const float off = fmaf(BmNum<ET>::kCentre, s, beta[h]);
 #pragma unroll
     for (int jb = 0; jb < JB; ++jb) {
         const int j = (wave + NW * jb) * 32 + fl;
@@ -738,7 +762,7 @@ __global__ __launch_bounds__(64 * NW, (tn_waves_per_simd<DT, JB, NW>())) void k_
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     const float add = WIDE_CODED ? off * acc1[dt][4 * g + k] : cs;
-                    o[k] = (_Float16)(scale * fmaf(s, acc[jb][dt][4 * g + k], add));
+                    o[k] = BmNum<ET>::round(scale * fmaf(s, acc[jb][dt][4 * g + k], add));
                 }
                 *reinterpret_cast<bm_v4h *>(po + dt * 32 + g * 8) = o;
             }
@@ -764,7 +788,7 @@ template <int DT> struct NnCfg {
     static size_t lds_bytes(int64_t N) { return ds_bytes(N) + size_t(ceil_div(N, 16)) * 16 * kRowK; }
 };
 
-template <int DT>
+template <int DT, typename ET>
 __global__ __launch_bounds__(NnCfg<DT>::kNt, 3) void k_attn_nn(const _Float16 *__restrict__ dS, const int8_t *__restrict__ kq,
                                                          _Float16 *__restrict__ dQ, int N, int heads, float scale,
                                                          const float *__restrict__ alpha_k, const float *__restrict__ beta_k,
@@ -828,7 +852,7 @@ __global__ __launch_bounds__(NnCfg<DT>::kNt, 3) void k_attn_nn(const _Float16 *_
     const unsigned *lds32 = reinterpret_cast<const unsigned *>(lds_nn);
     const int h = int(bh % heads);
     const float s = alpha_k[h] / 255.0f;
-    const float off = fmaf(128.0f, s, beta_k[h]);
+    const float off = fmaf(BmNum<ET>::kCentre, s, beta_k[h]);
 
     for (int c = 0; c < nchunks; ++c) {
         __syncthreads();                                   // the previous chunk has been multiplied
@@ -862,11 +886,11 @@ __global__ __launch_bounds__(NnCfg<DT>::kNt, 3) void k_attn_nn(const _Float16 *_
             const bm_v8h fs = __builtin_bit_cast(bm_v8h, f);
 #pragma unroll
             for (int q = 0; q < 8; q += 2)
-                rsum = __builtin_amdgcn_fdot2(bm_v2h{fs[q], fs[q + 1]}, bm_v2h{(_Float16)1.0f, (_Float16)1.0f}, rsum, false);
+                rsum = BmNum<ET>::dot_ones(fs[q], fs[q + 1], rsum);
 #pragma unroll
             for (int t = 0; t < C::kTiles; ++t) {
-                const bm_v8h fc = bm_codes_to_half8(__builtin_amdgcn_ds_read_tr8_b64_v2i32(BM_LDS3(bm_v2i, pk + j0 * C::kRowK + t * 32)));
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fc, fs, acc[t], 0, 0, 0);
+                const bm_v8h fc = BmNum<ET>::codes8(__builtin_amdgcn_ds_read_tr8_b64_v2i32(BM_LDS3(bm_v2i, pk + j0 * C::kRowK + t * 32)));
+                acc[t] = BmNum<ET>::mfma(fc, fs, acc[t]);
             }
         }
         rsum += __shfl_xor(rsum, 32);                      // both halves of the row's slots
@@ -880,7 +904,7 @@ __global__ __launch_bounds__(NnCfg<DT>::kNt, 3) void k_attn_nn(const _Float16 *_
                 for (int g = 0; g < 4; ++g) {
                     bm_v4h o;
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) o[k] = (_Float16)(scale * fmaf(s, acc[t][4 * g + k], add));
+                    for (int k = 0; k < 4; ++k) o[k] = BmNum<ET>::round(scale * fmaf(s, acc[t][4 * g + k], add));
                     *reinterpret_cast<bm_v4h *>(po + t * 32 + g * 8) = o;
                 }
         }
@@ -891,21 +915,21 @@ __global__ __launch_bounds__(NnCfg<DT>::kNt, 3) void k_attn_nn(const _Float16 *_
 static bool da_solo(int64_t batches, int64_t N) { return N <= 64 && batches * ceil_div(N, 32) < (int64_t(1) << 32); }
 template <int KS> static bool da_fits(int64_t batches, int64_t N) { return DaCfg<KS>::lds_bytes(N, da_solo(batches, N)) <= 65536; }
 
-template <int KS> static void launch_da(const _Float16 *dO, const int8_t *vq, _Float16 *dA, int64_t batches, int N, int heads,
+template <int KS, typename ET> static void launch_da(const _Float16 *dO, const int8_t *vq, _Float16 *dA, int64_t batches, int N, int heads,
                                         const float *alpha_v, const float *beta_v, hipStream_t s)
 {
     typedef DaCfg<KS> C;
     const int codes_at = int(C::codes_at(N));
     if (da_solo(batches, N)) {
         const int64_t items = batches * ceil_div(N, 32);
-        hipLaunchKernelGGL((k_attn_da<KS, true>), dim3(unsigned(ceil_div(items, C::kWaves))), dim3(kThreads), C::lds_bytes(N, true), s, dO,
+        hipLaunchKernelGGL((k_attn_da<KS, true, ET>), dim3(unsigned(ceil_div(items, C::kWaves))), dim3(kThreads), C::lds_bytes(N, true), s, dO,
                            vq, dA, N, heads, alpha_v, beta_v, int64_t(0), codes_at, unsigned(items));
         return;
     }
     const unsigned gx = unsigned(ceil_div(N, 32));
     for (int64_t b0 = 0; b0 < batches; b0 += 65535) {   // the y extent of a grid is limited to 65535
         const int64_t nb = batches - b0 < 65535 ? batches - b0 : 65535;
-        hipLaunchKernelGGL((k_attn_da<KS, false>), dim3(gx, unsigned(nb)), dim3(kThreads), C::lds_bytes(N, false), s, dO, vq, dA, N,
+        hipLaunchKernelGGL((k_attn_da<KS, false, ET>), dim3(gx, unsigned(nb)), dim3(kThreads), C::lds_bytes(N, false), s, dO, vq, dA, N,
                            heads, alpha_v, beta_v, b0, codes_at, 0u);
     }
 }
@@ -922,26 +946,26 @@ template <bool WIDE_CODED> static bool tn_fits(int64_t N, int64_t Dh)
     return 2 * (wide + narrow) <= 65536;
 }
 
-template <int DT, int JB, bool WIDE_CODED, int NW>
+template <int DT, int JB, bool WIDE_CODED, int NW, typename ET>
 static void launch_tn_one(const void *wide, const void *narrow, _Float16 *out, int64_t batches, int N, int heads, float scale,
                           const float *alpha, const float *beta, hipStream_t s)
 {
     typedef TnCfg<DT, JB, WIDE_CODED, NW> C;
-    hipLaunchKernelGGL((k_attn_tn<DT, JB, WIDE_CODED, NW>), dim3(unsigned(batches)), dim3(C::kNt), C::lds_bytes(N), s, wide, narrow,
+    hipLaunchKernelGGL((k_attn_tn<DT, JB, WIDE_CODED, NW, ET>), dim3(unsigned(batches)), dim3(C::kNt), C::lds_bytes(N), s, wide, narrow,
                        out, N, heads, scale, alpha, beta, int(C::wide_bytes(N)), batches * N * int64_t(N));
 }
 
-template <bool WIDE_CODED>
+template <bool WIDE_CODED, typename ET>
 static void launch_tn(const void *wide, const void *narrow, _Float16 *out, int64_t batches, int N, int Dh, int heads, float scale,
                       const float *alpha, const float *beta, hipStream_t s)
 {
     // waves per workgroup and blocks of j per wave, so that no wave is left without a block
 #define MESA_TN(DT_) \
     do { \
-        if (N <= 32) launch_tn_one<DT_, 1, WIDE_CODED, 1>(wide, narrow, out, batches, N, heads, scale, alpha, beta, s); \
-        else if (N <= 64) launch_tn_one<DT_, 1, WIDE_CODED, 2>(wide, narrow, out, batches, N, heads, scale, alpha, beta, s); \
-        else if (N <= 128) launch_tn_one<DT_, 1, WIDE_CODED, 4>(wide, narrow, out, batches, N, heads, scale, alpha, beta, s); \
-        else launch_tn_one<DT_, 2, WIDE_CODED, 4>(wide, narrow, out, batches, N, heads, scale, alpha, beta, s); \
+        if (N <= 32) launch_tn_one<DT_, 1, WIDE_CODED, 1, ET>(wide, narrow, out, batches, N, heads, scale, alpha, beta, s); \
+        else if (N <= 64) launch_tn_one<DT_, 1, WIDE_CODED, 2, ET>(wide, narrow, out, batches, N, heads, scale, alpha, beta, s); \
+        else if (N <= 128) launch_tn_one<DT_, 1, WIDE_CODED, 4, ET>(wide, narrow, out, batches, N, heads, scale, alpha, beta, s); \
+        else launch_tn_one<DT_, 2, WIDE_CODED, 4, ET>(wide, narrow, out, batches, N, heads, scale, alpha, beta, s); \
     } while (0)
     if (Dh == 32) MESA_TN(1);
     else if (Dh == 64) MESA_TN(2);
@@ -959,11 +983,11 @@ static bool nn_fits(int64_t N, int64_t Dh)
     return ds + ceil_div(N, 16) * 16 * (Dh + 32) <= 65536;
 }
 
-template <int DT> static void launch_nn(const _Float16 *dS, const int8_t *kq, _Float16 *dQ, int64_t batches, int N, int heads,
+template <int DT, typename ET> static void launch_nn(const _Float16 *dS, const int8_t *kq, _Float16 *dQ, int64_t batches, int N, int heads,
                                         float scale, const float *alpha_k, const float *beta_k, hipStream_t s)
 {
     typedef NnCfg<DT> C;
-    hipLaunchKernelGGL((k_attn_nn<DT>), dim3(unsigned(batches)), dim3(C::kNt), C::lds_bytes(N), s, dS, kq, dQ, N, heads, scale,
+    hipLaunchKernelGGL((k_attn_nn<DT, ET>), dim3(unsigned(batches)), dim3(C::kNt), C::lds_bytes(N), s, dS, kq, dQ, N, heads, scale,
                        alpha_k, beta_k, int(C::ds_bytes(N)), batches * N * int64_t(N));
 }
 
@@ -1007,37 +1031,32 @@ extern "C" MESA_EXPORT mesa_status mesa_attn_av_bwd_q(const int8_t *aq, const in
     a.R = int(N); a.Cn = int(N); a.Tn = int(Dh);
     a.p_rs = Dh; a.p_ts = 1; a.q_ts = 1; a.q_cs = Dh;
     a.alpha = alpha_v; a.beta = beta_v;
-    if (dt == MESA_BF16) {   // bfloat16 tensors: the general kernel for both products
-        launch_bmm<false, true, true, __bf16>(a, batches, s);
-        a.y = aq; a.c = static_cast<_Float16 *>(dV);
-        a.y_batch = N * N; a.c_batch = N * Dh;
-        a.R = int(N); a.Cn = int(Dh); a.Tn = int(N);
-        a.p_rs = 1; a.p_ts = N; a.q_ts = Dh; a.q_cs = 1;
-        a.alpha = alpha_a; a.beta = beta_a;
-        launch_bmm<true, false, false, __bf16>(a, batches, s);
-        return launch_status();
-    }
     // the 32 x N output block has to fit the 64 KiB of LDS a kernel gets by default; else the general kernel
-    if (Dh == 32 && da_fits<2>(batches, N))
-        launch_da<2>(a.x, vq, a.c, batches, int(N), int(H), alpha_v, beta_v, s);
-    else if (Dh == 64 && da_fits<4>(batches, N))
-        launch_da<4>(a.x, vq, a.c, batches, int(N), int(H), alpha_v, beta_v, s);
-    else if (Dh == 96 && da_fits<6>(batches, N))
-        launch_da<6>(a.x, vq, a.c, batches, int(N), int(H), alpha_v, beta_v, s);
-    else if (Dh == 128 && da_fits<8>(batches, N))
-        launch_da<8>(a.x, vq, a.c, batches, int(N), int(H), alpha_v, beta_v, s);
-    else
-        launch_bmm<false, true, true>(a, batches, s);
+#define MESA_AV_DA(ET) \
+    do { \
+        if (Dh == 32 && da_fits<2>(batches, N)) launch_da<2, ET>(a.x, vq, a.c, batches, int(N), int(H), alpha_v, beta_v, s); \
+        else if (Dh == 64 && da_fits<4>(batches, N)) launch_da<4, ET>(a.x, vq, a.c, batches, int(N), int(H), alpha_v, beta_v, s); \
+        else if (Dh == 96 && da_fits<6>(batches, N)) launch_da<6, ET>(a.x, vq, a.c, batches, int(N), int(H), alpha_v, beta_v, s); \
+        else if (Dh == 128 && da_fits<8>(batches, N)) launch_da<8, ET>(a.x, vq, a.c, batches, int(N), int(H), alpha_v, beta_v, s); \
+        else launch_bmm<false, true, true, ET>(a, batches, s); \
+    } while (0)
+    if (dt == MESA_BF16) MESA_AV_DA(__bf16); else MESA_AV_DA(_Float16);
+#undef MESA_AV_DA
     // dV[j,d] = sum_i A_hat[i,j] * dO[i,d]:  P = A (r = j, t = i),  Q = dO (t = i, c = d)
     a.y = aq; a.c = static_cast<_Float16 *>(dV);
     a.y_batch = N * N; a.c_batch = N * Dh;
     a.R = int(N); a.Cn = int(Dh); a.Tn = int(N);
     a.p_rs = 1; a.p_ts = N; a.q_ts = Dh; a.q_cs = 1;
     a.alpha = alpha_a; a.beta = beta_a;
-    if (tn_fits<true>(N, Dh) && batches < (int64_t(1) << 31))
-        launch_tn<true>(aq, dO, a.c, batches, int(N), int(Dh), int(H), 1.0f, alpha_a, beta_a, s);
-    else
-        launch_bmm<true, false, false>(a, batches, s);
+#define MESA_AV_DV(ET) \
+    do { \
+        if (tn_fits<true>(N, Dh) && batches < (int64_t(1) << 31)) \
+            launch_tn<true, ET>(aq, dO, a.c, batches, int(N), int(Dh), int(H), 1.0f, alpha_a, beta_a, s); \
+        else \
+            launch_bmm<true, false, false, ET>(a, batches, s); \
+    } while (0)
+    if (dt == MESA_BF16) MESA_AV_DV(__bf16); else MESA_AV_DV(_Float16);
+#undef MESA_AV_DV
     return launch_status();
 }
 
@@ -1066,27 +1085,29 @@ extern "C" MESA_EXPORT mesa_status mesa_attn_qk_bwd_q(const int8_t *qq, const in
     a.y = kq; a.c = static_cast<_Float16 *>(dQ);
     a.p_rs = N; a.p_ts = 1; a.q_ts = Dh; a.q_cs = 1;
     a.alpha = alpha_k; a.beta = beta_k;
-    if (dt == MESA_BF16) {   // bfloat16 tensors: the general kernel for both products
-        launch_bmm<false, true, false, __bf16>(a, batches, s);
-        a.y = qq; a.c = static_cast<_Float16 *>(dK);
-        a.p_rs = 1; a.p_ts = N; a.q_ts = Dh; a.q_cs = 1;
-        a.alpha = alpha_q; a.beta = beta_q;
-        launch_bmm<false, false, false, __bf16>(a, batches, s);
-        return launch_status();
-    }
-    if (nn_fits(N, Dh) && batches < (int64_t(1) << 31)) {
-        if (Dh == 32) launch_nn<1>(a.x, kq, a.c, batches, int(N), int(H), scale, alpha_k, beta_k, s);
-        else if (Dh == 64) launch_nn<2>(a.x, kq, a.c, batches, int(N), int(H), scale, alpha_k, beta_k, s);
-        else launch_nn<4>(a.x, kq, a.c, batches, int(N), int(H), scale, alpha_k, beta_k, s);
-    } else
-        launch_bmm<false, true, false>(a, batches, s);
+#define MESA_QK_DQ(ET) \
+    do { \
+        if (nn_fits(N, Dh) && batches < (int64_t(1) << 31)) { \
+            if (Dh == 32) launch_nn<1, ET>(a.x, kq, a.c, batches, int(N), int(H), scale, alpha_k, beta_k, s); \
+            else if (Dh == 64) launch_nn<2, ET>(a.x, kq, a.c, batches, int(N), int(H), scale, alpha_k, beta_k, s); \
+            else launch_nn<4, ET>(a.x, kq, a.c, batches, int(N), int(H), scale, alpha_k, beta_k, s); \
+        } else \
+            launch_bmm<false, true, false, ET>(a, batches, s); \
+    } while (0)
+    if (dt == MESA_BF16) MESA_QK_DQ(__bf16); else MESA_QK_DQ(_Float16);
+#undef MESA_QK_DQ
     // dK[j,d] = scale * sum_i dS[i,j] * Q_hat[i,d]:  P = dS (r = j, t = i),  Q = Q codes (t = i, c = d)
     a.y = qq; a.c = static_cast<_Float16 *>(dK);
     a.p_rs = 1; a.p_ts = N; a.q_ts = Dh; a.q_cs = 1;
     a.alpha = alpha_q; a.beta = beta_q;
-    if (tn_fits<false>(N, Dh) && batches < (int64_t(1) << 31))
-        launch_tn<false>(dS, qq, a.c, batches, int(N), int(Dh), int(H), scale, alpha_q, beta_q, s);
-    else
-        launch_bmm<false, false, false>(a, batches, s);
+#define MESA_QK_DK(ET) \
+    do { \
+        if (tn_fits<false>(N, Dh) && batches < (int64_t(1) << 31)) \
+            launch_tn<false, ET>(dS, qq, a.c, batches, int(N), int(Dh), int(H), scale, alpha_q, beta_q, s); \
+        else \
+            launch_bmm<false, false, false, ET>(a, batches, s); \
+    } while (0)
+    if (dt == MESA_BF16) MESA_QK_DK(__bf16); else MESA_QK_DK(_Float16);
+#undef MESA_QK_DK
     return launch_status();
 }

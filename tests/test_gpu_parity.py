@@ -379,9 +379,11 @@ def test_attention_matmul_backward_against_the_oracle(M, B, H, N, Dh):
     _attention_case(M, B, H, N, Dh, torch.float16)
 
 
-@pytest.mark.parametrize("B,H,N,Dh", [(2, 3, 19, 8), (2, 6, 197, 64), (3, 3, 49, 32), (1, 2, 130, 100), (1, 1, 65, 96), (1, 2, 8, 128)])
+@pytest.mark.parametrize("B,H,N,Dh", [(2, 3, 19, 8), (2, 6, 197, 64), (3, 3, 49, 32), (1, 2, 130, 100), (1, 1, 65, 96), (1, 2, 8, 128),
+                                      (2, 4, 64, 32), (1, 2, 300, 128), (3, 2, 40, 64), (1, 2, 24, 128), (1, 1, 255, 128), (1, 2, 223, 32),
+                                      (2, 1, 224, 64), (1, 1, 256, 96)])
 def test_attention_matmul_backward_bfloat16(M, B, H, N, Dh):
-    """The same products on bfloat16 tensors (the general kernel: full and partial tiles in every extent)."""
+    """The same products on bfloat16 tensors: every kernel variant and the general kernel."""
     _attention_case(M, B, H, N, Dh, torch.bfloat16)
 
 

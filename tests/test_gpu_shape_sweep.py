@@ -50,8 +50,9 @@ ATTN_N = (8, 9, 15, 16, 17, 31, 32, 33, 48, 63, 64, 65, 96, 127, 128, 129, 160, 
           256, 257)
 
 
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16], ids=["f16", "bf16"])
 @pytest.mark.parametrize("Dh", [32, 64, 96, 128, 8, 40])
-def test_attention_products_around_every_size_limit(M, Dh):
+def test_attention_products_around_every_size_limit(M, Dh, dtype):
     """Sequence lengths on both sides of each dedicated kernel's limits (chunk sizes, LDS capacity, the general
     kernel's tiles) for the head sizes with dedicated kernels and two without."""
     rnd = random.Random(Dh)
@@ -60,21 +61,21 @@ def test_attention_products_around_every_size_limit(M, Dh):
         g = torch.Generator(device="cuda").manual_seed(1000 * Dh + idx)
         aq = torch.randint(-128, 128, (B, H, N, N), dtype=torch.int8, device="cuda", generator=g)
         qq, kq, vq = (torch.randint(-128, 128, (B, H, N, Dh), dtype=torch.int8, device="cuda", generator=g) for _ in range(3))
-        dO = torch.randn((B, H, N, Dh), device="cuda", generator=g).half()
-        dS = (torch.randn((B, H, N, N), device="cuda", generator=g) * 0.1).half()
+        dO = torch.randn((B, H, N, Dh), device="cuda", generator=g).to(dtype)
+        dS = (torch.randn((B, H, N, N), device="cuda", generator=g) * 0.1).to(dtype)
         par = {k: (torch.linspace(1.0, 4.0, H, device="cuda") * s, torch.linspace(-2.0, -0.5, H, device="cuda") * s)
                for k, s in (("a", 0.25), ("q", 1.0), ("k", 1.5), ("v", 0.75))}
-        fA, dA = framed((B, H, N, N), torch.float16)
-        fV, dV = framed((B, H, N, Dh), torch.float16)
-        fQ, dQ = framed((B, H, N, Dh), torch.float16)
-        fK, dK = framed((B, H, N, Dh), torch.float16)
+        fA, dA = framed((B, H, N, N), dtype)
+        fV, dV = framed((B, H, N, Dh), dtype)
+        fQ, dQ = framed((B, H, N, Dh), dtype)
+        fK, dK = framed((B, H, N, Dh), dtype)
         M.mesa_attn_av_bwd_q(aq, vq, B, H, N, Dh, *par["a"], *par["v"], dO, dA, dV)
         M.mesa_attn_qk_bwd_q(qq, kq, B, H, N, Dh, *par["q"], *par["k"], dS, 0.2, dQ, dK)
         rp = {k: (npy(a), npy(b)) for k, (a, b) in par.items()}
         rdA, rdV = R.attn_av_bwd_q(npy(aq), npy(vq), B, H, N, Dh, *rp["a"], *rp["v"], npy(dO))
         rdQ, rdK = R.attn_qk_bwd_q(npy(qq), npy(kq), B, H, N, Dh, *rp["q"], *rp["k"], npy(dS), 0.2)
         errs = {"dA": relerr(npy(dA), rdA), "dV": relerr(npy(dV), rdV), "dQ": relerr(npy(dQ), rdQ), "dK": relerr(npy(dK), rdK)}
-        assert all(v <= TOL[torch.float16] for v in errs.values()), ((B, H, N, Dh), errs)
+        assert all(v <= TOL[dtype] for v in errs.values()), ((B, H, N, Dh), errs)
         assert all(intact(f) for f in (fA, fV, fQ, fK)), (B, H, N, Dh)
 
 
