@@ -17,7 +17,8 @@
 // vectors inside the extents, single elements and zero fill at the edges, so any extents work) and
 // kept in the operand's own orientation; where that is not the orientation the MFMA wants, the
 // fragments come from the LDS transpose reads.  The next stage's loads are in flight while a stage
-// is multiplied.  binary16 or bfloat16 tensors (every kernel here takes the number type as a parameter).
+// is multiplied.  binary16 or bfloat16 tensors (every kernel here takes the number type as a parameter);
+// binary32 tensors through one plain kernel (k_bmm_q_f32).
 #include <hip/hip_runtime.h>
 
 #include "api_util.hpp"
@@ -365,6 +366,59 @@ static void launch_bmm(BmmArgs a, int64_t batches, hipStream_t s)
         const int64_t nb = batches - b0 < 65535 ? batches - b0 : 65535;
         hipLaunchKernelGGL((k_bmm_q<P_CODED, P_TFAST, Q_TFAST, ET>), dim3(unsigned(a.tiles_c), unsigned(a.tiles_r), unsigned(nb)),
                            dim3(kThreads), 0, s, a);
+    }
+}
+
+// binary32 tensors: 32x32x2 binary32 MFMA with operands straight from global memory (a lane needs one value per
+// operand and step: lane l holds row / column l%32 at contraction slot l/32).  Kept simple: it serves the binary32
+// configuration, which is far too small to be a throughput case.  BmmArgs' 16-bit pointers carry binary32 here.
+template <bool P_CODED>
+__global__ __launch_bounds__(kThreads) void k_bmm_q_f32(BmmArgs a)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t b = blockIdx.z;
+    const int r = int(blockIdx.y) * kBmTile + (wave >> 1) * 32 + (lane & 31);
+    const int c = int(blockIdx.x) * kBmTile + (wave & 1) * 32 + (lane & 31);
+    const uint32_t h = (b + uint32_t(a.head0)) % uint32_t(a.heads);
+    const float *xb = reinterpret_cast<const float *>(a.x) + (int64_t(b) + a.batch0) * a.x_batch;
+    const int8_t *yb = a.y + (int64_t(b) + a.batch0) * a.y_batch;
+    const bool r_ok = r < a.R, c_ok = c < a.Cn;
+    bm_v16f acc, acc1;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { acc[v] = 0.0f; acc1[v] = 0.0f; }
+    for (int t0 = 0; t0 < a.Tn; t0 += 2) {
+        const int t = t0 + (lane >> 5);
+        const bool t_ok = t < a.Tn;
+        float pa = 0.0f, qb = 0.0f;
+        const int64_t po = int64_t(r) * a.p_rs + int64_t(t) * a.p_ts, qo = int64_t(t) * a.q_ts + int64_t(c) * a.q_cs;
+        if (t_ok && r_ok) pa = P_CODED ? float(int(yb[po])) : xb[po];
+        if (t_ok && c_ok) qb = P_CODED ? xb[qo] : float(int(yb[qo]));
+        const float one = t_ok ? 1.0f : 0.0f;
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(pa, qb, acc, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(P_CODED ? one : pa, P_CODED ? qb : one, acc1, 0, 0, 0);   // sums of the plain operand
+    }
+    const float s = a.alpha[h] / 255.0f;
+    const float off = fmaf(128.0f, s, a.beta[h]);
+    const int row_l = int(blockIdx.y) * kBmTile + (wave >> 1) * 32 + (lane >> 5) * 4;
+    float *cb = reinterpret_cast<float *>(a.c) + (int64_t(b) + a.batch0) * a.c_batch;
+    if (c_ok) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int rr = row_l + (v >> 2) * 8 + (v & 3);
+            if (rr < a.R) cb[int64_t(rr) * a.Cn + c] = a.scale * fmaf(s, acc[v], off * acc1[v]);
+        }
+    }
+}
+
+template <bool P_CODED> static void launch_bmm_f32(BmmArgs a, int64_t batches, hipStream_t s)
+{
+    a.tiles_r = int(ceil_div(a.R, kBmTile));
+    a.tiles_c = int(ceil_div(a.Cn, kBmTile));
+    for (int64_t b0 = 0; b0 < batches; b0 += 65535) {
+        a.batch0 = b0;
+        a.head0 = int(b0 % a.heads);
+        const int64_t nb = batches - b0 < 65535 ? batches - b0 : 65535;
+        hipLaunchKernelGGL((k_bmm_q_f32<P_CODED>), dim3(unsigned(a.tiles_c), unsigned(a.tiles_r), unsigned(nb)), dim3(kThreads), 0, s, a);
     }
 }
 
@@ -994,7 +1048,6 @@ template <int DT, typename ET> static void launch_nn(const _Float16 *dS, const i
 static mesa_status check_attn(int64_t B, int64_t H, int64_t N, int64_t Dh, mesa_dtype dt)
 {
     if (!valid_dtype(dt) || B < 0 || H < 0 || N < 0 || Dh < 0) return MESA_ERR_INVALID_ARG;
-    if (dt == MESA_F32) return MESA_ERR_UNSUPPORTED;
     if (N >= (int64_t(1) << 20) || Dh >= (int64_t(1) << 20)) return MESA_ERR_UNSUPPORTED;
     if ((N > 0 && N < 8) || (Dh > 0 && Dh < 8)) return MESA_ERR_UNSUPPORTED;   // an extent shorter than one load vector
     // 32-bit element offsets inside one (sample, head); the row / column tile counts fit a grid dimension
@@ -1031,6 +1084,16 @@ extern "C" MESA_EXPORT mesa_status mesa_attn_av_bwd_q(const int8_t *aq, const in
     a.R = int(N); a.Cn = int(N); a.Tn = int(Dh);
     a.p_rs = Dh; a.p_ts = 1; a.q_ts = 1; a.q_cs = Dh;
     a.alpha = alpha_v; a.beta = beta_v;
+    if (dt == MESA_F32) {
+        launch_bmm_f32<false>(a, batches, s);
+        a.y = aq; a.c = static_cast<_Float16 *>(dV);
+        a.y_batch = N * N; a.c_batch = N * Dh;
+        a.R = int(N); a.Cn = int(Dh); a.Tn = int(N);
+        a.p_rs = 1; a.p_ts = N; a.q_ts = Dh; a.q_cs = 1;
+        a.alpha = alpha_a; a.beta = beta_a;
+        launch_bmm_f32<true>(a, batches, s);
+        return launch_status();
+    }
     // the 32 x N output block has to fit the 64 KiB of LDS a kernel gets by default; else the general kernel
 #define MESA_AV_DA(ET) \
     do { \
@@ -1085,6 +1148,14 @@ extern "C" MESA_EXPORT mesa_status mesa_attn_qk_bwd_q(const int8_t *qq, const in
     a.y = kq; a.c = static_cast<_Float16 *>(dQ);
     a.p_rs = N; a.p_ts = 1; a.q_ts = Dh; a.q_cs = 1;
     a.alpha = alpha_k; a.beta = beta_k;
+    if (dt == MESA_F32) {
+        launch_bmm_f32<false>(a, batches, s);
+        a.y = qq; a.c = static_cast<_Float16 *>(dK);
+        a.p_rs = 1; a.p_ts = N; a.q_ts = Dh; a.q_cs = 1;
+        a.alpha = alpha_q; a.beta = beta_q;
+        launch_bmm_f32<false>(a, batches, s);
+        return launch_status();
+    }
 #define MESA_QK_DQ(ET) \
     do { \
         if (nn_fits(N, Dh) && batches < (int64_t(1) << 31)) { \

@@ -387,6 +387,12 @@ def test_attention_matmul_backward_bfloat16(M, B, H, N, Dh):
     _attention_case(M, B, H, N, Dh, torch.bfloat16)
 
 
+@pytest.mark.parametrize("B,H,N,Dh", [(2, 3, 19, 8), (2, 3, 197, 64), (1, 2, 65, 40), (2, 2, 49, 32)])
+def test_attention_matmul_backward_binary32(M, B, H, N, Dh):
+    """The same products on binary32 tensors (one plain kernel), to the binary32 bound."""
+    _attention_case(M, B, H, N, Dh, torch.float32)
+
+
 def _attention_case(M, B, H, N, Dh, dtype):
     gen = torch.Generator(device="cuda").manual_seed(B * 1000 + N)
     sig = torch.linspace(0.5, 2.0, H, device="cuda").view(1, H, 1, 1)
