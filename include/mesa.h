@@ -182,7 +182,7 @@ mesa_status mesa_softmax_fwd_q(const void *s, int64_t B, int64_t H, int64_t rows
  *   alpha, beta then moved by this batch's per-group extrema of x, Eq. (6)-(7)  (as mesa_quantize_update_fused).
  * x: (M, D) of dt (in).  gamma, bias: [D] of dt.  y: (M, D) of dt (out), not aliasing x.  mean, rstd: [M] binary32
  * (out).  q: int8 (out).  alpha, beta: [G] (in/out).  ws: MESA_OP_LAYERNORM_FWD_Q bytes.
- * Limits: D % 8 == 0, (D/G) % 8 == 0, D <= 1024, G <= 1024, else MESA_ERR_UNSUPPORTED.
+ * Limits: D % 8 == 0, (D/G) % 8 == 0, D <= 2048, G <= 1024, else MESA_ERR_UNSUPPORTED.
  */
 mesa_status mesa_layernorm_fwd_q(const void *x, int64_t M, int64_t D, int64_t G,
                                  const void *gamma, const void *bias, float eps,

@@ -44,9 +44,13 @@ __global__ __launch_bounds__(kThreads, 3) void k_layernorm_fwd(const void *__res
     const uint32_t sub = lane / LPR, l = lane % LPR;
     const uint32_t vpr = D / kVec;
 
+    // gamma and bias stay in registers for rows of up to 1024 elements; for longer rows they are read again for
+    // every row (a few KB that stay in the cache), which costs less than the registers would
+    constexpr bool kKeep = VPL <= 2;
+    constexpr int kHeld = kKeep ? VPL : 1;
     uint32_t col[VPL], grp[VPL];
     bool act[VPL];
-    float gam[VPL][8], bia[VPL][8], mn[VPL], mx[VPL];
+    float gam[kHeld][8], bia[kHeld][8], mn[VPL], mx[VPL];
     float2 prm[VPL];                                // (255 / alpha, beta) of the vector's channel group
 #pragma unroll
     for (int k = 0; k < VPL; ++k) {
@@ -57,11 +61,15 @@ __global__ __launch_bounds__(kThreads, 3) void k_layernorm_fwd(const void *__res
         mn[k] = __builtin_inff();
         mx[k] = -__builtin_inff();
         prm[k] = make_float2(0.0f, 0.0f);
+        if (kKeep) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) { gam[k][j] = 0.0f; bia[k][j] = 0.0f; }
+            for (int j = 0; j < 8; ++j) { gam[k % kHeld][j] = 0.0f; bia[k % kHeld][j] = 0.0f; }
+        }
         if (act[k]) {
-            Store<T>::unpack(Store<T>::load(gamma, col[k]), gam[k]);
-            Store<T>::unpack(Store<T>::load(bias, col[k]), bia[k]);
+            if (kKeep) {
+                Store<T>::unpack(Store<T>::load(gamma, col[k]), gam[k % kHeld]);
+                Store<T>::unpack(Store<T>::load(bias, col[k]), bia[k % kHeld]);
+            }
             grp[k] = fastdiv(cv, div_vpg);
             const float a = alpha[grp[k]];
             prm[k] = make_float2(a > 0.0f ? 255.0f / a : 0.0f, beta[grp[k]]);
@@ -115,8 +123,12 @@ __global__ __launch_bounds__(kThreads, 3) void k_layernorm_fwd(const void *__res
                 if (ok && act[k]) {
                     const int64_t e = row * D + col[k];
                     float o[8], w[8], bits[8];
+                    if (!kKeep) {
+                        Store<T>::unpack(Store<T>::load(gamma, col[k]), gam[0]);
+                        Store<T>::unpack(Store<T>::load(bias, col[k]), bia[0]);
+                    }
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) o[j] = fmaf((f[k][j] - mu) * rs, gam[k][j], bia[k][j]);
+                    for (int j = 0; j < 8; ++j) o[j] = fmaf((f[k][j] - mu) * rs, gam[k % kHeld][j], bia[k % kHeld][j]);
                     Nt<T>::store(y, e, Store<T>::pack(o));
                     if (SR) sr_bits(seed, offset + uint64_t(e >> 3), bits);
 #pragma unroll
@@ -155,9 +167,9 @@ static LfPlan lf_plan(int64_t M, int64_t D)
 {
     LfPlan p{};
     const int64_t vpr = D / kVec;
-    p.ok = D % kVec == 0 && vpr >= 1 && vpr <= 128;
+    p.ok = D % kVec == 0 && vpr >= 1 && vpr <= 256;
     if (!p.ok) return p;
-    p.vpl = vpr > 64 ? 2 : 1;
+    p.vpl = vpr > 128 ? 4 : vpr > 64 ? 2 : 1;
     int lpr = 8;
     while (int64_t(lpr) * p.vpl < vpr) lpr *= 2;
     p.lpr = lpr;
@@ -208,7 +220,8 @@ extern "C" MESA_EXPORT mesa_status mesa_layernorm_fwd_q(const void *x, int64_t M
     do { if (sr) MESA_LAUNCH_LF(T, LPR_, VPL_, true); else MESA_LAUNCH_LF(T, LPR_, VPL_, false); } while (0)
 #define MESA_LAUNCH_LF_T(T) \
     do { \
-        if (p.vpl == 2) MESA_LAUNCH_LF_S(T, 64, 2); \
+        if (p.vpl == 4) MESA_LAUNCH_LF_S(T, 64, 4); \
+        else if (p.vpl == 2) MESA_LAUNCH_LF_S(T, 64, 2); \
         else if (p.lpr == 8) MESA_LAUNCH_LF_S(T, 8, 1); \
         else if (p.lpr == 16) MESA_LAUNCH_LF_S(T, 16, 1); \
         else if (p.lpr == 32) MESA_LAUNCH_LF_S(T, 32, 1); \

@@ -78,7 +78,7 @@ def test_argument_errors_are_reported_before_any_launch(M):
     F = C.c_float
     assert L.mesa_layernorm_fwd_q(P, 100, 384, 6, P, P, F(1e-5), P, P, F(0.9), P, P, P, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_INVALID_ARG  # y aliases x
     assert L.mesa_layernorm_fwd_q(P, 100, 384, 6, P, P, F(1e-5), P, P, F(0.9), P2, P, P, P, 0, 0, 0, P, 8, M.F16, None) == M.ERR_WORKSPACE
-    assert L.mesa_layernorm_fwd_q(P, 100, 2048, 8, P, P, F(1e-5), P, P, F(0.9), P2, P, P, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_UNSUPPORTED  # rows too long
+    assert L.mesa_layernorm_fwd_q(P, 100, 4096, 8, P, P, F(1e-5), P, P, F(0.9), P2, P, P, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_UNSUPPORTED  # rows too long
     assert L.mesa_layernorm_fwd_q(P, 100, 384, 5, P, P, F(1e-5), P, P, F(0.9), P2, P, P, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_INVALID_ARG  # D % G
     assert L.mesa_layernorm_fwd_q(P, 100, 384, 6, P, P, F(-1.0), P, P, F(0.9), P2, P, P, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_INVALID_ARG  # eps
     assert L.mesa_dequantize(P, lay, P, None, P, M.F16, None) == M.ERR_INVALID_ARG

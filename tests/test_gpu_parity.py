@@ -564,7 +564,8 @@ def test_softmax_layer_forward_in_one_pass(M, B, H, rows, cols, dtype):
 
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=DTYPE_IDS)
-@pytest.mark.parametrize("Mr,D,G", [(1000, 384, 6), (77, 768, 12), (50, 1024, 4), (33, 64, 2), (19, 8, 1), (300, 96, 3), (5, 520, 1)])
+@pytest.mark.parametrize("Mr,D,G", [(1000, 384, 6), (77, 768, 12), (50, 1024, 4), (33, 64, 2), (19, 8, 1), (300, 96, 3), (5, 520, 1),
+                                    (41, 1032, 3), (130, 1536, 12), (9, 2048, 16)])
 def test_layernorm_layer_forward_in_one_pass(M, Mr, D, G, dtype):
     """y, mean and rstd within tolerance of the oracle's binary64 LayerNorm; codes of x and the moved estimates bit
     for bit (two steps, both rounding modes); the statistics feed the backward call as they are."""

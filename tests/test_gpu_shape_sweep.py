@@ -120,7 +120,7 @@ def test_softmax_layer_forward_and_backward_over_row_lengths(M, dtype):
 @pytest.mark.parametrize("dtype", [torch.float16, torch.float32, torch.bfloat16], ids=["f16", "f32", "bf16"])
 def test_layernorm_and_gelu_layer_forwards_over_extents(M, dtype):
     rnd = random.Random("ln" + str(dtype))
-    for D in (8, 16, 24, 64, 96, 128, 192, 384, 512, 520, 768, 1000, 1024):
+    for D in (8, 16, 24, 64, 96, 128, 192, 384, 512, 520, 768, 1000, 1024, 1032, 1536, 2048):
         Mr = rnd.choice((1, 3, 31, 100, 257))
         G = rnd.choice([gg for gg in (1, 2, 3, 4, 6, 8, 12) if D % gg == 0 and (D // gg) % 8 == 0])
         g = torch.Generator(device="cuda").manual_seed(D)
