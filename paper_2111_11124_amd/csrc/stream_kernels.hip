@@ -519,17 +519,19 @@ __global__ __launch_bounds__(kThreads) void k_quantize(const void *__restrict__ 
 // Quantize and take the extrema in one pass over x: the loop of k_quantize with the bookkeeping of
 // k_minmax_partial on the same registers.  Dynamic LDS: the (scale, beta) table, then the two
 // ordered-int extrema tables.  Partials as k_minmax_partial writes them.
-// gelu(x) = x * Phi(x), Phi(-|x|) = erfc(|x|/sqrt 2)/2 by Abramowitz & Stegun 7.1.26 (|error| <= 7.5e-8 on Phi)
+// gelu(x) = x * Phi(x), Phi(-|x|) = erfc(|x|/sqrt 2)/2 by Abramowitz & Stegun 7.1.26 (|error| <= 7.5e-8 on Phi;
+// the coefficients below are the published ones halved).  With h = Phi(-|x|):  x >= 0: x - |x| h,  x < 0: -|x| h,
+// i.e. max(x, 0) - |x| h in both cases.
 __device__ __forceinline__ float gelu_value(float x)
 {
     const float ax = fabsf(x);
     const float t = __builtin_amdgcn_rcpf(fmaf(ax, 0.3275911f * 0.70710678118654752f, 1.0f));
-    float poly = fmaf(t, 1.061405429f, -1.453152027f);
-    poly = fmaf(poly, t, 1.421413741f);
-    poly = fmaf(poly, t, -0.284496736f);
-    poly = fmaf(poly, t, 0.254829592f);
-    const float h = 0.5f * (poly * t) * __builtin_amdgcn_exp2f(x * x * -0.72134752044448170f);   // Phi(-|x|)
-    return x * (x >= 0.0f ? 1.0f - h : h);
+    float poly = fmaf(t, 0.5f * 1.061405429f, 0.5f * -1.453152027f);
+    poly = fmaf(poly, t, 0.5f * 1.421413741f);
+    poly = fmaf(poly, t, 0.5f * -0.284496736f);
+    poly = fmaf(poly, t, 0.5f * 0.254829592f);
+    const float h = (poly * t) * __builtin_amdgcn_exp2f(x * x * -0.72134752044448170f);   // Phi(-|x|)
+    return fmaf(-ax, h, vmax(x, 0.0f));
 }
 
 // GELU_FWD: the kernel is a GELU layer's whole forward -- y = gelu(x) leaves in the same pass that takes the codes of x
