@@ -663,3 +663,21 @@ def test_softmax_layer_forward_with_masked_logits(M, rows, cols, dtype):
     rq, ra2, rb2 = R.quantize_update_fused(yh, (B, H, rows * cols), ra, rb, 0.9, R.ROUND_STOCHASTIC, 1, 2)
     assert np.array_equal(npy(q), rq.reshape(-1))
     assert np.array_equal(canon(npy(a)), canon(ra2)) and np.array_equal(canon(npy(b)), canon(rb2))
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=DTYPE_IDS)
+@pytest.mark.parametrize("scale", [20.0, 3000.0])
+def test_softmax_layer_forward_with_large_logits(M, scale, dtype):
+    """Logits far from zero (nearly one-hot rows): the maximum is subtracted before the exponential, so the result
+    keeps its accuracy, in the short-row and in the long-row kernel."""
+    for cols in (49, 197, 300):
+        B, H, rows = 2, 3, 33
+        gen = torch.Generator(device="cuda").manual_seed(int(scale) + cols)
+        s = (torch.randn((B, H, rows, cols), generator=gen, device="cuda") * scale).to(dtype).contiguous()
+        y = torch.empty_like(s)
+        q = torch.empty(s.numel(), dtype=torch.int8, device="cuda")
+        a = torch.full((H,), 0.9, device="cuda")
+        b = torch.zeros(H, device="cuda")
+        ws = torch.empty(max(M.workspace_bytes(M.OP_SOFTMAX_FWD_Q, B * H * rows, H, cols, M.F16), 16), dtype=torch.uint8, device="cuda")
+        M.mesa_softmax_fwd_q(s, B, H, rows, cols, a, b, 0.9, y, q, ws, M.ROUND_NEAREST_EVEN, 0, 0)
+        assert relerr(npy(y), R.softmax_fwd(npy(s), B * H * rows, cols)) <= TOL[dtype], (cols, scale)
