@@ -46,7 +46,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_layernorm_fwd(const void *__res
 
     // gamma and bias stay in registers for rows of up to 1024 elements; for longer rows they are read again for
     // every row (a few KB that stay in the cache), which costs less than the registers would
-    constexpr bool kKeep = VPL <= 2;
+    constexpr bool kKeep = VPL <= 2 || (VPL == 3 && Store<T>::kBytes == 2);
     constexpr int kHeld = kKeep ? VPL : 1;
     uint32_t col[VPL], grp[VPL];
     bool act[VPL];
@@ -169,11 +169,16 @@ static LfPlan lf_plan(int64_t M, int64_t D)
     const int64_t vpr = D / kVec;
     p.ok = D % kVec == 0 && vpr >= 1 && vpr <= 256;
     if (!p.ok) return p;
-    p.vpl = vpr > 128 ? 4 : vpr > 64 ? 2 : 1;
-    int lpr = 8;
-    while (int64_t(lpr) * p.vpl < vpr) lpr *= 2;
-    p.lpr = lpr;
-    const int64_t block_rows = int64_t(kThreads / 64) * kLfRows * (64 / lpr);
+    // lanes per row (a power of two) x vectors per lane with the fewest idle slots: three vectors per lane fit the
+    // widths of the paper's models (96, 192, 384, 768 = 3 * 2^k vectors of 8) exactly, where a power of two wastes a quarter
+    int best = 1 << 30;
+    for (int vpl = 1; vpl <= 4; ++vpl) {
+        int lpr = 8;                                           // at least 128 contiguous bytes of a row per load instruction
+        while (int64_t(lpr) * vpl < vpr) lpr *= 2;
+        if (lpr > 64 || (vpl == 4 && lpr != 64)) continue;     // four vectors per lane: only for the longest rows
+        if (lpr * vpl < best) { best = lpr * vpl; p.lpr = lpr; p.vpl = vpl; }
+    }
+    const int64_t block_rows = int64_t(kThreads / 64) * kLfRows * (64 / p.lpr);
     const int64_t wgs = ceil_div(M, block_rows);
     const int64_t resident = 256 * 3;
     p.grid = int(wgs < resident ? wgs : resident);
@@ -221,7 +226,11 @@ extern "C" MESA_EXPORT mesa_status mesa_layernorm_fwd_q(const void *x, int64_t M
 #define MESA_LAUNCH_LF_T(T) \
     do { \
         if (p.vpl == 4) MESA_LAUNCH_LF_S(T, 64, 4); \
-        else if (p.vpl == 2) MESA_LAUNCH_LF_S(T, 64, 2); \
+        else if (p.vpl == 3 && p.lpr == 8) MESA_LAUNCH_LF_S(T, 8, 3); \
+        else if (p.vpl == 3 && p.lpr == 16) MESA_LAUNCH_LF_S(T, 16, 3); \
+        else if (p.vpl == 3 && p.lpr == 32) MESA_LAUNCH_LF_S(T, 32, 3); \
+        else if (p.vpl == 3) MESA_LAUNCH_LF_S(T, 64, 3); \
+        else if (p.vpl == 2) MESA_LAUNCH_LF_S(T, 64, 2);   /* two vectors per lane never win below 64 lanes */ \
         else if (p.lpr == 8) MESA_LAUNCH_LF_S(T, 8, 1); \
         else if (p.lpr == 16) MESA_LAUNCH_LF_S(T, 16, 1); \
         else if (p.lpr == 32) MESA_LAUNCH_LF_S(T, 32, 1); \
