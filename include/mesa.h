@@ -265,7 +265,7 @@ mesa_status mesa_linear_dw_q(const int8_t *xq, int64_t M, int64_t K, int64_t G,
  * Eq. (2) with G_l = the gradient of a matrix product (the "MatMul" rows of the paper's overhead table;
  * Sec. 3.2: the operands are saved as codes with one (alpha, beta) pair per head).  All tensors are
  * (B, H, N, .) contiguous, upstream gradients and results of dt (binary32 tensors run one plain, slow
- * kernel), accumulation in binary32; any N >= 8 and Dh >= 8 (nothing needs to be aligned).
+ * kernel, as do extents below 8), accumulation in binary32; any N and Dh (nothing needs to be aligned).
  *
  * O = A V with A the attention map (B,H,N,N) and V (B,H,N,Dh):
  *   dA[i,j] = sum_d dO[i,d] * V_hat[j,d],    dV[j,d] = sum_i A_hat[i,j] * dO[i,d]

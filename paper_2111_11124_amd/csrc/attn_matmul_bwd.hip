@@ -369,10 +369,11 @@ static void launch_bmm(BmmArgs a, int64_t batches, hipStream_t s)
     }
 }
 
-// binary32 tensors: 32x32x2 binary32 MFMA with operands straight from global memory (a lane needs one value per
-// operand and step: lane l holds row / column l%32 at contraction slot l/32).  Kept simple: it serves the binary32
-// configuration, which is far too small to be a throughput case.  BmmArgs' 16-bit pointers carry binary32 here.
-template <bool P_CODED>
+// The plain kernel: 32x32x2 binary32 MFMA with operands straight from global memory, one element at a time (a lane
+// needs one value per operand and step: lane l holds row / column l%32 at contraction slot l/32).  Kept simple: it
+// serves binary32 tensors (the binary32 configuration is far too small to be a throughput case) and, for the 16-bit
+// types, extents shorter than one load vector.  T: the tensors' element type (BmmArgs' pointers are reinterpreted).
+template <bool P_CODED, typename T>
 __global__ __launch_bounds__(kThreads) void k_bmm_q_f32(BmmArgs a)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -380,7 +381,7 @@ __global__ __launch_bounds__(kThreads) void k_bmm_q_f32(BmmArgs a)
     const int r = int(blockIdx.y) * kBmTile + (wave >> 1) * 32 + (lane & 31);
     const int c = int(blockIdx.x) * kBmTile + (wave & 1) * 32 + (lane & 31);
     const uint32_t h = (b + uint32_t(a.head0)) % uint32_t(a.heads);
-    const float *xb = reinterpret_cast<const float *>(a.x) + (int64_t(b) + a.batch0) * a.x_batch;
+    const int64_t xb0 = (int64_t(b) + a.batch0) * a.x_batch;
     const int8_t *yb = a.y + (int64_t(b) + a.batch0) * a.y_batch;
     const bool r_ok = r < a.R, c_ok = c < a.Cn;
     bm_v16f acc, acc1;
@@ -391,8 +392,8 @@ __global__ __launch_bounds__(kThreads) void k_bmm_q_f32(BmmArgs a)
         const bool t_ok = t < a.Tn;
         float pa = 0.0f, qb = 0.0f;
         const int64_t po = int64_t(r) * a.p_rs + int64_t(t) * a.p_ts, qo = int64_t(t) * a.q_ts + int64_t(c) * a.q_cs;
-        if (t_ok && r_ok) pa = P_CODED ? float(int(yb[po])) : xb[po];
-        if (t_ok && c_ok) qb = P_CODED ? xb[qo] : float(int(yb[qo]));
+        if (t_ok && r_ok) pa = P_CODED ? float(int(yb[po])) : Store<T>::load1(a.x, xb0 + po);
+        if (t_ok && c_ok) qb = P_CODED ? Store<T>::load1(a.x, xb0 + qo) : float(int(yb[qo]));
         const float one = t_ok ? 1.0f : 0.0f;
         acc = __builtin_amdgcn_mfma_f32_32x32x2f32(pa, qb, acc, 0, 0, 0);
         acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(P_CODED ? one : pa, P_CODED ? qb : one, acc1, 0, 0, 0);   // sums of the plain operand
@@ -400,17 +401,17 @@ __global__ __launch_bounds__(kThreads) void k_bmm_q_f32(BmmArgs a)
     const float s = a.alpha[h] / 255.0f;
     const float off = fmaf(128.0f, s, a.beta[h]);
     const int row_l = int(blockIdx.y) * kBmTile + (wave >> 1) * 32 + (lane >> 5) * 4;
-    float *cb = reinterpret_cast<float *>(a.c) + (int64_t(b) + a.batch0) * a.c_batch;
+    const int64_t cb0 = (int64_t(b) + a.batch0) * a.c_batch;
     if (c_ok) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int rr = row_l + (v >> 2) * 8 + (v & 3);
-            if (rr < a.R) cb[int64_t(rr) * a.Cn + c] = a.scale * fmaf(s, acc[v], off * acc1[v]);
+            if (rr < a.R) Store<T>::store1(a.c, cb0 + int64_t(rr) * a.Cn + c, a.scale * fmaf(s, acc[v], off * acc1[v]));
         }
     }
 }
 
-template <bool P_CODED> static void launch_bmm_f32(BmmArgs a, int64_t batches, hipStream_t s)
+template <bool P_CODED> static void launch_bmm_f32(BmmArgs a, int64_t batches, mesa_dtype dt, hipStream_t s)
 {
     a.tiles_r = int(ceil_div(a.R, kBmTile));
     a.tiles_c = int(ceil_div(a.Cn, kBmTile));
@@ -418,7 +419,10 @@ template <bool P_CODED> static void launch_bmm_f32(BmmArgs a, int64_t batches, h
         a.batch0 = b0;
         a.head0 = int(b0 % a.heads);
         const int64_t nb = batches - b0 < 65535 ? batches - b0 : 65535;
-        hipLaunchKernelGGL((k_bmm_q_f32<P_CODED>), dim3(unsigned(a.tiles_c), unsigned(a.tiles_r), unsigned(nb)), dim3(kThreads), 0, s, a);
+#define MESA_LAUNCH_PLAIN(T) \
+    hipLaunchKernelGGL((k_bmm_q_f32<P_CODED, T>), dim3(unsigned(a.tiles_c), unsigned(a.tiles_r), unsigned(nb)), dim3(kThreads), 0, s, a)
+        MESA_FOR_DTYPE(dt, MESA_LAUNCH_PLAIN);
+#undef MESA_LAUNCH_PLAIN
     }
 }
 
@@ -1049,7 +1053,6 @@ static mesa_status check_attn(int64_t B, int64_t H, int64_t N, int64_t Dh, mesa_
 {
     if (!valid_dtype(dt) || B < 0 || H < 0 || N < 0 || Dh < 0) return MESA_ERR_INVALID_ARG;
     if (N >= (int64_t(1) << 20) || Dh >= (int64_t(1) << 20)) return MESA_ERR_UNSUPPORTED;
-    if ((N > 0 && N < 8) || (Dh > 0 && Dh < 8)) return MESA_ERR_UNSUPPORTED;   // an extent shorter than one load vector
     // 32-bit element offsets inside one (sample, head); the row / column tile counts fit a grid dimension
     if ((long double)N * (long double)N >= 2147483648.0L || (long double)N * (long double)Dh >= 2147483648.0L)
         return MESA_ERR_UNSUPPORTED;
@@ -1084,14 +1087,14 @@ extern "C" MESA_EXPORT mesa_status mesa_attn_av_bwd_q(const int8_t *aq, const in
     a.R = int(N); a.Cn = int(N); a.Tn = int(Dh);
     a.p_rs = Dh; a.p_ts = 1; a.q_ts = 1; a.q_cs = Dh;
     a.alpha = alpha_v; a.beta = beta_v;
-    if (dt == MESA_F32) {
-        launch_bmm_f32<false>(a, batches, s);
+    if (dt == MESA_F32 || N < 8 || Dh < 8) {   // binary32, or an extent shorter than one load vector: the plain kernel
+        launch_bmm_f32<false>(a, batches, dt, s);
         a.y = aq; a.c = static_cast<_Float16 *>(dV);
         a.y_batch = N * N; a.c_batch = N * Dh;
         a.R = int(N); a.Cn = int(Dh); a.Tn = int(N);
         a.p_rs = 1; a.p_ts = N; a.q_ts = Dh; a.q_cs = 1;
         a.alpha = alpha_a; a.beta = beta_a;
-        launch_bmm_f32<true>(a, batches, s);
+        launch_bmm_f32<true>(a, batches, dt, s);
         return launch_status();
     }
     // the 32 x N output block has to fit the 64 KiB of LDS a kernel gets by default; else the general kernel
@@ -1148,12 +1151,12 @@ extern "C" MESA_EXPORT mesa_status mesa_attn_qk_bwd_q(const int8_t *qq, const in
     a.y = kq; a.c = static_cast<_Float16 *>(dQ);
     a.p_rs = N; a.p_ts = 1; a.q_ts = Dh; a.q_cs = 1;
     a.alpha = alpha_k; a.beta = beta_k;
-    if (dt == MESA_F32) {
-        launch_bmm_f32<false>(a, batches, s);
+    if (dt == MESA_F32 || N < 8 || Dh < 8) {
+        launch_bmm_f32<false>(a, batches, dt, s);
         a.y = qq; a.c = static_cast<_Float16 *>(dK);
         a.p_rs = 1; a.p_ts = N; a.q_ts = Dh; a.q_cs = 1;
         a.alpha = alpha_q; a.beta = beta_q;
-        launch_bmm_f32<false>(a, batches, s);
+        launch_bmm_f32<false>(a, batches, dt, s);
         return launch_status();
     }
 #define MESA_QK_DQ(ET) \

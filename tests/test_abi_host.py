@@ -92,7 +92,7 @@ def test_argument_errors_are_reported_before_any_launch(M):
     assert L.mesa_linear_dw_q(P, 100, 40, 1, P, P, P, 64, M.F16, P, None, P, 1 << 30, None) == M.ERR_UNSUPPORTED   # K % 16
     assert L.mesa_linear_dw_q(P, 100, 48, 5, P, P, P, 64, M.F16, P, None, P, 1 << 30, None) == M.ERR_INVALID_ARG   # K % G
     assert L.mesa_linear_dw_q(P, 100, 48, 3, P, P, P, 64, M.F16, P, None, P, 64, None) == M.ERR_WORKSPACE
-    assert L.mesa_attn_av_bwd_q(P, P, 2, 3, 4, 8, P, P, P, P, P, P, P, M.F16, None) == M.ERR_UNSUPPORTED           # an extent below 8
+    assert L.mesa_attn_av_bwd_q(P, P, 2, 3, 1 << 20, 8, P, P, P, P, P, P, P, M.F16, None) == M.ERR_UNSUPPORTED     # sequence too long
     assert L.mesa_attn_av_bwd_q(P, P, 2, 3, 19, 8, P, P, P, P, None, P, P, M.BF16, None) == M.ERR_INVALID_ARG      # bfloat16 is accepted
     assert L.mesa_attn_qk_bwd_q(P, P, 2, 3, 19, 8, P, P, P, P, None, 0.5, P, P, M.F32, None) == M.ERR_INVALID_ARG   # binary32 is accepted
     assert L.mesa_linear_dw_q(P, 100, 48, 3, P, P, P, 64, M.BF16, P, None, P, 64, None) == M.ERR_WORKSPACE        # bfloat16 is a valid type

@@ -393,6 +393,13 @@ def test_attention_matmul_backward_binary32(M, B, H, N, Dh):
     _attention_case(M, B, H, N, Dh, torch.float32)
 
 
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16], ids=["f16", "bf16"])
+@pytest.mark.parametrize("B,H,N,Dh", [(2, 3, 3, 5), (1, 2, 7, 64), (2, 1, 40, 4), (1, 1, 1, 1)])
+def test_attention_matmul_backward_short_extents(M, B, H, N, Dh, dtype):
+    """Sequences or heads shorter than one load vector (the plain kernel, in the 16-bit types too)."""
+    _attention_case(M, B, H, N, Dh, dtype)
+
+
 def _attention_case(M, B, H, N, Dh, dtype):
     gen = torch.Generator(device="cuda").manual_seed(B * 1000 + N)
     sig = torch.linspace(0.5, 2.0, H, device="cuda").view(1, H, 1, 1)
