@@ -253,7 +253,8 @@ mesa_status mesa_layernorm_bwd_q(const int8_t *xq, int64_t M, int64_t D, int64_t
  * (binary16 products for MESA_F16, bfloat16 products for MESA_BF16, binary32 accumulation; fixed summation order).
  * xq: (M, K) int8, K in G channel groups.  dy: (M, N_out) of dt.  dW: (N_out, K) binary32, row-major,
  * overwritten.  db: [N_out] binary32 or NULL.  ws: MESA_OP_LINEAR_DW_Q bytes.
- * Limits: K % 16 == 0, N_out % 8 == 0, K % G == 0, else MESA_ERR_UNSUPPORTED.
+ * K % G == 0.  Widths with K % 16 != 0 or N_out % 8 != 0 (and binary32 tensors) run a plain, slow kernel.
+ * Limits: K * N_out < 2^31, else MESA_ERR_UNSUPPORTED.
  */
 mesa_status mesa_linear_dw_q(const int8_t *xq, int64_t M, int64_t K, int64_t G,
                              const float *alpha, const float *beta,

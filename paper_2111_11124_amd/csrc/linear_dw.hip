@@ -390,12 +390,14 @@ __global__ __launch_bounds__(WGN * WGK * 64, 1) void k_dw_f16(const int8_t *__re
     }
 }
 
-// binary32 path: 32x32x2 MFMA, operands straight from global memory (a lane needs a single value
-// per operand, so no transposition is involved).  Kept simple: it serves the fp32 configuration,
-// which is far too small to be a throughput case.
+// The plain path: 32x32x2 binary32 MFMA, operands straight from global memory, one element at a time (a lane
+// needs a single value per operand, so no transposition and no alignment is involved).  Kept simple: it serves
+// binary32 tensors (the binary32 configuration is far too small to be a throughput case) and, for the 16-bit
+// types, widths that the vector loads of the kernel above cannot take (K not a multiple of 16, N not of 8).
 constexpr int kDw32BN = 128, kDw32BK = 128;
 
-__global__ __launch_bounds__(kThreads) void k_dw_f32(const int8_t *__restrict__ xq, const float *__restrict__ dy, int64_t M,
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_dw_f32(const int8_t *__restrict__ xq, const void *__restrict__ dy, int64_t M,
                                                      int K, int N, int tiles_n, int tiles_k, int splits, int64_t rows_per_split,
                                                      float *__restrict__ P, float *__restrict__ S0)
 {
@@ -421,7 +423,7 @@ __global__ __launch_bounds__(kThreads) void k_dw_f32(const int8_t *__restrict__ 
     for (int64_t m2 = m_begin; m2 < m_end; m2 += 2) {
         const int64_t m = m2 + (lane >> 5);
         const bool mv = m < m_end;
-        const float a = (mv && n < N) ? dy[m * N + n] : 0.0f;
+        const float a = (mv && n < N) ? Store<T>::load1(dy, m * N + n) : 0.0f;
         s0 += a;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -477,8 +479,29 @@ __global__ __launch_bounds__(kThreads) void k_dw_reduce(const float *__restrict_
     if (db && kk == 0) db[n] = s0;
 }
 
+// the same for any K: one output per thread
+__global__ __launch_bounds__(kThreads) void k_dw_reduce_any(const float *__restrict__ P, const float *__restrict__ S0, int splits,
+                                                            int N, int K, FastDiv div_k, FastDiv div_per,
+                                                            const float *__restrict__ alpha, const float *__restrict__ beta,
+                                                            float centre, float *__restrict__ dW, float *__restrict__ db)
+{
+    const int64_t idx = int64_t(blockIdx.x) * kThreads + threadIdx.x;
+    if (idx >= int64_t(N) * K) return;
+    const uint32_t n = fastdiv(uint32_t(idx), div_k);
+    const uint32_t kk = uint32_t(idx) - n * div_k.d;
+    float s1 = 0.0f, s0 = 0.0f;
+    for (int sp = 0; sp < splits; ++sp) {
+        s1 += P[(int64_t(sp) * N + n) * K + kk];
+        s0 += S0[int64_t(sp) * N + n];
+    }
+    const uint32_t g = fastdiv(kk, div_per);
+    const float sg = alpha[g] / 255.0f;
+    dW[idx] = fmaf(sg, s1, fmaf(centre, sg, beta[g]) * s0);
+    if (db && kk == 0) db[n] = s0;
+}
+
 struct DwPlan {
-    int variant;   // 16-bit tiles (n x k): 0: 256 x 256, 1: 256 x 128, 3: 128 x 128; 2: binary32
+    int variant;   // 16-bit tiles (n x k): 0: 256 x 256, 1: 256 x 128, 3: 128 x 128; 2: the plain path
     int bn, bk, tiles_n, tiles_k, splits, grid;
     int64_t rows_per_split;
 };
@@ -486,7 +509,7 @@ struct DwPlan {
 static DwPlan dw_plan(int64_t M, int64_t K, int64_t N, mesa_dtype dt)
 {
     DwPlan p;
-    if (dt != MESA_F32) {
+    if (dt != MESA_F32 && K % 16 == 0 && N % 8 == 0) {
         // 256-wide k tiles unless they would waste much of the last one.  (A 128 x 384 tile for K = 384 was
         // measured too: no faster per MFMA, and its 21 slices instead of 14 cost more partial-sum traffic.)
         if (K % 256 == 0 || K > 1024) { p.variant = 0; p.bn = 256; p.bk = 256; }
@@ -536,10 +559,8 @@ extern "C" MESA_EXPORT mesa_status mesa_linear_dw_q(const int8_t *xq, int64_t M,
     if (!alpha || !beta || !dW || !aligned4(alpha) || !aligned4(beta) || !aligned16(dW) || (db && !aligned4(db)))
         return MESA_ERR_INVALID_ARG;
     if (M > 0 && (!xq || !dy || !aligned16(xq) || !aligned16(dy))) return MESA_ERR_INVALID_ARG;
-    if (K % 16 != 0 || N_out % 8 != 0 || K >= (int64_t(1) << 30) || N_out >= (int64_t(1) << 30) ||
-        (long double)K * (long double)N_out >= 17179869184.0L /* 2^34 */)
+    if (K >= (int64_t(1) << 30) || N_out >= (int64_t(1) << 30) || (long double)K * (long double)N_out >= 2147483648.0L)
         return MESA_ERR_UNSUPPORTED;
-    if ((long double)K * (long double)N_out / 4 >= 2147483648.0L) return MESA_ERR_UNSUPPORTED;
     if (!ws || !aligned16(ws) || ws_bytes < linear_dw_ws_bytes(M, K, N_out, dt)) return MESA_ERR_WORKSPACE;
     DwPlan p = dw_plan(M, K, N_out, dt);
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -554,18 +575,28 @@ extern "C" MESA_EXPORT mesa_status mesa_linear_dw_q(const int8_t *xq, int64_t M,
                            static_cast<const E *>(dy), M, Ki, Ni, p.tiles_n, p.tiles_k, p.splits, p.rows_per_split, P, S0); \
         centre = DwElem<E>::kCentre; \
     } while (0)
-    if (dt == MESA_F16) {
+    if (p.variant == 2) {   // the plain path contracts with the signed code
+#define MESA_LAUNCH_DW_PLAIN(T) \
+    hipLaunchKernelGGL((k_dw_f32<T>), dim3(p.grid), dim3(kThreads), 0, s, xq, dy, M, Ki, Ni, p.tiles_n, p.tiles_k, p.splits, \
+                       p.rows_per_split, P, S0)
+        MESA_FOR_DTYPE(dt, MESA_LAUNCH_DW_PLAIN);
+#undef MESA_LAUNCH_DW_PLAIN
+    } else if (dt == MESA_F16) {
         if (p.variant == 0) MESA_LAUNCH_DW(_Float16, 256, 256); else if (p.variant == 1) MESA_LAUNCH_DW(_Float16, 256, 128); else MESA_LAUNCH_DW(_Float16, 128, 128);
-    } else if (dt == MESA_BF16) {
-        if (p.variant == 0) MESA_LAUNCH_DW(__bf16, 256, 256); else if (p.variant == 1) MESA_LAUNCH_DW(__bf16, 256, 128); else MESA_LAUNCH_DW(__bf16, 128, 128);
     } else {
-        hipLaunchKernelGGL(k_dw_f32, dim3(p.grid), dim3(kThreads), 0, s, xq, static_cast<const float *>(dy), M, Ki, Ni,
-                           p.tiles_n, p.tiles_k, p.splits, p.rows_per_split, P, S0);
+        if (p.variant == 0) MESA_LAUNCH_DW(__bf16, 256, 256); else if (p.variant == 1) MESA_LAUNCH_DW(__bf16, 256, 128); else MESA_LAUNCH_DW(__bf16, 128, 128);
     }
-    const int64_t nvec = N_out * (K / 4);
-    FastDiv dk4 = make_fastdiv(uint32_t(K / 4)), dper = make_fastdiv(uint32_t(K / G));
-    hipLaunchKernelGGL(k_dw_reduce, dim3(unsigned(ceil_div(nvec, kThreads))), dim3(kThreads), 0, s, P, S0, p.splits, Ni, Ki, dk4,
-                       dper, alpha, beta, centre, dW, db);
+    FastDiv dper = make_fastdiv(uint32_t(K / G));
+    if (K % 4 == 0) {
+        const int64_t nvec = N_out * (K / 4);
+        FastDiv dk4 = make_fastdiv(uint32_t(K / 4));
+        hipLaunchKernelGGL(k_dw_reduce, dim3(unsigned(ceil_div(nvec, kThreads))), dim3(kThreads), 0, s, P, S0, p.splits, Ni, Ki, dk4,
+                           dper, alpha, beta, centre, dW, db);
+    } else {
+        FastDiv dk = make_fastdiv(uint32_t(K));
+        hipLaunchKernelGGL(k_dw_reduce_any, dim3(unsigned(ceil_div(N_out * K, kThreads))), dim3(kThreads), 0, s, P, S0, p.splits, Ni,
+                           Ki, dk, dper, alpha, beta, centre, dW, db);
+    }
 #undef MESA_LAUNCH_DW
     return launch_status();
 }

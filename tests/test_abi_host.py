@@ -89,7 +89,7 @@ def test_argument_errors_are_reported_before_any_launch(M):
     assert L.mesa_layernorm_bwd_q(P, 10, 100, 5, P, P, P, P, P, P, P, P, P, M.F16, P, 1 << 20, None) == M.ERR_UNSUPPORTED
     assert L.mesa_layernorm_bwd_q(P, 10, 96, 5, P, P, P, P, P, P, P, P, P, M.F16, P, 1 << 20, None) == M.ERR_INVALID_ARG
     assert L.mesa_layernorm_bwd_q(P, 10, 96, 3, P, P, P, P, P, P, P, P, P, M.F16, P, 16, None) == M.ERR_WORKSPACE
-    assert L.mesa_linear_dw_q(P, 100, 40, 1, P, P, P, 64, M.F16, P, None, P, 1 << 30, None) == M.ERR_UNSUPPORTED   # K % 16
+    assert L.mesa_linear_dw_q(P, 100, 1 << 20, 1, P, P, P, 1 << 12, M.F16, P, None, P, 1 << 30, None) == M.ERR_UNSUPPORTED   # K * N_out >= 2^31
     assert L.mesa_linear_dw_q(P, 100, 48, 5, P, P, P, 64, M.F16, P, None, P, 1 << 30, None) == M.ERR_INVALID_ARG   # K % G
     assert L.mesa_linear_dw_q(P, 100, 48, 3, P, P, P, 64, M.F16, P, None, P, 64, None) == M.ERR_WORKSPACE
     assert L.mesa_attn_av_bwd_q(P, P, 2, 3, 1 << 20, 8, P, P, P, P, P, P, P, M.F16, None) == M.ERR_UNSUPPORTED     # sequence too long

@@ -223,7 +223,8 @@ def test_stream_kernels_and_layernorm_backward_keep_inside_their_outputs(M, dtyp
 def test_linear_dw_keeps_inside_its_outputs(M, dtype):
     """dW and db framed by sentinels, over every tile variant (256 x 256, 256 x 128, 128 x 128, the binary32 path)
     with partial tiles in both extents and ragged slices of m."""
-    for Mr, K, N in ((31, 16, 8), (97, 128, 264), (3205, 256, 520), (909, 784, 136), (9000, 272, 1000), (5000, 96, 384), (777, 1280, 72)):
+    for Mr, K, N in ((31, 16, 8), (97, 128, 264), (3205, 256, 520), (909, 784, 136), (9000, 272, 1000), (5000, 96, 384), (777, 1280, 72),
+                     (100, 40, 64), (333, 17, 5), (1000, 100, 12), (65, 3, 1), (700, 48, 20)):
         H = 1 if K % 3 else 3
         lay = (Mr, H, K // H)
         g = torch.Generator(device="cuda").manual_seed(Mr + K)
