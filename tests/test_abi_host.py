@@ -163,3 +163,22 @@ def test_host_integer_helpers_are_exact():
                        check=True)
         out = subprocess.run([exe], capture_output=True, text=True)
         assert out.returncode == 0 and out.stdout.strip() == "OK", out.stdout
+
+
+def test_the_binding_has_no_fallback(monkeypatch, tmp_path):
+    """Without the shared library every call fails loudly; host tensors are refused before anything is called."""
+    import torch
+    from paper_2111_11124_amd import _ffi
+    monkeypatch.setattr(_ffi, "_lib", None)
+    monkeypatch.setattr(_ffi, "_LIB_PATH", tmp_path / "libmesa.so")
+    x = torch.zeros(64)
+    with pytest.raises(RuntimeError, match="no fallback"):
+        _ffi.lib()
+    with pytest.raises(RuntimeError, match="no fallback"):
+        _ffi.workspace_bytes(_ffi.OP_UPDATE_RUNNING_PARAMS, 1, 1, 64)
+    monkeypatch.undo()
+    _ffi.lib()
+    q = torch.zeros(64, dtype=torch.int8)
+    a = torch.ones(1)
+    with pytest.raises(ValueError, match="device tensors"):
+        _ffi.mesa_quantize_headwise(x, (1, 1, 64), a, a, q)
