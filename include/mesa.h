@@ -23,8 +23,11 @@
  *               returns; there is no host synchronisation and no host read of device data.
  *   ws          caller-provided device scratch of at least mesa_workspace_bytes(...) bytes; its
  *               contents are undefined before and after a call.
- *   Errors      Arguments are checked on the host before anything is enqueued.  On any error
- *               nothing is written.  Zero elements is MESA_OK and a no-op.
+ *   Errors      Arguments are checked on the host before anything is enqueued.  On an argument,
+ *               shape or workspace error nothing is written.  MESA_ERR_LAUNCH is what the HIP runtime
+ *               reports after a launch (a call of several kernels stops at the first that fails, so a
+ *               later kernel never consumes scratch nobody wrote); it may also be an error that an
+ *               earlier HIP call of the calling thread left unread.  Zero elements is MESA_OK and a no-op.
  *   Threads     No global mutable state; calls on distinct streams may run concurrently provided
  *               they use distinct ws and outputs.
  *   Limits      groups <= 8192; for groups > 1, inner < 2^30.  Outside them: MESA_ERR_UNSUPPORTED.
@@ -98,7 +101,7 @@ mesa_status mesa_update_running_params_sym(const void *x, mesa_dtype dt, mesa_la
 
 /*
  * Fixed offset, Sec. 6 (evolution of alpha and beta in FFN layers): the offset of the second FFN
- * layer's input stays at GELU's minimum -0.17 and "can be fixed" there.  beta_g = beta_fixed for
+ * layer's input settles at the minimum of GELU, about -0.17, so it need not be estimated.  beta_g = beta_fixed for
  * every group; alpha_g is the running estimate of mx_g - beta_fixed (Eq. (6) with the minimum
  * replaced by beta_fixed; first_call != 0: alpha_g = mx_g - beta_fixed).  Values below beta_fixed
  * saturate at the lowest code.  beta: [groups] (out).  beta_fixed must be finite.
@@ -135,7 +138,8 @@ mesa_status mesa_quantize_headwise(const void *x, mesa_dtype dt, mesa_layout L,
  * the second iteration on; its parameters then lag the two-call order by exactly one step.
  * Arithmetic, rounding modes, random source and layouts: as in the two calls it combines, bit for bit.
  * x: [numel] of dt (in).  alpha, beta: [groups] (in/out).  q: [numel] int8 (out).
- * ws: MESA_OP_UPDATE_RUNNING_PARAMS bytes.
+ * ws: MESA_OP_UPDATE_RUNNING_PARAMS bytes.  Limit: groups <= 4096 (this call and mesa_gelu_fwd_q), else
+ * MESA_ERR_UNSUPPORTED.
  */
 mesa_status mesa_quantize_update_fused(const void *x, mesa_dtype dt, mesa_layout L,
                                        float *alpha, float *beta, float lambda, int8_t *q,

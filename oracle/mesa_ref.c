@@ -244,7 +244,7 @@ int mesa_ref_update_running_params_sym(const void *x, int dt, int64_t outer, int
 
 /*
  * Fixed offset (Sec. 6, evolution of alpha and beta in FFN layers: the offset of the second FFN layer's
- * input stays at GELU's minimum, -0.17, so it "can be fixed" there): beta_g = beta_fixed for every
+ * input settles at the minimum of GELU, about -0.17, so it need not be estimated): beta_g = beta_fixed for every
  * group, and only the range is a running estimate, of max - beta_fixed:
  *   first call : alpha = max - beta_fixed
  *   otherwise  : alpha = lambda*alpha + (1-lambda)*(max - beta_fixed)

@@ -433,6 +433,7 @@ extern "C" MESA_EXPORT mesa_status mesa_layernorm_bwd_q(const int8_t *xq, int64_
 #undef MESA_LAUNCH_LN
 #undef MESA_LAUNCH_ROWS_T
 #undef MESA_LAUNCH_ROWS
+    if (launch_status() != MESA_OK) return MESA_ERR_LAUNCH;   // the consumer must not run on a workspace nobody wrote
     hipLaunchKernelGGL(k_layernorm_finalize, dim3(unsigned(ceil_div(D, 32))), dim3(kLnFinThreads), 0, s, part, p.grid,
                        uint32_t(D), dgamma, dbeta);
     return launch_status();

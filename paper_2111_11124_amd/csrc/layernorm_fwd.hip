@@ -240,6 +240,7 @@ extern "C" MESA_EXPORT mesa_status mesa_layernorm_fwd_q(const void *x, int64_t M
 #undef MESA_LAUNCH_LF_T
 #undef MESA_LAUNCH_LF_S
 #undef MESA_LAUNCH_LF
+    if (launch_status() != MESA_OK) return MESA_ERR_LAUNCH;   // the consumer must not run on a workspace nobody wrote
     launch_ema_finalize(part, p.grid, uint32_t(G), alpha, beta, lambda, 0, 0, 0.0f, s);
     return launch_status();
 }

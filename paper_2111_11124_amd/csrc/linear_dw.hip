@@ -559,7 +559,8 @@ extern "C" MESA_EXPORT mesa_status mesa_linear_dw_q(const int8_t *xq, int64_t M,
     if (!alpha || !beta || !dW || !aligned4(alpha) || !aligned4(beta) || !aligned16(dW) || (db && !aligned4(db)))
         return MESA_ERR_INVALID_ARG;
     if (M > 0 && (!xq || !dy || !aligned16(xq) || !aligned16(dy))) return MESA_ERR_INVALID_ARG;
-    if (K >= (int64_t(1) << 30) || N_out >= (int64_t(1) << 30) || (long double)K * (long double)N_out >= 2147483648.0L)
+    // a thread's byte offsets inside a stage of 32 rows are 32-bit (32*K and 64*N_out), the reduction indexes N_out*K/4 in 32 bits
+    if (K >= (int64_t(1) << 26) || N_out >= (int64_t(1) << 25) || (long double)K * (long double)N_out >= 2147483648.0L)
         return MESA_ERR_UNSUPPORTED;
     if (!ws || !aligned16(ws) || ws_bytes < linear_dw_ws_bytes(M, K, N_out, dt)) return MESA_ERR_WORKSPACE;
     DwPlan p = dw_plan(M, K, N_out, dt);
@@ -586,6 +587,7 @@ extern "C" MESA_EXPORT mesa_status mesa_linear_dw_q(const int8_t *xq, int64_t M,
     } else {
         if (p.variant == 0) MESA_LAUNCH_DW(__bf16, 256, 256); else if (p.variant == 1) MESA_LAUNCH_DW(__bf16, 256, 128); else MESA_LAUNCH_DW(__bf16, 128, 128);
     }
+    if (launch_status() != MESA_OK) return MESA_ERR_LAUNCH;   // the reduction must not run on partial sums nobody wrote
     FastDiv dper = make_fastdiv(uint32_t(K / G));
     if (K % 4 == 0) {
         const int64_t nvec = N_out * (K / 4);

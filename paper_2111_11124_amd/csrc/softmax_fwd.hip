@@ -562,6 +562,7 @@ extern "C" MESA_EXPORT mesa_status mesa_softmax_fwd_q(const void *s_in, int64_t 
 #undef MESA_LAUNCH_SR_C
 #undef MESA_LAUNCH_SR_M
 #undef MESA_LAUNCH_SR
+        if (launch_status() != MESA_OK) return MESA_ERR_LAUNCH;   // the consumer must not run on a workspace nobody wrote
         launch_ema_finalize(part, rp.grid, uint32_t(H), alpha, beta, lambda, 0, 0, 0.0f, s);
         return launch_status();
     }
@@ -576,6 +577,7 @@ extern "C" MESA_EXPORT mesa_status mesa_softmax_fwd_q(const void *s_in, int64_t 
     MESA_FOR_DTYPE(dt, MESA_LAUNCH_SF_T);
 #undef MESA_LAUNCH_SF_T
 #undef MESA_LAUNCH_SF
+    if (launch_status() != MESA_OK) return MESA_ERR_LAUNCH;
     launch_ema_finalize(part, p.grid, uint32_t(H), alpha, beta, lambda, 0, 0, 0.0f, s);
     return launch_status();
 }

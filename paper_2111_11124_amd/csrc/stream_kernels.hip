@@ -924,6 +924,7 @@ static mesa_status update_running_params(const void *x, mesa_dtype dt, mesa_layo
         MESA_FOR_DTYPE(dt, MESA_LAUNCH_MM);
 #undef MESA_LAUNCH_MM
     }
+    if (launch_status() != MESA_OK) return MESA_ERR_LAUNCH;   // the consumer must not run on partials nobody wrote
     hipLaunchKernelGGL(k_ema_finalize, dim3(gg.groups), dim3(kThreads), 0, s, part, grid, gg.groups, alpha, beta, lambda,
                        first_call, variant, beta_fixed);
     return launch_status();
@@ -990,6 +991,8 @@ static mesa_status quantize_update_fused(const void *x, mesa_dtype dt, mesa_layo
         return MESA_ERR_INVALID_ARG;
     if (gelu_fwd && (!y || !aligned16(y) || y == x)) return MESA_ERR_INVALID_ARG;   // not in place: the kernel's pointers do not alias
     if (!gelu_fwd) y = nullptr;
+    // parameter table and extrema of every group live in LDS, 16 bytes a group, within the 64 KiB a launch gets by default
+    if (size_t(L.groups) * (sizeof(float2) + 2 * sizeof(int)) > size_t(64) * 1024) return MESA_ERR_UNSUPPORTED;
     if (!ws || !aligned16(ws) || ws_bytes < update_ws_bytes(L.outer, L.groups, L.inner)) return MESA_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int grid = minmax_grid(L, kFuU, kFuGridCap);
@@ -1008,6 +1011,7 @@ static mesa_status quantize_update_fused(const void *x, mesa_dtype dt, mesa_layo
     MESA_FOR_DTYPE(dt, MESA_LAUNCH_QM_T);
 #undef MESA_LAUNCH_QM_T
 #undef MESA_LAUNCH_QM
+    if (launch_status() != MESA_OK) return MESA_ERR_LAUNCH;
     hipLaunchKernelGGL(k_ema_finalize, dim3(gg.groups), dim3(kThreads), 0, s, part, grid, gg.groups, alpha, beta, lambda, 0);
     return launch_status();
 }

@@ -688,3 +688,46 @@ def test_softmax_layer_forward_with_large_logits(M, scale, dtype):
         ws = torch.empty(max(M.workspace_bytes(M.OP_SOFTMAX_FWD_Q, B * H * rows, H, cols, M.F16), 16), dtype=torch.uint8, device="cuda")
         M.mesa_softmax_fwd_q(s, B, H, rows, cols, a, b, 0.9, y, q, ws, M.ROUND_NEAREST_EVEN, 0, 0)
         assert relerr(npy(y), R.softmax_fwd(npy(s), B * H * rows, cols)) <= TOL[dtype], (cols, scale)
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.float32], ids=["f16", "f32"])
+@pytest.mark.parametrize("layout", [(3, 3000, 40), (2, 4096, 16), (1, 8192, 24), (5, 700, 361)])
+def test_thousands_of_groups(M, layout, dtype):
+    """Per-sample statistics of a large batch are thousands of groups: the parameter tables and the per-group
+    extrema then fill most of a workgroup's local memory.  Update, quantize, de-quantize and GELU backward up to
+    the limit of 8192 groups, the single-pass forward up to its own limit of 4096 (beyond it: a clean refusal)."""
+    outer, G, inner = layout
+    n = outer * G * inner
+    gen = torch.Generator(device="cuda").manual_seed(G + inner)
+    scale = (0.2 + 3.0 * torch.rand((1, G, 1), generator=gen, device="cuda"))
+    xs = [((torch.randn(layout, generator=gen, device="cuda") * scale) + 0.1 * t).to(dtype).contiguous() for t in range(2)]
+    a, b, ra, rb = run_params(M, xs, layout)
+    assert np.array_equal(canon(npy(a)), canon(ra)) and np.array_equal(canon(npy(b)), canon(rb))
+    x = xs[-1]
+    q = torch.empty(n, dtype=torch.int8, device="cuda")
+    M.mesa_quantize_headwise(x, layout, a, b, q, M.ROUND_STOCHASTIC, 9, 1)
+    rq = R.quantize_headwise(npy(x), layout, ra, rb, R.ROUND_STOCHASTIC, 9, 1).reshape(-1)
+    assert np.array_equal(npy(q), rq)
+    xh = torch.empty(n, dtype=dtype, device="cuda")
+    M.mesa_dequantize(q, layout, a, b, xh)
+    u = np.uint32 if dtype == torch.float32 else np.uint16
+    assert np.array_equal(npy(xh).view(u), R.dequantize(rq, layout, ra, rb, np.float32 if dtype == torch.float32 else np.float16).view(u).reshape(-1))
+    dy = torch.randn(layout, generator=gen, device="cuda").to(dtype)
+    dx = torch.empty_like(dy)
+    M.mesa_gelu_bwd_q(q, layout, a, b, dy, dx)
+    assert relerr(npy(dx).reshape(-1), R.gelu_bwd_q(rq, layout, ra, rb, npy(dy)).reshape(-1)) <= TOL[dtype]
+    # the single-pass forward on the same tensor
+    a2, b2 = a.clone(), b.clone()
+    q2 = torch.empty(n, dtype=torch.int8, device="cuda")
+    ws = ws_for(M, M.OP_UPDATE_RUNNING_PARAMS, *layout, dt=dtype)
+    if G <= 4096:
+        M.mesa_quantize_update_fused(x, layout, a2, b2, 0.9, q2, ws, M.ROUND_STOCHASTIC, 9, 1)
+        rq2, ra2, rb2 = R.quantize_update_fused(npy(x), layout, ra, rb, 0.9, R.ROUND_STOCHASTIC, 9, 1)
+        assert np.array_equal(npy(q2), rq2.reshape(-1))
+        assert np.array_equal(canon(npy(a2)), canon(ra2)) and np.array_equal(canon(npy(b2)), canon(rb2))
+    else:
+        with pytest.raises(M.MesaError) as e:
+            M.mesa_quantize_update_fused(x, layout, a2, b2, 0.9, q2, ws, M.ROUND_STOCHASTIC, 9, 1)
+        assert e.value.status == M.ERR_UNSUPPORTED
+        torch.cuda.synchronize()
+        assert torch.equal(a2, a) and torch.equal(b2, b)
