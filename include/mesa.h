@@ -113,6 +113,21 @@ mesa_status mesa_update_running_params_fixed_beta(const void *x, mesa_dtype dt, 
                                                   void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * For callers that cannot allocate device memory (code under HIP graph capture, serving loops,
+ * harnesses that forbid hipMalloc): mesa_update_running_params with the partial extrema in a
+ * device array that the library owns (mesa_static_scratch_bytes() = 1 MiB per GPU, held until the
+ * process ends) instead of a caller's workspace.  Same kernels, same results bit for bit.  The call
+ * allocates nothing and frees nothing; its first use on a device looks the array's address up once.
+ * Limit: shapes whose MESA_OP_UPDATE_RUNNING_PARAMS workspace exceeds the array (groups > 4096)
+ * return MESA_ERR_UNSUPPORTED.  Every call on a GPU shares that GPU's array: two calls that overlap
+ * in time on one GPU (distinct streams, or threads) race; calls on one stream do not.
+ */
+mesa_status mesa_update_running_params_static(const void *x, mesa_dtype dt, mesa_layout L,
+                                              float *alpha, float *beta, float lambda, int first_call,
+                                              void *stream);
+size_t mesa_static_scratch_bytes(void);
+
+/*
  * Quantizer, Sec. 3.2 Eq. (3)-(4):  x_bar = clip(round((x - beta_g) * (255 / alpha_g)), 0, 255).
  * binary32, separately rounded: r = 255/alpha_g (0 when alpha_g <= 0), t = x - beta_g, v = t*r,
  *   nearest:     w = v rounded to the nearest integer, ties to even

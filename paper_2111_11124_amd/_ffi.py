@@ -20,7 +20,7 @@ ROUND_NEAREST_EVEN, ROUND_STOCHASTIC = 0, 1
 OP_UPDATE_RUNNING_PARAMS, OP_LAYERNORM_BWD_Q, OP_LINEAR_DW_Q, OP_SOFTMAX_FWD_Q, OP_LAYERNORM_FWD_Q = 0, 1, 2, 3, 4
 
 EXPORTS = [
-    "mesa_update_running_params", "mesa_update_running_params_sym", "mesa_update_running_params_fixed_beta", "mesa_quantize_headwise", "mesa_quantize_update_fused", "mesa_gelu_fwd_q", "mesa_softmax_fwd_q", "mesa_layernorm_fwd_q", "mesa_dequantize", "mesa_softmax_bwd_q",
+    "mesa_update_running_params", "mesa_update_running_params_sym", "mesa_update_running_params_fixed_beta", "mesa_update_running_params_static", "mesa_static_scratch_bytes", "mesa_quantize_headwise", "mesa_quantize_update_fused", "mesa_gelu_fwd_q", "mesa_softmax_fwd_q", "mesa_layernorm_fwd_q", "mesa_dequantize", "mesa_softmax_bwd_q",
     "mesa_gelu_bwd_q", "mesa_relu_bwd_q", "mesa_layernorm_bwd_q", "mesa_linear_dw_q", "mesa_attn_av_bwd_q", "mesa_attn_qk_bwd_q",
     "mesa_workspace_bytes",
     "mesa_status_string", "mesa_version", "mesa_stream_copy", "mesa_event_create", "mesa_event_record",
@@ -52,6 +52,9 @@ def lib() -> C.CDLL:
         L.mesa_update_running_params.argtypes = [_vp, _int, Layout, _vp, _vp, _f32, _int, _vp, _sz, _vp]
         L.mesa_update_running_params_sym.argtypes = L.mesa_update_running_params.argtypes
         L.mesa_update_running_params_fixed_beta.argtypes = [_vp, _int, Layout, _vp, _vp, _f32, _int, _f32, _vp, _sz, _vp]
+        L.mesa_update_running_params_static.argtypes = [_vp, _int, Layout, _vp, _vp, _f32, _int, _vp]
+        L.mesa_static_scratch_bytes.argtypes = []
+        L.mesa_static_scratch_bytes.restype = _sz
         L.mesa_quantize_headwise.argtypes = [_vp, _int, Layout, _vp, _vp, _vp, _int, _u64, _u64, _vp]
         L.mesa_quantize_update_fused.argtypes = [_vp, _int, Layout, _vp, _vp, _f32, _vp, _int, _u64, _u64, _vp, _sz, _vp]
         L.mesa_gelu_fwd_q.argtypes = [_vp, _int, Layout, _vp, _vp, _f32, _vp, _vp, _int, _u64, _u64, _vp, _sz, _vp]
@@ -79,7 +82,7 @@ def lib() -> C.CDLL:
         L.mesa_event_destroy.argtypes = [_vp]
         for name in EXPORTS:
             fn = getattr(L, name)
-            if name not in ("mesa_workspace_bytes", "mesa_status_string", "mesa_version"):
+            if name not in ("mesa_workspace_bytes", "mesa_status_string", "mesa_version", "mesa_static_scratch_bytes"):
                 fn.restype = _int
         _lib = L
     return _lib
@@ -147,6 +150,15 @@ def mesa_update_running_params_fixed_beta(x, layout, alpha, beta, lam, first_cal
     _check(lib().mesa_update_running_params_fixed_beta(_ptr(x), _dt(x), Layout(*layout), _ptr(alpha), _ptr(beta), float(lam),
                                                        int(bool(first_call)), float(beta_fixed), p, n, _stream()),
            "mesa_update_running_params_fixed_beta")
+
+
+def mesa_update_running_params_static(x, layout, alpha, beta, lam, first_call):
+    _check(lib().mesa_update_running_params_static(_ptr(x), _dt(x), Layout(*layout), _ptr(alpha), _ptr(beta), float(lam),
+                                                   int(bool(first_call)), _stream()), "mesa_update_running_params_static")
+
+
+def static_scratch_bytes() -> int:
+    return int(lib().mesa_static_scratch_bytes())
 
 
 def mesa_quantize_headwise(x, layout, alpha, beta, q, mode=ROUND_STOCHASTIC, seed=0, offset=0):

@@ -16,6 +16,7 @@
 // kernel that may fuse (GELU backward) asks for it explicitly with fmaf.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <type_traits>
 
 #include "api_util.hpp"
@@ -950,6 +951,47 @@ extern "C" MESA_EXPORT mesa_status mesa_update_running_params_fixed_beta(const v
     if (!(beta_fixed == beta_fixed) || beta_fixed - beta_fixed != 0.0f) return MESA_ERR_INVALID_ARG;   // NaN or infinite
     return update_running_params(x, dt, L, alpha, beta, lambda, first_call, kEmaFixedBeta, beta_fixed, ws, ws_bytes, stream);
 }
+
+// ---- the running-estimate update for callers that cannot allocate device memory -----------------
+// The partial extrema go to a file-scope device array instead of a caller's workspace.  The array's
+// name is a host-side stand-in, not a device address: host code asks the runtime for the address
+// once per device (with that device current) and hands the kernels that pointer.
+constexpr size_t kStaticScratchBytes = size_t(1) << 20;
+constexpr int kStaticMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static std::atomic<void *> g_scratch_ptr[kStaticMaxDevices];
+
+// device address of `scratch` on the current device; nullptr when the runtime cannot tell
+static void *static_scratch_ptr()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kStaticMaxDevices) return nullptr;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    void *q = nullptr;
+    if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess || !q) return nullptr;
+    g_scratch_ptr[dev].store(q, std::memory_order_release);   // every thread finds the same address: a benign race
+    return q;
+}
+
+extern "C" MESA_EXPORT mesa_status mesa_update_running_params_static(const void *x, mesa_dtype dt, mesa_layout L, float *alpha,
+                                                                     float *beta, float lambda, int first_call, void *stream)
+{
+    // the argument checks come first, so that a bad call reports the same status as the workspace form
+    if (!valid_dtype(dt)) return MESA_ERR_INVALID_ARG;
+    mesa_status st = check_layout(L);
+    if (st != MESA_OK) return st;
+    if (!(lambda >= 0.0f && lambda <= 1.0f)) return MESA_ERR_INVALID_ARG;
+    if (layout_numel(L) == 0) return MESA_OK;
+    if (update_ws_bytes(L.outer, L.groups, L.inner) > kStaticScratchBytes) return MESA_ERR_UNSUPPORTED;
+    void *ws = static_scratch_ptr();
+    if (!ws) return MESA_ERR_LAUNCH;
+    // every workgroup overwrites its whole row of partial extrema before the second kernel reads
+    // them, so nothing of the previous call's contents is ever read and nothing needs clearing
+    return update_running_params(x, dt, L, alpha, beta, lambda, first_call, kEmaPlain, 0.0f, ws, kStaticScratchBytes, stream);
+}
+
+extern "C" MESA_EXPORT size_t mesa_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 extern "C" MESA_EXPORT mesa_status mesa_quantize_headwise(const void *x, mesa_dtype dt, mesa_layout L, const float *alpha,
                                               const float *beta, int8_t *q, mesa_round mode, uint64_t seed, uint64_t offset,
