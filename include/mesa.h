@@ -318,6 +318,11 @@ int mesa_version(void);
  * for `stop` on the host.
  */
 mesa_status mesa_stream_copy(const void *src, void *dst, size_t bytes, void *stream);
+/* mesa_stream_read: reads `bytes` bytes and writes nothing (sink: one device word, left as it is unless
+ * the data fold to one particular value); mesa_stream_fill: writes `word` over `bytes` bytes and reads
+ * nothing.  The bandwidth of one direction alone, next to the copy's.  Alignment as for the copy. */
+mesa_status mesa_stream_read(const void *src, size_t bytes, void *sink, void *stream);
+mesa_status mesa_stream_fill(void *dst, size_t bytes, uint32_t word, void *stream);
 mesa_status mesa_event_create(void **event);
 mesa_status mesa_event_record(void *event, void *stream);
 mesa_status mesa_event_elapsed_ms(void *start, void *stop, float *ms);

@@ -159,8 +159,8 @@ def layernorm_gamma(spec: BlockSpec, device="cpu") -> torch.Tensor:
     return (0.5 + torch.rand(spec.dim, generator=g, dtype=torch.float32)).to(spec.dtype).to(device)
 
 
-def upstream_grad(spec: BlockSpec, what: str, shape: Sequence[int], device="cpu") -> torch.Tensor:
-    g = _gen(spec, what, 0, device)
+def upstream_grad(spec: BlockSpec, what: str, shape: Sequence[int], device="cpu", draw: int = 0) -> torch.Tensor:
+    g = _gen(spec, what, draw, device)
     return _randn(tuple(shape), g, spec.dtype, device)
 
 

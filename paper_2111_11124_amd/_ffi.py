@@ -23,7 +23,7 @@ EXPORTS = [
     "mesa_update_running_params", "mesa_update_running_params_sym", "mesa_update_running_params_fixed_beta", "mesa_update_running_params_static", "mesa_static_scratch_bytes", "mesa_quantize_headwise", "mesa_quantize_update_fused", "mesa_gelu_fwd_q", "mesa_softmax_fwd_q", "mesa_layernorm_fwd_q", "mesa_dequantize", "mesa_softmax_bwd_q",
     "mesa_gelu_bwd_q", "mesa_relu_bwd_q", "mesa_layernorm_bwd_q", "mesa_linear_dw_q", "mesa_attn_av_bwd_q", "mesa_attn_qk_bwd_q",
     "mesa_workspace_bytes",
-    "mesa_status_string", "mesa_version", "mesa_stream_copy", "mesa_event_create", "mesa_event_record",
+    "mesa_status_string", "mesa_version", "mesa_stream_copy", "mesa_stream_read", "mesa_stream_fill", "mesa_event_create", "mesa_event_record",
     "mesa_event_elapsed_ms", "mesa_event_destroy",
 ]
 
@@ -76,6 +76,8 @@ def lib() -> C.CDLL:
         L.mesa_status_string.restype = C.c_char_p
         L.mesa_version.restype = _int
         L.mesa_stream_copy.argtypes = [_vp, _vp, _sz, _vp]
+        L.mesa_stream_read.argtypes = [_vp, _sz, _vp, _vp]
+        L.mesa_stream_fill.argtypes = [_vp, _sz, C.c_uint32, _vp]
         L.mesa_event_create.argtypes = [C.POINTER(_vp)]
         L.mesa_event_record.argtypes = [_vp, _vp]
         L.mesa_event_elapsed_ms.argtypes = [_vp, _vp, C.POINTER(_f32)]
@@ -245,6 +247,14 @@ def mesa_linear_dw_q(xq, M, K, G, alpha, beta, dy, N_out, dW, db, ws):
 
 def mesa_stream_copy(src, dst, nbytes):
     _check(lib().mesa_stream_copy(_ptr(src), _ptr(dst), int(nbytes), _stream()), "mesa_stream_copy")
+
+
+def mesa_stream_read(src, nbytes, sink):
+    _check(lib().mesa_stream_read(_ptr(src), int(nbytes), _ptr(sink), _stream()), "mesa_stream_read")
+
+
+def mesa_stream_fill(dst, nbytes, word=0):
+    _check(lib().mesa_stream_fill(_ptr(dst), int(nbytes), int(word), _stream()), "mesa_stream_fill")
 
 
 class Event:

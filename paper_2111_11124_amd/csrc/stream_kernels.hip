@@ -831,6 +831,39 @@ __global__ __launch_bounds__(kThreads) void k_copy(const u32x4 *__restrict__ src
 }
 
 
+// read-only and write-only probes: what the memory system delivers in one direction alone.  The read probe
+// folds what it loads into one word per thread and stores it only if it is a value no fold of the caller's
+// data produces twice in a row (the store exists so that the loads cannot be dropped; it moves 4 bytes a thread).
+__global__ __launch_bounds__(kThreads) void k_read_probe(const u32x4 *__restrict__ src, int64_t n16, uint32_t *__restrict__ sink)
+{
+    const int64_t chunk = kThreads * 4;
+    uint32_t acc = 0u;
+    for (int64_t base = int64_t(blockIdx.x) * chunk; base < n16; base += int64_t(gridDim.x) * chunk) {
+        u32x4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t i = base + u * kThreads + threadIdx.x;
+            v[u] = (i < n16) ? nt_load<u32x4>(src + i) : u32x4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc ^= v[u][0] ^ v[u][1] ^ v[u][2] ^ v[u][3];
+    }
+    if (acc == 0x9E3779B9u) sink[0] = acc;
+}
+
+__global__ __launch_bounds__(kThreads) void k_fill_probe(u32x4 *__restrict__ dst, int64_t n16, uint32_t word)
+{
+    const int64_t chunk = kThreads * 4;
+    const u32x4 v = {word, word, word, word};
+    for (int64_t base = int64_t(blockIdx.x) * chunk; base < n16; base += int64_t(gridDim.x) * chunk) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t i = base + u * kThreads + threadIdx.x;
+            if (i < n16) nt_store<u32x4>(dst + i, v);
+        }
+    }
+}
+
 void launch_ema_finalize(const float *part, int nwg, uint32_t groups, float *alpha, float *beta, float lambda, int first_call,
                          int variant, float beta_fixed, hipStream_t stream)
 {
@@ -1138,6 +1171,28 @@ extern "C" MESA_EXPORT mesa_status mesa_stream_copy(const void *src, void *dst, 
     const int grid = plan_grid(n16, int64_t(kThreads) * 4, 4 * kGridCap, 0);
     hipLaunchKernelGGL(k_copy, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
                        static_cast<const u32x4 *>(src), static_cast<u32x4 *>(dst), n16);
+    return launch_status();
+}
+
+extern "C" MESA_EXPORT mesa_status mesa_stream_read(const void *src, size_t bytes, void *sink, void *stream)
+{
+    if (bytes == 0) return MESA_OK;
+    if (!src || !sink || !aligned16(src) || !aligned4(sink) || (bytes & 15u)) return MESA_ERR_INVALID_ARG;
+    const int64_t n16 = int64_t(bytes / 16);
+    const int grid = plan_grid(n16, int64_t(kThreads) * 4, 4 * kGridCap, 0);
+    hipLaunchKernelGGL(k_read_probe, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const u32x4 *>(src), n16, static_cast<uint32_t *>(sink));
+    return launch_status();
+}
+
+extern "C" MESA_EXPORT mesa_status mesa_stream_fill(void *dst, size_t bytes, uint32_t word, void *stream)
+{
+    if (bytes == 0) return MESA_OK;
+    if (!dst || !aligned16(dst) || (bytes & 15u)) return MESA_ERR_INVALID_ARG;
+    const int64_t n16 = int64_t(bytes / 16);
+    const int grid = plan_grid(n16, int64_t(kThreads) * 4, 4 * kGridCap, 0);
+    hipLaunchKernelGGL(k_fill_probe, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream), static_cast<u32x4 *>(dst), n16,
+                       word);
     return launch_status();
 }
 
