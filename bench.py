@@ -501,6 +501,30 @@ def traffic_from_profile(spec, call):
     return None, None
 
 
+def dw_only(m, spec, steps):
+    """--only-dw: the configuration's weight-gradient calls alone, launched back to back over three rotating buffer sets
+    (the sustained rate, and the launch sequence the per-kernel counter summaries in profiles/ are taken on)."""
+    dev = "cuda"
+    H = spec.heads
+    out = {}
+    dtc = dtype_code(m, spec.dtype)
+    for K, N in spec.linears:
+        g = torch.Generator(device=dev).manual_seed(spec.seed + K + N)
+        qs = [torch.randint(-128, 128, (spec.tokens, K), dtype=torch.int8, device=dev, generator=g) for _ in range(3)]
+        dys = [W._randn((spec.tokens, N), g, spec.dtype, dev) for _ in range(3)]
+        a = torch.full((H,), 8.0, device=dev)
+        b = torch.full((H,), -4.0, device=dev)
+        dW = torch.empty((N, K), device=dev)
+        db = torch.empty(N, device=dev)
+        ws = torch.empty(m.workspace_bytes(m.OP_LINEAR_DW_Q, spec.tokens, K, N, dtc), dtype=torch.uint8, device=dev)
+        ms = timed_leg(lambda i: m.mesa_linear_dw_q(qs[i % 3], spec.tokens, K, H, a, b, dys[i % 3], N, dW, db, ws), steps)
+        fl = 2.0 * spec.tokens * K * N
+        out[f"{K}->{N}"] = {"ms": round(ms, 5), "tflops": round(fl / (ms * 1e-3) / 1e12, 1),
+                            "mfma_frac": round(fl / (ms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4), "shape": [spec.tokens, K, N]}
+        del qs, dys
+    return out
+
+
 def workload_name(spec, number, nblocks):
     b, h, r, c = spec.attn
     lins = ", ".join(f"{k}->{n}" for k, n in spec.linears) if spec.linears else "no Linear layer named"
@@ -517,6 +541,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the legs outside the headline (layer forwards, attention products, "
                                                              "single-pass variant, probes)")
+    ap.add_argument("--only-dw", action="store_true", help="run only the configuration's weight-gradient calls, back to back, and "
+                                                           "print their figures (a measurement helper, not the benchmark line)")
     ap.add_argument("--config", type=int, default=HEADLINE_CONFIG, choices=[2, 3, 4, 5],
                     help="which of the baseline configurations to run; the default (4) is the whole-model one, twelve blocks per "
                          "step; 2, 3 and 5 are single blocks")
@@ -536,6 +562,11 @@ def main():
     spec = W.CONFIGS[number]
     if args.storage == "bf16":
         spec = dataclasses.replace(spec, dtype=torch.bfloat16)
+    if args.only_dw:
+        print(json.dumps({"only_dw": dw_only(m, spec, args.steps or 20), "config": spec.name,
+                          "note": "weight gradients launched back to back: the sustained rate, below what the same calls reach "
+                                  "between the memory-bound kernels of a whole step"}))
+        return
     nblocks = BLOCKS[number]
     steps = args.steps if args.steps is not None else (30 if nblocks > 1 else 50)
     warmup = args.warmup if args.warmup is not None else (3 if nblocks > 1 else 10)

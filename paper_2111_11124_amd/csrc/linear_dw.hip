@@ -68,15 +68,16 @@ template <int BN, int BK, int WGN, int WGK> struct DwCfg {
     static_assert(2 * STAGE <= 64 * 1024, "two stages must fit the default dynamic LDS limit");
 };
 
-// four signed codes (the bytes of x) -> four binary16 values q: 0x6400 | (byte ^ 0x80) is 1152 + q exactly
-__device__ __forceinline__ v4h codes_to_half4(int raw)
+// four signed codes (the bytes of x) -> four binary16 values 1024 + x_bar: 0x6400 | (byte ^ 0x80), exactly.
+// The constant rides along in the contraction (dy^T (x_bar + 1024) = dy^T x_bar + 1024 S0) and is taken out
+// with the row sums afterwards: three instructions per four codes instead of five, at the price of four bits
+// of the binary32 sums (the products are at most 14 times larger than with the centred code).
+__device__ __forceinline__ v4s codes_to_half4(int raw)
 {
-    const h2 k1152 = {(_Float16)1152.0f, (_Float16)1152.0f};
     const uint32_t x = uint32_t(raw) ^ 0x80808080u;
-    const h2 a = as_h2(__builtin_amdgcn_perm(0x64646464u, x, 0x04010400u)) - k1152;   // bytes 0, 1
-    const h2 b = as_h2(__builtin_amdgcn_perm(0x64646464u, x, 0x04030402u)) - k1152;   // bytes 2, 3
-    v4h out = {a.x, a.y, b.x, b.y};
-    return out;
+    const v2i w = {int(__builtin_amdgcn_perm(0x64646464u, x, 0x04010400u)),    // bytes 0, 1
+                   int(__builtin_amdgcn_perm(0x64646464u, x, 0x04030402u))};   // bytes 2, 3
+    return __builtin_bit_cast(v4s, w);
 }
 
 // four signed codes -> four bfloat16 values q + 128 (bfloat16 has no spare mantissa bit for the exponent trick
@@ -94,8 +95,8 @@ __device__ __forceinline__ v4s codes_to_bf4(int raw)
 // contracted (kCentre: the offset c in "operand = x_bar - c"), the row sums of dy, and the MFMA itself.
 template <typename E> struct DwElem;
 template <> struct DwElem<_Float16> {
-    static constexpr float kCentre = 128.0f;
-    __device__ static __forceinline__ v4s convert(int raw) { return __builtin_bit_cast(v4s, codes_to_half4(raw)); }
+    static constexpr float kCentre = -1024.0f;
+    __device__ static __forceinline__ v4s convert(int raw) { return codes_to_half4(raw); }
     __device__ static __forceinline__ float dot_ones(uint32_t pair, float acc)
     {
         const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
@@ -271,22 +272,42 @@ __global__ __launch_bounds__(WGN * WGK * 64, 1) void k_dw_f16(const int8_t *__re
 #pragma unroll
         for (int r = 0; r < kNM; ++r) {
             mfma_item(r, PH);
+            // LDS reads: the code fragments in the first TJ slices (one each), the dy fragments over the rest
+            constexpr int kRA = kNR - C::TJ, kSA = kNM - C::TJ;
+            if (r < C::TJ) {
+                if (PH == 0) read_item(r, cur, 1, 1);
+                else read_item(r, nxt, 0, 0);
+            } else {
 #pragma unroll
-            for (int t = r * kNR / kNM; t < (r + 1) * kNR / kNM; ++t) {
-                if (PH == 0) read_item(t, cur, 1, 1);
-                else read_item(t, nxt, 0, 0);
+                for (int t = C::TJ + (r - C::TJ) * kRA / kSA; t < C::TJ + (r + 1 - C::TJ) * kRA / kSA; ++t) {
+                    if (PH == 0) read_item(t, cur, 1, 1);
+                    else read_item(t, nxt, 0, 0);
+                }
             }
 #pragma unroll
             for (int t = r * kMove / kNM; t < (r + 1) * kMove / kNM; ++t) {
                 if (PH == 0) store_item(t, nxt, ra, rb);
                 else load_item(t, m_fill, ra, rb);
             }
+            // conversions: fragment j's codes were requested in slice j; its two conversions run kLat slices
+            // later at the earliest, one per slice where the step is long enough, and the row sums take the
+            // slices the conversions leave free
+            constexpr int kLat = kNM >= 16 ? 4 : kNM / 2;
+            constexpr int kSC = kNM - kLat;                  // slices that carry conversions
+            if (r >= kLat) {
 #pragma unroll
-            for (int d = r * kND / kNM; d < (r + 1) * kND / kNM; ++d) dot_item(d, PH);
-            if (r >= kNM / 2) {
+                for (int c = (r - kLat) * kNC / kSC; c < (r + 1 - kLat) * kNC / kSC; ++c) conv_item(c, 1 - PH);
+            }
+            if (kNC >= kSC) {   // conversions everywhere behind kLat: the dots go wherever they fall evenly
 #pragma unroll
-                for (int c = (r - kNM / 2) * kNC / (kNM / 2); c < (r + 1 - kNM / 2) * kNC / (kNM / 2); ++c)
-                    conv_item(c, 1 - PH);
+                for (int d = r * kND / kNM; d < (r + 1) * kND / kNM; ++d) dot_item(d, PH);
+            } else {            // slices without a conversion (the first kLat, and the tail) take the dots
+                constexpr int kFree = (kLat + (kSC - kNC)) > 0 ? kLat + (kSC - kNC) : 1;
+                const int f = r < kLat ? r : (r >= kLat + kNC ? r - kNC : -1);
+                if (f >= 0) {
+#pragma unroll
+                    for (int d = f * kND / kFree; d < (f + 1) * kND / kFree; ++d) dot_item(d, PH);
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -322,14 +343,20 @@ __global__ __launch_bounds__(WGN * WGK * 64, 1) void k_dw_f16(const int8_t *__re
         // The stage loop is unrolled by the ring length so that every ring slot is a fixed set of
         // registers: stage s+1 sits in slot s % kDwPF, goes to LDS during the first step of stage s,
         // and the slot is refilled during the second step with stage s+1+kDwPF.
-        // The loop is left from the inside when the stages run out, so that there is one copy of
-        // each of the kDwPF stage bodies and every path to the loop head has all slots in flight.
-        for (int sbase = 0; sbase < nfull; sbase += C::PF) {
+        // The loop body is kDwPF whole stages with no way out of its middle, and the stages left over
+        // are separate copies behind it.  (Leaving the loop from the inside makes every exit a
+        // predecessor of the loop's latch: the compiler then has to assume at the loop head that ANY
+        // slot may hold the youngest loads, waits for the whole ring before the first slot's LDS
+        // writes -- a third of all stages then run with no prefetch distance at all -- and copies
+        // fragment registers at the latch.)
+        int sbase = 0;
+        for (; sbase + C::PF <= nfull; sbase += C::PF) {
 #pragma unroll
-            for (int d = 0; d < C::PF; ++d) {
-                stage(sbase + d, ring_a[d], ring_b[d]);
-                if (d + 1 < C::PF && sbase + d + 1 >= nfull) break;
-            }
+            for (int d = 0; d < C::PF; ++d) stage(sbase + d, ring_a[d], ring_b[d]);
+        }
+#pragma unroll
+        for (int d = 0; d < C::PF - 1; ++d) {
+            if (sbase + d < nfull) stage(sbase + d, ring_a[d], ring_b[d]);
         }
     }
     // The rows left over when the slice is not a whole number of stages (only the slice that ends

@@ -731,3 +731,24 @@ def test_thousands_of_groups(M, layout, dtype):
         assert e.value.status == M.ERR_UNSUPPORTED
         torch.cuda.synchronize()
         assert torch.equal(a2, a) and torch.equal(b2, b)
+
+
+@pytest.mark.parametrize("mean", [0.0, 0.5])
+def test_linear_dw_upstream_gradient_with_a_mean(M, mean):
+    """The binary16 weight gradient contracts dy with 1024 + x_bar (the constant is taken out again with the row
+    sums), so the binary32 sums carry a term 1024 * sum(dy) that the result does not: with an upstream gradient whose
+    mean is far from zero AND a de-quantized input centred on zero the cancellation is at its worst.  Half a standard
+    deviation of mean over 20000 rows must stay well inside the 2e-3 bound (measured: 3e-4 at 50000 rows)."""
+    Mr, K, N, G = 20000, 256, 512, 4
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    q = torch.randint(-128, 128, (Mr, K), dtype=torch.int8, device="cuda", generator=gen)
+    dy = (torch.randn((Mr, N), device="cuda", generator=gen) + mean).half()
+    a = torch.full((G,), 8.0, device="cuda")
+    b = torch.full((G,), -4.0, device="cuda")     # x_hat in [-4, 4]
+    dW = torch.empty((N, K), device="cuda")
+    db = torch.empty(N, device="cuda")
+    ws = ws_for(M, M.OP_LINEAR_DW_Q, Mr, K, N, torch.float16)
+    M.mesa_linear_dw_q(q, Mr, K, G, a, b, dy, N, dW, db, ws)
+    rW, rb = R.linear_dw_q(npy(q), Mr, K, G, npy(a), npy(b), npy(dy), N)
+    assert relerr(npy(dW), rW) <= 5e-4, relerr(npy(dW), rW)
+    assert relerr(npy(db), rb) <= 1e-5
