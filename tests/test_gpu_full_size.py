@@ -149,15 +149,25 @@ def test_config5_long_sequence_full_sampled(M):
     lay = spec.attn_layout
     n = B * H * rows * cols
     assert n == 1 << 31
-    x = W.attention_map(spec, 0, "cuda")
     a = torch.zeros(H, device="cuda")
     b = torch.zeros(H, device="cuda")
-    m.mesa_update_running_params(x, lay, a, b, spec.lam, True, ws(m, m.OP_UPDATE_RUNNING_PARAMS, *lay))
-    # first call: alpha = max - min, beta = min over each head (torch's reductions as the checker)
-    xv = x.view(B, H, rows * cols)
-    mn = xv.amin(dim=(0, 2)).float()
-    mx = xv.amax(dim=(0, 2)).float()
-    assert torch.equal(b, mn + 0.0) and torch.equal(a, mx - mn)
+    ra, rb = np.zeros(H, np.float32), np.zeros(H, np.float32)
+    # a first-call update and one moving-average step, each on its own draw of the 2^31-element map, against the
+    # oracle's scan of the same bits (and torch's reductions as a second opinion on the first)
+    for draw in range(2):
+        x = W.attention_map(spec, draw, "cuda")
+        m.mesa_update_running_params(x, lay, a, b, spec.lam, draw == 0, ws(m, m.OP_UPDATE_RUNNING_PARAMS, *lay))
+        if draw == 0:
+            xv = x.view(B, H, rows * cols)
+            mn = xv.amin(dim=(0, 2)).float()
+            mx = xv.amax(dim=(0, 2)).float()
+            assert torch.equal(b, mn + 0.0) and torch.equal(a, mx - mn)
+        xh = x.cpu().numpy()
+        ra, rb = R.update_running_params(xh, lay, ra, rb, spec.lam, draw == 0)
+        del xh
+        assert np.array_equal(canon(a.cpu().numpy()), canon(ra)) and np.array_equal(canon(b.cpu().numpy()), canon(rb)), draw
+        if draw == 0:
+            del x
     q = torch.empty(n, dtype=torch.int8, device="cuda")
     seed, off = 99, 12345
     m.mesa_quantize_headwise(x, lay, a, b, q, m.ROUND_STOCHASTIC, seed, off)
@@ -205,7 +215,112 @@ def test_config5_long_sequence_full_sampled(M):
         dw_sampled(m, spec, q, rq, a, b, ra, rb, K, N, tol, li)
 
 
-@pytest.mark.parametrize("number", [2, 3])
+def test_config5_layernorm_backward_full(M):
+    """(32768, 1024) rows in 16 channel groups, one element in a thousand scaled by 50: in full against the oracle."""
+    m = M
+    spec = W.CONFIGS[5]
+    tol = TOL[spec.dtype]
+    Mr, D, H = spec.tokens, spec.dim, spec.heads
+    assert (Mr, D, H) == (32768, 1024, 16)
+    draws = [W.token_matrix(spec, "ln", d, "cuda") for d in range(3)]
+    a, b, ra, rb, q, rq = forward(m, draws, spec.ln_layout, spec.lam, 7, 2 << 40)
+    mean, rstd = W.layernorm_stats(draws[-1])
+    assert float(draws[-1].abs().max()) > 60.0      # the outliers are there
+    del draws
+    gamma = W.layernorm_gamma(spec, "cuda")
+    dy = W.upstream_grad(spec, "dy_ln", (Mr, D), "cuda")
+    dx = torch.empty_like(dy)
+    dg = torch.empty(D, device="cuda")
+    db = torch.empty(D, device="cuda")
+    m.mesa_layernorm_bwd_q(q, Mr, D, H, a, b, mean, rstd, gamma, dy, dx, dg, db, ws(m, m.OP_LAYERNORM_BWD_Q, Mr, D, H))
+    rdx, rdg, rdb = R.layernorm_bwd_q(rq, Mr, D, H, ra, rb, mean.cpu().numpy(), rstd.cpu().numpy(), gamma.cpu().numpy(),
+                                      dy.cpu().numpy())
+    assert relerr(dx.cpu().numpy(), rdx) <= tol and relerr(dg.cpu().numpy(), rdg) <= tol and relerr(db.cpu().numpy(), rdb) <= tol
+
+
+def test_config5_softmax_layer_forward_sampled(M):
+    """mesa_softmax_fwd_q on the long-sequence logits (8, 16, 4096, 4096): the GPU runs all 2^31 elements; the stored
+    attention map against the oracle's softmax, and the codes against the oracle's quantizer applied to the stored
+    values, on whole row blocks at the start, across a head boundary, in the middle and at the end; the moved
+    estimates against the oracle's scan of the whole stored map."""
+    m = M
+    spec = W.CONFIGS[5]
+    tol = TOL[spec.dtype]
+    B, H, rows, cols = spec.attn
+    lay = spec.attn_layout
+    n = B * H * rows * cols
+    g = torch.Generator(device="cuda").manual_seed(55)
+    sig = W.head_sigmas(spec).to("cuda").view(1, H, 1, 1)
+    s = torch.empty(spec.attn, dtype=spec.dtype, device="cuda")
+    for bb in range(B):
+        s[bb] = (torch.randn((H, rows, cols), generator=g, device="cuda") * sig[0]).to(spec.dtype)
+    y = torch.empty_like(s)
+    q = torch.empty(n, dtype=torch.int8, device="cuda")
+    a = torch.full((H,), 0.05, device="cuda")
+    b = torch.zeros(H, device="cuda")
+    ra, rb = a.cpu().numpy().copy(), b.cpu().numpy().copy()
+    w = torch.empty(max(m.workspace_bytes(m.OP_SOFTMAX_FWD_Q, B * H * rows, H, cols, m.F16), 16), dtype=torch.uint8, device="cuda")
+    seed, off = 17, 1 << 35
+    m.mesa_softmax_fwd_q(s, B, H, rows, cols, a, b, spec.lam, y, q, w, m.ROUND_STOCHASTIC, seed, off)
+    torch.cuda.synchronize()
+    slab = rows * cols
+    nrows_blk = 48
+    starts = [0, rows - nrows_blk // 2, (B * H // 2) * rows + 777, B * H * rows - nrows_blk]
+    sf, yf = s.view(-1), y.view(-1)
+    for r0 in starts:
+        e0, e1 = r0 * cols, (r0 + nrows_blk) * cols
+        for h_slab in sorted({r // rows for r in range(r0, r0 + nrows_blk)}):
+            lo, hi = max(e0, h_slab * slab), min(e1, (h_slab + 1) * slab)
+            gi = h_slab % H
+            nr = (hi - lo) // cols
+            ys = yf[lo:hi].cpu().numpy()
+            assert relerr(ys, R.softmax_fwd(sf[lo:hi].cpu().numpy(), nr, cols)) <= tol
+            rq = R.quantize_headwise(ys, (1, 1, hi - lo), ra[gi:gi + 1], rb[gi:gi + 1], R.ROUND_STOCHASTIC, seed, off + lo // 8)
+            assert np.array_equal(q[lo:hi].cpu().numpy(), rq.reshape(-1))
+    del s
+    yh = y.cpu().numpy()
+    ra2, rb2 = R.update_running_params(yh, lay, ra, rb, spec.lam, False)
+    assert np.array_equal(canon(a.cpu().numpy()), canon(ra2)) and np.array_equal(canon(b.cpu().numpy()), canon(rb2))
+
+
+def test_config5_attention_products_backward_sampled(M):
+    """The four attention-product gradients at the long-sequence shape (8, 16, 4096, 64) -- sequences far beyond what
+    the dedicated short-sequence kernels take: the GPU runs every head, the oracle the first and the last one."""
+    spec = W.CONFIGS[5]
+    B, H, N, _ = spec.attn
+    Dh = spec.dim // spec.heads
+    dev = "cuda"
+    g = torch.Generator(device=dev).manual_seed(spec.seed + 78)
+    aq = torch.empty((B, H, N, N), dtype=torch.int8, device=dev)
+    dS = torch.empty((B, H, N, N), dtype=spec.dtype, device=dev)
+    for bb in range(B):
+        aq[bb] = torch.randint(-128, 128, (H, N, N), dtype=torch.int8, device=dev, generator=g)
+        dS[bb] = (torch.randn((H, N, N), device=dev, generator=g) * 0.05).to(spec.dtype)
+    qq, kq, vq = (torch.randint(-128, 128, (B, H, N, Dh), dtype=torch.int8, device=dev, generator=g) for _ in range(3))
+    dO = torch.randn((B, H, N, Dh), device=dev, generator=g).to(spec.dtype)
+    par = {k: (torch.linspace(1.0, 4.0, H, device=dev) * sc, torch.linspace(-2.0, -0.5, H, device=dev) * sc)
+           for k, sc in (("a", 0.25), ("q", 1.0), ("k", 1.5), ("v", 0.75))}
+    dA = torch.empty((B, H, N, N), dtype=spec.dtype, device=dev)
+    dV, dQ, dK = (torch.empty((B, H, N, Dh), dtype=spec.dtype, device=dev) for _ in range(3))
+    M.mesa_attn_av_bwd_q(aq, vq, B, H, N, Dh, *par["a"], *par["v"], dO, dA, dV)
+    scale = Dh ** -0.5
+    M.mesa_attn_qk_bwd_q(qq, kq, B, H, N, Dh, *par["q"], *par["k"], dS, scale, dQ, dK)
+    torch.cuda.synchronize()
+    rp = {k: (a.cpu().numpy(), b.cpu().numpy()) for k, (a, b) in par.items()}
+    rep = {}
+    # (one head's four products are 4.3 G multiply-adds in the oracle's plain binary64 loops: the first head serves
+    # the A V pair, the last head the Q K^T pair)
+    one = lambda t, bb, hh: t[bb:bb + 1, hh:hh + 1].contiguous().cpu().numpy()   # noqa: E731
+    hp = lambda k, hh: (rp[k][0][hh:hh + 1], rp[k][1][hh:hh + 1])                # noqa: E731
+    rdA, rdV = R.attn_av_bwd_q(one(aq, 0, 0), one(vq, 0, 0), 1, 1, N, Dh, *hp("a", 0), *hp("v", 0), one(dO, 0, 0))
+    rep["dA"], rep["dV"] = relerr(one(dA, 0, 0), rdA), relerr(one(dV, 0, 0), rdV)
+    bb, hh = B - 1, H - 1
+    rdQ, rdK = R.attn_qk_bwd_q(one(qq, bb, hh), one(kq, bb, hh), 1, 1, N, Dh, *hp("q", hh), *hp("k", hh), one(dS, bb, hh), scale)
+    rep["dQ"], rep["dK"] = relerr(one(dQ, bb, hh), rdQ), relerr(one(dK, bb, hh), rdK)
+    assert all(v <= TOL[spec.dtype] for v in rep.values()), rep
+
+
+@pytest.mark.parametrize("number", [2, 3, 4])
 def test_attention_products_backward_full_size_sampled(M, number):
     """The four attention-product gradients at the configuration's full attention shape (the launch the
     bench times): the GPU runs every sample, the oracle the first, a middle and the last sample (all heads)."""
