@@ -103,9 +103,37 @@ uint16_t mesa_ref_float_to_half(float f)
     return (uint16_t)(sign | out);
 }
 
+/* ------------------------------------------------------------------------ */
+/* bfloat16 (the upper half of a binary32 word) <-> binary32                 */
+/* ------------------------------------------------------------------------ */
+
+float mesa_ref_bf16_to_float(uint16_t h)
+{
+    uint32_t bits = (uint32_t)h << 16; /* widening is exact */
+    float f;
+    memcpy(&f, &bits, 4);
+    return f;
+}
+
+/* round-to-nearest, ties-to-even on the 16 bits that are dropped */
+uint16_t mesa_ref_float_to_bf16(float f)
+{
+    uint32_t bits;
+    memcpy(&bits, &f, 4);
+    if ((bits & 0x7FFFFFFFu) > 0x7F800000u) { /* nan: keep it a nan whatever the dropped bits were */
+        return (uint16_t)((bits >> 16) | 0x0040u);
+    }
+    uint32_t kept = bits >> 16;
+    uint32_t rem = bits & 0xFFFFu;
+    if (rem > 0x8000u || (rem == 0x8000u && (kept & 1u))) kept += 1u; /* a carry out of the mantissa bumps the exponent; 0x7F7F + 1 is infinity */
+    return (uint16_t)kept;
+}
+
+/* dt: 0 binary32, 1 binary16, 2 bfloat16 */
 static float load_as_float(const void *p, int dt, int64_t idx)
 {
     if (dt == 0) return ((const float *)p)[idx];
+    if (dt == 2) return mesa_ref_bf16_to_float(((const uint16_t *)p)[idx]);
     return mesa_ref_half_to_float(((const uint16_t *)p)[idx]);
 }
 
@@ -237,6 +265,93 @@ int mesa_ref_update_running_params_sym(const void *x, int dt, int64_t outer, int
             float e = lambda * beta[g];
             float f = b * mn;
             beta[g] = e + f;
+        }
+    }
+    return 0;
+}
+
+/*
+ * Scale-only symmetric quantization, the scheme the ablation of Sec. 5.3 compares Mesa with: the input is
+ * quantized "by a scale factor only" -- no offset, zero is a code.  The paper prints the scale as
+ * (2^b - 1) / max|X|; with signed b-bit codes that range would need b + 1 bits, so the reading taken here is
+ * the usual signed one: 2^(b-1) - 1 = 127 steps on each side of zero,
+ *   m      running estimate of max |x| over the group (Eq. (6) with max|x| in place of the range;
+ *          first call: m = max|x|)
+ *   r      = 127 / m   (0 when m <= 0)
+ *   q      = clip(round(x * r), -127, 127)     round: nearest-even, or floor(v + u) as in Eq. (4)
+ *   x_hat  = q * (m / 127)
+ * binary32, each operation rounded on its own.
+ */
+int mesa_ref_update_running_scale_sym(const void *x, int dt, int64_t outer, int64_t groups, int64_t inner,
+                                      float *m, float lambda, int first_call)
+{
+    if (outer <= 0 || groups <= 0 || inner <= 0) return 0;
+    for (int64_t g = 0; g < groups; ++g) {
+        float mx = 0.0f;
+        for (int64_t o = 0; o < outer; ++o)
+            for (int64_t i = 0; i < inner; ++i) {
+                float v = fabsf(load_as_float(x, dt, (o * groups + g) * inner + i));
+                if (v > mx) mx = v;
+            }
+        if (first_call) {
+            m[g] = mx;
+        } else {
+            float a = lambda * m[g];
+            float b = 1.0f - lambda;
+            float c = b * mx;
+            m[g] = a + c;
+        }
+    }
+    return 0;
+}
+
+int mesa_ref_quantize_sym(const void *x, int dt, int64_t outer, int64_t groups, int64_t inner,
+                          const float *m, int8_t *q, int mode, uint64_t seed, uint64_t offset)
+{
+    if (outer <= 0 || groups <= 0 || inner <= 0) return 0;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t o = 0; o < outer; ++o) {
+        for (int64_t g = 0; g < groups; ++g) {
+            float r = (m[g] > 0.0f) ? 127.0f / m[g] : 0.0f;
+            for (int64_t i = 0; i < inner; ++i) {
+                int64_t e = (o * groups + g) * inner + i;
+                float v = load_as_float(x, dt, e) * r;
+                float w;
+                if (mode == 0) {
+                    w = rintf(v);
+                } else {
+                    float u = mesa_ref_sr_uniform(seed, offset, (uint64_t)e);
+                    float s = v + u;
+                    w = floorf(s);
+                }
+                if (w < -127.0f) w = -127.0f;
+                if (w > 127.0f) w = 127.0f;
+                q[e] = (int8_t)(int)w;
+            }
+        }
+    }
+    return 0;
+}
+
+int mesa_ref_dequantize_sym(const int8_t *q, int64_t outer, int64_t groups, int64_t inner,
+                            const float *m, void *x_hat, int dt)
+{
+    if (outer <= 0 || groups <= 0 || inner <= 0) return 0;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t o = 0; o < outer; ++o) {
+        for (int64_t g = 0; g < groups; ++g) {
+            float step = m[g] / 127.0f;
+            for (int64_t i = 0; i < inner; ++i) {
+                int64_t e = (o * groups + g) * inner + i;
+                float xh = (float)(int)q[e] * step;
+                if (dt == 0) ((float *)x_hat)[e] = xh;
+                else if (dt == 2) ((uint16_t *)x_hat)[e] = mesa_ref_float_to_bf16(xh);
+                else ((uint16_t *)x_hat)[e] = mesa_ref_float_to_half(xh);
+            }
         }
     }
     return 0;
@@ -394,6 +509,7 @@ int mesa_ref_dequantize(const int8_t *q, int64_t outer, int64_t groups, int64_t 
                 int64_t e = (o * groups + g) * inner + i;
                 float xh = dequant_one(q[e], step, b);
                 if (dt == 0) ((float *)x_hat)[e] = xh;
+                else if (dt == 2) ((uint16_t *)x_hat)[e] = mesa_ref_float_to_bf16(xh);
                 else ((uint16_t *)x_hat)[e] = mesa_ref_float_to_half(xh);
             }
         }

@@ -18,7 +18,7 @@ _HERE = Path(__file__).resolve().parent
 _SRC = _HERE / "mesa_ref.c"
 _LIB = _HERE / "libmesa_ref.so"
 
-F32, F16 = 0, 1
+F32, F16, BF16 = 0, 1, 2
 ROUND_NEAREST, ROUND_STOCHASTIC = 0, 1
 
 
@@ -45,6 +45,10 @@ def lib():
         _lib.mesa_ref_half_to_float.argtypes = [C.c_uint16]
         _lib.mesa_ref_float_to_half.restype = C.c_uint16
         _lib.mesa_ref_float_to_half.argtypes = [C.c_float]
+        _lib.mesa_ref_bf16_to_float.restype = C.c_float
+        _lib.mesa_ref_bf16_to_float.argtypes = [C.c_uint16]
+        _lib.mesa_ref_float_to_bf16.restype = C.c_uint16
+        _lib.mesa_ref_float_to_bf16.argtypes = [C.c_float]
         _lib.mesa_ref_sr_uniform.restype = C.c_float
         _lib.mesa_ref_sr_uniform.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64]
         _lib.mesa_ref_num_threads.restype = C.c_int
@@ -188,15 +192,65 @@ def gelu_fwd_q(x, layout, alpha, beta, lam, mode=ROUND_NEAREST, seed=0, offset=0
     return y.reshape(x.shape), q.reshape(x.shape), a, b
 
 
+def update_running_scale_sym(x, layout, m, lam, first_call):
+    """Scale-only symmetric scheme: the running estimate of max |x| per group; returns the new m."""
+    outer, groups, inner = layout
+    x = _c(x)
+    assert x.size == outer * groups * inner
+    m = _c(m, np.float32).copy()
+    lib().mesa_ref_update_running_scale_sym(_p(x), _dt(x), I64(outer), I64(groups), I64(inner), _p(m), C.c_float(lam),
+                                            C.c_int(int(bool(first_call))))
+    return m
+
+
+def quantize_sym(x, layout, m, mode=ROUND_NEAREST, seed=0, offset=0):
+    outer, groups, inner = layout
+    x = _c(x)
+    assert x.size == outer * groups * inner
+    m = _c(m, np.float32)
+    q = np.empty(x.shape, np.int8)
+    lib().mesa_ref_quantize_sym(_p(x), _dt(x), I64(outer), I64(groups), I64(inner), _p(m), _p(q), C.c_int(mode),
+                                C.c_uint64(seed), C.c_uint64(offset))
+    return q
+
+
+def dequantize_sym(q, layout, m, dtype=np.float32):
+    outer, groups, inner = layout
+    q = _c(q, np.int8)
+    assert q.size == outer * groups * inner
+    m = _c(m, np.float32)
+    if isinstance(dtype, str) and dtype == "bf16":
+        out = np.empty(q.shape, np.uint16)
+        lib().mesa_ref_dequantize_sym(_p(q), I64(outer), I64(groups), I64(inner), _p(m), _p(out), BF16)
+        return out
+    out = np.empty(q.shape, dtype)
+    lib().mesa_ref_dequantize_sym(_p(q), I64(outer), I64(groups), I64(inner), _p(m), _p(out), _dt(out))
+    return out
+
+
 def dequantize(q, layout, alpha, beta, dtype=np.float32):
+    """dtype: np.float32, np.float16, or the string "bf16" -- then the result is the bfloat16 bit patterns as uint16
+    (numpy has no bfloat16)."""
     outer, groups, inner = layout
     q = _c(q, np.int8)
     assert q.size == outer * groups * inner
     a = _c(alpha, np.float32)
     b = _c(beta, np.float32)
+    if isinstance(dtype, str) and dtype == "bf16":
+        out = np.empty(q.shape, np.uint16)
+        lib().mesa_ref_dequantize(_p(q), I64(outer), I64(groups), I64(inner), _p(a), _p(b), _p(out), BF16)
+        return out
     out = np.empty(q.shape, dtype)
     lib().mesa_ref_dequantize(_p(q), I64(outer), I64(groups), I64(inner), _p(a), _p(b), _p(out), _dt(out))
     return out
+
+
+def float_to_bf16(f: float) -> int:
+    return int(lib().mesa_ref_float_to_bf16(C.c_float(f)))
+
+
+def bf16_to_float(bits: int) -> float:
+    return float(lib().mesa_ref_bf16_to_float(int(bits)))
 
 
 def softmax_fwd(s, total_rows, cols):

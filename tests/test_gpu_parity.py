@@ -113,7 +113,7 @@ def test_params_codes_and_dequantize_are_bit_exact(M, layout, dtype):
         assert np.array_equal(npy(out).view(u), ref.view(u))
     out = torch.empty(n, dtype=torch.bfloat16, device="cuda")
     M.mesa_dequantize(q, layout, a, b, out)
-    assert np.array_equal(out.view(torch.int16).cpu().numpy(), bf16_bits(R.dequantize(rq, layout, an, bn, np.float32)))
+    assert np.array_equal(out.view(torch.int16).cpu().numpy().view(np.uint16), R.dequantize(rq, layout, an, bn, "bf16").reshape(-1))
 
 
 def block_parity(m, spec, modes=("nearest", "stochastic")):

@@ -172,3 +172,70 @@ def test_attention_offsets_are_non_negative():
     y = W.attention_map(spec).numpy()
     a, b = R.update_running_params(y, spec.attn_layout, np.zeros(spec.heads), np.zeros(spec.heads), 0.9, True)
     assert np.all(b >= 0) and np.all(a > 0) and np.all(a + b <= 1.0 + 1e-6)
+
+
+def test_bfloat16_conversions_match_torch():
+    """The oracle's own bfloat16 rounding (nearest, ties to even on the dropped 16 bits) against torch's CPU conversion,
+    a library routine for exactly this, on random magnitudes plus ties, carries into the exponent and the overflow to
+    infinity; widening back is exact."""
+    rng = np.random.default_rng(1)
+    v = np.concatenate([
+        rng.standard_normal(20000).astype(np.float32) * np.float32(10.0) ** rng.integers(-30, 30, 20000).astype(np.float32),
+        np.array([0.0, -0.0, 1.0, 1.0 + 2.0 ** -8, 1.0 + 2.0 ** -7, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20,
+                  1.99609375, 1.998046875, 3.3895313892515355e38, 3.4e38, -3.4e38, 1e-40, 2.0 ** -133, np.inf, -np.inf],
+                 np.float32),
+    ])
+    want = torch.from_numpy(v).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = np.array([R.float_to_bf16(float(x)) for x in v], np.uint16)
+    assert np.array_equal(got, want), np.nonzero(got != want)[0][:5]
+    bits = np.arange(0, 65536, 7, dtype=np.uint16)
+    wide = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).float().numpy()
+    mine = np.array([R.bf16_to_float(int(b)) for b in bits], np.float32)
+    fin = np.isfinite(wide)
+    assert np.array_equal(mine[fin].view(np.uint32), wide[fin].view(np.uint32))
+    # and the de-quantizer's bfloat16 output is its binary32 output rounded that way
+    q = np.arange(-128, 128, dtype=np.int8)
+    a, b = np.array([3.7], np.float32), np.array([-1.3], np.float32)
+    x32 = R.dequantize(q, (1, 1, 256), a, b, np.float32)
+    xb = R.dequantize(q, (1, 1, 256), a, b, "bf16")
+    assert np.array_equal(xb, torch.from_numpy(x32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16))
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+def test_nearest_rounding_sends_exact_half_steps_to_the_even_code(dtype):
+    """Tie rule of the nearest mode: x = beta + (k + 1/2) * s on a grid where everything is exact (s = 1/8, beta = -4:
+    x is a multiple of 1/16, exact in binary16 too, and v = (x - beta) * 8 = k + 1/2 exactly) must give the EVEN
+    neighbour for every k -- round-half-away-from-zero or round-half-up would give k + 1 throughout."""
+    a, b = np.array([255.0 / 8.0], np.float32), np.array([-4.0], np.float32)
+    k = np.arange(0, 255)
+    x = (b[0] + (k + 0.5) / 8.0).astype(dtype)
+    assert np.array_equal(x.astype(np.float64), -4.0 + (k + 0.5) / 8.0)          # the inputs are exact
+    u = R.quantize_headwise(x, (1, 1, x.size), a, b, R.ROUND_NEAREST).astype(np.int64) + 128
+    even = np.where(k % 2 == 0, k, k + 1)
+    assert np.array_equal(u, even)
+    assert np.all(u % 2 == 0)
+    # a little off the tie (an eighth of a step or less; every value still exact) the nearer neighbour wins on either side
+    e = -10 if dtype == np.float32 else -6
+    d = dtype(2.0 ** e)
+    lo = R.quantize_headwise(x - d, (1, 1, x.size), a, b, R.ROUND_NEAREST).astype(np.int64) + 128
+    hi = R.quantize_headwise(x + d, (1, 1, x.size), a, b, R.ROUND_NEAREST).astype(np.int64) + 128
+    assert np.array_equal((x - d).astype(np.float64), x.astype(np.float64) - 2.0 ** e)
+    assert np.array_equal(lo, k) and np.array_equal(hi, k + 1)
+
+
+def test_stochastic_rounding_is_unbiased_over_many_draws():
+    """Eq. (4): E[x_hat] = x.  Twenty thousand independent draws (distinct counter blocks) per value, the mean
+    reconstruction within four standard errors of x, for fractions across (0, 1) including tiny ones."""
+    a, b = np.array([255.0], np.float32), np.array([0.0], np.float32)   # x_hat = code
+    x = np.array([0.015625, 0.1, 3.25, 17.5, 100.9, 254.01, 77.984375, 200.0], np.float32)   # one Philox block per row
+    n = 20000
+    xs = np.tile(x, n)
+    q = R.quantize_headwise(xs, (1, 1, xs.size), a, b, R.ROUND_STOCHASTIC, seed=777, offset=12345).astype(np.int64) + 128
+    xh = R.dequantize((q - 128).astype(np.int8), (1, 1, xs.size), a, b).astype(np.float64).reshape(n, x.size)
+    assert np.all((xh == np.floor(x)[None, :]) | (xh == np.ceil(x)[None, :]))
+    frac = (x - np.floor(x)).astype(np.float64)
+    se = np.sqrt(np.maximum(frac * (1 - frac), 1e-12) / n)
+    assert np.all(np.abs(xh.mean(axis=0) - x) <= 4 * se + 2.0 ** -16), (xh.mean(axis=0) - x, se)
+    # the empirical probability of rounding up is the fraction, to the generator's 16-bit resolution
+    up = (xh == np.ceil(x)[None, :]).mean(axis=0)[frac > 0]
+    assert np.all(np.abs(up - frac[frac > 0]) <= 4 * se[frac > 0] + 2.0 ** -16)
