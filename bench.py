@@ -468,6 +468,34 @@ def layer_forward_legs(m, spec, steps):
     return out
 
 
+def symmetric_leg(m, spec, steps):
+    """Outside the headline figure: the forward half (statistics + quantize) of the scale-only symmetric scheme the paper's
+    ablation compares with (Sec. 5.3), next to the method's asymmetric forward, on the configuration's GELU input."""
+    lay = spec.gelu_layout
+    n = lay[0] * lay[1] * lay[2]
+    dev = "cuda"
+    esz = elem_bytes(spec.dtype)
+    nbytes = (2 * esz + 1) * n
+    ns = max(3, min(LEG_SETS, int(math.ceil(600e6 / nbytes)) + 1))
+    g = torch.Generator(device=dev).manual_seed(spec.seed + 6)
+    xs = [W._randn(lay, g, spec.dtype, dev) for _ in range(ns)]
+    qs = [torch.empty(n, dtype=torch.int8, device=dev) for _ in range(ns)]
+    a = torch.zeros(lay[1], device=dev)
+    b = torch.zeros(lay[1], device=dev)
+    mm = torch.zeros(lay[1], device=dev)
+    ws = torch.empty(max(m.workspace_bytes(m.OP_UPDATE_RUNNING_PARAMS, *lay, dtype_code(m, spec.dtype)), 16), dtype=torch.uint8, device=dev)
+    m.mesa_update_running_params(xs[0], lay, a, b, 0.9, True, ws)
+    m.mesa_update_running_scale_sym(xs[0], lay, mm, 0.9, True, ws)
+    asym = timed_leg(lambda i: (m.mesa_update_running_params(xs[i % ns], lay, a, b, 0.9, False, ws),
+                                m.mesa_quantize_headwise(xs[i % ns], lay, a, b, qs[i % ns], m.ROUND_STOCHASTIC, 1, i)), steps)
+    sym = timed_leg(lambda i: (m.mesa_update_running_scale_sym(xs[i % ns], lay, mm, 0.9, False, ws),
+                               m.mesa_quantize_sym(xs[i % ns], lay, mm, qs[i % ns], m.ROUND_STOCHASTIC, 1, i)), steps)
+    return {"symmetric_ms": round(sym, 4), "asymmetric_ms": round(asym, 4), "bytes": nbytes,
+            "symmetric_GBps": round(nbytes / (sym * 1e-3) / 1e9, 1), "asymmetric_GBps": round(nbytes / (asym * 1e-3) / 1e9, 1),
+            "note": "update + quantize of the GELU input, stochastic rounding: mesa_update_running_scale_sym + mesa_quantize_sym "
+                    "against mesa_update_running_params + mesa_quantize_headwise; both read x twice and write one byte per element"}
+
+
 def bandwidth_probes(m):
     """Untimed extras: what plain kernels reach on this GPU -- a copy (the known-traffic kernel the bandwidth counters are
     scaled against), a read-only and a write-only stream, 256 MiB each, three rotating buffers, median of event pairs."""
@@ -672,6 +700,7 @@ def main():
         leg_steps = 20
         out["attention_matmul_bwd"] = attention_matmul_leg(m, spec, leg_steps) if number != 5 else None
         out.update(layer_forward_legs(m, spec, leg_steps))
+        out["symmetric_scale_only_forward"] = symmetric_leg(m, spec, leg_steps)
     if not args.no_cpu_baseline and number in (2, HEADLINE_CONFIG):
         # the oracle reads binary16 or binary32 arrays: for bfloat16 runs it is timed on the binary16 workload (same bytes)
         out["cpu_baseline"] = cpu_baseline(dataclasses.replace(spec, dtype=torch.float16), number)

@@ -89,15 +89,34 @@ mesa_status mesa_update_running_params(const void *x, mesa_dtype dt, mesa_layout
                                        void *ws, size_t ws_bytes, void *stream);
 
 /*
- * Symmetric range, the ablation of Sec. 5.3 (asymmetric vs. symmetric quantization): one scale from
- * m_g = max |x| over group g, no free offset.  The paper states the scale factor only; here the
- * clipping range is [-m_g, +m_g]: the call above with mn_g := -m_g and mx_g := +m_g, so that alpha_g
+ * Symmetric RANGE (a second, milder reading of the ablation of Sec. 5.3; the scale-only scheme proper is
+ * mesa_quantize_sym below): one scale from m_g = max |x| over group g, no free offset, but the codes and
+ * every other call stay the asymmetric ones.  The clipping range is [-m_g, +m_g]: the call above with mn_g := -m_g and mx_g := +m_g, so that alpha_g
  * moves towards 2 m_g and beta_g towards -m_g.  Quantizer, dequantizer and the backward calls take
  * the resulting alpha, beta unchanged.  Arguments, workspace and errors: as for the call above.
  */
 mesa_status mesa_update_running_params_sym(const void *x, mesa_dtype dt, mesa_layout L,
                                            float *alpha, float *beta, float lambda, int first_call,
                                            void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Scale-only symmetric quantization, the scheme the ablation of Sec. 5.3 ("asymmetric vs. symmetric quantization")
+ * compares the method with: the input is quantized by a scale factor only -- no offset, zero is a code.  The paper
+ * prints the scale as (2^b - 1) / max|X|; with signed b-bit codes that would need b + 1 bits, so the signed reading is
+ * taken: 127 steps on each side of zero.  Three calls:
+ *   mesa_update_running_scale_sym   m_g <- lambda*m_g + (1-lambda)*max|x| over group g  (first_call: m_g = max|x|)
+ *   mesa_quantize_sym               q = clip(round(x * (127 / m_g)), -127, 127);  round: nearest-even or Eq. (4)
+ *   mesa_dequantize_sym             x_hat = q * (m_g / 127)
+ * binary32, every operation rounded on its own; random source, layouts, workspace and errors as for the asymmetric
+ * calls.  m: [groups] binary32 on the device.  The fused backward calls take these codes as well, with
+ * alpha_g = m_g * 255/127 and beta_g = -m_g * 128/127 (the same x_hat up to rounding).
+ */
+mesa_status mesa_update_running_scale_sym(const void *x, mesa_dtype dt, mesa_layout L, float *m, float lambda,
+                                          int first_call, void *ws, size_t ws_bytes, void *stream);
+mesa_status mesa_quantize_sym(const void *x, mesa_dtype dt, mesa_layout L, const float *m, int8_t *q,
+                              mesa_round mode, uint64_t seed, uint64_t offset, void *stream);
+mesa_status mesa_dequantize_sym(const int8_t *q, mesa_layout L, const float *m, void *x_hat, mesa_dtype dt,
+                                void *stream);
 
 /*
  * Fixed offset, Sec. 6 (evolution of alpha and beta in FFN layers): the offset of the second FFN

@@ -20,7 +20,7 @@ ROUND_NEAREST_EVEN, ROUND_STOCHASTIC = 0, 1
 OP_UPDATE_RUNNING_PARAMS, OP_LAYERNORM_BWD_Q, OP_LINEAR_DW_Q, OP_SOFTMAX_FWD_Q, OP_LAYERNORM_FWD_Q = 0, 1, 2, 3, 4
 
 EXPORTS = [
-    "mesa_update_running_params", "mesa_update_running_params_sym", "mesa_update_running_params_fixed_beta", "mesa_update_running_params_static", "mesa_static_scratch_bytes", "mesa_quantize_headwise", "mesa_quantize_update_fused", "mesa_gelu_fwd_q", "mesa_softmax_fwd_q", "mesa_layernorm_fwd_q", "mesa_dequantize", "mesa_softmax_bwd_q",
+    "mesa_update_running_params", "mesa_update_running_params_sym", "mesa_update_running_params_fixed_beta", "mesa_update_running_scale_sym", "mesa_quantize_sym", "mesa_dequantize_sym", "mesa_update_running_params_static", "mesa_static_scratch_bytes", "mesa_quantize_headwise", "mesa_quantize_update_fused", "mesa_gelu_fwd_q", "mesa_softmax_fwd_q", "mesa_layernorm_fwd_q", "mesa_dequantize", "mesa_softmax_bwd_q",
     "mesa_gelu_bwd_q", "mesa_relu_bwd_q", "mesa_layernorm_bwd_q", "mesa_linear_dw_q", "mesa_attn_av_bwd_q", "mesa_attn_qk_bwd_q",
     "mesa_workspace_bytes",
     "mesa_status_string", "mesa_version", "mesa_stream_copy", "mesa_stream_read", "mesa_stream_fill", "mesa_event_create", "mesa_event_record",
@@ -52,6 +52,9 @@ def lib() -> C.CDLL:
         L.mesa_update_running_params.argtypes = [_vp, _int, Layout, _vp, _vp, _f32, _int, _vp, _sz, _vp]
         L.mesa_update_running_params_sym.argtypes = L.mesa_update_running_params.argtypes
         L.mesa_update_running_params_fixed_beta.argtypes = [_vp, _int, Layout, _vp, _vp, _f32, _int, _f32, _vp, _sz, _vp]
+        L.mesa_update_running_scale_sym.argtypes = [_vp, _int, Layout, _vp, _f32, _int, _vp, _sz, _vp]
+        L.mesa_quantize_sym.argtypes = [_vp, _int, Layout, _vp, _vp, _int, _u64, _u64, _vp]
+        L.mesa_dequantize_sym.argtypes = [_vp, Layout, _vp, _vp, _int, _vp]
         L.mesa_update_running_params_static.argtypes = [_vp, _int, Layout, _vp, _vp, _f32, _int, _vp]
         L.mesa_static_scratch_bytes.argtypes = []
         L.mesa_static_scratch_bytes.restype = _sz
@@ -152,6 +155,21 @@ def mesa_update_running_params_fixed_beta(x, layout, alpha, beta, lam, first_cal
     _check(lib().mesa_update_running_params_fixed_beta(_ptr(x), _dt(x), Layout(*layout), _ptr(alpha), _ptr(beta), float(lam),
                                                        int(bool(first_call)), float(beta_fixed), p, n, _stream()),
            "mesa_update_running_params_fixed_beta")
+
+
+def mesa_update_running_scale_sym(x, layout, m, lam, first_call, ws):
+    p, n = _ws_args(ws)
+    _check(lib().mesa_update_running_scale_sym(_ptr(x), _dt(x), Layout(*layout), _ptr(m), float(lam), int(bool(first_call)), p, n,
+                                               _stream()), "mesa_update_running_scale_sym")
+
+
+def mesa_quantize_sym(x, layout, m, q, mode=ROUND_STOCHASTIC, seed=0, offset=0):
+    _check(lib().mesa_quantize_sym(_ptr(x), _dt(x), Layout(*layout), _ptr(m), _ptr(q), int(mode), int(seed), int(offset),
+                                   _stream()), "mesa_quantize_sym")
+
+
+def mesa_dequantize_sym(q, layout, m, x_hat):
+    _check(lib().mesa_dequantize_sym(_ptr(q), Layout(*layout), _ptr(m), _ptr(x_hat), _dt(x_hat), _stream()), "mesa_dequantize_sym")
 
 
 def mesa_update_running_params_static(x, layout, alpha, beta, lam, first_call):

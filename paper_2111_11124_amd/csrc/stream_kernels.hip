@@ -60,7 +60,9 @@ template <int U> __device__ __forceinline__ void place_cursors(Cursor c[U], cons
 // ---------------------------------------------------------------------------------------------
 // per-group parameter table in LDS: (scale, beta) per group
 // ---------------------------------------------------------------------------------------------
-enum class Scale { Quant, Dequant };
+// (QuantSym / DequantSym: the scale-only symmetric scheme -- alpha holds m, the running estimate of max |x|;
+// 127 steps on each side of zero, no offset, beta is not read)
+enum class Scale { Quant, Dequant, QuantSym, DequantSym };
 
 template <Scale S>
 __device__ __forceinline__ void fill_table(float2 *tab, const float *alpha, const float *beta, uint32_t groups)
@@ -69,8 +71,10 @@ __device__ __forceinline__ void fill_table(float2 *tab, const float *alpha, cons
         float a = alpha[g];
         float s;
         if (S == Scale::Quant) s = (a > 0.0f) ? 255.0f / a : 0.0f;  // correctly rounded division
+        else if (S == Scale::QuantSym) s = (a > 0.0f) ? 127.0f / a : 0.0f;
+        else if (S == Scale::DequantSym) s = a / 127.0f;
         else s = a / 255.0f;
-        tab[g] = make_float2(s, beta[g]);
+        tab[g] = make_float2(s, (S == Scale::QuantSym || S == Scale::DequantSym) ? 0.0f : beta[g]);
     }
     __syncthreads();
 }
@@ -415,14 +419,15 @@ __device__ __forceinline__ void ema_update(float mn, float mx, float alpha_old, 
 // one workgroup per group: combine the partial extrema, then Eq. (6)-(7)
 // variant kEmaSymmetric: the extrema are replaced by -m and +m, m = max |x| = max(-min, max);
 // variant kEmaFixedBeta: the offset is beta_fixed, only alpha is a running estimate (of max - beta_fixed)
-enum { kEmaPlain = 0, kEmaSymmetric = 1, kEmaFixedBeta = 2 };
+// variant kEmaScaleOnly: the scale-only symmetric scheme -- alpha is the running estimate of m = max |x|, beta is not touched
+enum { kEmaPlain = 0, kEmaSymmetric = 1, kEmaFixedBeta = 2, kEmaScaleOnly = 3 };
 __global__ __launch_bounds__(kThreads) void k_ema_finalize(const float *__restrict__ part, int nwg, uint32_t groups,
                                                            float *alpha, float *beta, float lambda, int first_call,
                                                            int variant = kEmaPlain, float beta_fixed = 0.0f)
 {
     __shared__ float smn[kThreads / 64], smx[kThreads / 64];
     const uint32_t g = blockIdx.x;
-    const float alpha_old = alpha[g], beta_old = beta[g];   // in flight together with the partial extrema
+    const float alpha_old = alpha[g], beta_old = variant == kEmaScaleOnly ? 0.0f : beta[g];   // in flight together with the partial extrema
     float mn = __builtin_inff(), mx = -__builtin_inff();
     for (int w = threadIdx.x; w < nwg; w += kThreads) {
         mn = vmin(mn, part[int64_t(w) * 2 * groups + g]);
@@ -442,7 +447,17 @@ __global__ __launch_bounds__(kThreads) void k_ema_finalize(const float *__restri
             mx = vmax(-mn, mx);
             mn = -mx;
         }
-        if (variant == kEmaFixedBeta) {
+        if (variant == kEmaScaleOnly) {
+            const float m = vmax(-mn, mx) + 0.0f;
+            if (first_call) {
+                alpha[g] = m;
+            } else {
+                float a = lambda * alpha_old;
+                float b = 1.0f - lambda;
+                float c = b * m;
+                alpha[g] = a + c;
+            }
+        } else if (variant == kEmaFixedBeta) {
             ema_update(beta_fixed, mx, alpha_old, beta_old, alpha, beta, g, lambda, first_call);
             beta[g] = beta_fixed;
         } else {
@@ -458,13 +473,13 @@ __device__ __forceinline__ void params_of(const Cursor &c, const GroupGeom &gg, 
     for (int j = 0; j < 8; ++j) p[j] = tab[group_of(c, j, gg)];
 }
 
-template <typename T, int U, bool SR>
+template <typename T, int U, bool SR, bool SYM = false>
 __global__ __launch_bounds__(kThreads) void k_quantize(const void *__restrict__ x, int8_t *__restrict__ q, int64_t numel,
                                                        GroupGeom gg, const float *__restrict__ alpha,
                                                        const float *__restrict__ beta, uint64_t seed, uint64_t offset)
 {
     extern __shared__ float2 lds_tab[];
-    fill_table<Scale::Quant>(lds_tab, alpha, beta, gg.groups);
+    fill_table<SYM ? Scale::QuantSym : Scale::Quant>(lds_tab, alpha, beta, gg.groups);
 
     Cursor c[U];
     place_cursors<U>(c, gg, numel);
@@ -492,12 +507,12 @@ __global__ __launch_bounds__(kThreads) void k_quantize(const void *__restrict__ 
                 if (__builtin_expect(c[u].rem + kVec <= gg.inner, 1)) {
                     const float2 p = lds_tab[c[u].g];
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) w[j] = quantize_one<SR>(f[j], p.x, p.y, SR ? bits[j] : 0.0f);
+                    for (int j = 0; j < 8; ++j) w[j] = quantize_one<SR, SYM>(f[j], p.x, p.y, SR ? bits[j] : 0.0f);
                 } else {   // the vector crosses a slab end: parameters per element
                     float2 p[8];
                     params_of(c[u], gg, lds_tab, p);
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) w[j] = quantize_one<SR>(f[j], p[j].x, p[j].y, SR ? bits[j] : 0.0f);
+                    for (int j = 0; j < 8; ++j) w[j] = quantize_one<SR, SYM>(f[j], p[j].x, p[j].y, SR ? bits[j] : 0.0f);
                 }
                 nt_store<u32x2>(q + e, pack_codes(w));
             } else if (e < numel) {   // the ragged end of the tensor, once per launch
@@ -505,7 +520,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize(const void *__restrict__ 
                 if (SR) sr_bits(seed, offset + uint64_t(e >> 3), bits);
                 for (int j = 0; e + j < numel; ++j) {
                     const float2 p = lds_tab[group_of(c[u], j, gg)];
-                    const float w = clamp_code(quantize_one<SR>(Store<T>::load1(x, e + j), p.x, p.y, SR ? bits[j] : 0.0f));
+                    const float w = clamp_code(quantize_one<SR, SYM>(Store<T>::load1(x, e + j), p.x, p.y, SR ? bits[j] : 0.0f));
                     q[e + j] = int8_t(int(w) - 128);
                 }
             }
@@ -638,14 +653,16 @@ __device__ __forceinline__ float dequant_exact(float u, float s, float b)
     xh = xh + b;
     return xh;
 }
+// scale-only symmetric scheme: x_hat = q * (m / 127); u = q + 128 as the code bytes unpack
+__device__ __forceinline__ float dequant_sym(float u, float s) { return (u - 128.0f) * s; }
 
-template <typename T, int U>
+template <typename T, int U, bool SYM = false>
 __global__ __launch_bounds__(kThreads) void k_dequantize(const int8_t *__restrict__ q, void *__restrict__ xh, int64_t numel,
                                                          GroupGeom gg, const float *__restrict__ alpha,
                                                          const float *__restrict__ beta)
 {
     extern __shared__ float2 lds_tab[];
-    fill_table<Scale::Dequant>(lds_tab, alpha, beta, gg.groups);
+    fill_table<SYM ? Scale::DequantSym : Scale::Dequant>(lds_tab, alpha, beta, gg.groups);
 
     Cursor c[U];
     place_cursors<U>(c, gg, numel);
@@ -672,18 +689,18 @@ __global__ __launch_bounds__(kThreads) void k_dequantize(const int8_t *__restric
                 if (__builtin_expect(c[u].rem + kVec <= gg.inner, 1)) {
                     const float2 p = lds_tab[c[u].g];
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) f[j] = dequant_exact(uu[j], p.x, p.y);
+                    for (int j = 0; j < 8; ++j) f[j] = (SYM ? dequant_sym(uu[j], p.x) : dequant_exact(uu[j], p.x, p.y));
                 } else {
                     float2 p[8];
                     params_of(c[u], gg, lds_tab, p);
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) f[j] = dequant_exact(uu[j], p[j].x, p[j].y);
+                    for (int j = 0; j < 8; ++j) f[j] = (SYM ? dequant_sym(uu[j], p[j].x) : dequant_exact(uu[j], p[j].x, p[j].y));
                 }
                 Nt<T>::store(xh, e, Store<T>::pack(f));
             } else if (e < numel) {
                 for (int j = 0; e + j < numel; ++j) {
                     const float2 p = lds_tab[group_of(c[u], j, gg)];
-                    Store<T>::store1(xh, e + j, dequant_exact(code_to_float(q[e + j]), p.x, p.y));
+                    Store<T>::store1(xh, e + j, (SYM ? dequant_sym(code_to_float(q[e + j]), p.x) : dequant_exact(code_to_float(q[e + j]), p.x, p.y)));
                 }
             }
             cursor_advance(c[u], gg);
@@ -931,7 +948,8 @@ static mesa_status update_running_params(const void *x, mesa_dtype dt, mesa_layo
     if (!(lambda >= 0.0f && lambda <= 1.0f)) return MESA_ERR_INVALID_ARG;
     const int64_t numel = layout_numel(L);
     if (numel == 0) return MESA_OK;
-    if (!x || !alpha || !beta || !aligned16(x) || !aligned4(alpha) || !aligned4(beta)) return MESA_ERR_INVALID_ARG;
+    if (!x || !alpha || !aligned16(x) || !aligned4(alpha)) return MESA_ERR_INVALID_ARG;
+    if (variant != kEmaScaleOnly && (!beta || !aligned4(beta))) return MESA_ERR_INVALID_ARG;
     if (!ws || !aligned16(ws) || ws_bytes < update_ws_bytes(L.outer, L.groups, L.inner))
         return MESA_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -1026,29 +1044,52 @@ extern "C" MESA_EXPORT mesa_status mesa_update_running_params_static(const void 
 
 extern "C" MESA_EXPORT size_t mesa_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
-extern "C" MESA_EXPORT mesa_status mesa_quantize_headwise(const void *x, mesa_dtype dt, mesa_layout L, const float *alpha,
-                                              const float *beta, int8_t *q, mesa_round mode, uint64_t seed, uint64_t offset,
-                                              void *stream)
+// sym: the scale-only symmetric scheme (alpha holds m, beta is absent)
+static mesa_status quantize(const void *x, mesa_dtype dt, mesa_layout L, const float *alpha, const float *beta, int8_t *q,
+                            mesa_round mode, uint64_t seed, uint64_t offset, bool sym, void *stream)
 {
     if (!valid_dtype(dt) || (mode != MESA_ROUND_NEAREST_EVEN && mode != MESA_ROUND_STOCHASTIC)) return MESA_ERR_INVALID_ARG;
     mesa_status st = check_layout(L);
     if (st != MESA_OK) return st;
     const int64_t numel = layout_numel(L);
     if (numel == 0) return MESA_OK;
-    if (!x || !q || !alpha || !beta || !aligned16(x) || !aligned16(q) || !aligned4(alpha) || !aligned4(beta))
-        return MESA_ERR_INVALID_ARG;
+    if (!x || !q || !alpha || !aligned16(x) || !aligned16(q) || !aligned4(alpha)) return MESA_ERR_INVALID_ARG;
+    if (!sym && (!beta || !aligned4(beta))) return MESA_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int grid = stream_grid(numel, L.groups > 1 ? L.groups * L.inner : 0);
     GroupGeom gg = make_geom(L.groups, L.inner, int64_t(grid) * kThreads * kU * kVec);
     const size_t lds = size_t(gg.groups) * sizeof(float2);
     const bool sr = mode == MESA_ROUND_STOCHASTIC;
-#define MESA_LAUNCH_Q(T, SRF) \
-    hipLaunchKernelGGL((k_quantize<T, kU, SRF>), dim3(grid), dim3(kThreads), lds, s, x, q, numel, gg, alpha, beta, seed, offset)
-#define MESA_LAUNCH_Q_T(T) do { if (sr) MESA_LAUNCH_Q(T, true); else MESA_LAUNCH_Q(T, false); } while (0)
+#define MESA_LAUNCH_Q(T, SRF, SYMF) \
+    hipLaunchKernelGGL((k_quantize<T, kU, SRF, SYMF>), dim3(grid), dim3(kThreads), lds, s, x, q, numel, gg, alpha, beta, seed, offset)
+#define MESA_LAUNCH_Q_T(T) \
+    do { \
+        if (sym) { if (sr) MESA_LAUNCH_Q(T, true, true); else MESA_LAUNCH_Q(T, false, true); } \
+        else { if (sr) MESA_LAUNCH_Q(T, true, false); else MESA_LAUNCH_Q(T, false, false); } \
+    } while (0)
     MESA_FOR_DTYPE(dt, MESA_LAUNCH_Q_T);
 #undef MESA_LAUNCH_Q_T
 #undef MESA_LAUNCH_Q
     return launch_status();
+}
+
+extern "C" MESA_EXPORT mesa_status mesa_quantize_headwise(const void *x, mesa_dtype dt, mesa_layout L, const float *alpha,
+                                              const float *beta, int8_t *q, mesa_round mode, uint64_t seed, uint64_t offset,
+                                              void *stream)
+{
+    return quantize(x, dt, L, alpha, beta, q, mode, seed, offset, false, stream);
+}
+
+extern "C" MESA_EXPORT mesa_status mesa_quantize_sym(const void *x, mesa_dtype dt, mesa_layout L, const float *m, int8_t *q,
+                                                     mesa_round mode, uint64_t seed, uint64_t offset, void *stream)
+{
+    return quantize(x, dt, L, m, nullptr, q, mode, seed, offset, true, stream);
+}
+
+extern "C" MESA_EXPORT mesa_status mesa_update_running_scale_sym(const void *x, mesa_dtype dt, mesa_layout L, float *m, float lambda,
+                                                                 int first_call, void *ws, size_t ws_bytes, void *stream)
+{
+    return update_running_params(x, dt, L, m, nullptr, lambda, first_call, kEmaScaleOnly, 0.0f, ws, ws_bytes, stream);
 }
 
 // the single-pass forward, optionally with the layer's own output: gelu_fwd: y = gelu(x) leaves in the same pass
@@ -1105,24 +1146,40 @@ extern "C" MESA_EXPORT mesa_status mesa_gelu_fwd_q(const void *x, mesa_dtype dt,
     return quantize_update_fused(x, dt, L, alpha, beta, lambda, true, y, q, mode, seed, offset, ws, ws_bytes, stream);
 }
 
-extern "C" MESA_EXPORT mesa_status mesa_dequantize(const int8_t *q, mesa_layout L, const float *alpha, const float *beta, void *x_hat,
-                                       mesa_dtype dt, void *stream)
+static mesa_status dequantize(const int8_t *q, mesa_layout L, const float *alpha, const float *beta, void *x_hat, mesa_dtype dt,
+                              bool sym, void *stream)
 {
     if (!valid_dtype(dt)) return MESA_ERR_INVALID_ARG;
     mesa_status st = check_layout(L);
     if (st != MESA_OK) return st;
     const int64_t numel = layout_numel(L);
     if (numel == 0) return MESA_OK;
-    if (!q || !x_hat || !alpha || !beta || !aligned16(q) || !aligned16(x_hat) || !aligned4(alpha) || !aligned4(beta))
-        return MESA_ERR_INVALID_ARG;
+    if (!q || !x_hat || !alpha || !aligned16(q) || !aligned16(x_hat) || !aligned4(alpha)) return MESA_ERR_INVALID_ARG;
+    if (!sym && (!beta || !aligned4(beta))) return MESA_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int grid = stream_grid(numel, L.groups > 1 ? L.groups * L.inner : 0);
     GroupGeom gg = make_geom(L.groups, L.inner, int64_t(grid) * kThreads * kU * kVec);
     const size_t lds = size_t(gg.groups) * sizeof(float2);
-#define MESA_LAUNCH_DQ(T) hipLaunchKernelGGL((k_dequantize<T, kU>), dim3(grid), dim3(kThreads), lds, s, q, x_hat, numel, gg, alpha, beta)
+#define MESA_LAUNCH_DQ(T) \
+    do { \
+        if (sym) hipLaunchKernelGGL((k_dequantize<T, kU, true>), dim3(grid), dim3(kThreads), lds, s, q, x_hat, numel, gg, alpha, beta); \
+        else hipLaunchKernelGGL((k_dequantize<T, kU, false>), dim3(grid), dim3(kThreads), lds, s, q, x_hat, numel, gg, alpha, beta); \
+    } while (0)
     MESA_FOR_DTYPE(dt, MESA_LAUNCH_DQ);
 #undef MESA_LAUNCH_DQ
     return launch_status();
+}
+
+extern "C" MESA_EXPORT mesa_status mesa_dequantize(const int8_t *q, mesa_layout L, const float *alpha, const float *beta, void *x_hat,
+                                       mesa_dtype dt, void *stream)
+{
+    return dequantize(q, L, alpha, beta, x_hat, dt, false, stream);
+}
+
+extern "C" MESA_EXPORT mesa_status mesa_dequantize_sym(const int8_t *q, mesa_layout L, const float *m, void *x_hat, mesa_dtype dt,
+                                                       void *stream)
+{
+    return dequantize(q, L, m, nullptr, x_hat, dt, true, stream);
 }
 
 template <int ACT>

@@ -24,11 +24,6 @@ def npy(t):
     return (t.float() if t.dtype == torch.bfloat16 else t).cpu().numpy()
 
 
-def bf16_bits(a32):
-    """binary32 array -> the bits of its round-to-nearest-even bfloat16 (torch's conversion)."""
-    return torch.from_numpy(np.ascontiguousarray(a32, np.float32)).to(torch.bfloat16).view(torch.int16).numpy()
-
-
 @pytest.fixture(scope="module")
 def M():
     import paper_2111_11124_amd as m
@@ -213,7 +208,7 @@ def block_parity(m, spec, modes=("nearest", "stochastic")):
                 assert np.array_equal(npy(out).view(u), R.dequantize(rq, lay, ra, rb, npo).view(u))
             out = torch.empty(q.numel(), dtype=torch.bfloat16, device="cuda")
             m.mesa_dequantize(q, lay, a, b, out)
-            assert np.array_equal(out.view(torch.int16).cpu().numpy(), bf16_bits(R.dequantize(rq, lay, ra, rb, np.float32)))
+            assert np.array_equal(out.view(torch.int16).cpu().numpy().view(np.uint16), R.dequantize(rq, lay, ra, rb, "bf16").reshape(-1))
     bad = {k: v for k, v in report.items() if not v <= tol}
     assert not bad, (bad, report)
     return report
@@ -752,3 +747,50 @@ def test_linear_dw_upstream_gradient_with_a_mean(M, mean):
     rW, rb = R.linear_dw_q(npy(q), Mr, K, G, npy(a), npy(b), npy(dy), N)
     assert relerr(npy(dW), rW) <= 5e-4, relerr(npy(dW), rW)
     assert relerr(npy(db), rb) <= 1e-5
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=DTYPE_IDS)
+@pytest.mark.parametrize("layout", [(3, 4, 1000), (5, 3, 361), (37, 6, 64), (1, 1, 12345), (7, 5, 3), (3000, 12, 256)])
+def test_scale_only_symmetric_scheme_is_bit_exact(M, layout, dtype):
+    """The ablation's comparison scheme (Sec. 5.3): running scale after a first call and two moving-average steps,
+    codes in both rounding modes and the de-quantized values, all bit for bit against the oracle; and the fused GELU
+    backward fed with these codes through the equivalent (alpha, beta) pair."""
+    outer, G, inner = layout
+    n = outer * G * inner
+    gen = torch.Generator(device="cuda").manual_seed(n + 5)
+    scale = torch.tensor([0.3, 1.0, 4.0, 11.0, 0.05, 2.0, 7.0, 1.5, 0.8, 3.0, 0.1, 6.0], device="cuda")[:G].view(1, G, 1)
+    xs = [(torch.randn((outer, G, inner), generator=gen, device="cuda") * scale * (1.0 + 0.3 * i) - 0.2 * i).to(dtype).contiguous()
+          for i in range(3)]
+    m = torch.full((G,), 9.0, device="cuda")
+    rm = np.full(G, 9.0, np.float32)
+    ws = ws_for(M, M.OP_UPDATE_RUNNING_PARAMS, *layout, dt=dtype)
+    for i, x in enumerate(xs):
+        M.mesa_update_running_scale_sym(x, layout, m, 0.9, i == 0, ws)
+        rm = R.update_running_scale_sym(npy(x), layout, rm, 0.9, i == 0)
+        assert np.array_equal(canon(npy(m)), canon(rm)), i
+    x = xs[-1]          # the running scale lags the last batch: some elements saturate
+    for mode, seed, off in ((M.ROUND_NEAREST_EVEN, 0, 0), (M.ROUND_STOCHASTIC, 0xABCDEF0123, (1 << 34) + 3)):
+        q = torch.empty(n, dtype=torch.int8, device="cuda")
+        M.mesa_quantize_sym(x, layout, m, q, mode, seed, off)
+        rq = R.quantize_sym(npy(x), layout, rm, mode, seed, off).reshape(-1)
+        bad = np.nonzero(npy(q) != rq)[0]
+        assert bad.size == 0, (mode, bad[:10], npy(q)[bad[:10]], rq[bad[:10]])
+        assert int(q.min()) >= -127
+    for odt, npo, u in ((torch.float32, np.float32, np.uint32), (torch.float16, np.float16, np.uint16)):
+        out = torch.empty(n, dtype=odt, device="cuda")
+        M.mesa_dequantize_sym(q, layout, m, out)
+        assert np.array_equal(npy(out).view(u), R.dequantize_sym(rq, layout, rm, npo).view(u))
+    out = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    M.mesa_dequantize_sym(q, layout, m, out)
+    assert np.array_equal(out.view(torch.int16).cpu().numpy().view(np.uint16), R.dequantize_sym(rq, layout, rm, "bf16").reshape(-1))
+    # backward through the asymmetric form of the same reconstruction
+    a_eq, b_eq = m * (255.0 / 127.0), m * (-128.0 / 127.0)
+    dy = torch.randn((outer, G, inner), generator=gen, device="cuda").to(dtype)
+    dx = torch.empty_like(dy)
+    M.mesa_gelu_bwd_q(q, layout, a_eq, b_eq, dy, dx)
+    ref = R.gelu_bwd_q(rq, layout, npy(a_eq), npy(b_eq), npy(dy)).reshape(-1)
+    assert relerr(npy(dx).reshape(-1), ref) <= TOL[dtype]
+    # and that pair does reproduce the symmetric reconstruction, to rounding
+    xa = R.dequantize(rq, layout, npy(a_eq), npy(b_eq), np.float32).astype(np.float64)
+    xsym = R.dequantize_sym(rq, layout, rm, np.float32).astype(np.float64)
+    assert np.abs(xa - xsym).max() <= 4e-6 * max(float(rm.max()), 1e-30)
