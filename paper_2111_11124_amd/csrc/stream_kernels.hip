@@ -31,7 +31,7 @@ namespace mesa {
 // vectors in flight per thread and many workgroups (more waves to hide the integer multiplies of
 // the random generator); the read-only min/max scan with four vectors and fewer workgroups.
 constexpr int kU = 2;                            // vectors per thread and iteration
-constexpr int kGridCap = 4096;                   // 16 workgroups of 4 waves per CU, two rounds of 8
+constexpr int kGridCap = 16384;                  // one chunk per workgroup up to 67 M elements: more, shorter workgroups balance better than a grid-stride loop
 constexpr int kMmU = 4;                          // the same two numbers for the min/max scan
 constexpr int kMmGridCap = 1024;
 constexpr int kMmFew = 8;                        // groups for which a thread can hold every group's extrema
@@ -895,9 +895,17 @@ void launch_ema_finalize(const float *part, int nwg, uint32_t groups, float *alp
 // =================================================================================================
 using namespace mesa;
 
-static int stream_grid(int64_t numel, int64_t row)
+// min_chunks: how many chunks a workgroup should move at the very least (a kernel that builds a table per workgroup
+// wants the table paid for by more than one chunk)
+static int stream_grid(int64_t numel, int64_t row, int min_chunks = 1)
 {
-    return plan_grid(numel, int64_t(kThreads) * kU * kVec, kGridCap, row);
+    const int64_t chunk = int64_t(kThreads) * kU * kVec;
+    int64_t cap = kGridCap;
+    if (min_chunks > 1) {
+        const int64_t fit = numel / (chunk * min_chunks);
+        if (fit < cap) cap = fit < 256 ? 256 : fit;
+    }
+    return plan_grid(numel, chunk, int(cap), row);
 }
 
 // grid of a kernel that tracks extrema with `unroll` vectors per thread and at most `grid_cap` workgroups
@@ -1195,7 +1203,8 @@ static mesa_status act_bwd_q(const int8_t *xq, mesa_layout L, const float *alpha
         !aligned4(beta))
         return MESA_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int grid = stream_grid(numel, L.groups > 1 ? L.groups * L.inner : 0);
+    const bool lut_fits = (L.groups <= 1 ? 1 : L.groups) <= kLutMaxGroups;
+    const int grid = stream_grid(numel, L.groups > 1 ? L.groups * L.inner : 0, lut_fits ? 2 : 1);
     GroupGeom gg = make_geom(L.groups, L.inner, int64_t(grid) * kThreads * kU * kVec);
     const bool lut = gg.groups <= uint32_t(kLutMaxGroups);
     const size_t lds = lut ? size_t(gg.groups) * 256 * sizeof(float) : size_t(gg.groups) * sizeof(float2);
