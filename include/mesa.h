@@ -238,6 +238,23 @@ mesa_status mesa_dequantize(const int8_t *q, mesa_layout L, const float *alpha, 
                             void *x_hat, mesa_dtype dt, void *stream);
 
 /*
+ * Four-bit codes (Sec. 4.2 names lower bit widths as the step beyond the method's fixed eight bits): Eq. (3)-(5)
+ * with 2^4 - 1 = 15 steps across the clipping range,
+ *   x_bar = clip(round((x - beta_g) * (15 / alpha_g)), 0, 15),     x_hat = x_bar * (alpha_g / 15) + beta_g,
+ * same binary32 operation sequence, rounding modes and random source as mesa_quantize_headwise, same running
+ * estimates (mesa_update_running_params).  Two codes per byte: element e in byte e/2, the low four bits for even e;
+ * q4 holds (numel + 1) / 2 bytes (16-byte aligned; with an odd numel the last byte's high bits are zero).
+ * mesa_gelu_bwd_q_b4: dx = dy * gelu'(x_hat) at that reconstruction; dx may alias dy.
+ */
+mesa_status mesa_quantize_headwise_b4(const void *x, mesa_dtype dt, mesa_layout L,
+                                      const float *alpha, const float *beta, uint8_t *q4,
+                                      mesa_round mode, uint64_t seed, uint64_t offset, void *stream);
+mesa_status mesa_dequantize_b4(const uint8_t *q4, mesa_layout L, const float *alpha, const float *beta,
+                               void *x_hat, mesa_dtype dt, void *stream);
+mesa_status mesa_gelu_bwd_q_b4(const uint8_t *q4, mesa_layout L, const float *alpha, const float *beta,
+                               const void *dy, void *dx, mesa_dtype dt, void *stream);
+
+/*
  * Softmax backward at the de-quantized output, Sec. 3.1 Eq. (2) with G_l = softmax's gradient.
  * The saved tensor is the softmax OUTPUT y (the attention map), shape (B, H, rows, cols),
  * head-wise parameters alpha[H], beta[H].  Per row:  d = sum_j dy_j*y_hat_j,

@@ -450,6 +450,84 @@ int mesa_ref_quantize_headwise(const void *x, int dt, int64_t outer, int64_t gro
 }
 
 /*
+ * Four-bit codes (Sec. 4.2 names lower bit widths as the step beyond the method's fixed 8 bits): Eq. (3)-(5) with
+ * 2^b - 1 = 15 steps across the clipping range,
+ *   x_bar = clip(round((x - beta) * (15 / alpha)), 0, 15),    x_hat = x_bar * (alpha / 15) + beta,
+ * the same binary32 operation sequence and the same random fractions as the 8-bit quantizer.  Two codes share a
+ * byte: element e sits in byte e / 2, in the low four bits when e is even, the high four when it is odd; with an odd
+ * number of elements the last byte's high bits are zero.  q4 holds (numel + 1) / 2 bytes.
+ */
+int mesa_ref_quantize_headwise_b4(const void *x, int dt, int64_t outer, int64_t groups, int64_t inner,
+                                  const float *alpha, const float *beta, uint8_t *q4,
+                                  int mode, uint64_t seed, uint64_t offset)
+{
+    if (outer <= 0 || groups <= 0 || inner <= 0) return 0;
+    int64_t numel = outer * groups * inner;
+    memset(q4, 0, (size_t)((numel + 1) / 2));
+    for (int64_t e = 0; e < numel; ++e) {
+        int64_t g = (e / inner) % groups;
+        float a = alpha[g];
+        float b = beta[g];
+        float r = (a > 0.0f) ? 15.0f / a : 0.0f;
+        float xv = load_as_float(x, dt, e);
+        float t = xv - b;
+        float v = t * r;
+        float w;
+        if (mode == 0) {
+            w = rintf(v);
+        } else {
+            float u = mesa_ref_sr_uniform(seed, offset, (uint64_t)e);
+            float s = v + u;
+            w = floorf(s);
+        }
+        if (w < 0.0f) w = 0.0f;
+        if (w > 15.0f) w = 15.0f;
+        unsigned code = (unsigned)(int)w;
+        q4[e / 2] = (uint8_t)(q4[e / 2] | (code << (4 * (e & 1))));
+    }
+    return 0;
+}
+
+static float dequant_one_b4(const uint8_t *q4, int64_t e, float step, float b)
+{
+    unsigned code = (q4[e / 2] >> (4 * (e & 1))) & 0xFu;
+    float xh = (float)code * step;
+    xh = xh + b;
+    return xh;
+}
+
+int mesa_ref_dequantize_b4(const uint8_t *q4, int64_t outer, int64_t groups, int64_t inner,
+                           const float *alpha, const float *beta, void *x_hat, int dt)
+{
+    if (outer <= 0 || groups <= 0 || inner <= 0) return 0;
+    int64_t numel = outer * groups * inner;
+    for (int64_t e = 0; e < numel; ++e) {
+        int64_t g = (e / inner) % groups;
+        float xh = dequant_one_b4(q4, e, alpha[g] / 15.0f, beta[g]);
+        if (dt == 0) ((float *)x_hat)[e] = xh;
+        else if (dt == 2) ((uint16_t *)x_hat)[e] = mesa_ref_float_to_bf16(xh);
+        else ((uint16_t *)x_hat)[e] = mesa_ref_float_to_half(xh);
+    }
+    return 0;
+}
+
+/* GELU backward at the four-bit x_hat: the formula of mesa_ref_gelu_bwd_q, binary64, at the binary32 x_hat above */
+int mesa_ref_gelu_bwd_q_b4(const uint8_t *q4, int64_t outer, int64_t groups, int64_t inner,
+                           const float *alpha, const float *beta, const void *dy, int dt, double *dx)
+{
+    if (outer <= 0 || groups <= 0 || inner <= 0) return 0;
+    int64_t numel = outer * groups * inner;
+    for (int64_t e = 0; e < numel; ++e) {
+        int64_t g = (e / inner) % groups;
+        double xh = (double)dequant_one_b4(q4, e, alpha[g] / 15.0f, beta[g]);
+        double cdf = 0.5 * (1.0 + erf(xh / sqrt(2.0)));
+        double pdf = exp(-0.5 * xh * xh) / sqrt(2.0 * 3.14159265358979323846);
+        dx[e] = load_as_double(dy, dt, e) * (cdf + xh * pdf);
+    }
+    return 0;
+}
+
+/*
  * Single-pass forward (a variant of the method, not the order the paper implies
  * in Sec. 5.1, where the first iteration's statistics initialise the
  * parameters it quantizes with): the codes are taken with the running

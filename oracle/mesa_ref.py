@@ -192,6 +192,49 @@ def gelu_fwd_q(x, layout, alpha, beta, lam, mode=ROUND_NEAREST, seed=0, offset=0
     return y.reshape(x.shape), q.reshape(x.shape), a, b
 
 
+def quantize_headwise_b4(x, layout, alpha, beta, mode=ROUND_NEAREST, seed=0, offset=0):
+    """Four-bit codes, two per byte (element e in byte e // 2, low nibble for even e); returns uint8[(numel + 1) // 2]."""
+    outer, groups, inner = layout
+    x = _c(x)
+    n = outer * groups * inner
+    assert x.size == n
+    a = _c(alpha, np.float32)
+    b = _c(beta, np.float32)
+    q4 = np.empty((n + 1) // 2, np.uint8)
+    lib().mesa_ref_quantize_headwise_b4(_p(x), _dt(x), I64(outer), I64(groups), I64(inner), _p(a), _p(b), _p(q4), C.c_int(mode),
+                                        C.c_uint64(seed), C.c_uint64(offset))
+    return q4
+
+
+def dequantize_b4(q4, layout, alpha, beta, dtype=np.float32):
+    outer, groups, inner = layout
+    n = outer * groups * inner
+    q4 = _c(q4, np.uint8)
+    assert q4.size == (n + 1) // 2
+    a = _c(alpha, np.float32)
+    b = _c(beta, np.float32)
+    if isinstance(dtype, str) and dtype == "bf16":
+        out = np.empty(n, np.uint16)
+        lib().mesa_ref_dequantize_b4(_p(q4), I64(outer), I64(groups), I64(inner), _p(a), _p(b), _p(out), BF16)
+        return out
+    out = np.empty(n, dtype)
+    lib().mesa_ref_dequantize_b4(_p(q4), I64(outer), I64(groups), I64(inner), _p(a), _p(b), _p(out), _dt(out))
+    return out
+
+
+def gelu_bwd_q_b4(q4, layout, alpha, beta, dy):
+    outer, groups, inner = layout
+    n = outer * groups * inner
+    q4 = _c(q4, np.uint8)
+    dy = _c(dy)
+    assert q4.size == (n + 1) // 2 and dy.size == n
+    a = _c(alpha, np.float32)
+    b = _c(beta, np.float32)
+    dx = np.empty(n, np.float64)
+    lib().mesa_ref_gelu_bwd_q_b4(_p(q4), I64(outer), I64(groups), I64(inner), _p(a), _p(b), _p(dy), _dt(dy), _p(dx))
+    return dx
+
+
 def update_running_scale_sym(x, layout, m, lam, first_call):
     """Scale-only symmetric scheme: the running estimate of max |x| per group; returns the new m."""
     outer, groups, inner = layout

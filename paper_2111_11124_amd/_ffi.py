@@ -20,7 +20,7 @@ ROUND_NEAREST_EVEN, ROUND_STOCHASTIC = 0, 1
 OP_UPDATE_RUNNING_PARAMS, OP_LAYERNORM_BWD_Q, OP_LINEAR_DW_Q, OP_SOFTMAX_FWD_Q, OP_LAYERNORM_FWD_Q = 0, 1, 2, 3, 4
 
 EXPORTS = [
-    "mesa_update_running_params", "mesa_update_running_params_sym", "mesa_update_running_params_fixed_beta", "mesa_update_running_scale_sym", "mesa_quantize_sym", "mesa_dequantize_sym", "mesa_update_running_params_static", "mesa_static_scratch_bytes", "mesa_quantize_headwise", "mesa_quantize_update_fused", "mesa_gelu_fwd_q", "mesa_softmax_fwd_q", "mesa_layernorm_fwd_q", "mesa_dequantize", "mesa_softmax_bwd_q",
+    "mesa_update_running_params", "mesa_update_running_params_sym", "mesa_update_running_params_fixed_beta", "mesa_update_running_scale_sym", "mesa_quantize_sym", "mesa_dequantize_sym", "mesa_update_running_params_static", "mesa_static_scratch_bytes", "mesa_quantize_headwise", "mesa_quantize_update_fused", "mesa_gelu_fwd_q", "mesa_softmax_fwd_q", "mesa_layernorm_fwd_q", "mesa_dequantize", "mesa_quantize_headwise_b4", "mesa_dequantize_b4", "mesa_gelu_bwd_q_b4", "mesa_softmax_bwd_q",
     "mesa_gelu_bwd_q", "mesa_relu_bwd_q", "mesa_layernorm_bwd_q", "mesa_linear_dw_q", "mesa_attn_av_bwd_q", "mesa_attn_qk_bwd_q",
     "mesa_workspace_bytes",
     "mesa_status_string", "mesa_version", "mesa_stream_copy", "mesa_stream_read", "mesa_stream_fill", "mesa_event_create", "mesa_event_record",
@@ -65,6 +65,9 @@ def lib() -> C.CDLL:
         L.mesa_layernorm_fwd_q.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _vp, _vp, _f32, _vp, _vp, _vp, _vp, _int, _u64, _u64,
                                            _vp, _sz, _int, _vp]
         L.mesa_dequantize.argtypes = [_vp, Layout, _vp, _vp, _vp, _int, _vp]
+        L.mesa_quantize_headwise_b4.argtypes = L.mesa_quantize_headwise.argtypes
+        L.mesa_dequantize_b4.argtypes = L.mesa_dequantize.argtypes
+        L.mesa_gelu_bwd_q_b4.argtypes = [_vp, Layout, _vp, _vp, _vp, _vp, _int, _vp]
         L.mesa_softmax_bwd_q.argtypes = [_vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _int, _vp]
         L.mesa_gelu_bwd_q.argtypes = [_vp, Layout, _vp, _vp, _vp, _vp, _int, _vp]
         L.mesa_relu_bwd_q.argtypes = L.mesa_gelu_bwd_q.argtypes
@@ -217,6 +220,22 @@ def mesa_layernorm_fwd_q(x, M, D, G, gamma, bias, eps, alpha, beta, lam, y, mean
 def mesa_dequantize(q, layout, alpha, beta, x_hat):
     _check(lib().mesa_dequantize(_ptr(q), Layout(*layout), _ptr(alpha), _ptr(beta), _ptr(x_hat), _dt(x_hat), _stream()),
            "mesa_dequantize")
+
+
+def mesa_quantize_headwise_b4(x, layout, alpha, beta, q4, mode=ROUND_STOCHASTIC, seed=0, offset=0):
+    _check(lib().mesa_quantize_headwise_b4(_ptr(x), _dt(x), Layout(*layout), _ptr(alpha), _ptr(beta), _ptr(q4), int(mode),
+                                           int(seed), int(offset), _stream()), "mesa_quantize_headwise_b4")
+
+
+def mesa_dequantize_b4(q4, layout, alpha, beta, x_hat):
+    _check(lib().mesa_dequantize_b4(_ptr(q4), Layout(*layout), _ptr(alpha), _ptr(beta), _ptr(x_hat), _dt(x_hat), _stream()),
+           "mesa_dequantize_b4")
+
+
+def mesa_gelu_bwd_q_b4(q4, layout, alpha, beta, dy, dx):
+    assert dx.dtype == dy.dtype
+    _check(lib().mesa_gelu_bwd_q_b4(_ptr(q4), Layout(*layout), _ptr(alpha), _ptr(beta), _ptr(dy), _ptr(dx), _dt(dy), _stream()),
+           "mesa_gelu_bwd_q_b4")
 
 
 def mesa_softmax_bwd_q(yq, B, H, rows, cols, alpha, beta, dy, dx):

@@ -794,3 +794,43 @@ def test_scale_only_symmetric_scheme_is_bit_exact(M, layout, dtype):
     xa = R.dequantize(rq, layout, npy(a_eq), npy(b_eq), np.float32).astype(np.float64)
     xsym = R.dequantize_sym(rq, layout, rm, np.float32).astype(np.float64)
     assert np.abs(xa - xsym).max() <= 4e-6 * max(float(rm.max()), 1e-30)
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=DTYPE_IDS)
+@pytest.mark.parametrize("layout", [(3, 4, 1000), (5, 3, 361), (37, 6, 64), (1, 1, 12345), (7, 5, 3), (1, 1, 5), (3000, 12, 256),
+                                    (3, 2000, 40)])
+def test_four_bit_codes_are_bit_exact(M, layout, dtype):
+    """Four-bit codes (fifteen steps, two codes per byte): packed codes in both rounding modes and the de-quantized
+    values bit for bit against the oracle -- odd element counts, slabs shorter than a vector, nibble pairs that
+    straddle groups, more groups than the gradient table holds -- and the GELU backward within tolerance."""
+    outer, G, inner = layout
+    n = outer * G * inner
+    gen = torch.Generator(device="cuda").manual_seed(n + 11)
+    scale = (0.3 + 3.0 * torch.rand((1, G, 1), generator=gen, device="cuda"))
+    xs = [((torch.randn((outer, G, inner), generator=gen, device="cuda") * scale) + 0.2 * i).to(dtype).contiguous() for i in range(2)]
+    a, b, ra, rb = run_params(M, xs, layout)
+    x = xs[-1]
+    nb = (n + 1) // 2
+    for mode, seed, off in ((M.ROUND_NEAREST_EVEN, 0, 0), (M.ROUND_STOCHASTIC, 0xFEED5EED, (1 << 33) + 5)):
+        q4 = torch.full((nb + 16,), 0xAB, dtype=torch.uint8, device="cuda")     # sentinel bytes behind the codes
+        M.mesa_quantize_headwise_b4(x, layout, a, b, q4, mode, seed, off)
+        rq4 = R.quantize_headwise_b4(npy(x), layout, ra, rb, mode, seed, off)
+        got = q4.cpu().numpy()
+        bad = np.nonzero(got[:nb] != rq4)[0]
+        assert bad.size == 0, (mode, bad[:10], got[bad[:10]], rq4[bad[:10]])
+        assert np.all(got[nb:] == 0xAB)
+    q4 = q4[:nb].clone()
+    for odt, npo, u in ((torch.float32, np.float32, np.uint32), (torch.float16, np.float16, np.uint16)):
+        out = torch.empty(n, dtype=odt, device="cuda")
+        M.mesa_dequantize_b4(q4, layout, a, b, out)
+        assert np.array_equal(npy(out).view(u), R.dequantize_b4(rq4, layout, ra, rb, npo).view(u))
+    out = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    M.mesa_dequantize_b4(q4, layout, a, b, out)
+    assert np.array_equal(out.view(torch.int16).cpu().numpy().view(np.uint16), R.dequantize_b4(rq4, layout, ra, rb, "bf16"))
+    dy = torch.randn((outer, G, inner), generator=gen, device="cuda").to(dtype)
+    dx = torch.empty_like(dy)
+    M.mesa_gelu_bwd_q_b4(q4, layout, a, b, dy, dx)
+    ref = R.gelu_bwd_q_b4(rq4, layout, ra, rb, npy(dy))
+    assert relerr(npy(dx).reshape(-1), ref) <= TOL[dtype]
+    M.mesa_gelu_bwd_q_b4(q4, layout, a, b, dy, dy)          # in place
+    assert torch.equal(dy, dx)
