@@ -496,6 +496,36 @@ def symmetric_leg(m, spec, steps):
                     "against mesa_update_running_params + mesa_quantize_headwise; both read x twice and write one byte per element"}
 
 
+def four_bit_leg(m, spec, steps):
+    """Outside the headline figure: the lower bit width of the ablation (Sec. 5.3) on the configuration's GELU input --
+    quantize to four-bit codes (two per byte) and GELU backward from them, next to the eight-bit calls."""
+    lay = spec.gelu_layout
+    n = lay[0] * lay[1] * lay[2]
+    dev = "cuda"
+    esz = elem_bytes(spec.dtype)
+    ns = max(3, min(LEG_SETS, int(math.ceil(600e6 / ((2 * esz + 1) * n))) + 1))
+    g = torch.Generator(device=dev).manual_seed(spec.seed + 7)
+    xs = [W._randn(lay, g, spec.dtype, dev) for _ in range(ns)]
+    dys = [W._randn(lay, g, spec.dtype, dev) for _ in range(ns)]
+    q8 = [torch.empty(n, dtype=torch.int8, device=dev) for _ in range(ns)]
+    q4 = [torch.empty((n + 1) // 2, dtype=torch.uint8, device=dev) for _ in range(ns)]
+    a = torch.zeros(lay[1], device=dev)
+    b = torch.zeros(lay[1], device=dev)
+    ws = torch.empty(max(m.workspace_bytes(m.OP_UPDATE_RUNNING_PARAMS, *lay, dtype_code(m, spec.dtype)), 16), dtype=torch.uint8, device=dev)
+    m.mesa_update_running_params(xs[0], lay, a, b, 0.9, True, ws)
+    for k in range(ns):
+        m.mesa_quantize_headwise(xs[k], lay, a, b, q8[k], m.ROUND_STOCHASTIC, 1, k)
+        m.mesa_quantize_headwise_b4(xs[k], lay, a, b, q4[k], m.ROUND_STOCHASTIC, 1, k)
+    t = {"quantize_b8": timed_leg(lambda i: m.mesa_quantize_headwise(xs[i % ns], lay, a, b, q8[i % ns], m.ROUND_STOCHASTIC, 1, i), steps),
+         "quantize_b4": timed_leg(lambda i: m.mesa_quantize_headwise_b4(xs[i % ns], lay, a, b, q4[i % ns], m.ROUND_STOCHASTIC, 1, i), steps),
+         "gelu_bwd_b8": timed_leg(lambda i: m.mesa_gelu_bwd_q(q8[i % ns], lay, a, b, dys[i % ns], dys[i % ns]), steps),
+         "gelu_bwd_b4": timed_leg(lambda i: m.mesa_gelu_bwd_q_b4(q4[i % ns], lay, a, b, dys[i % ns], dys[i % ns]), steps)}
+    nb = {"quantize_b8": (esz + 1) * n, "quantize_b4": esz * n + (n + 1) // 2,
+          "gelu_bwd_b8": (2 * esz + 1) * n, "gelu_bwd_b4": 2 * esz * n + (n + 1) // 2}
+    return {k: {"ms": round(v, 5), "bytes": nb[k], "GBps": round(nb[k] / (v * 1e-3) / 1e9, 1),
+                "frac_hbm": round(nb[k] / (v * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)} for k, v in t.items()}
+
+
 def bandwidth_probes(m):
     """Untimed extras: what plain kernels reach on this GPU -- a copy (the known-traffic kernel the bandwidth counters are
     scaled against), a read-only and a write-only stream, 256 MiB each, three rotating buffers, median of event pairs."""
@@ -549,7 +579,17 @@ def dw_only(m, spec, steps):
         fl = 2.0 * spec.tokens * K * N
         out[f"{K}->{N}"] = {"ms": round(ms, 5), "tflops": round(fl / (ms * 1e-3) / 1e12, 1),
                             "mfma_frac": round(fl / (ms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4), "shape": [spec.tokens, K, N]}
-        del qs, dys
+        # context, not part of the path: the vendor library's GEMM (through torch.matmul) on the same shape with the
+        # activation already de-quantized to 16-bit floats in memory -- what this GPU sustains on this contraction without
+        # the conversion of the codes in the loop
+        xh = [torch.empty((spec.tokens, K), dtype=spec.dtype, device=dev) for _ in range(3)]
+        for k in range(3):
+            m.mesa_dequantize(qs[k].view(-1), (spec.tokens, H, K // H), a, b, xh[k])
+        lib_out = torch.empty((N, K), dtype=spec.dtype, device=dev)
+        lib_ms = timed_leg(lambda i: torch.matmul(dys[i % 3].t(), xh[i % 3], out=lib_out), steps)
+        out[f"{K}->{N}"]["library_gemm_16bit_operands"] = {"ms": round(lib_ms, 5), "tflops": round(fl / (lib_ms * 1e-3) / 1e12, 1),
+                                                          "mfma_frac": round(fl / (lib_ms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4)}
+        del qs, dys, xh, lib_out
     return out
 
 
@@ -701,6 +741,7 @@ def main():
         out["attention_matmul_bwd"] = attention_matmul_leg(m, spec, leg_steps) if number != 5 else None
         out.update(layer_forward_legs(m, spec, leg_steps))
         out["symmetric_scale_only_forward"] = symmetric_leg(m, spec, leg_steps)
+        out["four_bit_codes"] = four_bit_leg(m, spec, leg_steps)
     if not args.no_cpu_baseline and number in (2, HEADLINE_CONFIG):
         # the oracle reads binary16 or binary32 arrays: for bfloat16 runs it is timed on the binary16 workload (same bytes)
         out["cpu_baseline"] = cpu_baseline(dataclasses.replace(spec, dtype=torch.float16), number)

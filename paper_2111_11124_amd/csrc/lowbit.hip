@@ -45,13 +45,23 @@ __device__ __forceinline__ void b4_table(float2 *tab, const float *alpha, const 
     __syncthreads();
 }
 
-// eight integers (as floats, any range) -> eight four-bit codes in one word, element j in bits 4j .. 4j+3
+// eight integers (as floats, any range) -> eight four-bit codes in one word, element j in bits 4j .. 4j+3.
+// Four clipped values are summed with weights 1, 16, 256, 4096 in binary32 (exact: the sum stays below 2^16), so a
+// half-word costs four clamps, three multiply-adds and one conversion.
 __device__ __forceinline__ uint32_t pack_nibbles(const float w[8])
 {
-    uint32_t out = 0u;
+    uint32_t half[2];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) out |= uint32_t(fminf(fmaxf(w[j], 0.0f), 15.0f)) << (4 * j);
-    return out;
+    for (int k = 0; k < 2; ++k) {
+        float c[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) c[j] = __builtin_amdgcn_fmed3f(w[4 * k + j], 0.0f, 15.0f);
+        float s = fmaf(c[3], 16.0f, c[2]);
+        s = fmaf(s, 16.0f, c[1]);
+        s = fmaf(s, 16.0f, c[0]);
+        half[k] = uint32_t(s);
+    }
+    return half[0] | (half[1] << 16);
 }
 
 template <typename T, bool SR>
@@ -62,40 +72,50 @@ __global__ __launch_bounds__(kThreads) void k_quantize_b4(const void *__restrict
     extern __shared__ float2 b4_tab[];
     b4_table<true>(b4_tab, alpha, beta, gg.groups);
     const bool small = numel < (int64_t(1) << 31);
-    const int64_t nvec = (numel + kVec - 1) / kVec;
-    for (int64_t v = int64_t(blockIdx.x) * kThreads + threadIdx.x; v < nvec; v += int64_t(gridDim.x) * kThreads) {
+    const int64_t nfull = numel / kVec;
+    const int64_t stride = int64_t(gridDim.x) * kThreads;
+    int64_t v = int64_t(blockIdx.x) * kThreads + threadIdx.x;
+    // the next vector's load is in flight while this one's random bits and codes are computed
+    decltype(Nt<T>::load(x, 0)) nxt = {};
+    if (v < nfull) nxt = Nt<T>::load(x, v * kVec);
+    for (; v < nfull; v += stride) {
+        const auto raw = nxt;
+        if (v + stride < nfull) nxt = Nt<T>::load(x, (v + stride) * kVec);
         const int64_t e = v * kVec;
         const Cursor c = b4_cursor(e, gg, small);
-        float bits[8], w[8];
+        float bits[8], w[8], f[8];
         if (SR) sr_bits(seed, offset + uint64_t(v), bits);
-        if (e + kVec <= numel) {
-            float f[8];
-            Store<T>::unpack(Nt<T>::load(x, e), f);
-            if (c.rem + kVec <= gg.inner) {
-                const float2 p = b4_tab[c.g];
+        Store<T>::unpack(raw, f);
+        if (c.rem + kVec <= gg.inner) {
+            const float2 p = b4_tab[c.g];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) w[j] = quantize_one<SR>(f[j], p.x, p.y, SR ? bits[j] : 0.0f);
-            } else {
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const float2 p = b4_tab[group_of(c, j, gg)];
-                    w[j] = quantize_one<SR>(f[j], p.x, p.y, SR ? bits[j] : 0.0f);
-                }
-            }
-            nt_store<uint32_t>(q4 + (e >> 1), pack_nibbles(w));
-        } else {   // the ragged end of the tensor, one thread of the launch: whole bytes, the odd last code's partner zero
-            const int cnt = int(numel - e);
+            for (int j = 0; j < 8; ++j) w[j] = quantize_one<SR>(f[j], p.x, p.y, SR ? bits[j] : 0.0f);
+        } else {
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                w[j] = 0.0f;
-                if (j < cnt) {
-                    const float2 p = b4_tab[group_of(c, j, gg)];
-                    w[j] = quantize_one<SR>(Store<T>::load1(x, e + j), p.x, p.y, SR ? bits[j] : 0.0f);
-                }
+                const float2 p = b4_tab[group_of(c, j, gg)];
+                w[j] = quantize_one<SR>(f[j], p.x, p.y, SR ? bits[j] : 0.0f);
             }
-            const uint32_t word = pack_nibbles(w);
-            for (int k = 0; 2 * k < cnt; ++k) q4[(e >> 1) + k] = uint8_t(word >> (8 * k));
         }
+        nt_store<uint32_t>(q4 + (e >> 1), pack_nibbles(w));
+    }
+    // the ragged end of the tensor, one thread of the launch: whole bytes, the odd last code's partner zero
+    const int cnt = int(numel - nfull * kVec);
+    if (cnt > 0 && blockIdx.x == 0 && threadIdx.x == 0) {
+        const int64_t e = nfull * kVec;
+        const Cursor c = b4_cursor(e, gg, small);
+        float bits[8], w[8];
+        if (SR) sr_bits(seed, offset + uint64_t(nfull), bits);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            w[j] = 0.0f;
+            if (j < cnt) {
+                const float2 p = b4_tab[group_of(c, j, gg)];
+                w[j] = quantize_one<SR>(Store<T>::load1(x, e + j), p.x, p.y, SR ? bits[j] : 0.0f);
+            }
+        }
+        const uint32_t word = pack_nibbles(w);
+        for (int k = 0; 2 * k < cnt; ++k) q4[(e >> 1) + k] = uint8_t(word >> (8 * k));
     }
 }
 

@@ -24,6 +24,9 @@ int mesa_ref_quantize_update_fused(const void *x, int dt, int64_t outer, int64_t
 int mesa_ref_gelu_fwd_q(const void *x, int dt, int64_t outer, int64_t groups, int64_t inner, float *alpha, float *beta, float lambda, double *y, int8_t *q, int mode, uint64_t seed, uint64_t offset);
 int mesa_ref_dequantize(const int8_t *q, int64_t outer, int64_t groups, int64_t inner, const float *alpha, const float *beta, void *x_hat, int dt);
 int mesa_ref_dequantize_sym(const int8_t *q, int64_t outer, int64_t groups, int64_t inner, const float *m, void *x_hat, int dt);
+int mesa_ref_quantize_headwise_b4(const void *x, int dt, int64_t outer, int64_t groups, int64_t inner, const float *alpha, const float *beta, uint8_t *q4, int mode, uint64_t seed, uint64_t offset);
+int mesa_ref_dequantize_b4(const uint8_t *q4, int64_t outer, int64_t groups, int64_t inner, const float *alpha, const float *beta, void *x_hat, int dt);
+int mesa_ref_gelu_bwd_q_b4(const uint8_t *q4, int64_t outer, int64_t groups, int64_t inner, const float *alpha, const float *beta, const void *dy, int dt, double *dx);
 int mesa_ref_softmax_fwd(const void *s, int dt, int64_t total_rows, int64_t cols, double *y);
 int mesa_ref_layernorm_fwd(const void *x, int dt, int64_t M, int64_t D, const void *gamma, const void *bias, double eps, double *y, double *mean, double *rstd);
 int mesa_ref_softmax_bwd_q(const int8_t *yq, int64_t B, int64_t H, int64_t rows, int64_t cols, const float *alpha, const float *beta, const void *dy, int dt, double *dx);
@@ -88,6 +91,15 @@ int main(void)
             mesa_ref_quantize_update_fused(x, dt, outer, G, inner, a, b, 0.9f, q, mode, 3, 5);
             mesa_ref_gelu_fwd_q(x, dt, outer, G, inner, a, b, 0.9f, d64, q, mode, 3, 5);
         }
+        /* four-bit codes: n is odd, so the last byte holds one code */
+        uint8_t *q4 = NEW(uint8_t, (n + 1) / 2);
+        for (int mode = 0; mode < 2; ++mode) {
+            mesa_ref_quantize_headwise_b4(x, dt, outer, G, inner, a, b, q4, mode, 9, 1ull << 33);
+            mesa_ref_dequantize_b4(q4, outer, G, inner, a, b, xh, dt);
+            mesa_ref_gelu_bwd_q_b4(q4, outer, G, inner, a, b, dy, dt, d64);
+        }
+        acc += d64[n - 1];
+        free(q4);
         mesa_ref_dequantize(q, outer, G, inner, a, b, xh, dt);
         mesa_ref_gelu_bwd_q(q, outer, G, inner, a, b, dy, dt, d64);
         mesa_ref_relu_bwd_q(q, outer, G, inner, a, b, dy, dt, d64);

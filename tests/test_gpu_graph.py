@@ -157,3 +157,52 @@ def test_captured_layer_forwards_and_the_remaining_backwards_replay_exactly(M):
         for k, ref in eager[t].items():
             got = st[k] if k in st else buf[k]
             assert torch.equal(got, ref), (t, k)
+
+
+def test_captured_scale_only_four_bit_and_static_scratch_calls_replay_exactly(M):
+    """The later additions: the scale-only symmetric trio, the four-bit trio and the update that keeps its partial
+    extrema in the library's own static array (whose contents survive from replay to replay)."""
+    dev = "cuda"
+    Mr, H, mlp = 197 * 3, 3, 384
+    g = torch.Generator(device=dev).manual_seed(21)
+    x = (torch.randn((Mr, mlp), device=dev, generator=g) * 1.5).half()
+    dy = torch.randn((Mr, mlp), device=dev, generator=g).half()
+    lay = (Mr, H, mlp // H)
+    n = x.numel()
+    init = {"m": torch.full((H,), 5.0, device=dev), "a": torch.full((H,), 6.0, device=dev), "b": torch.full((H,), -3.0, device=dev)}
+    st = {k: v.clone() for k, v in init.items()}
+    buf = {"qs": torch.empty(n, dtype=torch.int8, device=dev), "xs": torch.empty_like(x),
+           "q4": torch.empty((n + 1) // 2, dtype=torch.uint8, device=dev), "x4": torch.empty_like(x), "dx4": torch.empty_like(dy)}
+    w = ws(M, M.OP_UPDATE_RUNNING_PARAMS, *lay)
+
+    def step():
+        M.mesa_update_running_scale_sym(x, lay, st["m"], 0.9, False, w)
+        M.mesa_quantize_sym(x, lay, st["m"], buf["qs"], M.ROUND_STOCHASTIC, 11, 0)
+        M.mesa_dequantize_sym(buf["qs"], lay, st["m"], buf["xs"])
+        M.mesa_update_running_params_static(x, lay, st["a"], st["b"], 0.9, False)
+        M.mesa_quantize_headwise_b4(x, lay, st["a"], st["b"], buf["q4"], M.ROUND_STOCHASTIC, 12, 0)
+        M.mesa_dequantize_b4(buf["q4"], lay, st["a"], st["b"], buf["x4"])
+        M.mesa_gelu_bwd_q_b4(buf["q4"], lay, st["a"], st["b"], dy, buf["dx4"])
+
+    eager = []
+    for _ in range(3):
+        step()
+        torch.cuda.synchronize()
+        eager.append({k: v.clone() for k, v in list(st.items()) + list(buf.items())})
+    for k in st:
+        st[k].copy_(init[k])
+    for v in buf.values():
+        v.zero_()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    other = (torch.randn((64, H, 40), device=dev, generator=g)).half()
+    oa, ob = torch.zeros(H, device=dev), torch.zeros(H, device=dev)
+    for t in range(3):
+        graph.replay()
+        M.mesa_update_running_params_static(other, (64, H, 40), oa, ob, 0.9, True)   # eager work that dirties the static array
+        torch.cuda.synchronize()
+        for k, ref in eager[t].items():
+            got = st[k] if k in st else buf[k]
+            assert torch.equal(got, ref), (t, k)
