@@ -841,6 +841,93 @@ int mesa_ref_linear_dw_q_entries(const int8_t *xq, int64_t M, int64_t K, int64_t
 }
 
 /*
+ * Weight gradient of a two-dimensional convolution at the de-quantized input (Eq. (2) with G_l the gradient of a
+ * convolution; Sec. 3.3 covers the convolutional layer with the group-wise scheme, the input's channels split into
+ * G groups of C_in / G consecutive channels, one (alpha, beta) pair each).  Tensors are contiguous, channels-first:
+ *   xq (B, C_in, H, W) codes,   dy (B, C_out, OH, OW),   dW (C_out, C_in, KH, KW),   db [C_out]
+ *   OH = (H + 2*pad_h - dil_h*(KH-1) - 1) / stride_h + 1,  OW likewise
+ *   dW[co, ci, kh, kw] = sum over b, oh, ow of dy[b, co, oh, ow] * x_hat[b, ci, oh*stride_h - pad_h + kh*dil_h,
+ *                                                                             ow*stride_w - pad_w + kw*dil_w]
+ * where a position outside the image contributes nothing: the forward pads with zeros, not with de-quantized codes.
+ * geom: {B, C_in, H, W, C_out, KH, KW, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w}.
+ */
+static int conv_out_extent(int64_t in, int64_t k, int64_t stride, int64_t pad, int64_t dil, int64_t *out)
+{
+    int64_t span = in + 2 * pad - dil * (k - 1) - 1;
+    if (in <= 0 || k <= 0 || stride <= 0 || pad < 0 || dil <= 0 || span < 0) return 1;
+    *out = span / stride + 1;
+    return 0;
+}
+
+static double conv_dw_entry(const int8_t *xq, const int64_t *geom, int64_t OH, int64_t OW, int64_t per,
+                            const float *alpha, const float *beta, const void *dy, int dt,
+                            int64_t co, int64_t ci, int64_t kh, int64_t kw)
+{
+    int64_t B = geom[0], Cin = geom[1], H = geom[2], W = geom[3], Cout = geom[4];
+    int64_t sh = geom[7], sw = geom[8], ph = geom[9], pw = geom[10], dh = geom[11], dw = geom[12];
+    float step = alpha[ci / per] / 255.0f;
+    float off = beta[ci / per];
+    double acc = 0.0;
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t oh = 0; oh < OH; ++oh) {
+            int64_t ih = oh * sh - ph + kh * dh;
+            if (ih < 0 || ih >= H) continue;
+            for (int64_t ow = 0; ow < OW; ++ow) {
+                int64_t iw = ow * sw - pw + kw * dw;
+                if (iw < 0 || iw >= W) continue;
+                double g = load_as_double(dy, dt, ((b * Cout + co) * OH + oh) * OW + ow);
+                acc += g * (double)dequant_one(xq[((b * Cin + ci) * H + ih) * W + iw], step, off);
+            }
+        }
+    return acc;
+}
+
+int mesa_ref_conv2d_dw_q(const int8_t *xq, const int64_t *geom, int64_t G, const float *alpha, const float *beta,
+                         const void *dy, int dt, double *dW, double *db)
+{
+    int64_t B = geom[0], Cin = geom[1], Cout = geom[4], KH = geom[5], KW = geom[6], OH, OW;
+    if (B < 0 || Cin <= 0 || Cout <= 0 || G <= 0 || Cin % G != 0) return 1;
+    if (conv_out_extent(geom[2], KH, geom[7], geom[9], geom[11], &OH)) return 1;
+    if (conv_out_extent(geom[3], KW, geom[8], geom[10], geom[12], &OW)) return 1;
+    int64_t per = Cin / G;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t co = 0; co < Cout; ++co) {
+        for (int64_t ci = 0; ci < Cin; ++ci)
+            for (int64_t kh = 0; kh < KH; ++kh)
+                for (int64_t kw = 0; kw < KW; ++kw)
+                    dW[((co * Cin + ci) * KH + kh) * KW + kw] =
+                        conv_dw_entry(xq, geom, OH, OW, per, alpha, beta, dy, dt, co, ci, kh, kw);
+        if (db) {
+            double acc = 0.0;
+            for (int64_t b = 0; b < B; ++b)
+                for (int64_t p = 0; p < OH * OW; ++p) acc += load_as_double(dy, dt, (b * Cout + co) * OH * OW + p);
+            db[co] = acc;
+        }
+    }
+    return 0;
+}
+
+/* the same definition at a list of (co, ci, kh, kw) positions, idx[4*t .. 4*t+3], for sizes where the full
+   gradient is out of reach of a CPU */
+int mesa_ref_conv2d_dw_q_entries(const int8_t *xq, const int64_t *geom, int64_t G, const float *alpha, const float *beta,
+                                 const void *dy, int dt, const int64_t *idx, int64_t count, double *out)
+{
+    int64_t B = geom[0], Cin = geom[1], Cout = geom[4], KH = geom[5], KW = geom[6], OH, OW;
+    if (B < 0 || Cin <= 0 || Cout <= 0 || G <= 0 || Cin % G != 0) return 1;
+    if (conv_out_extent(geom[2], KH, geom[7], geom[9], geom[11], &OH)) return 1;
+    if (conv_out_extent(geom[3], KW, geom[8], geom[10], geom[12], &OW)) return 1;
+    int64_t per = Cin / G;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t t = 0; t < count; ++t)
+        out[t] = conv_dw_entry(xq, geom, OH, OW, per, alpha, beta, dy, dt, idx[4 * t], idx[4 * t + 1], idx[4 * t + 2], idx[4 * t + 3]);
+    return 0;
+}
+
+/*
  * The two matrix products of self-attention, backward, at the de-quantized
  * operands (Eq. (2) with G_l the gradient of a matrix product; the operands
  * are saved head-wise, Sec. 3.2: one (alpha, beta) pair per head for each of

@@ -421,3 +421,42 @@ def linear_dw_q_entries(xq, M, K, G, alpha, beta, dy, N_out, n_idx, k_idx):
                                             _dt(dy), _p(n_idx), _p(k_idx), I64(n_idx.size), _p(out))
     assert rc == 0
     return out
+
+
+def conv_geometry(B, C_in, H, W, C_out, KH, KW, stride=(1, 1), pad=(0, 0), dil=(1, 1)):
+    """the thirteen integers the convolution functions take, and the output extent they imply"""
+    geom = np.array([B, C_in, H, W, C_out, KH, KW, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1]], np.int64)
+    OH = (H + 2 * pad[0] - dil[0] * (KH - 1) - 1) // stride[0] + 1
+    OW = (W + 2 * pad[1] - dil[1] * (KW - 1) - 1) // stride[1] + 1
+    return geom, OH, OW
+
+
+def conv2d_dw_q(xq, geom, G, alpha, beta, dy):
+    """weight gradient of a convolution at the de-quantized input (Eq. 2; Sec. 3.3, convolutional layers):
+    (dW (C_out, C_in, KH, KW), db [C_out]) in binary64"""
+    xq = _c(xq, np.int8)
+    dy = _c(dy)
+    geom = _c(geom, np.int64)
+    a = _c(alpha, np.float32)
+    b = _c(beta, np.float32)
+    B, Cin, H, W, Cout, KH, KW = (int(v) for v in geom[:7])
+    assert xq.size == B * Cin * H * W
+    dW = np.empty((Cout, Cin, KH, KW), np.float64)
+    db = np.empty(Cout, np.float64)
+    rc = lib().mesa_ref_conv2d_dw_q(_p(xq), _p(geom), I64(G), _p(a), _p(b), _p(dy), _dt(dy), _p(dW), _p(db))
+    assert rc == 0
+    return dW, db
+
+
+def conv2d_dw_q_entries(xq, geom, G, alpha, beta, dy, idx):
+    """the same gradient at the (co, ci, kh, kw) rows of idx"""
+    xq = _c(xq, np.int8)
+    dy = _c(dy)
+    geom = _c(geom, np.int64)
+    idx = _c(idx, np.int64)
+    a = _c(alpha, np.float32)
+    b = _c(beta, np.float32)
+    out = np.empty(idx.size // 4, np.float64)
+    rc = lib().mesa_ref_conv2d_dw_q_entries(_p(xq), _p(geom), I64(G), _p(a), _p(b), _p(dy), _dt(dy), _p(idx), I64(idx.size // 4), _p(out))
+    assert rc == 0
+    return out

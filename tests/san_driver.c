@@ -35,6 +35,8 @@ int mesa_ref_relu_bwd_q(const int8_t *xq, int64_t outer, int64_t groups, int64_t
 int mesa_ref_layernorm_bwd_q(const int8_t *xq, int64_t M, int64_t D, int64_t G, const float *alpha, const float *beta, const float *mean, const float *rstd, const void *gamma, const void *dy, int dt, double *dx, double *dgamma, double *dbeta);
 int mesa_ref_linear_dw_q(const int8_t *xq, int64_t M, int64_t K, int64_t G, const float *alpha, const float *beta, const void *dy, int64_t N_out, int dt, double *dW, double *db);
 int mesa_ref_linear_dw_q_entries(const int8_t *xq, int64_t M, int64_t K, int64_t G, const float *alpha, const float *beta, const void *dy, int64_t N_out, int dt, const int64_t *n_idx, const int64_t *k_idx, int64_t count, double *out);
+int mesa_ref_conv2d_dw_q(const int8_t *xq, const int64_t *geom, int64_t G, const float *alpha, const float *beta, const void *dy, int dt, double *dW, double *db);
+int mesa_ref_conv2d_dw_q_entries(const int8_t *xq, const int64_t *geom, int64_t G, const float *alpha, const float *beta, const void *dy, int dt, const int64_t *idx, int64_t count, double *out);
 int mesa_ref_attn_av_bwd_q(const int8_t *aq, const int8_t *vq, int64_t B, int64_t H, int64_t N, int64_t Dh, const float *alpha_a, const float *beta_a, const float *alpha_v, const float *beta_v, const void *dO, int dt, double *dA, double *dV);
 int mesa_ref_attn_qk_bwd_q(const int8_t *qq, const int8_t *kq, int64_t B, int64_t H, int64_t N, int64_t Dh, const float *alpha_q, const float *beta_q, const float *alpha_k, const float *beta_k, const void *dS, int dt, double scale, double *dQ, double *dK);
 
@@ -135,6 +137,19 @@ int main(void)
         acc += dW[Nout * D - 1] + ent[2] + dg[D - 1] + dbt[0];
         free(t); free(gam); free(bias); free(dyt); free(dyl); free(y); free(mean); free(rstd); free(meanf); free(rstdf);
         free(ta); free(tb); free(tq); free(dx); free(dg); free(dbt); free(dW); free(db);
+
+        /* convolution weight gradient: stride, padding and dilation all in play; OH = 4, OW = 10 */
+        const int64_t geom[13] = {2, 4, 7, 9, 3, 3, 2, 2, 1, 1, 2, 1, 3};
+        int8_t *cq = NEW(int8_t, 2 * 4 * 7 * 9);
+        for (int64_t i = 0; i < 2 * 4 * 7 * 9; ++i) cq[i] = (int8_t)(i * 53 % 256 - 128);
+        void *cdy = make_x(dt, 2 * 3 * 4 * 10, 1.0f);
+        float ca[2] = {1.5f, 3.0f}, cb[2] = {-0.5f, 0.25f};
+        double *cdW = NEW(double, 3 * 4 * 3 * 2), *cdb = NEW(double, 3), cent[2];
+        int64_t cidx[8] = {0, 0, 0, 0, 2, 3, 2, 1};
+        mesa_ref_conv2d_dw_q(cq, geom, 2, ca, cb, cdy, dt, cdW, cdb);
+        mesa_ref_conv2d_dw_q_entries(cq, geom, 2, ca, cb, cdy, dt, cidx, 2, cent);
+        acc += cdW[3 * 4 * 3 * 2 - 1] + cdb[2] + cent[1];
+        free(cq); free(cdy); free(cdW); free(cdb);
 
         /* attention products */
         const int64_t B = 2, H = 2, N = 7, Dh = 5;
