@@ -320,6 +320,31 @@ mesa_status mesa_linear_dw_q(const int8_t *xq, int64_t M, int64_t K, int64_t G,
                              float *dW, float *db, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Weight gradient of a two-dimensional convolution at the de-quantized input, Eq. (2) with the gradient of a
+ * convolution as G_l (Sec. 3.3: convolutional layers take the group-wise scheme; the input's C_in channels form G
+ * groups of C_in / G consecutive channels, one (alpha, beta) pair each).  Contiguous channels-first tensors:
+ *   xq (B, C_in, H, W) int8,  dy (B, C_out, OH, OW) of dt,  dW (C_out, C_in, KH, KW) binary32,  db [C_out] binary32 or NULL
+ *   OH = (H + 2*pad_h - dil_h*(KH-1) - 1) / stride_h + 1,  OW likewise
+ *   dW[co,ci,kh,kw] = sum_{b,oh,ow} dy[b,co,oh,ow] * x_hat[b,ci, oh*stride_h - pad_h + kh*dil_h, ow*stride_w - pad_w + kw*dil_w]
+ *   db[co]          = sum_{b,oh,ow} dy[b,co,oh,ow]
+ * A position outside the image contributes nothing (the forward pads with zeros, not with de-quantized codes).
+ * dW and db are overwritten.  Fixed summation order.  ws: mesa_conv2d_dw_q_workspace_bytes(cv, dt) bytes.
+ * 16-bit tensors with stride_w = dil_w = 1, KH, KW <= 3, pad_w <= 8 and W, OW multiples of 8 run on the matrix cores
+ * (binary16 / bfloat16 products, binary32 sums, the contracted operand as in mesa_linear_dw_q); every other case
+ * runs a plain kernel, one thread per element of dW, summed in binary64.
+ * Errors: a kernel larger than the padded image, a zero stride or dilation, C_in % G != 0 -> MESA_ERR_INVALID_ARG;
+ * C_out*C_in*KH*KW, H*W or OH*OW >= 2^31 -> MESA_ERR_UNSUPPORTED.
+ */
+typedef struct mesa_conv2d {
+    int64_t B, C_in, H, W, C_out, KH, KW;
+    int64_t stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
+} mesa_conv2d;
+size_t mesa_conv2d_dw_q_workspace_bytes(mesa_conv2d cv, mesa_dtype dt);
+mesa_status mesa_conv2d_dw_q(const int8_t *xq, mesa_conv2d cv, int64_t G, const float *alpha, const float *beta,
+                             const void *dy, mesa_dtype dt, float *dW, float *db,
+                             void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Backward of the two matrix products of self-attention at head-wise de-quantized operands, Sec. 3.1
  * Eq. (2) with G_l = the gradient of a matrix product (the "MatMul" rows of the paper's overhead table;
  * Sec. 3.2: the operands are saved as codes with one (alpha, beta) pair per head).  All tensors are

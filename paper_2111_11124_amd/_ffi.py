@@ -21,7 +21,7 @@ OP_UPDATE_RUNNING_PARAMS, OP_LAYERNORM_BWD_Q, OP_LINEAR_DW_Q, OP_SOFTMAX_FWD_Q, 
 
 EXPORTS = [
     "mesa_update_running_params", "mesa_update_running_params_sym", "mesa_update_running_params_fixed_beta", "mesa_update_running_scale_sym", "mesa_quantize_sym", "mesa_dequantize_sym", "mesa_update_running_params_static", "mesa_static_scratch_bytes", "mesa_quantize_headwise", "mesa_quantize_update_fused", "mesa_gelu_fwd_q", "mesa_softmax_fwd_q", "mesa_layernorm_fwd_q", "mesa_dequantize", "mesa_quantize_headwise_b4", "mesa_dequantize_b4", "mesa_gelu_bwd_q_b4", "mesa_softmax_bwd_q",
-    "mesa_gelu_bwd_q", "mesa_relu_bwd_q", "mesa_layernorm_bwd_q", "mesa_linear_dw_q", "mesa_attn_av_bwd_q", "mesa_attn_qk_bwd_q",
+    "mesa_gelu_bwd_q", "mesa_relu_bwd_q", "mesa_layernorm_bwd_q", "mesa_linear_dw_q", "mesa_conv2d_dw_q", "mesa_conv2d_dw_q_workspace_bytes", "mesa_attn_av_bwd_q", "mesa_attn_qk_bwd_q",
     "mesa_workspace_bytes",
     "mesa_status_string", "mesa_version", "mesa_stream_copy", "mesa_stream_read", "mesa_stream_fill", "mesa_event_create", "mesa_event_record",
     "mesa_event_elapsed_ms", "mesa_event_destroy",
@@ -36,6 +36,16 @@ class MesaError(RuntimeError):
 
 class Layout(C.Structure):
     _fields_ = [("outer", C.c_int64), ("groups", C.c_int64), ("inner", C.c_int64)]
+
+
+class Conv2d(C.Structure):
+    """mesa_conv2d: the sizes of a convolution, in the header's order"""
+    _fields_ = [(n, C.c_int64) for n in ("B", "C_in", "H", "W", "C_out", "KH", "KW", "stride_h", "stride_w", "pad_h", "pad_w",
+                                         "dil_h", "dil_w")]
+
+    def out_hw(self):
+        return ((self.H + 2 * self.pad_h - self.dil_h * (self.KH - 1) - 1) // self.stride_h + 1,
+                (self.W + 2 * self.pad_w - self.dil_w * (self.KW - 1) - 1) // self.stride_w + 1)
 
 
 _lib = None
@@ -88,9 +98,13 @@ def lib() -> C.CDLL:
         L.mesa_event_record.argtypes = [_vp, _vp]
         L.mesa_event_elapsed_ms.argtypes = [_vp, _vp, C.POINTER(_f32)]
         L.mesa_event_destroy.argtypes = [_vp]
+        L.mesa_conv2d_dw_q.argtypes = [_vp, Conv2d, _i64, _vp, _vp, _vp, _int, _vp, _vp, _vp, _sz, _vp]
+        L.mesa_conv2d_dw_q_workspace_bytes.argtypes = [Conv2d, _int]
+        L.mesa_conv2d_dw_q_workspace_bytes.restype = _sz
         for name in EXPORTS:
             fn = getattr(L, name)
-            if name not in ("mesa_workspace_bytes", "mesa_status_string", "mesa_version", "mesa_static_scratch_bytes"):
+            if name not in ("mesa_workspace_bytes", "mesa_status_string", "mesa_version", "mesa_static_scratch_bytes",
+                            "mesa_conv2d_dw_q_workspace_bytes"):
                 fn.restype = _int
         _lib = L
     return _lib
@@ -280,6 +294,16 @@ def mesa_linear_dw_q(xq, M, K, G, alpha, beta, dy, N_out, dW, db, ws):
     p, n = _ws_args(ws)
     _check(lib().mesa_linear_dw_q(_ptr(xq), M, K, G, _ptr(alpha), _ptr(beta), _ptr(dy), N_out, _dt(dy), _ptr(dW), _ptr(db),
                                   p, n, _stream()), "mesa_linear_dw_q")
+
+
+def conv2d_dw_q_workspace_bytes(cv: Conv2d, dtype: int = F16) -> int:
+    return int(lib().mesa_conv2d_dw_q_workspace_bytes(cv, int(dtype)))
+
+
+def mesa_conv2d_dw_q(xq, cv: Conv2d, G, alpha, beta, dy, dW, db, ws):
+    p, n = _ws_args(ws)
+    _check(lib().mesa_conv2d_dw_q(_ptr(xq), cv, G, _ptr(alpha), _ptr(beta), _ptr(dy), _dt(dy), _ptr(dW), _ptr(db), p, n, _stream()),
+           "mesa_conv2d_dw_q")
 
 
 def mesa_stream_copy(src, dst, nbytes):
