@@ -526,6 +526,46 @@ def four_bit_leg(m, spec, steps):
                 "frac_hbm": round(nb[k] / (v * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)} for k, v in t.items()}
 
 
+CONV_SHAPES = [  # B, C_in, H, W, C_out, KH, KW, pad: the 3x3 and 1x1 convolutions of a segmentation head on 128 x 128 feature maps
+    ("3x3 512->512", (2, 512, 128, 128, 512, 3, 3, 1)),
+    ("1x1 2048->512", (2, 2048, 128, 128, 512, 1, 1, 0)),
+]
+
+
+def conv_dw_leg(m, spec, steps):
+    """Outside the headline figure: the weight gradient of a convolution at group-wise codes (Sec. 3.3), on the shapes of
+    a segmentation head (batch 2 per GPU, 128 x 128 feature maps), with the vendor library's convolution weight gradient
+    on the de-quantized 16-bit input beside it."""
+    dev = "cuda"
+    out = {}
+    dtc = dtype_code(m, spec.dtype)
+    for name, (B, Cin, H, Wd, Cout, KH, KW, pad) in CONV_SHAPES:
+        cv = m.Conv2d(B, Cin, H, Wd, Cout, KH, KW, 1, 1, pad, pad, 1, 1)
+        OH, OW = cv.out_hw()
+        G = 8
+        g = torch.Generator(device=dev).manual_seed(spec.seed + Cin + KH)
+        xq = [torch.randint(-128, 128, (B, Cin, H, Wd), dtype=torch.int8, device=dev, generator=g) for _ in range(3)]
+        dy = [W._randn((B, Cout, OH, OW), g, spec.dtype, dev) for _ in range(3)]
+        a = torch.full((G,), 8.0, device=dev)
+        b = torch.full((G,), -4.0, device=dev)
+        dW = torch.empty((Cout, Cin, KH, KW), device=dev)
+        db = torch.empty(Cout, device=dev)
+        ws = torch.empty(max(m.conv2d_dw_q_workspace_bytes(cv, dtc), 16), dtype=torch.uint8, device=dev)
+        ms = timed_leg(lambda i: m.mesa_conv2d_dw_q(xq[i % 3], cv, G, a, b, dy[i % 3], dW, db, ws), steps)
+        fl = 2.0 * B * OH * OW * Cin * Cout * KH * KW
+        entry = {"ms": round(ms, 5), "tflops": round(fl / (ms * 1e-3) / 1e12, 1),
+                 "mfma_frac": round(fl / (ms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4),
+                 "shape": [B, Cin, H, Wd, Cout, KH, KW], "workspace_bytes": int(ws.numel())}
+        xh = [torch.empty((B, Cin, H, Wd), dtype=spec.dtype, device=dev) for _ in range(3)]
+        for k in range(3):
+            m.mesa_dequantize(xq[k].view(-1), (B, G, (Cin // G) * H * Wd), a, b, xh[k])
+        lib_ms = timed_leg(lambda i: torch.nn.grad.conv2d_weight(xh[i % 3], (Cout, Cin, KH, KW), dy[i % 3], padding=pad), steps)
+        entry["library_conv_16bit_operands"] = {"ms": round(lib_ms, 5), "tflops": round(fl / (lib_ms * 1e-3) / 1e12, 1)}
+        out[name] = entry
+        del xq, dy, xh
+    return out
+
+
 def bandwidth_probes(m):
     """Untimed extras: what plain kernels reach on this GPU -- a copy (the known-traffic kernel the bandwidth counters are
     scaled against), a read-only and a write-only stream, 256 MiB each, three rotating buffers, median of event pairs."""
@@ -742,6 +782,7 @@ def main():
         out.update(layer_forward_legs(m, spec, leg_steps))
         out["symmetric_scale_only_forward"] = symmetric_leg(m, spec, leg_steps)
         out["four_bit_codes"] = four_bit_leg(m, spec, leg_steps)
+        out["conv2d_dw_q"] = conv_dw_leg(m, spec, leg_steps)
     if not args.no_cpu_baseline and number in (2, HEADLINE_CONFIG):
         # the oracle reads binary16 or binary32 arrays: for bfloat16 runs it is timed on the binary16 workload (same bytes)
         out["cpu_baseline"] = cpu_baseline(dataclasses.replace(spec, dtype=torch.float16), number)

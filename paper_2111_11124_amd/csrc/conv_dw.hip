@@ -16,9 +16,12 @@
 // are written to LDS (pads as zeros).  Every tap of a 3x3 kernel then reuses the same dy fragment: nine MFMAs per
 // fragment read.  Slices of the (b, oh, segment) range are combined in a fixed order by a second kernel.
 //
-// This path takes 16-bit tensors with stride_w = dil_w = 1, KH, KW <= 3, pad_w <= 8, W and OW multiples of 8;
+// This path takes 16-bit tensors, 3x3 kernels with pad_w = 1 and 1x1 kernels with pad_w = 0, stride_w = dil_w = 1 (any
+// row stride, dilation and padding), W and OW multiples of 8;
 // anything else runs the plain kernel at the end of the file.
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 
 #include "api_util.hpp"
 #include "common.hpp"
@@ -33,10 +36,6 @@ struct ConvGeom {
     int B, Cin, H, W, Cout, KH, KW, sh, sw, ph, pw, dh, dw, OH, OW;
 };
 
-constexpr int kCvSeg = 128;            // output columns per stage
-constexpr int kCvPA = kCvSeg + 8;      // LDS pitch of a dy row, elements: 68 words, so eight rows' 16-byte reads miss each other's banks
-constexpr int kCvXW = kCvSeg + 16;     // staged input columns: the segment and one 8-column vector on either side
-constexpr int kCvPX = kCvXW;           // 72 words
 constexpr int kCvXcd = 8;
 constexpr int kCvThreads = 256;
 
@@ -72,30 +71,41 @@ template <> struct CvElem<__bf16> {
     }
 };
 
-// TAPS3 = true:  kernels up to 3x3; a wave owns 32 output x 32 input channels for all taps (nine accumulator tiles),
-//                the workgroup 64 x 64.
-// TAPS3 = false: 1x1 kernels; a wave owns 64 x 64 channels (four tiles), the workgroup 128 x 128.
-template <bool TAPS3> struct CvCfg {
-    static constexpr int TM = TAPS3 ? 1 : 2, TN = TAPS3 ? 1 : 2;
-    static constexpr int XR = TAPS3 ? 3 : 1, XC = TAPS3 ? 3 : 1;      // staged input rows (kh), window shifts (kw)
+// T3 = true:  3x3 kernels with pad_w = 1; a wave owns 32 output x 32 input channels for all nine taps (nine
+//              accumulator tiles), the workgroup 64 x 64 channels.
+// T3 = false: 1x1 kernels with pad_w = 0; a wave owns 64 x 64 channels (four tiles), the workgroup 128 x 128.
+// NKS: contraction steps of 16 output columns per stage (a stage is a row segment of 16*NKS columns).
+template <bool T3, int NKS> struct CvCfg {
+    static constexpr int TM = T3 ? 1 : 2, TN = T3 ? 1 : 2;
+    static constexpr int XR = T3 ? 3 : 1;                 // staged input rows (one per kh)
     static constexpr int COT = 64 * TM, CIT = 64 * TN;
-    static constexpr int A_BYTES = COT * kCvPA * 2;
-    static constexpr int X_BYTES = XR * CIT * kCvPX * 2;
-    static constexpr int LDS = A_BYTES + X_BYTES;
-    static constexpr int ND = COT * (kCvSeg / 8) / kCvThreads;        // dy vectors a thread stages
-    static constexpr int NXMAX = (XR * CIT * (kCvXW / 8) + kCvThreads - 1) / kCvThreads;   // input vectors, at most
+    static constexpr int SEG = 16 * NKS;                  // output columns per stage
+    static constexpr int NVA = 2 * NKS;                   // dy vectors (eight columns) per row
+    static constexpr int NVX = T3 ? 2 * NKS + 2 : 2 * NKS;   // input vectors per row: T3 adds one vector of halo on either side
+    // LDS pitches in elements: multiples of eight (16-byte rows), and such that eight rows' 16-byte reads start in
+    // eight different groups of four banks
+    static constexpr int PA = SEG + 8;
+    static constexpr int PX = T3 ? SEG + 16 : SEG + 8;
+    static constexpr int A_BYTES = COT * PA * 2;
+    static constexpr int X_BYTES = XR * CIT * PX * 2;
+    static constexpr int BUF = A_BYTES + X_BYTES;         // one of the two stage buffers
+    static constexpr int LDS = 2 * BUF;
+    static constexpr int ND = COT * NVA / kCvThreads;     // dy vectors a thread stages
+    static constexpr int NX = (XR * CIT * NVX + kCvThreads - 1) / kCvThreads;   // input vectors, at most
+    static_assert(COT * NVA % kCvThreads == 0, "every thread stages the same number of dy vectors");
+    static_assert(LDS <= 160 * 1024, "two stage buffers must fit the LDS of a CU");
 };
 
-// part[split][tap][co][ci] = sum over the split's (b, oh, segment) stages of dy * u,  tap = kh*KW + kw
-template <typename E, bool TAPS3, bool PODD>
+// part[split][tap][co][ci] = sum over the split's (b, oh, segment) stages of dy * u,  tap = kh*KW + kw.
+// Two LDS buffers: while stage s is multiplied out of one, stage s+1 -- loaded into registers at the start of s --
+// is converted and written into the other between the MFMAs; one barrier per stage.
+template <typename E, bool T3, int NKS>
 __global__ __launch_bounds__(kCvThreads, 1) void k_conv_dw(const int8_t *__restrict__ xq, const E *__restrict__ dy, ConvGeom cg,
                                                            int tiles_co, int tiles_ci, int splits, int stages_per_split,
                                                            int nseg, float *__restrict__ part)
 {
-    using C = CvCfg<TAPS3>;
+    using C = CvCfg<T3, NKS>;
     extern __shared__ __attribute__((aligned(16))) unsigned char cv_lds[];
-    unsigned char *const lds_a = cv_lds;
-    unsigned char *const lds_x = cv_lds + C::A_BYTES;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int total = gridDim.x;
@@ -111,172 +121,243 @@ __global__ __launch_bounds__(kCvThreads, 1) void k_conv_dw(const int8_t *__restr
     const int nstages = cg.B * cg.OH * nseg;
     const int st_begin = split * stages_per_split;
     const int st_end = min(st_begin + stages_per_split, nstages);
-    const int KH = cg.KH, KW = cg.KW;
+    constexpr int KH = T3 ? 3 : 1, KW = T3 ? 3 : 1;
 
-    cv16f acc[C::TM][C::TN][C::XR][C::XC];
+    cv16f acc[C::TM][C::TN][KH][KW];
 #pragma unroll
     for (int i = 0; i < C::TM; ++i)
 #pragma unroll
         for (int j = 0; j < C::TN; ++j)
 #pragma unroll
-            for (int a = 0; a < C::XR; ++a)
+            for (int a = 0; a < KH; ++a)
 #pragma unroll
-                for (int b = 0; b < C::XC; ++b)
+                for (int b = 0; b < KW; ++b)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) acc[i][j][a][b][v] = 0.0f;
 
-    // staging registers: what the next stage needs, in flight while this one is multiplied
-    u32x4 dreg[C::ND];
-    u32x2 xreg[C::NXMAX];
-    const int nxrows = KH * C::CIT;                       // staged input rows (kh-major)
-    const int nxvec = nxrows * (kCvXW / 8);
+    // What a thread stages, fixed for the whole kernel.  Input vector n of the thread: row (kh, channel) and vector v
+    // of that row -> its place in LDS, its offset in the tensor relative to the stage's origin, and kh, v for the
+    // in-image tests.  LDS element i of a staged input row is input column seg0 - 8 + i (T3) resp. seg0 + i.
+    int xmeta[C::NX], xoff[C::NX];
+#pragma unroll
+    for (int n = 0; n < C::NX; ++n) {
+        const int idx = tid + n * kCvThreads;
+        const int row = idx / C::NVX, v = idx - row * C::NVX;
+        const int kh = row / C::CIT, cl = row - kh * C::CIT;
+        const bool ok = idx < C::XR * C::CIT * C::NVX && ci0 + cl < cg.Cin;
+        xmeta[n] = ((row * C::PX + v * 8) * 2) | (v << 20) | (kh << 26) | (ok ? 1 << 28 : 0);
+        xoff[n] = (cl * cg.H + kh * cg.dh) * cg.W + v * 8;
+    }
+    int dmeta[C::ND], doff[C::ND];
+#pragma unroll
+    for (int n = 0; n < C::ND; ++n) {
+        const int idx = tid + n * kCvThreads;
+        const int row = idx / C::NVA, v = idx - row * C::NVA;
+        dmeta[n] = ((row * C::PA + v * 8) * 2) | (v << 20) | (co0 + row < cg.Cout ? 1 << 28 : 0);
+        doff[n] = row * cg.OH * cg.OW + v * 8;
+    }
 
-    auto stage_coords = [&](int st, int &b, int &oh, int &seg) {
-        seg = st % nseg;
-        const int r = st / nseg;
-        oh = r % cg.OH;
-        b = r / cg.OH;
-    };
-    auto load_stage = [&](int st) {
-        int b, oh, seg;
-        stage_coords(st, b, oh, seg);
-#pragma unroll
-        for (int n = 0; n < C::ND; ++n) {
-            const int idx = tid + n * kCvThreads;
-            const int row = idx >> 4, v = idx & 15;       // 16 vectors of eight columns per row
-            const int co = co0 + row, ow0 = seg * kCvSeg + v * 8;
-            u32x4 val = {0u, 0u, 0u, 0u};
-            if (co < cg.Cout && ow0 < cg.OW)
-                val = *reinterpret_cast<const u32x4 *>(dy + ((int64_t(b) * cg.Cout + co) * cg.OH + oh) * cg.OW + ow0);
-            dreg[n] = val;
-        }
-#pragma unroll
-        for (int n = 0; n < C::NXMAX; ++n) {
-            const int idx = tid + n * kCvThreads;
-            u32x2 val = {0u, 0u};
-            if (idx < nxvec) {
-                const int row = idx / (kCvXW / 8), v = idx - row * (kCvXW / 8);
-                const int kh = row / C::CIT, ci = ci0 + (row - kh * C::CIT);
-                const int ih = oh * cg.sh - cg.ph + kh * cg.dh;
-                const int iw0 = seg * kCvSeg - 8 + v * 8;
-                // (whether the vector lies inside the image is decided again, from the same coordinates, when it is stored)
-                if (ci < cg.Cin && ih >= 0 && ih < cg.H && iw0 >= 0 && iw0 < cg.W)
-                    val = *reinterpret_cast<const u32x2 *>(xq + ((int64_t(b) * cg.Cin + ci) * cg.H + ih) * cg.W + iw0);
-            }
-            xreg[n] = val;
+    u32x4 dreg[C::ND];
+    u32x2 xreg[C::NX];
+    uint32_t xkeep = 0u;       // bit n: input vector n lies inside the image (elsewhere the forward saw padding: zeros)
+
+    // the stage's coordinates, advanced one stage at a time
+    int seg = st_begin % nseg;
+    int oh = (st_begin / nseg) % cg.OH;
+    int b = (st_begin / nseg) / cg.OH;
+    auto advance = [&]() {
+        if (++seg == nseg) {
+            seg = 0;
+            if (++oh == cg.OH) { oh = 0; ++b; }
         }
     };
-    auto store_stage = [&](int st) {
-        int b, oh, seg;
-        stage_coords(st, b, oh, seg);
+    // Loads are unconditional: a vector outside its tensor is fetched from the tensor's first bytes instead and masked
+    // to zero when it is written to LDS (bit n of dkeep / xkeep), so the stage loop has no divergent branches.
+    uint32_t dkeep = 0u;
+    auto load_stage = [&]() {   // the stage at (b, oh, seg)
+        const int seg0 = seg * C::SEG;
+        const E *dbase = dy + ((int64_t(b) * cg.Cout + co0) * cg.OH + oh) * cg.OW + seg0;
+        const int dv_end = (cg.OW - seg0) >> 3;                       // vectors of this row that lie inside it
+        dkeep = 0u;
 #pragma unroll
         for (int n = 0; n < C::ND; ++n) {
-            const int idx = tid + n * kCvThreads;
-            const int row = idx >> 4, v = idx & 15;
-            *reinterpret_cast<u32x4 *>(lds_a + (row * kCvPA + v * 8) * 2) = dreg[n];
+            const int v = (dmeta[n] >> 20) & 31;
+            const bool in = (dmeta[n] >> 28) && v < dv_end;
+            dreg[n] = *reinterpret_cast<const u32x4 *>(in ? dbase + doff[n] : dy);
+            dkeep |= in ? 1u << n : 0u;
         }
+        const int ih0 = oh * cg.sh - cg.ph;
+        const int8_t *xbase = xq + ((int64_t(b) * cg.Cin + ci0) * cg.H + ih0) * cg.W + seg0 - (T3 ? 8 : 0);
+        int rowmask = 0;
+        xkeep = 0u;
 #pragma unroll
-        for (int n = 0; n < C::NXMAX; ++n) {
-            const int idx = tid + n * kCvThreads;
-            if (idx < nxvec) {
-                const int row = idx / (kCvXW / 8), v = idx - row * (kCvXW / 8);
-                const int kh = row / C::CIT, ci = ci0 + (row - kh * C::CIT);
-                const int ih = oh * cg.sh - cg.ph + kh * cg.dh;
-                const int iw0 = seg * kCvSeg - 8 + v * 8;
-                u32x4 o = {0u, 0u, 0u, 0u};
-                if (ci < cg.Cin && ih >= 0 && ih < cg.H && iw0 >= 0 && iw0 < cg.W) {
-                    uint32_t lo[2], hi[2];
-                    CvElem<E>::convert(xreg[n][0], lo);
-                    CvElem<E>::convert(xreg[n][1], hi);
-                    o = u32x4{lo[0], lo[1], hi[0], hi[1]};
-                }
-                *reinterpret_cast<u32x4 *>(lds_x + (row * kCvPX + v * 8) * 2) = o;
-            }
+        for (int a = 0; a < C::XR; ++a) {
+            const int ih = ih0 + a * cg.dh;
+            rowmask |= (ih >= 0 && ih < cg.H) ? 1 << a : 0;
+        }
+        const int v_lo = (T3 && seg0 == 0) ? 1 : 0;                   // the left halo of the first segment is padding
+        const int v_end = (cg.W - seg0 + (T3 ? 8 : 0)) >> 3;
+#pragma unroll
+        for (int n = 0; n < C::NX; ++n) {
+            const int v = (xmeta[n] >> 20) & 31, kh = (xmeta[n] >> 26) & 3;
+            const bool in = (xmeta[n] >> 28) && ((rowmask >> kh) & 1) && v >= v_lo && v < v_end;
+            xreg[n] = *reinterpret_cast<const u32x2 *>(in ? xbase + xoff[n] : xq);
+            xkeep |= in ? 1u << n : 0u;
+        }
+    };
+    auto store_d = [&](int n, unsigned char *buf) {
+        const uint32_t k = 0u - ((dkeep >> n) & 1u);
+        *reinterpret_cast<u32x4 *>(buf + (dmeta[n] & 0xFFFFF)) = u32x4{dreg[n][0] & k, dreg[n][1] & k, dreg[n][2] & k, dreg[n][3] & k};
+    };
+    auto store_x = [&](int n, unsigned char *buf) {
+        if (C::XR * C::CIT * C::NVX % kCvThreads == 0 || tid + n * kCvThreads < C::XR * C::CIT * C::NVX) {
+            uint32_t lo[2], hi[2];
+            CvElem<E>::convert(xreg[n][0], lo);
+            CvElem<E>::convert(xreg[n][1], hi);
+            const uint32_t k = 0u - ((xkeep >> n) & 1u);
+            *reinterpret_cast<u32x4 *>(buf + C::A_BYTES + (xmeta[n] & 0xFFFFF)) = u32x4{lo[0] & k, lo[1] & k, hi[0] & k, hi[1] & k};
         }
     };
 
     const int half = lane >> 5, l32 = lane & 31;
-    // LDS element i of a staged input row is input column seg*128 - 8 + i; output column k of the segment meets,
-    // for tap kw, element k + kw - pw + 8.  The six-word window starts at the even element k + 8 - pw - (pw & 1).
-    const int win0 = 8 - cg.pw - (PODD ? 1 : 0);
-    auto compute_stage = [&](int st) {
-        const int seg = st % nseg;
-        const int segw = min(kCvSeg, cg.OW - seg * kCvSeg);
-        const int nks = (segw + 15) >> 4;
-        for (int ks = 0; ks < nks; ++ks) {
-            const int k0 = ks * 16 + half * 8;
+    constexpr int NSLOT = C::ND + C::NX;
+    constexpr int K0 = NKS >= 4 ? 1 : 0;                              // first contraction step that also stores
+    constexpr int PER = (NSLOT + (NKS - K0) - 1) / (NKS - K0);        // staging slots per contraction step
+    // one stage out of `cur`; when `fill`, the registers of the next stage go into `nxt` on the way
+    auto compute_stage = [&](const unsigned char *cur, unsigned char *nxt, auto fill_tag) {
+        constexpr bool fill = decltype(fill_tag)::value;
+        const unsigned char *xa = cur + C::A_BYTES;
+        // T3: chunk c of a row holds input columns seg0 - 8 + 8c ..; output columns k..k+7 (k = 16ks + 8*half) meet, for
+        // the taps kw = 0, 1, 2, the elements k+7.., k+8.., k+9..: the middle tap is chunk 2ks + half + 1 as it lies,
+        // the outer two also need the last element of the chunk before and the first of the chunk after -- which the
+        // other half of the wave holds (one step earlier or later), so each lane reads one chunk per row and step
+        // and the halves exchange two words.
+        uint32_t e0[KH][2], e3[KH][2];                                // exchanged words of the previous and the current step
+        u32x4 cnext[KH][C::TN];
+        // chunk c of (kh row a, channel tile j) for this lane: a per-lane row address plus a constant
+        const unsigned char *xrow[KH][C::TN];
+#pragma unroll
+        for (int a = 0; a < KH; ++a)
+#pragma unroll
+            for (int j = 0; j < C::TN; ++j) xrow[a][j] = xa + ((a * C::CIT + wn * 32 * C::TN + j * 32 + l32) * C::PX + half * 8) * 2;
+        // T3: the step's chunk is 2ks + half + 1.  The reads before the first step and after the last one matter for
+        // one half of the wave only; the other half reads the same chunk (inside the row) and its value is never used.
+        auto chunk_addr = [&](int a, int j, int ks) {
+            if (!T3) return xrow[a][j] + ks * 32;
+            if (ks < 0) return xrow[a][j] - half * 16 + 0;                    // chunk 0 for both halves
+            if (ks >= NKS) return xrow[a][j] - half * 16 + (2 * NKS + 1) * 16;   // the last chunk for both halves
+            return xrow[a][j] + (2 * ks + 1) * 16;
+        };
+        static_assert(!T3 || C::TN == 1, "the exchange below is written for one input-channel tile per wave");
+        if (T3) {
+#pragma unroll
+            for (int a = 0; a < KH; ++a) {
+                const u32x4 cm1 = *reinterpret_cast<const u32x4 *>(chunk_addr(a, 0, -1));   // only the upper half's matters
+                e3[a][0] = __shfl_xor(cm1[3], 32, 64);
+                e0[a][0] = 0u;
+                cnext[a][0] = *reinterpret_cast<const u32x4 *>(chunk_addr(a, 0, 0));
+                e3[a][1] = __shfl_xor(cnext[a][0][3], 32, 64);
+                e0[a][1] = __shfl_xor(cnext[a][0][0], 32, 64);
+            }
+        }
+        u32x4 anext[C::TM];
+#pragma unroll
+        for (int i = 0; i < C::TM; ++i)
+            anext[i] = *reinterpret_cast<const u32x4 *>(cur + ((wm * 32 * C::TM + i * 32 + l32) * C::PA + half * 8) * 2);
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
             u32x4 afr[C::TM];
 #pragma unroll
-            for (int i = 0; i < C::TM; ++i)
-                afr[i] = *reinterpret_cast<const u32x4 *>(lds_a + ((wm * 32 * C::TM + i * 32 + l32) * kCvPA + k0) * 2);
+            for (int i = 0; i < C::TM; ++i) {
+                afr[i] = anext[i];
+                if (ks + 1 < NKS)
+                    anext[i] = *reinterpret_cast<const u32x4 *>(cur + ((wm * 32 * C::TM + i * 32 + l32) * C::PA + (ks + 1) * 16 + half * 8) * 2);
+            }
+            if (T3) {
 #pragma unroll
-            for (int a = 0; a < C::XR; ++a) {
-                if (a < KH) {
+                for (int a = 0; a < KH; ++a) {
+                    const u32x4 c1 = cnext[a][0];
+                    // the chunk of the next step, and its outer words from the other half
+                    cnext[a][0] = *reinterpret_cast<const u32x4 *>(chunk_addr(a, 0, ks + 1));
+                    const uint32_t n3 = __shfl_xor(cnext[a][0][3], 32, 64), n0 = __shfl_xor(cnext[a][0][0], 32, 64);
+                    // lower half: before = other's chunk of the previous step, after = other's chunk of this step;
+                    // upper half: before = other's chunk of this step, after = other's chunk of the next step
+                    const uint32_t before = half ? e3[a][1] : e3[a][0];
+                    const uint32_t after = half ? n0 : e0[a][1];
+                    e3[a][0] = e3[a][1]; e3[a][1] = n3;
+                    e0[a][0] = e0[a][1]; e0[a][1] = n0;
+                    u32x4 f0, f2;
+                    f0[0] = __builtin_amdgcn_alignbyte(c1[0], before, 2);
+                    f0[1] = __builtin_amdgcn_alignbyte(c1[1], c1[0], 2);
+                    f0[2] = __builtin_amdgcn_alignbyte(c1[2], c1[1], 2);
+                    f0[3] = __builtin_amdgcn_alignbyte(c1[3], c1[2], 2);
+                    f2[0] = __builtin_amdgcn_alignbyte(c1[1], c1[0], 2);
+                    f2[1] = __builtin_amdgcn_alignbyte(c1[2], c1[1], 2);
+                    f2[2] = __builtin_amdgcn_alignbyte(c1[3], c1[2], 2);
+                    f2[3] = __builtin_amdgcn_alignbyte(after, c1[3], 2);
+                    acc[0][0][a][0] = CvElem<E>::mfma(afr[0], f0, acc[0][0][a][0]);
+                    acc[0][0][a][KW > 1 ? 1 : 0] = CvElem<E>::mfma(afr[0], c1, acc[0][0][a][KW > 1 ? 1 : 0]);
+                    acc[0][0][a][KW > 2 ? 2 : 0] = CvElem<E>::mfma(afr[0], f2, acc[0][0][a][KW > 2 ? 2 : 0]);
+                }
+            } else {
 #pragma unroll
-                    for (int j = 0; j < C::TN; ++j) {
-                        const int row = a * C::CIT + wn * 32 * C::TN + j * 32 + l32;
-                        const uint32_t *w = reinterpret_cast<const uint32_t *>(lds_x + (row * kCvPX + k0 + win0) * 2);
-                        uint32_t D[6];
-                        constexpr int NW = (C::XC > 1) ? 6 : 5;
+                for (int j = 0; j < C::TN; ++j) {
+                    const u32x4 bfr = *reinterpret_cast<const u32x4 *>(chunk_addr(0, j, ks));
 #pragma unroll
-                        for (int d = 0; d < NW; ++d) D[d] = w[d];
-#pragma unroll
-                        for (int c = 0; c < C::XC; ++c) {
-                            if (c < KW) {
-                                const int r = (PODD ? 1 : 0) + c;         // the window's offset from its first element
-                                const int q = r >> 1;
-                                u32x4 bfr;
-                                if (r & 1) {
-#pragma unroll
-                                    for (int k = 0; k < 4; ++k) bfr[k] = __builtin_amdgcn_alignbyte(D[q + k + 1], D[q + k], 2);
-                                } else {
-#pragma unroll
-                                    for (int k = 0; k < 4; ++k) bfr[k] = D[q + k];
-                                }
-#pragma unroll
-                                for (int i = 0; i < C::TM; ++i) acc[i][j][a][c] = CvElem<E>::mfma(afr[i], bfr, acc[i][j][a][c]);
-                            }
-                        }
-                    }
+                    for (int i = 0; i < C::TM; ++i) acc[i][j][0][0] = CvElem<E>::mfma(afr[i], bfr, acc[i][j][0][0]);
                 }
             }
+            if (fill && ks >= K0) {
+#pragma unroll
+                for (int q = 0; q < PER; ++q) {
+                    const int slot = (ks - K0) * PER + q;
+                    if (slot < C::ND) store_d(slot, nxt);
+                    else if (slot < NSLOT) store_x(slot - C::ND, nxt);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);     // keep each step's reads, conversions and stores with its MFMAs
         }
     };
 
     if (st_begin < st_end) {
-        load_stage(st_begin);
-        store_stage(st_begin);
+        unsigned char *buf0 = cv_lds, *buf1 = cv_lds + C::BUF;
+        load_stage();
+#pragma unroll
+        for (int n = 0; n < C::ND; ++n) store_d(n, buf0);
+#pragma unroll
+        for (int n = 0; n < C::NX; ++n) store_x(n, buf0);
         __syncthreads();
         for (int st = st_begin; st < st_end; ++st) {
             const bool more = st + 1 < st_end;
-            if (more) load_stage(st + 1);
-            compute_stage(st);
-            __syncthreads();          // every wave is done reading this stage
-            if (more) store_stage(st + 1);
-            __syncthreads();
+            if (more) {
+                advance();
+                load_stage();
+            }
+            if (more) compute_stage(buf0, buf1, std::true_type());
+            else compute_stage(buf0, buf1, std::false_type());
+            __syncthreads();      // the next stage is complete in the other buffer, and every wave is done with this one
+            unsigned char *tmp = buf0; buf0 = buf1; buf1 = tmp;
         }
     }
 
     // lane l, register v of a 32x32 tile -> row (output channel) 8*(v/4) + 4*(l/32) + v%4, column (input channel) l%32
-    const int ntap = KH * KW;
+    constexpr int ntap = KH * KW;
 #pragma unroll
-    for (int a = 0; a < C::XR; ++a)
+    for (int a = 0; a < KH; ++a)
 #pragma unroll
-        for (int c = 0; c < C::XC; ++c) {
-            if (a < KH && c < KW) {
-                float *P = part + (int64_t(split) * ntap + (a * KW + c)) * cg.Cout * cg.Cin;
+        for (int c = 0; c < KW; ++c) {
+            float *P = part + (int64_t(split) * ntap + (a * KW + c)) * cg.Cout * cg.Cin;
 #pragma unroll
-                for (int i = 0; i < C::TM; ++i)
+            for (int i = 0; i < C::TM; ++i)
 #pragma unroll
-                    for (int j = 0; j < C::TN; ++j) {
-                        const int ci = ci0 + wn * 32 * C::TN + j * 32 + l32;
+                for (int j = 0; j < C::TN; ++j) {
+                    const int ci = ci0 + wn * 32 * C::TN + j * 32 + l32;
 #pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            const int co = co0 + wm * 32 * C::TM + i * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
-                            if (co < cg.Cout && ci < cg.Cin) P[int64_t(co) * cg.Cin + ci] = acc[i][j][a][c][v];
-                        }
+                    for (int v = 0; v < 16; ++v) {
+                        const int co = co0 + wm * 32 * C::TM + i * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+                        if (co < cg.Cout && ci < cg.Cin) P[int64_t(co) * cg.Cin + ci] = acc[i][j][a][c][v];
                     }
-            }
+                }
         }
 }
 
@@ -419,22 +500,26 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_dw_plain(const int8_t *__re
 
 struct CvPlan {
     bool fast, taps3;
-    int tiles_co, tiles_ci, splits, stages_per_split, nseg, grid, parts, imgs_per_part;
+    int nks, tiles_co, tiles_ci, splits, stages_per_split, nseg, grid, parts, imgs_per_part;
 };
 
 static CvPlan cv_plan(const ConvGeom &cg, mesa_dtype dt)
 {
     CvPlan p = {};
-    p.fast = dt != MESA_F32 && cg.sw == 1 && cg.dw == 1 && cg.KH <= 3 && cg.KW <= 3 && cg.pw <= 8 && cg.W % 8 == 0 && cg.OW % 8 == 0;
+    const bool k3 = cg.KH == 3 && cg.KW == 3 && cg.pw == 1, k1 = cg.KH == 1 && cg.KW == 1 && cg.pw == 0;
+    const int64_t lim = int64_t(1) << 23;      // per-thread offsets inside a tile of 128 channels stay below 2^31
+    p.fast = dt != MESA_F32 && cg.sw == 1 && cg.dw == 1 && (k3 || k1) && cg.W % 8 == 0 && cg.OW % 8 == 0 &&
+             int64_t(cg.H) * cg.W <= lim && int64_t(cg.OH) * cg.OW <= lim && 3 * int64_t(cg.dh) * cg.W < (int64_t(1) << 30);
     if (!p.fast) return p;
-    p.taps3 = cg.KH * cg.KW > 1;
+    p.taps3 = k3;
+    p.nks = cg.OW <= 32 ? 2 : cg.OW <= 64 ? 4 : 8;
     const int cot = p.taps3 ? 64 : 128, cit = p.taps3 ? 64 : 128;
     p.tiles_co = int(ceil_div(cg.Cout, cot));
     p.tiles_ci = int(ceil_div(cg.Cin, cit));
-    p.nseg = int(ceil_div(cg.OW, kCvSeg));
+    p.nseg = int(ceil_div(cg.OW, 16 * p.nks));
     const int64_t nstages = int64_t(cg.B) * cg.OH * p.nseg;
     const int64_t tiles = int64_t(p.tiles_co) * p.tiles_ci;
-    // about two workgroups per CU over the launch, slices of at least eight stages, at most 64 slices
+    // one workgroup per CU and round, about two rounds; slices of at least eight stages, at most 64 slices
     int64_t splits = ceil_div(512, tiles);
     if (splits > 64) splits = 64;
     if (splits > ceil_div(nstages, 8)) splits = ceil_div(nstages, 8);
@@ -476,7 +561,7 @@ static bool cv_supported(const ConvGeom &cg)
     const int64_t lim = int64_t(1) << 31;
     if (int64_t(cg.Cout) * cg.Cin * cg.KH * cg.KW >= lim) return false;
     if (int64_t(cg.OH) * cg.OW >= lim || int64_t(cg.H) * cg.W >= lim) return false;
-    if (int64_t(cg.B) * cg.OH * ceil_div(cg.OW, kCvSeg) >= lim) return false;
+    if (int64_t(cg.B) * cg.OH * ceil_div(cg.OW, 32) >= lim) return false;
     if (int64_t(cg.sh) * cg.OH + int64_t(cg.dh) * cg.KH + cg.ph >= lim) return false;
     if (int64_t(cg.sw) * cg.OW + int64_t(cg.dw) * cg.KW + cg.pw >= lim) return false;
     return true;
@@ -535,20 +620,24 @@ extern "C" MESA_EXPORT mesa_status mesa_conv2d_dw_q(const int8_t *xq, mesa_conv2
     float *part = static_cast<float *>(ws);
     const size_t part_bytes = size_t(p.splits) * cg.KH * cg.KW * cg.Cout * cg.Cin * sizeof(float);
     float *V = reinterpret_cast<float *>(static_cast<char *>(ws) + part_bytes);
-    const bool podd = (cg.pw & 1) != 0;
-#define MESA_LAUNCH_CV(E, T3, PO) \
+#define MESA_LAUNCH_CV(E, T3, NKS) \
     do { \
-        auto kern = k_conv_dw<E, T3, PO>; \
-        constexpr int lds = CvCfg<T3>::LDS; \
+        auto kern = k_conv_dw<E, T3, NKS>; \
+        constexpr int lds = CvCfg<T3, NKS>::LDS; \
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) \
             return MESA_ERR_LAUNCH; \
         hipLaunchKernelGGL(kern, dim3(p.grid), dim3(kCvThreads), lds, s, xq, static_cast<const E *>(dy), cg, p.tiles_co, p.tiles_ci, \
                            p.splits, p.stages_per_split, p.nseg, part); \
     } while (0)
+#define MESA_PICK_NKS(E, T3) \
+    do { \
+        if (p.nks == 8) MESA_LAUNCH_CV(E, T3, 8); \
+        else if (p.nks == 4) MESA_LAUNCH_CV(E, T3, 4); \
+        else MESA_LAUNCH_CV(E, T3, 2); \
+    } while (0)
 #define MESA_PICK_CV(E) \
     do { \
-        if (p.taps3) { if (podd) MESA_LAUNCH_CV(E, true, true); else MESA_LAUNCH_CV(E, true, false); } \
-        else { if (podd) MESA_LAUNCH_CV(E, false, true); else MESA_LAUNCH_CV(E, false, false); } \
+        if (p.taps3) MESA_PICK_NKS(E, true); else MESA_PICK_NKS(E, false); \
         hipLaunchKernelGGL((k_conv_valid_sums<E>), dim3(unsigned(cg.Cout) * p.parts), dim3(kCvThreads), 0, s, \
                            static_cast<const E *>(dy), cg, p.parts, p.imgs_per_part, V); \
     } while (0)
@@ -556,6 +645,7 @@ extern "C" MESA_EXPORT mesa_status mesa_conv2d_dw_q(const int8_t *xq, mesa_conv2
     if (dt == MESA_F16) { MESA_PICK_CV(_Float16); centre = CvElem<_Float16>::kCentre; }
     else { MESA_PICK_CV(__bf16); centre = CvElem<__bf16>::kCentre; }
 #undef MESA_PICK_CV
+#undef MESA_PICK_NKS
 #undef MESA_LAUNCH_CV
     if (launch_status() != MESA_OK) return MESA_ERR_LAUNCH;   // the last kernel must not read sums nobody wrote
     hipLaunchKernelGGL(k_conv_finish, dim3(unsigned(ceil_div(plane, kCvThreads))), dim3(kCvThreads), 0, s, part, V, p.splits, p.parts,

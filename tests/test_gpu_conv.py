@@ -1,6 +1,6 @@
 """mesa_conv2d_dw_q against the oracle: the matrix-core path over ragged channel tiles, several row segments, kernel
-shapes from 1x1 to 3x3, row strides and dilations; the plain path over everything else (column strides, dilations,
-large kernels, binary32 tensors); the empty batch and the error paths."""
+shapes 3x3 and 1x1, row strides, dilations and paddings; the plain path over everything else (column strides and
+dilations, other kernel shapes and column paddings, binary32 tensors); the empty batch and the error paths."""
 import numpy as np
 import pytest
 import torch
@@ -53,17 +53,15 @@ def run_case(M, case, dtype, seed=0, dy_mean=0.0):
 
 # B, Cin, H, W, Cout, KH, KW, stride, pad, dil, G   -- all on the matrix-core path for 16-bit tensors
 FAST = [
-    (2, 96, 16, 24, 80, 3, 3, (1, 1), (1, 1), (1, 1), 3),        # ragged channel tiles, a half contraction step at the row end
+    (2, 96, 16, 24, 80, 3, 3, (1, 1), (1, 1), (1, 1), 3),        # ragged channel tiles, a row narrower than a stage
     (1, 64, 5, 264, 64, 3, 3, (1, 1), (1, 1), (1, 1), 2),        # three row segments, the last eight columns wide
     (3, 40, 17, 16, 24, 3, 3, (2, 1), (1, 1), (1, 1), 5),        # row stride 2
     (2, 32, 12, 32, 72, 3, 3, (1, 1), (2, 1), (2, 1), 1),        # row dilation 2
-    (2, 64, 9, 40, 64, 3, 3, (1, 1), (0, 1), (1, 1), 4),         # no row padding
-    (2, 48, 8, 16, 40, 3, 1, (1, 1), (1, 0), (1, 1), 3),         # 3x1 kernel: even window offset
-    (2, 48, 8, 16, 40, 1, 3, (1, 1), (0, 1), (1, 1), 3),         # 1x3 kernel
-    (2, 16, 8, 24, 16, 3, 3, (1, 1), (1, 5), (1, 1), 2),         # wide column padding: OW = W + 8
+    (2, 64, 9, 40, 64, 3, 3, (1, 1), (0, 1), (1, 1), 4),         # no row padding; four contraction steps per stage
+    (2, 64, 6, 72, 64, 3, 3, (1, 1), (1, 1), (1, 1), 4),         # eight steps per stage, the row ends half way through one
     (4, 200, 8, 16, 136, 1, 1, (1, 1), (0, 0), (1, 1), 4),       # 1x1: ragged 128-channel tiles
     (2, 128, 6, 136, 128, 1, 1, (2, 1), (0, 0), (1, 1), 2),      # 1x1: two segments, row stride
-    (2, 32, 6, 16, 32, 1, 1, (1, 1), (0, 4), (1, 1), 2),         # 1x1 with column padding
+    (2, 256, 12, 48, 128, 1, 1, (1, 1), (3, 0), (1, 1), 2),      # 1x1 with row padding (rows of dy that meet no input row)
     (16, 64, 32, 32, 64, 3, 3, (1, 1), (1, 1), (1, 1), 4),       # many stages: several slices of the (image, row) range
 ]
 
@@ -82,6 +80,10 @@ PLAIN = [
     (2, 3, 8, 8, 2, 4, 4, (4, 4), (0, 0), (1, 1), 3),            # patch embedding: stride = kernel
     (1, 8, 14, 14, 6, 5, 5, (1, 1), (2, 2), (1, 1), 2),          # 5x5
     (2, 8, 7, 9, 5, 3, 3, (1, 1), (1, 1), (1, 1), 2),            # widths that are no multiples of eight
+    (2, 48, 8, 16, 40, 3, 1, (1, 1), (1, 0), (1, 1), 3),         # 3x1 kernel
+    (2, 48, 8, 16, 40, 1, 3, (1, 1), (0, 1), (1, 1), 3),         # 1x3 kernel
+    (2, 16, 8, 24, 16, 3, 3, (1, 1), (1, 5), (1, 1), 2),         # 3x3 with wide column padding
+    (2, 32, 6, 16, 32, 1, 1, (1, 1), (0, 4), (1, 1), 2),         # 1x1 with column padding
 ]
 
 
