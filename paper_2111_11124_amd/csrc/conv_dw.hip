@@ -138,30 +138,40 @@ __global__ __launch_bounds__(kCvThreads, 1) void k_conv_dw(const int8_t *__restr
     // What a thread stages, fixed for the whole kernel.  Input vector n of the thread: row (kh, channel) and vector v
     // of that row -> its place in LDS, its offset in the tensor relative to the stage's origin, and kh, v for the
     // in-image tests.  LDS element i of a staged input row is input column seg0 - 8 + i (T3) resp. seg0 + i.
-    int xmeta[C::NX], xoff[C::NX];
+    // xlds: its place in a stage buffer; xoff: its byte offset from the first byte of (image b, channel ci0); xbits: bit v
+    // and bit 24 + kh, to be tested against the stage's valid vectors and rows (bit 31, never valid, marks a vector that
+    // does not exist or a channel beyond C_in).
+    int xlds[C::NX], xoff[C::NX];
+    uint32_t xbits[C::NX];
 #pragma unroll
     for (int n = 0; n < C::NX; ++n) {
         const int idx = tid + n * kCvThreads;
         const int row = idx / C::NVX, v = idx - row * C::NVX;
         const int kh = row / C::CIT, cl = row - kh * C::CIT;
         const bool ok = idx < C::XR * C::CIT * C::NVX && ci0 + cl < cg.Cin;
-        xmeta[n] = ((row * C::PX + v * 8) * 2) | (v << 20) | (kh << 26) | (ok ? 1 << 28 : 0);
+        xlds[n] = C::A_BYTES + (row * C::PX + v * 8) * 2;
         xoff[n] = (cl * cg.H + kh * cg.dh) * cg.W + v * 8;
+        xbits[n] = ok ? (1u << v) | (1u << (24 + kh)) : 0x80000000u;
     }
-    int dmeta[C::ND], doff[C::ND];
+    int dlds[C::ND], doff[C::ND];
+    uint32_t dbits[C::ND];
 #pragma unroll
     for (int n = 0; n < C::ND; ++n) {
         const int idx = tid + n * kCvThreads;
         const int row = idx / C::NVA, v = idx - row * C::NVA;
-        dmeta[n] = ((row * C::PA + v * 8) * 2) | (v << 20) | (co0 + row < cg.Cout ? 1 << 28 : 0);
-        doff[n] = row * cg.OH * cg.OW + v * 8;
+        dlds[n] = (row * C::PA + v * 8) * 2;
+        doff[n] = (row * cg.OH * cg.OW + v * 8) * 2;
+        dbits[n] = co0 + row < cg.Cout ? 1u << v : 0x80000000u;
     }
 
-    u32x4 dreg[C::ND];
-    u32x2 xreg[C::NX];
-    uint32_t xkeep = 0u;       // bit n: input vector n lies inside the image (elsewhere the forward saw padding: zeros)
+    // Two register sets: while stage s is multiplied, set (s+1)%2 -- loaded during stage s-1 -- is written to the other LDS
+    // buffer and set s%2 receives stage s+2, so a load has a whole stage to arrive.
+    u32x4 dreg[2][C::ND];
+    u32x2 xreg[2][C::NX];
+    uint32_t xkeep[2] = {0u, 0u};   // bit n: input vector n lies inside the image (elsewhere the forward saw padding: zeros)
+    uint32_t dkeep[2] = {0u, 0u};
 
-    // the stage's coordinates, advanced one stage at a time
+    // the coordinates of the stage being loaded, advanced one stage at a time
     int seg = st_begin % nseg;
     int oh = (st_begin / nseg) % cg.OH;
     int b = (st_begin / nseg) / cg.OH;
@@ -171,61 +181,69 @@ __global__ __launch_bounds__(kCvThreads, 1) void k_conv_dw(const int8_t *__restr
             if (++oh == cg.OH) { oh = 0; ++b; }
         }
     };
-    // Loads are unconditional: a vector outside its tensor is fetched from the tensor's first bytes instead and masked
-    // to zero when it is written to LDS (bit n of dkeep / xkeep), so the stage loop has no divergent branches.
-    uint32_t dkeep = 0u;
-    auto load_stage = [&]() {   // the stage at (b, oh, seg)
+    // Loads are unconditional and their addresses a uniform base plus a 32-bit offset per lane: a vector outside its
+    // tensor is fetched from offset zero instead and masked to zero when it is written to LDS (bit n of dkeep / xkeep),
+    // so the stage loop has no divergent branches.
+    auto load_stage = [&](auto set_tag) {   // the stage at (b, oh, seg) into register set S
+        constexpr int S = decltype(set_tag)::value;
         const int seg0 = seg * C::SEG;
-        const E *dbase = dy + ((int64_t(b) * cg.Cout + co0) * cg.OH + oh) * cg.OW + seg0;
+        const char *dbase = reinterpret_cast<const char *>(dy + (int64_t(b) * cg.Cout + co0) * cg.OH * cg.OW);
+        const int ddelta = (oh * cg.OW + seg0) * 2;
         const int dv_end = (cg.OW - seg0) >> 3;                       // vectors of this row that lie inside it
-        dkeep = 0u;
+        const uint32_t dmask = dv_end >= 32 ? 0xFFFFFFFFu : (1u << dv_end) - 1u;
+        dkeep[S] = 0u;
 #pragma unroll
         for (int n = 0; n < C::ND; ++n) {
-            const int v = (dmeta[n] >> 20) & 31;
-            const bool in = (dmeta[n] >> 28) && v < dv_end;
-            dreg[n] = *reinterpret_cast<const u32x4 *>(in ? dbase + doff[n] : dy);
-            dkeep |= in ? 1u << n : 0u;
+            const bool in = (dbits[n] & dmask) == dbits[n];
+            dreg[S][n] = *reinterpret_cast<const u32x4 *>(dbase + uint32_t(in ? doff[n] + ddelta : 0));
+            dkeep[S] |= in ? 1u << n : 0u;
         }
         const int ih0 = oh * cg.sh - cg.ph;
-        const int8_t *xbase = xq + ((int64_t(b) * cg.Cin + ci0) * cg.H + ih0) * cg.W + seg0 - (T3 ? 8 : 0);
-        int rowmask = 0;
-        xkeep = 0u;
+        const char *xbase = reinterpret_cast<const char *>(xq + (int64_t(b) * cg.Cin + ci0) * cg.H * cg.W);
+        const int xdelta = ih0 * cg.W + seg0 - (T3 ? 8 : 0);
+        uint32_t smask = 0u;                                          // rows, then vectors, of this stage that lie in the image
 #pragma unroll
         for (int a = 0; a < C::XR; ++a) {
             const int ih = ih0 + a * cg.dh;
-            rowmask |= (ih >= 0 && ih < cg.H) ? 1 << a : 0;
+            smask |= (ih >= 0 && ih < cg.H) ? 1u << (24 + a) : 0u;
         }
         const int v_lo = (T3 && seg0 == 0) ? 1 : 0;                   // the left halo of the first segment is padding
-        const int v_end = (cg.W - seg0 + (T3 ? 8 : 0)) >> 3;
+        const int v_end = min((cg.W - seg0 + (T3 ? 8 : 0)) >> 3, 24);
+        smask |= ((1u << v_end) - 1u) & ~((1u << v_lo) - 1u);
+        xkeep[S] = 0u;
 #pragma unroll
         for (int n = 0; n < C::NX; ++n) {
-            const int v = (xmeta[n] >> 20) & 31, kh = (xmeta[n] >> 26) & 3;
-            const bool in = (xmeta[n] >> 28) && ((rowmask >> kh) & 1) && v >= v_lo && v < v_end;
-            xreg[n] = *reinterpret_cast<const u32x2 *>(in ? xbase + xoff[n] : xq);
-            xkeep |= in ? 1u << n : 0u;
+            const bool in = (xbits[n] & smask) == xbits[n];
+            xreg[S][n] = *reinterpret_cast<const u32x2 *>(xbase + uint32_t(in ? xoff[n] + xdelta : 0));
+            xkeep[S] |= in ? 1u << n : 0u;
         }
     };
-    auto store_d = [&](int n, unsigned char *buf) {
-        const uint32_t k = 0u - ((dkeep >> n) & 1u);
-        *reinterpret_cast<u32x4 *>(buf + (dmeta[n] & 0xFFFFF)) = u32x4{dreg[n][0] & k, dreg[n][1] & k, dreg[n][2] & k, dreg[n][3] & k};
+    auto store_d = [&](int S, int n, unsigned char *buf) {
+        const uint32_t k = 0u - ((dkeep[S] >> n) & 1u);
+        *reinterpret_cast<u32x4 *>(buf + dlds[n]) = u32x4{dreg[S][n][0] & k, dreg[S][n][1] & k, dreg[S][n][2] & k, dreg[S][n][3] & k};
     };
-    auto store_x = [&](int n, unsigned char *buf) {
+    auto store_x = [&](int S, int n, unsigned char *buf) {
         if (C::XR * C::CIT * C::NVX % kCvThreads == 0 || tid + n * kCvThreads < C::XR * C::CIT * C::NVX) {
             uint32_t lo[2], hi[2];
-            CvElem<E>::convert(xreg[n][0], lo);
-            CvElem<E>::convert(xreg[n][1], hi);
-            const uint32_t k = 0u - ((xkeep >> n) & 1u);
-            *reinterpret_cast<u32x4 *>(buf + C::A_BYTES + (xmeta[n] & 0xFFFFF)) = u32x4{lo[0] & k, lo[1] & k, hi[0] & k, hi[1] & k};
+            CvElem<E>::convert(xreg[S][n][0], lo);
+            CvElem<E>::convert(xreg[S][n][1], hi);
+            const uint32_t k = 0u - ((xkeep[S] >> n) & 1u);
+            *reinterpret_cast<u32x4 *>(buf + xlds[n]) = u32x4{lo[0] & k, lo[1] & k, hi[0] & k, hi[1] & k};
         }
     };
 
     const int half = lane >> 5, l32 = lane & 31;
     constexpr int NSLOT = C::ND + C::NX;
-    constexpr int K0 = NKS >= 4 ? 1 : 0;                              // first contraction step that also stores
-    constexpr int PER = (NSLOT + (NKS - K0) - 1) / (NKS - K0);        // staging slots per contraction step
-    // one stage out of `cur`; when `fill`, the registers of the next stage go into `nxt` on the way
-    auto compute_stage = [&](const unsigned char *cur, unsigned char *nxt, auto fill_tag) {
-        constexpr bool fill = decltype(fill_tag)::value;
+    constexpr int PER = (NSLOT + NKS - 1) / NKS;                      // staging slots per contraction step
+    int st_load = st_begin;                                           // the stage the coordinates (b, oh, seg) stand at
+    // Stage s (s - st_begin of parity P) out of `cur`.  On the way, register set 1-P (stage s+1) goes into `nxt` and set P
+    // is loaded with stage s+2.  Past the end of the slice the coordinates stay on the last stage: its vectors are
+    // loaded and stored once or twice more, into registers and a buffer nobody reads again -- cheaper than a second
+    // code path.
+    auto compute_stage = [&](const unsigned char *cur, unsigned char *nxt, auto parity_tag) {
+        constexpr int P = decltype(parity_tag)::value;
+        if (st_load + 1 < st_end) { advance(); ++st_load; }
+        load_stage(std::integral_constant<int, P>());
         const unsigned char *xa = cur + C::A_BYTES;
         // T3: chunk c of a row holds input columns seg0 - 8 + 8c ..; output columns k..k+7 (k = 16ks + 8*half) meet, for
         // the taps kw = 0, 1, 2, the elements k+7.., k+8.., k+9..: the middle tap is chunk 2ks + half + 1 as it lies,
@@ -307,37 +325,35 @@ __global__ __launch_bounds__(kCvThreads, 1) void k_conv_dw(const int8_t *__restr
                     for (int i = 0; i < C::TM; ++i) acc[i][j][0][0] = CvElem<E>::mfma(afr[i], bfr, acc[i][j][0][0]);
                 }
             }
-            if (fill && ks >= K0) {
 #pragma unroll
-                for (int q = 0; q < PER; ++q) {
-                    const int slot = (ks - K0) * PER + q;
-                    if (slot < C::ND) store_d(slot, nxt);
-                    else if (slot < NSLOT) store_x(slot - C::ND, nxt);
-                }
+            for (int q = 0; q < PER; ++q) {
+                const int slot = ks * PER + q;
+                if (slot < C::ND) store_d(1 - P, slot, nxt);
+                else if (slot < NSLOT) store_x(1 - P, slot - C::ND, nxt);
             }
             __builtin_amdgcn_sched_barrier(0);     // keep each step's reads, conversions and stores with its MFMAs
         }
     };
 
     if (st_begin < st_end) {
-        unsigned char *buf0 = cv_lds, *buf1 = cv_lds + C::BUF;
-        load_stage();
+        unsigned char *const buf0 = cv_lds, *const buf1 = cv_lds + C::BUF;
+        load_stage(std::integral_constant<int, 0>());                 // the first stage, straight into its buffer
 #pragma unroll
-        for (int n = 0; n < C::ND; ++n) store_d(n, buf0);
+        for (int n = 0; n < C::ND; ++n) store_d(0, n, buf0);
 #pragma unroll
-        for (int n = 0; n < C::NX; ++n) store_x(n, buf0);
+        for (int n = 0; n < C::NX; ++n) store_x(0, n, buf0);
+        if (st_load + 1 < st_end) { advance(); ++st_load; }
+        load_stage(std::integral_constant<int, 1>());                 // the second, into the set the first stage stores
         __syncthreads();
-        for (int st = st_begin; st < st_end; ++st) {
-            const bool more = st + 1 < st_end;
-            if (more) {
-                advance();
-                load_stage();
-            }
-            if (more) compute_stage(buf0, buf1, std::true_type());
-            else compute_stage(buf0, buf1, std::false_type());
-            __syncthreads();      // the next stage is complete in the other buffer, and every wave is done with this one
-            unsigned char *tmp = buf0; buf0 = buf1; buf1 = tmp;
+        // one barrier per stage: the next stage is complete in the other buffer, and every wave is done with this one
+        int st = st_begin;
+        for (; st + 1 < st_end; st += 2) {
+            compute_stage(buf0, buf1, std::integral_constant<int, 0>());
+            __syncthreads();
+            compute_stage(buf1, buf0, std::integral_constant<int, 1>());
+            __syncthreads();
         }
+        if (st < st_end) compute_stage(buf0, buf1, std::integral_constant<int, 0>());
     }
 
     // lane l, register v of a 32x32 tile -> row (output channel) 8*(v/4) + 4*(l/32) + v%4, column (input channel) l%32
@@ -507,9 +523,10 @@ static CvPlan cv_plan(const ConvGeom &cg, mesa_dtype dt)
 {
     CvPlan p = {};
     const bool k3 = cg.KH == 3 && cg.KW == 3 && cg.pw == 1, k1 = cg.KH == 1 && cg.KW == 1 && cg.pw == 0;
-    const int64_t lim = int64_t(1) << 23;      // per-thread offsets inside a tile of 128 channels stay below 2^31
+    // per-lane byte offsets inside a tile of 128 channels, plus the stage's own offset, stay below 2^31
+    const int64_t lim = int64_t(1) << 22;
     p.fast = dt != MESA_F32 && cg.sw == 1 && cg.dw == 1 && (k3 || k1) && cg.W % 8 == 0 && cg.OW % 8 == 0 &&
-             int64_t(cg.H) * cg.W <= lim && int64_t(cg.OH) * cg.OW <= lim && 3 * int64_t(cg.dh) * cg.W < (int64_t(1) << 30);
+             (int64_t(cg.H) + 2 * cg.ph + 3 * int64_t(cg.dh)) * cg.W <= lim && int64_t(cg.OH) * cg.OW <= lim;
     if (!p.fast) return p;
     p.taps3 = k3;
     p.nks = cg.OW <= 32 ? 2 : cg.OW <= 64 ? 4 : 8;
