@@ -422,3 +422,35 @@ def test_layer_forwards_full_size(M, number):
         assert np.array_equal(q.cpu().numpy(), rq.reshape(-1))
         assert np.array_equal(canon(a.cpu().numpy()), canon(ra2)) and np.array_equal(canon(b.cpu().numpy()), canon(rb2))
         del x, y, q, xh, ry, rq
+
+
+@pytest.mark.parametrize("shape", [(2, 512, 128, 128, 512, 3, 3, 1), (2, 2048, 128, 128, 512, 1, 1, 0)], ids=["3x3", "1x1"])
+def test_convolution_weight_gradient_full_size_sampled(M, shape):
+    """mesa_conv2d_dw_q at the segmentation-head shapes bench.py times: 400 sampled entries of dW against the oracle
+    (each a sum over all 32768 output positions), the bias gradient in full."""
+    B, Cin, H, Wd, Cout, KH, KW, pad = shape
+    G = 8
+    cv = M.Conv2d(B, Cin, H, Wd, Cout, KH, KW, 1, 1, pad, pad, 1, 1)
+    OH, OW = cv.out_hw()
+    gen = torch.Generator(device="cuda").manual_seed(Cin + KH)
+    xq = torch.randint(-128, 128, (B, Cin, H, Wd), dtype=torch.int8, device="cuda", generator=gen)
+    dy = torch.randn((B, Cout, OH, OW), device="cuda", generator=gen).half()
+    a = (2.0 + 6.0 * torch.rand(G, device="cuda", generator=gen)).float()
+    b = (-4.0 + 2.0 * torch.rand(G, device="cuda", generator=gen)).float()
+    dW = torch.full((Cout, Cin, KH, KW), float("nan"), device="cuda")
+    db = torch.full((Cout,), float("nan"), device="cuda")
+    ws = torch.empty(M.conv2d_dw_q_workspace_bytes(cv, M.F16), dtype=torch.uint8, device="cuda")
+    M.mesa_conv2d_dw_q(xq, cv, G, a, b, dy, dW, db, ws)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(3)
+    idx = np.stack([rng.integers(0, Cout, 400), rng.integers(0, Cin, 400), rng.integers(0, KH, 400), rng.integers(0, KW, 400)], 1)
+    idx[:4] = [[0, 0, 0, 0], [Cout - 1, Cin - 1, KH - 1, KW - 1], [Cout - 1, 0, 0, KW - 1], [0, Cin - 1, KH - 1, 0]]
+    geom, _, _ = R.conv_geometry(B, Cin, H, Wd, Cout, KH, KW, (1, 1), (pad, pad), (1, 1))
+    ref = R.conv2d_dw_q_entries(xq.cpu().numpy(), geom, G, a.cpu().numpy(), b.cpu().numpy(), dy.cpu().numpy(), idx)
+    got = dW.cpu().numpy()[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].astype(np.float64)
+    scale = float(np.abs(dW.cpu().numpy()).max())
+    assert np.isfinite(dW.cpu().numpy()).all()
+    assert np.abs(got - ref).max() <= 2e-3 * scale, float(np.abs(got - ref).max() / scale)
+    ref_db = dy.cpu().numpy().astype(np.float64).sum(axis=(0, 2, 3))      # db is a plain sum over dy, here in binary64 on the host
+    assert np.abs(db.cpu().numpy() - ref_db).max() <= 1e-5 * np.abs(ref_db).max() + 1e-3
+

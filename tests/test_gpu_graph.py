@@ -159,9 +159,10 @@ def test_captured_layer_forwards_and_the_remaining_backwards_replay_exactly(M):
             assert torch.equal(got, ref), (t, k)
 
 
-def test_captured_scale_only_four_bit_and_static_scratch_calls_replay_exactly(M):
-    """The later additions: the scale-only symmetric trio, the four-bit trio and the update that keeps its partial
-    extrema in the library's own static array (whose contents survive from replay to replay)."""
+def test_captured_scale_only_four_bit_static_scratch_and_convolution_calls_replay_exactly(M):
+    """The later additions: the scale-only symmetric trio, the four-bit trio, the update that keeps its partial
+    extrema in the library's own static array (whose contents survive from replay to replay), and the convolution
+    weight gradient on both of its paths (the matrix-core one raises its kernel's LDS limit on every call)."""
     dev = "cuda"
     Mr, H, mlp = 197 * 3, 3, 384
     g = torch.Generator(device=dev).manual_seed(21)
@@ -174,8 +175,19 @@ def test_captured_scale_only_four_bit_and_static_scratch_calls_replay_exactly(M)
     buf = {"qs": torch.empty(n, dtype=torch.int8, device=dev), "xs": torch.empty_like(x),
            "q4": torch.empty((n + 1) // 2, dtype=torch.uint8, device=dev), "x4": torch.empty_like(x), "dx4": torch.empty_like(dy)}
     w = ws(M, M.OP_UPDATE_RUNNING_PARAMS, *lay)
+    cv3 = M.Conv2d(2, 48, 12, 24, 40, 3, 3, 1, 1, 1, 1, 1, 1)          # matrix cores
+    cv5 = M.Conv2d(2, 6, 9, 10, 4, 5, 5, 2, 2, 2, 2, 1, 1)             # the plain kernel
+    xq3 = torch.randint(-128, 128, (2, 48, 12, 24), dtype=torch.int8, device=dev, generator=g)
+    xq5 = torch.randint(-128, 128, (2, 6, 9, 10), dtype=torch.int8, device=dev, generator=g)
+    dy3 = torch.randn((2, 40) + cv3.out_hw(), device=dev, generator=g).half()
+    dy5 = torch.randn((2, 4) + cv5.out_hw(), device=dev, generator=g).half()
+    buf.update({"dW3": torch.empty((40, 48, 3, 3), device=dev), "db3": torch.empty(40, device=dev),
+                "dW5": torch.empty((4, 6, 5, 5), device=dev), "db5": torch.empty(4, device=dev)})
+    w3 = torch.empty(max(M.conv2d_dw_q_workspace_bytes(cv3, M.F16), 16), dtype=torch.uint8, device=dev)
 
     def step():
+        M.mesa_conv2d_dw_q(xq3, cv3, H, st["a"], st["b"], dy3, buf["dW3"], buf["db3"], w3)
+        M.mesa_conv2d_dw_q(xq5, cv5, H, st["a"], st["b"], dy5, buf["dW5"], buf["db5"], None)
         M.mesa_update_running_scale_sym(x, lay, st["m"], 0.9, False, w)
         M.mesa_quantize_sym(x, lay, st["m"], buf["qs"], M.ROUND_STOCHASTIC, 11, 0)
         M.mesa_dequantize_sym(buf["qs"], lay, st["m"], buf["xs"])
