@@ -778,7 +778,7 @@ def main():
         torch.cuda.empty_cache()
         out.update(bandwidth_probes(m))
         leg_steps = 20
-        out["attention_matmul_bwd"] = attention_matmul_leg(m, spec, leg_steps) if number != 5 else None
+        out["attention_matmul_bwd"] = attention_matmul_leg(m, spec, leg_steps if number != 5 else 5)
         out.update(layer_forward_legs(m, spec, leg_steps))
         out["symmetric_scale_only_forward"] = symmetric_leg(m, spec, leg_steps)
         out["four_bit_codes"] = four_bit_leg(m, spec, leg_steps)
