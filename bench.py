@@ -470,7 +470,7 @@ def layer_forward_legs(m, spec, steps):
 
 def symmetric_leg(m, spec, steps):
     """Outside the headline figure: the forward half (statistics + quantize) of the scale-only symmetric scheme the paper's
-    ablation compares with (Sec. 5.3), next to the method's asymmetric forward, on the configuration's GELU input."""
+    ablation compares with (Sec. 5.2), next to the method's asymmetric forward, on the configuration's GELU input."""
     lay = spec.gelu_layout
     n = lay[0] * lay[1] * lay[2]
     dev = "cuda"
@@ -497,7 +497,7 @@ def symmetric_leg(m, spec, steps):
 
 
 def four_bit_leg(m, spec, steps):
-    """Outside the headline figure: the lower bit width of the ablation (Sec. 5.3) on the configuration's GELU input --
+    """Outside the headline figure: the lower bit width that Sec. 4.2 discusses, on the configuration's GELU input --
     quantize to four-bit codes (two per byte) and GELU backward from them, next to the eight-bit calls."""
     lay = spec.gelu_layout
     n = lay[0] * lay[1] * lay[2]
@@ -651,6 +651,9 @@ def main():
                                                              "single-pass variant, probes)")
     ap.add_argument("--only-dw", action="store_true", help="run only the configuration's weight-gradient calls, back to back, and "
                                                            "print their figures (a measurement helper, not the benchmark line)")
+    ap.add_argument("--only-leg", default=None, choices=["attention", "conv", "four_bit", "symmetric", "layer_forwards"],
+                    help="run one of the legs outside the headline alone and print its figures (a measurement helper: the "
+                         "launch sequence the per-kernel counter summaries in profiles/ are taken on)")
     ap.add_argument("--config", type=int, default=HEADLINE_CONFIG, choices=[2, 3, 4, 5],
                     help="which of the baseline configurations to run; the default (4) is the whole-model one, twelve blocks per "
                          "step; 2, 3 and 5 are single blocks")
@@ -674,6 +677,11 @@ def main():
         print(json.dumps({"only_dw": dw_only(m, spec, args.steps or 20), "config": spec.name,
                           "note": "weight gradients launched back to back: the sustained rate, below what the same calls reach "
                                   "between the memory-bound kernels of a whole step"}))
+        return
+    if args.only_leg:
+        leg = {"attention": attention_matmul_leg, "conv": conv_dw_leg, "four_bit": four_bit_leg, "symmetric": symmetric_leg,
+               "layer_forwards": layer_forward_legs}[args.only_leg]
+        print(json.dumps({"only_leg": args.only_leg, "config": spec.name, "result": leg(m, spec, args.steps or 20)}))
         return
     nblocks = BLOCKS[number]
     steps = args.steps if args.steps is not None else (30 if nblocks > 1 else 50)

@@ -89,7 +89,7 @@ mesa_status mesa_update_running_params(const void *x, mesa_dtype dt, mesa_layout
                                        void *ws, size_t ws_bytes, void *stream);
 
 /*
- * Symmetric RANGE (a second, milder reading of the ablation of Sec. 5.3; the scale-only scheme proper is
+ * Symmetric RANGE (a second, milder reading of the ablation of Sec. 5.2; the scale-only scheme proper is
  * mesa_quantize_sym below): one scale from m_g = max |x| over group g, no free offset, but the codes and
  * every other call stay the asymmetric ones.  The clipping range is [-m_g, +m_g]: the call above with mn_g := -m_g and mx_g := +m_g, so that alpha_g
  * moves towards 2 m_g and beta_g towards -m_g.  Quantizer, dequantizer and the backward calls take
@@ -100,7 +100,7 @@ mesa_status mesa_update_running_params_sym(const void *x, mesa_dtype dt, mesa_la
                                            void *ws, size_t ws_bytes, void *stream);
 
 /*
- * Scale-only symmetric quantization, the scheme the ablation of Sec. 5.3 ("asymmetric vs. symmetric quantization")
+ * Scale-only symmetric quantization, the scheme the ablation of Sec. 5.2 ("asymmetric vs. symmetric quantization")
  * compares the method with: the input is quantized by a scale factor only -- no offset, zero is a code.  The paper
  * prints the scale as (2^b - 1) / max|X|; with signed b-bit codes that would need b + 1 bits, so the signed reading is
  * taken: 127 steps on each side of zero.  Three calls:

@@ -235,7 +235,7 @@ int mesa_ref_update_running_params(const void *x, int dt, int64_t outer, int64_t
 }
 
 /*
- * Symmetric range (the ablation of Sec. 5.3, asymmetric vs. symmetric quantization): one scale from
+ * Symmetric range (the ablation of Sec. 5.2, asymmetric vs. symmetric quantization): one scale from
  * m = max |x| over the group and no free offset.  Reading taken here (the paper gives the scale factor
  * only): the clipping range is [-m, +m], i.e. Eq. (3)-(7) with the group's minimum replaced by -m and
  * its maximum by +m, so alpha moves towards 2m and beta towards -m; everything downstream (quantizer,
@@ -271,7 +271,7 @@ int mesa_ref_update_running_params_sym(const void *x, int dt, int64_t outer, int
 }
 
 /*
- * Scale-only symmetric quantization, the scheme the ablation of Sec. 5.3 compares Mesa with: the input is
+ * Scale-only symmetric quantization, the scheme the ablation of Sec. 5.2 compares Mesa with: the input is
  * quantized "by a scale factor only" -- no offset, zero is a code.  The paper prints the scale as
  * (2^b - 1) / max|X|; with signed b-bit codes that range would need b + 1 bits, so the reading taken here is
  * the usual signed one: 2^(b-1) - 1 = 127 steps on each side of zero,

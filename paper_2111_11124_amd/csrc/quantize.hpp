@@ -56,7 +56,7 @@ __device__ __forceinline__ void sr_bits(uint64_t seed, uint64_t counter, float b
 // Eq. (3)-(4) for one element; returns the integer x_bar (unclipped) as a float.
 // Stochastic rounding adds u = bits*2^-16: the product is exact, so the fused form rounds once,
 // exactly like the separate sum v + u.
-// SYM: the scale-only symmetric scheme of the ablation (Sec. 5.3) -- no offset, v = x * r with r = 127 / m, and the
+// SYM: the scale-only symmetric scheme of the ablation (Sec. 5.2) -- no offset, v = x * r with r = 127 / m, and the
 // integer returned is already moved to the stored form's range: max(w, -127) + 128 in [1, 255] (the packing below
 // saturates the upper end and takes the 128 off again), so that the code is clip(w, -127, 127).
 template <bool SR, bool SYM = false> __device__ __forceinline__ float quantize_one(float x, float r, float b, float bits)

@@ -427,7 +427,7 @@ def _attention_case(M, B, H, N, Dh, dtype):
 @pytest.mark.parametrize("dtype", DTYPES, ids=DTYPE_IDS)
 @pytest.mark.parametrize("layout", [(3, 4, 1000), (5, 3, 361), (37, 6, 64), (64, 3, 2401), (1, 1, 77)])
 def test_symmetric_range_update_matches_the_oracle_bit_for_bit(M, layout, dtype):
-    """Symmetric-range running estimates (Sec. 5.3 ablation): first call and two EMA steps, then the codes
+    """Symmetric-range running estimates (Sec. 5.2 ablation): first call and two EMA steps, then the codes
     taken with them."""
     G = layout[1]
     gen = torch.Generator(device="cuda").manual_seed(layout[0] * 31 + layout[2])
@@ -752,7 +752,7 @@ def test_linear_dw_upstream_gradient_with_a_mean(M, mean):
 @pytest.mark.parametrize("dtype", DTYPES, ids=DTYPE_IDS)
 @pytest.mark.parametrize("layout", [(3, 4, 1000), (5, 3, 361), (37, 6, 64), (1, 1, 12345), (7, 5, 3), (3000, 12, 256)])
 def test_scale_only_symmetric_scheme_is_bit_exact(M, layout, dtype):
-    """The ablation's comparison scheme (Sec. 5.3): running scale after a first call and two moving-average steps,
+    """The ablation's comparison scheme (Sec. 5.2): running scale after a first call and two moving-average steps,
     codes in both rounding modes and the de-quantized values, all bit for bit against the oracle; and the fused GELU
     backward fed with these codes through the equivalent (alpha, beta) pair."""
     outer, G, inner = layout

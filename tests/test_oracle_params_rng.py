@@ -151,7 +151,7 @@ def test_fused_forward_constant_group_and_saturation():
     assert a1[0] == 0.0 and b1[0] == 0.0 and a1[1] == np.float32(0.5 * 10.0 + 0.5 * 100.0) and b1[1] == np.float32(-2.5 - 25.0)
 
 
-# ---- symmetric range (Sec. 5.3, asymmetric vs. symmetric quantization) --------------------------------
+# ---- symmetric range (Sec. 5.2, asymmetric vs. symmetric quantization) --------------------------------
 
 def test_symmetric_first_call_is_twice_and_minus_the_largest_magnitude():
     for dtype in (np.float32, np.float16):

@@ -1,5 +1,5 @@
 """Pins for the oracle's scale-only symmetric scheme (the comparison scheme of the ablation "asymmetric vs.
-symmetric quantization", Sec. 5.3): a scale factor only, no offset, zero is a code.
+symmetric quantization", Sec. 5.2): a scale factor only, no offset, zero is a code.
 
 Against what the definition fixes, never the oracle's formula retyped: zero and the whole grid round-trip exactly,
 codes stay in [-127, 127], the error is at most half a step (one step under stochastic rounding), the quantizer is an
