@@ -10,15 +10,17 @@
 // Unlike the Linear layer's operands, both tensors here are contiguous along the contraction (the output column
 // ow, for stride_w = 1), which is what an MFMA operand wants: a lane holds eight consecutive contraction values of
 // one channel.  A kernel tap (kh, kw) only shifts which input row and column meet a given output: kh picks another
-// staged row, kw slides the eight-value window by one element -- taken from the same six LDS words with a byte
-// alignment instruction.  One stage = one output row segment of up to 128 columns: the dy rows of the workgroup's
-// output channels, and for each kh the input row of its input channels, converted once to 16-bit operands as they
-// are written to LDS (pads as zeros).  Every tap of a 3x3 kernel then reuses the same dy fragment: nine MFMAs per
-// fragment read.  Slices of the (b, oh, segment) range are combined in a fixed order by a second kernel.
+// input row, kw slides the eight-value window by one element.  One stage = one output row segment of up to 128
+// columns: the dy rows of the workgroup's 128 output channels and ONE input row (the workgroup's kh) of its 64 input
+// channels, converted once to 16-bit operands as they are written to LDS (pads as zeros).  A lane reads one aligned
+// eight-element chunk per contraction step -- the middle tap's fragment as it lies; the outer taps need the last
+// element of the chunk before and the first of the chunk after, which the other half of the wave holds one step
+// earlier or later (ds_bpermute), then a byte alignment instruction per word.  Each of the three fragments feeds
+// two MFMAs (the wave's two blocks of 32 output channels).  Slices of the (image, row, segment) range and the three
+// kernel rows go to separate workgroups; the slices are combined in a fixed order by a second kernel.
 //
 // This path takes 16-bit tensors, 3x3 kernels with pad_w = 1 and 1x1 kernels with pad_w = 0, stride_w = dil_w = 1 (any
-// row stride, dilation and padding), W and OW multiples of 8;
-// anything else runs the plain kernel at the end of the file.
+// row stride, dilation and padding), W and OW multiples of 8; anything else runs the plain kernel at the end of the file.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -71,13 +73,15 @@ template <> struct CvElem<__bf16> {
     }
 };
 
-// T3 = true:  3x3 kernels with pad_w = 1; a wave owns 32 output x 32 input channels for all nine taps (nine
-//              accumulator tiles), the workgroup 64 x 64 channels.
+// T3 = true:  3x3 kernels with pad_w = 1; a workgroup owns 128 output x 64 input channels and ONE kernel row kh (the three
+//              rows go to three workgroups: a third of the accumulators each, so that several workgroups share a CU and
+//              one's staging and window shifts run while another's MFMAs do); a wave 64 x 32 channels for that row's
+//              three taps (six accumulator tiles; every shifted fragment feeds two MFMAs).
 // T3 = false: 1x1 kernels with pad_w = 0; a wave owns 64 x 64 channels (four tiles), the workgroup 128 x 128.
 // NKS: contraction steps of 16 output columns per stage (a stage is a row segment of 16*NKS columns).
 template <bool T3, int NKS> struct CvCfg {
-    static constexpr int TM = T3 ? 1 : 2, TN = T3 ? 1 : 2;
-    static constexpr int XR = T3 ? 3 : 1;                 // staged input rows (one per kh)
+    static constexpr int TM = 2, TN = T3 ? 1 : 2;
+    static constexpr int XR = 1;                          // staged input rows: the one that the workgroup's kh meets
     static constexpr int COT = 64 * TM, CIT = 64 * TN;
     static constexpr int SEG = 16 * NKS;                  // output columns per stage
     static constexpr int NVA = 2 * NKS;                   // dy vectors (eight columns) per row
@@ -88,19 +92,22 @@ template <bool T3, int NKS> struct CvCfg {
     static constexpr int PX = T3 ? SEG + 16 : SEG + 8;
     static constexpr int A_BYTES = COT * PA * 2;
     static constexpr int X_BYTES = XR * CIT * PX * 2;
-    static constexpr int BUF = A_BYTES + X_BYTES;         // one of the two stage buffers
-    static constexpr int LDS = 2 * BUF;
+    static constexpr int BUF = A_BYTES + X_BYTES;         // the stage buffer
+    static constexpr int LDS = BUF;
     static constexpr int ND = COT * NVA / kCvThreads;     // dy vectors a thread stages
-    static constexpr int NX = (XR * CIT * NVX + kCvThreads - 1) / kCvThreads;   // input vectors, at most
+    static constexpr int NX = (XR * CIT * NVX + kCvThreads - 1) / kCvThreads;   // input vectors per thread
+    static_assert(XR * CIT * NVX >= kCvThreads, "the ragged round wraps around once");
     static_assert(COT * NVA % kCvThreads == 0, "every thread stages the same number of dy vectors");
-    static_assert(LDS <= 160 * 1024, "two stage buffers must fit the LDS of a CU");
+    static_assert(2 * LDS <= 160 * 1024, "two workgroups must fit the LDS of a CU");
 };
 
 // part[split][tap][co][ci] = sum over the split's (b, oh, segment) stages of dy * u,  tap = kh*KW + kw.
-// Two LDS buffers: while stage s is multiplied out of one, stage s+1 -- loaded into registers at the start of s --
-// is converted and written into the other between the MFMAs; one barrier per stage.
+// One LDS stage buffer per workgroup and two or three workgroups per CU: the next stage's vectors are requested before a
+// stage is multiplied, and converted and written to LDS after it (a barrier on either side) -- while one workgroup does
+// that, the others' MFMAs keep the matrix cores busy.  (With one wave per SIMD the vector instructions of a stage and its
+// MFMAs took turns instead of overlapping: 31 % matrix-core time.)
 template <typename E, bool T3, int NKS>
-__global__ __launch_bounds__(kCvThreads, 1) void k_conv_dw(const int8_t *__restrict__ xq, const E *__restrict__ dy, ConvGeom cg,
+__global__ __launch_bounds__(kCvThreads, 2) void k_conv_dw(const int8_t *__restrict__ xq, const E *__restrict__ dy, ConvGeom cg,
                                                            int tiles_co, int tiles_ci, int splits, int stages_per_split,
                                                            int nseg, float *__restrict__ part)
 {
@@ -111,17 +118,20 @@ __global__ __launch_bounds__(kCvThreads, 1) void k_conv_dw(const int8_t *__restr
     const int total = gridDim.x;
     // workgroups that share a slice of the stages run on the same XCD (same L2)
     const int logical = int(blockIdx.x % kCvXcd) * (total / kCvXcd) + int(blockIdx.x / kCvXcd);
+    constexpr int NKH = T3 ? 3 : 1;                       // kernel rows, one workgroup each (neighbours: they share dy in L2)
     const int ntiles = tiles_co * tiles_ci;
-    if (logical >= ntiles * splits) return;
-    const int split = logical / ntiles;
-    const int t = logical - split * ntiles;
+    if (logical >= ntiles * splits * NKH) return;
+    const int kh_w = logical % NKH;
+    const int lt = logical / NKH;
+    const int split = lt / ntiles;
+    const int t = lt - split * ntiles;
     const int tco = t / tiles_ci, tci = t - tco * tiles_ci;
     const int co0 = tco * C::COT, ci0 = tci * C::CIT;
     const int wm = wave >> 1, wn = wave & 1;
     const int nstages = cg.B * cg.OH * nseg;
     const int st_begin = split * stages_per_split;
     const int st_end = min(st_begin + stages_per_split, nstages);
-    constexpr int KH = T3 ? 3 : 1, KW = T3 ? 3 : 1;
+    constexpr int KH = 1, KW = T3 ? 3 : 1;               // taps of this workgroup: one kernel row
 
     cv16f acc[C::TM][C::TN][KH][KW];
 #pragma unroll
@@ -145,12 +155,15 @@ __global__ __launch_bounds__(kCvThreads, 1) void k_conv_dw(const int8_t *__restr
     uint32_t xbits[C::NX];
 #pragma unroll
     for (int n = 0; n < C::NX; ++n) {
-        const int idx = tid + n * kCvThreads;
+        // the threads that the last, ragged round of vectors leaves without one stage one of the first vectors a second
+        // time (same bytes to the same place), so that no load or store of the stage loop is conditional
+        constexpr int kXVecs = C::XR * C::CIT * C::NVX;
+        const int idx = tid + n * kCvThreads < kXVecs ? tid + n * kCvThreads : tid + n * kCvThreads - kXVecs;
         const int row = idx / C::NVX, v = idx - row * C::NVX;
         const int kh = row / C::CIT, cl = row - kh * C::CIT;
-        const bool ok = idx < C::XR * C::CIT * C::NVX && ci0 + cl < cg.Cin;
+        const bool ok = ci0 + cl < cg.Cin;
         xlds[n] = C::A_BYTES + (row * C::PX + v * 8) * 2;
-        xoff[n] = (cl * cg.H + kh * cg.dh) * cg.W + v * 8;
+        xoff[n] = cl * cg.H * cg.W + v * 8;
         xbits[n] = ok ? (1u << v) | (1u << (24 + kh)) : 0x80000000u;
     }
     int dlds[C::ND], doff[C::ND];
@@ -164,12 +177,10 @@ __global__ __launch_bounds__(kCvThreads, 1) void k_conv_dw(const int8_t *__restr
         dbits[n] = co0 + row < cg.Cout ? 1u << v : 0x80000000u;
     }
 
-    // Two register sets: while stage s is multiplied, set (s+1)%2 -- loaded during stage s-1 -- is written to the other LDS
-    // buffer and set s%2 receives stage s+2, so a load has a whole stage to arrive.
-    u32x4 dreg[2][C::ND];
-    u32x2 xreg[2][C::NX];
-    uint32_t xkeep[2] = {0u, 0u};   // bit n: input vector n lies inside the image (elsewhere the forward saw padding: zeros)
-    uint32_t dkeep[2] = {0u, 0u};
+    u32x4 dreg[1][C::ND];
+    u32x2 xreg[1][C::NX];
+    uint32_t xkeep[1] = {0u};       // bit n: input vector n lies inside the image (elsewhere the forward saw padding: zeros)
+    uint32_t dkeep[1] = {0u};
 
     // the coordinates of the stage being loaded, advanced one stage at a time
     int seg = st_begin % nseg;
@@ -198,7 +209,7 @@ __global__ __launch_bounds__(kCvThreads, 1) void k_conv_dw(const int8_t *__restr
             dreg[S][n] = *reinterpret_cast<const u32x4 *>(dbase + uint32_t(in ? doff[n] + ddelta : 0));
             dkeep[S] |= in ? 1u << n : 0u;
         }
-        const int ih0 = oh * cg.sh - cg.ph;
+        const int ih0 = oh * cg.sh - cg.ph + kh_w * cg.dh;
         const char *xbase = reinterpret_cast<const char *>(xq + (int64_t(b) * cg.Cin + ci0) * cg.H * cg.W);
         const int xdelta = ih0 * cg.W + seg0 - (T3 ? 8 : 0);
         uint32_t smask = 0u;                                          // rows, then vectors, of this stage that lie in the image
@@ -223,35 +234,25 @@ __global__ __launch_bounds__(kCvThreads, 1) void k_conv_dw(const int8_t *__restr
         *reinterpret_cast<u32x4 *>(buf + dlds[n]) = u32x4{dreg[S][n][0] & k, dreg[S][n][1] & k, dreg[S][n][2] & k, dreg[S][n][3] & k};
     };
     auto store_x = [&](int S, int n, unsigned char *buf) {
-        if (C::XR * C::CIT * C::NVX % kCvThreads == 0 || tid + n * kCvThreads < C::XR * C::CIT * C::NVX) {
-            uint32_t lo[2], hi[2];
-            CvElem<E>::convert(xreg[S][n][0], lo);
-            CvElem<E>::convert(xreg[S][n][1], hi);
-            const uint32_t k = 0u - ((xkeep[S] >> n) & 1u);
-            *reinterpret_cast<u32x4 *>(buf + xlds[n]) = u32x4{lo[0] & k, lo[1] & k, hi[0] & k, hi[1] & k};
-        }
+        uint32_t lo[2], hi[2];
+        CvElem<E>::convert(xreg[S][n][0], lo);
+        CvElem<E>::convert(xreg[S][n][1], hi);
+        const uint32_t k = 0u - ((xkeep[S] >> n) & 1u);
+        *reinterpret_cast<u32x4 *>(buf + xlds[n]) = u32x4{lo[0] & k, lo[1] & k, hi[0] & k, hi[1] & k};
     };
 
     const int half = lane >> 5, l32 = lane & 31;
-    constexpr int NSLOT = C::ND + C::NX;
-    constexpr int PER = (NSLOT + NKS - 1) / NKS;                      // staging slots per contraction step
-    int st_load = st_begin;                                           // the stage the coordinates (b, oh, seg) stand at
-    // Stage s (s - st_begin of parity P) out of `cur`.  On the way, register set 1-P (stage s+1) goes into `nxt` and set P
-    // is loaded with stage s+2.  Past the end of the slice the coordinates stay on the last stage: its vectors are
-    // loaded and stored once or twice more, into registers and a buffer nobody reads again -- cheaper than a second
-    // code path.
-    auto compute_stage = [&](const unsigned char *cur, unsigned char *nxt, auto parity_tag) {
-        constexpr int P = decltype(parity_tag)::value;
-        if (st_load + 1 < st_end) { advance(); ++st_load; }
-        load_stage(std::integral_constant<int, P>());
+    auto compute_stage = [&](const unsigned char *cur) {
         const unsigned char *xa = cur + C::A_BYTES;
         // T3: chunk c of a row holds input columns seg0 - 8 + 8c ..; output columns k..k+7 (k = 16ks + 8*half) meet, for
         // the taps kw = 0, 1, 2, the elements k+7.., k+8.., k+9..: the middle tap is chunk 2ks + half + 1 as it lies,
         // the outer two also need the last element of the chunk before and the first of the chunk after -- which the
         // other half of the wave holds (one step earlier or later), so each lane reads one chunk per row and step
         // and the halves exchange two words.
-        uint32_t e0[KH][2], e3[KH][2];                                // exchanged words of the previous and the current step
-        u32x4 cnext[KH][C::TN];
+        // Every LDS value is requested at least one whole step before it is used: chunk j is read in step j - 3, its two
+        // outer words are exchanged in step j - 2 (indices below are j + 1, j = -1 .. NKS).
+        u32x4 Cc[KH][NKS + 2];
+        uint32_t X0[KH][NKS + 2], X3[KH][NKS + 2];
         // chunk c of (kh row a, channel tile j) for this lane: a per-lane row address plus a constant
         const unsigned char *xrow[KH][C::TN];
 #pragma unroll
@@ -267,21 +268,28 @@ __global__ __launch_bounds__(kCvThreads, 1) void k_conv_dw(const int8_t *__restr
             return xrow[a][j] + (2 * ks + 1) * 16;
         };
         static_assert(!T3 || C::TN == 1, "the exchange below is written for one input-channel tile per wave");
-        if (T3) {
-#pragma unroll
-            for (int a = 0; a < KH; ++a) {
-                const u32x4 cm1 = *reinterpret_cast<const u32x4 *>(chunk_addr(a, 0, -1));   // only the upper half's matters
-                e3[a][0] = __shfl_xor(cm1[3], 32, 64);
-                e0[a][0] = 0u;
-                cnext[a][0] = *reinterpret_cast<const u32x4 *>(chunk_addr(a, 0, 0));
-                e3[a][1] = __shfl_xor(cnext[a][0][3], 32, 64);
-                e0[a][1] = __shfl_xor(cnext[a][0][0], 32, 64);
-            }
-        }
-        u32x4 anext[C::TM];
+        auto rd = [&](int a, int jj) { Cc[a][jj + 1] = *reinterpret_cast<const u32x4 *>(chunk_addr(a, 0, jj)); };
+        auto ex = [&](int a, int jj) {
+            X0[a][jj + 1] = __shfl_xor(Cc[a][jj + 1][0], 32, 64);
+            X3[a][jj + 1] = __shfl_xor(Cc[a][jj + 1][3], 32, 64);
+        };
+        u32x4 anext[C::TM], bnext[C::TN];
 #pragma unroll
         for (int i = 0; i < C::TM; ++i)
             anext[i] = *reinterpret_cast<const u32x4 *>(cur + ((wm * 32 * C::TM + i * 32 + l32) * C::PA + half * 8) * 2);
+        if (T3) {
+#pragma unroll
+            for (int a = 0; a < KH; ++a) { rd(a, -1); rd(a, 0); rd(a, 1); }
+#pragma unroll
+            for (int a = 0; a < KH; ++a) { ex(a, -1); ex(a, 0); ex(a, 1); }
+#pragma unroll
+            for (int a = 0; a < KH; ++a)
+                if (2 <= NKS) rd(a, 2);
+        } else {
+#pragma unroll
+            for (int j = 0; j < C::TN; ++j) bnext[j] = *reinterpret_cast<const u32x4 *>(chunk_addr(0, j, 0));
+        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
             u32x4 afr[C::TM];
@@ -293,17 +301,18 @@ __global__ __launch_bounds__(kCvThreads, 1) void k_conv_dw(const int8_t *__restr
             }
             if (T3) {
 #pragma unroll
+                for (int a = 0; a < KH; ++a)
+                    if (ks + 3 <= NKS) rd(a, ks + 3);
+#pragma unroll
+                for (int a = 0; a < KH; ++a)
+                    if (ks + 2 <= NKS) ex(a, ks + 2);
+#pragma unroll
                 for (int a = 0; a < KH; ++a) {
-                    const u32x4 c1 = cnext[a][0];
-                    // the chunk of the next step, and its outer words from the other half
-                    cnext[a][0] = *reinterpret_cast<const u32x4 *>(chunk_addr(a, 0, ks + 1));
-                    const uint32_t n3 = __shfl_xor(cnext[a][0][3], 32, 64), n0 = __shfl_xor(cnext[a][0][0], 32, 64);
-                    // lower half: before = other's chunk of the previous step, after = other's chunk of this step;
-                    // upper half: before = other's chunk of this step, after = other's chunk of the next step
-                    const uint32_t before = half ? e3[a][1] : e3[a][0];
-                    const uint32_t after = half ? n0 : e0[a][1];
-                    e3[a][0] = e3[a][1]; e3[a][1] = n3;
-                    e0[a][0] = e0[a][1]; e0[a][1] = n0;
+                    const u32x4 c1 = Cc[a][ks + 1];
+                    // lower half: before = the other half's chunk of the previous step, after = its chunk of this step;
+                    // upper half: before = the other half's chunk of this step, after = its chunk of the next step
+                    const uint32_t before = half ? X3[a][ks + 1] : X3[a][ks];
+                    const uint32_t after = half ? X0[a][ks + 2] : X0[a][ks + 1];
                     u32x4 f0, f2;
                     f0[0] = __builtin_amdgcn_alignbyte(c1[0], before, 2);
                     f0[1] = __builtin_amdgcn_alignbyte(c1[1], c1[0], 2);
@@ -313,56 +322,58 @@ __global__ __launch_bounds__(kCvThreads, 1) void k_conv_dw(const int8_t *__restr
                     f2[1] = __builtin_amdgcn_alignbyte(c1[2], c1[1], 2);
                     f2[2] = __builtin_amdgcn_alignbyte(c1[3], c1[2], 2);
                     f2[3] = __builtin_amdgcn_alignbyte(after, c1[3], 2);
-                    acc[0][0][a][0] = CvElem<E>::mfma(afr[0], f0, acc[0][0][a][0]);
-                    acc[0][0][a][KW > 1 ? 1 : 0] = CvElem<E>::mfma(afr[0], c1, acc[0][0][a][KW > 1 ? 1 : 0]);
-                    acc[0][0][a][KW > 2 ? 2 : 0] = CvElem<E>::mfma(afr[0], f2, acc[0][0][a][KW > 2 ? 2 : 0]);
+#pragma unroll
+                    for (int i = 0; i < C::TM; ++i) {
+                        acc[i][0][a][0] = CvElem<E>::mfma(afr[i], f0, acc[i][0][a][0]);
+                        acc[i][0][a][KW > 1 ? 1 : 0] = CvElem<E>::mfma(afr[i], c1, acc[i][0][a][KW > 1 ? 1 : 0]);
+                        acc[i][0][a][KW > 2 ? 2 : 0] = CvElem<E>::mfma(afr[i], f2, acc[i][0][a][KW > 2 ? 2 : 0]);
+                    }
                 }
             } else {
+                u32x4 bfr[C::TN];
 #pragma unroll
                 for (int j = 0; j < C::TN; ++j) {
-                    const u32x4 bfr = *reinterpret_cast<const u32x4 *>(chunk_addr(0, j, ks));
-#pragma unroll
-                    for (int i = 0; i < C::TM; ++i) acc[i][j][0][0] = CvElem<E>::mfma(afr[i], bfr, acc[i][j][0][0]);
+                    bfr[j] = bnext[j];
+                    if (ks + 1 < NKS) bnext[j] = *reinterpret_cast<const u32x4 *>(chunk_addr(0, j, ks + 1));
                 }
-            }
 #pragma unroll
-            for (int q = 0; q < PER; ++q) {
-                const int slot = ks * PER + q;
-                if (slot < C::ND) store_d(1 - P, slot, nxt);
-                else if (slot < NSLOT) store_x(1 - P, slot - C::ND, nxt);
+                for (int j = 0; j < C::TN; ++j)
+#pragma unroll
+                    for (int i = 0; i < C::TM; ++i) acc[i][j][0][0] = CvElem<E>::mfma(afr[i], bfr[j], acc[i][j][0][0]);
             }
-            __builtin_amdgcn_sched_barrier(0);     // keep each step's reads, conversions and stores with its MFMAs
+            __builtin_amdgcn_sched_barrier(0);     // keep each step's reads and window shifts with its MFMAs
         }
     };
 
     if (st_begin < st_end) {
-        unsigned char *const buf0 = cv_lds, *const buf1 = cv_lds + C::BUF;
-        load_stage(std::integral_constant<int, 0>());                 // the first stage, straight into its buffer
+        auto store_all = [&]() {
 #pragma unroll
-        for (int n = 0; n < C::ND; ++n) store_d(0, n, buf0);
+            for (int n = 0; n < C::ND; ++n) store_d(0, n, cv_lds);
 #pragma unroll
-        for (int n = 0; n < C::NX; ++n) store_x(0, n, buf0);
-        if (st_load + 1 < st_end) { advance(); ++st_load; }
-        load_stage(std::integral_constant<int, 1>());                 // the second, into the set the first stage stores
+            for (int n = 0; n < C::NX; ++n) store_x(0, n, cv_lds);
+        };
+        load_stage(std::integral_constant<int, 0>());
+        store_all();
         __syncthreads();
-        // one barrier per stage: the next stage is complete in the other buffer, and every wave is done with this one
-        int st = st_begin;
-        for (; st + 1 < st_end; st += 2) {
-            compute_stage(buf0, buf1, std::integral_constant<int, 0>());
-            __syncthreads();
-            compute_stage(buf1, buf0, std::integral_constant<int, 1>());
+        // the last stage is peeled off so that the loop has a single path
+        for (int st = st_begin; st + 1 < st_end; ++st) {
+            advance();
+            load_stage(std::integral_constant<int, 0>());   // in flight while this stage is multiplied
+            compute_stage(cv_lds);
+            __syncthreads();                                  // every wave is done reading this stage
+            store_all();
             __syncthreads();
         }
-        if (st < st_end) compute_stage(buf0, buf1, std::integral_constant<int, 0>());
+        compute_stage(cv_lds);
     }
 
     // lane l, register v of a 32x32 tile -> row (output channel) 8*(v/4) + 4*(l/32) + v%4, column (input channel) l%32
-    constexpr int ntap = KH * KW;
+    constexpr int ntap = NKH * KW;
 #pragma unroll
     for (int a = 0; a < KH; ++a)
 #pragma unroll
         for (int c = 0; c < KW; ++c) {
-            float *P = part + (int64_t(split) * ntap + (a * KW + c)) * cg.Cout * cg.Cin;
+            float *P = part + (int64_t(split) * ntap + (kh_w * KW + c)) * cg.Cout * cg.Cin;
 #pragma unroll
             for (int i = 0; i < C::TM; ++i)
 #pragma unroll
@@ -530,14 +541,15 @@ static CvPlan cv_plan(const ConvGeom &cg, mesa_dtype dt)
     if (!p.fast) return p;
     p.taps3 = k3;
     p.nks = cg.OW <= 32 ? 2 : cg.OW <= 64 ? 4 : 8;
-    const int cot = p.taps3 ? 64 : 128, cit = p.taps3 ? 64 : 128;
+    const int cot = 128, cit = p.taps3 ? 64 : 128;
     p.tiles_co = int(ceil_div(cg.Cout, cot));
     p.tiles_ci = int(ceil_div(cg.Cin, cit));
     p.nseg = int(ceil_div(cg.OW, 16 * p.nks));
     const int64_t nstages = int64_t(cg.B) * cg.OH * p.nseg;
-    const int64_t tiles = int64_t(p.tiles_co) * p.tiles_ci;
-    // one workgroup per CU and round, about two rounds; slices of at least eight stages, at most 64 slices
-    int64_t splits = ceil_div(512, tiles);
+    const int64_t tiles = int64_t(p.tiles_co) * p.tiles_ci * (p.taps3 ? 3 : 1);
+    // two workgroups per CU: as many slices as fill one such round of the chip without starting a second (a round and
+    // an eighth costs two rounds); slices of at least eight stages, at most 64 slices
+    int64_t splits = 512 / tiles;
     if (splits > 64) splits = 64;
     if (splits > ceil_div(nstages, 8)) splits = ceil_div(nstages, 8);
     if (splits < 1) splits = 1;
