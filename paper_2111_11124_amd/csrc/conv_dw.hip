@@ -407,27 +407,44 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_valid_sums(const E *__restr
         for (int c = 0; c < 3; ++c) acc[a][c] = 0.0f;
     for (int b = b0; b < b1; ++b) {
         const E *plane = dy + (int64_t(b) * cg.Cout + co) * cg.OH * cg.OW;
-        for (int idx = threadIdx.x; idx < vec_per_img; idx += kCvThreads) {
-            const int oh = idx / vec_per_row, ow0 = (idx - oh * vec_per_row) * 8;
-            float f[8];
-            Store<E>::unpack(*reinterpret_cast<const u32x4 *>(plane + int64_t(oh) * cg.OW + ow0), f);
-            float cs[3] = {0.0f, 0.0f, 0.0f}, all = 0.0f;
+        // four vectors per thread and round, requested together
+        for (int base = 0; base < vec_per_img; base += 4 * kCvThreads) {
+            u32x4 raw[4];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                all += f[j];
-#pragma unroll
-                for (int c = 0; c < 3; ++c) {
-                    const int iw = ow0 + j - cg.pw + c;
-                    cs[c] += (c < cg.KW && iw >= 0 && iw < cg.W) ? f[j] : 0.0f;
-                }
+            for (int u = 0; u < 4; ++u) {
+                const int idx = base + u * kCvThreads + int(threadIdx.x);
+                raw[u] = idx < vec_per_img ? *reinterpret_cast<const u32x4 *>(plane + int64_t(idx) * 8) : u32x4{0u, 0u, 0u, 0u};
             }
-            tot += all;
 #pragma unroll
-            for (int a = 0; a < 3; ++a) {
-                const int ih = oh * cg.sh - cg.ph + a * cg.dh;
-                if (a < cg.KH && ih >= 0 && ih < cg.H) {
+            for (int u = 0; u < 4; ++u) {
+                const int idx = base + u * kCvThreads + int(threadIdx.x);
+                if (idx >= vec_per_img) continue;
+                const int oh = idx / vec_per_row, ow0 = (idx - oh * vec_per_row) * 8;
+                float f[8];
+                Store<E>::unpack(raw[u], f);
+                float cs[3] = {0.0f, 0.0f, 0.0f}, all = 0.0f;
 #pragma unroll
-                    for (int c = 0; c < 3; ++c) acc[a][c] += cs[c];
+                for (int j = 0; j < 8; ++j) all += f[j];
+                if (ow0 - cg.pw >= 0 && ow0 + 7 - cg.pw + 2 < cg.W) {   // every tap of every element lies inside: all but a row's ends
+#pragma unroll
+                    for (int c = 0; c < 3; ++c) cs[c] = c < cg.KW ? all : 0.0f;
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+#pragma unroll
+                        for (int c = 0; c < 3; ++c) {
+                            const int iw = ow0 + j - cg.pw + c;
+                            cs[c] += (c < cg.KW && iw >= 0 && iw < cg.W) ? f[j] : 0.0f;
+                        }
+                }
+                tot += all;
+#pragma unroll
+                for (int a = 0; a < 3; ++a) {
+                    const int ih = oh * cg.sh - cg.ph + a * cg.dh;
+                    if (a < cg.KH && ih >= 0 && ih < cg.H) {
+#pragma unroll
+                        for (int c = 0; c < 3; ++c) acc[a][c] += cs[c];
+                    }
                 }
             }
         }
@@ -460,26 +477,50 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_finish(const float *__restr
                                                             const float *__restrict__ beta, float centre, float *__restrict__ dW,
                                                             float *__restrict__ db)
 {
+    // A thread owns one (co, ci) pair: its reads of a tap's plane are coalesced; its ntap results are consecutive in dW, so
+    // the workgroup's 256 * ntap results go through LDS and leave as one contiguous run (up to nine taps; more only
+    // occur with an empty batch, where plain strided stores of zeros will do).
+    __shared__ float tile[kCvThreads * 9];
     const int64_t idx = int64_t(blockIdx.x) * kCvThreads + threadIdx.x;
     const int64_t plane = int64_t(cg.Cout) * cg.Cin;
-    if (idx >= plane) return;
-    const int co = int(idx / cg.Cin), ci = int(idx - int64_t(co) * cg.Cin);
     const int ntap = cg.KH * cg.KW;
-    const int g = ci / per;
-    const float sg = alpha[g] / 255.0f;
-    const float off = fmaf(centre, sg, beta[g]);
-    for (int a = 0; a < cg.KH; ++a)
-        for (int c = 0; c < cg.KW; ++c) {
-            const int tap = a * cg.KW + c;
-            float s1 = 0.0f, v = 0.0f;
-            for (int sp = 0; sp < splits; ++sp) s1 += part[(int64_t(sp) * ntap + tap) * plane + idx];
-            for (int pt = 0; pt < parts; ++pt) v += V[(int64_t(pt) * cg.Cout + co) * 10 + a * 3 + c];
-            dW[idx * ntap + tap] = fmaf(sg, s1, off * v);
+    const bool staged = ntap <= 9;
+    const bool live = idx < plane;
+    if (live) {
+        const int co = int(idx / cg.Cin), ci = int(idx - int64_t(co) * cg.Cin);
+        const int g = ci / per;
+        const float sg = alpha[g] / 255.0f;
+        const float off = fmaf(centre, sg, beta[g]);
+        if (staged) {       // the taps' sums side by side: nine loads in flight per slice instead of one
+            float s1[9];
+#pragma unroll
+            for (int t = 0; t < 9; ++t) s1[t] = 0.0f;
+            for (int sp = 0; sp < splits; ++sp)
+#pragma unroll
+                for (int t = 0; t < 9; ++t)
+                    if (t < ntap) s1[t] += part[(int64_t(sp) * ntap + t) * plane + idx];
+#pragma unroll
+            for (int t = 0; t < 9; ++t)
+                if (t < ntap) {
+                    const int a = t / cg.KW, c = t - a * cg.KW;
+                    float v = 0.0f;
+                    for (int pt = 0; pt < parts; ++pt) v += V[(int64_t(pt) * cg.Cout + co) * 10 + a * 3 + c];
+                    tile[threadIdx.x * ntap + t] = splits == 0 ? 0.0f : fmaf(sg, s1[t], off * v);   // no slices: an empty batch
+                }
+        } else {
+            for (int tap = 0; tap < ntap; ++tap) dW[idx * ntap + tap] = 0.0f;   // only reached with an empty batch
         }
-    if (db && ci == 0) {
-        float v = 0.0f;
-        for (int pt = 0; pt < parts; ++pt) v += V[(int64_t(pt) * cg.Cout + co) * 10 + 9];
-        db[co] = v;
+        if (db && ci == 0) {
+            float v = 0.0f;
+            for (int pt = 0; pt < parts; ++pt) v += V[(int64_t(pt) * cg.Cout + co) * 10 + 9];
+            db[co] = v;
+        }
+    }
+    if (staged) {
+        __syncthreads();
+        const int64_t first = int64_t(blockIdx.x) * kCvThreads;
+        const int64_t count = (plane - first < kCvThreads ? plane - first : kCvThreads) * ntap;
+        for (int k = threadIdx.x; k < count; k += kCvThreads) dW[first * ntap + k] = tile[k];
     }
 }
 
