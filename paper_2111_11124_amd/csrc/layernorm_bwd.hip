@@ -368,7 +368,9 @@ static LnPlan ln_plan(int64_t M, int64_t D, mesa_dtype dt)
         p.vpl = vpr <= 64 ? 1 : 2;
         const int64_t block_rows = (kThreads / 64) * kLnRowsInFlight * (64 / p.lpr);   // rows a workgroup has in flight
         const int64_t wgs = ceil_div(M, block_rows);
-        const int64_t resident = 256 * ln_rows_wg_per_cu(size_t(dtype_bytes(dt)), p.vpl);   // one round of workgroups
+        // one round of workgroups: every workgroup writes 2 D partial sums, and two / four / eight rounds' worth measured
+        // 0.49 / 0.41 / 0.32 against 0.54 of the HBM peak (768-wide rows)
+        const int64_t resident = 256 * ln_rows_wg_per_cu(size_t(dtype_bytes(dt)), p.vpl);
         p.grid = int(wgs < resident ? wgs : resident);
         return p;
     }
