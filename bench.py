@@ -585,6 +585,38 @@ def bandwidth_probes(m):
     return out
 
 
+def mfma_probes(m):
+    """Untimed extras: the rate at which this GPU sustains the weight gradient's matrix-core instruction stream with the
+    operands in registers, read from LDS, and with the tile's operand movement beside it (mesa_mfma_probe; one workgroup
+    of four waves per CU, 640 contraction steps a launch).  `first_launches` is the median of the first 10 launches after
+    an idle second, `sustained` the median of launches 200..299 of an unbroken sequence (the power limit has set in)."""
+    steps = 640
+    flops = m.MFMA_PROBE_WAVES * steps * m.MFMA_PROBE_FLOPS_PER_STEP
+    sink = torch.empty(65536, dtype=torch.float32, device="cuda")
+    gen = torch.Generator(device="cuda").manual_seed(77)
+    feed = torch.randn(8 << 20, device="cuda", generator=gen).half()        # 16 MiB: 2 MiB per XCD, within its L2
+    out = {}
+    for form, name in ((0, "operands_in_registers"), (1, "operands_from_lds"), (2, "operands_from_lds_and_tile_loads")):
+        torch.cuda.synchronize()
+        time.sleep(1.0)
+        evs = []
+        for i in range(300):
+            e0, e1 = m.Event(), m.Event()
+            e0.record()
+            m.mesa_mfma_probe(form, steps, feed if form == 2 else None, sink)
+            e1.record()
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        ms = [a.elapsed_ms(b) for a, b in evs]
+        first, sust = statistics.median(ms[:10]), statistics.median(ms[200:])
+        out[name] = {"first_launches": {"ms": round(first, 5), "tflops": round(flops / (first * 1e-3) / 1e12, 1)},
+                     "sustained": {"ms": round(sust, 5), "tflops": round(flops / (sust * 1e-3) / 1e12, 1),
+                                   "mfma_frac": round(flops / (sust * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4)}}
+    out["note"] = ("v_mfma_f32_32x32x16_f16 on 128 x 128 accumulator tiles per wave, pseudo-random binary16 operands; "
+                   f"{flops / 1e9:.1f} GFLOP per launch; the ceiling the weight gradient's `mfma_frac` is to be read against")
+    return {"mfma_probe": out}
+
+
 def traffic_from_profile(spec, call):
     """HBM bytes per launch of the kernel behind `call`, from the rocprofv3 --pmc summary committed for this workload
     (FETCH_SIZE / WRITE_SIZE scaled by the copy kernel's reading); None when no summary covers it."""
@@ -651,7 +683,7 @@ def main():
                                                              "single-pass variant, probes)")
     ap.add_argument("--only-dw", action="store_true", help="run only the configuration's weight-gradient calls, back to back, and "
                                                            "print their figures (a measurement helper, not the benchmark line)")
-    ap.add_argument("--only-leg", default=None, choices=["attention", "conv", "four_bit", "symmetric", "layer_forwards"],
+    ap.add_argument("--only-leg", default=None, choices=["attention", "conv", "four_bit", "symmetric", "layer_forwards", "mfma_probe"],
                     help="run one of the legs outside the headline alone and print its figures (a measurement helper: the "
                          "launch sequence the per-kernel counter summaries in profiles/ are taken on)")
     ap.add_argument("--config", type=int, default=HEADLINE_CONFIG, choices=[2, 3, 4, 5],
@@ -680,7 +712,7 @@ def main():
         return
     if args.only_leg:
         leg = {"attention": attention_matmul_leg, "conv": conv_dw_leg, "four_bit": four_bit_leg, "symmetric": symmetric_leg,
-               "layer_forwards": layer_forward_legs}[args.only_leg]
+               "layer_forwards": layer_forward_legs, "mfma_probe": lambda m, spec, steps: mfma_probes(m)}[args.only_leg]
         print(json.dumps({"only_leg": args.only_leg, "config": spec.name, "result": leg(m, spec, args.steps or 20)}))
         return
     nblocks = BLOCKS[number]
@@ -785,6 +817,7 @@ def main():
         del path
         torch.cuda.empty_cache()
         out.update(bandwidth_probes(m))
+        out.update(mfma_probes(m))
         leg_steps = 20
         out["attention_matmul_bwd"] = attention_matmul_leg(m, spec, leg_steps if number != 5 else 5)
         out.update(layer_forward_legs(m, spec, leg_steps))

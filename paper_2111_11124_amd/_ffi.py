@@ -23,7 +23,7 @@ EXPORTS = [
     "mesa_update_running_params", "mesa_update_running_params_sym", "mesa_update_running_params_fixed_beta", "mesa_update_running_scale_sym", "mesa_quantize_sym", "mesa_dequantize_sym", "mesa_update_running_params_static", "mesa_static_scratch_bytes", "mesa_quantize_headwise", "mesa_quantize_update_fused", "mesa_gelu_fwd_q", "mesa_softmax_fwd_q", "mesa_layernorm_fwd_q", "mesa_dequantize", "mesa_quantize_headwise_b4", "mesa_dequantize_b4", "mesa_gelu_bwd_q_b4", "mesa_softmax_bwd_q",
     "mesa_gelu_bwd_q", "mesa_relu_bwd_q", "mesa_layernorm_bwd_q", "mesa_linear_dw_q", "mesa_conv2d_dw_q", "mesa_conv2d_dw_q_workspace_bytes", "mesa_attn_av_bwd_q", "mesa_attn_qk_bwd_q",
     "mesa_workspace_bytes",
-    "mesa_status_string", "mesa_version", "mesa_stream_copy", "mesa_stream_read", "mesa_stream_fill", "mesa_event_create", "mesa_event_record",
+    "mesa_status_string", "mesa_version", "mesa_stream_copy", "mesa_stream_read", "mesa_stream_fill", "mesa_mfma_probe", "mesa_event_create", "mesa_event_record",
     "mesa_event_elapsed_ms", "mesa_event_destroy",
 ]
 
@@ -94,6 +94,7 @@ def lib() -> C.CDLL:
         L.mesa_stream_copy.argtypes = [_vp, _vp, _sz, _vp]
         L.mesa_stream_read.argtypes = [_vp, _sz, _vp, _vp]
         L.mesa_stream_fill.argtypes = [_vp, _sz, C.c_uint32, _vp]
+        L.mesa_mfma_probe.argtypes = [C.c_int, _i64, _vp, _sz, _vp, _vp]
         L.mesa_event_create.argtypes = [C.POINTER(_vp)]
         L.mesa_event_record.argtypes = [_vp, _vp]
         L.mesa_event_elapsed_ms.argtypes = [_vp, _vp, C.POINTER(_f32)]
@@ -316,6 +317,15 @@ def mesa_stream_read(src, nbytes, sink):
 
 def mesa_stream_fill(dst, nbytes, word=0):
     _check(lib().mesa_stream_fill(_ptr(dst), int(nbytes), int(word), _stream()), "mesa_stream_fill")
+
+
+MFMA_PROBE_WAVES = 256 * 4          # per launch
+MFMA_PROBE_FLOPS_PER_STEP = 16 * 2 * 32 * 32 * 16   # per wave
+
+
+def mesa_mfma_probe(form, steps, feed, sink):
+    nbytes = 0 if feed is None else feed.numel() * feed.element_size()
+    _check(lib().mesa_mfma_probe(int(form), int(steps), _ptr(feed), nbytes, _ptr(sink), _stream()), "mesa_mfma_probe")
 
 
 class Event:

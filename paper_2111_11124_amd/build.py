@@ -12,7 +12,7 @@ CSRC = PKG / "csrc"
 INCLUDE = PKG.parent / "include"
 LIB = PKG / "libmesa.so"
 OBJ = PKG / "_build"
-SOURCES = ["stream_kernels.hip", "softmax_fwd.hip", "softmax_bwd.hip", "layernorm_fwd.hip", "layernorm_bwd.hip", "linear_dw.hip", "attn_matmul_bwd.hip", "lowbit.hip", "conv_dw.hip"]
+SOURCES = ["stream_kernels.hip", "softmax_fwd.hip", "softmax_bwd.hip", "layernorm_fwd.hip", "layernorm_bwd.hip", "linear_dw.hip", "attn_matmul_bwd.hip", "lowbit.hip", "conv_dw.hip", "mfma_probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # -ffp-contract=off: no implicit fused multiply-adds anywhere; kernels that may fuse call fmaf.
