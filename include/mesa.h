@@ -260,9 +260,10 @@ mesa_status mesa_gelu_bwd_q_b4(const uint8_t *q4, mesa_layout L, const float *al
  * head-wise parameters alpha[H], beta[H].  Per row:  d = sum_j dy_j*y_hat_j,
  * dx_j = y_hat_j * (dy_j - d), accumulated in binary32.
  * yq: int8 (in); dy, dx: [B*H*rows*cols] of dt (in / out); dx may alias dy.
- * Limits: rows of up to 256 elements: any length; longer rows: R*cols <= 8192 for R = 8/gcd(cols, 8) (so
- * cols <= 8192 when cols % 8 == 0, cols <= 1024 when cols is odd); H <= 1024 and B*H*rows < 2^31; else
- * MESA_ERR_UNSUPPORTED.
+ * Limits: rows, cols, H and B*H*rows below 2^31, else MESA_ERR_UNSUPPORTED.  The tiled kernels take rows of up
+ * to 256 elements of any length, and longer rows with R*cols <= 8192 for R = 8/gcd(cols, 8) (cols <= 8192 when
+ * cols % 8 == 0, cols <= 1024 when cols is odd), at H <= 1024; every other shape runs a plain kernel, one
+ * workgroup per row, at about a third of their rate.
  */
 mesa_status mesa_softmax_bwd_q(const int8_t *yq, int64_t B, int64_t H, int64_t rows, int64_t cols,
                                const float *alpha, const float *beta, const void *dy, void *dx,
@@ -293,7 +294,9 @@ mesa_status mesa_relu_bwd_q(const int8_t *xq, mesa_layout L, const float *alpha,
  *   dgamma_j = sum_rows dy*xn,  dbeta_j = sum_rows dy        (binary32, fixed summation order)
  * gamma: [D] of dt.  dx: (M, D) of dt, may alias dy.  dgamma, dbeta: [D] binary32 (overwritten).
  * ws: MESA_OP_LAYERNORM_BWD_Q bytes.
- * Limits: D % 8 == 0, (D/G) % 8 == 0, D <= 4096, else MESA_ERR_UNSUPPORTED.
+ * Limit: D < 2^31, else MESA_ERR_UNSUPPORTED.  The vector kernels take D % 8 == 0, (D/G) % 8 == 0, D <= 4096;
+ * every other row length runs two plain kernels (element by element, no workspace needed; the column sums
+ * with one lane per column), far below their rate.
  */
 mesa_status mesa_layernorm_bwd_q(const int8_t *xq, int64_t M, int64_t D, int64_t G,
                                  const float *alpha, const float *beta,

@@ -383,6 +383,78 @@ static LnPlan ln_plan(int64_t M, int64_t D, mesa_dtype dt)
     return p;
 }
 
+// ---- rows the vector kernels cannot take (D or D/G no multiple of 8, D above kLnMaxD): element by element ---------------
+// dx: one workgroup per row, the row read twice (the two row sums, then the result); any D.  dx may alias dy: a thread
+// writes only elements it has just read, after both sums are complete.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_layernorm_bwd_plain_dx(const int8_t *__restrict__ xq, const void *dy, void *dx,
+                                                                     const void *__restrict__ gamma, const float *__restrict__ mean,
+                                                                     const float *__restrict__ rstd, const float *__restrict__ alpha,
+                                                                     const float *__restrict__ beta, int64_t M, uint32_t D, uint32_t dpg,
+                                                                     float inv_D)
+{
+    __shared__ float p1[kThreads / 64], p2[kThreads / 64];
+    for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
+        const float mu = mean[row], rs = rstd[row];
+        const int64_t e0 = row * int64_t(D);
+        float s1 = 0.0f, s2 = 0.0f;
+        for (uint32_t j = threadIdx.x; j < D; j += kThreads) {
+            const uint32_t g = j / dpg;
+            const float xn = (fmaf(code_to_float(xq[e0 + j]), alpha[g] / 255.0f, beta[g]) - mu) * rs;
+            const float gg = Store<T>::load1(dy, e0 + j) * Store<T>::load1(gamma, j);
+            s1 += gg;
+            s2 = fmaf(gg, xn, s2);
+        }
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) { s1 += __shfl_xor(s1, m); s2 += __shfl_xor(s2, m); }
+        if ((threadIdx.x & 63) == 0) { p1[threadIdx.x >> 6] = s1; p2[threadIdx.x >> 6] = s2; }
+        __syncthreads();
+        const float c1 = ((p1[0] + p1[1]) + (p1[2] + p1[3])) * inv_D, c2 = ((p2[0] + p2[1]) + (p2[2] + p2[3])) * inv_D;
+        for (uint32_t j = threadIdx.x; j < D; j += kThreads) {
+            const uint32_t g = j / dpg;
+            const float xn = (fmaf(code_to_float(xq[e0 + j]), alpha[g] / 255.0f, beta[g]) - mu) * rs;
+            const float gg = Store<T>::load1(dy, e0 + j) * Store<T>::load1(gamma, j);
+            Store<T>::store1(dx, e0 + j, rs * (gg - c1 - xn * c2));
+        }
+        __syncthreads();                                   // the next row's sums reuse p1, p2
+    }
+}
+
+// dgamma, dbeta: a workgroup takes 64 columns; its four waves walk the rows r = wave, wave + 4, .. in order, a lane per
+// column (consecutive lanes read consecutive elements), and the four partial sums are added in a fixed order.  Runs
+// BEFORE the dx kernel, so that dx may alias dy.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_layernorm_bwd_plain_cols(const int8_t *__restrict__ xq, const void *__restrict__ dy,
+                                                                       const float *__restrict__ mean, const float *__restrict__ rstd,
+                                                                       const float *__restrict__ alpha, const float *__restrict__ beta,
+                                                                       int64_t M, uint32_t D, uint32_t dpg, float *__restrict__ dgamma,
+                                                                       float *__restrict__ dbeta)
+{
+    __shared__ float sg[kThreads / 64][64], sb[kThreads / 64][64];
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t c = blockIdx.x * 64 + lane;
+    float ag = 0.0f, ab = 0.0f;
+    if (c < D) {
+        const uint32_t g = c / dpg;
+        const float st = alpha[g] / 255.0f, b = beta[g];
+        for (int64_t r = wave; r < M; r += kThreads / 64) {
+            const float d = Store<T>::load1(dy, r * int64_t(D) + c);
+            const float xn = (fmaf(code_to_float(xq[r * int64_t(D) + c]), st, b) - mean[r]) * rstd[r];
+            ag = fmaf(d, xn, ag);
+            ab += d;
+        }
+    }
+    sg[wave][lane] = ag;
+    sb[wave][lane] = ab;
+    __syncthreads();
+    if (wave == 0 && c < D) {
+        dgamma[c] = (sg[0][lane] + sg[1][lane]) + (sg[2][lane] + sg[3][lane]);
+        dbeta[c] = (sb[0][lane] + sb[1][lane]) + (sb[2][lane] + sb[3][lane]);
+    }
+}
+
+static bool ln_vector_path(int64_t D, int64_t G) { return D % kVec == 0 && (D / G) % kVec == 0 && D <= kLnMaxD; }
+
 size_t layernorm_ws_bytes(int64_t M, int64_t D)
 {
     if (M <= 0 || D <= 0 || D > kLnMaxD || D % kVec != 0) return 16;
@@ -406,11 +478,24 @@ extern "C" MESA_EXPORT mesa_status mesa_layernorm_bwd_q(const int8_t *xq, int64_
     if (!aligned16(xq) || !aligned16(dy) || !aligned16(dx) || !aligned16(gamma) || !aligned4(alpha) || !aligned4(beta) ||
         !aligned4(mean) || !aligned4(rstd) || !aligned4(dgamma) || !aligned4(dbeta))
         return MESA_ERR_INVALID_ARG;
-    if (D % kVec != 0 || (D / G) % kVec != 0 || D > kLnMaxD) return MESA_ERR_UNSUPPORTED;
+    if (D >= (int64_t(1) << 31)) return MESA_ERR_UNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!ln_vector_path(D, G)) {                           // element by element, no workspace
+        const unsigned grid_rows = unsigned(M < (int64_t(1) << 20) ? M : (int64_t(1) << 20));
+#define MESA_LAUNCH_LN_PLAIN(T) \
+    do { \
+        hipLaunchKernelGGL((k_layernorm_bwd_plain_cols<T>), dim3(unsigned(ceil_div(D, 64))), dim3(kThreads), 0, s, xq, dy, mean, rstd, \
+                           alpha, beta, M, uint32_t(D), uint32_t(D / G), dgamma, dbeta); \
+        hipLaunchKernelGGL((k_layernorm_bwd_plain_dx<T>), dim3(grid_rows), dim3(kThreads), 0, s, xq, dy, dx, gamma, mean, rstd, alpha, \
+                           beta, M, uint32_t(D), uint32_t(D / G), 1.0f / float(D)); \
+    } while (0)
+        MESA_FOR_DTYPE(dt, MESA_LAUNCH_LN_PLAIN);
+#undef MESA_LAUNCH_LN_PLAIN
+        return launch_status();
+    }
     if (!ws || !aligned16(ws) || ws_bytes < layernorm_ws_bytes(M, D)) return MESA_ERR_WORKSPACE;
     const LnPlan p = ln_plan(M, D, dt);
     FastDiv dvpr = make_fastdiv(uint32_t(D / kVec)), dvpg = make_fastdiv(uint32_t(D / G / kVec));
-    hipStream_t s = static_cast<hipStream_t>(stream);
     float *part = static_cast<float *>(ws);
     const float inv_D = 1.0f / float(D);
 #define MESA_LAUNCH_ROWS(T, LPR_, VPL_) \

@@ -402,6 +402,37 @@ __global__ __launch_bounds__(kThreads, kSbRowWaves) void k_softmax_bwd_rows(cons
     }
 }
 
+// Rows the tiled kernels cannot take (eight rows of an odd length above 1024 do not fit a tile, more than
+// kSmMaxHeads heads, rows shorter than a vector next to many heads): one workgroup per row, element by element, the
+// row read twice -- once for d = sum_j dy_j * y_hat_j (per-thread sums in a fixed order, then the wave's lanes, then
+// the four waves), once more for dx_j = y_hat_j * (dy_j - d).  Any length; about a third of the tiled kernels' rate.
+// dx may alias dy: a thread writes only the elements it has just read, and every sum is complete before the first write.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_softmax_bwd_plain(const int8_t *__restrict__ yq, const void *dy, void *dx, int64_t total_rows,
+                                                                uint32_t cols, uint32_t rows, uint32_t heads,
+                                                                const float *__restrict__ alpha, const float *__restrict__ beta)
+{
+    __shared__ float part[kThreads / 64];
+    for (int64_t row = blockIdx.x; row < total_rows; row += gridDim.x) {
+        const uint32_t h = uint32_t((row / rows) % heads);
+        const float s = alpha[h] / 255.0f, off = fmaf(128.0f, s, beta[h]);   // y_hat = s * q + off with q the signed code
+        const int64_t e0 = row * int64_t(cols);
+        float d = 0.0f;
+        for (uint32_t j = threadIdx.x; j < cols; j += kThreads)
+            d = fmaf(Store<T>::load1(dy, e0 + j), fmaf(float(int(yq[e0 + j])), s, off), d);
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) d += __shfl_xor(d, m);
+        if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = d;
+        __syncthreads();
+        d = (part[0] + part[1]) + (part[2] + part[3]);
+        for (uint32_t j = threadIdx.x; j < cols; j += kThreads) {
+            const float yh = fmaf(float(int(yq[e0 + j])), s, off);
+            Store<T>::store1(dx, e0 + j, yh * (Store<T>::load1(dy, e0 + j) - d));
+        }
+        __syncthreads();                                   // the next row's sums reuse `part`
+    }
+}
+
 struct SbPlan {
     bool ok;
     SrShape sh;
@@ -440,10 +471,20 @@ extern "C" MESA_EXPORT mesa_status mesa_softmax_bwd_q(const int8_t *yq, int64_t 
     if (!yq || !dy || !dx || !alpha || !beta || !aligned16(yq) || !aligned16(dy) || !aligned16(dx) || !aligned4(alpha) ||
         !aligned4(beta))
         return MESA_ERR_INVALID_ARG;
-    if (H > kSmMaxHeads || rows >= (int64_t(1) << 31)) return MESA_ERR_UNSUPPORTED;
+    if (rows >= (int64_t(1) << 31) || cols >= (int64_t(1) << 31) || H >= (int64_t(1) << 31)) return MESA_ERR_UNSUPPORTED;
     const long double tr = (long double)B * (long double)H * (long double)rows;
     if (tr >= 2147483648.0L) return MESA_ERR_UNSUPPORTED;
     const int64_t total_rows = B * H * rows;
+    auto plain = [&]() {
+        hipStream_t sp = static_cast<hipStream_t>(stream);
+#define MESA_LAUNCH_SP(T) \
+    hipLaunchKernelGGL((k_softmax_bwd_plain<T>), dim3(unsigned(total_rows < (int64_t(1) << 20) ? total_rows : (int64_t(1) << 20))), \
+                       dim3(kThreads), 0, sp, yq, dy, dx, total_rows, uint32_t(cols), uint32_t(rows), uint32_t(H), alpha, beta)
+        MESA_FOR_DTYPE(dt, MESA_LAUNCH_SP);
+#undef MESA_LAUNCH_SP
+        return launch_status();
+    };
+    if (H > kSmMaxHeads) return plain();
     const SbPlan rp = sb_plan(total_rows, H, cols, dtype_bytes(dt));
     if (rp.ok) {
         FastDiv drr = make_fastdiv(uint32_t(rows)), dhh = make_fastdiv(uint32_t(H));
@@ -466,7 +507,7 @@ extern "C" MESA_EXPORT mesa_status mesa_softmax_bwd_q(const int8_t *yq, int64_t 
 #undef MESA_LAUNCH_SB
         return launch_status();
     }
-    if (cols < kVec) return MESA_ERR_UNSUPPORTED;
+    if (cols < kVec) return plain();
     // rows per tile: a multiple of 8/gcd(cols, 8) so that every tile starts on a vector boundary.
     // Short rows: one wave per tile (2048 elements); long rows: the whole workgroup (8192 elements).
     int64_t gc = cols, b8 = 8;
@@ -475,7 +516,7 @@ extern "C" MESA_EXPORT mesa_status mesa_softmax_bwd_q(const int8_t *yq, int64_t 
     const bool wave_tiles = unit * cols <= int64_t(64) * kSmU * kVec;
     const int64_t cap = (wave_tiles ? 64 : kThreads) * int64_t(kSmU) * kVec;
     int64_t R = (cap / cols) / unit * unit;
-    if (R < unit) return MESA_ERR_UNSUPPORTED;   // `unit` rows of this length do not fit one tile
+    if (R < unit) return plain();                // `unit` rows of this length do not fit one tile
     if (R > total_rows) R = ceil_div(total_rows, unit) * unit;
     const int64_t tiles = ceil_div(total_rows, R);
     const int64_t teams = wave_tiles ? kThreads / 64 : 1;

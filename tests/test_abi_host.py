@@ -83,10 +83,10 @@ def test_argument_errors_are_reported_before_any_launch(M):
     assert L.mesa_layernorm_fwd_q(P, 100, 384, 6, P, P, F(-1.0), P, P, F(0.9), P2, P, P, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_INVALID_ARG  # eps
     assert L.mesa_dequantize(P, lay, P, None, P, M.F16, None) == M.ERR_INVALID_ARG
     assert L.mesa_gelu_bwd_q(P, lay, P, P, P + 8, P, M.F16, None) == M.ERR_INVALID_ARG
-    assert L.mesa_softmax_bwd_q(P, 2, 2000, 5, 40, P, P, P, P, M.F16, None) == M.ERR_UNSUPPORTED          # heads
-    assert L.mesa_softmax_bwd_q(P, 2, 3, 5, 3001, P, P, P, P, M.F16, None) == M.ERR_UNSUPPORTED           # 8 odd rows exceed a tile
+    assert L.mesa_softmax_bwd_q(P, 2, 3, 1 << 31, 40, P, P, P, P, M.F16, None) == M.ERR_UNSUPPORTED       # rows per head
+    assert L.mesa_softmax_bwd_q(P, 1 << 20, 1 << 10, 5, 40, P, P, P, P, M.F16, None) == M.ERR_UNSUPPORTED  # 2^31 rows or more in all
     assert L.mesa_softmax_bwd_q(P, -2, 3, 5, 16, P, P, P, P, M.F16, None) == M.ERR_INVALID_ARG
-    assert L.mesa_layernorm_bwd_q(P, 10, 100, 5, P, P, P, P, P, P, P, P, P, M.F16, P, 1 << 20, None) == M.ERR_UNSUPPORTED
+    assert L.mesa_layernorm_bwd_q(P, 10, 1 << 31, 1, P, P, P, P, P, P, P, P, P, M.F16, P, 1 << 20, None) == M.ERR_UNSUPPORTED
     assert L.mesa_layernorm_bwd_q(P, 10, 96, 5, P, P, P, P, P, P, P, P, P, M.F16, P, 1 << 20, None) == M.ERR_INVALID_ARG
     assert L.mesa_layernorm_bwd_q(P, 10, 96, 3, P, P, P, P, P, P, P, P, P, M.F16, P, 16, None) == M.ERR_WORKSPACE
     assert L.mesa_linear_dw_q(P, 100, 1 << 20, 1, P, P, P, 1 << 12, M.F16, P, None, P, 1 << 30, None) == M.ERR_UNSUPPORTED   # K * N_out >= 2^31

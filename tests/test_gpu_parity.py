@@ -281,6 +281,15 @@ def test_layernorm_bwd_every_row_length_class(M, D, G, tokens, dtype):
     assert all(v <= TOL[dtype] for v in rep.values()), rep
 
 
+@pytest.mark.parametrize("dtype", DTYPES, ids=DTYPE_IDS)
+@pytest.mark.parametrize("D,G,tokens", [(100, 5, 37), (7, 1, 5), (120, 3, 1030), (4104, 3, 9), (8192, 16, 6), (5000, 8, 11)])
+def test_layernorm_bwd_rows_the_vector_kernels_cannot_take(M, D, G, tokens, dtype):
+    """Row lengths and group widths that are no multiple of 8, rows above 4096 elements: the plain kernels."""
+    spec = W.small_case(dtype, seed=D + tokens, B=1, H=G, N=tokens, D=D, mlp=D)
+    rep = _ln_case(M, spec, G)
+    assert all(v <= TOL[dtype] for v in rep.values()), rep
+
+
 @pytest.mark.parametrize("Mr,K,N", [(31, 16, 8), (32, 48, 24), (97, 128, 264), (100 * 32, 384, 256), (101 * 32 + 5, 256, 520),
                                     (4 * 32 * 7 + 13, 784, 136), (9000, 272, 1000)])
 @pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16], ids=["f16", "bf16"])
@@ -514,11 +523,12 @@ def test_gelu_layer_forward_in_one_pass(M, layout, dtype):
 @pytest.mark.parametrize("dtype", DTYPES, ids=DTYPE_IDS)
 @pytest.mark.parametrize("B,H,rows,cols", [(3, 6, 197, 197), (5, 3, 49, 49), (2, 4, 64, 64), (1, 2, 33, 1000), (2, 3, 7, 19), (1, 1, 5, 8),
                                            (2, 2, 9, 3), (1, 3, 11, 57), (2, 1, 13, 104), (1, 2, 30, 105), (3, 1, 5, 200), (1, 2, 17, 201),
-                                           (2, 2, 6, 256), (1, 2, 10, 257), (40, 3, 61, 61), (1, 1, 3, 4096)])
+                                           (2, 2, 6, 256), (1, 2, 10, 257), (40, 3, 61, 61), (1, 1, 3, 4096),
+                                           (1, 2, 5, 1025), (1, 1, 3, 4097), (2, 1, 2, 9001), (1, 1, 2, 8200), (1, 1100, 2, 300)])
 def test_softmax_backward_every_row_shape(M, B, H, rows, cols, dtype):
     """Softmax backward at head-wise codes over every lane-group shape of the short-row kernel (and both of its
-    variants), rows shorter than a vector, ragged tiles, tiles that straddle heads, and the long-row kernel; out of
-    place and in place."""
+    variants), rows shorter than a vector, ragged tiles, tiles that straddle heads, and the long-row kernel; the plain
+    kernel's shapes (odd rows above 1024 elements, rows above 8192, more than 1024 heads); out of place and in place."""
     gen = torch.Generator(device="cuda").manual_seed(B * 10 + cols)
     lay = (B, H, rows * cols)
     sig = torch.linspace(0.5, 3.0, H, device="cuda").view(1, H, 1, 1)
