@@ -403,10 +403,12 @@ __global__ __launch_bounds__(kThreads, kSbRowWaves) void k_softmax_bwd_rows(cons
 }
 
 // Rows the tiled kernels cannot take (eight rows of an odd length above 1024 do not fit a tile, more than
-// kSmMaxHeads heads, rows shorter than a vector next to many heads): one workgroup per row, element by element, the
-// row read twice -- once for d = sum_j dy_j * y_hat_j (per-thread sums in a fixed order, then the wave's lanes, then
-// the four waves), once more for dx_j = y_hat_j * (dy_j - d).  Any length; about a third of the tiled kernels' rate.
-// dx may alias dy: a thread writes only the elements it has just read, and every sum is complete before the first write.
+// kSmMaxHeads heads, rows shorter than a vector next to many heads): one workgroup per row, the row read twice --
+// once for d = sum_j dy_j * y_hat_j (per-thread sums in a fixed order, then the wave's lanes, then the four waves),
+// once more for dx_j = y_hat_j * (dy_j - d); the second read comes from the caches.  A row starts wherever the one
+// before it ended: the elements up to the first 16-byte boundary of dy and those behind the last one go one by one,
+// the vectors between them whole.  Any length.  dx may alias dy: a thread writes only the elements it has just read,
+// and every sum is complete before the first write.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void k_softmax_bwd_plain(const int8_t *__restrict__ yq, const void *dy, void *dx, int64_t total_rows,
                                                                 uint32_t cols, uint32_t rows, uint32_t heads,
@@ -415,19 +417,42 @@ __global__ __launch_bounds__(kThreads) void k_softmax_bwd_plain(const int8_t *__
     __shared__ float part[kThreads / 64];
     for (int64_t row = blockIdx.x; row < total_rows; row += gridDim.x) {
         const uint32_t h = uint32_t((row / rows) % heads);
-        const float s = alpha[h] / 255.0f, off = fmaf(128.0f, s, beta[h]);   // y_hat = s * q + off with q the signed code
+        const float s = alpha[h] / 255.0f, b = beta[h];                  // y_hat = s * x_bar + beta, x_bar = code + 128
         const int64_t e0 = row * int64_t(cols);
+        const uint32_t lead = uint32_t((8 - (e0 & 7)) & 7);
+        const uint32_t head = lead < cols ? lead : cols;                  // elements before the first whole vector
+        const uint32_t nvec = (cols - head) / kVec;
+        const uint32_t tail0 = head + nvec * kVec;                        // first element behind the last whole vector
+        // the edge elements: thread t takes head element t or tail element t - 8
+        const uint32_t edge = threadIdx.x < 8 ? threadIdx.x : tail0 + (threadIdx.x - 8);
+        const bool has_edge = threadIdx.x < 8 ? threadIdx.x < head : (threadIdx.x < 16 && edge < cols);
         float d = 0.0f;
-        for (uint32_t j = threadIdx.x; j < cols; j += kThreads)
-            d = fmaf(Store<T>::load1(dy, e0 + j), fmaf(float(int(yq[e0 + j])), s, off), d);
+        if (has_edge) d = Store<T>::load1(dy, e0 + edge) * fmaf(code_to_float(yq[e0 + edge]), s, b);
+        for (uint32_t v = threadIdx.x; v < nvec; v += kThreads) {
+            const int64_t e = e0 + head + int64_t(v) * kVec;
+            float g[8], y[8];
+            Store<T>::unpack(Store<T>::load(dy, e), g);
+            codes_to_float(*reinterpret_cast<const u32x2 *>(yq + e), y);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) d = fmaf(g[k], fmaf(y[k], s, b), d);
+        }
 #pragma unroll
         for (int m = 32; m >= 1; m >>= 1) d += __shfl_xor(d, m);
         if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = d;
         __syncthreads();
         d = (part[0] + part[1]) + (part[2] + part[3]);
-        for (uint32_t j = threadIdx.x; j < cols; j += kThreads) {
-            const float yh = fmaf(float(int(yq[e0 + j])), s, off);
-            Store<T>::store1(dx, e0 + j, yh * (Store<T>::load1(dy, e0 + j) - d));
+        if (has_edge) {
+            const float yh = fmaf(code_to_float(yq[e0 + edge]), s, b);
+            Store<T>::store1(dx, e0 + edge, yh * (Store<T>::load1(dy, e0 + edge) - d));
+        }
+        for (uint32_t v = threadIdx.x; v < nvec; v += kThreads) {
+            const int64_t e = e0 + head + int64_t(v) * kVec;
+            float g[8], y[8], o[8];
+            Store<T>::unpack(Store<T>::load(dy, e), g);
+            codes_to_float(*reinterpret_cast<const u32x2 *>(yq + e), y);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) o[k] = fmaf(y[k], s, b) * (g[k] - d);
+            Store<T>::store(dx, e, Store<T>::pack(o));
         }
         __syncthreads();                                   // the next row's sums reuse `part`
     }
