@@ -596,14 +596,15 @@ def mfma_probes(m):
     gen = torch.Generator(device="cuda").manual_seed(77)
     feed = torch.randn(8 << 20, device="cuda", generator=gen).half()        # 16 MiB: 2 MiB per XCD, within its L2
     out = {}
-    for form, name in ((0, "operands_in_registers"), (1, "operands_from_lds"), (2, "operands_from_lds_and_tile_loads")):
+    for form, name in ((0, "operands_in_registers"), (1, "operands_from_lds"), (2, "operands_from_lds_and_tile_loads"),
+                       (3, "eight_waves_operands_from_lds_and_tile_loads")):
         torch.cuda.synchronize()
         time.sleep(1.0)
         evs = []
         for i in range(300):
             e0, e1 = m.Event(), m.Event()
             e0.record()
-            m.mesa_mfma_probe(form, steps, feed if form == 2 else None, sink)
+            m.mesa_mfma_probe(form, steps, feed if form >= 2 else None, sink)
             e1.record()
             evs.append((e0, e1))
         torch.cuda.synchronize()

@@ -395,8 +395,9 @@ mesa_status mesa_stream_fill(void *dst, size_t bytes, uint32_t word, void *strea
  * waves, each wave `steps` times sixteen v_mfma_f32_32x32x16_f16 on a 128 x 128 tile of accumulators
  * (flops of a launch: 256 * 4 * steps * 16 * 32768).  form 0: operands in registers; form 1: operands read
  * from LDS every step; form 2: form 1 plus 12 KB per workgroup and step loaded from `feed` (device memory,
- * 16-byte aligned, 1 MiB <= feed_bytes <= 16 GiB, a multiple of 16; read cyclically) and stored to
- * LDS.  feed is ignored by forms 0 and 1.  sink: 65536 floats of device memory, overwritten (one sum per
+ * 16-byte aligned, 2 MiB <= feed_bytes <= 16 GiB, a multiple of 16; read cyclically) and stored to
+ * LDS; form 3: form 2's work shared out among eight waves per workgroup (two per SIMD, a 128 x 64 tile
+ * each).  feed is ignored by forms 0 and 1.  sink: 65536 floats of device memory, overwritten (one sum per
  * thread; zeros for steps == 0).  0 <= steps <= 2^20. */
 mesa_status mesa_mfma_probe(int form, int64_t steps, const void *feed, size_t feed_bytes, float *sink, void *stream);
 mesa_status mesa_event_create(void **event);

@@ -102,10 +102,10 @@ def test_argument_errors_are_reported_before_any_launch(M):
     assert L.mesa_attn_qk_bwd_q(P, P + 4, 2, 3, 19, 8, P, P, P, P, P, 0.5, P, P, M.F16, None) == M.ERR_INVALID_ARG
     assert L.mesa_attn_qk_bwd_q(None, None, 0, 3, 19, 8, None, None, None, None, None, 0.5, None, None, M.F16, None) == M.OK
     assert L.mesa_stream_copy(P, P, 24, None) == M.ERR_INVALID_ARG
-    assert L.mesa_mfma_probe(3, 10, None, 0, P, None) == M.ERR_INVALID_ARG            # no such form
+    assert L.mesa_mfma_probe(4, 10, None, 0, P, None) == M.ERR_INVALID_ARG            # no such form
     assert L.mesa_mfma_probe(0, -1, None, 0, P, None) == M.ERR_INVALID_ARG
     assert L.mesa_mfma_probe(0, 10, None, 0, None, None) == M.ERR_INVALID_ARG         # no sink
-    assert L.mesa_mfma_probe(2, 10, P, 4096, P, None) == M.ERR_INVALID_ARG            # feed below 1 MiB
+    assert L.mesa_mfma_probe(2, 10, P, 4096, P, None) == M.ERR_INVALID_ARG            # feed below 2 MiB
     # zero elements: OK without touching anything
     assert L.mesa_quantize_headwise(None, M.F16, M.Layout(0, 3, 64), None, None, None, 0, 0, 0, None) == M.OK
     assert L.mesa_softmax_bwd_q(None, 0, 3, 5, 16, None, None, None, None, M.F16, None) == M.OK

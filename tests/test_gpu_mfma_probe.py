@@ -67,14 +67,15 @@ def test_probe_with_tile_loads_and_edge_cases(M):
     assert float(sink.abs().max()) == 0.0
     gen = torch.Generator(device="cuda").manual_seed(3)
     feed = torch.randn(1 << 20, device="cuda", generator=gen).half()        # 2 MiB
-    out = []
-    for _ in range(2):
-        sink.fill_(float("nan"))
-        M.mesa_mfma_probe(2, 37, feed, sink)
-        torch.cuda.synchronize()
-        out.append(sink.clone())
-    assert bool(torch.isfinite(out[0]).all()) and torch.equal(out[0], out[1])
+    for form in (2, 3):
+        out = []
+        for _ in range(2):
+            sink.fill_(float("nan"))
+            M.mesa_mfma_probe(form, 37, feed, sink)
+            torch.cuda.synchronize()
+            out.append(sink.clone())
+        assert bool(torch.isfinite(out[0]).all()) and torch.equal(out[0], out[1])
     with pytest.raises(M.MesaError):
-        M.mesa_mfma_probe(2, 5, feed[:1000], sink)            # feed below 1 MiB
+        M.mesa_mfma_probe(2, 5, feed[:1000], sink)            # feed below 2 MiB
     with pytest.raises(M.MesaError):
-        M.mesa_mfma_probe(3, 5, None, sink)
+        M.mesa_mfma_probe(4, 5, None, sink)
