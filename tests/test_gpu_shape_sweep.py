@@ -240,3 +240,55 @@ def test_linear_dw_keeps_inside_its_outputs(M, dtype):
         rW, rb_ = R.linear_dw_q(npy(q), Mr, K, H, npy(a), npy(b), npy(dy), N)
         assert relerr(npy(dW), rW) <= 2e-3 and relerr(npy(db), rb_) <= 2e-3, (Mr, K, N)
         assert intact(fW) and intact(fb), (Mr, K, N)
+
+
+def _conv_cases(seed, count):
+    """Seeded convolution geometries that take the matrix-core path: 3x3 with one column of padding or 1x1 with none,
+    unit column stride and dilation, widths that are multiples of 8; everything else drawn freely (ragged channel
+    tiles, one to three row segments, row strides, dilations and paddings, batch sizes that leave ragged slices)."""
+    rnd = random.Random(seed)
+    out = []
+    while len(out) < count:
+        k = rnd.choice((3, 3, 1))
+        B = rnd.randint(1, 5)
+        G = rnd.choice((1, 2, 3, 4, 6))
+        Cin = G * rnd.randint(2, 40)
+        Cout = rnd.randint(3, 150)
+        W = 8 * rnd.choice((1, 2, 3, 4, 5, 8, 9, 16, 17, 33))
+        sh, dh, ph = rnd.choice((1, 1, 2, 3)), rnd.choice((1, 1, 2, 3)), rnd.randint(0, 3)
+        H = rnd.randint(max(1, dh * (k - 1) + 1 - 2 * ph), 22)
+        if B * Cin * Cout * H * W > 3.0e8:           # keeps the oracle's binary64 loops to a second or two
+            continue
+        out.append((B, Cin, H, W, Cout, k, k, (sh, 1), (ph, 1 if k == 3 else 0), (dh, 1), G))
+    return out
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16], ids=["f16", "bf16"])
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_convolution_weight_gradient_over_seeded_geometries(M, seed, dtype):
+    """dW and db framed by sentinels, against the oracle, over ten geometries per seed; every case must take the
+    matrix-core path (a workspace is asked for)."""
+    for case in _conv_cases(seed, 10):
+        B, Cin, H, W, Cout, KH, KW, stride, pad, dil, G = case
+        cv = M.Conv2d(B, Cin, H, W, Cout, KH, KW, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1])
+        OH, OW = cv.out_hw()
+        gen = torch.Generator(device="cuda").manual_seed(seed * 1000 + Cin + Cout)
+        xq = torch.randint(-128, 128, (B, Cin, H, W), dtype=torch.int8, device="cuda", generator=gen)
+        dy = torch.randn((B, Cout, OH, OW), device="cuda", generator=gen).to(dtype)
+        a = (0.5 + 4.0 * torch.rand(G, device="cuda", generator=gen)).float()
+        b = (-2.5 + 2.0 * torch.rand(G, device="cuda", generator=gen)).float()
+        fW, dW = framed((Cout, Cin, KH, KW), torch.float32)
+        fb, db = framed((Cout,), torch.float32)
+        dtc = M.F16 if dtype == torch.float16 else M.BF16
+        nws = M.conv2d_dw_q_workspace_bytes(cv, dtc)
+        assert nws > 0, case
+        fws = torch.full((nws + 512,), 0x5A, dtype=torch.uint8, device="cuda")
+        ws = fws[256:256 + nws]
+        M.mesa_conv2d_dw_q(xq, cv, G, a, b, dy, dW, db, ws)
+        torch.cuda.synchronize()
+        geom, rOH, rOW = R.conv_geometry(B, Cin, H, W, Cout, KH, KW, stride, pad, dil)
+        assert (rOH, rOW) == (OH, OW)
+        rW, rb = R.conv2d_dw_q(npy(xq), geom, G, npy(a), npy(b), npy(dy).astype(np.float32))
+        assert relerr(npy(dW), rW) <= 2e-3 and relerr(npy(db), rb) <= 1e-5, (case, relerr(npy(dW), rW), relerr(npy(db), rb))
+        assert intact(fW) and intact(fb), case
+        assert bool((fws[:256] == 0x5A).all() and (fws[256 + nws:] == 0x5A).all()), case
