@@ -20,6 +20,7 @@
 // is multiplied.  binary16 or bfloat16 tensors (every kernel here takes the number type as a parameter);
 // binary32 tensors through one plain kernel (k_bmm_q_f32).
 #include <hip/hip_runtime.h>
+#include <type_traits>
 
 #include "api_util.hpp"
 #include "common.hpp"
@@ -610,6 +611,120 @@ __global__ __launch_bounds__(kThreads, KS <= 4 ? 7 : 4) void k_attn_da(const _Fl
     }
 }
 
+// ---- dA for long sequences (N a multiple of 8, beyond what k_attn_da's 32 x N output block can hold in LDS) ----------
+// A workgroup takes 64 rows i and 256 columns j of one head: the 64 rows of dO and the 256 rows of V codes go to LDS
+// once (the codes only until every wave holds its fragments), wave w multiplies the 64 rows by the code rows 64 w ..+63 (four accumulator tiles, codes on the M side as in
+// k_attn_da: a lane ends up with one row i and runs of four consecutive j), and its 64 x 64 piece of the result leaves
+// through a private LDS region, 32 rows at a time, as aligned 16-byte vectors: 128 contiguous bytes per row and wave,
+// 512 per row and workgroup.  The column tiles of a row block are neighbours in the grid.  Dh == 16 * KS.
+template <int KS> struct DcCfg {
+    static constexpr int Dh = 16 * KS;
+    static constexpr int kRowO = 2 * Dh + 16, kRowV = Dh + 16;     // bytes per staged row of dO, of codes
+    static constexpr int kRowOut = 64 * 2 + 16;                    // bytes per staged row of a wave's result
+    static constexpr int kVecO = Dh / 8, kVecV = Dh / 16;
+    // the waves' result regions take the place of the codes once every wave holds its code fragments
+    static constexpr int kRows = KS <= 4 ? 128 : 64;               // rows of dO per workgroup (the codes are read once for all of them)
+    static constexpr int kCodesAt = kRows * kRowO, kOutAt = kCodesAt;
+    static constexpr int kLds = kCodesAt + (256 * kRowV > 4 * 32 * kRowOut ? 256 * kRowV : 4 * 32 * kRowOut);
+};
+
+template <int KS, typename ET>
+__global__ __launch_bounds__(kThreads, KS <= 4 ? 3 : 2) void k_attn_da_cols(const _Float16 *__restrict__ dO, const int8_t *__restrict__ vq,
+                                                                            _Float16 *__restrict__ dA, int N, int heads, int tiles_j,
+                                                                            int tiles_i, const float *__restrict__ alpha_v,
+                                                                            const float *__restrict__ beta_v)
+{
+    typedef DcCfg<KS> C;
+    __shared__ __attribute__((aligned(16))) unsigned char lds_dc[C::kLds];
+    constexpr int Dh = C::Dh;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int fl = lane & 31, fk = (lane >> 5) * 8;
+    const unsigned tj = blockIdx.x % unsigned(tiles_j), rest = blockIdx.x / unsigned(tiles_j);
+    const int64_t bh = rest / unsigned(tiles_i);
+    const int i0 = int(rest % unsigned(tiles_i)) * C::kRows, j0 = int(tj) * 256;
+    const int rows = N - i0 < C::kRows ? N - i0 : C::kRows, cols = N - j0 < 256 ? N - j0 : 256;
+
+    {   // staging: rows past the end repeat the last one (their results are never written)
+        const u32x4 *ovec = reinterpret_cast<const u32x4 *>(dO + (bh * N + i0) * int64_t(Dh));
+        const int o_vecs = rows * C::kVecO;
+#pragma unroll
+        for (int k = 0; k < (C::kRows * C::kVecO + kThreads - 1) / kThreads; ++k) {
+            const int idx = tid + k * kThreads;
+            if (idx < C::kRows * C::kVecO)
+                *reinterpret_cast<u32x4 *>(lds_dc + (idx / C::kVecO) * C::kRowO + (idx % C::kVecO) * 16) = ovec[idx < o_vecs ? idx : o_vecs - 1];
+        }
+        const u32x4 *vvec = reinterpret_cast<const u32x4 *>(vq + (bh * N + j0) * int64_t(Dh));
+        const int v_vecs = cols * C::kVecV;
+#pragma unroll
+        for (int k = 0; k < 256 * C::kVecV / kThreads; ++k) {
+            const int idx = tid + k * kThreads;
+            *reinterpret_cast<u32x4 *>(lds_dc + C::kCodesAt + (idx / C::kVecV) * C::kRowV + (idx % C::kVecV) * 16) = vvec[idx < v_vecs ? idx : v_vecs - 1];
+        }
+    }
+    __syncthreads();
+    const int h = int(bh % heads);
+    const float s = alpha_v[h] / 255.0f;
+    const float off = fmaf(BmNum<ET>::kCentre, s, beta_v[h]);
+    unsigned char *lout = lds_dc + C::kOutAt + wave * (32 * C::kRowOut);
+    auto wave_sync = [&]() {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+    // the codes of this wave's 64 columns, as operands: lane l holds code row l%32 (+32), slots 8*(l/32) ..+7 of a step
+    bm_v8h fc[2][KS];
+#pragma unroll
+    for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            fc[jb][ks] = BmNum<ET>::codes8(*reinterpret_cast<const bm_v2i *>(lds_dc + C::kCodesAt + (wave * 64 + jb * 32 + fl) * C::kRowV + ks * 16 + fk));
+    __syncthreads();                                       // the codes' place becomes the result regions
+    if (wave * 64 >= cols) return;                         // this wave's columns lie past N (no barrier follows)
+#pragma unroll
+    for (int rb = 0; rb < C::kRows / 32; ++rb) {
+        if (rb * 32 >= rows) break;                        // uniform
+        bm_v8h fo[KS];
+        float rsum = 0.0f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            fo[ks] = *reinterpret_cast<const bm_v8h *>(lds_dc + (rb * 32 + fl) * C::kRowO + (ks * 16 + fk) * 2);
+#pragma unroll
+            for (int j = 0; j < 8; j += 2) rsum = BmNum<ET>::dot_ones(fo[ks][j], fo[ks][j + 1], rsum);
+        }
+        rsum += __shfl_xor(rsum, 32);                      // both halves of the row's slots
+        const float add = off * rsum;
+#pragma unroll
+        for (int jb = 0; jb < 2; ++jb) {
+            bm_v16f acc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) acc = BmNum<ET>::mfma(fc[jb][ks], fo[ks], acc);
+            // lane l, register v: column 32*jb + 8*(v/4) + 4*(l/32) + v%4 of the wave's 64, row l%32
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                bm_v4h o;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) o[k] = BmNum<ET>::round(fmaf(s, acc[4 * g + k], add));
+                *reinterpret_cast<bm_v4h *>(lout + fl * C::kRowOut + (jb * 32 + 8 * g + (lane >> 5) * 4) * 2) = o;
+            }
+        }
+        wave_sync();
+        // 32 rows x eight vectors of eight columns: lane l takes vector l%8 of rows l/8, l/8 + 8, ..
+        const int cv = lane & 7;
+        if (wave * 64 + cv * 8 < cols) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int r = (lane >> 3) + 8 * k;
+                if (rb * 32 + r < rows)
+                    *reinterpret_cast<u32x4 *>(dA + (bh * N + i0 + rb * 32 + r) * int64_t(N) + j0 + wave * 64 + cv * 8) =
+                        *reinterpret_cast<const u32x4 *>(lout + r * C::kRowOut + cv * 16);
+            }
+        }
+        wave_sync();                                       // the region is free for the next 32 rows
+    }
+}
+
 // ---- the two products that contract over the ROW index of both operands: dK = scale * dS^T Q_hat, dV = A_hat^T dO ----
 // One workgroup per head.  It walks down the rows i in chunks of 32: the chunk of the N x N operand (dS or the
 // A codes) is one contiguous, merely element-aligned piece of memory that comes in as aligned 16-byte
@@ -811,6 +926,191 @@ __global__ __launch_bounds__(64 * NW, (tn_waves_per_simd<DT, JB, NW>())) void k_
         if (j >= N) continue;
         float cs = 0.0f;
         if (!WIDE_CODED) cs = off * (csum[jb] + __shfl_xor(csum[jb], 32));
+        _Float16 *po = out + (bh * N + j) * int64_t(Dh) + half * 4;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                bm_v4h o;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const float add = WIDE_CODED ? off * acc1[dt][4 * g + k] : cs;
+                    o[k] = BmNum<ET>::round(scale * fmaf(s, acc[jb][dt][4 * g + k], add));
+                }
+                *reinterpret_cast<bm_v4h *>(po + dt * 32 + g * 8) = o;
+            }
+    }
+}
+
+// ---- the same two products for long sequences (N a multiple of 16, beyond what one workgroup per head can hold) -----
+// A workgroup takes 256 columns j of one head and walks down ALL rows i in chunks of 32: per chunk 32 row segments of
+// 256 elements of the N x N operand (512 contiguous bytes of dS, 256 of the A codes: aligned 16-byte vectors, rows a
+// multiple of 16 elements apart) and the chunk's 32 rows of the N x Dh operand.  Both lie in LDS row by row, with a
+// pitch that keeps the transposing reads of sixteen lanes on different banks; every MFMA operand is one or two
+// transposing reads (lane: column j or d, eight consecutive rows i).  The next chunk's vectors wait in registers
+// while a chunk is multiplied (two LDS buffers, one barrier per chunk).  Wave w takes columns 64 w ..+63 of the tile.
+// The workgroups of a head's column tiles are neighbours in the grid: they read adjacent segments of the same rows at
+// about the same time and share the N x Dh chunks in the L2.  The N x N operand is read exactly once.
+// As in k_attn_tn the N x Dh operand sits on the M side: a lane ends up with one output row j and runs of four d.
+template <int DT, bool WIDE_CODED> struct TcCfg {
+    static constexpr int Dh = 32 * DT;
+    static constexpr int kJW = 256;                        // columns of the N x N operand per workgroup
+    static constexpr int kNt = kJW;                        // threads: a wave per 64 columns (two blocks of 32)
+    static constexpr int kJB = 2;
+    static constexpr int kAhead = WIDE_CODED ? 2 : 1;      // chunks in registers ahead of the one in LDS: the codes' chunks are
+                                                           // half the bytes, and it is bytes in flight that hide the latency
+    static constexpr int kWideEb = WIDE_CODED ? 1 : 2;
+    static constexpr int kPitchW = kJW * kWideEb + (WIDE_CODED ? 16 : 32);   // bytes per staged row segment
+    static constexpr int kVecRowW = kJW * kWideEb / 16;    // 16-byte vectors per row segment
+    static constexpr int kWideVecs = 32 * kVecRowW / kNt;   // per thread and chunk: 4 (binary16) or 2 (codes)
+    static constexpr int kRowN = WIDE_CODED ? 2 * Dh + 32 : Dh + 32;   // bytes per staged row of the N x Dh operand
+    static constexpr int kVecRowN = Dh * (WIDE_CODED ? 2 : 1) / 16;
+    static constexpr int kNarrowVecs = (32 * kVecRowN + kNt - 1) / kNt;
+    static constexpr int kStage = 32 * kPitchW + 32 * kRowN;
+    static constexpr int kLds = 2 * kStage;
+};
+
+template <int DT, bool WIDE_CODED, typename ET>
+__global__ __launch_bounds__((TcCfg<DT, WIDE_CODED>::kNt), DT == 4 ? 1 : 2) void k_attn_tn_cols(const void *__restrict__ wide_, const void *__restrict__ narrow_,
+                                                              _Float16 *__restrict__ out, int N, int heads, int tiles_j, float scale,
+                                                              const float *__restrict__ alpha, const float *__restrict__ beta)
+{
+    typedef TcCfg<DT, WIDE_CODED> C;
+    __shared__ __attribute__((aligned(16))) unsigned char lds_tc[C::kLds];
+    constexpr int Dh = C::Dh;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t bh = blockIdx.x / unsigned(tiles_j);
+    const int j0 = int(blockIdx.x % unsigned(tiles_j)) * C::kJW;
+    const unsigned char *wide = static_cast<const unsigned char *>(wide_) + (bh * N * int64_t(N) + j0) * C::kWideEb;
+    const unsigned char *narrow = static_cast<const unsigned char *>(narrow_) + bh * N * int64_t(Dh) * (WIDE_CODED ? 2 : 1);
+    const int fl = lane & 31, half = lane >> 5, blk = lane >> 4, sl = lane & 15;
+    const int nchunks = (N + 31) >> 5;
+    const int cols = N - j0 < C::kJW ? N - j0 : C::kJW;    // columns of this tile that exist (a multiple of 16)
+
+    // ---- staging: a thread's vectors sit at the same place of every chunk ---------------------------------------------
+    u32x4 wv[C::kAhead][C::kWideVecs], nv[C::kAhead][C::kNarrowVecs];
+    int w_src[C::kWideVecs], w_dst[C::kWideVecs];          // byte offsets from the chunk's first row: in memory (-1: past N), in LDS
+#pragma unroll
+    for (int k = 0; k < C::kWideVecs; ++k) {
+        const int v = tid + k * C::kNt, r = v / C::kVecRowW, cv = v % C::kVecRowW;
+        w_src[k] = cv * 16 < cols * C::kWideEb ? r * N * C::kWideEb + cv * 16 : -1;
+        w_dst[k] = r * C::kPitchW + cv * 16;
+    }
+    auto load_chunk = [&](int c, auto set_) {
+        constexpr int S = decltype(set_)::value;
+        const int rows = N - c * 32 < 32 ? N - c * 32 : 32;
+        const unsigned char *src = wide + int64_t(c) * 32 * N * C::kWideEb;
+#pragma unroll
+        for (int k = 0; k < C::kWideVecs; ++k) {
+            const int r = (tid + k * C::kNt) / C::kVecRowW;
+            wv[S][k] = u32x4{0u, 0u, 0u, 0u};              // columns past N, rows past the end: zeros
+            if (w_src[k] >= 0 && r < rows) wv[S][k] = *reinterpret_cast<const u32x4 *>(src + w_src[k]);
+        }
+        const u32x4 *nsrc = reinterpret_cast<const u32x4 *>(narrow + int64_t(c) * 32 * Dh * (WIDE_CODED ? 2 : 1));
+#pragma unroll
+        for (int k = 0; k < C::kNarrowVecs; ++k) {
+            const int v = tid + k * C::kNt;
+            nv[S][k] = v < rows * C::kVecRowN ? nsrc[v] : u32x4{0u, 0u, 0u, 0u};
+        }
+    };
+    auto store_chunk = [&](int b, auto set_) {
+        constexpr int S = decltype(set_)::value;
+        unsigned char *lw = lds_tc + b * C::kStage, *ln = lw + 32 * C::kPitchW;
+#pragma unroll
+        for (int k = 0; k < C::kWideVecs; ++k) *reinterpret_cast<u32x4 *>(lw + w_dst[k]) = wv[S][k];
+#pragma unroll
+        for (int k = 0; k < C::kNarrowVecs; ++k) {
+            const int v = tid + k * C::kNt;
+            if (v < 32 * C::kVecRowN) *reinterpret_cast<u32x4 *>(ln + (v / C::kVecRowN) * C::kRowN + (v % C::kVecRowN) * 16) = nv[S][k];
+        }
+    };
+
+    bm_v16f acc[C::kJB][DT];
+    bm_v16f acc1[WIDE_CODED ? DT : 1];                     // dV: column sums of dO per d, from MFMAs against ones
+    float csum[C::kJB];                                    // dK: column sums of dS per j, per lane
+#pragma unroll
+    for (int jb = 0; jb < C::kJB; ++jb) {
+        csum[jb] = 0.0f;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[jb][dt][v] = 0.0f;
+    }
+#pragma unroll
+    for (int dt = 0; dt < (WIDE_CODED ? DT : 1); ++dt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc1[dt][v] = 0.0f;
+    bm_v8h ones;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) ones[j] = __builtin_bit_cast(_Float16, BmNum<ET>::kOne);
+    // transposing reads: lane gets column (first column) + l%32 and the rows (first row) + 8*(l/32) ..+7
+    const int wide_at = WIDE_CODED ? ((blk >> 1) * 8 + (sl >> 1)) * C::kPitchW + wave * 64 + (blk & 1) * 16 + (sl & 1) * 8
+                                   : ((blk >> 1) * 8 + (sl >> 2)) * C::kPitchW + (wave * 64 + (blk & 1) * 16 + (sl & 3) * 4) * 2;
+    const int narrow_at = WIDE_CODED ? ((blk >> 1) * 8 + (sl >> 2)) * C::kRowN + ((blk & 1) * 16 + (sl & 3) * 4) * 2
+                                     : ((blk >> 1) * 8 + (sl >> 1)) * C::kRowN + (blk & 1) * 16 + (sl & 1) * 8;
+    const bool wave_live = wave * 64 < cols;               // uniform per wave
+
+    // chunk c waits in register set c % kAhead; it goes to LDS buffer c % 2 when chunk c - 1 is being multiplied
+    auto chunk_step = [&](int c, auto set_) {
+        const int b = c & 1;
+        store_chunk(b, set_);
+        if (c + C::kAhead < nchunks) load_chunk(c + C::kAhead, set_);
+        __syncthreads();   // chunk c is in LDS; every wave has finished with chunk c - 1 (the other buffer)
+        const int rows = N - c * 32 < 32 ? N - c * 32 : 32;
+        const unsigned char *lw = lds_tc + b * C::kStage, *ln = lw + 32 * C::kPitchW;
+        if (!wave_live) return;                          // its columns lie past N (the barrier above is still met)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            if (ks * 16 >= rows) break;                    // uniform
+            bm_v8h fn[DT];
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                if (WIDE_CODED) {
+                    const unsigned char *p = ln + narrow_at + ks * 16 * C::kRowN + dt * 64;
+                    const bm_v4h lo = __builtin_bit_cast(bm_v4h, __builtin_amdgcn_ds_read_tr16_b64_v4i16(BM_LDS3(bm_v4s, p)));
+                    const bm_v4h hi = __builtin_bit_cast(bm_v4h, __builtin_amdgcn_ds_read_tr16_b64_v4i16(BM_LDS3(bm_v4s, p + 4 * C::kRowN)));
+                    fn[dt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    acc1[dt] = BmNum<ET>::mfma(fn[dt], ones, acc1[dt]);
+                } else {
+                    fn[dt] = BmNum<ET>::codes8(__builtin_amdgcn_ds_read_tr8_b64_v2i32(BM_LDS3(bm_v2i, ln + narrow_at + ks * 16 * C::kRowN + dt * 32)));
+                }
+            }
+#pragma unroll
+            for (int jb = 0; jb < C::kJB; ++jb) {
+                if (wave * 64 + jb * 32 >= cols) break;       // uniform per wave: blocks past N
+                bm_v8h fw;
+                if (WIDE_CODED) {
+                    fw = BmNum<ET>::codes8(__builtin_amdgcn_ds_read_tr8_b64_v2i32(BM_LDS3(bm_v2i, lw + wide_at + ks * 16 * C::kPitchW + jb * 32)));
+                } else {
+                    const unsigned char *p = lw + wide_at + ks * 16 * C::kPitchW + jb * 64;
+                    const bm_v4h lo = __builtin_bit_cast(bm_v4h, __builtin_amdgcn_ds_read_tr16_b64_v4i16(BM_LDS3(bm_v4s, p)));
+                    const bm_v4h hi = __builtin_bit_cast(bm_v4h, __builtin_amdgcn_ds_read_tr16_b64_v4i16(BM_LDS3(bm_v4s, p + 4 * C::kPitchW)));
+                    fw = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+                    for (int k = 0; k < 8; k += 2) csum[jb] = BmNum<ET>::dot_ones(fw[k], fw[k + 1], csum[jb]);
+                }
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) acc[jb][dt] = BmNum<ET>::mfma(fn[dt], fw, acc[jb][dt]);
+            }
+        }
+    };
+    load_chunk(0, std::integral_constant<int, 0>());
+    if (C::kAhead == 2 && nchunks > 1) load_chunk(1, std::integral_constant<int, C::kAhead - 1>());
+    for (int c = 0; c < nchunks; c += C::kAhead) {
+        chunk_step(c, std::integral_constant<int, 0>());
+        if (C::kAhead == 2 && c + 1 < nchunks) chunk_step(c + 1, std::integral_constant<int, C::kAhead - 1>());
+    }
+
+    // ---- epilogue: lane l, register v of a tile: d = 32*dt + 8*(v/4) + 4*(l/32) + v%4, row j = (tile's first) + l%32 ----
+    const int h = int(bh % heads);
+    const float s = alpha[h] / 255.0f;
+    const float off = fmaf(BmNum<ET>::kCentre, s, beta[h]);
+#pragma unroll
+    for (int jb = 0; jb < C::kJB; ++jb) {
+        const int j = j0 + wave * 64 + jb * 32 + fl;
+        float cs = 0.0f;
+        if (!WIDE_CODED) cs = off * (csum[jb] + __shfl_xor(csum[jb], 32));
+        if (j >= N) continue;
         _Float16 *po = out + (bh * N + j) * int64_t(Dh) + half * 4;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
@@ -1033,6 +1333,53 @@ static void launch_tn(const void *wide, const void *narrow, _Float16 *out, int64
 }
 
 // whether k_attn_nn can take the shape: a 64-row chunk of dS within kMaxVecs vectors per thread, LDS within 64 KiB
+// long sequences: k_attn_da_cols
+static bool da_cols_fits(int64_t batches, int64_t N, int64_t Dh)
+{
+    if (Dh != 32 && Dh != 64 && Dh != 128) return false;
+    return N % 8 == 0 && N >= 32 && batches * ceil_div(N, 256) * ceil_div(N, 64) < (int64_t(1) << 31);   // 64: the fewest rows a workgroup takes
+}
+
+template <typename ET>
+static void launch_da_cols(const _Float16 *dO, const int8_t *vq, _Float16 *dA, int64_t batches, int N, int Dh, int heads,
+                           const float *alpha_v, const float *beta_v, hipStream_t s)
+{
+#define MESA_LAUNCH_DC(KS_) \
+    do { \
+        const int tiles_j = int(ceil_div(N, 256)), tiles_i = int(ceil_div(N, DcCfg<KS_>::kRows)); \
+        hipLaunchKernelGGL((k_attn_da_cols<KS_, ET>), dim3(unsigned(batches * tiles_j * tiles_i)), dim3(kThreads), 0, s, dO, vq, dA, N, heads, \
+                           tiles_j, tiles_i, alpha_v, beta_v); \
+    } while (0)
+    if (Dh == 32) MESA_LAUNCH_DC(2);
+    else if (Dh == 64) MESA_LAUNCH_DC(4);
+    else MESA_LAUNCH_DC(8);
+#undef MESA_LAUNCH_DC
+}
+
+// long sequences: k_attn_tn_cols
+static bool tn_cols_fits(int64_t batches, int64_t N, int64_t Dh)
+{
+    if (Dh != 32 && Dh != 64 && Dh != 128) return false;
+    return N % 16 == 0 && N >= 32 && batches * ceil_div(N, 256) < (int64_t(1) << 31);
+}
+
+template <bool WIDE_CODED, typename ET>
+static void launch_tn_cols(const void *wide, const void *narrow, _Float16 *out, int64_t batches, int N, int Dh, int heads, float scale,
+                           const float *alpha, const float *beta, hipStream_t s)
+{
+#define MESA_LAUNCH_TC(DT_) \
+    do { \
+        typedef TcCfg<DT_, WIDE_CODED> C; \
+        const int tiles_j = int(ceil_div(N, C::kJW)); \
+        hipLaunchKernelGGL((k_attn_tn_cols<DT_, WIDE_CODED, ET>), dim3(unsigned(batches * tiles_j)), dim3(C::kNt), 0, s, wide, narrow, out, N, \
+                           heads, tiles_j, scale, alpha, beta); \
+    } while (0)
+    if (Dh == 32) MESA_LAUNCH_TC(1);
+    else if (Dh == 64) MESA_LAUNCH_TC(2);
+    else MESA_LAUNCH_TC(4);
+#undef MESA_LAUNCH_TC
+}
+
 static bool nn_fits(int64_t N, int64_t Dh)
 {
     if (Dh != 32 && Dh != 64 && Dh != 128) return false;
@@ -1104,6 +1451,7 @@ extern "C" MESA_EXPORT mesa_status mesa_attn_av_bwd_q(const int8_t *aq, const in
         else if (Dh == 64 && da_fits<4>(batches, N)) launch_da<4, ET>(a.x, vq, a.c, batches, int(N), int(H), alpha_v, beta_v, s); \
         else if (Dh == 96 && da_fits<6>(batches, N)) launch_da<6, ET>(a.x, vq, a.c, batches, int(N), int(H), alpha_v, beta_v, s); \
         else if (Dh == 128 && da_fits<8>(batches, N)) launch_da<8, ET>(a.x, vq, a.c, batches, int(N), int(H), alpha_v, beta_v, s); \
+        else if (da_cols_fits(batches, N, Dh)) launch_da_cols<ET>(a.x, vq, a.c, batches, int(N), int(Dh), int(H), alpha_v, beta_v, s); \
         else launch_bmm<false, true, true, ET>(a, batches, s); \
     } while (0)
     if (dt == MESA_BF16) MESA_AV_DA(__bf16); else MESA_AV_DA(_Float16);
@@ -1118,6 +1466,8 @@ extern "C" MESA_EXPORT mesa_status mesa_attn_av_bwd_q(const int8_t *aq, const in
     do { \
         if (tn_fits<true>(N, Dh) && batches < (int64_t(1) << 31)) \
             launch_tn<true, ET>(aq, dO, a.c, batches, int(N), int(Dh), int(H), 1.0f, alpha_a, beta_a, s); \
+        else if (tn_cols_fits(batches, N, Dh)) \
+            launch_tn_cols<true, ET>(aq, dO, a.c, batches, int(N), int(Dh), int(H), 1.0f, alpha_a, beta_a, s); \
         else \
             launch_bmm<true, false, false, ET>(a, batches, s); \
     } while (0)
@@ -1178,6 +1528,8 @@ extern "C" MESA_EXPORT mesa_status mesa_attn_qk_bwd_q(const int8_t *qq, const in
     do { \
         if (tn_fits<false>(N, Dh) && batches < (int64_t(1) << 31)) \
             launch_tn<false, ET>(dS, qq, a.c, batches, int(N), int(Dh), int(H), scale, alpha_q, beta_q, s); \
+        else if (tn_cols_fits(batches, N, Dh)) \
+            launch_tn_cols<false, ET>(dS, qq, a.c, batches, int(N), int(Dh), int(H), scale, alpha_q, beta_q, s); \
         else \
             launch_bmm<false, false, false, ET>(a, batches, s); \
     } while (0)

@@ -391,6 +391,16 @@ def test_attention_matmul_backward_bfloat16(M, B, H, N, Dh):
     _attention_case(M, B, H, N, Dh, torch.bfloat16)
 
 
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16], ids=["f16", "bf16"])
+@pytest.mark.parametrize("B,H,N,Dh", [(1, 2, 272, 64), (1, 1, 512, 32), (1, 2, 528, 128), (1, 1, 1024, 64), (2, 1, 304, 64), (1, 3, 288, 32),
+                                      (1, 1, 784, 128), (1, 2, 264, 64), (1, 1, 328, 32)])
+def test_attention_matmul_backward_long_sequences(M, B, H, N, Dh, dtype):
+    """Sequences beyond one workgroup per head, multiples of 16: the column-tile kernels -- a ragged last column tile
+    (272, 304, 528, 784), a last chunk of 16 rows (272, 304, 528, 784), several whole tiles (512, 1024), every head size;
+    264 and 328 are multiples of 8 only (dA by column tiles, the rest by the general kernel)."""
+    _attention_case(M, B, H, N, Dh, dtype)
+
+
 @pytest.mark.parametrize("B,H,N,Dh", [(2, 3, 19, 8), (2, 3, 197, 64), (1, 2, 65, 40), (2, 2, 49, 32)])
 def test_attention_matmul_backward_binary32(M, B, H, N, Dh):
     """The same products on binary32 tensors (one plain kernel), to the binary32 bound."""
