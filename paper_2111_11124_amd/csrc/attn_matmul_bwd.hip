@@ -19,6 +19,10 @@
 // fragments come from the LDS transpose reads.  The next stage's loads are in flight while a stage
 // is multiplied.  binary16 or bfloat16 tensors (every kernel here takes the number type as a parameter);
 // binary32 tensors through one plain kernel (k_bmm_q_f32).
+//
+// That general kernel (k_bmm_q) serves every shape; dedicated kernels take the shapes that matter: k_attn_da,
+// k_attn_tn, k_attn_nn for sequences one workgroup per head (or per 32 rows) can hold, odd lengths included, and
+// k_attn_da_cols, k_attn_tn_cols, k_attn_nn_rows for long sequences whose rows are aligned (N a multiple of 8 or 16).
 #include <hip/hip_runtime.h>
 #include <type_traits>
 
@@ -1269,6 +1273,143 @@ __global__ __launch_bounds__(NnCfg<DT>::kNt, 3) void k_attn_nn(const _Float16 *_
     }
 }
 
+// ---- dQ for long sequences (N a multiple of 8): a workgroup takes 64 rows i of one head and walks along the columns ----
+// j in chunks of 128 (64 at head size 128): per chunk 64 row segments of dS (aligned 16-byte vectors) and the chunk's rows
+// of K codes, both in LDS row by row, the next chunk's vectors waiting in registers (two LDS buffers, one barrier per
+// chunk).  Wave w takes rows 32 (w & 1) ..+31 and the d tiles of parity w >> 1.  A lane's dS fragment (its row, eight
+// consecutive j) is one aligned 16-byte LDS read; the codes come through the byte-transposing read.  Codes on the M
+// side as in k_attn_nn: a lane ends up with one row i and runs of four consecutive d.  dS is read exactly once.
+template <int DT> struct NrCfg {
+    static constexpr int Dh = 32 * DT;
+    static constexpr int kJC = DT <= 2 ? 128 : 64;         // columns per chunk
+    static constexpr int kPitchS = kJC * 2 + 16;           // bytes per staged row segment of dS: 16 (mod 128), eight rows' reads on different banks
+    static constexpr int kRowK = Dh + 32;                  // bytes per staged code row
+    static constexpr int kTiles = DT >= 2 ? DT / 2 : 1;
+    static constexpr int kVecRowS = kJC / 8, kVecRowK = Dh / 16;
+    static constexpr int kSVecs = 64 * kVecRowS / kThreads, kKVecs = (kJC * kVecRowK + kThreads - 1) / kThreads;
+    static constexpr int kStage = 64 * kPitchS + kJC * kRowK;
+    static constexpr int kLds = 2 * kStage;
+};
+
+template <int DT, typename ET>
+__global__ __launch_bounds__(kThreads, 2) void k_attn_nn_rows(const _Float16 *__restrict__ dS, const int8_t *__restrict__ kq,
+                                                              _Float16 *__restrict__ dQ, int N, int heads, int tiles_i, float scale,
+                                                              const float *__restrict__ alpha_k, const float *__restrict__ beta_k)
+{
+    typedef NrCfg<DT> C;
+    __shared__ __attribute__((aligned(16))) unsigned char lds_nr[C::kLds];
+    constexpr int Dh = C::Dh;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t bh = blockIdx.x / unsigned(tiles_i);
+    const int i0 = int(blockIdx.x % unsigned(tiles_i)) * 64;
+    const int rows = N - i0 < 64 ? N - i0 : 64;
+    const int fl = lane & 31, half = lane >> 5, blk = lane >> 4, sl = lane & 15;
+    const int nchunks = (N + C::kJC - 1) / C::kJC;
+    const unsigned char *srow = reinterpret_cast<const unsigned char *>(dS + (bh * N + i0) * int64_t(N));
+    const unsigned char *krow = reinterpret_cast<const unsigned char *>(kq + bh * N * int64_t(Dh));
+
+    u32x4 sv[C::kSVecs], kv[C::kKVecs];
+    auto load_chunk = [&](int c) {
+        const int j0 = c * C::kJC;
+        const int cols = N - j0 < C::kJC ? N - j0 : C::kJC;   // a multiple of 8
+#pragma unroll
+        for (int k = 0; k < C::kSVecs; ++k) {
+            const int v = tid + k * kThreads, r = v / C::kVecRowS, cv = v % C::kVecRowS;
+            sv[k] = u32x4{0u, 0u, 0u, 0u};              // columns past N meet codes of zero weight: zeros; rows past the end are never written
+            if (r < rows && cv * 8 < cols) sv[k] = *reinterpret_cast<const u32x4 *>(srow + (int64_t(r) * N + j0 + cv * 8) * 2);
+        }
+        const u32x4 *ksrc = reinterpret_cast<const u32x4 *>(krow + int64_t(j0) * Dh);
+#pragma unroll
+        for (int k = 0; k < C::kKVecs; ++k) {
+            const int v = tid + k * kThreads;
+            kv[k] = v < cols * C::kVecRowK ? ksrc[v] : u32x4{0u, 0u, 0u, 0u};
+        }
+    };
+    auto store_chunk = [&](int b) {
+        unsigned char *ls = lds_nr + b * C::kStage, *lk = ls + 64 * C::kPitchS;
+#pragma unroll
+        for (int k = 0; k < C::kSVecs; ++k) {
+            const int v = tid + k * kThreads;
+            *reinterpret_cast<u32x4 *>(ls + (v / C::kVecRowS) * C::kPitchS + (v % C::kVecRowS) * 16) = sv[k];
+        }
+#pragma unroll
+        for (int k = 0; k < C::kKVecs; ++k) {
+            const int v = tid + k * kThreads;
+            if (v < C::kJC * C::kVecRowK) *reinterpret_cast<u32x4 *>(lk + (v / C::kVecRowK) * C::kRowK + (v % C::kVecRowK) * 16) = kv[k];
+        }
+    };
+
+    const int i_loc = (wave & 1) * 32 + fl;
+    const int tpar = wave >> 1;                            // this wave's d tiles: tpar, tpar + 2, ..  (DT == 1: only parity 0 multiplies)
+    const bool wave_live = (wave & 1) * 32 < rows && (DT >= 2 || tpar == 0);
+    const int s_at = i_loc * C::kPitchS + half * 16;
+    const int k_at = ((blk >> 1) * 8 + (sl >> 1)) * C::kRowK + (blk & 1) * 16 + (sl & 1) * 8 + tpar * 32;
+    bm_v16f acc[C::kTiles];
+#pragma unroll
+    for (int t = 0; t < C::kTiles; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
+    float rsum = 0.0f;
+
+    load_chunk(0);
+    for (int c = 0; c < nchunks; ++c) {
+        const int b = c & 1;
+        store_chunk(b);
+        if (c + 1 < nchunks) load_chunk(c + 1);
+        __syncthreads();   // chunk c is in LDS; every wave has finished with chunk c - 1 (the other buffer)
+        if (!wave_live) continue;
+        const unsigned char *ls = lds_nr + b * C::kStage, *lk = ls + 64 * C::kPitchS;
+        const int cols = N - c * C::kJC < C::kJC ? N - c * C::kJC : C::kJC;
+#pragma unroll
+        for (int ks = 0; ks < C::kJC / 16; ++ks) {
+            if (ks * 16 >= cols) break;                    // uniform; a last step of eight columns multiplies zeros in its second half
+            const bm_v8h fs = *reinterpret_cast<const bm_v8h *>(ls + s_at + ks * 32);
+#pragma unroll
+            for (int q = 0; q < 8; q += 2) rsum = BmNum<ET>::dot_ones(fs[q], fs[q + 1], rsum);
+#pragma unroll
+            for (int t = 0; t < C::kTiles; ++t) {
+                const bm_v8h fc = BmNum<ET>::codes8(__builtin_amdgcn_ds_read_tr8_b64_v2i32(BM_LDS3(bm_v2i, lk + k_at + ks * 16 * C::kRowK + t * 64)));
+                acc[t] = BmNum<ET>::mfma(fc, fs, acc[t]);
+            }
+        }
+    }
+    if (!wave_live) return;
+    rsum += __shfl_xor(rsum, 32);                          // both halves of the row's slots
+    if (i_loc < rows) {
+        // lane l, register v of a tile: d = 32*(tile) + 8*(v/4) + 4*(l/32) + v%4, row i = l%32
+        const int h = int(bh % heads);
+        const float s = alpha_k[h] / 255.0f;
+        const float add = fmaf(BmNum<ET>::kCentre, s, beta_k[h]) * rsum;
+        _Float16 *po = dQ + (bh * N + i0 + i_loc) * int64_t(Dh) + tpar * 32 + half * 4;
+#pragma unroll
+        for (int t = 0; t < C::kTiles; ++t)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                bm_v4h o;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) o[k] = BmNum<ET>::round(scale * fmaf(s, acc[t][4 * g + k], add));
+                *reinterpret_cast<bm_v4h *>(po + t * 64 + g * 8) = o;
+            }
+    }
+}
+
+static bool nn_rows_fits(int64_t batches, int64_t N, int64_t Dh)
+{
+    if (Dh != 32 && Dh != 64 && Dh != 128) return false;
+    return N % 8 == 0 && N >= 32 && batches * ceil_div(N, 64) < (int64_t(1) << 31);
+}
+
+template <typename ET>
+static void launch_nn_rows(const _Float16 *dS, const int8_t *kq, _Float16 *dQ, int64_t batches, int N, int Dh, int heads, float scale,
+                           const float *alpha_k, const float *beta_k, hipStream_t s)
+{
+    const int tiles_i = int(ceil_div(N, 64));
+    const dim3 grid(unsigned(batches * tiles_i));
+    if (Dh == 32) hipLaunchKernelGGL((k_attn_nn_rows<1, ET>), grid, dim3(kThreads), 0, s, dS, kq, dQ, N, heads, tiles_i, scale, alpha_k, beta_k);
+    else if (Dh == 64) hipLaunchKernelGGL((k_attn_nn_rows<2, ET>), grid, dim3(kThreads), 0, s, dS, kq, dQ, N, heads, tiles_i, scale, alpha_k, beta_k);
+    else hipLaunchKernelGGL((k_attn_nn_rows<4, ET>), grid, dim3(kThreads), 0, s, dS, kq, dQ, N, heads, tiles_i, scale, alpha_k, beta_k);
+}
+
 // whether k_attn_da can take the shape, and in which mode
 static bool da_solo(int64_t batches, int64_t N) { return N <= 64 && batches * ceil_div(N, 32) < (int64_t(1) << 32); }
 template <int KS> static bool da_fits(int64_t batches, int64_t N) { return DaCfg<KS>::lds_bytes(N, da_solo(batches, N)) <= 65536; }
@@ -1515,7 +1656,9 @@ extern "C" MESA_EXPORT mesa_status mesa_attn_qk_bwd_q(const int8_t *qq, const in
             if (Dh == 32) launch_nn<1, ET>(a.x, kq, a.c, batches, int(N), int(H), scale, alpha_k, beta_k, s); \
             else if (Dh == 64) launch_nn<2, ET>(a.x, kq, a.c, batches, int(N), int(H), scale, alpha_k, beta_k, s); \
             else launch_nn<4, ET>(a.x, kq, a.c, batches, int(N), int(H), scale, alpha_k, beta_k, s); \
-        } else \
+        } else if (nn_rows_fits(batches, N, Dh)) \
+            launch_nn_rows<ET>(a.x, kq, a.c, batches, int(N), int(Dh), int(H), scale, alpha_k, beta_k, s); \
+        else \
             launch_bmm<false, true, false, ET>(a, batches, s); \
     } while (0)
     if (dt == MESA_BF16) MESA_QK_DQ(__bf16); else MESA_QK_DQ(_Float16);
