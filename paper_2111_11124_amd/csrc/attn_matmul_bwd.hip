@@ -1030,7 +1030,7 @@ __global__ __launch_bounds__((TcCfg<DT, WIDE_CODED>::kNt), DT == 4 ? 1 : 2) void
     };
 
     bm_v16f acc[C::kJB][DT];
-    bm_v16f acc1[WIDE_CODED ? DT : 1];                     // dV: column sums of dO per d, from MFMAs against ones
+    float dsum[DT];                                        // dV: column sums of dO for d = 32 dt + l%32 over this lane's rows
     float csum[C::kJB];                                    // dK: column sums of dS per j, per lane
 #pragma unroll
     for (int jb = 0; jb < C::kJB; ++jb) {
@@ -1041,12 +1041,7 @@ __global__ __launch_bounds__((TcCfg<DT, WIDE_CODED>::kNt), DT == 4 ? 1 : 2) void
             for (int v = 0; v < 16; ++v) acc[jb][dt][v] = 0.0f;
     }
 #pragma unroll
-    for (int dt = 0; dt < (WIDE_CODED ? DT : 1); ++dt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc1[dt][v] = 0.0f;
-    bm_v8h ones;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) ones[j] = __builtin_bit_cast(_Float16, BmNum<ET>::kOne);
+    for (int dt = 0; dt < DT; ++dt) dsum[dt] = 0.0f;
     // transposing reads: lane gets column (first column) + l%32 and the rows (first row) + 8*(l/32) ..+7
     const int wide_at = WIDE_CODED ? ((blk >> 1) * 8 + (sl >> 1)) * C::kPitchW + wave * 64 + (blk & 1) * 16 + (sl & 1) * 8
                                    : ((blk >> 1) * 8 + (sl >> 2)) * C::kPitchW + (wave * 64 + (blk & 1) * 16 + (sl & 3) * 4) * 2;
@@ -1074,7 +1069,8 @@ __global__ __launch_bounds__((TcCfg<DT, WIDE_CODED>::kNt), DT == 4 ? 1 : 2) void
                     const bm_v4h lo = __builtin_bit_cast(bm_v4h, __builtin_amdgcn_ds_read_tr16_b64_v4i16(BM_LDS3(bm_v4s, p)));
                     const bm_v4h hi = __builtin_bit_cast(bm_v4h, __builtin_amdgcn_ds_read_tr16_b64_v4i16(BM_LDS3(bm_v4s, p + 4 * C::kRowN)));
                     fn[dt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    acc1[dt] = BmNum<ET>::mfma(fn[dt], ones, acc1[dt]);
+#pragma unroll
+                    for (int q = 0; q < 8; q += 2) dsum[dt] = BmNum<ET>::dot_ones(fn[dt][q], fn[dt][q + 1], dsum[dt]);
                 } else {
                     fn[dt] = BmNum<ET>::codes8(__builtin_amdgcn_ds_read_tr8_b64_v2i32(BM_LDS3(bm_v2i, ln + narrow_at + ks * 16 * C::kRowN + dt * 32)));
                 }
@@ -1109,6 +1105,18 @@ __global__ __launch_bounds__((TcCfg<DT, WIDE_CODED>::kNt), DT == 4 ? 1 : 2) void
     const int h = int(bh % heads);
     const float s = alpha[h] / 255.0f;
     const float off = fmaf(BmNum<ET>::kCentre, s, beta[h]);
+    float *dsums = reinterpret_cast<float *>(lds_tc);      // dV: the sums of dO per d, for every lane to pick its four
+    if (WIDE_CODED) {
+        __syncthreads();                                   // every wave is done with the chunks
+        if (wave == 0) {                                   // (a live wave: column 0 of the tile always exists)
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                const float t = dsum[dt] + __shfl_xor(dsum[dt], 32);   // both halves of the rows
+                if (half == 0) dsums[dt * 32 + fl] = t;
+            }
+        }
+        __syncthreads();
+    }
 #pragma unroll
     for (int jb = 0; jb < C::kJB; ++jb) {
         const int j = j0 + wave * 64 + jb * 32 + fl;
@@ -1123,7 +1131,7 @@ __global__ __launch_bounds__((TcCfg<DT, WIDE_CODED>::kNt), DT == 4 ? 1 : 2) void
                 bm_v4h o;
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
-                    const float add = WIDE_CODED ? off * acc1[dt][4 * g + k] : cs;
+                    const float add = WIDE_CODED ? off * dsums[dt * 32 + g * 8 + half * 4 + k] : cs;
                     o[k] = BmNum<ET>::round(scale * fmaf(s, acc[jb][dt][4 * g + k], add));
                 }
                 *reinterpret_cast<bm_v4h *>(po + dt * 32 + g * 8) = o;
