@@ -1282,14 +1282,14 @@ __global__ __launch_bounds__(NnCfg<DT>::kNt, 3) void k_attn_nn(const _Float16 *_
 }
 
 // ---- dQ for long sequences (N a multiple of 8): a workgroup takes 64 rows i of one head and walks along the columns ----
-// j in chunks of 128 (64 at head size 128): per chunk 64 row segments of dS (aligned 16-byte vectors) and the chunk's rows
-// of K codes, both in LDS row by row, the next chunk's vectors waiting in registers (two LDS buffers, one barrier per
-// chunk).  Wave w takes rows 32 (w & 1) ..+31 and the d tiles of parity w >> 1.  A lane's dS fragment (its row, eight
+// j in chunks of 64 (larger chunks cost workgroups per CU, which cost more than the shorter row segments): per chunk 64
+// row segments of dS (aligned 16-byte vectors) and the chunk's rows of K codes, both in LDS row by row, the next two
+// chunks' vectors waiting in registers (two LDS buffers, one barrier per chunk).  Wave w takes rows 32 (w & 1) ..+31 and the d tiles of parity w >> 1.  A lane's dS fragment (its row, eight
 // consecutive j) is one aligned 16-byte LDS read; the codes come through the byte-transposing read.  Codes on the M
 // side as in k_attn_nn: a lane ends up with one row i and runs of four consecutive d.  dS is read exactly once.
 template <int DT> struct NrCfg {
     static constexpr int Dh = 32 * DT;
-    static constexpr int kJC = DT <= 2 ? 128 : 64;         // columns per chunk
+    static constexpr int kJC = 64;                         // columns per chunk
     static constexpr int kPitchS = kJC * 2 + 16;           // bytes per staged row segment of dS: 16 (mod 128), eight rows' reads on different banks
     static constexpr int kRowK = Dh + 32;                  // bytes per staged code row
     static constexpr int kTiles = DT >= 2 ? DT / 2 : 1;
@@ -1297,6 +1297,7 @@ template <int DT> struct NrCfg {
     static constexpr int kSVecs = 64 * kVecRowS / kThreads, kKVecs = (kJC * kVecRowK + kThreads - 1) / kThreads;
     static constexpr int kStage = 64 * kPitchS + kJC * kRowK;
     static constexpr int kLds = 2 * kStage;
+    static constexpr int kAhead = 2;                       // chunks in registers ahead of the one in LDS
 };
 
 template <int DT, typename ET>
@@ -1316,34 +1317,36 @@ __global__ __launch_bounds__(kThreads, 2) void k_attn_nn_rows(const _Float16 *__
     const unsigned char *srow = reinterpret_cast<const unsigned char *>(dS + (bh * N + i0) * int64_t(N));
     const unsigned char *krow = reinterpret_cast<const unsigned char *>(kq + bh * N * int64_t(Dh));
 
-    u32x4 sv[C::kSVecs], kv[C::kKVecs];
-    auto load_chunk = [&](int c) {
+    u32x4 sv[C::kAhead][C::kSVecs], kv[C::kAhead][C::kKVecs];
+    auto load_chunk = [&](int c, auto set_) {
+        constexpr int S = decltype(set_)::value;
         const int j0 = c * C::kJC;
         const int cols = N - j0 < C::kJC ? N - j0 : C::kJC;   // a multiple of 8
 #pragma unroll
         for (int k = 0; k < C::kSVecs; ++k) {
             const int v = tid + k * kThreads, r = v / C::kVecRowS, cv = v % C::kVecRowS;
-            sv[k] = u32x4{0u, 0u, 0u, 0u};              // columns past N meet codes of zero weight: zeros; rows past the end are never written
-            if (r < rows && cv * 8 < cols) sv[k] = *reinterpret_cast<const u32x4 *>(srow + (int64_t(r) * N + j0 + cv * 8) * 2);
+            sv[S][k] = u32x4{0u, 0u, 0u, 0u};           // columns past N meet codes of zero weight: zeros; rows past the end are never written
+            if (r < rows && cv * 8 < cols) sv[S][k] = *reinterpret_cast<const u32x4 *>(srow + (int64_t(r) * N + j0 + cv * 8) * 2);
         }
         const u32x4 *ksrc = reinterpret_cast<const u32x4 *>(krow + int64_t(j0) * Dh);
 #pragma unroll
         for (int k = 0; k < C::kKVecs; ++k) {
             const int v = tid + k * kThreads;
-            kv[k] = v < cols * C::kVecRowK ? ksrc[v] : u32x4{0u, 0u, 0u, 0u};
+            kv[S][k] = v < cols * C::kVecRowK ? ksrc[v] : u32x4{0u, 0u, 0u, 0u};
         }
     };
-    auto store_chunk = [&](int b) {
+    auto store_chunk = [&](int b, auto set_) {
+        constexpr int S = decltype(set_)::value;
         unsigned char *ls = lds_nr + b * C::kStage, *lk = ls + 64 * C::kPitchS;
 #pragma unroll
         for (int k = 0; k < C::kSVecs; ++k) {
             const int v = tid + k * kThreads;
-            *reinterpret_cast<u32x4 *>(ls + (v / C::kVecRowS) * C::kPitchS + (v % C::kVecRowS) * 16) = sv[k];
+            *reinterpret_cast<u32x4 *>(ls + (v / C::kVecRowS) * C::kPitchS + (v % C::kVecRowS) * 16) = sv[S][k];
         }
 #pragma unroll
         for (int k = 0; k < C::kKVecs; ++k) {
             const int v = tid + k * kThreads;
-            if (v < C::kJC * C::kVecRowK) *reinterpret_cast<u32x4 *>(lk + (v / C::kVecRowK) * C::kRowK + (v % C::kVecRowK) * 16) = kv[k];
+            if (v < C::kJC * C::kVecRowK) *reinterpret_cast<u32x4 *>(lk + (v / C::kVecRowK) * C::kRowK + (v % C::kVecRowK) * 16) = kv[S][k];
         }
     };
 
@@ -1359,13 +1362,13 @@ __global__ __launch_bounds__(kThreads, 2) void k_attn_nn_rows(const _Float16 *__
         for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
     float rsum = 0.0f;
 
-    load_chunk(0);
-    for (int c = 0; c < nchunks; ++c) {
+    // chunk c waits in register set c % 2; it goes to LDS buffer c % 2 when chunk c - 1 is being multiplied
+    auto chunk_step = [&](int c, auto set_) {
         const int b = c & 1;
-        store_chunk(b);
-        if (c + 1 < nchunks) load_chunk(c + 1);
+        store_chunk(b, set_);
+        if (c + C::kAhead < nchunks) load_chunk(c + C::kAhead, set_);
         __syncthreads();   // chunk c is in LDS; every wave has finished with chunk c - 1 (the other buffer)
-        if (!wave_live) continue;
+        if (!wave_live) return;
         const unsigned char *ls = lds_nr + b * C::kStage, *lk = ls + 64 * C::kPitchS;
         const int cols = N - c * C::kJC < C::kJC ? N - c * C::kJC : C::kJC;
 #pragma unroll
@@ -1380,6 +1383,12 @@ __global__ __launch_bounds__(kThreads, 2) void k_attn_nn_rows(const _Float16 *__
                 acc[t] = BmNum<ET>::mfma(fc, fs, acc[t]);
             }
         }
+    };
+    load_chunk(0, std::integral_constant<int, 0>());
+    if (nchunks > 1) load_chunk(1, std::integral_constant<int, 1>());
+    for (int c = 0; c < nchunks; c += 2) {
+        chunk_step(c, std::integral_constant<int, 0>());
+        if (c + 1 < nchunks) chunk_step(c + 1, std::integral_constant<int, 1>());
     }
     if (!wave_live) return;
     rsum += __shfl_xor(rsum, 32);                          // both halves of the row's slots
