@@ -961,16 +961,17 @@ template <int DT, bool WIDE_CODED> struct TcCfg {
     static constexpr int kJW = 256;                        // columns of the N x N operand per workgroup
     static constexpr int kNt = kJW;                        // threads: a wave per 64 columns (two blocks of 32)
     static constexpr int kJB = 2;
+    static constexpr int kCR = 16;                         // rows per chunk (N is a multiple of 16: no ragged chunk)
     static constexpr int kAhead = WIDE_CODED ? 2 : 1;      // chunks in registers ahead of the one in LDS: the codes' chunks are
                                                            // half the bytes, and it is bytes in flight that hide the latency
     static constexpr int kWideEb = WIDE_CODED ? 1 : 2;
     static constexpr int kPitchW = kJW * kWideEb + (WIDE_CODED ? 16 : 32);   // bytes per staged row segment
     static constexpr int kVecRowW = kJW * kWideEb / 16;    // 16-byte vectors per row segment
-    static constexpr int kWideVecs = 32 * kVecRowW / kNt;   // per thread and chunk: 4 (binary16) or 2 (codes)
+    static constexpr int kWideVecs = kCR * kVecRowW / kNt;   // per thread and chunk: 4 (binary16) or 2 (codes)
     static constexpr int kRowN = WIDE_CODED ? 2 * Dh + 32 : Dh + 32;   // bytes per staged row of the N x Dh operand
     static constexpr int kVecRowN = Dh * (WIDE_CODED ? 2 : 1) / 16;
-    static constexpr int kNarrowVecs = (32 * kVecRowN + kNt - 1) / kNt;
-    static constexpr int kStage = 32 * kPitchW + 32 * kRowN;
+    static constexpr int kNarrowVecs = (kCR * kVecRowN + kNt - 1) / kNt;
+    static constexpr int kStage = kCR * kPitchW + kCR * kRowN;
     static constexpr int kLds = 2 * kStage;
 };
 
@@ -988,7 +989,7 @@ __global__ __launch_bounds__((TcCfg<DT, WIDE_CODED>::kNt), DT == 4 ? 1 : 2) void
     const unsigned char *wide = static_cast<const unsigned char *>(wide_) + (bh * N * int64_t(N) + j0) * C::kWideEb;
     const unsigned char *narrow = static_cast<const unsigned char *>(narrow_) + bh * N * int64_t(Dh) * (WIDE_CODED ? 2 : 1);
     const int fl = lane & 31, half = lane >> 5, blk = lane >> 4, sl = lane & 15;
-    const int nchunks = (N + 31) >> 5;
+    const int nchunks = N / C::kCR;
     const int cols = N - j0 < C::kJW ? N - j0 : C::kJW;    // columns of this tile that exist (a multiple of 16)
 
     // ---- staging: a thread's vectors sit at the same place of every chunk ---------------------------------------------
@@ -1002,15 +1003,15 @@ __global__ __launch_bounds__((TcCfg<DT, WIDE_CODED>::kNt), DT == 4 ? 1 : 2) void
     }
     auto load_chunk = [&](int c, auto set_) {
         constexpr int S = decltype(set_)::value;
-        const int rows = N - c * 32 < 32 ? N - c * 32 : 32;
-        const unsigned char *src = wide + int64_t(c) * 32 * N * C::kWideEb;
+        constexpr int rows = C::kCR;
+        const unsigned char *src = wide + int64_t(c) * C::kCR * N * C::kWideEb;
 #pragma unroll
         for (int k = 0; k < C::kWideVecs; ++k) {
             const int r = (tid + k * C::kNt) / C::kVecRowW;
             wv[S][k] = u32x4{0u, 0u, 0u, 0u};              // columns past N, rows past the end: zeros
             if (w_src[k] >= 0 && r < rows) wv[S][k] = *reinterpret_cast<const u32x4 *>(src + w_src[k]);
         }
-        const u32x4 *nsrc = reinterpret_cast<const u32x4 *>(narrow + int64_t(c) * 32 * Dh * (WIDE_CODED ? 2 : 1));
+        const u32x4 *nsrc = reinterpret_cast<const u32x4 *>(narrow + int64_t(c) * C::kCR * Dh * (WIDE_CODED ? 2 : 1));
 #pragma unroll
         for (int k = 0; k < C::kNarrowVecs; ++k) {
             const int v = tid + k * C::kNt;
@@ -1019,13 +1020,13 @@ __global__ __launch_bounds__((TcCfg<DT, WIDE_CODED>::kNt), DT == 4 ? 1 : 2) void
     };
     auto store_chunk = [&](int b, auto set_) {
         constexpr int S = decltype(set_)::value;
-        unsigned char *lw = lds_tc + b * C::kStage, *ln = lw + 32 * C::kPitchW;
+        unsigned char *lw = lds_tc + b * C::kStage, *ln = lw + C::kCR * C::kPitchW;
 #pragma unroll
         for (int k = 0; k < C::kWideVecs; ++k) *reinterpret_cast<u32x4 *>(lw + w_dst[k]) = wv[S][k];
 #pragma unroll
         for (int k = 0; k < C::kNarrowVecs; ++k) {
             const int v = tid + k * C::kNt;
-            if (v < 32 * C::kVecRowN) *reinterpret_cast<u32x4 *>(ln + (v / C::kVecRowN) * C::kRowN + (v % C::kVecRowN) * 16) = nv[S][k];
+            if (v < C::kCR * C::kVecRowN) *reinterpret_cast<u32x4 *>(ln + (v / C::kVecRowN) * C::kRowN + (v % C::kVecRowN) * 16) = nv[S][k];
         }
     };
 
@@ -1055,12 +1056,10 @@ __global__ __launch_bounds__((TcCfg<DT, WIDE_CODED>::kNt), DT == 4 ? 1 : 2) void
         store_chunk(b, set_);
         if (c + C::kAhead < nchunks) load_chunk(c + C::kAhead, set_);
         __syncthreads();   // chunk c is in LDS; every wave has finished with chunk c - 1 (the other buffer)
-        const int rows = N - c * 32 < 32 ? N - c * 32 : 32;
-        const unsigned char *lw = lds_tc + b * C::kStage, *ln = lw + 32 * C::kPitchW;
+        const unsigned char *lw = lds_tc + b * C::kStage, *ln = lw + C::kCR * C::kPitchW;
         if (!wave_live) return;                          // its columns lie past N (the barrier above is still met)
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            if (ks * 16 >= rows) break;                    // uniform
+        for (int ks = 0; ks < C::kCR / 16; ++ks) {
             bm_v8h fn[DT];
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) {
