@@ -22,7 +22,9 @@
 //
 // That general kernel (k_bmm_q) serves every shape; dedicated kernels take the shapes that matter: k_attn_da,
 // k_attn_tn, k_attn_nn for sequences one workgroup per head (or per 32 rows) can hold, odd lengths included, and
-// k_attn_da_cols, k_attn_tn_cols, k_attn_nn_rows for long sequences whose rows are aligned (N a multiple of 8 or 16).
+// k_attn_da_cols, k_attn_tn_cols, k_attn_nn_rows for sequences of any length whose rows are aligned (N a multiple of 8
+// or 16): long ones, and short ones too -- a pitch of N elements with N a multiple of 32 puts the first three kernels'
+// lanes on the same LDS banks.
 #include <hip/hip_runtime.h>
 #include <type_traits>
 
@@ -1601,14 +1603,16 @@ extern "C" MESA_EXPORT mesa_status mesa_attn_av_bwd_q(const int8_t *aq, const in
         launch_bmm_f32<true>(a, batches, dt, s);
         return launch_status();
     }
-    // the 32 x N output block has to fit the 64 KiB of LDS a kernel gets by default; else the general kernel
+    // aligned rows (N a multiple of 8): the column-tile kernel, at every length -- k_attn_da keeps its 32 x N block at a
+    // pitch of N elements, and for N a multiple of 32 its lanes' rows fall on the same LDS banks (N = 256: 0.73 against
+    // 0.48 ms for the four products).  Else k_attn_da if its block fits the 64 KiB of LDS a kernel gets by default.
 #define MESA_AV_DA(ET) \
     do { \
-        if (Dh == 32 && da_fits<2>(batches, N)) launch_da<2, ET>(a.x, vq, a.c, batches, int(N), int(H), alpha_v, beta_v, s); \
+        if (da_cols_fits(batches, N, Dh)) launch_da_cols<ET>(a.x, vq, a.c, batches, int(N), int(Dh), int(H), alpha_v, beta_v, s); \
+        else if (Dh == 32 && da_fits<2>(batches, N)) launch_da<2, ET>(a.x, vq, a.c, batches, int(N), int(H), alpha_v, beta_v, s); \
         else if (Dh == 64 && da_fits<4>(batches, N)) launch_da<4, ET>(a.x, vq, a.c, batches, int(N), int(H), alpha_v, beta_v, s); \
         else if (Dh == 96 && da_fits<6>(batches, N)) launch_da<6, ET>(a.x, vq, a.c, batches, int(N), int(H), alpha_v, beta_v, s); \
         else if (Dh == 128 && da_fits<8>(batches, N)) launch_da<8, ET>(a.x, vq, a.c, batches, int(N), int(H), alpha_v, beta_v, s); \
-        else if (da_cols_fits(batches, N, Dh)) launch_da_cols<ET>(a.x, vq, a.c, batches, int(N), int(Dh), int(H), alpha_v, beta_v, s); \
         else launch_bmm<false, true, true, ET>(a, batches, s); \
     } while (0)
     if (dt == MESA_BF16) MESA_AV_DA(__bf16); else MESA_AV_DA(_Float16);
@@ -1619,12 +1623,14 @@ extern "C" MESA_EXPORT mesa_status mesa_attn_av_bwd_q(const int8_t *aq, const in
     a.R = int(N); a.Cn = int(Dh); a.Tn = int(N);
     a.p_rs = 1; a.p_ts = N; a.q_ts = Dh; a.q_cs = 1;
     a.alpha = alpha_a; a.beta = beta_a;
+    // aligned rows (N a multiple of 16): the column-tile kernel at every length (k_attn_tn's gathers, a row apart at a
+    // pitch of N elements, meet on the same banks when N is a multiple of 32)
 #define MESA_AV_DV(ET) \
     do { \
-        if (tn_fits<true>(N, Dh) && batches < (int64_t(1) << 31)) \
-            launch_tn<true, ET>(aq, dO, a.c, batches, int(N), int(Dh), int(H), 1.0f, alpha_a, beta_a, s); \
-        else if (tn_cols_fits(batches, N, Dh)) \
+        if (tn_cols_fits(batches, N, Dh)) \
             launch_tn_cols<true, ET>(aq, dO, a.c, batches, int(N), int(Dh), int(H), 1.0f, alpha_a, beta_a, s); \
+        else if (tn_fits<true>(N, Dh) && batches < (int64_t(1) << 31)) \
+            launch_tn<true, ET>(aq, dO, a.c, batches, int(N), int(Dh), int(H), 1.0f, alpha_a, beta_a, s); \
         else \
             launch_bmm<true, false, false, ET>(a, batches, s); \
     } while (0)
@@ -1666,9 +1672,12 @@ extern "C" MESA_EXPORT mesa_status mesa_attn_qk_bwd_q(const int8_t *qq, const in
         launch_bmm_f32<false>(a, batches, dt, s);
         return launch_status();
     }
+    // k_attn_nn (K codes resident) where it fits, except for N a multiple of 32 (its rows' reads meet on the same banks)
 #define MESA_QK_DQ(ET) \
     do { \
-        if (nn_fits(N, Dh) && batches < (int64_t(1) << 31)) { \
+        if (nn_rows_fits(batches, N, Dh) && (N % 32 == 0 || !nn_fits(N, Dh))) \
+            launch_nn_rows<ET>(a.x, kq, a.c, batches, int(N), int(Dh), int(H), scale, alpha_k, beta_k, s); \
+        else if (nn_fits(N, Dh) && batches < (int64_t(1) << 31)) { \
             if (Dh == 32) launch_nn<1, ET>(a.x, kq, a.c, batches, int(N), int(H), scale, alpha_k, beta_k, s); \
             else if (Dh == 64) launch_nn<2, ET>(a.x, kq, a.c, batches, int(N), int(H), scale, alpha_k, beta_k, s); \
             else launch_nn<4, ET>(a.x, kq, a.c, batches, int(N), int(H), scale, alpha_k, beta_k, s); \
@@ -1685,10 +1694,10 @@ extern "C" MESA_EXPORT mesa_status mesa_attn_qk_bwd_q(const int8_t *qq, const in
     a.alpha = alpha_q; a.beta = beta_q;
 #define MESA_QK_DK(ET) \
     do { \
-        if (tn_fits<false>(N, Dh) && batches < (int64_t(1) << 31)) \
-            launch_tn<false, ET>(dS, qq, a.c, batches, int(N), int(Dh), int(H), scale, alpha_q, beta_q, s); \
-        else if (tn_cols_fits(batches, N, Dh)) \
+        if (tn_cols_fits(batches, N, Dh)) \
             launch_tn_cols<false, ET>(dS, qq, a.c, batches, int(N), int(Dh), int(H), scale, alpha_q, beta_q, s); \
+        else if (tn_fits<false>(N, Dh) && batches < (int64_t(1) << 31)) \
+            launch_tn<false, ET>(dS, qq, a.c, batches, int(N), int(Dh), int(H), scale, alpha_q, beta_q, s); \
         else \
             launch_bmm<false, false, false, ET>(a, batches, s); \
     } while (0)
