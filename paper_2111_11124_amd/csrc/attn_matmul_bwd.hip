@@ -1414,7 +1414,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_attn_nn_rows(const _Float16 *__
 static bool nn_rows_fits(int64_t batches, int64_t N, int64_t Dh)
 {
     if (Dh != 32 && Dh != 64 && Dh != 128) return false;
-    return N % 8 == 0 && N >= 32 && batches * ceil_div(N, 64) < (int64_t(1) << 31);
+    return N % 8 == 0 && N >= 64 && batches * ceil_div(N, 64) < (int64_t(1) << 31);
 }
 
 template <typename ET>
@@ -1496,7 +1496,8 @@ static void launch_tn(const void *wide, const void *narrow, _Float16 *out, int64
 static bool da_cols_fits(int64_t batches, int64_t N, int64_t Dh)
 {
     if (Dh != 32 && Dh != 64 && Dh != 128) return false;
-    return N % 8 == 0 && N >= 32 && batches * ceil_div(N, 256) * ceil_div(N, 64) < (int64_t(1) << 31);   // 64: the fewest rows a workgroup takes
+    // from 64 on: below, at most one of a workgroup's four waves has columns (N = 48: 0.28 against 0.24 ms for N = 49 through k_attn_da)
+    return N % 8 == 0 && N >= 64 && batches * ceil_div(N, 256) * ceil_div(N, 64) < (int64_t(1) << 31);   // 64: the fewest rows a workgroup takes
 }
 
 template <typename ET>
@@ -1519,7 +1520,7 @@ static void launch_da_cols(const _Float16 *dO, const int8_t *vq, _Float16 *dA, i
 static bool tn_cols_fits(int64_t batches, int64_t N, int64_t Dh)
 {
     if (Dh != 32 && Dh != 64 && Dh != 128) return false;
-    return N % 16 == 0 && N >= 32 && batches * ceil_div(N, 256) < (int64_t(1) << 31);
+    return N % 16 == 0 && N >= 64 && batches * ceil_div(N, 256) < (int64_t(1) << 31);
 }
 
 template <bool WIDE_CODED, typename ET>
