@@ -524,6 +524,8 @@ extern "C" MESA_EXPORT mesa_status mesa_softmax_bwd_q(const int8_t *yq, int64_t 
         if (rp.sh.lpr == 16) MESA_LAUNCH_SB_C(T, 16, 16); \
         else if (rp.sh.epl == 25) MESA_LAUNCH_SB_C(T, 8, 25); \
         else if (rp.sh.epl == 13) MESA_LAUNCH_SB_C(T, 8, 13); \
+        else if (rp.sh.epl == 16) MESA_LAUNCH_SB_C(T, 8, 16); \
+        else if (rp.sh.epl == 8) MESA_LAUNCH_SB_C(T, 8, 8); \
         else MESA_LAUNCH_SB_C(T, 8, 7); \
     } while (0)
         MESA_FOR_DTYPE(dt, MESA_LAUNCH_SB_T);

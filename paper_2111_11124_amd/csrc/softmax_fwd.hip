@@ -555,6 +555,8 @@ extern "C" MESA_EXPORT mesa_status mesa_softmax_fwd_q(const void *s_in, int64_t 
         if (rp.lpr == 16) MESA_LAUNCH_SR_C(T, 16, 16); \
         else if (rp.epl == 25) MESA_LAUNCH_SR_C(T, 8, 25); \
         else if (rp.epl == 13) MESA_LAUNCH_SR_C(T, 8, 13); \
+        else if (rp.epl == 16) MESA_LAUNCH_SR_C(T, 8, 16); \
+        else if (rp.epl == 8) MESA_LAUNCH_SR_C(T, 8, 8); \
         else MESA_LAUNCH_SR_C(T, 8, 7); \
     } while (0)
         MESA_FOR_DTYPE(dt, MESA_LAUNCH_SR_T);

@@ -87,7 +87,9 @@ inline SrShape sr_shape(int64_t total_rows, int64_t cols)
 {
     SrShape p{};
     if (cols <= 56) { p.lpr = 8; p.epl = 7; }
+    else if (cols <= 64) { p.lpr = 8; p.epl = 8; }         // 8 x 8 windows: every slot used (8 x 13 leaves 38 % idle)
     else if (cols <= 104) { p.lpr = 8; p.epl = 13; }
+    else if (cols <= 128) { p.lpr = 8; p.epl = 16; }
     else if (cols <= 200) { p.lpr = 8; p.epl = 25; }
     else { p.lpr = 16; p.epl = 16; }
     p.tight = cols > int64_t(p.lpr) * (p.epl - 1);

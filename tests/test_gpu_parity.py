@@ -534,7 +534,8 @@ def test_gelu_layer_forward_in_one_pass(M, layout, dtype):
 @pytest.mark.parametrize("B,H,rows,cols", [(3, 6, 197, 197), (5, 3, 49, 49), (2, 4, 64, 64), (1, 2, 33, 1000), (2, 3, 7, 19), (1, 1, 5, 8),
                                            (2, 2, 9, 3), (1, 3, 11, 57), (2, 1, 13, 104), (1, 2, 30, 105), (3, 1, 5, 200), (1, 2, 17, 201),
                                            (2, 2, 6, 256), (1, 2, 10, 257), (40, 3, 61, 61), (1, 1, 3, 4096),
-                                           (1, 2, 5, 1025), (1, 1, 3, 4097), (2, 1, 2, 9001), (1, 1, 2, 8200), (1, 1100, 2, 300)])
+                                           (1, 2, 5, 1025), (1, 1, 3, 4097), (2, 1, 2, 9001), (1, 1, 2, 8200), (1, 1100, 2, 300),
+                                           (2, 2, 9, 57), (1, 3, 8, 63), (2, 1, 5, 105), (1, 2, 6, 128), (1, 1, 7, 120)])
 def test_softmax_backward_every_row_shape(M, B, H, rows, cols, dtype):
     """Softmax backward at head-wise codes over every lane-group shape of the short-row kernel (and both of its
     variants), rows shorter than a vector, ragged tiles, tiles that straddle heads, and the long-row kernel; the plain
@@ -559,7 +560,8 @@ def test_softmax_backward_every_row_shape(M, B, H, rows, cols, dtype):
 @pytest.mark.parametrize("dtype", DTYPES, ids=DTYPE_IDS)
 @pytest.mark.parametrize("B,H,rows,cols", [(3, 6, 197, 197), (5, 3, 49, 49), (2, 4, 64, 64), (1, 2, 33, 1000), (2, 3, 7, 19), (1, 1, 5, 8),
                                            (2, 2, 9, 3), (1, 3, 11, 57), (2, 1, 13, 104), (1, 2, 30, 105), (3, 1, 5, 200), (1, 2, 17, 201),
-                                           (2, 2, 6, 256), (1, 2, 10, 257), (40, 3, 61, 61)])
+                                           (2, 2, 6, 256), (1, 2, 10, 257), (40, 3, 61, 61),
+                                           (2, 2, 9, 57), (1, 3, 8, 63), (2, 1, 5, 105), (1, 2, 6, 128), (1, 1, 7, 120)])
 def test_softmax_layer_forward_in_one_pass(M, B, H, rows, cols, dtype):
     """y = softmax(s) within tolerance of the oracle's binary64 softmax and with rows that sum to 1; the codes and
     the moved estimates are exactly the oracle's single-pass forward applied to the y the kernel stored
