@@ -506,6 +506,56 @@ __global__ __launch_bounds__(kThreads) void k_dw_reduce(const float *__restrict_
     if (db && kk == 0) db[n] = s0;
 }
 
+// Small matrices with many slices (the narrow layers of a windowed transformer: 96 x 96 outputs, 128 slices): too few
+// outputs to hide 128 dependent loads per thread behind other threads' -- eight threads share an output vector, each adds
+// every eighth slice in order, and the eight partial sums are added in a fixed order.
+__global__ __launch_bounds__(kThreads) void k_dw_reduce_few(const float *__restrict__ P, const float *__restrict__ S0, int splits,
+                                                            int N, int K, FastDiv div_k4, FastDiv div_per,
+                                                            const float *__restrict__ alpha, const float *__restrict__ beta,
+                                                            float centre, float *__restrict__ dW, float *__restrict__ db)
+{
+    __shared__ float4 part1[8][32];
+    __shared__ float part0[8][32];
+    const int vl = threadIdx.x & 31, sl = threadIdx.x >> 5;
+    const int64_t idx = int64_t(blockIdx.x) * 32 + vl;
+    const int64_t nvec = int64_t(N) * (K / 4);
+    const bool live = idx < nvec;
+    const uint32_t n = live ? fastdiv(uint32_t(idx), div_k4) : 0u;
+    const uint32_t kk = live ? (uint32_t(idx) - n * div_k4.d) * 4 : 0u;
+    float4 s1 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    float s0 = 0.0f;
+    if (live) {
+        for (int sp = sl; sp < splits; sp += 8) {
+            const float4 p = *reinterpret_cast<const float4 *>(P + (int64_t(sp) * N + n) * K + kk);
+            s1.x += p.x; s1.y += p.y; s1.z += p.z; s1.w += p.w;
+            s0 += S0[int64_t(sp) * N + n];
+        }
+    }
+    part1[sl][vl] = s1;
+    part0[sl][vl] = s0;
+    __syncthreads();
+    if (sl != 0 || !live) return;
+    float o[4], t0;
+    {
+        float4 q[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) q[i] = part1[i][vl];
+        o[0] = ((q[0].x + q[1].x) + (q[2].x + q[3].x)) + ((q[4].x + q[5].x) + (q[6].x + q[7].x));
+        o[1] = ((q[0].y + q[1].y) + (q[2].y + q[3].y)) + ((q[4].y + q[5].y) + (q[6].y + q[7].y));
+        o[2] = ((q[0].z + q[1].z) + (q[2].z + q[3].z)) + ((q[4].z + q[5].z) + (q[6].z + q[7].z));
+        o[3] = ((q[0].w + q[1].w) + (q[2].w + q[3].w)) + ((q[4].w + q[5].w) + (q[6].w + q[7].w));
+        t0 = ((part0[0][vl] + part0[1][vl]) + (part0[2][vl] + part0[3][vl])) + ((part0[4][vl] + part0[5][vl]) + (part0[6][vl] + part0[7][vl]));
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t g = fastdiv(kk + j, div_per);
+        const float sg = alpha[g] / 255.0f;
+        o[j] = fmaf(sg, o[j], fmaf(centre, sg, beta[g]) * t0);
+    }
+    *reinterpret_cast<float4 *>(dW + int64_t(n) * K + kk) = make_float4(o[0], o[1], o[2], o[3]);
+    if (db && kk == 0) db[n] = t0;
+}
+
 // the same for any K: one output per thread
 __global__ __launch_bounds__(kThreads) void k_dw_reduce_any(const float *__restrict__ P, const float *__restrict__ S0, int splits,
                                                             int N, int K, FastDiv div_k, FastDiv div_per,
@@ -540,7 +590,7 @@ static DwPlan dw_plan(int64_t M, int64_t K, int64_t N, mesa_dtype dt)
         // 256-wide k tiles unless they would waste much of the last one.  (A 128 x 384 tile for K = 384 was
         // measured too: no faster per MFMA, and its 21 slices instead of 14 cost more partial-sum traffic.)
         if (K % 256 == 0 || K > 1024) { p.variant = 0; p.bn = 256; p.bk = 256; }
-        else if (K <= 128 && N % 256 != 0 && N % 256 <= 128) { p.variant = 3; p.bn = 128; p.bk = 128; }   // narrow K: no empty half tile in N
+        else if ((K <= 128 || N <= 128) && N % 256 != 0 && N % 256 <= 128) { p.variant = 3; p.bn = 128; p.bk = 128; }   // narrow K or N: no empty half tile in N
         else { p.variant = 1; p.bn = 256; p.bk = 128; }
     } else {
         p.variant = 2;
@@ -556,7 +606,7 @@ static DwPlan dw_plan(int64_t M, int64_t K, int64_t N, mesa_dtype dt)
     int64_t max_splits = M / 256;
     if (max_splits < 1) max_splits = 1;
     if (splits > max_splits) splits = max_splits;
-    if (splits > 128) splits = 128;   // the second kernel adds the slices one after the other
+    if (splits > 256) splits = 256;   // one workgroup per CU also where there is a single tile
     int64_t rps = ceil_div(ceil_div(M > 0 ? M : 1, splits), kDwBM) * kDwBM;
     splits = ceil_div(M > 0 ? M : 1, rps);
     p.splits = int(splits);
@@ -619,8 +669,12 @@ extern "C" MESA_EXPORT mesa_status mesa_linear_dw_q(const int8_t *xq, int64_t M,
     if (K % 4 == 0) {
         const int64_t nvec = N_out * (K / 4);
         FastDiv dk4 = make_fastdiv(uint32_t(K / 4));
-        hipLaunchKernelGGL(k_dw_reduce, dim3(unsigned(ceil_div(nvec, kThreads))), dim3(kThreads), 0, s, P, S0, p.splits, Ni, Ki, dk4,
-                           dper, alpha, beta, centre, dW, db);
+        if (nvec <= 65536 && p.splits >= 16)
+            hipLaunchKernelGGL(k_dw_reduce_few, dim3(unsigned(ceil_div(nvec, 32))), dim3(kThreads), 0, s, P, S0, p.splits, Ni, Ki, dk4,
+                               dper, alpha, beta, centre, dW, db);
+        else
+            hipLaunchKernelGGL(k_dw_reduce, dim3(unsigned(ceil_div(nvec, kThreads))), dim3(kThreads), 0, s, P, S0, p.splits, Ni, Ki, dk4,
+                               dper, alpha, beta, centre, dW, db);
     } else {
         FastDiv dk = make_fastdiv(uint32_t(K));
         hipLaunchKernelGGL(k_dw_reduce_any, dim3(unsigned(ceil_div(N_out * K, kThreads))), dim3(kThreads), 0, s, P, S0, p.splits, Ni,
