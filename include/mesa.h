@@ -137,8 +137,9 @@ mesa_status mesa_update_running_params_fixed_beta(const void *x, mesa_dtype dt, 
  * device array that the library owns (mesa_static_scratch_bytes() = 1 MiB per GPU, held until the
  * process ends) instead of a caller's workspace.  Same kernels, same results bit for bit.  The call
  * allocates nothing and frees nothing; its first use on a device looks the array's address up once.
- * Limit: shapes whose MESA_OP_UPDATE_RUNNING_PARAMS workspace exceeds the array (groups > 4096)
- * return MESA_ERR_UNSUPPORTED.  Every call on a GPU shares that GPU's array: two calls that overlap
+ * Limit: groups <= 4096 (the array holds the partial extrema, 8 bytes per group, of at least 32
+ * workgroups), else MESA_ERR_UNSUPPORTED; with many groups the scan runs on as many workgroups as
+ * the array has room for (fewer than with a caller's workspace: slower, same results).  Every call on a GPU shares that GPU's array: two calls that overlap
  * in time on one GPU (distinct streams, or threads) race; calls on one stream do not.
  */
 mesa_status mesa_update_running_params_static(const void *x, mesa_dtype dt, mesa_layout L,

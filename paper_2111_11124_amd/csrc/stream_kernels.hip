@@ -79,6 +79,38 @@ __device__ __forceinline__ void fill_table(float2 *tab, const float *alpha, cons
     __syncthreads();
 }
 
+// The same for a kernel whose workgroups take ONE chunk of `chunk` consecutive elements each (the grid covers the
+// tensor): with many groups -- per-sample statistics are a layout of B * G groups -- a workgroup fills only the
+// entries of the groups its chunk touches, a cyclic run of the group numbers.  Filling all 3072 entries of the layout
+// (1, 3072, 38809) in every workgroup (twelve loads and divisions per thread before the first element moves) held
+// quantize at 2.5 TB/s where six groups reach 3.7.
+template <Scale S>
+__device__ __forceinline__ void fill_table_touched(float2 *tab, const float *alpha, const float *beta, const GroupGeom &gg, int64_t numel,
+                                                   int64_t chunk)
+{
+    const int64_t base = int64_t(blockIdx.x) * chunk;
+    const int64_t row = int64_t(gg.groups) * gg.inner;
+    if (gg.groups <= uint32_t(kThreads) || int64_t(gridDim.x) * chunk < numel || chunk >= row || base >= numel) {
+        fill_table<S>(tab, alpha, beta, gg.groups);
+        return;
+    }
+    const int64_t last = (base + chunk <= numel ? base + chunk : numel) - 1;
+    const uint32_t g_first = cursor_init(base, gg).g, g_last = cursor_init(last, gg).g;
+    const uint32_t count = (g_last >= g_first ? g_last - g_first : g_last + gg.groups - g_first) + 1;
+    for (uint32_t t = threadIdx.x; t < count; t += kThreads) {
+        uint32_t g = g_first + t;
+        g -= g >= gg.groups ? gg.groups : 0u;
+        float a = alpha[g];
+        float s;
+        if (S == Scale::Quant) s = (a > 0.0f) ? 255.0f / a : 0.0f;
+        else if (S == Scale::QuantSym) s = (a > 0.0f) ? 127.0f / a : 0.0f;
+        else if (S == Scale::DequantSym) s = a / 127.0f;
+        else s = a / 255.0f;
+        tab[g] = make_float2(s, (S == Scale::QuantSym || S == Scale::DequantSym) ? 0.0f : beta[g]);
+    }
+    __syncthreads();
+}
+
 // ---------------------------------------------------------------------------------------------
 // min / max
 // ---------------------------------------------------------------------------------------------
@@ -479,11 +511,11 @@ __global__ __launch_bounds__(kThreads) void k_quantize(const void *__restrict__ 
                                                        const float *__restrict__ beta, uint64_t seed, uint64_t offset)
 {
     extern __shared__ float2 lds_tab[];
-    fill_table<SYM ? Scale::QuantSym : Scale::Quant>(lds_tab, alpha, beta, gg.groups);
+    constexpr int kChunk = kThreads * U * kVec;
+    fill_table_touched<SYM ? Scale::QuantSym : Scale::Quant>(lds_tab, alpha, beta, gg, numel, kChunk);
 
     Cursor c[U];
     place_cursors<U>(c, gg, numel);
-    constexpr int kChunk = kThreads * U * kVec;
     const int64_t stride = int64_t(gridDim.x) * kChunk;
     const int64_t toff = int64_t(threadIdx.x) * kVec;
     // CHECK = false: the chunk lies wholly inside the tensor, no per-vector bounds test
@@ -662,11 +694,11 @@ __global__ __launch_bounds__(kThreads) void k_dequantize(const int8_t *__restric
                                                          const float *__restrict__ beta)
 {
     extern __shared__ float2 lds_tab[];
-    fill_table<SYM ? Scale::DequantSym : Scale::Dequant>(lds_tab, alpha, beta, gg.groups);
+    constexpr int kChunk = kThreads * U * kVec;
+    fill_table_touched<SYM ? Scale::DequantSym : Scale::Dequant>(lds_tab, alpha, beta, gg, numel, kChunk);
 
     Cursor c[U];
     place_cursors<U>(c, gg, numel);
-    constexpr int kChunk = kThreads * U * kVec;
     const int64_t stride = int64_t(gridDim.x) * kChunk;
     const int64_t toff = int64_t(threadIdx.x) * kVec;
     // CHECK = false: the chunk lies wholly inside the tensor, no per-vector bounds test
@@ -760,7 +792,7 @@ __global__ __launch_bounds__(kThreads) void k_gelu_bwd(const int8_t *__restrict_
         }
         __syncthreads();
     } else {
-        fill_table<Scale::Dequant>(tab2, alpha, beta, gg.groups);
+        fill_table_touched<Scale::Dequant>(tab2, alpha, beta, gg, numel, int64_t(kThreads) * U * kVec);
     }
 
     auto grad_of = [&](uint32_t g, uint32_t raw) -> float {
@@ -909,15 +941,21 @@ static int stream_grid(int64_t numel, int64_t row, int min_chunks = 1)
 }
 
 // grid of a kernel that tracks extrema with `unroll` vectors per thread and at most `grid_cap` workgroups
-static int minmax_grid(const mesa_layout &L, int unroll = kMmU, int grid_cap = kMmGridCap)
+// max_wgs > 0: never more workgroups than that (a caller with a fixed amount of scratch)
+static int minmax_grid(const mesa_layout &L, int unroll = kMmU, int grid_cap = kMmGridCap, int max_wgs = 0)
 {
     int64_t numel = layout_numel(L);
-    // many groups: every workgroup writes 2*groups partial values, so keep their number down
+    // many groups: every workgroup writes 2*groups partial values (8 bytes per group), so keep their number down -- to
+    // what the tensor pays for: the partial values stay below an eighth of an element's byte per element.  (A fixed
+    // 64 / groups of the cap left the per-sample layout (1, 3072, 38809) with 32 workgroups: 1.04 ms for 238 MB.)
     int cap = grid_cap;
     if (L.groups > 64) {
-        cap = int(int64_t(grid_cap) * 64 / L.groups);
-        if (cap < 32) cap = 32;
+        const int64_t fixed = int64_t(grid_cap) * 64 / L.groups, paid = numel / (64 * L.groups);
+        int64_t c = fixed > paid ? fixed : paid;
+        if (c < 32) c = 32;
+        if (c < cap) cap = int(c);
     }
+    if (max_wgs > 0 && cap > max_wgs) cap = max_wgs;
     const int64_t chunk = int64_t(kThreads) * unroll * kVec;
     int n = plan_grid(numel, chunk, cap, L.groups > 1 ? L.groups * L.inner : 0);
     // Long slabs (head-wise tensors): a thread hands its extrema to LDS whenever its group changes,
@@ -927,7 +965,8 @@ static int minmax_grid(const mesa_layout &L, int unroll = kMmU, int grid_cap = k
     if (L.groups > 1 && L.inner > chunk && ceil_div(numel, chunk) > n) {
         int best = n;
         int64_t best_rem = (int64_t(n) * chunk) % row;
-        for (int k = n + 1; k < n + 256 && best_rem >= L.inner / 16; ++k) {
+        const int k_end = max_wgs > 0 && n + 256 > max_wgs + 1 ? max_wgs + 1 : n + 256;
+        for (int k = n + 1; k < k_end && best_rem >= L.inner / 16; ++k) {
             const int64_t rem = (int64_t(k) * chunk) % row;
             if (rem < best_rem) { best_rem = rem; best = k; }
         }
@@ -947,8 +986,10 @@ static bool minmax_few_groups(const mesa_layout &L, int grid, int unroll)
     return off > L.inner / 16;
 }
 
+// max_wgs > 0: the scan runs on at most that many workgroups and the workspace need only hold their partial values
 static mesa_status update_running_params(const void *x, mesa_dtype dt, mesa_layout L, float *alpha, float *beta, float lambda,
-                                         int first_call, int variant, float beta_fixed, void *ws, size_t ws_bytes, void *stream)
+                                         int first_call, int variant, float beta_fixed, void *ws, size_t ws_bytes, void *stream,
+                                         int max_wgs = 0)
 {
     if (!valid_dtype(dt)) return MESA_ERR_INVALID_ARG;
     mesa_status st = check_layout(L);
@@ -958,10 +999,10 @@ static mesa_status update_running_params(const void *x, mesa_dtype dt, mesa_layo
     if (numel == 0) return MESA_OK;
     if (!x || !alpha || !aligned16(x) || !aligned4(alpha)) return MESA_ERR_INVALID_ARG;
     if (variant != kEmaScaleOnly && (!beta || !aligned4(beta))) return MESA_ERR_INVALID_ARG;
-    if (!ws || !aligned16(ws) || ws_bytes < update_ws_bytes(L.outer, L.groups, L.inner))
-        return MESA_ERR_WORKSPACE;
+    const int grid = minmax_grid(L, kMmU, kMmGridCap, max_wgs);
+    const size_t need = max_wgs > 0 ? size_t(grid) * 2 * size_t(L.groups) * sizeof(float) : update_ws_bytes(L.outer, L.groups, L.inner);
+    if (!ws || !aligned16(ws) || ws_bytes < need) return MESA_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int grid = minmax_grid(L);
     GroupGeom gg = make_geom(L.groups, L.inner, int64_t(grid) * kThreads * kMmU * kVec);
     const size_t lds = size_t(2) * gg.groups * sizeof(int);
     float *part = static_cast<float *>(ws);
@@ -1042,12 +1083,14 @@ extern "C" MESA_EXPORT mesa_status mesa_update_running_params_static(const void 
     if (st != MESA_OK) return st;
     if (!(lambda >= 0.0f && lambda <= 1.0f)) return MESA_ERR_INVALID_ARG;
     if (layout_numel(L) == 0) return MESA_OK;
-    if (update_ws_bytes(L.outer, L.groups, L.inner) > kStaticScratchBytes) return MESA_ERR_UNSUPPORTED;
+    // as many workgroups as the array has room for (2 * groups partial values each), and no fewer than the scan's minimum of 32
+    const int max_wgs = int(kStaticScratchBytes / (size_t(2) * size_t(L.groups < 1 ? 1 : L.groups) * sizeof(float)));
+    if (max_wgs < 32) return MESA_ERR_UNSUPPORTED;          // groups > 4096
     void *ws = static_scratch_ptr();
     if (!ws) return MESA_ERR_LAUNCH;
     // every workgroup overwrites its whole row of partial extrema before the second kernel reads
     // them, so nothing of the previous call's contents is ever read and nothing needs clearing
-    return update_running_params(x, dt, L, alpha, beta, lambda, first_call, kEmaPlain, 0.0f, ws, kStaticScratchBytes, stream);
+    return update_running_params(x, dt, L, alpha, beta, lambda, first_call, kEmaPlain, 0.0f, ws, kStaticScratchBytes, stream, max_wgs);
 }
 
 extern "C" MESA_EXPORT size_t mesa_static_scratch_bytes(void) { return kStaticScratchBytes; }

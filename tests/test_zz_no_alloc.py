@@ -32,8 +32,10 @@ def test_static_scratch_update_equals_workspace_update_twice_in_a_row(M, dtype):
     dtc = {torch.float32: M.F32, torch.float16: M.F16, torch.bfloat16: M.BF16}[dtype]
     g = torch.Generator(device="cuda").manual_seed(77)
     # the large call first (many workgroups' partials land in the array), then a small one whose grid is a
-    # fraction of it, then one with more groups than either
-    layouts = [(64, 12, 197 * 197), (3, 5, 361), (500, 48, 24)]
+    # fraction of it, then one with more groups than either, then many groups on a tensor large enough that the
+    # workspace form would use more workgroups than the array has room for (the static form runs on fewer)
+    layouts = [(64, 12, 197 * 197), (3, 5, 361), (500, 48, 24), (1, 1024, 9001)]
+    assert M.workspace_bytes(M.OP_UPDATE_RUNNING_PARAMS, 1, 1024, 9001, dtc) > M.static_scratch_bytes()
     for step, (outer, G, inner) in enumerate(layouts):
         x = (torch.randn((outer, G, inner), generator=g, device="cuda") * (1.0 + step) - 0.5 * step).to(dtype).contiguous()
         lay = M.Layout(outer, G, inner)
