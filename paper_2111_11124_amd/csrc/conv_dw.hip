@@ -524,46 +524,74 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_finish(const float *__restr
     }
 }
 
-// The plain path: any stride, dilation, kernel size and storage type.  One thread per element of dW, the whole sum in
-// binary64 at the binary32 x_hat; threads of a workgroup share (co, ci-range) so that dy is read once per wave.
+// The plain path: any stride, dilation, kernel size and storage type.  One workgroup per (output channel, input channel):
+// its threads share out the output positions (consecutive threads, consecutive columns of dy), every thread keeps the
+// kernel taps' sums -- nine taps at a time -- in binary64 at the binary32 x_hat, and the threads' sums are added in a
+// fixed order (lanes, then waves).  Workgroups of input channel 0 also sum dy for the bias gradient.
+constexpr int kCvPlainTaps = 9;
 template <typename T>
 __global__ __launch_bounds__(kCvThreads) void k_conv_dw_plain(const int8_t *__restrict__ xq, const void *__restrict__ dy, ConvGeom cg,
                                                               int per, const float *__restrict__ alpha, const float *__restrict__ beta,
                                                               float *__restrict__ dW, float *__restrict__ db)
 {
+    __shared__ double red[kCvThreads / 64][kCvPlainTaps + 1];
     const int ntap = cg.KH * cg.KW;
-    const int64_t per_co = int64_t(cg.Cin) * ntap;
-    const int64_t idx = int64_t(blockIdx.x) * kCvThreads + threadIdx.x;
-    if (idx >= per_co * cg.Cout) return;
-    const int co = int(idx / per_co);
-    const int rem = int(idx - int64_t(co) * per_co);
-    const int ci = rem / ntap, tap = rem - ci * ntap;
-    const int kh = tap / cg.KW, kw = tap - kh * cg.KW;
+    const int co = int(blockIdx.x / unsigned(cg.Cin)), ci = int(blockIdx.x % unsigned(cg.Cin));
     const int g = ci / per;
     const float step = alpha[g] / 255.0f, off = beta[g];
-    double acc = 0.0, tot = 0.0;
-    const bool want_db = db && rem == 0;
-    for (int b = 0; b < cg.B; ++b) {
-        const int64_t dbase = (int64_t(b) * cg.Cout + co) * cg.OH * cg.OW;
-        const int64_t xbase = (int64_t(b) * cg.Cin + ci) * cg.H * cg.W;
-        for (int oh = 0; oh < cg.OH; ++oh) {
-            const int ih = oh * cg.sh - cg.ph + kh * cg.dh;
-            const bool row_in = ih >= 0 && ih < cg.H;
-            if (!row_in && !want_db) continue;
-            for (int ow = 0; ow < cg.OW; ++ow) {
-                const float gy = Store<T>::load1(dy, dbase + int64_t(oh) * cg.OW + ow);
-                if (want_db) tot += double(gy);
-                const int iw = ow * cg.sw - cg.pw + kw * cg.dw;
-                if (row_in && iw >= 0 && iw < cg.W) {
-                    float xh = float(int(xq[xbase + int64_t(ih) * cg.W + iw]) + 128) * step;
-                    xh = xh + off;
-                    acc += double(gy) * double(xh);
+    const int plane = cg.OH * cg.OW;                       // < 2^31 (checked by the entry point)
+    const bool want_db = db && ci == 0;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int tap0 = 0; tap0 < ntap; tap0 += kCvPlainTaps) {
+        int dih[kCvPlainTaps], diw[kCvPlainTaps];          // a tap's offset from (oh * sh, ow * sw)
+#pragma unroll
+        for (int t = 0; t < kCvPlainTaps; ++t) {
+            const int tap = tap0 + t < ntap ? tap0 + t : tap0;
+            const int kh = tap / cg.KW, kw = tap - kh * cg.KW;
+            dih[t] = kh * cg.dh - cg.ph;
+            diw[t] = kw * cg.dw - cg.pw;
+        }
+        double acc[kCvPlainTaps], tot = 0.0;
+#pragma unroll
+        for (int t = 0; t < kCvPlainTaps; ++t) acc[t] = 0.0;
+        for (int b = 0; b < cg.B; ++b) {
+            const int64_t dbase = (int64_t(b) * cg.Cout + co) * plane;
+            const int8_t *xb = xq + (int64_t(b) * cg.Cin + ci) * cg.H * cg.W;
+            for (int r = threadIdx.x; r < plane; r += kCvThreads) {
+                const int oh = r / cg.OW, ow = r - oh * cg.OW;
+                const float gy = Store<T>::load1(dy, dbase + r);
+                tot += double(gy);
+#pragma unroll
+                for (int t = 0; t < kCvPlainTaps; ++t) {
+                    const int ih = oh * cg.sh + dih[t], iw = ow * cg.sw + diw[t];
+                    if (tap0 + t < ntap && ih >= 0 && ih < cg.H && iw >= 0 && iw < cg.W) {
+                        float xh = float(int(xb[ih * cg.W + iw]) + 128) * step;     // H * W < 2^31 (checked by the entry point)
+                        xh = xh + off;
+                        acc[t] += double(gy) * double(xh);
+                    }
                 }
             }
         }
+        // lanes, then waves, in a fixed order
+#pragma unroll
+        for (int t = 0; t <= kCvPlainTaps; ++t) {
+            double v = t < kCvPlainTaps ? acc[t] : tot;
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m);
+            if (lane == 0) red[wave][t] = v;
+        }
+        __syncthreads();
+        if (threadIdx.x <= kCvPlainTaps) {
+            const int t = threadIdx.x;
+            const double v = (red[0][t] + red[1][t]) + (red[2][t] + red[3][t]);
+            if (t < kCvPlainTaps) {
+                if (tap0 + t < ntap) dW[(int64_t(co) * cg.Cin + ci) * ntap + tap0 + t] = float(v);
+            } else if (want_db && tap0 == 0) {
+                db[co] = float(v);
+            }
+        }
+        __syncthreads();                                   // the next nine taps reuse `red`
     }
-    dW[idx] = float(acc);
-    if (want_db) db[co] = float(tot);
 }
 
 struct CvPlan {
@@ -667,7 +695,6 @@ extern "C" MESA_EXPORT mesa_status mesa_conv2d_dw_q(const int8_t *xq, mesa_conv2
         return MESA_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int per = int(cv.C_in / G);
-    const int64_t nout = int64_t(cg.Cout) * cg.Cin * cg.KH * cg.KW;
     const int64_t plane = int64_t(cg.Cout) * cg.Cin;
     if (cg.B == 0) {   // an empty batch: the last kernel over no partial sums writes the zeros
         hipLaunchKernelGGL(k_conv_finish, dim3(unsigned(ceil_div(plane, kCvThreads))), dim3(kCvThreads), 0, s,
@@ -678,7 +705,7 @@ extern "C" MESA_EXPORT mesa_status mesa_conv2d_dw_q(const int8_t *xq, mesa_conv2
     if (!xq || !dy || !aligned16(xq) || !aligned16(dy)) return MESA_ERR_INVALID_ARG;
     const CvPlan p = cv_plan(cg, dt);
     if (!p.fast) {
-        const unsigned grid = unsigned(ceil_div(nout, kCvThreads));
+        const unsigned grid = unsigned(plane);             // one workgroup per (co, ci): C_out * C_in < 2^31
 #define MESA_LAUNCH_CVP(T) \
         hipLaunchKernelGGL((k_conv_dw_plain<T>), dim3(grid), dim3(kCvThreads), 0, s, xq, dy, cg, per, alpha, beta, dW, db)
         MESA_FOR_DTYPE(dt, MESA_LAUNCH_CVP);
