@@ -201,7 +201,8 @@ __global__ __launch_bounds__(kCvThreads, 2) void k_conv_dw(const int8_t *__restr
         const char *dbase = reinterpret_cast<const char *>(dy + (int64_t(b) * cg.Cout + co0) * cg.OH * cg.OW);
         const int ddelta = (oh * cg.OW + seg0) * 2;
         const int dv_end = (cg.OW - seg0) >> 3;                       // vectors of this row that lie inside it
-        const uint32_t dmask = dv_end >= 32 ? 0xFFFFFFFFu : (1u << dv_end) - 1u;
+        // (never bit 31: it marks the rows beyond C_out, which must fail the test below whatever the row's length)
+        const uint32_t dmask = dv_end >= 31 ? 0x7FFFFFFFu : (1u << dv_end) - 1u;
         dkeep[S] = 0u;
 #pragma unroll
         for (int n = 0; n < C::ND; ++n) {

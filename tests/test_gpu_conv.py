@@ -63,6 +63,8 @@ FAST = [
     (2, 128, 6, 136, 128, 1, 1, (2, 1), (0, 0), (1, 1), 2),      # 1x1: two segments, row stride
     (2, 256, 12, 48, 128, 1, 1, (1, 1), (3, 0), (1, 1), 2),      # 1x1 with row padding (rows of dy that meet no input row)
     (16, 64, 32, 32, 64, 3, 3, (1, 1), (1, 1), (1, 1), 4),       # many stages: several slices of the (image, row) range
+    (2, 3, 6, 512, 72, 3, 3, (1, 1), (1, 1), (1, 1), 1),         # rows of 256 columns and more next to a ragged tile of output channels
+    (1, 136, 3, 264, 40, 1, 1, (1, 1), (0, 0), (1, 1), 1),       # the same for 1x1
 ]
 
 
