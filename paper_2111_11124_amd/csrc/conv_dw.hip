@@ -525,6 +525,64 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_finish(const float *__restr
     }
 }
 
+// The same for few channel pairs and many slices (narrow layers: 64 x 64 channels leave k_conv_finish 16 workgroups
+// whose threads walk 64 slices of nine dependent loads each -- 150 us, six times the matrix-core kernel): a workgroup takes
+// 32 pairs, eight threads share a pair's slices (every eighth each, in order) and the eight sums are added in a fixed
+// order; the sums of V for the workgroup's output channels are taken once, by its first threads.  ntap <= 9.
+__global__ __launch_bounds__(kCvThreads) void k_conv_finish_few(const float *__restrict__ part, const float *__restrict__ V, int splits,
+                                                                int parts, ConvGeom cg, int per, const float *__restrict__ alpha,
+                                                                const float *__restrict__ beta, float centre, float *__restrict__ dW,
+                                                                float *__restrict__ db)
+{
+    __shared__ float sums[8][32][9];
+    __shared__ float vsum[32][10];
+    __shared__ float tile[32 * 9];
+    const int pl = threadIdx.x & 31, sl = threadIdx.x >> 5;
+    const int64_t plane = int64_t(cg.Cout) * cg.Cin;
+    const int64_t first = int64_t(blockIdx.x) * 32, idx = first + pl;
+    const int ntap = cg.KH * cg.KW;
+    const bool live = idx < plane;
+    const int co_first = int(first / cg.Cin);              // the workgroup's pairs lie in the output channels from this one on
+    const int64_t last = first + 31 < plane ? first + 31 : plane - 1;
+    const int nco = int(last / cg.Cin) - co_first + 1;     // at most 32
+    for (int k = threadIdx.x; k < nco * 10; k += kCvThreads) {
+        const int c = k / 10, e = k - c * 10;
+        float v = 0.0f;
+        for (int pt = 0; pt < parts; ++pt) v += V[(int64_t(pt) * cg.Cout + co_first + c) * 10 + e];
+        vsum[c][e] = v;
+    }
+    float s1[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) s1[t] = 0.0f;
+    if (live)
+        for (int sp = sl; sp < splits; sp += 8)
+#pragma unroll
+            for (int t = 0; t < 9; ++t)
+                if (t < ntap) s1[t] += part[(int64_t(sp) * ntap + t) * plane + idx];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) sums[sl][pl][t] = s1[t];
+    __syncthreads();
+    if (sl == 0 && live) {
+        const int co = int(idx / cg.Cin), ci = int(idx - int64_t(co) * cg.Cin);
+        const int g = ci / per;
+        const float sg = alpha[g] / 255.0f;
+        const float off = fmaf(centre, sg, beta[g]);
+        const float *vs = vsum[co - co_first];
+#pragma unroll
+        for (int t = 0; t < 9; ++t)
+            if (t < ntap) {
+                const float tot = ((sums[0][pl][t] + sums[1][pl][t]) + (sums[2][pl][t] + sums[3][pl][t])) +
+                                  ((sums[4][pl][t] + sums[5][pl][t]) + (sums[6][pl][t] + sums[7][pl][t]));
+                const int a = t / cg.KW, c = t - a * cg.KW;
+                tile[pl * ntap + t] = fmaf(sg, tot, off * vs[a * 3 + c]);
+            }
+        if (db && ci == 0) db[co] = vs[9];
+    }
+    __syncthreads();
+    const int64_t count = (plane - first < 32 ? plane - first : 32) * ntap;
+    for (int k = threadIdx.x; k < count; k += kCvThreads) dW[first * ntap + k] = tile[k];
+}
+
 // The plain path: any stride, dilation, kernel size and storage type.  One workgroup per (output channel, input channel):
 // its threads share out the output positions (consecutive threads, consecutive columns of dy), every thread keeps the
 // kernel taps' sums -- nine taps at a time -- in binary64 at the binary32 x_hat, and the threads' sums are added in a
@@ -746,7 +804,11 @@ extern "C" MESA_EXPORT mesa_status mesa_conv2d_dw_q(const int8_t *xq, mesa_conv2
 #undef MESA_PICK_NKS
 #undef MESA_LAUNCH_CV
     if (launch_status() != MESA_OK) return MESA_ERR_LAUNCH;   // the last kernel must not read sums nobody wrote
-    hipLaunchKernelGGL(k_conv_finish, dim3(unsigned(ceil_div(plane, kCvThreads))), dim3(kCvThreads), 0, s, part, V, p.splits, p.parts,
-                       cg, per, alpha, beta, centre, dW, db);
+    if (plane <= 262144 && p.splits >= 8)
+        hipLaunchKernelGGL(k_conv_finish_few, dim3(unsigned(ceil_div(plane, 32))), dim3(kCvThreads), 0, s, part, V, p.splits, p.parts, cg,
+                           per, alpha, beta, centre, dW, db);
+    else
+        hipLaunchKernelGGL(k_conv_finish, dim3(unsigned(ceil_div(plane, kCvThreads))), dim3(kCvThreads), 0, s, part, V, p.splits, p.parts,
+                           cg, per, alpha, beta, centre, dW, db);
     return launch_status();
 }
