@@ -20,7 +20,10 @@
 // kernel rows go to separate workgroups; the slices are combined in a fixed order by a second kernel.
 //
 // This path takes 16-bit tensors, 3x3 kernels with pad_w = 1 and 1x1 kernels with pad_w = 0, stride_w = dil_w = 1 (any
-// row stride, dilation and padding), W and OW multiples of 8; anything else runs the plain kernel at the end of the file.
+// row stride, dilation and padding) and widths of at least 8; anything else runs the plain kernel at the end of the file.
+// Widths that are no multiples of 8 (RAG): rows start at any element, so the eight-element vectors are loaded from
+// unaligned addresses, and a row's last, partial vector is loaded from eight elements before the row's end instead (inside
+// the row, hence inside the tensor) and written to LDS element by element where it belongs, zeros behind it.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -106,7 +109,14 @@ template <bool T3, int NKS> struct CvCfg {
 // stage is multiplied, and converted and written to LDS after it (a barrier on either side) -- while one workgroup does
 // that, the others' MFMAs keep the matrix cores busy.  (With one wave per SIMD the vector instructions of a stage and its
 // MFMAs took turns instead of overlapping: 31 % matrix-core time.)
-template <typename E, bool T3, int NKS>
+template <typename V> __device__ __forceinline__ V cv_load_unaligned(const char *p)
+{
+    V v;
+    __builtin_memcpy(&v, p, sizeof(V));
+    return v;
+}
+
+template <typename E, bool T3, int NKS, bool RAG>
 __global__ __launch_bounds__(kCvThreads, 2) void k_conv_dw(const int8_t *__restrict__ xq, const E *__restrict__ dy, ConvGeom cg,
                                                            int tiles_co, int tiles_ci, int splits, int stages_per_split,
                                                            int nseg, float *__restrict__ part)
@@ -181,6 +191,10 @@ __global__ __launch_bounds__(kCvThreads, 2) void k_conv_dw(const int8_t *__restr
     u32x2 xreg[1][C::NX];
     uint32_t xkeep[1] = {0u};       // bit n: input vector n lies inside the image (elsewhere the forward saw padding: zeros)
     uint32_t dkeep[1] = {0u};
+    // RAG: bit n: vector n is its row's partial last vector, loaded `shift` elements early (shift = 8 - its valid elements,
+    // the same for every row of a stage)
+    uint32_t xtail[1] = {0u}, dtail[1] = {0u};
+    int xshift[1] = {0}, dshift[1] = {0};
 
     // the coordinates of the stage being loaded, advanced one stage at a time
     int seg = st_begin % nseg;
@@ -200,14 +214,24 @@ __global__ __launch_bounds__(kCvThreads, 2) void k_conv_dw(const int8_t *__restr
         const int seg0 = seg * C::SEG;
         const char *dbase = reinterpret_cast<const char *>(dy + (int64_t(b) * cg.Cout + co0) * cg.OH * cg.OW);
         const int ddelta = (oh * cg.OW + seg0) * 2;
-        const int dv_end = (cg.OW - seg0) >> 3;                       // vectors of this row that lie inside it
+        const int dfull = (cg.OW - seg0) >> 3, dr = RAG ? (cg.OW - seg0) & 7 : 0;
+        const int dv_end = dfull + (dr ? 1 : 0);                      // vectors of this row that lie inside it, or partly so
+        const uint32_t dtail_bit = (dr && dfull < C::NVA) ? 1u << dfull : 0u;
+        dshift[S] = 8 - dr;
+        dtail[S] = 0u;
         // (never bit 31: it marks the rows beyond C_out, which must fail the test below whatever the row's length)
         const uint32_t dmask = dv_end >= 31 ? 0x7FFFFFFFu : (1u << dv_end) - 1u;
         dkeep[S] = 0u;
 #pragma unroll
         for (int n = 0; n < C::ND; ++n) {
             const bool in = (dbits[n] & dmask) == dbits[n];
-            dreg[S][n] = *reinterpret_cast<const u32x4 *>(dbase + uint32_t(in ? doff[n] + ddelta : 0));
+            if (RAG) {
+                const bool tail = in && dbits[n] == dtail_bit;
+                dreg[S][n] = cv_load_unaligned<u32x4>(dbase + uint32_t(in ? doff[n] + ddelta - (tail ? (8 - dr) * 2 : 0) : 0));
+                dtail[S] |= tail ? 1u << n : 0u;
+            } else {
+                dreg[S][n] = *reinterpret_cast<const u32x4 *>(dbase + uint32_t(in ? doff[n] + ddelta : 0));
+            }
             dkeep[S] |= in ? 1u << n : 0u;
         }
         const int ih0 = oh * cg.sh - cg.ph + kh_w * cg.dh;
@@ -220,26 +244,49 @@ __global__ __launch_bounds__(kCvThreads, 2) void k_conv_dw(const int8_t *__restr
             smask |= (ih >= 0 && ih < cg.H) ? 1u << (24 + a) : 0u;
         }
         const int v_lo = (T3 && seg0 == 0) ? 1 : 0;                   // the left halo of the first segment is padding
-        const int v_end = min((cg.W - seg0 + (T3 ? 8 : 0)) >> 3, 24);
+        const int xcols = cg.W - seg0 + (T3 ? 8 : 0);                 // from LDS element 0 of the row to the image's last column
+        const int xfull = xcols >> 3, xr = RAG ? xcols & 7 : 0;
+        const int v_end = min(xfull + (xr ? 1 : 0), 24);
+        const uint32_t xtail_bit = (xr && xfull < C::NVX) ? 1u << xfull : 0u;
+        xshift[S] = 8 - xr;
+        xtail[S] = 0u;
         smask |= ((1u << v_end) - 1u) & ~((1u << v_lo) - 1u);
         xkeep[S] = 0u;
 #pragma unroll
         for (int n = 0; n < C::NX; ++n) {
             const bool in = (xbits[n] & smask) == xbits[n];
-            xreg[S][n] = *reinterpret_cast<const u32x2 *>(xbase + uint32_t(in ? xoff[n] + xdelta : 0));
+            if (RAG) {
+                const bool tail = in && (xbits[n] & 0x00FFFFFFu) == xtail_bit;
+                xreg[S][n] = cv_load_unaligned<u32x2>(xbase + uint32_t(in ? xoff[n] + xdelta - (tail ? 8 - xr : 0) : 0));
+                xtail[S] |= tail ? 1u << n : 0u;
+            } else {
+                xreg[S][n] = *reinterpret_cast<const u32x2 *>(xbase + uint32_t(in ? xoff[n] + xdelta : 0));
+            }
             xkeep[S] |= in ? 1u << n : 0u;
         }
     };
-    auto store_d = [&](int S, int n, unsigned char *buf) {
-        const uint32_t k = 0u - ((dkeep[S] >> n) & 1u);
-        *reinterpret_cast<u32x4 *>(buf + dlds[n]) = u32x4{dreg[S][n][0] & k, dreg[S][n][1] & k, dreg[S][n][2] & k, dreg[S][n][3] & k};
+    // a vector that was loaded `shift` elements early: its last 8 - shift elements to the first slots, zeros behind them
+    // (the same thread's writes to LDS take effect in program order)
+    auto store_tail = [&](unsigned char *at, u32x4 w, int shift) __attribute__((always_inline)) {
+        *reinterpret_cast<u32x4 *>(at) = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 1; i < 8; ++i)
+            if (i >= shift) *reinterpret_cast<uint16_t *>(at + (i - shift) * 2) = uint16_t(w[i >> 1] >> ((i & 1) * 16));
     };
-    auto store_x = [&](int S, int n, unsigned char *buf) {
+    auto store_d = [&](int S, int n, unsigned char *buf) __attribute__((always_inline)) {
+        const uint32_t k = 0u - ((dkeep[S] >> n) & 1u);
+        const u32x4 w = u32x4{dreg[S][n][0] & k, dreg[S][n][1] & k, dreg[S][n][2] & k, dreg[S][n][3] & k};
+        if (RAG && ((dtail[S] >> n) & 1u)) store_tail(buf + dlds[n], w, dshift[S]);
+        else *reinterpret_cast<u32x4 *>(buf + dlds[n]) = w;
+    };
+    auto store_x = [&](int S, int n, unsigned char *buf) __attribute__((always_inline)) {
         uint32_t lo[2], hi[2];
         CvElem<E>::convert(xreg[S][n][0], lo);
         CvElem<E>::convert(xreg[S][n][1], hi);
         const uint32_t k = 0u - ((xkeep[S] >> n) & 1u);
-        *reinterpret_cast<u32x4 *>(buf + xlds[n]) = u32x4{lo[0] & k, lo[1] & k, hi[0] & k, hi[1] & k};
+        const u32x4 w = u32x4{lo[0] & k, lo[1] & k, hi[0] & k, hi[1] & k};
+        if (RAG && ((xtail[S] >> n) & 1u)) store_tail(buf + xlds[n], w, xshift[S]);
+        else *reinterpret_cast<u32x4 *>(buf + xlds[n]) = w;
     };
 
     const int half = lane >> 5, l32 = lane & 31;
@@ -347,7 +394,7 @@ __global__ __launch_bounds__(kCvThreads, 2) void k_conv_dw(const int8_t *__restr
     };
 
     if (st_begin < st_end) {
-        auto store_all = [&]() {
+        auto store_all = [&]() __attribute__((always_inline)) {
 #pragma unroll
             for (int n = 0; n < C::ND; ++n) store_d(0, n, cv_lds);
 #pragma unroll
@@ -445,6 +492,72 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_valid_sums(const E *__restr
                     if (a < cg.KH && ih >= 0 && ih < cg.H) {
 #pragma unroll
                         for (int c = 0; c < 3; ++c) acc[a][c] += cs[c];
+                    }
+                }
+            }
+        }
+    }
+    float vals[10];
+#pragma unroll
+    for (int a = 0; a < 3; ++a)
+#pragma unroll
+        for (int c = 0; c < 3; ++c) vals[a * 3 + c] = acc[a][c];
+    vals[9] = tot;
+#pragma unroll
+    for (int k = 0; k < 10; ++k) {
+        float v = vals[k];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6][k] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x < 10) {
+        float v = red[0][threadIdx.x];
+#pragma unroll
+        for (int w = 1; w < kCvThreads / 64; ++w) v += red[w][threadIdx.x];
+        V[(int64_t(pt) * cg.Cout + co) * 10 + threadIdx.x] = v;
+    }
+}
+
+// The same sums for widths that are no multiples of 8: element by element (consecutive threads, consecutive elements of the
+// (image, channel) plane, four loads in flight per thread).
+template <typename E>
+__global__ __launch_bounds__(kCvThreads) void k_conv_valid_sums_any(const E *__restrict__ dy, ConvGeom cg, int parts, int imgs_per_part,
+                                                                    float *__restrict__ V)
+{
+    __shared__ float red[kCvThreads / 64][10];
+    const int co = blockIdx.x / parts, pt = blockIdx.x - co * parts;
+    const int b0 = pt * imgs_per_part, b1 = min(b0 + imgs_per_part, cg.B);
+    const int per_img = cg.OH * cg.OW;
+    float acc[3][3], tot = 0.0f;
+#pragma unroll
+    for (int a = 0; a < 3; ++a)
+#pragma unroll
+        for (int c = 0; c < 3; ++c) acc[a][c] = 0.0f;
+    for (int b = b0; b < b1; ++b) {
+        const E *plane = dy + (int64_t(b) * cg.Cout + co) * per_img;
+        for (int base = 0; base < per_img; base += 4 * kCvThreads) {
+            float f[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int idx = base + u * kCvThreads + int(threadIdx.x);
+                f[u] = idx < per_img ? float(plane[idx]) : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int idx = base + u * kCvThreads + int(threadIdx.x);
+                if (idx >= per_img) continue;
+                const int oh = idx / cg.OW, ow = idx - oh * cg.OW;
+                tot += f[u];
+#pragma unroll
+                for (int a = 0; a < 3; ++a) {
+                    const int ih = oh * cg.sh - cg.ph + a * cg.dh;
+                    if (a < cg.KH && ih >= 0 && ih < cg.H) {
+#pragma unroll
+                        for (int c = 0; c < 3; ++c) {
+                            const int iw = ow - cg.pw + c;
+                            acc[a][c] += (c < cg.KW && iw >= 0 && iw < cg.W) ? f[u] : 0.0f;
+                        }
                     }
                 }
             }
@@ -654,7 +767,7 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_dw_plain(const int8_t *__re
 }
 
 struct CvPlan {
-    bool fast, taps3;
+    bool fast, taps3, rag;
     int nks, tiles_co, tiles_ci, splits, stages_per_split, nseg, grid, parts, imgs_per_part;
 };
 
@@ -664,10 +777,11 @@ static CvPlan cv_plan(const ConvGeom &cg, mesa_dtype dt)
     const bool k3 = cg.KH == 3 && cg.KW == 3 && cg.pw == 1, k1 = cg.KH == 1 && cg.KW == 1 && cg.pw == 0;
     // per-lane byte offsets inside a tile of 128 channels, plus the stage's own offset, stay below 2^31
     const int64_t lim = int64_t(1) << 22;
-    p.fast = dt != MESA_F32 && cg.sw == 1 && cg.dw == 1 && (k3 || k1) && cg.W % 8 == 0 && cg.OW % 8 == 0 &&
+    p.fast = dt != MESA_F32 && cg.sw == 1 && cg.dw == 1 && (k3 || k1) && cg.W >= 8 && cg.OW >= 8 &&
              (int64_t(cg.H) + 2 * cg.ph + 3 * int64_t(cg.dh)) * cg.W <= lim && int64_t(cg.OH) * cg.OW <= lim;
     if (!p.fast) return p;
     p.taps3 = k3;
+    p.rag = cg.W % 8 != 0 || cg.OW % 8 != 0;
     p.nks = cg.OW <= 32 ? 2 : cg.OW <= 64 ? 4 : 8;
     const int cot = 128, cit = p.taps3 ? 64 : 128;
     p.tiles_co = int(ceil_div(cg.Cout, cot));
@@ -776,26 +890,32 @@ extern "C" MESA_EXPORT mesa_status mesa_conv2d_dw_q(const int8_t *xq, mesa_conv2
     float *part = static_cast<float *>(ws);
     const size_t part_bytes = size_t(p.splits) * cg.KH * cg.KW * cg.Cout * cg.Cin * sizeof(float);
     float *V = reinterpret_cast<float *>(static_cast<char *>(ws) + part_bytes);
-#define MESA_LAUNCH_CV(E, T3, NKS) \
+#define MESA_LAUNCH_CV(E, T3, NKS, RAG) \
     do { \
-        auto kern = k_conv_dw<E, T3, NKS>; \
+        auto kern = k_conv_dw<E, T3, NKS, RAG>; \
         constexpr int lds = CvCfg<T3, NKS>::LDS; \
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) \
             return MESA_ERR_LAUNCH; \
         hipLaunchKernelGGL(kern, dim3(p.grid), dim3(kCvThreads), lds, s, xq, static_cast<const E *>(dy), cg, p.tiles_co, p.tiles_ci, \
                            p.splits, p.stages_per_split, p.nseg, part); \
     } while (0)
-#define MESA_PICK_NKS(E, T3) \
+#define MESA_PICK_NKS(E, T3, RAG) \
     do { \
-        if (p.nks == 8) MESA_LAUNCH_CV(E, T3, 8); \
-        else if (p.nks == 4) MESA_LAUNCH_CV(E, T3, 4); \
-        else MESA_LAUNCH_CV(E, T3, 2); \
+        if (p.nks == 8) MESA_LAUNCH_CV(E, T3, 8, RAG); \
+        else if (p.nks == 4) MESA_LAUNCH_CV(E, T3, 4, RAG); \
+        else MESA_LAUNCH_CV(E, T3, 2, RAG); \
     } while (0)
 #define MESA_PICK_CV(E) \
     do { \
-        if (p.taps3) MESA_PICK_NKS(E, true); else MESA_PICK_NKS(E, false); \
-        hipLaunchKernelGGL((k_conv_valid_sums<E>), dim3(unsigned(cg.Cout) * p.parts), dim3(kCvThreads), 0, s, \
-                           static_cast<const E *>(dy), cg, p.parts, p.imgs_per_part, V); \
+        if (p.rag) { \
+            if (p.taps3) MESA_PICK_NKS(E, true, true); else MESA_PICK_NKS(E, false, true); \
+            hipLaunchKernelGGL((k_conv_valid_sums_any<E>), dim3(unsigned(cg.Cout) * p.parts), dim3(kCvThreads), 0, s, \
+                               static_cast<const E *>(dy), cg, p.parts, p.imgs_per_part, V); \
+        } else { \
+            if (p.taps3) MESA_PICK_NKS(E, true, false); else MESA_PICK_NKS(E, false, false); \
+            hipLaunchKernelGGL((k_conv_valid_sums<E>), dim3(unsigned(cg.Cout) * p.parts), dim3(kCvThreads), 0, s, \
+                               static_cast<const E *>(dy), cg, p.parts, p.imgs_per_part, V); \
+        } \
     } while (0)
     float centre;
     if (dt == MESA_F16) { MESA_PICK_CV(_Float16); centre = CvElem<_Float16>::kCentre; }

@@ -1,5 +1,5 @@
 """mesa_conv2d_dw_q against the oracle: the matrix-core path over ragged channel tiles, several row segments, kernel
-shapes 3x3 and 1x1, row strides, dilations and paddings; the plain path over everything else (column strides and
+shapes 3x3 and 1x1, row strides, dilations and paddings, widths that are and are not multiples of eight; the plain path over everything else (column strides and
 dilations, other kernel shapes and column paddings, binary32 tensors); the empty batch and the error paths."""
 import numpy as np
 import pytest
@@ -65,6 +65,17 @@ FAST = [
     (16, 64, 32, 32, 64, 3, 3, (1, 1), (1, 1), (1, 1), 4),       # many stages: several slices of the (image, row) range
     (2, 3, 6, 512, 72, 3, 3, (1, 1), (1, 1), (1, 1), 1),         # rows of 256 columns and more next to a ragged tile of output channels
     (1, 136, 3, 264, 40, 1, 1, (1, 1), (0, 0), (1, 1), 1),       # the same for 1x1
+    # widths that are no multiples of eight: unaligned rows, a row's last vector loaded early and placed element by element
+    (3, 40, 28, 28, 136, 3, 3, (1, 1), (1, 1), (1, 1), 2),       # 28 x 28 maps
+    (4, 72, 14, 14, 72, 3, 3, (1, 1), (1, 1), (1, 1), 3),        # 14 x 14
+    (2, 24, 5, 9, 10, 3, 3, (1, 1), (1, 1), (1, 1), 1),          # one column more than a vector; the tensors' last rows end the buffers
+    (1, 8, 3, 8, 4, 3, 3, (1, 1), (1, 1), (1, 1), 1),            # the narrowest width this path takes
+    (2, 64, 4, 135, 64, 3, 3, (2, 1), (1, 1), (1, 1), 4),        # two segments, seven columns in the second
+    (2, 64, 5, 129, 40, 3, 3, (1, 1), (1, 1), (1, 1), 1),        # one column in the second segment
+    (2, 130, 6, 63, 70, 3, 3, (1, 1), (0, 1), (2, 1), 5),        # four steps per stage, the last column missing
+    (2, 200, 14, 14, 136, 1, 1, (1, 1), (0, 0), (1, 1), 4),      # 1x1 on 14 x 14
+    (2, 128, 4, 257, 128, 1, 1, (1, 1), (1, 0), (1, 1), 2),      # 1x1: three segments, one column in the last
+    (3, 16, 7, 100, 24, 1, 1, (2, 1), (0, 0), (1, 1), 2),        # 1x1: rows that start at every alignment
 ]
 
 
@@ -81,7 +92,7 @@ PLAIN = [
     (1, 4, 11, 10, 2, 3, 3, (1, 2), (2, 2), (2, 2), 1),          # column stride and dilation
     (2, 3, 8, 8, 2, 4, 4, (4, 4), (0, 0), (1, 1), 3),            # patch embedding: stride = kernel
     (1, 8, 14, 14, 6, 5, 5, (1, 1), (2, 2), (1, 1), 2),          # 5x5
-    (2, 8, 7, 9, 5, 3, 3, (1, 1), (1, 1), (1, 1), 2),            # widths that are no multiples of eight
+    (2, 8, 9, 7, 5, 3, 3, (1, 1), (1, 1), (1, 1), 2),            # a width below eight
     (2, 48, 8, 16, 40, 3, 1, (1, 1), (1, 0), (1, 1), 3),         # 3x1 kernel
     (2, 48, 8, 16, 40, 1, 3, (1, 1), (0, 1), (1, 1), 3),         # 1x3 kernel
     (2, 16, 8, 24, 16, 3, 3, (1, 1), (1, 5), (1, 1), 2),         # 3x3 with wide column padding
