@@ -4,8 +4,9 @@
 //   then for the stored y: codes with the running estimates as they are on entry and this batch's
 //   per-head extrema, from which the estimates are moved afterwards (the single-pass forward).
 //
-// Two kernels.  Rows of up to 256 elements (the attention maps of the paper's models: 197, 49): k_softmax_fwd_rows,
-// further down -- tiles staged flat through LDS, a row per group of lanes.  Longer rows: k_softmax_fwd, tiled as
+// Three kernels.  Rows of up to 256 elements (the attention maps of the paper's models: 197, 49): k_softmax_fwd_rows,
+// further down -- tiles staged flat through LDS, a row per group of lanes.  Longer rows of 8k elements, up to 4096:
+// k_softmax_fwd_wave, after it -- a row per group of lanes, in registers.  Other long rows: k_softmax_fwd, tiled as
 // the backward kernel: rows start at odd byte offsets, so a team (one wave, or the workgroup for long rows) takes
 // R consecutive rows with R*cols a multiple of 8 -- a run of whole, aligned 8-element vectors, read and written
 // flat.  A vector touches at most two rows; its two partial maxima, then its two partial sums, go through LDS,
@@ -439,6 +440,159 @@ __global__ __launch_bounds__(kThreads, kSfRowWaves) void k_softmax_fwd_rows(cons
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Rows of 8k elements, 256 < cols <= 4096 (long sequences): a row per group of LPR lanes (a wave, or half or a quarter
+// of one where that fills the lanes better).  Such rows start on vector boundaries, so a lane holds NV whole vectors of
+// ONE row (vector u*LPR + its index in the group), all requested before the first is used; maximum and sum are
+// reductions inside the group -- no LDS traffic, no barrier.  The exponentials stay in registers between the passes.
+// A wave walks blocks of 64/LPR consecutive rows a grid stride apart (the entry point picks LPR < 64 only when the rows
+// per attention map are a multiple of 64/LPR, so that a block lies in one head) and keeps the extrema of the stored
+// values in registers for as long as its rows belong to one head (one pair of LDS atomics per wave and head).
+// ---------------------------------------------------------------------------------------------
+constexpr int kSwMaxCols = 4096;
+
+template <typename T, int LPR, int NV, bool SR>
+__global__ __launch_bounds__(kThreads, NV <= 4 ? 4 : 3) void k_softmax_fwd_wave(const void *__restrict__ s_in, void *__restrict__ y,
+                                                                              int8_t *__restrict__ q, int64_t total_rows, uint32_t cols,
+                                                                              FastDiv div_rows, FastDiv div_heads,
+                                                                              const float *__restrict__ alpha, const float *__restrict__ beta,
+                                                                              uint64_t seed, uint64_t offset, float *__restrict__ part)
+{
+    constexpr int RPW = 64 / LPR;              // rows a wave takes at a time
+    __shared__ float2 head_tab[kSfMaxHeads];   // (255 / alpha, beta) per head
+    __shared__ int lmn[kSfMaxHeads], lmx[kSfMaxHeads];
+    const uint32_t heads = div_heads.d;
+    for (uint32_t h = threadIdx.x; h < heads; h += kThreads) {
+        const float a = alpha[h];
+        head_tab[h] = make_float2(a > 0.0f ? 255.0f / a : 0.0f, beta[h]);
+        lmn[h] = order_key(__builtin_inff());
+        lmx[h] = order_key(-__builtin_inff());
+    }
+    __syncthreads();
+
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t sub = lane / LPR, lr = lane % LPR;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t nvec = cols >> 3;
+    constexpr uint32_t kNone = 0xFFFFFFFFu;
+    uint32_t cur = kNone;                                        // the head whose extrema tmn, tmx hold
+    float tmn = __builtin_inff(), tmx = -__builtin_inff();
+    auto flush = [&]() {
+        tmn = -lanes_combine<64, true>(-tmn);
+        tmx = lanes_combine<64, true>(tmx);
+        if (lane == 0 && tmn <= tmx) {
+            atomicMin(&lmn[cur], order_key(tmn));
+            atomicMax(&lmx[cur], order_key(tmx));
+        }
+        tmn = __builtin_inff();
+        tmx = -__builtin_inff();
+    };
+
+    const int64_t blocks = total_rows / RPW;                     // total_rows is a multiple of RPW
+    for (int64_t blk = int64_t(blockIdx.x) * (kThreads / 64) + wave; blk < blocks; blk += int64_t(gridDim.x) * (kThreads / 64)) {
+        const int64_t row0 = blk * RPW;
+        const uint32_t slab = fastdiv(uint32_t(row0), div_rows);
+        const uint32_t head = slab - fastdiv(slab, div_heads) * heads;
+        if (head != cur) {
+            if (cur != kNone) flush();
+            cur = head;
+        }
+        const float2 prm = head_tab[head];
+        const int64_t e0 = (row0 + sub) * int64_t(cols);
+
+        typename Store<T>::raw_t raw[NV];
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const uint32_t v = u * LPR + lr;
+            if (v < nvec) raw[u] = Nt<T>::load(s_in, e0 + int64_t(v) * kVec);
+        }
+        float ev[NV][8];
+        float m = -__builtin_inff();
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const uint32_t v = u * LPR + lr;
+            if (v < nvec) {
+                Store<T>::unpack(raw[u], ev[u]);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) m = vmax(m, ev[u][j]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) ev[u][j] = -__builtin_inff();   // exponential 0
+            }
+        }
+        m = lanes_combine<LPR, true>(m);
+        float sum = 0.0f;
+#pragma unroll
+        for (int u = 0; u < NV; ++u)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float ex = __builtin_amdgcn_exp2f((ev[u][j] - m) * 1.4426950408889634f);
+                ev[u][j] = ex;
+                sum += ex;
+            }
+        sum = lanes_combine<LPR, false>(sum);
+        const float inv = 1.0f / sum;
+
+        // y, rounded to its storage type; from the stored value the code and the extrema
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const uint32_t v = u * LPR + lr;
+            if (v < nvec) {
+                const int64_t e = e0 + int64_t(v) * kVec;
+                float yv[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) yv[j] = ev[u][j] * inv;
+                const typename Store<T>::raw_t out = Store<T>::pack(yv);
+                float f[8], bits[8], w[8];
+                Store<T>::unpack(out, f);                  // y as stored
+                if (SR) sr_bits(seed, offset + uint64_t(e >> 3), bits);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) w[j] = quantize_one<SR>(f[j], prm.x, prm.y, SR ? bits[j] : 0.0f);
+                Nt<T>::store(y, e, out);
+                nt_store<u32x2>(q + e, pack_codes(w));
+#pragma unroll
+                for (int j = 0; j < 8; ++j) { tmn = vmin(tmn, f[j]); tmx = vmax(tmx, f[j]); }
+            }
+        }
+    }
+    if (cur != kNone) flush();
+    __syncthreads();
+    float *out = part + int64_t(blockIdx.x) * 2 * heads;
+    for (uint32_t h = threadIdx.x; h < heads; h += kThreads) {
+        out[h] = order_val(lmn[h]);
+        out[heads + h] = order_val(lmx[h]);
+    }
+}
+
+static bool sw_fits(int64_t cols) { return cols % kVec == 0 && cols > kSrMaxCols && cols <= kSwMaxCols; }
+
+// lanes per row and vectors per lane: the smallest product that holds the row's vectors, among the shapes built
+struct SwPlan {
+    int lpr, nv, grid;
+};
+static SwPlan sw_plan(int64_t total_rows, int64_t rows, int64_t cols)
+{
+    const int64_t nvec = cols / kVec;
+    SwPlan p{};
+    if (nvec <= 48 && rows % 4 == 0) { p.lpr = 16; p.nv = 3; }
+    else if (nvec <= 64 && rows % 2 == 0) { p.lpr = 32; p.nv = 2; }
+    else if (nvec > 64 && nvec <= 96 && rows % 2 == 0) { p.lpr = 32; p.nv = 3; }
+    else if (nvec <= 128) { p.lpr = 64; p.nv = 2; }
+    else if (nvec <= 192) { p.lpr = 64; p.nv = 3; }
+    else if (nvec <= 256) { p.lpr = 64; p.nv = 4; }
+    else { p.lpr = 64; p.nv = 8; }
+    // one resident round: four workgroups per CU, two where a lane holds eight vectors
+    const int64_t wgs = ceil_div(total_rows / (64 / p.lpr), kThreads / 64), resident = 256 * (p.nv <= 4 ? 4 : 3);
+    p.grid = int(wgs < resident ? wgs : resident);
+    return p;
+}
+// the largest grid any shape of the plan may take for these rows (what the workspace is sized for)
+static int sw_grid_bound(int64_t total_rows)
+{
+    const int64_t wgs = ceil_div(total_rows, kThreads / 64);
+    return int(wgs < 1024 ? wgs : 1024);
+}
+
 struct SrPlan {
     bool ok, tight;
     int lpr, epl, grid;
@@ -507,6 +661,7 @@ size_t softmax_fwd_ws_bytes(int64_t total_rows, int64_t H, int64_t cols)
         const SfPlan p = sf_plan(total_rows, cols);
         if (p.ok && p.grid > grid) grid = p.grid;
     }
+    if (sw_fits(cols) && sw_grid_bound(total_rows) > grid) grid = sw_grid_bound(total_rows);
     if (grid == 0) return 16;
     return size_t(grid) * 2 * size_t(H) * sizeof(float) + 16;
 }
@@ -533,7 +688,8 @@ extern "C" MESA_EXPORT mesa_status mesa_softmax_fwd_q(const void *s_in, int64_t 
     const bool sr = mode == MESA_ROUND_STOCHASTIC;
     const SrPlan rp = sr_plan(total_rows, H, cols, dtype_bytes(dt), sr);
     SfPlan p{};
-    if (!rp.ok) {
+    const bool wave_rows = !rp.ok && sw_fits(cols);
+    if (!rp.ok && !wave_rows) {
         if (cols < kVec) return MESA_ERR_UNSUPPORTED;
         p = sf_plan(total_rows, cols);
         if (!p.ok) return MESA_ERR_UNSUPPORTED;
@@ -566,6 +722,31 @@ extern "C" MESA_EXPORT mesa_status mesa_softmax_fwd_q(const void *s_in, int64_t 
 #undef MESA_LAUNCH_SR
         if (launch_status() != MESA_OK) return MESA_ERR_LAUNCH;   // the consumer must not run on a workspace nobody wrote
         launch_ema_finalize(part, rp.grid, uint32_t(H), alpha, beta, lambda, 0, 0, 0.0f, s);
+        return launch_status();
+    }
+    if (wave_rows) {
+        const SwPlan wp = sw_plan(total_rows, rows, cols);
+#define MESA_LAUNCH_SW(T, LPR_, NV_, SR_) \
+    hipLaunchKernelGGL((k_softmax_fwd_wave<T, LPR_, NV_, SR_>), dim3(wp.grid), dim3(kThreads), 0, s, s_in, y, q, total_rows, uint32_t(cols), \
+                       dr, dh, alpha, beta, seed, offset, part)
+#define MESA_LAUNCH_SW_M(T, LPR_, NV_) \
+    do { if (sr) MESA_LAUNCH_SW(T, LPR_, NV_, true); else MESA_LAUNCH_SW(T, LPR_, NV_, false); } while (0)
+#define MESA_LAUNCH_SW_T(T) \
+    do { \
+        if (wp.lpr == 16) MESA_LAUNCH_SW_M(T, 16, 3); \
+        else if (wp.lpr == 32 && wp.nv == 2) MESA_LAUNCH_SW_M(T, 32, 2); \
+        else if (wp.lpr == 32) MESA_LAUNCH_SW_M(T, 32, 3); \
+        else if (wp.nv == 2) MESA_LAUNCH_SW_M(T, 64, 2); \
+        else if (wp.nv == 3) MESA_LAUNCH_SW_M(T, 64, 3); \
+        else if (wp.nv == 4) MESA_LAUNCH_SW_M(T, 64, 4); \
+        else MESA_LAUNCH_SW_M(T, 64, 8); \
+    } while (0)
+        MESA_FOR_DTYPE(dt, MESA_LAUNCH_SW_T);
+#undef MESA_LAUNCH_SW_T
+#undef MESA_LAUNCH_SW_M
+#undef MESA_LAUNCH_SW
+        if (launch_status() != MESA_OK) return MESA_ERR_LAUNCH;
+        launch_ema_finalize(part, wp.grid, uint32_t(H), alpha, beta, lambda, 0, 0, 0.0f, s);
         return launch_status();
     }
 #define MESA_LAUNCH_SF(T, TPT_, SR_) \

@@ -561,7 +561,12 @@ def test_softmax_backward_every_row_shape(M, B, H, rows, cols, dtype):
 @pytest.mark.parametrize("B,H,rows,cols", [(3, 6, 197, 197), (5, 3, 49, 49), (2, 4, 64, 64), (1, 2, 33, 1000), (2, 3, 7, 19), (1, 1, 5, 8),
                                            (2, 2, 9, 3), (1, 3, 11, 57), (2, 1, 13, 104), (1, 2, 30, 105), (3, 1, 5, 200), (1, 2, 17, 201),
                                            (2, 2, 6, 256), (1, 2, 10, 257), (40, 3, 61, 61),
-                                           (2, 2, 9, 57), (1, 3, 8, 63), (2, 1, 5, 105), (1, 2, 6, 128), (1, 1, 7, 120)])
+                                           (2, 2, 9, 57), (1, 3, 8, 63), (2, 1, 5, 105), (1, 2, 6, 128), (1, 1, 7, 120),
+                                           # rows of 8k elements beyond 256: a wave per row, one to eight vectors per lane
+                                           (1, 2, 5, 264), (2, 2, 3, 512), (1, 2, 4, 520), (1, 1, 3, 1024), (1, 2, 2, 1032),
+                                           (1, 1, 3, 2048), (1, 1, 2, 2056), (1, 2, 2, 4096), (1, 1, 2, 4104),
+                                           # ... whose waves walk several rows and change heads on the way
+                                           (2, 3, 700, 264), (1, 2, 1100, 2056)])
 def test_softmax_layer_forward_in_one_pass(M, B, H, rows, cols, dtype):
     """y = softmax(s) within tolerance of the oracle's binary64 softmax and with rows that sum to 1; the codes and
     the moved estimates are exactly the oracle's single-pass forward applied to the y the kernel stored
@@ -664,10 +669,10 @@ def test_in_place_gradients_and_determinism(M):
 
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=DTYPE_IDS)
-@pytest.mark.parametrize("rows,cols", [(49, 49), (197, 197), (5, 300)])
+@pytest.mark.parametrize("rows,cols", [(49, 49), (197, 197), (5, 300), (5, 304), (3, 2304)])
 def test_softmax_layer_forward_with_masked_logits(M, rows, cols, dtype):
     """Logits of -inf (an attention mask) get probability exactly 0 and do not disturb the rest of their row, in
-    the short-row and in the long-row kernel; rows keep at least one finite logit."""
+    the short-row, the long-row and the wave-per-row kernel; rows keep at least one finite logit."""
     B, H = 2, 3
     gen = torch.Generator(device="cuda").manual_seed(rows + cols)
     s = (torch.randn((B, H, rows, cols), generator=gen, device="cuda") * 3).to(dtype)
@@ -694,7 +699,7 @@ def test_softmax_layer_forward_with_masked_logits(M, rows, cols, dtype):
 def test_softmax_layer_forward_with_large_logits(M, scale, dtype):
     """Logits far from zero (nearly one-hot rows): the maximum is subtracted before the exponential, so the result
     keeps its accuracy, in the short-row and in the long-row kernel."""
-    for cols in (49, 197, 300):
+    for cols in (49, 197, 300, 320):
         B, H, rows = 2, 3, 33
         gen = torch.Generator(device="cuda").manual_seed(int(scale) + cols)
         s = (torch.randn((B, H, rows, cols), generator=gen, device="cuda") * scale).to(dtype).contiguous()
