@@ -204,9 +204,11 @@ mesa_status mesa_gelu_fwd_q(const void *x, mesa_dtype dt, mesa_layout L,
  * I.e. mesa_quantize_update_fused applied to y with the layout {B, H, rows*cols}, without the pass
  * that reads y back.  Logits of -infinity (a mask) get probability 0; every row needs one finite logit.  Per binary16 element 2 bytes in, 2 + 1 bytes out.
  * s: [B*H*rows*cols] of dt (in).  y: same (out), not aliasing s.  q: int8 (out).
- * alpha, beta: [H] (in/out).  ws: MESA_OP_SOFTMAX_FWD_Q bytes.  Limits: rows of up to 256 elements: any
- * length (with more than 256 heads such rows may fall under the next rule); longer rows as for
- * mesa_softmax_bwd_q.
+ * alpha, beta: [H] (in/out).  ws: MESA_OP_SOFTMAX_FWD_Q bytes.  Limits: H <= 1024 and B*H*rows < 2^31.  Rows of up to
+ * 256 elements: any length (with many heads such rows may fall under the last rule); rows of 8k elements up to 4096:
+ * any; other rows of at least 8 elements: as long as 8 / gcd(cols, 8) of them fit a tile of 8192 elements (odd lengths
+ * up to 1024, even ones up to 2048, ...).  Everything else: MESA_ERR_UNSUPPORTED (use the framework's softmax followed by
+ * mesa_quantize_update_fused there).
  */
 mesa_status mesa_softmax_fwd_q(const void *s, int64_t B, int64_t H, int64_t rows, int64_t cols,
                                float *alpha, float *beta, float lambda, void *y, int8_t *q,
