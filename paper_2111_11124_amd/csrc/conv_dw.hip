@@ -92,7 +92,7 @@ template <bool T3, int NKS> struct CvCfg {
     // LDS pitches in elements: multiples of eight (16-byte rows), and such that eight rows' 16-byte reads start in
     // eight different groups of four banks
     static constexpr int PA = SEG + 8;
-    static constexpr int PX = T3 ? SEG + 16 : SEG + 8;
+    static constexpr int PX = T3 ? SEG + 16 + (NKS == 1 ? 8 : 0) : SEG + 8;   // (a pitch of 32 elements would put every other row on the same banks)
     static constexpr int A_BYTES = COT * PA * 2;
     static constexpr int X_BYTES = XR * CIT * PX * 2;
     static constexpr int BUF = A_BYTES + X_BYTES;         // the stage buffer
@@ -782,7 +782,7 @@ static CvPlan cv_plan(const ConvGeom &cg, mesa_dtype dt)
     if (!p.fast) return p;
     p.taps3 = k3;
     p.rag = cg.W % 8 != 0 || cg.OW % 8 != 0;
-    p.nks = cg.OW <= 32 ? 2 : cg.OW <= 64 ? 4 : 8;
+    p.nks = cg.OW <= 16 ? 1 : cg.OW <= 32 ? 2 : cg.OW <= 64 ? 4 : 8;
     const int cot = 128, cit = p.taps3 ? 64 : 128;
     p.tiles_co = int(ceil_div(cg.Cout, cot));
     p.tiles_ci = int(ceil_div(cg.Cin, cit));
@@ -903,7 +903,8 @@ extern "C" MESA_EXPORT mesa_status mesa_conv2d_dw_q(const int8_t *xq, mesa_conv2
     do { \
         if (p.nks == 8) MESA_LAUNCH_CV(E, T3, 8, RAG); \
         else if (p.nks == 4) MESA_LAUNCH_CV(E, T3, 4, RAG); \
-        else MESA_LAUNCH_CV(E, T3, 2, RAG); \
+        else if (p.nks == 2) MESA_LAUNCH_CV(E, T3, 2, RAG); \
+        else MESA_LAUNCH_CV(E, T3, 1, RAG); \
     } while (0)
 #define MESA_PICK_CV(E) \
     do { \

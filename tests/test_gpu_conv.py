@@ -76,6 +76,11 @@ FAST = [
     (2, 200, 14, 14, 136, 1, 1, (1, 1), (0, 0), (1, 1), 4),      # 1x1 on 14 x 14
     (2, 128, 4, 257, 128, 1, 1, (1, 1), (1, 0), (1, 1), 2),      # 1x1: three segments, one column in the last
     (3, 16, 7, 100, 24, 1, 1, (2, 1), (0, 0), (1, 1), 2),        # 1x1: rows that start at every alignment
+    # maps of at most 16 columns: stages of one contraction step
+    (4, 72, 16, 16, 136, 3, 3, (1, 1), (1, 1), (1, 1), 3),
+    (5, 130, 8, 8, 70, 3, 3, (1, 1), (1, 1), (1, 1), 2),
+    (3, 64, 9, 13, 64, 3, 3, (2, 1), (2, 1), (2, 1), 4),
+    (3, 136, 11, 11, 200, 1, 1, (1, 1), (0, 0), (1, 1), 1),
 ]
 
 
