@@ -441,13 +441,15 @@ __global__ __launch_bounds__(kCvThreads, 2) void k_conv_dw(const int8_t *__restr
 // stride_w = dil_w = 1 and OW % 8 == 0 as in the kernel above.  Fixed summation order.
 template <typename E>
 __global__ __launch_bounds__(kCvThreads) void k_conv_valid_sums(const E *__restrict__ dy, ConvGeom cg, int parts, int imgs_per_part,
-                                                                float *__restrict__ V)
+                                                                int row_blocks, int rows_per_block, float *__restrict__ V)
 {
     __shared__ float red[kCvThreads / 64][10];
     const int co = blockIdx.x / parts, pt = blockIdx.x - co * parts;
-    const int b0 = pt * imgs_per_part, b1 = min(b0 + imgs_per_part, cg.B);
+    const int ip = pt / row_blocks, rk = pt - ip * row_blocks;        // a part: some images, one block of their rows
+    const int b0 = ip * imgs_per_part, b1 = min(b0 + imgs_per_part, cg.B);
     const int vec_per_row = cg.OW >> 3;
-    const int vec_per_img = cg.OH * vec_per_row;
+    const int v_begin = rk * rows_per_block * vec_per_row;
+    const int v_end = min((rk + 1) * rows_per_block, cg.OH) * vec_per_row;
     float acc[3][3], tot = 0.0f;
 #pragma unroll
     for (int a = 0; a < 3; ++a)
@@ -456,17 +458,17 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_valid_sums(const E *__restr
     for (int b = b0; b < b1; ++b) {
         const E *plane = dy + (int64_t(b) * cg.Cout + co) * cg.OH * cg.OW;
         // four vectors per thread and round, requested together
-        for (int base = 0; base < vec_per_img; base += 4 * kCvThreads) {
+        for (int base = v_begin; base < v_end; base += 4 * kCvThreads) {
             u32x4 raw[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int idx = base + u * kCvThreads + int(threadIdx.x);
-                raw[u] = idx < vec_per_img ? *reinterpret_cast<const u32x4 *>(plane + int64_t(idx) * 8) : u32x4{0u, 0u, 0u, 0u};
+                raw[u] = idx < v_end ? *reinterpret_cast<const u32x4 *>(plane + int64_t(idx) * 8) : u32x4{0u, 0u, 0u, 0u};
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int idx = base + u * kCvThreads + int(threadIdx.x);
-                if (idx >= vec_per_img) continue;
+                if (idx >= v_end) continue;
                 const int oh = idx / vec_per_row, ow0 = (idx - oh * vec_per_row) * 8;
                 float f[8];
                 Store<E>::unpack(raw[u], f);
@@ -523,12 +525,15 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_valid_sums(const E *__restr
 // (image, channel) plane, four loads in flight per thread).
 template <typename E>
 __global__ __launch_bounds__(kCvThreads) void k_conv_valid_sums_any(const E *__restrict__ dy, ConvGeom cg, int parts, int imgs_per_part,
-                                                                    float *__restrict__ V)
+                                                                    int row_blocks, int rows_per_block, float *__restrict__ V)
 {
     __shared__ float red[kCvThreads / 64][10];
     const int co = blockIdx.x / parts, pt = blockIdx.x - co * parts;
-    const int b0 = pt * imgs_per_part, b1 = min(b0 + imgs_per_part, cg.B);
+    const int ip = pt / row_blocks, rk = pt - ip * row_blocks;
+    const int b0 = ip * imgs_per_part, b1 = min(b0 + imgs_per_part, cg.B);
     const int per_img = cg.OH * cg.OW;
+    const int e_begin = rk * rows_per_block * cg.OW;
+    const int e_end = min((rk + 1) * rows_per_block, cg.OH) * cg.OW;
     float acc[3][3], tot = 0.0f;
 #pragma unroll
     for (int a = 0; a < 3; ++a)
@@ -536,17 +541,17 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_valid_sums_any(const E *__r
         for (int c = 0; c < 3; ++c) acc[a][c] = 0.0f;
     for (int b = b0; b < b1; ++b) {
         const E *plane = dy + (int64_t(b) * cg.Cout + co) * per_img;
-        for (int base = 0; base < per_img; base += 4 * kCvThreads) {
+        for (int base = e_begin; base < e_end; base += 4 * kCvThreads) {
             float f[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int idx = base + u * kCvThreads + int(threadIdx.x);
-                f[u] = idx < per_img ? float(plane[idx]) : 0.0f;
+                f[u] = idx < e_end ? float(plane[idx]) : 0.0f;
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int idx = base + u * kCvThreads + int(threadIdx.x);
-                if (idx >= per_img) continue;
+                if (idx >= e_end) continue;
                 const int oh = idx / cg.OW, ow = idx - oh * cg.OW;
                 tot += f[u];
 #pragma unroll
@@ -768,7 +773,7 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_dw_plain(const int8_t *__re
 
 struct CvPlan {
     bool fast, taps3, rag;
-    int nks, tiles_co, tiles_ci, splits, stages_per_split, nseg, grid, parts, imgs_per_part;
+    int nks, tiles_co, tiles_ci, splits, stages_per_split, nseg, grid, parts, imgs_per_part, row_blocks, rows_per_block;
 };
 
 static CvPlan cv_plan(const ConvGeom &cg, mesa_dtype dt)
@@ -799,11 +804,24 @@ static CvPlan cv_plan(const ConvGeom &cg, mesa_dtype dt)
     p.splits = int(ceil_div(nstages, p.stages_per_split));
     p.grid = int(ceil_div(tiles * p.splits, kCvXcd) * kCvXcd);
     // the sums of dy: enough workgroups to cover the chip when there are few output channels
-    int64_t parts = ceil_div(1024, cg.Cout);
-    if (parts > cg.B) parts = cg.B;
-    if (parts < 1) parts = 1;
-    p.imgs_per_part = int(ceil_div(cg.B, parts));
-    p.parts = int(ceil_div(cg.B, p.imgs_per_part));
+    // (a part is a run of images, or -- with fewer images than parts wanted -- a block of rows of one image, 8192 elements or more;
+    // at most 32 parts: the last kernel adds them up per output channel)
+    int64_t want = ceil_div(2048, cg.Cout);
+    if (want > 32) want = 32;
+    int64_t img_parts = want < cg.B ? want : cg.B;
+    if (img_parts < 1) img_parts = 1;
+    p.imgs_per_part = int(ceil_div(cg.B, img_parts));
+    img_parts = ceil_div(cg.B, p.imgs_per_part);
+    int64_t rb = 1;
+    if (img_parts < want) {
+        rb = ceil_div(want, img_parts);
+        if (rb > ceil_div(cg.OH, 8)) rb = ceil_div(cg.OH, 8);
+        const int64_t by_size = int64_t(cg.OH) * cg.OW / 8192;    // a block keeps every thread at least four vectors
+        if (rb > by_size) rb = by_size < 1 ? 1 : by_size;
+    }
+    p.rows_per_block = int(ceil_div(cg.OH, rb));
+    p.row_blocks = int(ceil_div(cg.OH, p.rows_per_block));
+    p.parts = int(img_parts) * p.row_blocks;
     return p;
 }
 
@@ -911,11 +929,11 @@ extern "C" MESA_EXPORT mesa_status mesa_conv2d_dw_q(const int8_t *xq, mesa_conv2
         if (p.rag) { \
             if (p.taps3) MESA_PICK_NKS(E, true, true); else MESA_PICK_NKS(E, false, true); \
             hipLaunchKernelGGL((k_conv_valid_sums_any<E>), dim3(unsigned(cg.Cout) * p.parts), dim3(kCvThreads), 0, s, \
-                               static_cast<const E *>(dy), cg, p.parts, p.imgs_per_part, V); \
+                               static_cast<const E *>(dy), cg, p.parts, p.imgs_per_part, p.row_blocks, p.rows_per_block, V); \
         } else { \
             if (p.taps3) MESA_PICK_NKS(E, true, false); else MESA_PICK_NKS(E, false, false); \
             hipLaunchKernelGGL((k_conv_valid_sums<E>), dim3(unsigned(cg.Cout) * p.parts), dim3(kCvThreads), 0, s, \
-                               static_cast<const E *>(dy), cg, p.parts, p.imgs_per_part, V); \
+                               static_cast<const E *>(dy), cg, p.parts, p.imgs_per_part, p.row_blocks, p.rows_per_block, V); \
         } \
     } while (0)
     float centre;
