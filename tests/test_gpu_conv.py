@@ -113,6 +113,36 @@ def test_conv_dw_plain_path(M, case, dtype):
     assert eW <= 1e-6 and eb <= 1e-6, (eW, eb)
 
 
+@pytest.mark.parametrize("case", [FAST[0], FAST[1], FAST[10], FAST[12], FAST[14], FAST[16], FAST[17], FAST[20], FAST[21], FAST[24]],
+                         ids=lambda c: "x".join(str(v) for v in c[:7]))
+def test_conv_dw_reads_nothing_it_uses_from_outside_the_tensors(M, case):
+    """Both inputs are the middle of larger buffers whose frames hold NaN (dy) and the extreme code (x): a vector that
+    reaches over a tensor's end, or a masked load whose value were multiplied instead of discarded, would show in dW."""
+    B, Cin, H, W, Cout, KH, KW, stride, pad, dil, G = case
+    cv = M.Conv2d(B, Cin, H, W, Cout, KH, KW, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1])
+    OH, OW = cv.out_hw()
+    gen = torch.Generator(device="cuda").manual_seed(77 + Cin + Cout)
+    nx, nd, fr = B * Cin * H * W, B * Cout * OH * OW, 256
+    bx = torch.full((nx + 2 * fr,), 127, dtype=torch.int8, device="cuda")
+    bd = torch.full((nd + 2 * fr,), float("nan"), dtype=torch.float16, device="cuda")
+    xq = bx[fr:fr + nx].view(B, Cin, H, W)
+    dy = bd[fr:fr + nd].view(B, Cout, OH, OW)
+    xq.copy_(torch.randint(-128, 128, (B, Cin, H, W), dtype=torch.int8, device="cuda", generator=gen))
+    dy.copy_(torch.randn((B, Cout, OH, OW), device="cuda", generator=gen).half())
+    a = (0.5 + 4.0 * torch.rand(G, device="cuda", generator=gen)).float()
+    b = (-2.5 + 2.0 * torch.rand(G, device="cuda", generator=gen)).float()
+    dW = torch.full((Cout, Cin, KH, KW), float("nan"), device="cuda")
+    db = torch.full((Cout,), float("nan"), device="cuda")
+    nws = M.conv2d_dw_q_workspace_bytes(cv, M.F16)
+    assert nws > 0
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+    M.mesa_conv2d_dw_q(xq, cv, G, a, b, dy, dW, db, ws)
+    torch.cuda.synchronize()
+    geom, _, _ = R.conv_geometry(B, Cin, H, W, Cout, KH, KW, stride, pad, dil)
+    rW, rb = R.conv2d_dw_q(npy(xq), geom, G, npy(a), npy(b), npy(dy))
+    assert relerr(npy(dW), rW) <= 2e-3 and relerr(npy(db), rb) <= 1e-5
+
+
 def test_conv_dw_binary32_tensors_take_the_plain_path(M):
     eW, eb, nws = run_case(M, FAST[0], torch.float32)
     assert nws == 0 and eW <= 1e-6 and eb <= 1e-6, (eW, eb, nws)
