@@ -414,6 +414,41 @@ def test_attention_matmul_backward_short_extents(M, B, H, N, Dh, dtype):
     _attention_case(M, B, H, N, Dh, dtype)
 
 
+def _mid_of_frame(t, fill):
+    """A copy of t in the middle of a larger buffer whose 256 elements on either side hold `fill`."""
+    buf = torch.full((t.numel() + 512,), fill, dtype=t.dtype, device=t.device)
+    view = buf[256:256 + t.numel()].view(t.shape)
+    view.copy_(t)
+    return view
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16], ids=["f16", "bf16"])
+@pytest.mark.parametrize("B,H,N,Dh", [(1, 2, 197, 64), (2, 1, 49, 32), (1, 2, 64, 64), (1, 1, 128, 64), (1, 1, 200, 64), (1, 1, 256, 64),
+                                      (1, 1, 264, 64), (1, 1, 272, 32), (1, 1, 577, 64), (1, 2, 33, 48), (1, 1, 100, 128), (1, 3, 223, 96)])
+def test_attention_matmul_backward_uses_nothing_from_outside_its_inputs(M, B, H, N, Dh, dtype):
+    """Every input is the middle of a buffer framed by NaN (gradients) or the extreme code: vectors moved back into the
+    tensor, clamped loads and masked lanes must not let a value from beyond a tensor's ends into a result."""
+    gen = torch.Generator(device="cuda").manual_seed(N * 7 + Dh)
+    n2, nd = B * H * N * N, B * H * N * Dh
+    ca = _mid_of_frame(torch.randint(-128, 128, (n2,), dtype=torch.int8, device="cuda", generator=gen), 127)
+    cq, ck, cvv = (_mid_of_frame(torch.randint(-128, 128, (nd,), dtype=torch.int8, device="cuda", generator=gen), -128) for _ in range(3))
+    dO = _mid_of_frame(torch.randn((B, H, N, Dh), device="cuda", generator=gen).to(dtype), float("nan"))
+    dS = _mid_of_frame((torch.randn((B, H, N, N), device="cuda", generator=gen) * 0.1).to(dtype), float("nan"))
+    par = [(0.5 + torch.rand(H, device="cuda", generator=gen), -0.5 * torch.rand(H, device="cuda", generator=gen)) for _ in range(4)]
+    dA = torch.empty((B, H, N, N), dtype=dtype, device="cuda")
+    dV, dQ, dK = (torch.empty((B, H, N, Dh), dtype=dtype, device="cuda") for _ in range(3))
+    scale = Dh ** -0.5
+    M.mesa_attn_av_bwd_q(ca, cvv, B, H, N, Dh, *par[0], *par[1], dO, dA, dV)
+    M.mesa_attn_qk_bwd_q(cq, ck, B, H, N, Dh, *par[2], *par[3], dS, scale, dQ, dK)
+    rp = [(npy(a), npy(b)) for a, b in par]
+    rdA, rdV = R.attn_av_bwd_q(npy(ca), npy(cvv), B, H, N, Dh, *rp[0], *rp[1], npy(dO))
+    rdQ, rdK = R.attn_qk_bwd_q(npy(cq), npy(ck), B, H, N, Dh, *rp[2], *rp[3], npy(dS), scale)
+    for name, got, ref in (("dA", dA, rdA), ("dV", dV, rdV), ("dQ", dQ, rdQ), ("dK", dK, rdK)):
+        g = npy(got)
+        assert np.all(np.isfinite(g)), name
+        assert relerr(g.reshape(ref.shape), ref) <= TOL[dtype], (name, relerr(g.reshape(ref.shape), ref))
+
+
 def _attention_case(M, B, H, N, Dh, dtype):
     gen = torch.Generator(device="cuda").manual_seed(B * 1000 + N)
     sig = torch.linspace(0.5, 2.0, H, device="cuda").view(1, H, 1, 1)
