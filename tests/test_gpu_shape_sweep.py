@@ -292,3 +292,115 @@ def test_convolution_weight_gradient_over_seeded_geometries(M, seed, dtype):
         assert relerr(npy(dW), rW) <= 2e-3 and relerr(npy(db), rb) <= 1e-5, (case, relerr(npy(dW), rW), relerr(npy(db), rb))
         assert intact(fW) and intact(fb), case
         assert bool((fws[:256] == 0x5A).all() and (fws[256 + nws:] == 0x5A).all()), case
+
+
+def _mid(t, fill):
+    """A copy of t in the middle of a larger buffer whose 256 elements on either side hold `fill`."""
+    buf = torch.full((t.numel() + 512,), fill, dtype=t.dtype, device=t.device)
+    view = buf[256:256 + t.numel()].view(t.shape)
+    view.copy_(t)
+    return view
+
+
+def canon(a):
+    return (np.asarray(a, np.float32) + np.float32(0.0)).view(np.uint32)
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16, torch.float32], ids=["f16", "bf16", "f32"])
+@pytest.mark.parametrize("layout", [(3, 5, 1001), (7, 3, 197 * 197), (1, 12, 8 * 333 + 5), (50, 6, 64), (1, 2, 4099), (2, 3000, 13)])
+def test_streaming_calls_use_nothing_from_outside_their_inputs(M, layout, dtype):
+    """x lies between values far outside its range, the codes between extreme codes, the gradient between NaN: the
+    extrema (hence alpha, beta), the codes and the gradients are the oracle's all the same -- ragged ends, prefetches and
+    masked lanes take nothing from beyond a tensor's last element."""
+    outer, G, inner = layout
+    n = outer * G * inner
+    gen = torch.Generator(device="cuda").manual_seed(n % 9973)
+    big = 60000.0 if dtype == torch.float16 else 1.0e30
+    x = _mid((torch.randn(n, device="cuda", generator=gen) * 1.5 + 0.2).to(dtype), big)
+    a = torch.zeros(G, device="cuda")
+    b = torch.zeros(G, device="cuda")
+    dtc = {torch.float16: M.F16, torch.bfloat16: M.BF16, torch.float32: M.F32}[dtype]
+    ws = torch.empty(max(M.workspace_bytes(M.OP_UPDATE_RUNNING_PARAMS, outer, G, inner, dtc), 16), dtype=torch.uint8, device="cuda")
+    M.mesa_update_running_params(x, layout, a, b, 0.9, True, ws)
+    ra, rb = R.update_running_params(npy(x), layout, np.zeros(G, np.float32), np.zeros(G, np.float32), 0.9, True)
+    assert np.array_equal(canon(npy(a)), canon(ra)) and np.array_equal(canon(npy(b)), canon(rb))
+    q = torch.empty(n, dtype=torch.int8, device="cuda")
+    M.mesa_quantize_headwise(x, layout, a, b, q, M.ROUND_STOCHASTIC, 9, 3)
+    rq = R.quantize_headwise(npy(x), layout, ra, rb, R.ROUND_STOCHASTIC, 9, 3).reshape(-1)
+    assert np.array_equal(npy(q), rq)
+    a2, b2 = a.clone(), b.clone()
+    q2 = torch.empty_like(q)
+    M.mesa_quantize_update_fused(x, layout, a2, b2, 0.9, q2, ws, M.ROUND_NEAREST_EVEN, 0, 0)
+    rq2, ra2, rb2 = R.quantize_update_fused(npy(x), layout, ra, rb, 0.9, R.ROUND_NEAREST, 0, 0)
+    assert np.array_equal(npy(q2), rq2.reshape(-1))
+    assert np.array_equal(canon(npy(a2)), canon(ra2)) and np.array_equal(canon(npy(b2)), canon(rb2))
+    qf = _mid(q, 127)
+    xh = torch.empty(n, dtype=dtype, device="cuda")
+    M.mesa_dequantize(qf, layout, a, b, xh)
+    ref = R.dequantize(rq, layout, ra, rb)
+    assert relerr(npy(xh), ref.reshape(-1)) <= TOL[dtype]
+    dy = _mid(torch.randn(n, device="cuda", generator=gen).to(dtype), float("nan"))
+    dx = torch.empty(n, dtype=dtype, device="cuda")
+    M.mesa_gelu_bwd_q(qf, layout, a, b, dy, dx)
+    g = npy(dx)
+    assert np.all(np.isfinite(g))
+    assert relerr(g, R.gelu_bwd_q(rq, layout, ra, rb, npy(dy)).reshape(-1)) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16], ids=["f16", "bf16"])
+@pytest.mark.parametrize("M_,K,N,G", [(1000, 256, 256, 4), (333, 96, 80, 3), (4097, 768, 144, 12), (65, 1024, 520, 8), (31, 64, 64, 1)])
+def test_weight_gradient_uses_nothing_from_outside_its_inputs(M, M_, K, N, G, dtype):
+    """The Linear weight gradient with its codes between extreme codes and dy between NaN: the prefetch ring runs past
+    the last stage and the last rows do not fill one, and none of that may reach dW or db."""
+    gen = torch.Generator(device="cuda").manual_seed(M_ + K + N)
+    xq = _mid(torch.randint(-128, 128, (M_, K), dtype=torch.int8, device="cuda", generator=gen), 127)
+    dy = _mid(torch.randn((M_, N), device="cuda", generator=gen).to(dtype), float("nan"))
+    a = 0.5 + 3.0 * torch.rand(G, device="cuda", generator=gen)
+    b = -2.0 * torch.rand(G, device="cuda", generator=gen)
+    dW = torch.empty((N, K), device="cuda")
+    db = torch.empty(N, device="cuda")
+    dtc = M.F16 if dtype == torch.float16 else M.BF16
+    ws = torch.empty(max(M.workspace_bytes(M.OP_LINEAR_DW_Q, M_, K, N, dtc), 16), dtype=torch.uint8, device="cuda")
+    M.mesa_linear_dw_q(xq, M_, K, G, a, b, dy, N, dW, db, ws)
+    rW, rb = R.linear_dw_q(npy(xq), M_, K, G, npy(a), npy(b), npy(dy), N)
+    gW, gb = npy(dW), npy(db)
+    assert np.all(np.isfinite(gW)) and np.all(np.isfinite(gb))
+    assert relerr(gW, rW) <= 2e-3 and relerr(gb, rb) <= 2e-3, (relerr(gW, rW), relerr(gb, rb))
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16], ids=["f16", "bf16"])
+def test_row_kernels_use_nothing_from_outside_their_inputs(M, dtype):
+    """Softmax backward and LayerNorm backward over rows that end the buffers: codes between extreme codes, gradients
+    between NaN."""
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    for (B, H, rows, cols) in ((2, 3, 197, 197), (1, 2, 50, 49), (1, 1, 9, 577), (1, 2, 6, 1024), (1, 1, 3, 4104)):
+        n = B * H * rows * cols
+        yq = _mid(torch.randint(-128, 128, (n,), dtype=torch.int8, device="cuda", generator=gen), 127)
+        dy = _mid(torch.randn((B, H, rows, cols), device="cuda", generator=gen).to(dtype), float("nan"))
+        a = 0.5 + torch.rand(H, device="cuda", generator=gen)
+        b = torch.zeros(H, device="cuda")
+        dx = torch.empty((B, H, rows, cols), dtype=dtype, device="cuda")
+        M.mesa_softmax_bwd_q(yq, B, H, rows, cols, a, b, dy, dx)
+        g = npy(dx)
+        assert np.all(np.isfinite(g)), (rows, cols)
+        ref = R.softmax_bwd_q(npy(yq), B, H, rows, cols, npy(a), npy(b), npy(dy))
+        assert relerr(g.reshape(ref.shape), ref) <= TOL[dtype], (rows, cols)
+    for (Mr, D, G) in ((197, 768, 12), (33, 1024, 16), (50, 96, 3), (9, 2048, 4), (5, 520, 1), (7, 100, 1)):
+        xq = _mid(torch.randint(-128, 128, (Mr, D), dtype=torch.int8, device="cuda", generator=gen), -128)
+        dy = _mid(torch.randn((Mr, D), device="cuda", generator=gen).to(dtype), float("nan"))
+        gamma = (1 + 0.1 * torch.randn(D, device="cuda", generator=gen)).to(dtype)
+        mean = 0.1 * torch.randn(Mr, device="cuda", generator=gen)
+        rstd = 0.5 + torch.rand(Mr, device="cuda", generator=gen)
+        a = 4.0 + torch.rand(G, device="cuda", generator=gen)
+        b = -2.0 - torch.rand(G, device="cuda", generator=gen)
+        dx = torch.empty((Mr, D), dtype=dtype, device="cuda")
+        dg = torch.empty(D, device="cuda")
+        dbt = torch.empty(D, device="cuda")
+        dtc = M.F16 if dtype == torch.float16 else M.BF16
+        ws = torch.empty(max(M.workspace_bytes(M.OP_LAYERNORM_BWD_Q, Mr, D, G, dtc), 16), dtype=torch.uint8, device="cuda")
+        M.mesa_layernorm_bwd_q(xq, Mr, D, G, a, b, mean, rstd, gamma, dy, dx, dg, dbt, ws)
+        rdx, rdg, rdb = R.layernorm_bwd_q(npy(xq), Mr, D, G, npy(a), npy(b), npy(mean), npy(rstd), npy(gamma), npy(dy))
+        for name, got, ref in (("dx", dx, rdx), ("dgamma", dg, rdg), ("dbeta", dbt, rdb)):
+            gg = npy(got)
+            assert np.all(np.isfinite(gg)), (name, Mr, D)
+            assert relerr(gg.reshape(ref.shape), ref) <= TOL[dtype], (name, Mr, D, relerr(gg.reshape(ref.shape), ref))
