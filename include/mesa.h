@@ -204,11 +204,12 @@ mesa_status mesa_gelu_fwd_q(const void *x, mesa_dtype dt, mesa_layout L,
  * I.e. mesa_quantize_update_fused applied to y with the layout {B, H, rows*cols}, without the pass
  * that reads y back.  Logits of -infinity (a mask) get probability 0; every row needs one finite logit.  Per binary16 element 2 bytes in, 2 + 1 bytes out.
  * s: [B*H*rows*cols] of dt (in).  y: same (out), not aliasing s.  q: int8 (out).
- * alpha, beta: [H] (in/out).  ws: MESA_OP_SOFTMAX_FWD_Q bytes.  Limits: H <= 1024 and B*H*rows < 2^31.  Rows of up to
- * 256 elements: any length (with many heads such rows may fall under the last rule); rows of 8k elements up to 4096:
- * any; other rows of at least 8 elements: as long as 8 / gcd(cols, 8) of them fit a tile of 8192 elements (odd lengths
- * up to 1024, even ones up to 2048, ...).  Everything else: MESA_ERR_UNSUPPORTED (use the framework's softmax followed by
- * mesa_quantize_update_fused there).
+ * alpha, beta: [H] (in/out).  ws: MESA_OP_SOFTMAX_FWD_Q bytes.  Limits: rows, cols and B*H*rows below 2^31, else
+ * MESA_ERR_UNSUPPORTED.  One pass over s for H <= 1024 and rows of up to 256 elements (any length), rows of 8k elements
+ * up to 4096, and other rows of at least 8 elements as long as 8 / gcd(cols, 8) of them fit a tile of 8192 elements
+ * (odd lengths up to 1024, even ones up to 2048, ...).  Every other shape takes two steps inside the call -- y by a
+ * plain kernel, one workgroup per row, then mesa_quantize_update_fused on y (which reads y back) -- and that step's
+ * limits: H <= 4096, rows*cols < 2^30.
  */
 mesa_status mesa_softmax_fwd_q(const void *s, int64_t B, int64_t H, int64_t rows, int64_t cols,
                                float *alpha, float *beta, float lambda, void *y, int8_t *q,
@@ -223,7 +224,9 @@ mesa_status mesa_softmax_fwd_q(const void *s, int64_t B, int64_t H, int64_t rows
  *   alpha, beta then moved by this batch's per-group extrema of x, Eq. (6)-(7)  (as mesa_quantize_update_fused).
  * x: (M, D) of dt (in).  gamma, bias: [D] of dt.  y: (M, D) of dt (out), not aliasing x.  mean, rstd: [M] binary32
  * (out).  q: int8 (out).  alpha, beta: [G] (in/out).  ws: MESA_OP_LAYERNORM_FWD_Q bytes.
- * Limits: D % 8 == 0, (D/G) % 8 == 0, D <= 2048, G <= 1024, else MESA_ERR_UNSUPPORTED.
+ * One pass over x for D % 8 == 0, (D/G) % 8 == 0, D <= 2048, G <= 1024.  Every other shape takes two steps inside the
+ * call -- mesa_quantize_update_fused on x, then mean, rstd and y by a plain kernel, one workgroup per row -- with that
+ * step's limit G <= 4096.  D >= 2^31 or M >= 2^40: MESA_ERR_UNSUPPORTED.
  */
 mesa_status mesa_layernorm_fwd_q(const void *x, int64_t M, int64_t D, int64_t G,
                                  const void *gamma, const void *bias, float eps,

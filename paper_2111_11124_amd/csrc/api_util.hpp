@@ -12,6 +12,7 @@ namespace mesa {
 
 // scratch sizes, each defined next to the launcher that uses the scratch
 size_t update_ws_bytes(int64_t outer, int64_t groups, int64_t inner);
+size_t update_ws_bound(int64_t numel, int64_t groups);
 size_t layernorm_ws_bytes(int64_t M, int64_t D);
 size_t linear_dw_ws_bytes(int64_t M, int64_t K, int64_t N, mesa_dtype dt);
 size_t softmax_fwd_ws_bytes(int64_t total_rows, int64_t H, int64_t cols);

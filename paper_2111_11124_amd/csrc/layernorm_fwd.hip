@@ -185,11 +185,56 @@ static LfPlan lf_plan(int64_t M, int64_t D)
     return p;
 }
 
+// Rows the kernel above does not take (lengths or groups that are no multiples of 8, rows beyond 2048 elements, more
+// groups than its tables hold): mean, 1/sqrt(var + eps) and y by a plain kernel -- one workgroup per row, the row read
+// three times, sums added in a fixed order --, the codes and the estimates by the single-pass quantizer on x, which is
+// how the call is defined.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_layernorm_fwd_plain_y(const void *__restrict__ x, void *__restrict__ y,
+                                                                    float *__restrict__ mean, float *__restrict__ rstd,
+                                                                    const void *__restrict__ gamma, const void *__restrict__ bias,
+                                                                    float eps, int64_t M, uint32_t D)
+{
+    __shared__ float red[kThreads / 64];
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    auto block_sum = [&](float v) {   // the same value in every thread
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+        if (lane == 0) red[wave] = v;
+        __syncthreads();
+        float r = red[0];
+#pragma unroll
+        for (int w = 1; w < kThreads / 64; ++w) r += red[w];
+        __syncthreads();
+        return r;
+    };
+    const float inv_D = 1.0f / float(D);
+    for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
+        const int64_t e0 = row * int64_t(D);
+        float s1 = 0.0f;
+        for (uint32_t c = threadIdx.x; c < D; c += kThreads) s1 += Store<T>::load1(x, e0 + c);
+        const float mu = block_sum(s1) * inv_D;
+        float s2 = 0.0f;
+        for (uint32_t c = threadIdx.x; c < D; c += kThreads) {
+            const float d = Store<T>::load1(x, e0 + c) - mu;
+            s2 = fmaf(d, d, s2);
+        }
+        const float rs = 1.0f / sqrtf(block_sum(s2) * inv_D + eps);
+        if (threadIdx.x == 0) { mean[row] = mu; rstd[row] = rs; }
+        for (uint32_t c = threadIdx.x; c < D; c += kThreads) {
+            const float xn = (Store<T>::load1(x, e0 + c) - mu) * rs;
+            Store<T>::store1(y, e0 + c, fmaf(xn, Store<T>::load1(gamma, c), Store<T>::load1(bias, c)));
+        }
+    }
+}
+
+static bool lf_two_step(const LfPlan &p, int64_t D, int64_t G) { return !p.ok || (D / G) % kVec != 0 || G > kLfMaxGroups; }
+
 size_t layernorm_fwd_ws_bytes(int64_t M, int64_t D, int64_t G)
 {
-    if (M <= 0 || D <= 0 || G <= 0 || G > kLfMaxGroups) return 16;
+    if (M <= 0 || D <= 0 || G <= 0 || D % G != 0) return 16;
     const LfPlan p = lf_plan(M, D);
-    if (!p.ok) return 16;
+    if (lf_two_step(p, D, G)) return update_ws_bytes(M, G, D / G) + 16;
     return size_t(p.grid) * 2 * size_t(G) * sizeof(float) + 16;
 }
 
@@ -211,9 +256,21 @@ extern "C" MESA_EXPORT mesa_status mesa_layernorm_fwd_q(const void *x, int64_t M
         !aligned16(gamma) || !aligned16(bias) || !aligned4(mean) || !aligned4(rstd) || !aligned4(alpha) || !aligned4(beta) || y == x)
         return MESA_ERR_INVALID_ARG;
     const LfPlan p = lf_plan(M, D);
-    if (!p.ok || (D / G) % kVec != 0 || G > kLfMaxGroups || M >= (int64_t(1) << 40)) return MESA_ERR_UNSUPPORTED;
-    if (!ws || !aligned16(ws) || ws_bytes < layernorm_fwd_ws_bytes(M, D, G)) return MESA_ERR_WORKSPACE;
+    if (M >= (int64_t(1) << 40) || D >= (int64_t(1) << 31)) return MESA_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (lf_two_step(p, D, G)) {
+        // the single-pass quantizer checks its own limits (up to 4096 groups) before it launches anything; y follows
+        const mesa_layout L = {M, G, D / G};
+        const mesa_status st = mesa_quantize_update_fused(x, dt, L, alpha, beta, lambda, q, mode, seed, offset, ws, ws_bytes, stream);
+        if (st != MESA_OK) return st;
+        const unsigned grid = unsigned(M < (int64_t(1) << 20) ? M : (int64_t(1) << 20));
+#define MESA_LAUNCH_LP(T) \
+        hipLaunchKernelGGL((k_layernorm_fwd_plain_y<T>), dim3(grid), dim3(kThreads), 0, s, x, y, mean, rstd, gamma, bias, eps, M, uint32_t(D))
+        MESA_FOR_DTYPE(dt, MESA_LAUNCH_LP);
+#undef MESA_LAUNCH_LP
+        return launch_status();
+    }
+    if (!ws || !aligned16(ws) || ws_bytes < layernorm_fwd_ws_bytes(M, D, G)) return MESA_ERR_WORKSPACE;
     float *part = static_cast<float *>(ws);
     FastDiv dv = make_fastdiv(uint32_t((D / G) / kVec));
     const float inv_D = 1.0f / float(D);

@@ -647,23 +647,83 @@ static SfPlan sf_plan(int64_t total_rows, int64_t cols)
     return p;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Rows no kernel above takes (odd lengths too long for a tile, rows shorter than a vector that have no row plan, more
+// heads than the tables hold): y by a plain kernel -- one workgroup per row, the row read three times --, then the
+// single-pass quantizer on the stored y, which is how the call is defined.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_softmax_fwd_plain_y(const void *__restrict__ s_in, void *__restrict__ y, int64_t total_rows,
+                                                                  uint32_t cols)
+{
+    __shared__ float red[kThreads / 64];
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    auto block_combine = [&](float v, auto is_max) {   // the same value in every thread; waves in a fixed order
+        constexpr bool MAX = decltype(is_max)::value;
+        v = lanes_combine<64, MAX>(v);
+        if (lane == 0) red[wave] = v;
+        __syncthreads();
+        float r = red[0];
+#pragma unroll
+        for (int w = 1; w < kThreads / 64; ++w) r = MAX ? vmax(r, red[w]) : r + red[w];
+        __syncthreads();
+        return r;
+    };
+    for (int64_t row = blockIdx.x; row < total_rows; row += gridDim.x) {
+        const int64_t e0 = row * int64_t(cols);
+        float m = -__builtin_inff();
+        for (uint32_t c = threadIdx.x; c < cols; c += kThreads) m = vmax(m, Store<T>::load1(s_in, e0 + c));
+        m = block_combine(m, std::true_type());
+        float sum = 0.0f;
+        for (uint32_t c = threadIdx.x; c < cols; c += kThreads)
+            sum += __builtin_amdgcn_exp2f((Store<T>::load1(s_in, e0 + c) - m) * 1.4426950408889634f);
+        sum = block_combine(sum, std::false_type());
+        const float inv = 1.0f / sum;
+        for (uint32_t c = threadIdx.x; c < cols; c += kThreads)
+            Store<T>::store1(y, e0 + c, __builtin_amdgcn_exp2f((Store<T>::load1(s_in, e0 + c) - m) * 1.4426950408889634f) * inv);
+    }
+}
+
+// which kernel family takes the call; two_step: none of the single-pass kernels
+struct SfRoute {
+    bool two_step, wave_rows;
+    SrPlan rp;
+    SfPlan p;
+};
+static SfRoute sf_route(int64_t total_rows, int64_t H, int64_t cols, int elem_bytes, bool sr)
+{
+    SfRoute r{};
+    if (H > kSfMaxHeads) { r.two_step = true; return r; }
+    r.rp = sr_plan(total_rows, H, cols, elem_bytes, sr);
+    if (r.rp.ok) return r;
+    r.wave_rows = sw_fits(cols);
+    if (r.wave_rows) return r;
+    if (cols < kVec) { r.two_step = true; return r; }
+    r.p = sf_plan(total_rows, cols);
+    r.two_step = !r.p.ok;
+    return r;
+}
+
 // enough for whichever kernel, storage type and rounding mode the call will use
 size_t softmax_fwd_ws_bytes(int64_t total_rows, int64_t H, int64_t cols)
 {
-    if (total_rows <= 0 || H <= 0 || cols <= 0 || H > kSfMaxHeads || total_rows >= (int64_t(1) << 31)) return 16;
+    if (total_rows <= 0 || H <= 0 || cols <= 0 || total_rows >= (int64_t(1) << 31)) return 16;
     int grid = 0;
+    bool two_step = false;
     for (int eb = 2; eb <= 4; eb += 2)
         for (int sr = 0; sr < 2; ++sr) {
-            const SrPlan r = sr_plan(total_rows, H, cols, eb, sr != 0);
-            if (r.ok && r.grid > grid) grid = r.grid;
+            const SfRoute r = sf_route(total_rows, H, cols, eb, sr != 0);
+            two_step = two_step || r.two_step;
+            if (r.rp.ok && r.rp.grid > grid) grid = r.rp.grid;
+            if (r.p.ok && r.p.grid > grid) grid = r.p.grid;
+            if (r.wave_rows && sw_grid_bound(total_rows) > grid) grid = sw_grid_bound(total_rows);
         }
-    if (cols >= kVec) {
-        const SfPlan p = sf_plan(total_rows, cols);
-        if (p.ok && p.grid > grid) grid = p.grid;
+    size_t need = grid == 0 ? 16 : size_t(grid) * 2 * size_t(H) * sizeof(float) + 16;
+    if (two_step) {
+        const size_t b = update_ws_bound(total_rows * cols, H);
+        if (b > need) need = b;
     }
-    if (sw_fits(cols) && sw_grid_bound(total_rows) > grid) grid = sw_grid_bound(total_rows);
-    if (grid == 0) return 16;
-    return size_t(grid) * 2 * size_t(H) * sizeof(float) + 16;
+    return need;
 }
 
 }  // namespace mesa
@@ -681,22 +741,32 @@ extern "C" MESA_EXPORT mesa_status mesa_softmax_fwd_q(const void *s_in, int64_t 
     if (!s_in || !y || !q || !alpha || !beta || !aligned16(s_in) || !aligned16(y) || !aligned16(q) || !aligned4(alpha) ||
         !aligned4(beta) || y == s_in)
         return MESA_ERR_INVALID_ARG;
-    if (H > kSfMaxHeads || rows >= (int64_t(1) << 31)) return MESA_ERR_UNSUPPORTED;
+    if (rows >= (int64_t(1) << 31) || cols >= (int64_t(1) << 31)) return MESA_ERR_UNSUPPORTED;
     const long double tr = (long double)B * (long double)H * (long double)rows;
     if (tr >= 2147483648.0L) return MESA_ERR_UNSUPPORTED;
     const int64_t total_rows = B * H * rows;
     const bool sr = mode == MESA_ROUND_STOCHASTIC;
-    const SrPlan rp = sr_plan(total_rows, H, cols, dtype_bytes(dt), sr);
-    SfPlan p{};
-    const bool wave_rows = !rp.ok && sw_fits(cols);
-    if (!rp.ok && !wave_rows) {
-        if (cols < kVec) return MESA_ERR_UNSUPPORTED;
-        p = sf_plan(total_rows, cols);
-        if (!p.ok) return MESA_ERR_UNSUPPORTED;
+    const SfRoute route = sf_route(total_rows, H, cols, dtype_bytes(dt), sr);
+    const SrPlan &rp = route.rp;
+    const SfPlan &p = route.p;
+    const bool wave_rows = route.wave_rows;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (route.two_step) {
+        // everything the second step would refuse is refused here, before anything is written
+        const mesa_layout L = {B, H, rows * cols};
+        const mesa_status st = check_layout(L);
+        if (st != MESA_OK) return st;
+        if (size_t(H) * 16 > size_t(64) * 1024) return MESA_ERR_UNSUPPORTED;
+        if (!ws || !aligned16(ws) || ws_bytes < update_ws_bytes(L.outer, L.groups, L.inner)) return MESA_ERR_WORKSPACE;
+        const unsigned grid = unsigned(total_rows < (int64_t(1) << 20) ? total_rows : (int64_t(1) << 20));
+#define MESA_LAUNCH_SP(T) hipLaunchKernelGGL((k_softmax_fwd_plain_y<T>), dim3(grid), dim3(kThreads), 0, s, s_in, y, total_rows, uint32_t(cols))
+        MESA_FOR_DTYPE(dt, MESA_LAUNCH_SP);
+#undef MESA_LAUNCH_SP
+        if (launch_status() != MESA_OK) return MESA_ERR_LAUNCH;
+        return mesa_quantize_update_fused(y, dt, L, alpha, beta, lambda, q, mode, seed, offset, ws, ws_bytes, stream);
     }
     if (!ws || !aligned16(ws) || ws_bytes < softmax_fwd_ws_bytes(total_rows, H, cols)) return MESA_ERR_WORKSPACE;
     FastDiv dc = make_fastdiv(uint32_t(cols)), dr = make_fastdiv(uint32_t(rows)), dh = make_fastdiv(uint32_t(H));
-    hipStream_t s = static_cast<hipStream_t>(stream);
     float *part = static_cast<float *>(ws);
     if (rp.ok) {
 #define MESA_LAUNCH_SR(T, LPR_, EPL_, TIGHT_, SR_) \

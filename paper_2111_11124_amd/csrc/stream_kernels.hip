@@ -1364,6 +1364,27 @@ extern "C" MESA_EXPORT size_t mesa_workspace_bytes(mesa_op op, int64_t d0, int64
     return 0;
 }
 
+// An upper bound of update_ws_bytes over every layout with this many elements and groups (for a caller that knows the
+// tensor's size and groups but not how outer and inner share the rest): minmax_grid stays within its cap, rounded up to
+// a multiple of at most 64, plus the at most 255 steps of its search.
+size_t mesa::update_ws_bound(int64_t numel, int64_t groups)
+{
+    if (numel <= 0 || groups <= 0) return 16;
+    int64_t worst = 0;
+    const int caps[2] = {kMmGridCap, kFuGridCap};
+    for (int v = 0; v < 2; ++v) {
+        int64_t cap = caps[v];
+        if (groups > 64) {
+            const int64_t fixed = int64_t(caps[v]) * 64 / groups, paid = numel / (64 * groups);
+            int64_t c = fixed > paid ? fixed : paid;
+            if (c < 32) c = 32;
+            if (c < cap) cap = c;
+        }
+        if (cap > worst) worst = cap;
+    }
+    return size_t(worst + 64 + 256) * 2 * size_t(groups) * sizeof(float);
+}
+
 // size of the min/max partials: enough for mesa_update_running_params and mesa_quantize_update_fused
 size_t mesa::update_ws_bytes(int64_t outer, int64_t groups, int64_t inner)
 {

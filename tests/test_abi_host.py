@@ -71,14 +71,19 @@ def test_argument_errors_are_reported_before_any_launch(M):
     assert L.mesa_gelu_fwd_q(P, M.F16, lay, P, P, 0.9, P2, P, 0, 0, 0, P, 8, None) == M.ERR_WORKSPACE
     assert L.mesa_softmax_fwd_q(P, 2, 3, 19, 19, P, P, 0.9, P, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_INVALID_ARG   # y aliases s
     assert L.mesa_softmax_fwd_q(P, 2, 3, 19, 19, P, P, 0.9, P2, P, 0, 0, 0, P, 8, M.F16, None) == M.ERR_WORKSPACE
-    assert L.mesa_softmax_fwd_q(P, 2, 3, 19, 3001, P, P, 0.9, P2, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_UNSUPPORTED  # 8 odd rows exceed a tile
-    assert L.mesa_softmax_fwd_q(P, 2, 2000, 19, 19, P, P, 0.9, P2, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_UNSUPPORTED  # heads
+    assert L.mesa_softmax_fwd_q(P, 2, 3, 19, 3001, P, P, 0.9, P2, P, 0, 0, 0, P, 8, M.F16, None) == M.ERR_WORKSPACE  # the two-step path checks its workspace first
+    assert L.mesa_softmax_fwd_q(P, 2, 5000, 19, 19, P, P, 0.9, P2, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_UNSUPPORTED  # heads
+    assert L.mesa_softmax_fwd_q(P, 2, 3, 1 << 16, 1 << 15, P, P, 0.9, P2, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_UNSUPPORTED  # 2^31 elements a map
+    assert M.workspace_bytes(M.OP_SOFTMAX_FWD_Q, 2 * 3 * 19, 3, 3001, M.F16) >= M.workspace_bytes(M.OP_UPDATE_RUNNING_PARAMS, 2, 3, 19 * 3001, M.F16)
+    assert M.workspace_bytes(M.OP_SOFTMAX_FWD_Q, 6 * 7 * 1000, 7, 1025, M.F16) >= M.workspace_bytes(M.OP_UPDATE_RUNNING_PARAMS, 6, 7, 1000 * 1025, M.F16)
+    assert M.workspace_bytes(M.OP_SOFTMAX_FWD_Q, 3 * 1500 * 64, 1500, 19, M.F16) >= M.workspace_bytes(M.OP_UPDATE_RUNNING_PARAMS, 3, 1500, 64 * 19, M.F16)
     assert L.mesa_softmax_fwd_q(P, 2, 3, 19, 19, P, P, 1.5, P2, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_INVALID_ARG  # lambda
     assert M.workspace_bytes(M.OP_SOFTMAX_FWD_Q, 128 * 6 * 197, 6, 197, M.F16) >= 768 * 2 * 6 * 4
     F = C.c_float
     assert L.mesa_layernorm_fwd_q(P, 100, 384, 6, P, P, F(1e-5), P, P, F(0.9), P, P, P, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_INVALID_ARG  # y aliases x
     assert L.mesa_layernorm_fwd_q(P, 100, 384, 6, P, P, F(1e-5), P, P, F(0.9), P2, P, P, P, 0, 0, 0, P, 8, M.F16, None) == M.ERR_WORKSPACE
-    assert L.mesa_layernorm_fwd_q(P, 100, 4096, 8, P, P, F(1e-5), P, P, F(0.9), P2, P, P, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_UNSUPPORTED  # rows too long
+    assert L.mesa_layernorm_fwd_q(P, 100, 4096, 8, P, P, F(1e-5), P, P, F(0.9), P2, P, P, P, 0, 0, 0, P, 8, M.F16, None) == M.ERR_WORKSPACE  # the two-step path
+    assert L.mesa_layernorm_fwd_q(P, 100, 40000, 5000, P, P, F(1e-5), P, P, F(0.9), P2, P, P, P, 0, 0, 0, P, 1 << 24, M.F16, None) == M.ERR_UNSUPPORTED  # groups
     assert L.mesa_layernorm_fwd_q(P, 100, 384, 5, P, P, F(1e-5), P, P, F(0.9), P2, P, P, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_INVALID_ARG  # D % G
     assert L.mesa_layernorm_fwd_q(P, 100, 384, 6, P, P, F(-1.0), P, P, F(0.9), P2, P, P, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_INVALID_ARG  # eps
     assert L.mesa_dequantize(P, lay, P, None, P, M.F16, None) == M.ERR_INVALID_ARG
@@ -186,3 +191,26 @@ def test_the_binding_has_no_fallback(monkeypatch, tmp_path):
     a = torch.ones(1)
     with pytest.raises(ValueError, match="device tensors"):
         _ffi.mesa_quantize_headwise(x, (1, 1, 64), a, a, q)
+
+
+def test_softmax_forward_workspace_covers_the_two_step_path():
+    """Rows that no single-pass softmax kernel takes (odd lengths above 1024, more than 1024 heads) run a plain softmax
+    and then the single-pass quantizer, whose workspace depends on how the rows split into batch and rows per map -- which
+    the size query is not told.  Its answer must cover every split."""
+    import random
+    import paper_2111_11124_amd as M
+    rnd = random.Random(5)
+    for _ in range(400):
+        if rnd.random() < 0.5:
+            H, cols = rnd.randint(1, 40), 2 * rnd.randint(513, 4000) + 1
+        else:
+            H, cols = rnd.randint(1025, 4096), rnd.randint(1, 300)
+        B, rows = rnd.randint(1, 64), rnd.randint(1, 3000)
+        if B * H * rows >= 1 << 31 or rows * cols >= 1 << 30:
+            continue
+        have = M.workspace_bytes(M.OP_SOFTMAX_FWD_Q, B * H * rows, H, cols, M.F16)
+        need = M.workspace_bytes(M.OP_UPDATE_RUNNING_PARAMS, B, H, rows * cols, M.F16)
+        assert have >= need, (B, H, rows, cols, have, need)
+        # the same number of rows split the other way round
+        need2 = M.workspace_bytes(M.OP_UPDATE_RUNNING_PARAMS, rows, H, B * cols, M.F16)
+        assert have >= need2, (rows, H, B, cols, have, need2)

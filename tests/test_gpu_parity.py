@@ -601,7 +601,9 @@ def test_softmax_backward_every_row_shape(M, B, H, rows, cols, dtype):
                                            (1, 2, 5, 264), (2, 2, 3, 512), (1, 2, 4, 520), (1, 1, 3, 1024), (1, 2, 2, 1032),
                                            (1, 1, 3, 2048), (1, 1, 2, 2056), (1, 2, 2, 4096), (1, 1, 2, 4104),
                                            # ... whose waves walk several rows and change heads on the way
-                                           (2, 3, 700, 264), (1, 2, 1100, 2056)])
+                                           (2, 3, 700, 264), (1, 2, 1100, 2056),
+                                           # what no single-pass kernel takes: a plain softmax, then the single-pass quantizer on y
+                                           (1, 2, 3, 3001), (2, 1, 5, 1025), (2, 1500, 3, 19), (1, 3, 2, 8200)])
 def test_softmax_layer_forward_in_one_pass(M, B, H, rows, cols, dtype):
     """y = softmax(s) within tolerance of the oracle's binary64 softmax and with rows that sum to 1; the codes and
     the moved estimates are exactly the oracle's single-pass forward applied to the y the kernel stored
@@ -629,7 +631,9 @@ def test_softmax_layer_forward_in_one_pass(M, B, H, rows, cols, dtype):
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=DTYPE_IDS)
 @pytest.mark.parametrize("Mr,D,G", [(1000, 384, 6), (77, 768, 12), (50, 1024, 4), (33, 64, 2), (19, 8, 1), (300, 96, 3), (5, 520, 1),
-                                    (41, 1032, 3), (130, 1536, 12), (9, 2048, 16)])
+                                    (41, 1032, 3), (130, 1536, 12), (9, 2048, 16),
+                                    # what the single-pass kernel does not take: plain statistics and y, then the single-pass quantizer on x
+                                    (6, 84, 7), (4, 4096, 8), (3, 5000, 5), (10, 96, 24), (3, 3000, 1500)])
 def test_layernorm_layer_forward_in_one_pass(M, Mr, D, G, dtype):
     """y, mean and rstd within tolerance of the oracle's binary64 LayerNorm; codes of x and the moved estimates bit
     for bit (two steps, both rounding modes); the statistics feed the backward call as they are."""
