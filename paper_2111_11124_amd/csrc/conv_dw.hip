@@ -521,11 +521,13 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_valid_sums(const E *__restr
     }
 }
 
-// The same sums for widths that are no multiples of 8: element by element (consecutive threads, consecutive elements of the
-// (image, channel) plane, four loads in flight per thread).
+// The same sums for widths that are no multiples of 8 (at least 8): a thread takes eight consecutive elements of the
+// (image, channel) plane with one unaligned vector load -- they lie in one row, or in two with the row's end between them --,
+// four such vectors requested together; the last, partial vector of a part element by element.
 template <typename E>
 __global__ __launch_bounds__(kCvThreads) void k_conv_valid_sums_any(const E *__restrict__ dy, ConvGeom cg, int parts, int imgs_per_part,
-                                                                    int row_blocks, int rows_per_block, float *__restrict__ V)
+                                                                    int row_blocks, int rows_per_block, FastDiv div_ow,
+                                                                    float *__restrict__ V)
 {
     __shared__ float red[kCvThreads / 64][10];
     const int co = blockIdx.x / parts, pt = blockIdx.x - co * parts;
@@ -539,33 +541,68 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_valid_sums_any(const E *__r
     for (int a = 0; a < 3; ++a)
 #pragma unroll
         for (int c = 0; c < 3; ++c) acc[a][c] = 0.0f;
-    for (int b = b0; b < b1; ++b) {
-        const E *plane = dy + (int64_t(b) * cg.Cout + co) * per_img;
-        for (int base = e_begin; base < e_end; base += 4 * kCvThreads) {
-            float f[4];
+    // the part's vectors, image after image, shared out among the threads (small maps: a part is several images of a few
+    // vectors each)
+    const int vpi = (e_end - e_begin + 7) >> 3;               // vectors per image
+    const int nv = (b1 - b0) * vpi;
+    for (int base = 0; base < nv; base += 4 * kCvThreads) {
+        u32x4 raw[4];
+        int at[4];                                            // the vector's first element in its plane, -1: none
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int idx = base + u * kCvThreads + int(threadIdx.x);
-                f[u] = idx < e_end ? float(plane[idx]) : 0.0f;
-            }
+        for (int u = 0; u < 4; ++u) {
+            const int v = base + u * kCvThreads + int(threadIdx.x);
+            raw[u] = u32x4{0u, 0u, 0u, 0u};
+            at[u] = -1;
+            if (v < nv) {
+                const int bi = v / vpi, idx = e_begin + (v - bi * vpi) * 8;
+                const E *plane = dy + (int64_t(b0 + bi) * cg.Cout + co) * per_img;
+                at[u] = idx;
+                if (idx + 8 <= e_end) {
+                    raw[u] = cv_load_unaligned<u32x4>(reinterpret_cast<const char *>(plane + idx));
+                } else {                                      // beyond the part there may be the end of the tensor
+                    uint16_t h[8];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int idx = base + u * kCvThreads + int(threadIdx.x);
-                if (idx >= e_end) continue;
-                const int oh = idx / cg.OW, ow = idx - oh * cg.OW;
-                tot += f[u];
+                    for (int j = 0; j < 8; ++j) h[j] = idx + j < e_end ? reinterpret_cast<const uint16_t *>(plane)[idx + j] : uint16_t(0);
 #pragma unroll
-                for (int a = 0; a < 3; ++a) {
-                    const int ih = oh * cg.sh - cg.ph + a * cg.dh;
-                    if (a < cg.KH && ih >= 0 && ih < cg.H) {
-#pragma unroll
-                        for (int c = 0; c < 3; ++c) {
-                            const int iw = ow - cg.pw + c;
-                            acc[a][c] += (c < cg.KW && iw >= 0 && iw < cg.W) ? f[u] : 0.0f;
-                        }
-                    }
+                    for (int k = 0; k < 4; ++k) raw[u][k] = uint32_t(h[2 * k]) | (uint32_t(h[2 * k + 1]) << 16);
                 }
             }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = at[u];
+            if (idx < 0) continue;
+            float f[8];
+            Store<E>::unpack(raw[u], f);
+            const int oh = int(fastdiv(uint32_t(idx), div_ow)), ow0 = idx - oh * cg.OW;
+            // elements j < n0 lie in row oh, the others in row oh + 1 (OW >= 8: at most one row end inside a vector)
+            const int n0 = cg.OW - ow0;
+            float cs[2][3] = {{0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f}}, all[2] = {0.0f, 0.0f};
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const bool second = j >= n0;
+                const int ow = second ? j - n0 : ow0 + j;
+                all[0] += second ? 0.0f : f[j];
+                all[1] += second ? f[j] : 0.0f;
+#pragma unroll
+                for (int c = 0; c < 3; ++c) {
+                    const int iw = ow - cg.pw + c;
+                    const float v = (c < cg.KW && iw >= 0 && iw < cg.W) ? f[j] : 0.0f;
+                    cs[0][c] += second ? 0.0f : v;
+                    cs[1][c] += second ? v : 0.0f;
+                }
+            }
+            tot += all[0] + all[1];      // (zeros beyond the part's end)
+#pragma unroll
+            for (int r = 0; r < 2; ++r)
+#pragma unroll
+                for (int a = 0; a < 3; ++a) {
+                    const int ih = (oh + r) * cg.sh - cg.ph + a * cg.dh;
+                    if (a < cg.KH && ih >= 0 && ih < cg.H) {
+#pragma unroll
+                        for (int c = 0; c < 3; ++c) acc[a][c] += cs[r][c];
+                    }
+                }
         }
     }
     float vals[10];
@@ -645,24 +682,26 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_finish(const float *__restr
 
 // The same for few channel pairs and many slices (narrow layers: 64 x 64 channels leave k_conv_finish 16 workgroups
 // whose threads walk 64 slices of nine dependent loads each -- 150 us, six times the matrix-core kernel): a workgroup takes
-// 32 pairs, eight threads share a pair's slices (every eighth each, in order) and the eight sums are added in a fixed
+// 256 / SL pairs, SL threads share a pair's slices (every SL-th each, in order) and their sums are added in a fixed
 // order; the sums of V for the workgroup's output channels are taken once, by its first threads.  ntap <= 9.
+template <int SL>
 __global__ __launch_bounds__(kCvThreads) void k_conv_finish_few(const float *__restrict__ part, const float *__restrict__ V, int splits,
                                                                 int parts, ConvGeom cg, int per, const float *__restrict__ alpha,
                                                                 const float *__restrict__ beta, float centre, float *__restrict__ dW,
                                                                 float *__restrict__ db)
 {
-    __shared__ float sums[8][32][9];
-    __shared__ float vsum[32][10];
-    __shared__ float tile[32 * 9];
-    const int pl = threadIdx.x & 31, sl = threadIdx.x >> 5;
+    constexpr int PW = kCvThreads / SL;                    // pairs per workgroup
+    __shared__ float sums[SL][PW][9];
+    __shared__ float vsum[PW][10];
+    __shared__ float tile[PW * 9];
+    const int pl = threadIdx.x % PW, sl = threadIdx.x / PW;
     const int64_t plane = int64_t(cg.Cout) * cg.Cin;
-    const int64_t first = int64_t(blockIdx.x) * 32, idx = first + pl;
+    const int64_t first = int64_t(blockIdx.x) * PW, idx = first + pl;
     const int ntap = cg.KH * cg.KW;
     const bool live = idx < plane;
     const int co_first = int(first / cg.Cin);              // the workgroup's pairs lie in the output channels from this one on
-    const int64_t last = first + 31 < plane ? first + 31 : plane - 1;
-    const int nco = int(last / cg.Cin) - co_first + 1;     // at most 32
+    const int64_t last = first + PW - 1 < plane ? first + PW - 1 : plane - 1;
+    const int nco = int(last / cg.Cin) - co_first + 1;     // at most PW
     for (int k = threadIdx.x; k < nco * 10; k += kCvThreads) {
         const int c = k / 10, e = k - c * 10;
         float v = 0.0f;
@@ -673,7 +712,7 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_finish_few(const float *__r
 #pragma unroll
     for (int t = 0; t < 9; ++t) s1[t] = 0.0f;
     if (live)
-        for (int sp = sl; sp < splits; sp += 8)
+        for (int sp = sl; sp < splits; sp += SL)
 #pragma unroll
             for (int t = 0; t < 9; ++t)
                 if (t < ntap) s1[t] += part[(int64_t(sp) * ntap + t) * plane + idx];
@@ -689,15 +728,20 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_finish_few(const float *__r
 #pragma unroll
         for (int t = 0; t < 9; ++t)
             if (t < ntap) {
-                const float tot = ((sums[0][pl][t] + sums[1][pl][t]) + (sums[2][pl][t] + sums[3][pl][t])) +
-                                  ((sums[4][pl][t] + sums[5][pl][t]) + (sums[6][pl][t] + sums[7][pl][t]));
+                float q[SL / 4];                           // groups of four in order, then the groups in order
+#pragma unroll
+                for (int k = 0; k < SL / 4; ++k)
+                    q[k] = (sums[4 * k][pl][t] + sums[4 * k + 1][pl][t]) + (sums[4 * k + 2][pl][t] + sums[4 * k + 3][pl][t]);
+                float tot = q[0];
+#pragma unroll
+                for (int k = 1; k < SL / 4; ++k) tot += q[k];
                 const int a = t / cg.KW, c = t - a * cg.KW;
                 tile[pl * ntap + t] = fmaf(sg, tot, off * vs[a * 3 + c]);
             }
         if (db && ci == 0) db[co] = vs[9];
     }
     __syncthreads();
-    const int64_t count = (plane - first < 32 ? plane - first : 32) * ntap;
+    const int64_t count = (plane - first < PW ? plane - first : PW) * ntap;
     for (int k = threadIdx.x; k < count; k += kCvThreads) dW[first * ntap + k] = tile[k];
 }
 
@@ -929,7 +973,8 @@ extern "C" MESA_EXPORT mesa_status mesa_conv2d_dw_q(const int8_t *xq, mesa_conv2
         if (p.rag) { \
             if (p.taps3) MESA_PICK_NKS(E, true, true); else MESA_PICK_NKS(E, false, true); \
             hipLaunchKernelGGL((k_conv_valid_sums_any<E>), dim3(unsigned(cg.Cout) * p.parts), dim3(kCvThreads), 0, s, \
-                               static_cast<const E *>(dy), cg, p.parts, p.imgs_per_part, p.row_blocks, p.rows_per_block, V); \
+                               static_cast<const E *>(dy), cg, p.parts, p.imgs_per_part, p.row_blocks, p.rows_per_block, \
+                               make_fastdiv(uint32_t(cg.OW)), V); \
         } else { \
             if (p.taps3) MESA_PICK_NKS(E, true, false); else MESA_PICK_NKS(E, false, false); \
             hipLaunchKernelGGL((k_conv_valid_sums<E>), dim3(unsigned(cg.Cout) * p.parts), dim3(kCvThreads), 0, s, \
@@ -943,8 +988,11 @@ extern "C" MESA_EXPORT mesa_status mesa_conv2d_dw_q(const int8_t *xq, mesa_conv2
 #undef MESA_PICK_NKS
 #undef MESA_LAUNCH_CV
     if (launch_status() != MESA_OK) return MESA_ERR_LAUNCH;   // the last kernel must not read sums nobody wrote
-    if (plane <= 262144 && p.splits >= 8)
-        hipLaunchKernelGGL(k_conv_finish_few, dim3(unsigned(ceil_div(plane, 32))), dim3(kCvThreads), 0, s, part, V, p.splits, p.parts, cg,
+    if (plane <= 32768 && p.splits >= 32)       // very few pairs: 32 threads per pair, so that the chip has workgroups enough
+        hipLaunchKernelGGL(k_conv_finish_few<32>, dim3(unsigned(ceil_div(plane, 8))), dim3(kCvThreads), 0, s, part, V, p.splits, p.parts, cg,
+                           per, alpha, beta, centre, dW, db);
+    else if (plane <= 262144 && p.splits >= 8)
+        hipLaunchKernelGGL(k_conv_finish_few<8>, dim3(unsigned(ceil_div(plane, 32))), dim3(kCvThreads), 0, s, part, V, p.splits, p.parts, cg,
                            per, alpha, beta, centre, dW, db);
     else
         hipLaunchKernelGGL(k_conv_finish, dim3(unsigned(ceil_div(plane, kCvThreads))), dim3(kCvThreads), 0, s, part, V, p.splits, p.parts,
