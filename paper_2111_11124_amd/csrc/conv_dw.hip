@@ -455,20 +455,30 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_valid_sums(const E *__restr
     for (int a = 0; a < 3; ++a)
 #pragma unroll
         for (int c = 0; c < 3; ++c) acc[a][c] = 0.0f;
-    for (int b = b0; b < b1; ++b) {
-        const E *plane = dy + (int64_t(b) * cg.Cout + co) * cg.OH * cg.OW;
-        // four vectors per thread and round, requested together
-        for (int base = v_begin; base < v_end; base += 4 * kCvThreads) {
+    // the part's vectors, image after image, shared out among the threads (small maps: a part is several images of a few
+    // vectors each); four vectors per thread and round, requested together
+    const int vpi = v_end - v_begin;                          // vectors per image
+    const int nv = (b1 - b0) * vpi;
+    {
+        for (int base = 0; base < nv; base += 4 * kCvThreads) {
             u32x4 raw[4];
+            int at[4];                                        // the vector's index in its plane, -1: none
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int idx = base + u * kCvThreads + int(threadIdx.x);
-                raw[u] = idx < v_end ? *reinterpret_cast<const u32x4 *>(plane + int64_t(idx) * 8) : u32x4{0u, 0u, 0u, 0u};
+                const int v = base + u * kCvThreads + int(threadIdx.x);
+                raw[u] = u32x4{0u, 0u, 0u, 0u};
+                at[u] = -1;
+                if (v < nv) {
+                    const int bi = v / vpi;
+                    at[u] = v_begin + (v - bi * vpi);
+                    const E *plane = dy + (int64_t(b0 + bi) * cg.Cout + co) * cg.OH * cg.OW;
+                    raw[u] = *reinterpret_cast<const u32x4 *>(plane + int64_t(at[u]) * 8);
+                }
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int idx = base + u * kCvThreads + int(threadIdx.x);
-                if (idx >= v_end) continue;
+                const int idx = at[u];
+                if (idx < 0) continue;
                 const int oh = idx / vec_per_row, ow0 = (idx - oh * vec_per_row) * 8;
                 float f[8];
                 Store<E>::unpack(raw[u], f);
