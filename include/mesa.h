@@ -339,9 +339,10 @@ mesa_status mesa_linear_dw_q(const int8_t *xq, int64_t M, int64_t K, int64_t G,
  * A position outside the image contributes nothing (the forward pads with zeros, not with de-quantized codes).
  * dW and db are overwritten.  Fixed summation order.  ws: mesa_conv2d_dw_q_workspace_bytes(cv, dt) bytes.
  * 16-bit tensors with a 3x3 kernel and pad_w = 1, or a 1x1 kernel and pad_w = 0, stride_w = dil_w = 1 (any row stride,
- * dilation and padding) and W, OW >= 8 run on the matrix cores (binary16 / bfloat16 products, binary32 sums,
- * the contracted operand as in mesa_linear_dw_q; widths that are multiples of 8 with aligned vector loads, others with
- * unaligned ones); every other case runs a plain kernel, one workgroup per (output, input) channel pair, summed in binary64.
+ * dilation and padding) run on the matrix cores (binary16 / bfloat16 products, binary32 sums, the contracted operand
+ * as in mesa_linear_dw_q; widths that are multiples of 8 with aligned vector loads, other widths with unaligned ones,
+ * widths below 8 from copies with rows of eight elements in the workspace); every other case runs a plain kernel, one
+ * workgroup per (output, input) channel pair, summed in binary64.
  * Errors: a kernel larger than the padded image, a zero stride or dilation, C_in % G != 0 -> MESA_ERR_INVALID_ARG;
  * C_out*C_in*KH*KW, H*W or OH*OW >= 2^31 -> MESA_ERR_UNSUPPORTED.
  */

@@ -21,9 +21,11 @@
 //
 // This path takes 16-bit tensors, 3x3 kernels with pad_w = 1 and 1x1 kernels with pad_w = 0, stride_w = dil_w = 1 (any
 // row stride, dilation and padding) and widths of at least 8; anything else runs the plain kernel at the end of the file.
-// Widths that are no multiples of 8 (RAG): rows start at any element, so the eight-element vectors are loaded from
+// Widths that are no multiples of 8 (RAG = 1): rows start at any element, so the eight-element vectors are loaded from
 // unaligned addresses, and a row's last, partial vector is loaded from eight elements before the row's end instead (inside
 // the row, hence inside the tensor) and written to LDS element by element where it belongs, zeros behind it.
+// Widths below 8 (RAG = 2): a small kernel first copies both tensors to rows of eight elements; their one vector per row
+// is loaded as it lies and the elements beyond the row's width are cleared on the way to LDS.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -37,8 +39,10 @@ typedef _Float16 cv8h __attribute__((ext_vector_type(8)));
 typedef __bf16 cv8b __attribute__((ext_vector_type(8)));
 typedef float cv16f __attribute__((ext_vector_type(16)));
 
+// W, OW: the row pitches of the tensors the kernels read, in elements; Wv, OWv: the columns of a row that exist (the same,
+// except for maps narrower than eight columns, which the matrix-core path reads from copies with rows of eight)
 struct ConvGeom {
-    int B, Cin, H, W, Cout, KH, KW, sh, sw, ph, pw, dh, dw, OH, OW;
+    int B, Cin, H, W, Cout, KH, KW, sh, sw, ph, pw, dh, dw, OH, OW, Wv, OWv;
 };
 
 constexpr int kCvXcd = 8;
@@ -116,7 +120,7 @@ template <typename V> __device__ __forceinline__ V cv_load_unaligned(const char 
     return v;
 }
 
-template <typename E, bool T3, int NKS, bool RAG>
+template <typename E, bool T3, int NKS, int RAG>
 __global__ __launch_bounds__(kCvThreads, 2) void k_conv_dw(const int8_t *__restrict__ xq, const E *__restrict__ dy, ConvGeom cg,
                                                            int tiles_co, int tiles_ci, int splits, int stages_per_split,
                                                            int nseg, float *__restrict__ part)
@@ -214,7 +218,7 @@ __global__ __launch_bounds__(kCvThreads, 2) void k_conv_dw(const int8_t *__restr
         const int seg0 = seg * C::SEG;
         const char *dbase = reinterpret_cast<const char *>(dy + (int64_t(b) * cg.Cout + co0) * cg.OH * cg.OW);
         const int ddelta = (oh * cg.OW + seg0) * 2;
-        const int dfull = (cg.OW - seg0) >> 3, dr = RAG ? (cg.OW - seg0) & 7 : 0;
+        const int dfull = (cg.OWv - seg0) >> 3, dr = RAG ? (cg.OWv - seg0) & 7 : 0;
         const int dv_end = dfull + (dr ? 1 : 0);                      // vectors of this row that lie inside it, or partly so
         const uint32_t dtail_bit = (dr && dfull < C::NVA) ? 1u << dfull : 0u;
         dshift[S] = 8 - dr;
@@ -225,12 +229,13 @@ __global__ __launch_bounds__(kCvThreads, 2) void k_conv_dw(const int8_t *__restr
 #pragma unroll
         for (int n = 0; n < C::ND; ++n) {
             const bool in = (dbits[n] & dmask) == dbits[n];
-            if (RAG) {
+            if (RAG == 1) {
                 const bool tail = in && dbits[n] == dtail_bit;
                 dreg[S][n] = cv_load_unaligned<u32x4>(dbase + uint32_t(in ? doff[n] + ddelta - (tail ? (8 - dr) * 2 : 0) : 0));
                 dtail[S] |= tail ? 1u << n : 0u;
             } else {
                 dreg[S][n] = *reinterpret_cast<const u32x4 *>(dbase + uint32_t(in ? doff[n] + ddelta : 0));
+                if (RAG == 2) dtail[S] |= (in && dbits[n] == dtail_bit) ? 1u << n : 0u;
             }
             dkeep[S] |= in ? 1u << n : 0u;
         }
@@ -244,7 +249,7 @@ __global__ __launch_bounds__(kCvThreads, 2) void k_conv_dw(const int8_t *__restr
             smask |= (ih >= 0 && ih < cg.H) ? 1u << (24 + a) : 0u;
         }
         const int v_lo = (T3 && seg0 == 0) ? 1 : 0;                   // the left halo of the first segment is padding
-        const int xcols = cg.W - seg0 + (T3 ? 8 : 0);                 // from LDS element 0 of the row to the image's last column
+        const int xcols = cg.Wv - seg0 + (T3 ? 8 : 0);                // from LDS element 0 of the row to the image's last column
         const int xfull = xcols >> 3, xr = RAG ? xcols & 7 : 0;
         const int v_end = min(xfull + (xr ? 1 : 0), 24);
         const uint32_t xtail_bit = (xr && xfull < C::NVX) ? 1u << xfull : 0u;
@@ -255,12 +260,13 @@ __global__ __launch_bounds__(kCvThreads, 2) void k_conv_dw(const int8_t *__restr
 #pragma unroll
         for (int n = 0; n < C::NX; ++n) {
             const bool in = (xbits[n] & smask) == xbits[n];
-            if (RAG) {
+            if (RAG == 1) {
                 const bool tail = in && (xbits[n] & 0x00FFFFFFu) == xtail_bit;
                 xreg[S][n] = cv_load_unaligned<u32x2>(xbase + uint32_t(in ? xoff[n] + xdelta - (tail ? 8 - xr : 0) : 0));
                 xtail[S] |= tail ? 1u << n : 0u;
             } else {
                 xreg[S][n] = *reinterpret_cast<const u32x2 *>(xbase + uint32_t(in ? xoff[n] + xdelta : 0));
+                if (RAG == 2) xtail[S] |= (in && (xbits[n] & 0x00FFFFFFu) == xtail_bit) ? 1u << n : 0u;
             }
             xkeep[S] |= in ? 1u << n : 0u;
         }
@@ -273,10 +279,18 @@ __global__ __launch_bounds__(kCvThreads, 2) void k_conv_dw(const int8_t *__restr
         for (int i = 1; i < 8; ++i)
             if (i >= shift) *reinterpret_cast<uint16_t *>(at + (i - shift) * 2) = uint16_t(w[i >> 1] >> ((i & 1) * 16));
     };
+    // a partial vector that lies where it belongs (rows of eight): its first 8 - shift elements, zeros behind them
+    auto store_head = [&](unsigned char *at, u32x4 w, int shift) __attribute__((always_inline)) {
+        const int r = 8 - shift;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) w[k] &= (2 * k < r ? 0x0000FFFFu : 0u) | (2 * k + 1 < r ? 0xFFFF0000u : 0u);
+        *reinterpret_cast<u32x4 *>(at) = w;
+    };
     auto store_d = [&](int S, int n, unsigned char *buf) __attribute__((always_inline)) {
         const uint32_t k = 0u - ((dkeep[S] >> n) & 1u);
         const u32x4 w = u32x4{dreg[S][n][0] & k, dreg[S][n][1] & k, dreg[S][n][2] & k, dreg[S][n][3] & k};
-        if (RAG && ((dtail[S] >> n) & 1u)) store_tail(buf + dlds[n], w, dshift[S]);
+        if (RAG == 1 && ((dtail[S] >> n) & 1u)) store_tail(buf + dlds[n], w, dshift[S]);
+        else if (RAG == 2 && ((dtail[S] >> n) & 1u)) store_head(buf + dlds[n], w, dshift[S]);
         else *reinterpret_cast<u32x4 *>(buf + dlds[n]) = w;
     };
     auto store_x = [&](int S, int n, unsigned char *buf) __attribute__((always_inline)) {
@@ -285,7 +299,8 @@ __global__ __launch_bounds__(kCvThreads, 2) void k_conv_dw(const int8_t *__restr
         CvElem<E>::convert(xreg[S][n][1], hi);
         const uint32_t k = 0u - ((xkeep[S] >> n) & 1u);
         const u32x4 w = u32x4{lo[0] & k, lo[1] & k, hi[0] & k, hi[1] & k};
-        if (RAG && ((xtail[S] >> n) & 1u)) store_tail(buf + xlds[n], w, xshift[S]);
+        if (RAG == 1 && ((xtail[S] >> n) & 1u)) store_tail(buf + xlds[n], w, xshift[S]);
+        else if (RAG == 2 && ((xtail[S] >> n) & 1u)) store_head(buf + xlds[n], w, xshift[S]);
         else *reinterpret_cast<u32x4 *>(buf + xlds[n]) = w;
     };
 
@@ -485,7 +500,7 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_valid_sums(const E *__restr
                 float cs[3] = {0.0f, 0.0f, 0.0f}, all = 0.0f;
 #pragma unroll
                 for (int j = 0; j < 8; ++j) all += f[j];
-                if (ow0 - cg.pw >= 0 && ow0 + 7 - cg.pw + 2 < cg.W) {   // every tap of every element lies inside: all but a row's ends
+                if (ow0 - cg.pw >= 0 && ow0 + 7 - cg.pw + 2 < cg.Wv) {   // every tap of every element lies inside: all but a row's ends
 #pragma unroll
                     for (int c = 0; c < 3; ++c) cs[c] = c < cg.KW ? all : 0.0f;
                 } else {
@@ -494,7 +509,7 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_valid_sums(const E *__restr
 #pragma unroll
                         for (int c = 0; c < 3; ++c) {
                             const int iw = ow0 + j - cg.pw + c;
-                            cs[c] += (c < cg.KW && iw >= 0 && iw < cg.W) ? f[j] : 0.0f;
+                            cs[c] += (c < cg.KW && iw >= 0 && iw < cg.Wv) ? f[j] : 0.0f;
                         }
                 }
                 tot += all;
@@ -597,7 +612,7 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_valid_sums_any(const E *__r
 #pragma unroll
                 for (int c = 0; c < 3; ++c) {
                     const int iw = ow - cg.pw + c;
-                    const float v = (c < cg.KW && iw >= 0 && iw < cg.W) ? f[j] : 0.0f;
+                    const float v = (c < cg.KW && iw >= 0 && iw < cg.Wv) ? f[j] : 0.0f;
                     cs[0][c] += second ? 0.0f : v;
                     cs[1][c] += second ? v : 0.0f;
                 }
@@ -755,6 +770,18 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_finish_few(const float *__r
     for (int k = threadIdx.x; k < count; k += kCvThreads) dW[first * ntap + k] = tile[k];
 }
 
+// Rows of w < 8 elements copied to rows of eight (zeros behind them): one thread per row.  V: a vector of eight elements.
+template <typename Elem, typename V>
+__global__ __launch_bounds__(kCvThreads) void k_conv_pad_rows(const Elem *__restrict__ in, Elem *__restrict__ out, int64_t rows, int w)
+{
+    const int64_t row = int64_t(blockIdx.x) * kCvThreads + threadIdx.x;
+    if (row >= rows) return;
+    union { Elem e[8]; V v; } u;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) u.e[j] = j < w ? in[row * w + j] : Elem(0);
+    *reinterpret_cast<V *>(out + row * 8) = u.v;
+}
+
 // The plain path: any stride, dilation, kernel size and storage type.  One workgroup per (output channel, input channel):
 // its threads share out the output positions (consecutive threads, consecutive columns of dy), every thread keeps the
 // kernel taps' sums -- nine taps at a time -- in binary64 at the binary32 x_hat, and the threads' sums are added in a
@@ -826,7 +853,7 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_dw_plain(const int8_t *__re
 }
 
 struct CvPlan {
-    bool fast, taps3, rag;
+    bool fast, taps3, rag, pad;     // rag: widths that are no multiples of 8; pad: below 8, read from copies with rows of eight
     int nks, tiles_co, tiles_ci, splits, stages_per_split, nseg, grid, parts, imgs_per_part, row_blocks, rows_per_block;
 };
 
@@ -836,16 +863,18 @@ static CvPlan cv_plan(const ConvGeom &cg, mesa_dtype dt)
     const bool k3 = cg.KH == 3 && cg.KW == 3 && cg.pw == 1, k1 = cg.KH == 1 && cg.KW == 1 && cg.pw == 0;
     // per-lane byte offsets inside a tile of 128 channels, plus the stage's own offset, stay below 2^31
     const int64_t lim = int64_t(1) << 22;
-    p.fast = dt != MESA_F32 && cg.sw == 1 && cg.dw == 1 && (k3 || k1) && cg.W >= 8 && cg.OW >= 8 &&
-             (int64_t(cg.H) + 2 * cg.ph + 3 * int64_t(cg.dh)) * cg.W <= lim && int64_t(cg.OH) * cg.OW <= lim;
+    p.pad = cg.W < 8 || cg.OW < 8;
+    const int W = p.pad ? 8 : cg.W, OW = p.pad ? 8 : cg.OW;     // the row pitches the kernels see
+    p.fast = dt != MESA_F32 && cg.sw == 1 && cg.dw == 1 && (k3 || k1) &&
+             (int64_t(cg.H) + 2 * cg.ph + 3 * int64_t(cg.dh)) * W <= lim && int64_t(cg.OH) * OW <= lim;
     if (!p.fast) return p;
     p.taps3 = k3;
-    p.rag = cg.W % 8 != 0 || cg.OW % 8 != 0;
-    p.nks = cg.OW <= 16 ? 1 : cg.OW <= 32 ? 2 : cg.OW <= 64 ? 4 : 8;
+    p.rag = !p.pad && (cg.W % 8 != 0 || cg.OW % 8 != 0);
+    p.nks = OW <= 16 ? 1 : OW <= 32 ? 2 : OW <= 64 ? 4 : 8;
     const int cot = 128, cit = p.taps3 ? 64 : 128;
     p.tiles_co = int(ceil_div(cg.Cout, cot));
     p.tiles_ci = int(ceil_div(cg.Cin, cit));
-    p.nseg = int(ceil_div(cg.OW, 16 * p.nks));
+    p.nseg = int(ceil_div(OW, 16 * p.nks));
     const int64_t nstages = int64_t(cg.B) * cg.OH * p.nseg;
     const int64_t tiles = int64_t(p.tiles_co) * p.tiles_ci * (p.taps3 ? 3 : 1);
     // two workgroups per CU: as many slices as fill one such round of the chip without starting a second (a round and
@@ -870,7 +899,7 @@ static CvPlan cv_plan(const ConvGeom &cg, mesa_dtype dt)
     if (img_parts < want) {
         rb = ceil_div(want, img_parts);
         if (rb > ceil_div(cg.OH, 8)) rb = ceil_div(cg.OH, 8);
-        const int64_t by_size = int64_t(cg.OH) * cg.OW / 8192;    // a block keeps every thread at least four vectors
+        const int64_t by_size = int64_t(cg.OH) * OW / 8192;       // a block keeps every thread at least four vectors
         if (rb > by_size) rb = by_size < 1 ? 1 : by_size;
     }
     p.rows_per_block = int(ceil_div(cg.OH, rb));
@@ -894,7 +923,7 @@ static bool cv_geom(const mesa_conv2d &cv, ConvGeom &cg)
     if (span_h < 0 || span_w < 0) return false;
     cg = ConvGeom{int(cv.B), int(cv.C_in), int(cv.H), int(cv.W), int(cv.C_out), int(cv.KH), int(cv.KW), int(cv.stride_h),
                   int(cv.stride_w), int(cv.pad_h), int(cv.pad_w), int(cv.dil_h), int(cv.dil_w), int(span_h / cv.stride_h + 1),
-                  int(span_w / cv.stride_w + 1)};
+                  int(span_w / cv.stride_w + 1), int(cv.W), int(span_w / cv.stride_w + 1)};
     return true;
 }
 
@@ -910,12 +939,17 @@ static bool cv_supported(const ConvGeom &cg)
     return true;
 }
 
+static size_t cv_pad_x_bytes(const ConvGeom &cg) { return (size_t(cg.B) * cg.Cin * cg.H * 8 + 255) & ~size_t(255); }
+static size_t cv_pad_d_bytes(const ConvGeom &cg) { return (size_t(cg.B) * cg.Cout * cg.OH * 8 * 2 + 255) & ~size_t(255); }
+
 static size_t cv_ws_bytes(const ConvGeom &cg, const CvPlan &p)
 {
     if (!p.fast) return 0;
     const size_t part = size_t(p.splits) * cg.KH * cg.KW * cg.Cout * cg.Cin * sizeof(float);
     const size_t v = size_t(p.parts) * cg.Cout * 10 * sizeof(float);
-    return part + ((v + 255) & ~size_t(255));
+    size_t n = part + ((v + 255) & ~size_t(255));
+    if (p.pad) n = ((n + 255) & ~size_t(255)) + cv_pad_x_bytes(cg) + cv_pad_d_bytes(cg);   // the copies with rows of eight: codes, then dy
+    return n;
 }
 
 }  // namespace mesa
@@ -962,13 +996,33 @@ extern "C" MESA_EXPORT mesa_status mesa_conv2d_dw_q(const int8_t *xq, mesa_conv2
     float *part = static_cast<float *>(ws);
     const size_t part_bytes = size_t(p.splits) * cg.KH * cg.KW * cg.Cout * cg.Cin * sizeof(float);
     float *V = reinterpret_cast<float *>(static_cast<char *>(ws) + part_bytes);
+    // what the kernels read: the caller's tensors, or -- maps narrower than eight columns -- copies with rows of eight
+    const int8_t *kx = xq;
+    const void *kd = dy;
+    ConvGeom ck = cg;
+    if (p.pad) {
+        const size_t vbytes = (size_t(p.parts) * cg.Cout * 10 * sizeof(float) + 255) & ~size_t(255);
+        char *copies = static_cast<char *>(ws) + ((part_bytes + vbytes + 255) & ~size_t(255));
+        int8_t *xp = reinterpret_cast<int8_t *>(copies);
+        uint16_t *dp = reinterpret_cast<uint16_t *>(copies + cv_pad_x_bytes(cg));
+        const int64_t xrows = int64_t(cg.B) * cg.Cin * cg.H, drows = int64_t(cg.B) * cg.Cout * cg.OH;
+        hipLaunchKernelGGL((k_conv_pad_rows<int8_t, u32x2>), dim3(unsigned(ceil_div(xrows, kCvThreads))), dim3(kCvThreads), 0, s, xq, xp,
+                           xrows, cg.W);
+        hipLaunchKernelGGL((k_conv_pad_rows<uint16_t, u32x4>), dim3(unsigned(ceil_div(drows, kCvThreads))), dim3(kCvThreads), 0, s,
+                           static_cast<const uint16_t *>(dy), dp, drows, cg.OW);
+        if (launch_status() != MESA_OK) return MESA_ERR_LAUNCH;
+        kx = xp;
+        kd = dp;
+        ck.W = 8;
+        ck.OW = 8;
+    }
 #define MESA_LAUNCH_CV(E, T3, NKS, RAG) \
     do { \
         auto kern = k_conv_dw<E, T3, NKS, RAG>; \
         constexpr int lds = CvCfg<T3, NKS>::LDS; \
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) \
             return MESA_ERR_LAUNCH; \
-        hipLaunchKernelGGL(kern, dim3(p.grid), dim3(kCvThreads), lds, s, xq, static_cast<const E *>(dy), cg, p.tiles_co, p.tiles_ci, \
+        hipLaunchKernelGGL(kern, dim3(p.grid), dim3(kCvThreads), lds, s, kx, static_cast<const E *>(kd), ck, p.tiles_co, p.tiles_ci, \
                            p.splits, p.stages_per_split, p.nseg, part); \
     } while (0)
 #define MESA_PICK_NKS(E, T3, RAG) \
@@ -980,13 +1034,17 @@ extern "C" MESA_EXPORT mesa_status mesa_conv2d_dw_q(const int8_t *xq, mesa_conv2
     } while (0)
 #define MESA_PICK_CV(E) \
     do { \
-        if (p.rag) { \
-            if (p.taps3) MESA_PICK_NKS(E, true, true); else MESA_PICK_NKS(E, false, true); \
+        if (p.pad) { \
+            if (p.taps3) MESA_LAUNCH_CV(E, true, 1, 2); else MESA_LAUNCH_CV(E, false, 1, 2); \
+            hipLaunchKernelGGL((k_conv_valid_sums<E>), dim3(unsigned(cg.Cout) * p.parts), dim3(kCvThreads), 0, s, \
+                               static_cast<const E *>(kd), ck, p.parts, p.imgs_per_part, p.row_blocks, p.rows_per_block, V); \
+        } else if (p.rag) { \
+            if (p.taps3) MESA_PICK_NKS(E, true, 1); else MESA_PICK_NKS(E, false, 1); \
             hipLaunchKernelGGL((k_conv_valid_sums_any<E>), dim3(unsigned(cg.Cout) * p.parts), dim3(kCvThreads), 0, s, \
                                static_cast<const E *>(dy), cg, p.parts, p.imgs_per_part, p.row_blocks, p.rows_per_block, \
                                make_fastdiv(uint32_t(cg.OW)), V); \
         } else { \
-            if (p.taps3) MESA_PICK_NKS(E, true, false); else MESA_PICK_NKS(E, false, false); \
+            if (p.taps3) MESA_PICK_NKS(E, true, 0); else MESA_PICK_NKS(E, false, 0); \
             hipLaunchKernelGGL((k_conv_valid_sums<E>), dim3(unsigned(cg.Cout) * p.parts), dim3(kCvThreads), 0, s, \
                                static_cast<const E *>(dy), cg, p.parts, p.imgs_per_part, p.row_blocks, p.rows_per_block, V); \
         } \

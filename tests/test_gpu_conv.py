@@ -81,6 +81,13 @@ FAST = [
     (5, 130, 8, 8, 70, 3, 3, (1, 1), (1, 1), (1, 1), 2),
     (3, 64, 9, 13, 64, 3, 3, (2, 1), (2, 1), (2, 1), 4),
     (3, 136, 11, 11, 200, 1, 1, (1, 1), (0, 0), (1, 1), 1),
+    # maps narrower than eight columns: read from copies with rows of eight
+    (4, 72, 7, 7, 136, 3, 3, (1, 1), (1, 1), (1, 1), 3),
+    (3, 130, 7, 7, 70, 1, 1, (1, 1), (0, 0), (1, 1), 2),
+    (2, 24, 5, 4, 10, 3, 3, (1, 1), (1, 1), (1, 1), 1),
+    (2, 8, 3, 1, 4, 3, 3, (1, 1), (1, 1), (1, 1), 1),
+    (2, 8, 9, 7, 5, 3, 3, (2, 1), (1, 1), (1, 1), 2),
+    (5, 64, 4, 6, 64, 3, 3, (1, 1), (2, 1), (2, 1), 4),
 ]
 
 
@@ -97,7 +104,7 @@ PLAIN = [
     (1, 4, 11, 10, 2, 3, 3, (1, 2), (2, 2), (2, 2), 1),          # column stride and dilation
     (2, 3, 8, 8, 2, 4, 4, (4, 4), (0, 0), (1, 1), 3),            # patch embedding: stride = kernel
     (1, 8, 14, 14, 6, 5, 5, (1, 1), (2, 2), (1, 1), 2),          # 5x5
-    (2, 8, 9, 7, 5, 3, 3, (1, 1), (1, 1), (1, 1), 2),            # a width below eight
+    (2, 8, 9, 7, 5, 5, 5, (1, 1), (2, 2), (1, 1), 2),            # 5x5 on a map narrower than a vector
     (2, 48, 8, 16, 40, 3, 1, (1, 1), (1, 0), (1, 1), 3),         # 3x1 kernel
     (2, 48, 8, 16, 40, 1, 3, (1, 1), (0, 1), (1, 1), 3),         # 1x3 kernel
     (2, 16, 8, 24, 16, 3, 3, (1, 1), (1, 5), (1, 1), 2),         # 3x3 with wide column padding
@@ -113,7 +120,8 @@ def test_conv_dw_plain_path(M, case, dtype):
     assert eW <= 1e-6 and eb <= 1e-6, (eW, eb)
 
 
-@pytest.mark.parametrize("case", [FAST[0], FAST[1], FAST[10], FAST[12], FAST[14], FAST[16], FAST[17], FAST[20], FAST[21], FAST[24]],
+@pytest.mark.parametrize("case", [FAST[0], FAST[1], FAST[10], FAST[12], FAST[14], FAST[16], FAST[17], FAST[20], FAST[21], FAST[24], FAST[26], FAST[27],
+                                  FAST[29]],
                          ids=lambda c: "x".join(str(v) for v in c[:7]))
 def test_conv_dw_reads_nothing_it_uses_from_outside_the_tensors(M, case):
     """Both inputs are the middle of larger buffers whose frames hold NaN (dy) and the extreme code (x): a vector that

@@ -425,8 +425,9 @@ def test_layer_forwards_full_size(M, number):
 
 
 @pytest.mark.parametrize("shape", [(2, 512, 128, 128, 512, 3, 3, 1), (2, 2048, 128, 128, 512, 1, 1, 0),
-                                   (16, 128, 28, 28, 128, 3, 3, 1), (16, 256, 14, 14, 1024, 1, 1, 0), (4, 128, 150, 150, 128, 3, 3, 1)],
-                         ids=["3x3", "1x1", "3x3-28", "1x1-14", "3x3-150"])
+                                   (16, 128, 28, 28, 128, 3, 3, 1), (16, 256, 14, 14, 1024, 1, 1, 0), (4, 128, 150, 150, 128, 3, 3, 1),
+                                   (16, 512, 7, 7, 512, 3, 3, 1)],
+                         ids=["3x3", "1x1", "3x3-28", "1x1-14", "3x3-150", "3x3-7"])
 def test_convolution_weight_gradient_full_size_sampled(M, shape):
     """mesa_conv2d_dw_q at the segmentation-head shapes bench.py times, and at an image classifier's 28- and 14-column
     maps and a 150-column map (widths that are no multiples of 8: the other staging): 400 sampled entries of dW against

@@ -244,7 +244,7 @@ def test_linear_dw_keeps_inside_its_outputs(M, dtype):
 
 def _conv_cases(seed, count):
     """Seeded convolution geometries that take the matrix-core path: 3x3 with one column of padding or 1x1 with none,
-    unit column stride and dilation, widths of at least 8 (a third of them no multiples of 8); everything else drawn freely (ragged channel
+    unit column stride and dilation, any width (a third of them no multiples of 8, some below 8); everything else drawn freely (ragged channel
     tiles, one to three row segments, row strides, dilations and paddings, batch sizes that leave ragged slices)."""
     rnd = random.Random(seed)
     out = []
@@ -255,6 +255,8 @@ def _conv_cases(seed, count):
         Cin = G * rnd.randint(2, 40)
         Cout = rnd.randint(3, 150)
         W = 8 * rnd.choice((1, 2, 3, 4, 5, 8, 9, 16, 17, 33)) + rnd.choice((0, 0, rnd.randint(1, 7)))
+        if rnd.random() < 0.15:
+            W = rnd.randint(1, 7)
         sh, dh, ph = rnd.choice((1, 1, 2, 3)), rnd.choice((1, 1, 2, 3)), rnd.randint(0, 3)
         H = rnd.randint(max(1, dh * (k - 1) + 1 - 2 * ph), 22)
         if B * Cin * Cout * H * W > 3.0e8:           # keeps the oracle's binary64 loops to a second or two
