@@ -570,7 +570,10 @@ def test_gelu_layer_forward_in_one_pass(M, layout, dtype):
                                            (2, 2, 9, 3), (1, 3, 11, 57), (2, 1, 13, 104), (1, 2, 30, 105), (3, 1, 5, 200), (1, 2, 17, 201),
                                            (2, 2, 6, 256), (1, 2, 10, 257), (40, 3, 61, 61), (1, 1, 3, 4096),
                                            (1, 2, 5, 1025), (1, 1, 3, 4097), (2, 1, 2, 9001), (1, 1, 2, 8200), (1, 1100, 2, 300),
-                                           (2, 2, 9, 57), (1, 3, 8, 63), (2, 1, 5, 105), (1, 2, 6, 128), (1, 1, 7, 120)])
+                                           (2, 2, 9, 57), (1, 3, 8, 63), (2, 1, 5, 105), (1, 2, 6, 128), (1, 1, 7, 120),
+                                           # more long rows of 8k elements, and tiles that change heads on the way
+                                           (1, 2, 5, 264), (2, 2, 4, 512), (1, 2, 4, 520), (1, 2, 6, 768), (1, 1, 3, 1024), (1, 2, 2, 1032),
+                                           (1, 1, 3, 1536), (1, 1, 3, 2048), (1, 1, 2, 2056), (2, 3, 4400, 264), (1, 2, 9000, 520)])
 def test_softmax_backward_every_row_shape(M, B, H, rows, cols, dtype):
     """Softmax backward at head-wise codes over every lane-group shape of the short-row kernel (and both of its
     variants), rows shorter than a vector, ragged tiles, tiles that straddle heads, and the long-row kernel; the plain
