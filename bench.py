@@ -214,10 +214,11 @@ class Path:
             out += self.backward_calls(layer, bwd)
         return out
 
-    def step(self, timed_call=None, events=None, single_pass=False, every_call=None):
+    def step(self, timed_call=None, events=None, single_pass=False, every_call=None, event_pool=None):
+        # event_pool: events created beforehand (creating one costs the host far more than a launch)
         for name, fn in self.calls(single_pass):
             if every_call is not None or name == timed_call:
-                e0, e1 = self.m.Event(), self.m.Event()
+                e0, e1 = (event_pool.pop(), event_pool.pop()) if event_pool else (self.m.Event(), self.m.Event())
                 e0.record()
                 fn()
                 e1.record()
@@ -745,12 +746,14 @@ def main():
     # timed region: exactly `steps` steps between two synchronisations; an event pair around every step and around
     # every launch of the dominant HBM-bound call
     events, step_events = [], []
+    # every event of the timed region exists before it starts, so that a short step is not timed at the host's pace
+    pool = [m.Event() for _ in range(steps * (2 + 2 * len(per_call[dominant]) // prof_steps) + 16)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
-        s0, s1 = m.Event(), m.Event()
+        s0, s1 = pool.pop(), pool.pop()
         s0.record()
-        path.step(timed_call=dominant, events=events)
+        path.step(timed_call=dominant, events=events, event_pool=pool)
         s1.record()
         step_events.append((s0, s1))
     torch.cuda.synchronize()
