@@ -867,6 +867,8 @@ static CvPlan cv_plan(const ConvGeom &cg, mesa_dtype dt)
     const int W = p.pad ? 8 : cg.W, OW = p.pad ? 8 : cg.OW;     // the row pitches the kernels see
     p.fast = dt != MESA_F32 && cg.sw == 1 && cg.dw == 1 && (k3 || k1) &&
              (int64_t(cg.H) + 2 * cg.ph + 3 * int64_t(cg.dh)) * W <= lim && int64_t(cg.OH) * OW <= lim;
+    // (the copies' rows are shared out one per thread of a 32-bit grid)
+    if (p.pad && (int64_t(cg.B) * cg.Cin * cg.H >= (int64_t(1) << 31) || int64_t(cg.B) * cg.Cout * cg.OH >= (int64_t(1) << 31))) p.fast = false;
     if (!p.fast) return p;
     p.taps3 = k3;
     p.rag = !p.pad && (cg.W % 8 != 0 || cg.OW % 8 != 0);
