@@ -530,13 +530,19 @@ def four_bit_leg(m, spec, steps):
 CONV_SHAPES = [  # B, C_in, H, W, C_out, KH, KW, pad: the 3x3 and 1x1 convolutions of a segmentation head on 128 x 128 feature maps
     ("3x3 512->512", (2, 512, 128, 128, 512, 3, 3, 1)),
     ("1x1 2048->512", (2, 2048, 128, 128, 512, 1, 1, 0)),
+    # the 3x3 convolutions of an image classifier's four stages, batch 16: maps of 56, 28, 14 and 7 columns (widths that
+    # are a multiple of eight, no multiple of eight, and below eight: the kernel's three ways of staging a row)
+    ("3x3 64->64 @56", (16, 64, 56, 56, 64, 3, 3, 1)),
+    ("3x3 128->128 @28", (16, 128, 28, 28, 128, 3, 3, 1)),
+    ("3x3 256->256 @14", (16, 256, 14, 14, 256, 3, 3, 1)),
+    ("3x3 512->512 @7", (16, 512, 7, 7, 512, 3, 3, 1)),
 ]
 
 
 def conv_dw_leg(m, spec, steps):
     """Outside the headline figure: the weight gradient of a convolution at group-wise codes (Sec. 3.3), on the shapes of
-    a segmentation head (batch 2 per GPU, 128 x 128 feature maps), with the vendor library's convolution weight gradient
-    on the de-quantized 16-bit input beside it."""
+    a segmentation head (batch 2 per GPU, 128 x 128 feature maps) and of an image classifier's stages (batch 16), with the
+    vendor library's convolution weight gradient on the de-quantized 16-bit input beside it."""
     dev = "cuda"
     out = {}
     dtc = dtype_code(m, spec.dtype)
