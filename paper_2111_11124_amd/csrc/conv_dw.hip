@@ -676,10 +676,32 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_finish(const float *__restr
             float s1[9];
 #pragma unroll
             for (int t = 0; t < 9; ++t) s1[t] = 0.0f;
-            for (int sp = 0; sp < splits; ++sp)
+            // 3x3: four slices' loads are requested together (the sums are still added slice by slice, in order; 23 -> 17.5 us
+            // at 512 x 512 channels and five slices).  A single tap gained nothing from it.
+            auto add_slices = [&](auto taps) {
+                constexpr int NT = decltype(taps)::value;
+                int sp = 0;
+                for (; sp + 4 <= splits; sp += 4) {
+                    float v[4][NT];
 #pragma unroll
-                for (int t = 0; t < 9; ++t)
-                    if (t < ntap) s1[t] += part[(int64_t(sp) * ntap + t) * plane + idx];
+                    for (int k = 0; k < 4; ++k)
+#pragma unroll
+                        for (int t = 0; t < NT; ++t) v[k][t] = part[(int64_t(sp + k) * NT + t) * plane + idx];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)
+#pragma unroll
+                        for (int t = 0; t < NT; ++t) s1[t] += v[k][t];
+                }
+                for (; sp < splits; ++sp)
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) s1[t] += part[(int64_t(sp) * NT + t) * plane + idx];
+            };
+            if (ntap == 9) add_slices(std::integral_constant<int, 9>());
+            else
+                for (int sp = 0; sp < splits; ++sp)
+#pragma unroll
+                    for (int t = 0; t < 9; ++t)
+                        if (t < ntap) s1[t] += part[(int64_t(sp) * ntap + t) * plane + idx];
 #pragma unroll
             for (int t = 0; t < 9; ++t)
                 if (t < ntap) {
