@@ -676,19 +676,20 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_finish(const float *__restr
             float s1[9];
 #pragma unroll
             for (int t = 0; t < 9; ++t) s1[t] = 0.0f;
-            // 3x3: four slices' loads are requested together (the sums are still added slice by slice, in order; 23 -> 17.5 us
-            // at 512 x 512 channels and five slices).  A single tap gained nothing from it.
-            auto add_slices = [&](auto taps) {
-                constexpr int NT = decltype(taps)::value;
+            // the loads of several slices are requested together (the sums are still added slice by slice, in order): four
+            // slices of nine taps (23 -> 17.5 us at 512 x 512 channels and five slices), eight slices of one tap; the two tap
+            // counts of the matrix-core path as compile-time constants
+            auto add_slices = [&](auto taps, auto batch) {
+                constexpr int NT = decltype(taps)::value, NB = decltype(batch)::value;
                 int sp = 0;
-                for (; sp + 4 <= splits; sp += 4) {
-                    float v[4][NT];
+                for (; sp + NB <= splits; sp += NB) {
+                    float v[NB][NT];
 #pragma unroll
-                    for (int k = 0; k < 4; ++k)
+                    for (int k = 0; k < NB; ++k)
 #pragma unroll
                         for (int t = 0; t < NT; ++t) v[k][t] = part[(int64_t(sp + k) * NT + t) * plane + idx];
 #pragma unroll
-                    for (int k = 0; k < 4; ++k)
+                    for (int k = 0; k < NB; ++k)
 #pragma unroll
                         for (int t = 0; t < NT; ++t) s1[t] += v[k][t];
                 }
@@ -696,7 +697,8 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_finish(const float *__restr
 #pragma unroll
                     for (int t = 0; t < NT; ++t) s1[t] += part[(int64_t(sp) * NT + t) * plane + idx];
             };
-            if (ntap == 9) add_slices(std::integral_constant<int, 9>());
+            if (ntap == 9) add_slices(std::integral_constant<int, 9>(), std::integral_constant<int, 4>());
+            else if (ntap == 1) add_slices(std::integral_constant<int, 1>(), std::integral_constant<int, 8>());
             else
                 for (int sp = 0; sp < splits; ++sp)
 #pragma unroll
