@@ -731,15 +731,16 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_finish(const float *__restr
 
 // The same for few channel pairs and many slices (narrow layers: 64 x 64 channels leave k_conv_finish 16 workgroups
 // whose threads walk 64 slices of nine dependent loads each -- 150 us, six times the matrix-core kernel): a workgroup takes
-// 256 / SL pairs, SL threads share a pair's slices (every SL-th each, in order) and their sums are added in a fixed
-// order; the sums of V for the workgroup's output channels are taken once, by its first threads.  ntap <= 9.
+// PW = 32 pairs (consecutive: a wave's loads of a slice are 128 contiguous bytes), SL threads share a pair's slices (every
+// SL-th each, in order) and their sums are added in a fixed order; the sums of V for the workgroup's output channels are
+// taken once, by its first threads.  SL * 32 threads.  ntap <= 9.
 template <int SL>
-__global__ __launch_bounds__(kCvThreads) void k_conv_finish_few(const float *__restrict__ part, const float *__restrict__ V, int splits,
+__global__ __launch_bounds__(SL * 32) void k_conv_finish_few(const float *__restrict__ part, const float *__restrict__ V, int splits,
                                                                 int parts, ConvGeom cg, int per, const float *__restrict__ alpha,
                                                                 const float *__restrict__ beta, float centre, float *__restrict__ dW,
                                                                 float *__restrict__ db)
 {
-    constexpr int PW = kCvThreads / SL;                    // pairs per workgroup
+    constexpr int PW = 32, NT = SL * PW;                   // pairs per workgroup, threads
     __shared__ float sums[SL][PW][9];
     __shared__ float vsum[PW][10];
     __shared__ float tile[PW * 9];
@@ -751,7 +752,7 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_finish_few(const float *__r
     const int co_first = int(first / cg.Cin);              // the workgroup's pairs lie in the output channels from this one on
     const int64_t last = first + PW - 1 < plane ? first + PW - 1 : plane - 1;
     const int nco = int(last / cg.Cin) - co_first + 1;     // at most PW
-    for (int k = threadIdx.x; k < nco * 10; k += kCvThreads) {
+    for (int k = threadIdx.x; k < nco * 10; k += NT) {
         const int c = k / 10, e = k - c * 10;
         float v = 0.0f;
         for (int pt = 0; pt < parts; ++pt) v += V[(int64_t(pt) * cg.Cout + co_first + c) * 10 + e];
@@ -791,7 +792,7 @@ __global__ __launch_bounds__(kCvThreads) void k_conv_finish_few(const float *__r
     }
     __syncthreads();
     const int64_t count = (plane - first < PW ? plane - first : PW) * ntap;
-    for (int k = threadIdx.x; k < count; k += kCvThreads) dW[first * ntap + k] = tile[k];
+    for (int k = threadIdx.x; k < count; k += NT) dW[first * ntap + k] = tile[k];
 }
 
 // Rows of w < 8 elements copied to rows of eight (zeros behind them): one thread per row.  V: a vector of eight elements.
@@ -1083,7 +1084,7 @@ extern "C" MESA_EXPORT mesa_status mesa_conv2d_dw_q(const int8_t *xq, mesa_conv2
 #undef MESA_LAUNCH_CV
     if (launch_status() != MESA_OK) return MESA_ERR_LAUNCH;   // the last kernel must not read sums nobody wrote
     if (plane <= 32768 && p.splits >= 32)       // very few pairs: 32 threads per pair, so that the chip has workgroups enough
-        hipLaunchKernelGGL(k_conv_finish_few<32>, dim3(unsigned(ceil_div(plane, 8))), dim3(kCvThreads), 0, s, part, V, p.splits, p.parts, cg,
+        hipLaunchKernelGGL(k_conv_finish_few<32>, dim3(unsigned(ceil_div(plane, 32))), dim3(1024), 0, s, part, V, p.splits, p.parts, cg,
                            per, alpha, beta, centre, dW, db);
     else if (plane <= 262144 && p.splits >= 8)
         hipLaunchKernelGGL(k_conv_finish_few<8>, dim3(unsigned(ceil_div(plane, 32))), dim3(kCvThreads), 0, s, part, V, p.splits, p.parts, cg,
