@@ -173,8 +173,8 @@ mesa_status mesa_quantize_headwise(const void *x, mesa_dtype dt, mesa_layout L,
  * the second iteration on; its parameters then lag the two-call order by exactly one step.
  * Arithmetic, rounding modes, random source and layouts: as in the two calls it combines, bit for bit.
  * x: [numel] of dt (in).  alpha, beta: [groups] (in/out).  q: [numel] int8 (out).
- * ws: MESA_OP_UPDATE_RUNNING_PARAMS bytes.  Limit: groups <= 4096 (this call and mesa_gelu_fwd_q), else
- * MESA_ERR_UNSUPPORTED.
+ * ws: MESA_OP_UPDATE_RUNNING_PARAMS bytes.  Limits: the layout's (groups <= 8192; beyond 4096 groups the kernel's
+ * tables take more than half of a compute unit's local memory: one workgroup per unit, slower).
  */
 mesa_status mesa_quantize_update_fused(const void *x, mesa_dtype dt, mesa_layout L,
                                        float *alpha, float *beta, float lambda, int8_t *q,
@@ -209,7 +209,7 @@ mesa_status mesa_gelu_fwd_q(const void *x, mesa_dtype dt, mesa_layout L,
  * up to 4096, and other rows of at least 8 elements as long as 8 / gcd(cols, 8) of them fit a tile of 8192 elements
  * (odd lengths up to 1024, even ones up to 2048, ...).  Every other shape takes two steps inside the call -- y by a
  * plain kernel, one workgroup per row, then mesa_quantize_update_fused on y (which reads y back) -- and that step's
- * limits: H <= 4096, rows*cols < 2^30.
+ * limits: H <= 8192, rows*cols < 2^30.
  */
 mesa_status mesa_softmax_fwd_q(const void *s, int64_t B, int64_t H, int64_t rows, int64_t cols,
                                float *alpha, float *beta, float lambda, void *y, int8_t *q,
@@ -226,7 +226,7 @@ mesa_status mesa_softmax_fwd_q(const void *s, int64_t B, int64_t H, int64_t rows
  * (out).  q: int8 (out).  alpha, beta: [G] (in/out).  ws: MESA_OP_LAYERNORM_FWD_Q bytes.
  * One pass over x for D % 8 == 0, (D/G) % 8 == 0, D <= 2048, G <= 1024.  Every other shape takes two steps inside the
  * call -- mesa_quantize_update_fused on x, then mean, rstd and y by a plain kernel, one workgroup per row -- with that
- * step's limit G <= 4096.  D >= 2^31 or M >= 2^40: MESA_ERR_UNSUPPORTED.
+ * step's limit G <= 8192.  D >= 2^31 or M >= 2^40: MESA_ERR_UNSUPPORTED.
  */
 mesa_status mesa_layernorm_fwd_q(const void *x, int64_t M, int64_t D, int64_t G,
                                  const void *gamma, const void *bias, float eps,

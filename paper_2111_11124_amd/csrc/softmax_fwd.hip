@@ -756,7 +756,6 @@ extern "C" MESA_EXPORT mesa_status mesa_softmax_fwd_q(const void *s_in, int64_t 
         const mesa_layout L = {B, H, rows * cols};
         const mesa_status st = check_layout(L);
         if (st != MESA_OK) return st;
-        if (size_t(H) * 16 > size_t(64) * 1024) return MESA_ERR_UNSUPPORTED;
         if (!ws || !aligned16(ws) || ws_bytes < update_ws_bytes(L.outer, L.groups, L.inner)) return MESA_ERR_WORKSPACE;
         const unsigned grid = unsigned(total_rows < (int64_t(1) << 20) ? total_rows : (int64_t(1) << 20));
 #define MESA_LAUNCH_SP(T) hipLaunchKernelGGL((k_softmax_fwd_plain_y<T>), dim3(grid), dim3(kThreads), 0, s, s_in, y, total_rows, uint32_t(cols))

@@ -1158,8 +1158,6 @@ static mesa_status quantize_update_fused(const void *x, mesa_dtype dt, mesa_layo
         return MESA_ERR_INVALID_ARG;
     if (gelu_fwd && (!y || !aligned16(y) || y == x)) return MESA_ERR_INVALID_ARG;   // not in place: the kernel's pointers do not alias
     if (!gelu_fwd) y = nullptr;
-    // parameter table and extrema of every group live in LDS, 16 bytes a group, within the 64 KiB a launch gets by default
-    if (size_t(L.groups) * (sizeof(float2) + 2 * sizeof(int)) > size_t(64) * 1024) return MESA_ERR_UNSUPPORTED;
     if (!ws || !aligned16(ws) || ws_bytes < update_ws_bytes(L.outer, L.groups, L.inner)) return MESA_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int grid = minmax_grid(L, kFuU, kFuGridCap);
@@ -1167,9 +1165,16 @@ static mesa_status quantize_update_fused(const void *x, mesa_dtype dt, mesa_layo
     const size_t lds = size_t(gg.groups) * (sizeof(float2) + 2 * sizeof(int));
     float *part = static_cast<float *>(ws);
     const bool sr = mode == MESA_ROUND_STOCHASTIC;
+    // parameter table and extrema of every group live in LDS, 16 bytes a group: beyond the 64 KiB a launch gets by default
+    // (more than 4096 groups, up to the layout's limit of 8192: 128 KiB) the kernel is given leave for more
 #define MESA_LAUNCH_QM(T, SRF, GF) \
-    hipLaunchKernelGGL((k_quantize_minmax<T, kFuU, SRF, GF>), dim3(grid), dim3(kThreads), lds, s, x, q, numel, gg, alpha, beta, seed, \
-                       offset, part, y)
+    do { \
+        auto kern = k_quantize_minmax<T, kFuU, SRF, GF>; \
+        if (lds > size_t(64) * 1024 && \
+            hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess) \
+            return MESA_ERR_LAUNCH; \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, s, x, q, numel, gg, alpha, beta, seed, offset, part, y); \
+    } while (0)
 #define MESA_LAUNCH_QM_T(T) \
     do { \
         if (y) { if (sr) MESA_LAUNCH_QM(T, true, true); else MESA_LAUNCH_QM(T, false, true); } \

@@ -72,7 +72,7 @@ def test_argument_errors_are_reported_before_any_launch(M):
     assert L.mesa_softmax_fwd_q(P, 2, 3, 19, 19, P, P, 0.9, P, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_INVALID_ARG   # y aliases s
     assert L.mesa_softmax_fwd_q(P, 2, 3, 19, 19, P, P, 0.9, P2, P, 0, 0, 0, P, 8, M.F16, None) == M.ERR_WORKSPACE
     assert L.mesa_softmax_fwd_q(P, 2, 3, 19, 3001, P, P, 0.9, P2, P, 0, 0, 0, P, 8, M.F16, None) == M.ERR_WORKSPACE  # the two-step path checks its workspace first
-    assert L.mesa_softmax_fwd_q(P, 2, 5000, 19, 19, P, P, 0.9, P2, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_UNSUPPORTED  # heads
+    assert L.mesa_softmax_fwd_q(P, 2, 9000, 19, 19, P, P, 0.9, P2, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_UNSUPPORTED  # heads
     assert L.mesa_softmax_fwd_q(P, 2, 3, 1 << 16, 1 << 15, P, P, 0.9, P2, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_UNSUPPORTED  # 2^31 elements a map
     assert M.workspace_bytes(M.OP_SOFTMAX_FWD_Q, 2 * 3 * 19, 3, 3001, M.F16) >= M.workspace_bytes(M.OP_UPDATE_RUNNING_PARAMS, 2, 3, 19 * 3001, M.F16)
     assert M.workspace_bytes(M.OP_SOFTMAX_FWD_Q, 6 * 7 * 1000, 7, 1025, M.F16) >= M.workspace_bytes(M.OP_UPDATE_RUNNING_PARAMS, 6, 7, 1000 * 1025, M.F16)
@@ -83,7 +83,7 @@ def test_argument_errors_are_reported_before_any_launch(M):
     assert L.mesa_layernorm_fwd_q(P, 100, 384, 6, P, P, F(1e-5), P, P, F(0.9), P, P, P, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_INVALID_ARG  # y aliases x
     assert L.mesa_layernorm_fwd_q(P, 100, 384, 6, P, P, F(1e-5), P, P, F(0.9), P2, P, P, P, 0, 0, 0, P, 8, M.F16, None) == M.ERR_WORKSPACE
     assert L.mesa_layernorm_fwd_q(P, 100, 4096, 8, P, P, F(1e-5), P, P, F(0.9), P2, P, P, P, 0, 0, 0, P, 8, M.F16, None) == M.ERR_WORKSPACE  # the two-step path
-    assert L.mesa_layernorm_fwd_q(P, 100, 40000, 5000, P, P, F(1e-5), P, P, F(0.9), P2, P, P, P, 0, 0, 0, P, 1 << 24, M.F16, None) == M.ERR_UNSUPPORTED  # groups
+    assert L.mesa_layernorm_fwd_q(P, 100, 72000, 9000, P, P, F(1e-5), P, P, F(0.9), P2, P, P, P, 0, 0, 0, P, 1 << 24, M.F16, None) == M.ERR_UNSUPPORTED  # groups
     assert L.mesa_layernorm_fwd_q(P, 100, 384, 5, P, P, F(1e-5), P, P, F(0.9), P2, P, P, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_INVALID_ARG  # D % G
     assert L.mesa_layernorm_fwd_q(P, 100, 384, 6, P, P, F(-1.0), P, P, F(0.9), P2, P, P, P, 0, 0, 0, P, 1 << 20, M.F16, None) == M.ERR_INVALID_ARG  # eps
     assert L.mesa_dequantize(P, lay, P, None, P, M.F16, None) == M.ERR_INVALID_ARG
@@ -204,7 +204,7 @@ def test_softmax_forward_workspace_covers_the_two_step_path():
         if rnd.random() < 0.5:
             H, cols = rnd.randint(1, 40), 2 * rnd.randint(513, 4000) + 1
         else:
-            H, cols = rnd.randint(1025, 4096), rnd.randint(1, 300)
+            H, cols = rnd.randint(1025, 8192), rnd.randint(1, 300)
         B, rows = rnd.randint(1, 64), rnd.randint(1, 3000)
         if B * H * rows >= 1 << 31 or rows * cols >= 1 << 30:
             continue
